@@ -1,0 +1,170 @@
+"""CPU oracle of the MoE layer and of the expert-cache bookkeeping.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package may import this; only
+tests, the smoke check and the benchmark's cpu_baseline leg do.  The numerical
+part is plain C (moe_oracle.c, loaded through ctypes); the cache simulator is
+plain Python (cache_sim.py).  Neither shares code with the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmoe_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    src = os.path.join(_HERE, "moe_oracle.c")
+    if force or not os.path.exists(_LIB_PATH):
+        subprocess.check_call([
+            "gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
+            src, "-o", _LIB_PATH, "-lm",
+        ])
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build()
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.ref_router_logits.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        lib.ref_topk_weights.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+        lib.ref_dispatch.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+        lib.ref_expert_ffn.argtypes = [vp, vp, ci, ci, vp]
+        lib.ref_moe_tokens.argtypes = [vp, ci, ci, ci, vp, vp, ci, vp, vp, vp, ci, vp, vp]
+        lib.ref_predictor_score.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+        lib.ref_bf16_from_f64.argtypes = [ctypes.c_double]
+        lib.ref_bf16_from_f64.restype = ctypes.c_uint16
+        for f in ("ref_router_logits", "ref_topk_weights", "ref_dispatch", "ref_expert_ffn",
+                  "ref_moe_tokens", "ref_predictor_score"):
+            getattr(lib, f).restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, "bf16 tensors travel as uint16 bit patterns"
+    return a
+
+
+def bf16_from_f64(v: float) -> int:
+    return int(_load().ref_bf16_from_f64(float(v)))
+
+
+def router_logits(x, wr, bias=None, want_f64=False):
+    """logits [T,E] fp32 in the fixed summation order (+ fp64 values on request)."""
+    x, wr = _u16(x), _u16(wr)
+    T, d = x.shape
+    E = wr.shape[0]
+    assert wr.shape[1] == d
+    stride = 0
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if bias.ndim == 2:
+            assert bias.shape == (T, E)
+            stride = E
+        else:
+            assert bias.shape == (E,)
+    l32 = np.empty((T, E), dtype=np.float32)
+    l64 = np.empty((T, E), dtype=np.float64) if want_f64 else None
+    _load().ref_router_logits(_p(x), _p(wr), _p(bias), stride, T, d, E, _p(l32), _p(l64))
+    return (l32, l64) if want_f64 else l32
+
+
+def topk_weights(logits, k, renormalize=True):
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    assert 1 <= k <= E
+    ids = np.empty((T, k), dtype=np.int32)
+    w = np.empty((T, k), dtype=np.float32)
+    _load().ref_topk_weights(_p(logits), T, E, k, 1 if renormalize else 0, _p(ids), _p(w))
+    return ids, w
+
+
+def dispatch(ids, E):
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T, k = ids.shape
+    counts = np.empty(E, dtype=np.int32)
+    offsets = np.empty(E + 1, dtype=np.int32)
+    perm = np.empty(T * k, dtype=np.int32)
+    inv = np.empty(T * k, dtype=np.int32)
+    _load().ref_dispatch(_p(ids), T, k, E, _p(counts), _p(offsets), _p(perm), _p(inv))
+    return counts, offsets, perm, inv
+
+
+def expert_ffn(x_row, blob, d, I):
+    x_row, blob = _u16(x_row), _u16(blob)
+    assert x_row.size == d and blob.size == 3 * d * I
+    y = np.empty(d, dtype=np.float64)
+    _load().ref_expert_ffn(_p(x_row), _p(blob), d, I, _p(y))
+    return y
+
+
+def moe_tokens(x, blobs, ids, w, sel=None, shared_blob=None, I=None, I_shared=0):
+    """Layer output for tokens `sel` (default: all).  blobs: list of E flat uint16 arrays or
+    raw host addresses (ints).  Returns (out_bf16 [n_sel,d] uint16, out_f64 [n_sel,d])."""
+    x = _u16(x)
+    T, d = x.shape
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    k = ids.shape[1]
+    keep = []
+    ptrs = (ctypes.c_void_p * len(blobs))()
+    for e, b in enumerate(blobs):
+        if isinstance(b, (int, np.integer)):
+            ptrs[e] = int(b)
+        else:
+            b = _u16(b)
+            if I is None:
+                I = b.size // (3 * d)
+            assert b.size == 3 * d * I
+            keep.append(b)
+            ptrs[e] = b.ctypes.data
+    assert I is not None
+    if sel is None:
+        sel = np.arange(T, dtype=np.int32)
+    sel = np.ascontiguousarray(sel, dtype=np.int32)
+    if shared_blob is not None:
+        shared_blob = _u16(shared_blob)
+        assert I_shared > 0 and shared_blob.size == 3 * d * I_shared
+    out16 = np.empty((sel.size, d), dtype=np.uint16)
+    out64 = np.empty((sel.size, d), dtype=np.float64)
+    _load().ref_moe_tokens(_p(x), d, I, k, ctypes.cast(ptrs, ctypes.c_void_p), _p(shared_blob),
+                           I_shared if shared_blob is not None else 0, _p(ids), _p(w), _p(sel),
+                           int(sel.size), _p(out16), _p(out64))
+    return out16, out64
+
+
+def moe_layer(x, wr, blobs, k, bias=None, renormalize=True, sel=None, shared_blob=None,
+              I=None, I_shared=0):
+    """Whole layer: gate -> top-k -> grouping -> experts -> weighted sum.  Returns a dict."""
+    E = wr.shape[0]
+    logits = router_logits(x, wr, bias)
+    ids, w = topk_weights(logits, k, renormalize)
+    counts, offsets, perm, inv = dispatch(ids, E)
+    out16, out64 = moe_tokens(x, blobs, ids, w, sel, shared_blob, I, I_shared)
+    return dict(logits=logits, ids=ids, w=w, counts=counts, offsets=offsets, perm=perm,
+                inv_perm=inv, out=out16, out_f64=out64)
+
+
+def predictor_score(x, wp, m):
+    x, wp = _u16(x), _u16(wp)
+    B, d = x.shape
+    E = wp.shape[0]
+    scores = np.empty(E, dtype=np.float32)
+    top = np.empty(m, dtype=np.int32)
+    _load().ref_predictor_score(_p(x), _p(wp), B, d, E, m, _p(scores), _p(top))
+    return scores, top

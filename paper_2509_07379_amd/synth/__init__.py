@@ -1,0 +1,220 @@
+"""Seeded synthetic inputs shared by the CPU oracle's tests and the HIP path.
+
+Nothing here is part of the MoE method: the module only names the workload
+shapes and fills tensors (Gaussian bf16 weights and activations, routing
+traces, popularity biases).  The shapes imitate the model table of the paper
+(Table I: Mixtral-8x7B 2-of-8, DeepSeekMoE 8-of-66 = 6 routed of 64 + 2 shared)
+and its observations that prefill activates every expert (Section II-B) while
+consecutive layers' choices are correlated (Section II-A, Fig. 2).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsynth.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the generator with gcc (host only)."""
+    src = os.path.join(_HERE, "synth.c")
+    if force or not os.path.exists(_LIB_PATH):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", src, "-o", _LIB_PATH, "-lm"]
+        )
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build()
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, ptr in (("synth_normal_bf16", ctypes.c_void_p), ("synth_normal_f32", ctypes.c_void_p)):
+            fn = getattr(lib, name)
+            fn.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64,
+                           ctypes.c_float, ptr]
+            fn.restype = None
+        _lib = lib
+    return _lib
+
+
+# ---------------------------------------------------------------------------
+# stream ids: one Gaussian stream per (tensor kind, layer, expert)
+# ---------------------------------------------------------------------------
+KIND_X, KIND_ROUTER, KIND_EXPERT, KIND_SHARED, KIND_PREDICTOR, KIND_ATTN = range(6)
+
+
+def stream_id(kind: int, layer: int = 0, index: int = 0, step: int = 0) -> int:
+    return ((kind * 4096 + layer) * 4096 + index) * 65536 + step
+
+
+def normal_bf16_into(ptr: int, n: int, seed: int, stream: int, sigma: float, first: int = 0) -> None:
+    """Fill n bf16 values at raw host address ptr (e.g. pinned memory)."""
+    _load().synth_normal_bf16(seed, stream, first, n, sigma, ctypes.c_void_p(ptr))
+
+
+def normal_bf16(shape, seed: int, stream: int, sigma: float) -> np.ndarray:
+    """bf16 bit patterns (uint16) of sigma*N(0,1), C-contiguous."""
+    out = np.empty(shape, dtype=np.uint16)
+    normal_bf16_into(out.ctypes.data, out.size, seed, stream, sigma)
+    return out
+
+
+def normal_f32(shape, seed: int, stream: int, sigma: float) -> np.ndarray:
+    out = np.empty(shape, dtype=np.float32)
+    _load().synth_normal_f32(seed, stream, 0, out.size, sigma, ctypes.c_void_p(out.ctypes.data))
+    return out
+
+
+def bf16_to_f32(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32)
+
+
+# ---------------------------------------------------------------------------
+# workload shapes
+# ---------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    d: int
+    I: int
+    E: int
+    k: int
+    T: int            # prompt tokens (prefill) or batch (decode)
+    L: int = 1
+    S: int = 0        # HBM cache slots per layer (0 = all experts resident)
+    I_shared: int = 0
+    steps: int = 0    # decode steps (0 = prefill workload)
+    p_stay: float = 0.0
+    top_m: int = 0    # predictor prefetch width
+    zipf_s: float = 0.0
+    seed: int = 0
+    sigma_w: float = 0.02
+
+    @property
+    def blob_elems(self) -> int:
+        return 3 * self.d * self.I
+
+    @property
+    def blob_bytes(self) -> int:
+        return 6 * self.d * self.I
+
+    @property
+    def shared_blob_bytes(self) -> int:
+        return 6 * self.d * self.I_shared
+
+
+WORKLOADS = {
+    "c1_tiny": Workload("c1_tiny", d=256, I=512, E=8, k=2, T=64, S=8),
+    "c2_mixtral_prefill": Workload("c2_mixtral_prefill", d=4096, I=14336, E=8, k=2, T=2048, S=2),
+    "c3_mixtral_decode": Workload("c3_mixtral_decode", d=4096, I=14336, E=8, k=2, T=1, L=32, S=3,
+                                  steps=256, p_stay=0.6, top_m=3),
+    "c4_deepseek_prefill": Workload("c4_deepseek_prefill", d=2048, I=1408, E=64, k=6, T=4096, L=28,
+                                    S=16, I_shared=2816, zipf_s=1.1),
+    "c5_qwen_decode": Workload("c5_qwen_decode", d=2048, I=1408, E=60, k=4, T=8, L=24, S=15,
+                                I_shared=5632, steps=128, p_stay=0.5, top_m=8),
+}
+
+
+# ---------------------------------------------------------------------------
+# tensors
+# ---------------------------------------------------------------------------
+def activations(w: Workload, layer: int = 0, step: int = 0, T: int | None = None) -> np.ndarray:
+    """x [T, d] bf16 ~ N(0,1); independent per (layer, step): no residual chaining."""
+    T = w.T if T is None else T
+    return normal_bf16((T, w.d), w.seed, stream_id(KIND_X, layer, 0, step), 1.0)
+
+
+def router_weight(w: Workload, layer: int = 0) -> np.ndarray:
+    """Wr [E, d] bf16 ~ N(0, 0.02^2)."""
+    return normal_bf16((w.E, w.d), w.seed, stream_id(KIND_ROUTER, layer), w.sigma_w)
+
+
+def predictor_weight(w: Workload, layer: int = 0) -> np.ndarray:
+    """Wp [E, d] bf16 ~ N(0, 0.02^2): the seeded linear stand-in for the paper's ExpertMLP."""
+    return normal_bf16((w.E, w.d), w.seed, stream_id(KIND_PREDICTOR, layer), w.sigma_w)
+
+
+def expert_blob(w: Workload, layer: int, e: int) -> np.ndarray:
+    """One expert, flat bf16: [W_gate (I x d); W_up (I x d); W_down (d x I)], row-major."""
+    return normal_bf16((w.blob_elems,), w.seed, stream_id(KIND_EXPERT, layer, e), w.sigma_w)
+
+
+def expert_blob_into(ptr: int, w: Workload, layer: int, e: int) -> None:
+    normal_bf16_into(ptr, w.blob_elems, w.seed, stream_id(KIND_EXPERT, layer, e), w.sigma_w)
+
+
+def shared_blob(w: Workload, layer: int) -> np.ndarray | None:
+    """Shared experts fused into one SwiGLU expert of width I_shared (same blob layout)."""
+    if w.I_shared == 0:
+        return None
+    return normal_bf16((3 * w.d * w.I_shared,), w.seed, stream_id(KIND_SHARED, layer), w.sigma_w)
+
+
+def split_blob(blob: np.ndarray, d: int, I: int):
+    """Views (W_gate [I,d], W_up [I,d], W_down [d,I]) of a flat blob."""
+    g = blob[: I * d].reshape(I, d)
+    u = blob[I * d: 2 * I * d].reshape(I, d)
+    dn = blob[2 * I * d: 3 * I * d].reshape(d, I)
+    return g, u, dn
+
+
+# ---------------------------------------------------------------------------
+# routing structure
+# ---------------------------------------------------------------------------
+def zipf_route_bias(w: Workload, layer: int) -> np.ndarray:
+    """bias[e] = ln p_e with p_e ~ rank(e)^-s, rank a seeded permutation per layer."""
+    rng = np.random.default_rng([w.seed, 7001, layer])
+    rank = rng.permutation(w.E) + 1
+    p = rank.astype(np.float64) ** (-w.zipf_s)
+    p /= p.sum()
+    return np.log(p).astype(np.float32)
+
+
+def markov_trace(w: Workload, steps: int | None = None) -> np.ndarray:
+    """ids [steps, L, B, k] int32.
+
+    Layer 0: uniform random k-subset.  Layer l: slot j keeps the previous layer's
+    slot-j expert with probability p_stay, else draws uniformly over E; a
+    duplicate within the token is redrawn uniformly from the unused ids.
+    Tokens and steps are independent.
+    """
+    steps = w.steps if steps is None else steps
+    B = w.T
+    rng = np.random.default_rng([w.seed, 7002])
+    out = np.empty((steps, w.L, B, w.k), dtype=np.int32)
+    for s in range(steps):
+        for b in range(B):
+            prev = rng.choice(w.E, size=w.k, replace=False)
+            out[s, 0, b] = prev
+            for l in range(1, w.L):
+                cur = []
+                for j in range(w.k):
+                    e = int(prev[j]) if rng.random() < w.p_stay else int(rng.integers(w.E))
+                    if e in cur:
+                        unused = [q for q in range(w.E) if q not in cur]
+                        e = int(unused[int(rng.integers(len(unused)))])
+                    cur.append(e)
+                prev = np.asarray(cur)
+                out[s, l, b] = prev
+    return out
+
+
+def trace_route_bias(ids_tk: np.ndarray, E: int, boost: float = 64.0) -> np.ndarray:
+    """[T, E] fp32 additive router bias that forces the traced experts to win.
+
+    Every traced expert gets the same shift, so the renormalised weights among
+    them still come from the natural logits.
+    """
+    T = ids_tk.shape[0]
+    b = np.zeros((T, E), dtype=np.float32)
+    b[np.arange(T)[:, None], ids_tk] = boost
+    return b
