@@ -1,0 +1,178 @@
+/*
+ * moe_offload.h - C ABI of the MI355X (gfx950) MoE-layer library.
+ *
+ * One Mixture-of-Experts FFN layer served from an offloaded expert pool, after the
+ * inference runtime of DuoServe-MoE (Section V of the paper): every expert lives in
+ * a pinned "CPU expert cache", a small "GPU expert cache" of S slots per layer is
+ * filled by a communication stream just before the experts run (Section V-A), the
+ * prefill stage pipelines "compute expert i / fetch expert i+1" (Section V-B) and the
+ * decode stage prefetches the experts a per-layer predictor names and re-fetches on
+ * a wrong guess (Section V-C).  The numbers a layer produces never depend on the
+ * cache state.
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) memory, "host" pointers are host memory, and
+ *    "pinned" means page-locked host memory (hipHostMalloc / torch pin_memory).
+ *    All of them are owned by the CALLER and must stay valid while the ctx uses them;
+ *    the library owns only bookkeeping (slot tables, events, a few KB of pinned
+ *    mailboxes).  bf16 tensors are raw 16-bit patterns, row-major.
+ *  - Streams are hipStream_t handles passed as void* (NULL = the default stream).
+ *    Calls enqueue work and return; they block the host only where stated.
+ *  - Every function returns 0 on success or a negative MOE_E_* code and never throws
+ *    or aborts; moe_last_error() returns a thread-local message for the last failure.
+ *  - One ctx serves one (compute stream, copy stream) pair at a time; calls on the
+ *    same ctx must not overlap in time from several host threads.
+ */
+#ifndef MOE_OFFLOAD_H
+#define MOE_OFFLOAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK 0
+#define MOE_E_ARG (-1)         /* null/unaligned pointer, T <= 0, k > E, cache_slots < 1, bad id ... */
+#define MOE_E_UNSUPPORTED (-2) /* E > 64, d % 8 != 0, I % 8 != 0 ... */
+#define MOE_E_HIP (-3)         /* a HIP runtime call failed (text in moe_last_error) */
+#define MOE_E_UNBOUND (-4)     /* layer not bound */
+#define MOE_E_WORKSPACE (-5)   /* workspace too small */
+
+typedef struct moe_ctx moe_ctx;
+
+/* Shape of the layer family (Fig. 1 of the paper: Top-k of n routed experts plus
+ * optional shared experts).  Experts are SwiGLU FFN blocks without biases. */
+typedef struct {
+  int32_t d;           /* hidden size, multiple of 8 */
+  int32_t I;           /* routed-expert intermediate size, multiple of 8 */
+  int32_t E;           /* routed experts per layer, 1..64 */
+  int32_t k;           /* experts per token, 1..E */
+  int32_t n_layers;    /* layers that can be bound */
+  int32_t cache_slots; /* S: GPU expert cache slots per layer, >= 1 (Section V-A) */
+  int32_t I_shared;    /* 0, or total intermediate size of the always-on shared experts */
+  int32_t renormalize; /* 1: gate values = softmax over the k selected; 0: over all E */
+} moe_config;
+
+/* Cache counters (host side).  hits/misses count active experts per layer call. */
+typedef struct {
+  int32_t hits, misses, prefetch_issued, prefetch_useful, prefetch_dropped, layer_calls;
+  int64_t bytes_h2d;
+} moe_stats;
+
+/* Kernel classes timed when profiling is on (moe_set_profiling). */
+enum {
+  MOE_K_ROUTER = 0, MOE_K_DISPATCH, MOE_K_GEMM1, MOE_K_GEMM2, MOE_K_GEMV1, MOE_K_GEMV2,
+  MOE_K_COMBINE, MOE_K_PREDICTOR, MOE_K_COUNT
+};
+
+const char *moe_last_error(void);
+
+/* Creates the bookkeeping for cfg on the current HIP device.  *out receives the ctx. */
+int moe_create(const moe_config *cfg, moe_ctx **out);
+/* Destroys events and tables.  Frees nothing the caller allocated.  Blocks until the
+ * device is idle. */
+int moe_destroy(moe_ctx *ctx);
+
+/* Bytes of device workspace a layer call on T tokens needs (256-byte aligned base). */
+size_t moe_workspace_bytes(const moe_config *cfg, int T);
+
+/*
+ * Attaches a layer's memory (Section V-A: CPU expert cache, GPU expert cache).
+ *  host_expert_blob[E]  pinned; each 6*d*I bytes: W_gate (I x d), W_up (I x d), W_down (d x I),
+ *                       row-major bf16, one contiguous blob per expert (= one DMA per expert).
+ *  dev_router_w         [E, d] bf16 gate weight.
+ *  dev_shared_blob      NULL, or 6*d*I_shared bytes in the same layout (always resident).
+ *  dev_slots            S * 6*d*I bytes: the layer's GPU expert cache.
+ *  initial_resident     NULL (all slots empty) or [S] expert ids / -1: slot s already holds
+ *                       that expert's blob (the caller copied it there).
+ * The pointers are read, not copied.
+ */
+int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
+                   const void *dev_router_w, const void *dev_shared_blob, void *dev_slots,
+                   const int32_t *initial_resident);
+
+/*
+ * Prefetch (Sections V-B, V-C): makes the named experts of `layer` resident by copies
+ * enqueued on copy_stream, ordered behind the last use of each overwritten slot.
+ * Resident ids cost nothing; repeated ids are ignored.  Victim: an empty slot, else the
+ * least recently used slot whose expert is not named in this request; if none is left
+ * the id is dropped (counted).  host_ids[n] are plain host ints.  Does not block.
+ */
+int expert_cache_prefetch(moe_ctx *ctx, int layer, const int32_t *host_ids, int n,
+                          void *copy_stream);
+
+/*
+ * Stand-in for the paper's layer-level predictor (Section IV-B, used as in Section V-C):
+ * score[e] = sum_t x[t] . Wp[e]; the m best (score descending, lower id on ties) go to
+ * pinned_topm[m] (pinned host ints, valid once `stream` has been synchronised) and, if
+ * dev_scores != NULL, the E scores to dev_scores.  dev_x [T, d] bf16, dev_wp [E, d] bf16.
+ */
+int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, int m,
+                    float *dev_scores, int32_t *pinned_topm, void *stream);
+
+/*
+ * One MoE layer in the prefill stage (Section V-B): gate -> Top-k -> tokens grouped by
+ * expert -> every active expert as a grouped bf16 MFMA GEMM from its cache slot -> weighted
+ * sum (+ shared experts) -> dev_y [T, d] bf16.  Experts that are not resident stream
+ * through the slots in ascending id, each fetched once on copy_stream while the previous
+ * one computes.  When some routed expert is not resident the call blocks the host once,
+ * until the gate's counts are known.
+ *  dev_route_bias  NULL, or fp32 added to the gate logits: element [t*bias_stride + e]
+ *                  (bias_stride 0 = one row for all tokens, E = one row per token).
+ *  dev_workspace   >= moe_workspace_bytes(cfg, T), 256-byte aligned; holds the routing
+ *                  tables afterwards (see moe_debug_routing).
+ */
+int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
+                      const float *dev_route_bias, int bias_stride, void *dev_y,
+                      void *dev_workspace, size_t ws_bytes, void *compute_stream,
+                      void *copy_stream);
+
+/*
+ * One MoE layer in the decode stage (Section V-C), T = batch (small).  Same contract and
+ * results as moe_prefill_layer; experts run as bandwidth-bound GEMVs.  The gate's choice is
+ * compared with the cache ("synchronisation point 1"): hits run first, misses are
+ * re-fetched on copy_stream and run as they land.
+ */
+int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
+                     const float *dev_route_bias, int bias_stride, void *dev_y,
+                     void *dev_workspace, size_t ws_bytes, void *compute_stream,
+                     void *copy_stream);
+
+/*
+ * Parity hook: copies the routing tables the last layer call left in `dev_workspace`
+ * (T as in that call) to caller device buffers on `stream`; any destination may be NULL.
+ * ids [T,k] i32, w [T,k] f32, counts [E], offsets [E+1], perm [T*k], inv_perm [T*k].
+ */
+int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *dev_ids,
+                      float *dev_w, int32_t *dev_counts, int32_t *dev_offsets, int32_t *dev_perm,
+                      int32_t *dev_inv_perm, void *stream);
+
+/* Cache counters of `layer` (or summed over all layers if layer < 0). */
+int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out);
+int moe_reset_stats(moe_ctx *ctx);
+/* Expert id held by each slot of `layer` (-1 = empty) into host_slot_expert[S]. */
+int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert);
+
+/*
+ * Kernel timing.  on != 0: every kernel launch of the layer calls is bracketed by HIP
+ * events on its own stream.  moe_get_kernel_times blocks until those events have
+ * completed, adds their durations into ms[MOE_K_COUNT] / launches[MOE_K_COUNT] and
+ * clears the record.
+ */
+int moe_set_profiling(moe_ctx *ctx, int on);
+int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches);
+
+/*
+ * Plain bf16 GEMM C[M,N] = A[M,K] * B[N,K]^T on the same MFMA kernel as the experts
+ * (the stand-in for the non-MoE block whose time hides the first expert fetch,
+ * Section V-B).  All device pointers, C bf16.  K a multiple of 8.
+ */
+int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M, int N, int K,
+                        void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_OFFLOAD_H */

@@ -1,0 +1,724 @@
+// Host side of the C ABI (include/moe_offload.h): argument checks, the expert-slot cache
+// (Section V-A of the paper), the stream/event ordering of prefetch, fetch and compute
+// (Sections V-B and V-C), and the sequencing of the kernels of one layer.
+//
+// Ordering rules (the paper's "synchronisation points"):
+//   - a slot is read by the compute stream only after hipStreamWaitEvent(compute, copied[slot]);
+//   - a slot is overwritten by the copy stream only after hipStreamWaitEvent(copy, <event
+//     recorded on the compute stream behind the last kernel that read the slot>).
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/moe_offload.h"
+#include "kernels.h"
+
+using namespace moe;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess)                                                                  \
+      return fail(MOE_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, __LINE__); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// K slices of the down projection.  Few, long tiles (Mixtral-like: K = 14336, ~320 tiles of
+// 256 x 256 on 256 CUs) leave most of the last round idle; slicing K makes the tiles finer.
+// The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
+int choose_splitk(const moe_config &cfg, int T) {
+  (void)cfg;
+  (void)T;
+  return 1;
+}
+
+struct WsLayout {
+  size_t logits, ids, w, counts, offsets, blk_hist, blk_base, perm, inv_perm, H, Hs, Y, Ys, total;
+  int splitk, nblk;
+};
+
+WsLayout ws_layout(const moe_config &c, int T) {
+  WsLayout L{};
+  const size_t n = (size_t)T * c.k;
+  L.splitk = choose_splitk(c, T);
+  L.nblk = (int)((n + kDispatchChunk - 1) / kDispatchChunk);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  L.logits = take((size_t)T * c.E * 4);
+  L.ids = take(n * 4);
+  L.w = take(n * 4);
+  L.counts = take((size_t)c.E * 4);
+  L.offsets = take((size_t)(c.E + 1) * 4);
+  L.blk_hist = take((size_t)L.nblk * c.E * 4);
+  L.blk_base = take((size_t)L.nblk * c.E * 4);
+  L.perm = take(n * 4);
+  L.inv_perm = take(n * 4);
+  L.H = take(n * c.I * 2);
+  L.Hs = take((size_t)T * c.I_shared * 2);
+  L.Y = take((size_t)L.splitk * n * c.d * 4);
+  L.Ys = take(c.I_shared ? (size_t)T * c.d * 4 : 0);
+  L.total = off;
+  return L;
+}
+
+struct Layer {
+  bool bound = false;
+  std::vector<const void *> host_blob;
+  const uint16_t *router_w = nullptr;
+  const char *shared_blob = nullptr;
+  char *slots = nullptr;
+  std::vector<int> slot_expert, expert_slot;
+  std::vector<unsigned long long> stamp;
+  std::vector<char> prefetched;      // slot filled by a prefetch and not yet served
+  std::vector<char> copy_pending;    // a copy into the slot was enqueued; compute has not waited yet
+  std::vector<char> use_kind;        // 0: never read, 1: read behind used[slot], 2: read behind group_done
+  std::vector<hipEvent_t> copied, used;
+  hipEvent_t group_done = nullptr;
+  unsigned long long clock = 0;
+  moe_stats stats{};
+};
+
+struct TimedLaunch {
+  hipEvent_t start, stop;
+  int kind;
+};
+
+}  // namespace
+
+struct moe_ctx {
+  moe_config cfg{};
+  int device = 0;
+  size_t blob_bytes = 0;
+  std::vector<Layer> layers;
+  int32_t *pinned_counts = nullptr;   // [E] mailbox the dispatch kernel fills
+  hipEvent_t routed = nullptr;
+  float *dev_scores = nullptr;        // [64] scratch for predictor_score without dev_scores
+  bool profiling = false;
+  std::vector<TimedLaunch> timed;
+  std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+int check_cfg(const moe_config *c) {
+  if (!c) return fail(MOE_E_ARG, "cfg is NULL");
+  if (c->d <= 0 || c->I <= 0 || c->E <= 0 || c->k <= 0 || c->n_layers <= 0 || c->I_shared < 0)
+    return fail(MOE_E_ARG, "d, I, E, k, n_layers must be positive (I_shared >= 0)");
+  if (c->k > c->E) return fail(MOE_E_ARG, "k = %d exceeds E = %d", c->k, c->E);
+  if (c->cache_slots < 1) return fail(MOE_E_ARG, "cache_slots = %d, need >= 1", c->cache_slots);
+  if (c->E > kMaxExperts) return fail(MOE_E_UNSUPPORTED, "E = %d > %d experts", c->E, kMaxExperts);
+  if (c->d % 8 || c->I % 8 || c->I_shared % 8)
+    return fail(MOE_E_UNSUPPORTED, "d, I and I_shared must be multiples of 8");
+  return MOE_OK;
+}
+
+int get_layer(moe_ctx *ctx, int layer, Layer **out, bool need_bound = true) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(MOE_E_ARG, "layer %d out of range", layer);
+  *out = &ctx->layers[layer];
+  if (need_bound && !(*out)->bound) return fail(MOE_E_UNBOUND, "layer %d is not bound", layer);
+  return MOE_OK;
+}
+
+// ---- kernel timing ------------------------------------------------------------------------
+struct Timer {
+  moe_ctx *ctx;
+  hipStream_t stream;
+  int kind;
+  hipEvent_t start = nullptr, stop = nullptr;
+  Timer(moe_ctx *c, hipStream_t s, int k) : ctx(c), stream(s), kind(k) {
+    if (!ctx->profiling) return;
+    auto get = [&]() -> hipEvent_t {
+      if (!ctx->event_pool.empty()) {
+        hipEvent_t e = ctx->event_pool.back();
+        ctx->event_pool.pop_back();
+        return e;
+      }
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      return e;
+    };
+    start = get();
+    stop = get();
+    if (start && stop) (void)hipEventRecord(start, stream);
+  }
+  ~Timer() {
+    if (!start || !stop) return;
+    (void)hipEventRecord(stop, stream);
+    ctx->timed.push_back({start, stop, kind});
+  }
+};
+
+// ---- cache bookkeeping --------------------------------------------------------------------
+void touch(Layer &L, int s) { L.stamp[s] = ++L.clock; }
+
+int pick_victim(const Layer &L, unsigned long long protected_mask) {
+  const int S = (int)L.slot_expert.size();
+  for (int s = 0; s < S; ++s)
+    if (L.slot_expert[s] < 0) return s;
+  int best = -1;
+  for (int s = 0; s < S; ++s) {
+    if ((protected_mask >> L.slot_expert[s]) & 1ull) continue;
+    if (best < 0 || L.stamp[s] < L.stamp[best]) best = s;
+  }
+  return best;
+}
+
+// Enqueue the copy of expert e into slot s on the copy stream, behind the slot's last reader.
+int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t copy_stream) {
+  if (L.use_kind[s] == 1) HIP_TRY(hipStreamWaitEvent(copy_stream, L.used[s], 0));
+  if (L.use_kind[s] == 2) HIP_TRY(hipStreamWaitEvent(copy_stream, L.group_done, 0));
+  HIP_TRY(hipMemcpyAsync(L.slots + (size_t)s * ctx->blob_bytes, L.host_blob[e], ctx->blob_bytes,
+                         hipMemcpyHostToDevice, copy_stream));
+  HIP_TRY(hipEventRecord(L.copied[s], copy_stream));
+  if (L.slot_expert[s] >= 0) L.expert_slot[L.slot_expert[s]] = -1;
+  L.slot_expert[s] = e;
+  L.expert_slot[e] = s;
+  L.prefetched[s] = by_prefetch;
+  L.copy_pending[s] = 1;
+  L.use_kind[s] = 0;
+  touch(L, s);
+  L.stats.bytes_h2d += (int64_t)ctx->blob_bytes;
+  return MOE_OK;
+}
+
+GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const WsLayout &W, int T,
+                     bool second, const void *x) {
+  const moe_config &c = ctx->cfg;
+  GemmArgs a{};
+  a.k_top = c.k;
+  a.offsets = reinterpret_cast<const int32_t *>(ws + W.offsets);
+  a.n_groups = c.E;
+  a.wbase = L.slots;
+  a.wstride = (long long)ctx->blob_bytes;
+  for (int e = 0; e < c.E; ++e) a.slot[e] = (signed char)(L.expert_slot[e] < 0 ? 0 : L.expert_slot[e]);
+  a.splitk = 1;
+  if (!second) {
+    a.A = reinterpret_cast<const uint16_t *>(x);
+    a.lda = c.d;
+    a.perm = reinterpret_cast<const int32_t *>(ws + W.perm);
+    a.b0_off = 0;
+    a.b1_off = (long long)c.I * c.d * 2;
+    a.ldb = c.d;
+    a.N = c.I;
+    a.K = c.d;
+    a.out = const_cast<char *>(ws + W.H);
+    a.ldo = c.I;
+  } else {
+    a.A = reinterpret_cast<const uint16_t *>(ws + W.H);
+    a.lda = c.I;
+    a.perm = nullptr;
+    a.b0_off = (long long)2 * c.I * c.d * 2;
+    a.b1_off = a.b0_off;
+    a.ldb = c.I;
+    a.N = c.d;
+    a.K = c.I;
+    a.out = const_cast<char *>(ws + W.Y);
+    a.ldo = c.d;
+    a.splitk = W.splitk;
+    a.out_split_stride = (long long)T * c.k * c.d;
+  }
+  return a;
+}
+
+GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const WsLayout &W, int T,
+                     bool second, const void *x) {
+  const moe_config &c = ctx->cfg;
+  GemmArgs a{};
+  a.k_top = 1;
+  a.offsets = nullptr;
+  a.single_row0 = 0;
+  a.single_rows = T;
+  a.group_mask = 1;
+  a.n_groups = 1;
+  a.wbase = L.shared_blob;
+  a.wstride = 0;
+  a.splitk = 1;
+  if (!second) {
+    a.A = reinterpret_cast<const uint16_t *>(x);
+    a.lda = c.d;
+    a.b0_off = 0;
+    a.b1_off = (long long)c.I_shared * c.d * 2;
+    a.ldb = c.d;
+    a.N = c.I_shared;
+    a.K = c.d;
+    a.out = const_cast<char *>(ws + W.Hs);
+    a.ldo = c.I_shared;
+  } else {
+    a.A = reinterpret_cast<const uint16_t *>(ws + W.Hs);
+    a.lda = c.I_shared;
+    a.b0_off = (long long)2 * c.I_shared * c.d * 2;
+    a.b1_off = a.b0_off;
+    a.ldb = c.I_shared;
+    a.N = c.d;
+    a.K = c.I_shared;
+    a.out = const_cast<char *>(ws + W.Ys);
+    a.ldo = c.d;
+  }
+  return a;
+}
+
+// Both expert matmuls of the groups in `mask`, on the compute stream.
+int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
+                int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream) {
+  a1.group_mask = a2.group_mask = mask;
+  if (decode) {
+    {
+      Timer t(ctx, stream, MOE_K_GEMV1);
+      HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, max_rows_per_group, n_groups, stream));
+    }
+    Timer t(ctx, stream, MOE_K_GEMV2);
+    HIP_TRY(launch_grouped_gemv(GEMM_PLAIN_F32, a2, max_rows_per_group, n_groups, stream));
+  } else {
+    {
+      Timer t(ctx, stream, MOE_K_GEMM1);
+      HIP_TRY(launch_grouped_gemm(GEMM_SWIGLU, a1, max_rows, n_groups, stream));
+    }
+    Timer t(ctx, stream, MOE_K_GEMM2);
+    HIP_TRY(launch_grouped_gemm(GEMM_PLAIN_F32, a2, max_rows, n_groups, stream));
+  }
+  return MOE_OK;
+}
+
+int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bias, int bias_stride,
+              void *dev_y, void *dev_ws, size_t ws_bytes, void *compute_stream, void *copy_stream,
+              bool decode) {
+  Layer *Lp = nullptr;
+  int rc = get_layer(ctx, layer, &Lp);
+  if (rc) return rc;
+  Layer &L = *Lp;
+  const moe_config &c = ctx->cfg;
+  if (!dev_x || !dev_y || !dev_ws) return fail(MOE_E_ARG, "dev_x, dev_y and dev_workspace must be non-NULL");
+  if (T <= 0) return fail(MOE_E_ARG, "T = %d, need > 0", T);
+  if ((long long)T * c.k > 0x3FFFFFFFll) return fail(MOE_E_UNSUPPORTED, "T*k too large");
+  if (!aligned(dev_x, 16) || !aligned(dev_y, 16)) return fail(MOE_E_ARG, "dev_x / dev_y need 16-byte alignment");
+  if (!aligned(dev_ws, 256)) return fail(MOE_E_ARG, "dev_workspace needs 256-byte alignment");
+  if (bias && bias_stride != 0 && bias_stride != c.E)
+    return fail(MOE_E_ARG, "bias_stride must be 0 or E");
+  const WsLayout W = ws_layout(c, T);
+  if (ws_bytes < W.total) return fail(MOE_E_WORKSPACE, "workspace %zu < %zu bytes", ws_bytes, W.total);
+  hipStream_t cs = reinterpret_cast<hipStream_t>(compute_stream);
+  hipStream_t ks = reinterpret_cast<hipStream_t>(copy_stream);
+  char *ws = reinterpret_cast<char *>(dev_ws);
+  const int S = c.cache_slots, E = c.E;
+  const int n = T * c.k;
+
+  bool all_resident = true;
+  for (int e = 0; e < E; ++e) all_resident &= L.expert_slot[e] >= 0;
+
+  // ---- gate, Top-k, grouping
+  {
+    Timer t(ctx, cs, MOE_K_ROUTER);
+    HIP_TRY(launch_router_topk(reinterpret_cast<const uint16_t *>(dev_x), L.router_w, bias, bias_stride, T,
+                               c.d, E, c.k, c.renormalize, reinterpret_cast<float *>(ws + W.logits),
+                               reinterpret_cast<int32_t *>(ws + W.ids), reinterpret_cast<float *>(ws + W.w),
+                               cs));
+  }
+  {
+    Timer t(ctx, cs, MOE_K_DISPATCH);
+    HIP_TRY(launch_dispatch(reinterpret_cast<const int32_t *>(ws + W.ids), n, E,
+                            reinterpret_cast<int32_t *>(ws + W.blk_hist),
+                            reinterpret_cast<int32_t *>(ws + W.blk_base),
+                            reinterpret_cast<int32_t *>(ws + W.counts),
+                            reinterpret_cast<int32_t *>(ws + W.offsets),
+                            reinterpret_cast<int32_t *>(ws + W.perm),
+                            reinterpret_cast<int32_t *>(ws + W.inv_perm), ctx->pinned_counts, cs));
+  }
+  HIP_TRY(hipEventRecord(ctx->routed, cs));
+
+  // ---- shared experts: independent of the routing, they also cover the host's wait below
+  if (c.I_shared) {
+    GemmArgs s1 = shared_args(ctx, L, ws, W, T, false, dev_x), s2 = shared_args(ctx, L, ws, W, T, true, dev_x);
+    rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, cs);
+    if (rc) return rc;
+  }
+
+  GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
+  L.stats.layer_calls++;
+
+  if (all_resident) {
+    // Every expert is in a slot: nothing to decide on the host, one grouped launch.
+    for (int s = 0; s < S; ++s)
+      if (L.copy_pending[s]) {
+        HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
+        L.copy_pending[s] = 0;
+      }
+    const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
+    rc = run_experts(ctx, decode, a1, a2, mask, E, n, T, cs);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(L.group_done, cs));
+    for (int s = 0; s < S; ++s) L.use_kind[s] = 2;
+    // counters need the counts: read them once the routing kernels are done
+    HIP_TRY(hipEventSynchronize(ctx->routed));
+    for (int e = 0; e < E; ++e)
+      if (ctx->pinned_counts[e] > 0) {
+        int s = L.expert_slot[e];
+        L.stats.hits++;
+        touch(L, s);
+        if (L.prefetched[s]) {
+          L.stats.prefetch_useful++;
+          L.prefetched[s] = 0;
+        }
+      }
+  } else {
+    // "Synchronisation point 1": the gate's choice is compared with the cache.
+    HIP_TRY(hipEventSynchronize(ctx->routed));
+    int counts[kMaxExperts];
+    unsigned long long hit_mask = 0;
+    int n_hits = 0, hit_rows = 0, hit_max = 0;
+    std::vector<int> misses;
+    for (int e = 0; e < E; ++e) {
+      counts[e] = ctx->pinned_counts[e];
+      if (counts[e] <= 0) continue;
+      if (L.expert_slot[e] >= 0) {
+        hit_mask |= 1ull << e;
+        n_hits++;
+        hit_rows += counts[e];
+        if (counts[e] > hit_max) hit_max = counts[e];
+      } else {
+        misses.push_back(e);
+      }
+    }
+    for (int e = 0; e < E; ++e)
+      if ((hit_mask >> e) & 1ull) {
+        int s = L.expert_slot[e];
+        touch(L, s);
+        L.stats.hits++;
+        if (L.prefetched[s]) {
+          L.stats.prefetch_useful++;
+          L.prefetched[s] = 0;
+        }
+        if (L.copy_pending[s]) {
+          HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
+          L.copy_pending[s] = 0;
+        }
+      }
+    L.stats.misses += (int32_t)misses.size();
+    if (n_hits) {
+      rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs);
+      if (rc) return rc;
+      HIP_TRY(hipEventRecord(L.group_done, cs));
+      for (int e = 0; e < E; ++e)
+        if ((hit_mask >> e) & 1ull) L.use_kind[L.expert_slot[e]] = 2;
+    }
+    // Misses stream through the slots in ascending id: fetch on the copy stream (behind the
+    // victim's last reader), compute as soon as the copy has landed.
+    for (int e : misses) {
+      int s = pick_victim(L, 0ull);
+      rc = place(ctx, L, e, s, false, ks);
+      if (rc) return rc;
+      HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
+      L.copy_pending[s] = 0;
+      a1.slot[e] = a2.slot[e] = (signed char)s;
+      rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
+      if (rc) return rc;
+      HIP_TRY(hipEventRecord(L.used[s], cs));
+      L.use_kind[s] = 1;
+    }
+  }
+
+  // ---- weighted sum per token (+ shared experts)
+  {
+    Timer t(ctx, cs, MOE_K_COMBINE);
+    HIP_TRY(launch_combine(reinterpret_cast<const float *>(ws + W.Y), W.splitk, (long long)n * c.d,
+                           reinterpret_cast<const float *>(ws + W.w),
+                           reinterpret_cast<const int32_t *>(ws + W.inv_perm),
+                           c.I_shared ? reinterpret_cast<const float *>(ws + W.Ys) : nullptr, 1, 0, T, c.d,
+                           c.k, reinterpret_cast<uint16_t *>(dev_y), cs));
+  }
+  return MOE_OK;
+}
+
+}  // namespace
+
+// ============================================================================================
+extern "C" {
+
+const char *moe_last_error(void) { return g_err; }
+
+int moe_create(const moe_config *cfg, moe_ctx **out) {
+  if (!out) return fail(MOE_E_ARG, "out is NULL");
+  *out = nullptr;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (ndev < 1) return fail(MOE_E_HIP, "no HIP device");
+  moe_ctx *ctx = new (std::nothrow) moe_ctx();
+  if (!ctx) return fail(MOE_E_ARG, "out of host memory");
+  ctx->cfg = *cfg;
+  ctx->blob_bytes = (size_t)6 * cfg->d * cfg->I;
+  HIP_TRY(hipGetDevice(&ctx->device));
+  ctx->layers.resize(cfg->n_layers);
+  HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), kMaxExperts * sizeof(int32_t), 0));
+  memset(ctx->pinned_counts, 0, kMaxExperts * sizeof(int32_t));
+  HIP_TRY(hipEventCreateWithFlags(&ctx->routed, hipEventDisableTiming));
+  HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ctx->dev_scores), kMaxExperts * sizeof(float)));
+  *out = ctx;
+  return MOE_OK;
+}
+
+int moe_destroy(moe_ctx *ctx) {
+  if (!ctx) return MOE_OK;
+  (void)hipDeviceSynchronize();
+  for (Layer &L : ctx->layers) {
+    for (hipEvent_t e : L.copied) (void)hipEventDestroy(e);
+    for (hipEvent_t e : L.used) (void)hipEventDestroy(e);
+    if (L.group_done) (void)hipEventDestroy(L.group_done);
+  }
+  for (auto &t : ctx->timed) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+  if (ctx->routed) (void)hipEventDestroy(ctx->routed);
+  if (ctx->pinned_counts) (void)hipHostFree(ctx->pinned_counts);
+  if (ctx->dev_scores) (void)hipFree(ctx->dev_scores);
+  delete ctx;
+  return MOE_OK;
+}
+
+size_t moe_workspace_bytes(const moe_config *cfg, int T) {
+  if (check_cfg(cfg) || T <= 0) return 0;
+  return ws_layout(*cfg, T).total;
+}
+
+int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob, const void *dev_router_w,
+                   const void *dev_shared_blob, void *dev_slots, const int32_t *initial_resident) {
+  Layer *Lp = nullptr;
+  int rc = get_layer(ctx, layer, &Lp, false);
+  if (rc) return rc;
+  const moe_config &c = ctx->cfg;
+  if (!host_expert_blob || !dev_router_w || !dev_slots) return fail(MOE_E_ARG, "NULL pointer in moe_bind_layer");
+  if (c.I_shared && !dev_shared_blob) return fail(MOE_E_ARG, "I_shared > 0 but dev_shared_blob is NULL");
+  if (!aligned(dev_router_w, 16) || !aligned(dev_slots, 16) || !aligned(dev_shared_blob, 16))
+    return fail(MOE_E_ARG, "device pointers need 16-byte alignment");
+  for (int e = 0; e < c.E; ++e)
+    if (!host_expert_blob[e]) return fail(MOE_E_ARG, "host_expert_blob[%d] is NULL", e);
+  const int S = c.cache_slots;
+  if (initial_resident) {
+    unsigned long long seen = 0;
+    for (int s = 0; s < S; ++s) {
+      int e = initial_resident[s];
+      if (e < -1 || e >= c.E) return fail(MOE_E_ARG, "initial_resident[%d] = %d out of range", s, e);
+      if (e >= 0 && ((seen >> e) & 1ull)) return fail(MOE_E_ARG, "expert %d named twice in initial_resident", e);
+      if (e >= 0) seen |= 1ull << e;
+    }
+  }
+  Layer &L = *Lp;
+  if (!L.bound) {
+    L.copied.resize(S);
+    L.used.resize(S);
+    for (int s = 0; s < S; ++s) {
+      HIP_TRY(hipEventCreateWithFlags(&L.copied[s], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&L.used[s], hipEventDisableTiming));
+    }
+    HIP_TRY(hipEventCreateWithFlags(&L.group_done, hipEventDisableTiming));
+  }
+  L.host_blob.assign(host_expert_blob, host_expert_blob + c.E);
+  L.router_w = reinterpret_cast<const uint16_t *>(dev_router_w);
+  L.shared_blob = reinterpret_cast<const char *>(dev_shared_blob);
+  L.slots = reinterpret_cast<char *>(dev_slots);
+  L.slot_expert.assign(S, -1);
+  L.expert_slot.assign(c.E, -1);
+  L.stamp.assign(S, 0);
+  L.prefetched.assign(S, 0);
+  L.copy_pending.assign(S, 0);
+  L.use_kind.assign(S, 0);
+  L.clock = 0;
+  L.stats = moe_stats{};
+  if (initial_resident)
+    for (int s = 0; s < S; ++s)
+      if (initial_resident[s] >= 0) {
+        L.slot_expert[s] = initial_resident[s];
+        L.expert_slot[initial_resident[s]] = s;
+      }
+  L.bound = true;
+  return MOE_OK;
+}
+
+int expert_cache_prefetch(moe_ctx *ctx, int layer, const int32_t *host_ids, int n, void *copy_stream) {
+  Layer *Lp = nullptr;
+  int rc = get_layer(ctx, layer, &Lp);
+  if (rc) return rc;
+  Layer &L = *Lp;
+  if (n < 0 || (n > 0 && !host_ids)) return fail(MOE_E_ARG, "bad id list");
+  unsigned long long protected_mask = 0;
+  for (int i = 0; i < n; ++i) {
+    if (host_ids[i] < 0 || host_ids[i] >= ctx->cfg.E) return fail(MOE_E_ARG, "expert id %d out of range", host_ids[i]);
+    protected_mask |= 1ull << host_ids[i];
+  }
+  unsigned long long seen = 0;
+  hipStream_t ks = reinterpret_cast<hipStream_t>(copy_stream);
+  for (int i = 0; i < n; ++i) {
+    const int e = host_ids[i];
+    if ((seen >> e) & 1ull) continue;
+    seen |= 1ull << e;
+    int s = L.expert_slot[e];
+    if (s >= 0) {
+      touch(L, s);
+      continue;
+    }
+    s = pick_victim(L, protected_mask);
+    if (s < 0) {
+      L.stats.prefetch_dropped++;
+      continue;
+    }
+    rc = place(ctx, L, e, s, true, ks);
+    if (rc) return rc;
+    L.stats.prefetch_issued++;
+  }
+  return MOE_OK;
+}
+
+int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, int m, float *dev_scores,
+                    int32_t *pinned_topm, void *stream) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  if (!dev_x || !dev_wp || !pinned_topm) return fail(MOE_E_ARG, "NULL pointer in predictor_score");
+  if (T <= 0 || m <= 0 || m > ctx->cfg.E) return fail(MOE_E_ARG, "need T > 0 and 1 <= m <= E");
+  if (!aligned(dev_x, 16) || !aligned(dev_wp, 16)) return fail(MOE_E_ARG, "16-byte alignment needed");
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  Timer t(ctx, s, MOE_K_PREDICTOR);
+  HIP_TRY(launch_predictor(reinterpret_cast<const uint16_t *>(dev_x), reinterpret_cast<const uint16_t *>(dev_wp),
+                           T, ctx->cfg.d, ctx->cfg.E, m, dev_scores ? dev_scores : ctx->dev_scores,
+                           pinned_topm, s));
+  return MOE_OK;
+}
+
+int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
+                      int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
+                      void *compute_stream, void *copy_stream) {
+  return run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
+                   compute_stream, copy_stream, false);
+}
+
+int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
+                     int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
+                     void *compute_stream, void *copy_stream) {
+  return run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
+                   compute_stream, copy_stream, true);
+}
+
+int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *dev_ids, float *dev_w,
+                      int32_t *dev_counts, int32_t *dev_offsets, int32_t *dev_perm, int32_t *dev_inv_perm,
+                      void *stream) {
+  if (!ctx || !dev_workspace || T <= 0) return fail(MOE_E_ARG, "bad argument to moe_debug_routing");
+  const moe_config &c = ctx->cfg;
+  const WsLayout W = ws_layout(c, T);
+  const char *ws = reinterpret_cast<const char *>(dev_workspace);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const size_t n = (size_t)T * c.k;
+  if (dev_ids) HIP_TRY(hipMemcpyAsync(dev_ids, ws + W.ids, n * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_w) HIP_TRY(hipMemcpyAsync(dev_w, ws + W.w, n * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_counts) HIP_TRY(hipMemcpyAsync(dev_counts, ws + W.counts, (size_t)c.E * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_offsets)
+    HIP_TRY(hipMemcpyAsync(dev_offsets, ws + W.offsets, (size_t)(c.E + 1) * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_perm) HIP_TRY(hipMemcpyAsync(dev_perm, ws + W.perm, n * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_inv_perm) HIP_TRY(hipMemcpyAsync(dev_inv_perm, ws + W.inv_perm, n * 4, hipMemcpyDeviceToDevice, s));
+  return MOE_OK;
+}
+
+int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out) {
+  if (!ctx || !out) return fail(MOE_E_ARG, "NULL argument");
+  moe_stats acc{};
+  if (layer >= ctx->cfg.n_layers) return fail(MOE_E_ARG, "layer %d out of range", layer);
+  for (int l = 0; l < ctx->cfg.n_layers; ++l) {
+    if (layer >= 0 && l != layer) continue;
+    const moe_stats &s = ctx->layers[l].stats;
+    acc.hits += s.hits;
+    acc.misses += s.misses;
+    acc.prefetch_issued += s.prefetch_issued;
+    acc.prefetch_useful += s.prefetch_useful;
+    acc.prefetch_dropped += s.prefetch_dropped;
+    acc.layer_calls += s.layer_calls;
+    acc.bytes_h2d += s.bytes_h2d;
+  }
+  *out = acc;
+  return MOE_OK;
+}
+
+int moe_reset_stats(moe_ctx *ctx) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  for (Layer &L : ctx->layers) L.stats = moe_stats{};
+  return MOE_OK;
+}
+
+int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert) {
+  Layer *Lp = nullptr;
+  int rc = get_layer(ctx, layer, &Lp);
+  if (rc) return rc;
+  if (!host_slot_expert) return fail(MOE_E_ARG, "NULL argument");
+  for (int s = 0; s < ctx->cfg.cache_slots; ++s) host_slot_expert[s] = Lp->slot_expert[s];
+  return MOE_OK;
+}
+
+int moe_set_profiling(moe_ctx *ctx, int on) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  ctx->profiling = on != 0;
+  return MOE_OK;
+}
+
+int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
+  if (!ctx || !ms || !launches) return fail(MOE_E_ARG, "NULL argument");
+  for (int i = 0; i < MOE_K_COUNT; ++i) {
+    ms[i] = 0.0f;
+    launches[i] = 0;
+  }
+  for (auto &t : ctx->timed) {
+    HIP_TRY(hipEventSynchronize(t.stop));
+    float dt = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&dt, t.start, t.stop));
+    ms[t.kind] += dt;
+    launches[t.kind]++;
+    ctx->event_pool.push_back(t.start);
+    ctx->event_pool.push_back(t.stop);
+  }
+  ctx->timed.clear();
+  return MOE_OK;
+}
+
+int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M, int N, int K, void *stream) {
+  if (!dev_a || !dev_b || !dev_c) return fail(MOE_E_ARG, "NULL pointer in moe_dense_gemm_bf16");
+  if (M <= 0 || N <= 0 || K <= 0 || K % 8) return fail(MOE_E_ARG, "M, N, K must be positive and K a multiple of 8");
+  if (!aligned(dev_a, 16) || !aligned(dev_b, 16) || !aligned(dev_c, 16)) return fail(MOE_E_ARG, "16-byte alignment needed");
+  GemmArgs a{};
+  a.A = reinterpret_cast<const uint16_t *>(dev_a);
+  a.lda = K;
+  a.k_top = 1;
+  a.single_rows = M;
+  a.group_mask = 1;
+  a.n_groups = 1;
+  a.wbase = reinterpret_cast<const char *>(dev_b);
+  a.ldb = K;
+  a.N = N;
+  a.K = K;
+  a.out = dev_c;
+  a.ldo = N;
+  a.splitk = 1;
+  HIP_TRY(launch_grouped_gemm(GEMM_PLAIN_BF16, a, M, 1, reinterpret_cast<hipStream_t>(stream)));
+  return MOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Grouping of the tokens by assigned expert (Section V-B of the paper): a stable counting sort
+// of the T*k assignments a = t*k + j by expert id.  Three small kernels, no ranks taken from
+// atomics, so the permutation is the unique stable one:
+//   1. per-block histogram (LDS integer atomics only count),
+//   2. one wave scans the block histograms per expert and the experts' totals,
+//   3. every block ranks its own assignments with wave ballots and scatters.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace moe {
+
+namespace {
+
+__global__ __launch_bounds__(kDispatchChunk) void dispatch_hist_kernel(const int32_t *__restrict__ ids,
+                                                                       int n, int E,
+                                                                       int32_t *__restrict__ blk_hist) {
+  __shared__ int hist[kMaxExperts];
+  const int tid = threadIdx.x;
+  if (tid < kMaxExperts) hist[tid] = 0;
+  __syncthreads();
+  const int a = blockIdx.x * kDispatchChunk + tid;
+  if (a < n) atomicAdd(&hist[ids[a]], 1);
+  __syncthreads();
+  if (tid < E) blk_hist[(size_t)blockIdx.x * E + tid] = hist[tid];
+}
+
+__global__ __launch_bounds__(64) void dispatch_scan_kernel(const int32_t *__restrict__ blk_hist,
+                                                           int nblk, int E,
+                                                           int32_t *__restrict__ blk_base,
+                                                           int32_t *__restrict__ counts,
+                                                           int32_t *__restrict__ offsets,
+                                                           int32_t *__restrict__ host_counts) {
+  const int e = threadIdx.x;
+  int run = 0;
+  if (e < E) {
+    for (int b = 0; b < nblk; ++b) {
+      int h = blk_hist[(size_t)b * E + e];
+      blk_base[(size_t)b * E + e] = run;
+      run += h;
+    }
+  }
+  // inclusive scan over the experts (lanes)
+  int incl = run;
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) {
+    int o = __shfl_up(incl, s);
+    if (e >= s) incl += o;
+  }
+  if (e < E) {
+    counts[e] = run;
+    offsets[e] = incl - run;
+    if (host_counts) host_counts[e] = run;
+  }
+  if (e == E - 1) offsets[E] = incl;
+}
+
+__global__ __launch_bounds__(kDispatchChunk) void dispatch_scatter_kernel(
+    const int32_t *__restrict__ ids, int n, int E, const int32_t *__restrict__ blk_base,
+    const int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm) {
+  constexpr int kWaves = kDispatchChunk / 64;
+  __shared__ int wave_cnt[kWaves][kMaxExperts];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < kWaves * kMaxExperts; i += kDispatchChunk) (&wave_cnt[0][0])[i] = 0;
+  __syncthreads();
+  const int a = blockIdx.x * kDispatchChunk + tid;
+  const bool valid = a < n;
+  const int e = valid ? ids[a] : 0;
+  // lanes of this wave holding the same expert (6 ballots, E <= 64)
+  unsigned long long peers = __ballot(valid);
+#pragma unroll
+  for (int bit = 0; bit < 6; ++bit) {
+    unsigned long long b = __ballot((e >> bit) & 1);
+    peers &= ((e >> bit) & 1) ? b : ~b;
+  }
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  const int rank_in_wave = __popcll(peers & lt);
+  if (valid && rank_in_wave == 0) wave_cnt[wave][e] = __popcll(peers);
+  __syncthreads();
+  if (valid) {
+    int base = offsets[e] + blk_base[(size_t)blockIdx.x * E + e];
+    for (int wv = 0; wv < wave; ++wv) base += wave_cnt[wv][e];
+    int p = base + rank_in_wave;
+    perm[p] = a;
+    inv_perm[a] = p;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
+                           int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                           int32_t *host_counts, hipStream_t stream) {
+  const int nblk = (n + kDispatchChunk - 1) / kDispatchChunk;
+  hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
+                     blk_hist);
+  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(64), 0, stream, blk_hist, nblk, E, blk_base,
+                     counts, offsets, host_counts);
+  hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
+                     blk_base, offsets, perm, inv_perm);
+  return hipGetLastError();
+}
+
+}  // namespace moe

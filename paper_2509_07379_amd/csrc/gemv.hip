@@ -1,0 +1,178 @@
+// Expert mat-vec for the decode stage (Section V-C of the paper): a decode step routes a
+// handful of tokens, so every active expert's weights are streamed once from its cache slot
+// and the kernel is bound by HBM bandwidth, not by the matrix cores.
+//
+//   GEMM_SWIGLU     h[p, n] = bf16( silu(x_p . Wg[n]) * (x_p . Wu[n]) )
+//   GEMM_PLAIN_F32  y[p, c] = h_p . Wd[c]
+//
+// One wave owns R consecutive weight rows: each lane streams 16-byte pieces of those rows
+// (R or 2R independent loads in flight per step), multiplies them with the group's token
+// vectors held in LDS, and the 64 partial sums are reduced with a butterfly at the end.
+// Up to 8 tokens share one pass over the weights; the token count selects the unrolling.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace moe {
+
+namespace {
+
+constexpr int GV_THREADS = 256;
+constexpr int GV_WAVES = GV_THREADS / 64;
+constexpr int GV_R = 4;        // weight rows per wave
+constexpr int GV_MAXTOK = 8;   // tokens per pass over the weights
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float dot8(const u32x4 &xv, const u32x4 &wv, float acc) {
+  acc = fmaf(bf16_lo(xv.x), bf16_lo(wv.x), acc);
+  acc = fmaf(bf16_hi(xv.x), bf16_hi(wv.x), acc);
+  acc = fmaf(bf16_lo(xv.y), bf16_lo(wv.y), acc);
+  acc = fmaf(bf16_hi(xv.y), bf16_hi(wv.y), acc);
+  acc = fmaf(bf16_lo(xv.z), bf16_lo(wv.z), acc);
+  acc = fmaf(bf16_hi(xv.z), bf16_hi(wv.z), acc);
+  acc = fmaf(bf16_lo(xv.w), bf16_lo(wv.w), acc);
+  acc = fmaf(bf16_hi(xv.w), bf16_hi(wv.w), acc);
+  return acc;
+}
+
+template <int MODE, int NT, int NTMAX>
+__device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg_chunks,
+                                           const u32x4 *const (&w0)[GV_R], const u32x4 *const (&w1)[GV_R],
+                                           int lane, float (&acc0)[GV_R][NTMAX],
+                                           float (&acc1)[GV_R][NTMAX]) {
+#pragma unroll 2
+  for (int c = lane; c < seg_chunks; c += 64) {
+    u32x4 wv0[GV_R], wv1[GV_R];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      wv0[r] = __builtin_nontemporal_load(w0[r] + c);
+      if (MODE == GEMM_SWIGLU) wv1[r] = __builtin_nontemporal_load(w1[r] + c);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      u32x4 xv = xs[t * seg_chunks + c];
+#pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        acc0[r][t] = dot8(xv, wv0[r], acc0[r][t]);
+        if (MODE == GEMM_SWIGLU) acc1[r][t] = dot8(xv, wv1[r], acc1[r][t]);
+      }
+    }
+  }
+}
+
+template <int MODE, int NTMAX>
+__global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs args, int kseg,
+                                                                     int ntcap) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  // group of this block: the blockIdx.y-th expert of the mask
+  int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
+  if (args.offsets) {
+    unsigned long long m = args.group_mask;
+    for (unsigned i = 0; i < blockIdx.y; ++i) m &= m - 1;
+    grp = __ffsll((long long)m) - 1;
+    row0 = args.offsets[grp];
+    cnt = args.offsets[grp + 1] - row0;
+  }
+  if (cnt <= 0) return;
+
+  const char *wptr = args.wbase + (long long)args.slot[grp] * args.wstride;
+  const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
+  const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
+  const int n_first = (blockIdx.x * GV_WAVES + wave) * GV_R;
+
+  for (int tok0 = 0; tok0 < cnt; tok0 += ntcap) {
+    const int ntok = min(ntcap, cnt - tok0);  // ntcap <= NTMAX tokens fit the LDS buffer
+    float acc0[GV_R][NTMAX], acc1[GV_R][NTMAX];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r)
+#pragma unroll
+      for (int t = 0; t < NTMAX; ++t) acc0[r][t] = acc1[r][t] = 0.0f;
+
+    for (int k0 = 0; k0 < args.K; k0 += kseg) {
+      const int seg = min(kseg, args.K - k0);
+      const int seg_chunks = seg >> 3;
+      __syncthreads();  // previous segment fully consumed
+      for (int c = tid; c < ntok * seg_chunks; c += GV_THREADS) {
+        int t = c / seg_chunks, cc = c - t * seg_chunks;
+        int p = row0 + tok0 + t;
+        long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
+        xs[c] = *reinterpret_cast<const u32x4 *>(args.A + srow * args.lda + k0 + cc * 8);
+      }
+      __syncthreads();
+      const u32x4 *w0[GV_R], *w1[GV_R];
+#pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        int n = min(n_first + r, args.N - 1);
+        w0[r] = reinterpret_cast<const u32x4 *>(B0 + (long long)n * args.ldb + k0);
+        w1[r] = reinterpret_cast<const u32x4 *>(B1 + (long long)n * args.ldb + k0);
+      }
+#define MOE_GEMV_CASE(NT)                                                             \
+  if constexpr (NT <= NTMAX) {                                                        \
+    if (ntok == NT) accumulate<MODE, NT, NTMAX>(xs, seg_chunks, w0, w1, lane, acc0, acc1); \
+  }
+      MOE_GEMV_CASE(1) MOE_GEMV_CASE(2) MOE_GEMV_CASE(3) MOE_GEMV_CASE(4)
+      MOE_GEMV_CASE(5) MOE_GEMV_CASE(6) MOE_GEMV_CASE(7) MOE_GEMV_CASE(8)
+#undef MOE_GEMV_CASE
+    }
+
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      const int n = n_first + r;
+#pragma unroll
+      for (int t = 0; t < NTMAX; ++t) {
+        if (t >= ntok) break;
+        float s0 = wave_sum_tree(acc0[r][t]);
+        float s1 = (MODE == GEMM_SWIGLU) ? wave_sum_tree(acc1[r][t]) : 0.0f;
+        if (lane == 0 && n < args.N) {
+          const long long o = (long long)(row0 + tok0 + t) * args.ldo + n;
+          if (MODE == GEMM_SWIGLU)
+            reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(silu(s0) * s1);
+          else
+            reinterpret_cast<float *>(args.out)[o] = s0;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
+                               int n_groups_in_mask, hipStream_t stream) {
+  if (n_groups_in_mask <= 0 || max_rows_per_group <= 0) return hipSuccess;
+  const int ntcap = max_rows_per_group < GV_MAXTOK ? max_rows_per_group : GV_MAXTOK;
+  int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
+  if (kseg >= args.K) kseg = args.K;
+  const size_t smem = (size_t)ntcap * kseg * 2;
+  dim3 grid((args.N + GV_WAVES * GV_R - 1) / (GV_WAVES * GV_R), n_groups_in_mask);
+#define MOE_GEMV_LAUNCH(MODE, NTMAX)                                                          \
+  do {                                                                                        \
+    auto kern = grouped_gemv_kernel<MODE, NTMAX>;                                             \
+    static bool attr_set = false;                                                             \
+    if (!attr_set) {                                                                          \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 65536);  \
+      if (e != hipSuccess) return e;                                                          \
+      attr_set = true;                                                                        \
+    }                                                                                         \
+    hipLaunchKernelGGL(kern, grid, dim3(GV_THREADS), smem, stream, args, kseg, ntcap);        \
+  } while (0)
+  if (mode == GEMM_SWIGLU) {
+    if (ntcap == 1) MOE_GEMV_LAUNCH(GEMM_SWIGLU, 1);
+    else if (ntcap == 2) MOE_GEMV_LAUNCH(GEMM_SWIGLU, 2);
+    else if (ntcap <= 4) MOE_GEMV_LAUNCH(GEMM_SWIGLU, 4);
+    else MOE_GEMV_LAUNCH(GEMM_SWIGLU, 8);
+  } else {
+    if (ntcap == 1) MOE_GEMV_LAUNCH(GEMM_PLAIN_F32, 1);
+    else if (ntcap == 2) MOE_GEMV_LAUNCH(GEMM_PLAIN_F32, 2);
+    else if (ntcap <= 4) MOE_GEMV_LAUNCH(GEMM_PLAIN_F32, 4);
+    else MOE_GEMV_LAUNCH(GEMM_PLAIN_F32, 8);
+  }
+#undef MOE_GEMV_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,71 @@
+// Internal launcher interface between the host logic (api.cpp) and the gfx950 kernels.
+// Every launcher only enqueues on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe {
+
+constexpr int kMaxExperts = 64;   // one lane per expert in the wave-wide top-k
+constexpr int kDispatchChunk = 256;  // assignments per dispatch block
+
+// ---- gate: logits (fixed fp32 summation order), top-k, gate values -------------------
+// x [T,d] bf16, wr [E,d] bf16, bias NULL or fp32 [t*bias_stride + e].
+// Outputs: ids [T,k] (descending logit, lower id on ties), w [T,k] fp32, logits [T,E] (may be NULL).
+hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
+                              int bias_stride, int T, int d, int E, int k, int renormalize,
+                              float *logits, int32_t *ids, float *w, hipStream_t stream);
+
+// Predictor stand-in: scores[e] = sum_t x[t].wp[e] (same summation order per token, tokens
+// ascending), top-m ids to `top_out` (device-visible, e.g. pinned host memory).
+hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
+                            float *scores, int32_t *top_out, hipStream_t stream);
+
+// ---- dispatch: stable counting sort of the T*k assignments by expert ------------------
+// blk_hist / blk_base: [ceil(n/kDispatchChunk) * E] scratch.  counts [E], offsets [E+1],
+// perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned).
+hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
+                           int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                           int32_t *host_counts, hipStream_t stream);
+
+// ---- grouped GEMM on bf16 MFMA --------------------------------------------------------
+struct GemmArgs {
+  const uint16_t *A;      // activations, row-major bf16
+  int lda;                // elements between A rows
+  const int32_t *perm;    // non-NULL: sorted row p reads A row perm[p] / k_top (token gather)
+  int k_top;
+  const int32_t *offsets; // device [n_groups+1] sorted-row offsets; NULL = one group
+  int single_row0, single_rows;   // the one group when offsets == NULL
+  unsigned long long group_mask;  // experts that take part (bit e)
+  int n_groups;
+  const char *wbase;      // expert e's blob at wbase + slot[e] * wstride
+  long long wstride;
+  signed char slot[kMaxExperts];
+  long long b0_off, b1_off;  // byte offsets in the blob of the B rows (gate|down) and (up)
+  int ldb;                // elements between B rows (= K)
+  int N;                  // output columns (SwiGLU: I; the block reads N gate rows and N up rows)
+  int K;
+  void *out;              // rows indexed by sorted position
+  int ldo;
+  int splitk;             // K slices, each written to its own output plane
+  long long out_split_stride;  // elements between planes
+};
+
+enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
+
+// max_rows: host upper bound of the rows summed over the groups in the mask.
+hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,
+                               hipStream_t stream);
+
+// ---- decode: bandwidth-bound expert mat-vec --------------------------------------------
+// Same argument block; rows per group are few (decode batch).  SWIGLU -> bf16 h, PLAIN_F32 -> fp32 y.
+hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
+                               int n_groups_in_mask, hipStream_t stream);
+
+// ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----
+hipError_t launch_combine(const float *Y, int y_planes, long long y_plane_stride, const float *w,
+                          const int32_t *inv_perm, const float *Yshared, int ys_planes,
+                          long long ys_plane_stride, int T, int d, int k, uint16_t *out,
+                          hipStream_t stream);
+
+}  // namespace moe

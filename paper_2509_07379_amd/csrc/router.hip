@@ -1,0 +1,184 @@
+// Gate of the MoE layer (Section II-A of the paper): logits = x . Wr^T, Top-k of n experts,
+// gate values by softmax.  Also the linear stand-in for the layer-level predictor
+// (Section IV-B / V-C): scores summed over the batch, top-m.
+//
+// The Top-k decision is an integer result, so the fp32 dot products are summed in one
+// documented order that a scalar CPU replay can follow: element i belongs to lane
+// (i / 8) mod 64, each lane adds its products in ascending i (bf16 x bf16 products are
+// exact in fp32, so fma == mul + add), the 64 lanes are then summed by a butterfly that
+// pairs lanes differing in bit 5 first and bit 0 last, and the bias is added last.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace moe {
+
+namespace {
+
+constexpr int kRouterThreads = 256;
+constexpr int kRouterWaves = kRouterThreads / 64;
+
+__device__ __forceinline__ float dot8_ordered(const uint4 &xv, const uint4 &wv, float acc) {
+  acc = fmaf(bf16_lo(xv.x), bf16_lo(wv.x), acc);
+  acc = fmaf(bf16_hi(xv.x), bf16_hi(wv.x), acc);
+  acc = fmaf(bf16_lo(xv.y), bf16_lo(wv.y), acc);
+  acc = fmaf(bf16_hi(xv.y), bf16_hi(wv.y), acc);
+  acc = fmaf(bf16_lo(xv.z), bf16_lo(wv.z), acc);
+  acc = fmaf(bf16_hi(xv.z), bf16_hi(wv.z), acc);
+  acc = fmaf(bf16_lo(xv.w), bf16_lo(wv.w), acc);
+  acc = fmaf(bf16_hi(xv.w), bf16_hi(wv.w), acc);
+  return acc;
+}
+
+// Wave-wide selection of the n_sel best of E values (one lane per expert): value descending,
+// lower index on ties.  Lane j < n_sel returns the j-th selected (value, index).
+__device__ __forceinline__ void wave_select(float v, int E, int n_sel, float &sel_val, int &sel_idx) {
+  const int lane = lane_id();
+  bool avail = lane < E;
+  sel_val = 0.0f;
+  sel_idx = -1;
+  for (int j = 0; j < n_sel; ++j) {
+    float cv = avail ? v : -INFINITY;
+    int ci = avail ? lane : 64 + lane;  // unavailable lanes lose every tie
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      float ov = __shfl_xor(cv, m);
+      int oi = __shfl_xor(ci, m);
+      bool take = (ov > cv) || (ov == cv && oi < ci);
+      cv = take ? ov : cv;
+      ci = take ? oi : ci;
+    }
+    if (lane == ci) avail = false;
+    if (lane == j) {
+      sel_val = cv;
+      sel_idx = ci;
+    }
+  }
+}
+
+template <int TPB>
+__global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr, const float *__restrict__ bias,
+    int bias_stride, int T, int d, int E, int k, int renormalize, float *__restrict__ logits,
+    int32_t *__restrict__ ids, float *__restrict__ w) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint4 *xs = reinterpret_cast<uint4 *>(smem);                           // [TPB][d/8]
+  float *lg = reinterpret_cast<float *>(smem + (size_t)TPB * d * 2);     // [TPB][64]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t0 = blockIdx.x * TPB;
+  const int nchunk = d >> 3;
+
+  for (int c = tid; c < TPB * nchunk; c += kRouterThreads) {
+    int tok = c / nchunk, cc = c - tok * nchunk;
+    int t = min(t0 + tok, T - 1);
+    xs[c] = reinterpret_cast<const uint4 *>(x + (size_t)t * d)[cc];
+  }
+  __syncthreads();
+
+  for (int e = wave; e < E; e += kRouterWaves) {
+    float acc[TPB];
+#pragma unroll
+    for (int q = 0; q < TPB; ++q) acc[q] = 0.0f;
+    const uint4 *wrow = reinterpret_cast<const uint4 *>(wr + (size_t)e * d);
+    for (int c = lane; c < nchunk; c += 64) {
+      uint4 wv = wrow[c];
+#pragma unroll
+      for (int q = 0; q < TPB; ++q) acc[q] = dot8_ordered(xs[q * nchunk + c], wv, acc[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < TPB; ++q) {
+      float s = wave_sum_tree(acc[q]);
+      int t = t0 + q;
+      if (lane == 0 && t < T) {
+        if (bias) s = s + bias[(size_t)t * bias_stride + e];
+        lg[q * 64 + e] = s;
+      }
+    }
+  }
+  __syncthreads();
+
+  for (int q = wave; q < TPB; q += kRouterWaves) {
+    int t = t0 + q;
+    if (t >= T) break;
+    float v = lane < E ? lg[q * 64 + lane] : -INFINITY;
+    if (logits && lane < E) logits[(size_t)t * E + lane] = v;
+    float sv;
+    int si;
+    wave_select(v, E, k, sv, si);
+    float top1 = __shfl(sv, 0);
+    float wj;
+    if (renormalize) {
+      float p = lane < k ? expf(sv - top1) : 0.0f;
+      wj = p / wave_sum_tree(p);
+    } else {
+      float p = lane < E ? expf(v - top1) : 0.0f;
+      wj = expf(sv - top1) / wave_sum_tree(p);
+    }
+    if (lane < k) {
+      ids[(size_t)t * k + lane] = si;
+      w[(size_t)t * k + lane] = wj;
+    }
+  }
+}
+
+// scores[e] = sum_t dot(x[t], wp[e]); one wave per expert.
+__global__ __launch_bounds__(kRouterThreads) void predictor_scores_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ wp, int T, int d, int E,
+    float *__restrict__ scores) {
+  const int lane = threadIdx.x & 63;
+  const int e = blockIdx.x * kRouterWaves + (threadIdx.x >> 6);
+  if (e >= E) return;
+  const int nchunk = d >> 3;
+  const uint4 *wrow = reinterpret_cast<const uint4 *>(wp + (size_t)e * d);
+  float s = 0.0f;
+  for (int t = 0; t < T; ++t) {
+    const uint4 *xrow = reinterpret_cast<const uint4 *>(x + (size_t)t * d);
+    float acc = 0.0f;
+    for (int c = lane; c < nchunk; c += 64) acc = dot8_ordered(xrow[c], wrow[c], acc);
+    s = s + wave_sum_tree(acc);
+  }
+  if (lane == 0) scores[e] = s;
+}
+
+__global__ __launch_bounds__(64) void predictor_topm_kernel(const float *__restrict__ scores, int E,
+                                                            int m, int32_t *__restrict__ top_out) {
+  const int lane = threadIdx.x;
+  float v = lane < E ? scores[lane] : -INFINITY;
+  float sv;
+  int si;
+  wave_select(v, E, m, sv, si);
+  if (lane < m) top_out[lane] = si;
+}
+
+}  // namespace
+
+hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
+                              int bias_stride, int T, int d, int E, int k, int renormalize,
+                              float *logits, int32_t *ids, float *w, hipStream_t stream) {
+  // 4 tokens per block share one pass over Wr; small batches use 1 token per block.
+  if (T >= 64) {
+    constexpr int TPB = 4;
+    size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
+    int grid = (T + TPB - 1) / TPB;
+    hipLaunchKernelGGL(router_topk_kernel<TPB>, dim3(grid), dim3(kRouterThreads), smem, stream, x, wr,
+                       bias, bias_stride, T, d, E, k, renormalize, logits, ids, w);
+  } else {
+    constexpr int TPB = 1;
+    size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
+    hipLaunchKernelGGL(router_topk_kernel<TPB>, dim3(T), dim3(kRouterThreads), smem, stream, x, wr,
+                       bias, bias_stride, T, d, E, k, renormalize, logits, ids, w);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
+                            float *scores, int32_t *top_out, hipStream_t stream) {
+  int grid = (E + kRouterWaves - 1) / kRouterWaves;
+  hipLaunchKernelGGL(predictor_scores_kernel, dim3(grid), dim3(kRouterThreads), 0, stream, x, wp, T,
+                     d, E, scores);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(predictor_topm_kernel, dim3(1), dim3(64), 0, stream, scores, E, m, top_out);
+  return hipGetLastError();
+}
+
+}  // namespace moe

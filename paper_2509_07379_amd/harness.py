@@ -1,0 +1,92 @@
+"""Memory plumbing around the C-ABI library: allocates the CPU expert cache (pinned), the GPU
+expert cache (slots), router / shared weights and the workspace with torch, fills them from the
+seeded generators and binds them to a MoeContext.  No arithmetic of the method lives here.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import synth as S
+from .binding import MoeContext
+
+
+def np_to_dev(a: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """uint16 (bf16 bits) / float32 / int32 numpy array -> device tensor with the same bits."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device)
+    return torch.from_numpy(a).to(device)
+
+
+def dev_to_np_u16(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+class HostPool:
+    """All experts of one layer in pinned host memory: the CPU expert cache (Section V-A)."""
+
+    def __init__(self, w: S.Workload, layer: int, fill: bool = True, share_from: "HostPool | None" = None):
+        self.w, self.layer = w, layer
+        if share_from is not None:
+            self.buf = share_from.buf
+        else:
+            self.buf = torch.empty((w.E, w.blob_elems), dtype=torch.int16, pin_memory=True)
+            if fill:
+                for e in range(w.E):
+                    S.expert_blob_into(self.ptr(e), w, layer, e)
+
+    def ptr(self, e: int) -> int:
+        return self.buf.data_ptr() + e * self.w.blob_bytes
+
+    def ptrs(self):
+        return [self.ptr(e) for e in range(self.w.E)]
+
+    def blob_np(self, e: int) -> np.ndarray:
+        return self.buf[e].numpy().view(np.uint16)
+
+
+class DeviceLayer:
+    """Device-side memory of one layer, bound to `ctx` as layer `layer`."""
+
+    def __init__(self, ctx: MoeContext, w: S.Workload, layer: int, pool: HostPool, initial=None,
+                 device="cuda:0", poison: bool = False):
+        self.ctx, self.w, self.layer, self.pool = ctx, w, layer, pool
+        Sslots = ctx.cfg.cache_slots
+        self.router_np = S.router_weight(w, layer)
+        self.router = np_to_dev(self.router_np, device)
+        self.shared_np = S.shared_blob(w, layer)
+        self.shared = np_to_dev(self.shared_np, device) if self.shared_np is not None else None
+        self.slots = torch.empty((Sslots, w.blob_elems), dtype=torch.int16, device=device)
+        if poison:
+            self.slots.fill_(0x7FC0)  # bf16 NaN pattern: any read of an unfilled slot shows up
+        if initial is not None:
+            for s, e in enumerate(initial):
+                if e >= 0:
+                    self.slots[s].copy_(pool.buf[e], non_blocking=False)
+        ctx.moe_bind_layer(layer, pool.ptrs(), self.router, self.shared, self.slots, initial)
+
+
+class Buffers:
+    """x / y / workspace / routing-table tensors for calls on T tokens."""
+
+    def __init__(self, ctx: MoeContext, T: int, device="cuda:0"):
+        c = ctx.cfg
+        self.T = T
+        self.ws = torch.empty(ctx.moe_workspace_bytes(T), dtype=torch.uint8, device=device)
+        assert self.ws.data_ptr() % 256 == 0
+        self.y = torch.empty((T, c.d), dtype=torch.int16, device=device)
+        n = T * c.k
+        self.ids = torch.empty((T, c.k), dtype=torch.int32, device=device)
+        self.wts = torch.empty((T, c.k), dtype=torch.float32, device=device)
+        self.counts = torch.empty(c.E, dtype=torch.int32, device=device)
+        self.offsets = torch.empty(c.E + 1, dtype=torch.int32, device=device)
+        self.perm = torch.empty(n, dtype=torch.int32, device=device)
+        self.inv_perm = torch.empty(n, dtype=torch.int32, device=device)
+
+    def routing(self, ctx: MoeContext, stream) -> dict:
+        ctx.moe_debug_routing(self.ws, self.T, self.ids, self.wts, self.counts, self.offsets, self.perm,
+                              self.inv_perm, stream)
+        stream.synchronize()
+        return dict(ids=self.ids.cpu().numpy(), w=self.wts.cpu().numpy(), counts=self.counts.cpu().numpy(),
+                    offsets=self.offsets.cpu().numpy(), perm=self.perm.cpu().numpy(),
+                    inv_perm=self.inv_perm.cpu().numpy())

@@ -1,0 +1,224 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle.  Needs an MI355X."""
+import numpy as np
+import pytest
+
+from paper_2509_07379_amd import synth as S
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+# tolerance stated for bf16-in / fp32-accumulate outputs: 2e-2 relative + 1e-2 absolute
+RTOL, ATOL = 2e-2, 1e-2
+
+
+def check_out(got_bits, ref_f64, tag=""):
+    """Element-wise |gpu - ref| <= ATOL + RTOL*|ref|, plus a scale-aware bound (the stated absolute
+    term alone would hide errors on outputs much smaller than 1e-2)."""
+    got = S.bf16_to_f32(got_bits).astype(np.float64)
+    err = np.abs(got - ref_f64)
+    assert np.all(np.isfinite(got)), tag
+    assert np.all(err <= ATOL + RTOL * np.abs(ref_f64)), f"{tag}: max err {err.max()}"
+    rms = float(np.sqrt(np.mean(ref_f64 ** 2)))
+    assert np.all(err <= RTOL * np.abs(ref_f64) + RTOL * rms), f"{tag}: max err {err.max()} rms {rms}"
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests selected but no GPU is visible")
+    from paper_2509_07379_amd import binding, harness
+    binding.load()
+    torch.cuda.set_device(0)
+    return dict(binding=binding, harness=harness, compute=torch.cuda.Stream(), copy=torch.cuda.Stream())
+
+
+def oracle_layer(oracle, w, x, router, pool, bias=None, sel=None, shared=None):
+    blobs = [pool.blob_np(e) for e in range(w.E)]
+    return oracle.moe_layer(x, router, blobs, w.k, bias=bias, sel=sel, shared_blob=shared, I=w.I,
+                            I_shared=w.I_shared)
+
+
+def run_layer(gpu, w, T, x_np, S_slots, initial, decode=False, bias=None, prefetch=None, poison=False,
+              pool=None):
+    H, B = gpu["harness"], gpu["binding"]
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True)
+    pool = pool or H.HostPool(w, 0)
+    lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=poison)
+    buf = H.Buffers(ctx, T)
+    x = H.np_to_dev(x_np)
+    bias_t = None if bias is None else torch.from_numpy(bias).cuda()
+    stride = 0 if bias is None or bias.ndim == 1 else w.E
+    torch.cuda.synchronize()
+    if prefetch is not None:
+        ctx.expert_cache_prefetch(0, prefetch, gpu["copy"])
+    fn = ctx.moe_decode_layer if decode else ctx.moe_prefill_layer
+    fn(0, x, T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias_t, stride)
+    gpu["compute"].synchronize()
+    out = H.dev_to_np_u16(buf.y)
+    routing = buf.routing(ctx, gpu["compute"])
+    stats = ctx.moe_get_stats(0)
+    state = ctx.moe_cache_state(0)
+    ctx.close()
+    return dict(out=out, routing=routing, stats=stats, state=state, pool=pool, lay=lay)
+
+
+# ---------------------------------------------------------------- the MFMA tile itself
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 136, 192), (8, 8, 8), (513, 264, 1096)])
+def test_dense_gemm_matches_matmul(gpu, M, N, K):
+    a = S.normal_bf16((M, K), 1, 100 + M, 1.0)
+    b = S.normal_bf16((N, K), 1, 200 + N, 1.0)
+    H, B = gpu["harness"], gpu["binding"]
+    c = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    B.moe_dense_gemm_bf16(H.np_to_dev(a), H.np_to_dev(b), c, M, N, K, gpu["compute"])
+    gpu["compute"].synchronize()
+    want = S.bf16_to_f32(a).astype(np.float64) @ S.bf16_to_f32(b).astype(np.float64).T
+    got = S.bf16_to_f32(H.dev_to_np_u16(c)).astype(np.float64)
+    assert np.all(np.abs(got - want) <= 2.0 ** -7 * np.abs(want) + 1e-3 * np.sqrt(K))
+
+
+# ---------------------------------------------------------------- config 1, all resident
+def test_c1_routing_bit_exact_and_output(gpu, oracle):
+    w = S.WORKLOADS["c1_tiny"]
+    x = S.activations(w)
+    r = run_layer(gpu, w, w.T, x, w.E, list(range(w.E)))
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"])
+    for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
+        np.testing.assert_array_equal(r["routing"][key], ref[key], err_msg=key)
+    np.testing.assert_allclose(r["routing"]["w"], ref["w"], rtol=1e-5, atol=1e-7)
+    check_out(r["out"], ref["out_f64"], "c1 prefill")
+    assert r["stats"]["hits"] == int((ref["counts"] > 0).sum()) and r["stats"]["misses"] == 0
+    assert r["stats"]["bytes_h2d"] == 0
+
+
+def test_c1_decode_kernels_same_layer(gpu, oracle):
+    # the mat-vec path on the same 64 tokens (several passes of 8 tokens per expert)
+    w = S.WORKLOADS["c1_tiny"]
+    x = S.activations(w)
+    r = run_layer(gpu, w, w.T, x, w.E, list(range(w.E)), decode=True)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"])
+    np.testing.assert_array_equal(r["routing"]["perm"], ref["perm"])
+    check_out(r["out"], ref["out_f64"], "c1 decode kernels")
+
+
+# ---------------------------------------------------------------- ragged shapes, biases, shared experts
+@pytest.mark.parametrize("d,I,E,k,T,Ish", [(256, 384, 60, 4, 333, 0), (512, 128, 64, 6, 777, 256),
+                                           (128, 64, 8, 2, 1, 0), (256, 192, 5, 5, 37, 64)])
+@pytest.mark.parametrize("decode", [False, True])
+def test_ragged_shapes(gpu, oracle, d, I, E, k, T, Ish, decode):
+    if decode and T > 64:
+        T = 9
+    w = S.Workload("rag", d=d, I=I, E=E, k=k, T=T, I_shared=Ish, seed=21, zipf_s=1.1)
+    x = S.activations(w)
+    bias = S.zipf_route_bias(w, 0)  # skewed popularity: some experts get few or no rows
+    r = run_layer(gpu, w, T, x, E, list(range(E)), decode=decode, bias=bias)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias, shared=r["lay"].shared_np)
+    for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
+        np.testing.assert_array_equal(r["routing"][key], ref[key], err_msg=key)
+    check_out(r["out"], ref["out_f64"], f"ragged decode={decode}")
+
+
+def test_per_token_bias_forces_trace(gpu, oracle):
+    w = S.Workload("trace", d=256, I=128, E=60, k=4, T=8, seed=5, L=3, steps=2, p_stay=0.5)
+    trace = S.markov_trace(w)
+    x = S.activations(w)
+    bias = S.trace_route_bias(trace[1, 2], w.E)
+    r = run_layer(gpu, w, w.T, x, w.E, list(range(w.E)), decode=True, bias=bias)
+    assert np.array_equal(np.sort(r["routing"]["ids"], 1), np.sort(trace[1, 2], 1))
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias)
+    np.testing.assert_array_equal(r["routing"]["ids"], ref["ids"])
+    check_out(r["out"], ref["out_f64"], "trace bias")
+
+
+# ---------------------------------------------------------------- offloaded: results never depend on the cache
+@pytest.mark.parametrize("decode", [False, True])
+def test_streaming_through_two_slots_is_bit_identical(gpu, oracle, decode):
+    from oracle.cache_sim import CacheSim
+    w = S.WORKLOADS["c1_tiny"]
+    T = 16 if decode else w.T
+    x = S.activations(w, T=T)
+    res = run_layer(gpu, w, T, x, w.E, list(range(w.E)), decode=decode)
+    off = run_layer(gpu, w, T, x, 2, None, decode=decode, prefetch=[0, 1], poison=True)
+    np.testing.assert_array_equal(off["out"], res["out"])  # same kernels, same numbers
+    sim = CacheSim(w.E, 2, w.blob_bytes)
+    sim.prefetch([0, 1])
+    active = np.nonzero(res["routing"]["counts"])[0]
+    sim.serve(active)
+    assert off["stats"] == {**sim.counters(), "layer_calls": 1}
+    assert off["state"] == sim.slot_expert
+    # each active expert fetched exactly once (Section V-B)
+    assert off["stats"]["bytes_h2d"] == len(set(active) | {0, 1}) * w.blob_bytes
+
+
+def test_wrong_prediction_is_refetched_not_used(gpu, oracle):
+    from oracle.cache_sim import CacheSim
+    w = S.Workload("mis", d=256, I=128, E=8, k=2, T=1, seed=9)
+    x = S.activations(w)
+    res = run_layer(gpu, w, 1, x, 8, list(range(8)), decode=True)
+    act = sorted(res["routing"]["ids"][0].tolist())
+    wrong = [e for e in range(8) if e not in act][:3]
+    off = run_layer(gpu, w, 1, x, 3, None, decode=True, prefetch=wrong, poison=True)
+    np.testing.assert_array_equal(off["out"], res["out"])
+    sim = CacheSim(8, 3, w.blob_bytes)
+    sim.prefetch(wrong)
+    sim.serve(act)
+    assert off["stats"] == {**sim.counters(), "layer_calls": 1}
+    assert off["stats"]["misses"] == 2 and off["stats"]["prefetch_useful"] == 0
+
+
+# ---------------------------------------------------------------- predictor stand-in
+@pytest.mark.parametrize("B,d,E,m", [(1, 4096, 8, 3), (8, 2048, 60, 8), (3, 256, 64, 64)])
+def test_predictor_scores_and_topm(gpu, oracle, B, d, E, m):
+    Bn, H = gpu["binding"], gpu["harness"]
+    x = S.normal_bf16((B, d), 3, 1, 1.0)
+    wp = S.normal_bf16((E, d), 3, 2, 0.02)
+    ctx = Bn.MoeContext(d, 64, E, 1, 1, 1)
+    top = torch.zeros(m, dtype=torch.int32).pin_memory()
+    scores = torch.empty(E, dtype=torch.float32, device="cuda")
+    ctx.predictor_score(H.np_to_dev(x), B, H.np_to_dev(wp), m, top, gpu["compute"], scores)
+    gpu["compute"].synchronize()
+    ref_s, ref_top = oracle.predictor_score(x, wp, m)
+    np.testing.assert_array_equal(scores.cpu().numpy(), ref_s)  # same fp32 summation order
+    np.testing.assert_array_equal(top.numpy(), ref_top)
+    ctx.close()
+
+
+# ---------------------------------------------------------------- error paths (host checks only)
+def test_error_codes(gpu):
+    B = gpu["binding"]
+    with pytest.raises(B.MoeError) as e:
+        B.MoeContext(256, 128, 8, 9)
+    assert e.value.code == -1
+    with pytest.raises(B.MoeError) as e:
+        B.MoeContext(256, 128, 8, 2, 1, 0)
+    assert e.value.code == -1
+    with pytest.raises(B.MoeError) as e:
+        B.MoeContext(256, 128, 65, 2)
+    assert e.value.code == -2
+    with pytest.raises(B.MoeError) as e:
+        B.MoeContext(250, 128, 8, 2)
+    assert e.value.code == -2
+    ctx = B.MoeContext(256, 128, 8, 2)
+    x = torch.zeros((4, 256), dtype=torch.int16, device="cuda")
+    y = torch.zeros_like(x)
+    ws = torch.empty(ctx.moe_workspace_bytes(4), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.MoeError) as e:
+        ctx.moe_prefill_layer(0, x, 4, y, ws, gpu["compute"], gpu["copy"])
+    assert e.value.code == -4
+    with pytest.raises(B.MoeError) as e:
+        ctx.moe_prefill_layer(3, x, 4, y, ws, gpu["compute"], gpu["copy"])
+    assert e.value.code == -1
+    w = S.Workload("err", d=256, I=128, E=8, k=2, T=4)
+    H = gpu["harness"]
+    pool = H.HostPool(w, 0)
+    H.DeviceLayer(ctx, w, 0, pool, list(range(8)))
+    with pytest.raises(B.MoeError) as e:
+        ctx.moe_prefill_layer(0, x, 0, y, ws, gpu["compute"], gpu["copy"])
+    assert e.value.code == -1
+    with pytest.raises(B.MoeError) as e:
+        ctx.moe_prefill_layer(0, x, 4, y, ws[:1024], gpu["compute"], gpu["copy"])
+    assert e.value.code == -5
+    with pytest.raises(B.MoeError) as e:
+        ctx.expert_cache_prefetch(0, [8], gpu["copy"])
+    assert e.value.code == -1
+    ctx.close()
