@@ -152,6 +152,12 @@ int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *d
 /* Cache counters of `layer` (or summed over all layers if layer < 0). */
 int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out);
 int moe_reset_stats(moe_ctx *ctx);
+/*
+ * Forgets which experts the slots of `layer` hold (all slots become empty), e.g. because the
+ * slot memory now backs another set of experts.  Ordering against kernels that still read the
+ * slots is kept: later copies into them wait for those readers.
+ */
+int moe_cache_invalidate(moe_ctx *ctx, int layer);
 /* Expert id held by each slot of `layer` (-1 = empty) into host_slot_expert[S]. */
 int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert);
 

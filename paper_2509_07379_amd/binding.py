@@ -19,7 +19,7 @@ KERNEL_NAMES = ["router", "dispatch", "gemm1", "gemm2", "gemv1", "gemv2", "combi
 EXPORTS = [
     "moe_last_error", "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_bind_layer",
     "expert_cache_prefetch", "predictor_score", "moe_prefill_layer", "moe_decode_layer",
-    "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_state", "moe_set_profiling",
+    "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_invalidate", "moe_cache_state", "moe_set_profiling",
     "moe_get_kernel_times", "moe_dense_gemm_bf16",
 ]
 
@@ -73,6 +73,7 @@ def load():
     lib.moe_get_stats.argtypes = [vp, c_int, POINTER(MoeStats)]
     lib.moe_reset_stats.argtypes = [vp]
     lib.moe_cache_state.argtypes = [vp, c_int, POINTER(c_int32)]
+    lib.moe_cache_invalidate.argtypes = [vp, c_int]
     lib.moe_set_profiling.argtypes = [vp, c_int]
     lib.moe_get_kernel_times.argtypes = [vp, POINTER(c_float), POINTER(c_int32)]
     lib.moe_dense_gemm_bf16.argtypes = [vp, vp, vp, c_int, c_int, c_int, vp]
@@ -175,6 +176,9 @@ class MoeContext:
 
     def moe_reset_stats(self):
         _check(self.lib.moe_reset_stats(self._h))
+
+    def moe_cache_invalidate(self, layer):
+        _check(self.lib.moe_cache_invalidate(self._h, layer))
 
     def moe_cache_state(self, layer):
         S = self.cfg.cache_slots

@@ -665,6 +665,20 @@ int moe_reset_stats(moe_ctx *ctx) {
   return MOE_OK;
 }
 
+int moe_cache_invalidate(moe_ctx *ctx, int layer) {
+  Layer *Lp = nullptr;
+  int rc = get_layer(ctx, layer, &Lp);
+  if (rc) return rc;
+  Layer &L = *Lp;
+  for (size_t s = 0; s < L.slot_expert.size(); ++s) {
+    if (L.slot_expert[s] >= 0) L.expert_slot[L.slot_expert[s]] = -1;
+    L.slot_expert[s] = -1;
+    L.prefetched[s] = 0;
+    L.stamp[s] = 0;
+  }
+  return MOE_OK;
+}
+
 int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert) {
   Layer *Lp = nullptr;
   int rc = get_layer(ctx, layer, &Lp);
