@@ -178,6 +178,12 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches);
 int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M, int N, int K,
                         void *stream);
 
+/*
+ * Tuning hook: forces MFMA tile variant `variant` (0 = chosen by shape, the default) for the
+ * gate/up GEMM (mode 0), the down GEMM (mode 1) or the dense GEMM (mode 2).  Process-wide.
+ */
+int moe_set_gemm_variant(int mode, int variant);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ EXPORTS = [
     "moe_last_error", "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_bind_layer",
     "expert_cache_prefetch", "predictor_score", "moe_prefill_layer", "moe_decode_layer",
     "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_invalidate", "moe_cache_state", "moe_set_profiling",
-    "moe_get_kernel_times", "moe_dense_gemm_bf16",
+    "moe_get_kernel_times", "moe_dense_gemm_bf16", "moe_set_gemm_variant",
 ]
 
 
@@ -77,6 +77,7 @@ def load():
     lib.moe_set_profiling.argtypes = [vp, c_int]
     lib.moe_get_kernel_times.argtypes = [vp, POINTER(c_float), POINTER(c_int32)]
     lib.moe_dense_gemm_bf16.argtypes = [vp, vp, vp, c_int, c_int, c_int, vp]
+    lib.moe_set_gemm_variant.argtypes = [c_int, c_int]
     for name in EXPORTS:
         if name not in ("moe_last_error", "moe_workspace_bytes"):
             getattr(lib, name).restype = c_int
@@ -198,3 +199,7 @@ class MoeContext:
 
 def moe_dense_gemm_bf16(a, b, c, M, N, K, stream=None):
     _check(load().moe_dense_gemm_bf16(_ptr(a), _ptr(b), _ptr(c), M, N, K, _stream(stream)))
+
+
+def moe_set_gemm_variant(mode: int, variant: int):
+    _check(load().moe_set_gemm_variant(mode, variant))

@@ -713,6 +713,12 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
   return MOE_OK;
 }
 
+int moe_set_gemm_variant(int mode, int variant) {
+  if (mode < 0 || mode > 2 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  set_gemm_variant(mode, variant);
+  return MOE_OK;
+}
+
 int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M, int N, int K, void *stream) {
   if (!dev_a || !dev_b || !dev_c) return fail(MOE_E_ARG, "NULL pointer in moe_dense_gemm_bf16");
   if (M <= 0 || N <= 0 || K <= 0 || K % 8) return fail(MOE_E_ARG, "M, N, K must be positive and K a multiple of 8");

@@ -259,15 +259,33 @@ hipError_t launch_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, 
 
 }  // namespace
 
+// Tile shapes.  Variant 0 picks by shape; 1.. force one (tuning hook).
+static int g_variant[3] = {0, 0, 0};
+
+void set_gemm_variant(int mode, int variant) {
+  if (mode >= 0 && mode < 3) g_variant[mode] = variant;
+}
+
+template <int MODE>
+static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  int v = g_variant[MODE];
+  if (v == 0) v = 1;
+  switch (v) {
+    case 2: return launch_cfg<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 3: return launch_cfg<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 4: return launch_cfg<128, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 5: return launch_cfg<256, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 6: return launch_cfg<128, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
+    default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+  }
+}
+
 hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,
                                hipStream_t stream) {
   switch (mode) {
-    case GEMM_SWIGLU:
-      return launch_cfg<128, 128, 2, 2, GEMM_SWIGLU>(args, max_rows, n_groups_in_mask, stream);
-    case GEMM_PLAIN_F32:
-      return launch_cfg<128, 128, 2, 2, GEMM_PLAIN_F32>(args, max_rows, n_groups_in_mask, stream);
-    default:
-      return launch_cfg<128, 128, 2, 2, GEMM_PLAIN_BF16>(args, max_rows, n_groups_in_mask, stream);
+    case GEMM_SWIGLU: return launch_mode<GEMM_SWIGLU>(args, max_rows, n_groups_in_mask, stream);
+    case GEMM_PLAIN_F32: return launch_mode<GEMM_PLAIN_F32>(args, max_rows, n_groups_in_mask, stream);
+    default: return launch_mode<GEMM_PLAIN_BF16>(args, max_rows, n_groups_in_mask, stream);
   }
 }
 

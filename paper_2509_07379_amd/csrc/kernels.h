@@ -57,6 +57,9 @@ enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
 hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,
                                hipStream_t stream);
 
+// Tuning hook: force tile variant `variant` (0 = choose by shape) for GemmMode `mode`.
+void set_gemm_variant(int mode, int variant);
+
 // ---- decode: bandwidth-bound expert mat-vec --------------------------------------------
 // Same argument block; rows per group are few (decode batch).  SWIGLU -> bf16 h, PLAIN_F32 -> fp32 y.
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
