@@ -7,9 +7,12 @@
 //   GEMM_PLAIN_BF16 C = A . B^T (bf16; dense stand-in for the non-MoE block)
 //
 // Both operands are K-contiguous ("NT"), so every lane feeds the MFMA with 8 consecutive
-// bf16 of a row (one 16-byte LDS read).  Tiles are BM x BN x 64, staged through LDS with a
-// 16-byte XOR swizzle and double buffering (global loads of tile i+1 are in flight while the
-// MFMAs of tile i run; one barrier per K step).
+// bf16 of a row (one 16-byte LDS read).  Tiles are BM x BN x 64 in a two-stage LDS ring with
+// a 16-byte XOR swizzle.  The main kernel fills the ring with direct global->LDS loads
+// (global_load_lds_dwordx4: no VGPR staging, no ds_write), issued right after the barrier so
+// that the loads of K step i+1 fly while the MFMAs of step i run; fragment reads of the next
+// 16-wide K slice are issued before the MFMAs of the current one.  A register-staged kernel
+// with zero fill covers K that is not a multiple of 64.
 //
 // Ragged groups: a group of `cnt` rows is cut into ceil(cnt/BM) M-tiles of equal height
 // (rounded up to 32), each wave owns every WARPS_M-th 32-row fragment, and fragments past
@@ -19,6 +22,8 @@
 // Launch: 1-D grid; hardware block b runs logical tile (b % 8) * chunk + b / 8 so that the
 // blocks one XCD receives (every 8th) are consecutive logical tiles - the M-tiles sharing a
 // weight tile hit the same L2.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -28,31 +33,25 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;           // K elements per stage (128 bytes per row)
 constexpr int ROW_BYTES = BK * 2;
 
-__device__ __forceinline__ int swz(int row, int kc) { return row * ROW_BYTES + ((kc ^ (row & 7)) << 4); }
+// 16-byte chunk kc of a 128-byte tile row lands at chunk kc ^ ((row >> 1) & 7): the LDS has 64 banks
+// (256 bytes per cycle), so the 16 rows that one b128 read phase touches (two rows per 256-byte
+// line) must spread over all 16 chunk positions.
+__device__ __forceinline__ int swz(int row, int kc) { return row * ROW_BYTES + ((kc ^ ((row >> 1) & 7)) << 4); }
 
-template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_kernel(const GemmArgs args) {
-  constexpr int NTHR = 64 * WARPS_M * WARPS_N;
-  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
-  constexpr int FM = BM / (32 * WARPS_M);
-  constexpr int FN = BN / (32 * WARPS_N);
-  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;  // column fragments per half
-  constexpr int CA = BM * 8 / NTHR;  // 16-byte chunks per thread, A tile
-  constexpr int CB = BN * 8 / NTHR;
-  constexpr int STAGE = (BM + BN) * ROW_BYTES;
-  static_assert(BM % (32 * WARPS_M) == 0 && BN % (32 * WARPS_N) == 0, "tile/wave mismatch");
-  static_assert((BM * 8) % NTHR == 0 && (BN * 8) % NTHR == 0, "chunk mismatch");
-  static_assert(MODE != GEMM_SWIGLU || FN % 2 == 0, "SwiGLU needs gate and up fragments");
 
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave % WARPS_M, wn = wave / WARPS_M;
+// ---------------------------------------------------------------------------------------------
+// Tile decode shared by both kernels.
+struct TileInfo {
+  int grp, row0, tile_row0, rows_valid, n0, ks;
+};
 
-  // ---------------- logical tile of this block
+template <int BM, int BN_OUT>
+__device__ __forceinline__ bool decode_tile(const GemmArgs &args, TileInfo &t) {
   const int n_tiles_n = (args.N + BN_OUT - 1) / BN_OUT;
   const int per_m = n_tiles_n * args.splitk;
   int total = 0;
@@ -68,7 +67,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_kernel(co
   const int chunk = (total + 7) >> 3;
   const int slot_in_xcd = (int)blockIdx.x >> 3;
   int l = ((int)blockIdx.x & 7) * chunk + slot_in_xcd;
-  if (slot_in_xcd >= chunk || l >= total) return;
+  if (slot_in_xcd >= chunk || l >= total) return false;
 
   int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
   if (args.offsets) {
@@ -83,55 +82,114 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_kernel(co
   const int mt = (cnt + BM - 1) / BM;
   const int m_idx = l % mt;
   const int rest = l / mt;
-  const int ks = rest % args.splitk;
+  t.ks = rest % args.splitk;
   const int n_idx = rest / args.splitk;
   int rpt = (((cnt + mt - 1) / mt) + 31) & ~31;   // balanced tile height
   if (rpt > BM) rpt = BM;
-  const int tile_row0 = m_idx * rpt;
-  const int rows_valid = min(rpt, cnt - tile_row0);
-  if (rows_valid <= 0) return;
-  const int n0 = n_idx * BN_OUT;
+  t.grp = grp;
+  t.row0 = row0;
+  t.tile_row0 = m_idx * rpt;
+  t.rows_valid = min(rpt, cnt - t.tile_row0);
+  t.n0 = n_idx * BN_OUT;
+  return t.rows_valid > 0;
+}
 
-  const char *wptr = args.wbase + (long long)args.slot[grp] * args.wstride;
+// Epilogue.  C fragment layout of the 32x32 MFMA: lane holds column (lane % 32) and rows
+// 8*(r/4) + 4*(lane/32) + r%4 for its 16 registers r.
+template <int MODE, int FM, int FN, int WARPS_M, int WARPS_N>
+__device__ __forceinline__ void store_tile(const GemmArgs &args, const TileInfo &t, int wm, int wn, int lane,
+                                           int fm_valid, floatx16 (&acc)[FM][FN]) {
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  const int lrow = lane & 31, lk = lane >> 5;
+  const long long out_row_base = (long long)t.row0 + t.tile_row0;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    if (i >= fm_valid) continue;
+    const int frow = (i * WARPS_M + wm) * 32;
+#pragma unroll
+    for (int j = 0; j < FNH; ++j) {
+      const int col = t.n0 + (j * WARPS_N + wn) * 32 + lrow;
+      if (col >= args.N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = frow + 8 * (r >> 2) + 4 * lk + (r & 3);
+        if (row >= t.rows_valid) continue;
+        const long long o = (out_row_base + row) * args.ldo + col;
+        if (MODE == GEMM_SWIGLU) {
+          float h = silu(acc[i][j][r]) * acc[i][j + FNH][r];
+          reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(h);
+        } else if (MODE == GEMM_PLAIN_F32) {
+          reinterpret_cast<float *>(args.out)[(long long)t.ks * args.out_split_stride + o] = acc[i][j][r];
+        } else {
+          reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(acc[i][j][r]);
+        }
+      }
+    }
+  }
+}
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef __attribute__((address_space(1))) const void *glb_ptr_t;
+
+// ---------------------------------------------------------------------------------------------
+// Main kernel: direct global->LDS loads.  Needs K % 64 == 0.
+template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_dma_kernel(const GemmArgs args) {
+  constexpr int NW = WARPS_M * WARPS_N;
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr int FM = BM / (32 * WARPS_M);
+  constexpr int FN = BN / (32 * WARPS_N);
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int STAGE = (BM + BN) * ROW_BYTES;
+  constexpr int GROUPS = (BM + BN) / 8;   // 8 tile rows = 1 KB = one wave-wide 16-byte load
+  constexpr int GPW = GROUPS / NW;        // loads per wave per stage
+  static_assert(BM % (32 * WARPS_M) == 0 && BN % (32 * WARPS_N) == 0, "tile/wave mismatch");
+  static_assert(GROUPS % NW == 0, "load split mismatch");
+  static_assert(MODE != GEMM_SWIGLU || FN % 2 == 0, "SwiGLU needs gate and up fragments");
+  static_assert(FM <= 4, "fragment-count dispatch covers up to 4 row fragments per wave");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: stays in scalar registers
+  const int wm = wave % WARPS_M, wn = wave / WARPS_M;
+
+  TileInfo t;
+  if (!decode_tile<BM, BN_OUT>(args, t)) return;
+
+  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride;
   const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
   const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
+  const int kt_total = args.K / BK;
+  const int kt_begin = (int)((long long)kt_total * t.ks / args.splitk);
+  const int kt_end = (int)((long long)kt_total * (t.ks + 1) / args.splitk);
 
-  // K range of this slice (in BK steps)
-  const int kt_total = (args.K + BK - 1) / BK;
-  const int kt_begin = (int)((long long)kt_total * ks / args.splitk);
-  const int kt_end = (int)((long long)kt_total * (ks + 1) / args.splitk);
-
-  // ---------------- per-thread global sources and LDS destinations
-  const uint16_t *a_src[CA];
-  int a_dst[CA];
+  // This lane's source of each of the wave's loads.  Load g fills tile rows 8g..8g+7 (A rows first,
+  // then B rows); lane l lands at row 8g + l/8, chunk position l%8, so it fetches the chunk that the
+  // swizzle maps there.
+  const uint16_t *src[GPW];
 #pragma unroll
-  for (int i = 0; i < CA; ++i) {
-    int c = tid + i * NTHR, r = c >> 3, kc = c & 7;
-    int rr = r < rows_valid ? r : 0;
-    int p = row0 + tile_row0 + rr;
-    long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
-    a_src[i] = args.A + srow * args.lda + kc * 8;
-    a_dst[i] = swz(r, kc);
+  for (int i = 0; i < GPW; ++i) {
+    const int g = i * NW + wave;
+    const int row = g * 8 + (lane >> 3);
+    const int kc = (lane & 7) ^ ((row >> 1) & 7);
+    if (g * 8 < BM) {
+      int rr = row < t.rows_valid ? row : 0;
+      int p = t.row0 + t.tile_row0 + rr;
+      long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
+      src[i] = args.A + srow * args.lda + kc * 8;
+    } else {
+      int r = row - BM;
+      const uint16_t *base = B0;
+      if (MODE == GEMM_SWIGLU && r >= BN / 2) { base = B1; r -= BN / 2; }
+      int n = t.n0 + r;
+      if (n >= args.N) n = args.N - 1;
+      src[i] = base + (long long)n * args.ldb + kc * 8;
+    }
   }
-  const uint16_t *b_src[CB];
-  int b_dst[CB];
-#pragma unroll
-  for (int i = 0; i < CB; ++i) {
-    int c = tid + i * NTHR, r = c >> 3, kc = c & 7;
-    const uint16_t *base = B0;
-    int rr = r;
-    if (MODE == GEMM_SWIGLU && r >= BN / 2) { base = B1; rr = r - BN / 2; }
-    int n = n0 + rr;
-    if (n >= args.N) n = args.N - 1;
-    b_src[i] = base + (long long)n * args.ldb + kc * 8;
-    b_dst[i] = BM * ROW_BYTES + swz(r, kc);
-  }
-  const int kc_lane = tid & 7;  // this thread's 16-byte column inside the 64-wide K step
 
-  // fragments of this wave that hold valid rows (interleaved ownership keeps them balanced)
   int fm_valid = 0;
 #pragma unroll
-  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < rows_valid) ? 1 : 0;
+  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < t.rows_valid) ? 1 : 0;
 
   floatx16 acc[FM][FN];
 #pragma unroll
@@ -141,26 +199,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_kernel(co
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  uint4 ra[CA], rb[CB];
-  auto load_global = [&](int kt) {
-    const int k0 = kt * BK;
-    const bool k_ok = k0 + kc_lane * 8 < args.K;
-#pragma unroll
-    for (int i = 0; i < CA; ++i)
-      ra[i] = k_ok ? *reinterpret_cast<const uint4 *>(a_src[i] + k0) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < CB; ++i)
-      rb[i] = k_ok ? *reinterpret_cast<const uint4 *>(b_src[i] + k0) : make_uint4(0, 0, 0, 0);
-  };
-  auto store_lds = [&](int stage) {
-    unsigned char *s = smem + stage * STAGE;
-#pragma unroll
-    for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4 *>(s + a_dst[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < CB; ++i) *reinterpret_cast<uint4 *>(s + b_dst[i]) = rb[i];
-  };
-
-  // LDS read offsets of this lane's fragment rows
   int a_off[FM], b_off[FN];
   const int lrow = lane & 31, lk = lane >> 5;
 #pragma unroll
@@ -173,65 +211,178 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_kernel(co
       b_off[j] = (j * WARPS_N + wn) * 32 + lrow;
   }
 
-  if (kt_begin < kt_end) {
-    load_global(kt_begin);
-    store_lds(0);
-  }
-  __syncthreads();
+#define MOE_ISSUE(kt_, stage_)                                                                       \
+  do {                                                                                               \
+    _Pragma("unroll") for (int i_ = 0; i_ < GPW; ++i_)                                               \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src[i_] + (long long)(kt_) * BK),                 \
+                                       (lds_ptr_t)(smem + (stage_) * STAGE + (i_ * NW + wave) * 1024), \
+                                       16, 0, 0);                                                    \
+  } while (0)
+#define MOE_READ_FRAGS(FMV, buf_, kk_)                                                               \
+  do {                                                                                               \
+    const int kc_ = (kk_) * 2 + lk;                                                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < FMV; ++i_)                                               \
+      af_[buf_][i_] = *reinterpret_cast<const bf16x8 *>(sa_ + swz(a_off[i_], kc_));                  \
+    _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                                \
+      bf_[buf_][j_] = *reinterpret_cast<const bf16x8 *>(sb_ + swz(b_off[j_], kc_));                  \
+  } while (0)
+#define MOE_MMA_STAGE(FMV, stage_)                                                                   \
+  do {                                                                                               \
+    const unsigned char *sa_ = smem + (stage_) * STAGE;                                              \
+    const unsigned char *sb_ = sa_ + BM * ROW_BYTES;                                                 \
+    bf16x8 af_[2][FMV > 0 ? FMV : 1], bf_[2][FN];                                                    \
+    if (FMV > 0) {                                                                                   \
+      MOE_READ_FRAGS(FMV, 0, 0);                                                                     \
+      _Pragma("unroll") for (int kk_ = 0; kk_ < BK / 16; ++kk_) {                                    \
+        if (kk_ + 1 < BK / 16) MOE_READ_FRAGS(FMV, (kk_ + 1) & 1, kk_ + 1);                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < FMV; ++i_)                                           \
+          _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                          \
+            acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[kk_ & 1][i_], bf_[kk_ & 1][j_], \
+                                                                  acc[i_][j_], 0, 0, 0);             \
+      }                                                                                              \
+    }                                                                                                \
+  } while (0)
+#define MOE_K_LOOP(FMV)                                                                              \
+  do {                                                                                               \
+    for (int kt = kt_begin; kt < kt_end; ++kt) {                                                     \
+      const int stage_ = (kt - kt_begin) & 1;                                                        \
+      __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's loads of step kt have landed */   \
+      __syncthreads();                    /* ... and everybody's; stage^1 is free again */          \
+      if (kt + 1 < kt_end) MOE_ISSUE(kt + 1, stage_ ^ 1);                                            \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      MOE_MMA_STAGE(FMV, stage_);                                                                    \
+    }                                                                                                \
+  } while (0)
 
+  if (kt_begin < kt_end) MOE_ISSUE(kt_begin, 0);
+  switch (fm_valid) {
+    case 0: MOE_K_LOOP(0); break;
+    case 1: MOE_K_LOOP(1); break;
+    case 2: if constexpr (FM >= 2) MOE_K_LOOP(2); break;
+    case 3: if constexpr (FM >= 3) MOE_K_LOOP(3); break;
+    default: if constexpr (FM >= 4) MOE_K_LOOP(4); break;
+  }
+#undef MOE_K_LOOP
+#undef MOE_MMA_STAGE
+#undef MOE_READ_FRAGS
+#undef MOE_ISSUE
+
+  store_tile<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Register-staged kernel with zero fill of the K tail (K % 8 == 0 is enough).
+template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_ktail_kernel(const GemmArgs args) {
+  constexpr int NTHR = 64 * WARPS_M * WARPS_N;
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr int FM = BM / (32 * WARPS_M);
+  constexpr int FN = BN / (32 * WARPS_N);
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int CA = BM * 8 / NTHR;  // 16-byte chunks per thread, A tile
+  constexpr int CB = BN * 8 / NTHR;
+  constexpr int STAGE = (BM + BN) * ROW_BYTES;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WARPS_M, wn = wave / WARPS_M;
+
+  TileInfo t;
+  if (!decode_tile<BM, BN_OUT>(args, t)) return;
+
+  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride;
+  const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
+  const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
+  const int kt_total = (args.K + BK - 1) / BK;
+  const int kt_begin = (int)((long long)kt_total * t.ks / args.splitk);
+  const int kt_end = (int)((long long)kt_total * (t.ks + 1) / args.splitk);
+
+  const uint16_t *a_src[CA];
+  int a_dst[CA];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) {
+    int c = tid + i * NTHR, r = c >> 3, kc = c & 7;
+    int rr = r < t.rows_valid ? r : 0;
+    int p = t.row0 + t.tile_row0 + rr;
+    long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
+    a_src[i] = args.A + srow * args.lda + kc * 8;
+    a_dst[i] = swz(r, kc);
+  }
+  const uint16_t *b_src[CB];
+  int b_dst[CB];
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    int c = tid + i * NTHR, r = c >> 3, kc = c & 7;
+    const uint16_t *base = B0;
+    int rr = r;
+    if (MODE == GEMM_SWIGLU && r >= BN / 2) { base = B1; rr = r - BN / 2; }
+    int n = t.n0 + rr;
+    if (n >= args.N) n = args.N - 1;
+    b_src[i] = base + (long long)n * args.ldb + kc * 8;
+    b_dst[i] = BM * ROW_BYTES + swz(r, kc);
+  }
+  const int kc_lane = tid & 7;
+
+  int fm_valid = 0;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < t.rows_valid) ? 1 : 0;
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  int a_off[FM], b_off[FN];
+  const int lrow = lane & 31, lk = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a_off[i] = (i * WARPS_M + wm) * 32 + lrow;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    if (MODE == GEMM_SWIGLU)
+      b_off[j] = (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow;
+    else
+      b_off[j] = (j * WARPS_N + wn) * 32 + lrow;
+  }
+
+  u32x4 ra[CA], rb[CB];
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int stage = (kt - kt_begin) & 1;
-    if (kt + 1 < kt_end) load_global(kt + 1);
-    const unsigned char *sa = smem + stage * STAGE;
-    const unsigned char *sb = sa + BM * ROW_BYTES;
+    const int k0 = kt * BK;
+    const bool k_ok = k0 + kc_lane * 8 < args.K;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < CA; ++i) ra[i] = k_ok ? *reinterpret_cast<const u32x4 *>(a_src[i] + k0) : zero;
+#pragma unroll
+    for (int i = 0; i < CB; ++i) rb[i] = k_ok ? *reinterpret_cast<const u32x4 *>(b_src[i] + k0) : zero;
+    __syncthreads();  // previous step's fragments have been read
+#pragma unroll
+    for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4 *>(smem + a_dst[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4 *>(smem + b_dst[i]) = rb[i];
+    __syncthreads();
+    const unsigned char *sa = smem, *sb = smem + BM * ROW_BYTES;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[FM], bfr[FN];
       const int kc = kk * 2 + lk;
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-        if (i < fm_valid) af[i] = *reinterpret_cast<const bf16x8 *>(sa + swz(a_off[i], kc));
+      bf16x8 bfr[FN];
 #pragma unroll
       for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(sb + swz(b_off[j], kc));
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int i = 0; i < FM; ++i) {
         if (i < fm_valid) {
+          bf16x8 af = *reinterpret_cast<const bf16x8 *>(sa + swz(a_off[i], kc));
 #pragma unroll
           for (int j = 0; j < FN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-    }
-    if (kt + 1 < kt_end) store_lds(stage ^ 1);
-    __syncthreads();
-  }
-
-  // ---------------- epilogue.  C fragment layout of the 32x32 MFMA: lane holds column
-  // (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 for its 16 registers r.
-  const long long out_row_base = (long long)row0 + tile_row0;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-    if (i >= fm_valid) continue;
-    const int frow = (i * WARPS_M + wm) * 32;
-#pragma unroll
-    for (int j = 0; j < FNH; ++j) {
-      const int col = n0 + (j * WARPS_N + wn) * 32 + lrow;
-      if (col >= args.N) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = frow + 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (row >= rows_valid) continue;
-        const long long o = (out_row_base + row) * args.ldo + col;
-        if (MODE == GEMM_SWIGLU) {
-          float h = silu(acc[i][j][r]) * acc[i][j + FNH][r];
-          reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(h);
-        } else if (MODE == GEMM_PLAIN_F32) {
-          reinterpret_cast<float *>(args.out)[(long long)ks * args.out_split_stride + o] = acc[i][j][r];
-        } else {
-          reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(acc[i][j][r]);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr[j], acc[i][j], 0, 0, 0);
         }
       }
     }
   }
+  (void)STAGE;
+  store_tile<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc);
 }
 
 template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
@@ -239,7 +390,7 @@ hipError_t launch_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, 
   constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
   constexpr int NTHR = 64 * WARPS_M * WARPS_N;
   constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES;
-  auto kern = grouped_gemm_kernel<BM, BN, WARPS_M, WARPS_N, MODE>;
+  auto kern = grouped_gemm_dma_kernel<BM, BN, WARPS_M, WARPS_N, MODE>;
   static bool attr_set = false;  // per instantiation; idempotent if two threads race
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -257,6 +408,22 @@ hipError_t launch_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, 
   return hipGetLastError();
 }
 
+template <int MODE>
+hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  constexpr int BM = 128, BN = 128;
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr size_t smem = (size_t)(BM + BN) * ROW_BYTES;
+  const long long n_tiles_n = (args.N + BN_OUT - 1) / BN_OUT;
+  const long long m_tiles_ub = (long long)max_rows / BM + n_groups_in_mask;
+  long long ub = m_tiles_ub * n_tiles_n * args.splitk;
+  if (ub <= 0) return hipSuccess;
+  ub = (ub + 7) / 8 * 8;
+  if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((grouped_gemm_ktail_kernel<BM, BN, 2, 2, MODE>), dim3((unsigned)ub), dim3(256), smem, stream,
+                     args);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 // Tile shapes.  Variant 0 picks by shape; 1.. force one (tuning hook).
@@ -268,14 +435,14 @@ void set_gemm_variant(int mode, int variant) {
 
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  if (args.K % BK != 0) return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
   int v = g_variant[MODE];
-  if (v == 0) v = 1;
+  if (v == 0) v = 3;
   switch (v) {
     case 2: return launch_cfg<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 3: return launch_cfg<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 4: return launch_cfg<128, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 5: return launch_cfg<256, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 6: return launch_cfg<128, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 5: return launch_cfg<256, 128, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
   }
 }
