@@ -44,10 +44,18 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // K slices of the down projection.  Few, long tiles (Mixtral-like: K = 14336, ~320 tiles of
 // 256 x 256 on 256 CUs) leave most of the last round idle; slicing K makes the tiles finer.
 // The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
+int g_splitk_override = 0;  // tuning hook (moe_set_gemm_variant mode 3); 0 = heuristic
+
 int choose_splitk(const moe_config &cfg, int T) {
-  (void)cfg;
-  (void)T;
-  return 1;
+  if (g_splitk_override > 0) return g_splitk_override;
+  const long long rows = (long long)T * cfg.k;
+  if (rows < 1024) return 1;  // decode-sized calls run the mat-vec path
+  const long long tiles = (rows / 256 + (cfg.E + 1) / 2) * ((cfg.d + 255) / 256);
+  long long s = (3 * 256 + tiles - 1) / tiles;  // aim at >= 3 rounds of tiles over 256 CUs
+  const long long max_by_k = cfg.I / 1024;      // keep every slice >= 16 K steps
+  if (s > max_by_k) s = max_by_k;
+  if (s > 4) s = 4;
+  return s < 1 ? 1 : (int)s;
 }
 
 struct WsLayout {
@@ -714,7 +722,12 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
 }
 
 int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 2 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 3 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode == 3) {
+    if (variant > 8) return fail(MOE_E_ARG, "at most 8 K slices");
+    g_splitk_override = variant;
+    return MOE_OK;
+  }
   set_gemm_variant(mode, variant);
   return MOE_OK;
 }

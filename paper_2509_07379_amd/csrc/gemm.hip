@@ -242,15 +242,29 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_dma_kerne
       }                                                                                              \
     }                                                                                                \
   } while (0)
+// One K step.  The loads of the next step go out first (the last step re-loads itself: harmless and
+// branch-free, so the whole body is one scheduling region).  The group barriers then pin the
+// software pipeline: fragments of 16-wide slice kk+1 are requested before the MFMAs of slice kk.
 #define MOE_K_LOOP(FMV)                                                                              \
   do {                                                                                               \
     for (int kt = kt_begin; kt < kt_end; ++kt) {                                                     \
       const int stage_ = (kt - kt_begin) & 1;                                                        \
+      const int kn_ = kt + 1 < kt_end ? kt + 1 : kt;                                                 \
       __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's loads of step kt have landed */   \
       __syncthreads();                    /* ... and everybody's; stage^1 is free again */          \
-      if (kt + 1 < kt_end) MOE_ISSUE(kt + 1, stage_ ^ 1);                                            \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
+      MOE_ISSUE(kn_, stage_ ^ 1);                                                                    \
       MOE_MMA_STAGE(FMV, stage_);                                                                    \
+      if (FMV > 0) {                                                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x020, GPW, 0);          /* global->LDS loads */        \
+        __builtin_amdgcn_sched_group_barrier(0x100, FMV + FN, 0);     /* fragments of slice 0 */     \
+        __builtin_amdgcn_sched_group_barrier(0x100, FMV + FN, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, FMV * FN, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, FMV + FN, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, FMV * FN, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, FMV + FN, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, FMV * FN, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, FMV * FN, 0);                                    \
+      }                                                                                              \
     }                                                                                                \
   } while (0)
 
@@ -437,12 +451,19 @@ template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.K % BK != 0) return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
   int v = g_variant[MODE];
-  if (v == 0) v = 3;
+  if (v == 0) {
+    // 256 x 256 tiles (8 waves, each 128 x 64) unless the groups are small on average, where the
+    // finer 128 x 128 tiles waste less of the matrix cores on empty rows
+    const long long avg_rows = n_groups_in_mask > 0 ? (long long)max_rows / n_groups_in_mask : max_rows;
+    v = avg_rows > 96 ? 6 : 1;
+  }
   switch (v) {
     case 2: return launch_cfg<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 3: return launch_cfg<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 4: return launch_cfg<128, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 5: return launch_cfg<256, 128, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 6: return launch_cfg<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 7: return launch_cfg<128, 256, 1, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
     default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
   }
 }
