@@ -1,0 +1,150 @@
+"""Parity at the full sizes of the workload list, in the launch configuration bench.py times.
+
+Routing tables are compared in full (integers, cheap on the CPU); layer outputs on sampled tokens
+that the oracle computes one by one.  Needs an MI355X.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_2509_07379_amd import synth as S
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+from test_gpu_parity import check_out, gpu  # noqa: E402,F401  (fixture + tolerance)
+
+
+def sample_tokens(T, n, seed=0):
+    rng = np.random.default_rng(seed)
+    return np.sort(rng.choice(T, size=min(n, T), replace=False)).astype(np.int32)
+
+
+def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=False):
+    H, B = gpu["harness"], gpu["binding"]
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, slots, w.I_shared)
+    pool = H.HostPool(w, 0)
+    initial = list(range(w.E)) if slots == w.E else None
+    lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=initial is None)
+    buf = H.Buffers(ctx, w.T)
+    x_np = S.activations(w)
+    x = H.np_to_dev(x_np)
+    bias_np = S.zipf_route_bias(w, 0) if w.zipf_s > 0 else None
+    bias = None if bias_np is None else torch.from_numpy(bias_np).cuda()
+    torch.cuda.synchronize()
+    if prefetch is not None:
+        ctx.expert_cache_prefetch(0, prefetch, gpu["copy"])
+    if with_attention:  # stand-in non-MoE block the first fetches hide behind (Section V-B)
+        wa = H.np_to_dev(S.normal_bf16((w.d, w.d), w.seed, S.stream_id(S.KIND_ATTN), 0.02))
+        tmp = torch.empty((w.T, w.d), dtype=torch.int16, device="cuda")
+        B.moe_dense_gemm_bf16(x, wa, tmp, w.T, w.d, w.d, gpu["compute"])
+    ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, 0)
+    gpu["compute"].synchronize()
+    out = H.dev_to_np_u16(buf.y)
+    routing = buf.routing(ctx, gpu["compute"])
+    stats, state = ctx.moe_get_stats(0), ctx.moe_cache_state(0)
+    ctx.close()
+    sel = sample_tokens(w.T, n_sample)
+    ref = oracle.moe_layer(x_np, lay.router_np, [pool.ptr(e) for e in range(w.E)], w.k, bias=bias_np, sel=sel,
+                           shared_blob=lay.shared_np, I=w.I, I_shared=w.I_shared)
+    for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
+        np.testing.assert_array_equal(routing[key], ref[key], err_msg=key)
+    np.testing.assert_allclose(routing["w"], ref["w"], rtol=2e-5, atol=1e-7)
+    check_out(out[sel], ref["out_f64"], w.name)
+    return dict(out=out, routing=routing, stats=stats, state=state, ref=ref)
+
+
+def test_c2_mixtral_prefill_resident(gpu, oracle):
+    """The configuration bench.py times: all 8 experts resident, one grouped launch."""
+    w = S.WORKLOADS["c2_mixtral_prefill"]
+    r = prefill_case(gpu, oracle, w, w.E, 24)
+    assert r["stats"]["misses"] == 0 and r["stats"]["bytes_h2d"] == 0
+    assert r["routing"]["counts"].sum() == w.T * w.k
+
+
+def test_c2_mixtral_prefill_two_slots_matches_resident(gpu, oracle):
+    """GPU expert cache of 2 (Section V-A): experts stream from pinned memory, same bits out."""
+    from oracle.cache_sim import CacheSim
+    w = S.WORKLOADS["c2_mixtral_prefill"]
+    res = prefill_case(gpu, oracle, w, w.E, 8)
+    off = prefill_case(gpu, oracle, w, w.S, 8, prefetch=list(range(w.S)), with_attention=True)
+    np.testing.assert_array_equal(off["out"], res["out"])
+    sim = CacheSim(w.E, w.S, w.blob_bytes)
+    sim.prefetch(range(w.S))
+    sim.serve(np.nonzero(res["routing"]["counts"])[0])
+    assert off["stats"] == {**sim.counters(), "layer_calls": 1}
+    assert off["state"] == sim.slot_expert
+    assert off["stats"]["bytes_h2d"] == w.E * w.blob_bytes  # every expert fetched exactly once
+
+
+def test_c4_deepseek_prefill_layer(gpu, oracle):
+    """64 routed experts top-6 with Zipf-skewed popularity + shared experts, 16 slots."""
+    from oracle.cache_sim import CacheSim
+    w = S.WORKLOADS["c4_deepseek_prefill"]
+    r = prefill_case(gpu, oracle, w, w.S, 32, prefetch=list(range(w.S)))
+    counts = r["routing"]["counts"]
+    assert counts.max() > 8 * max(1, counts[counts > 0].min())  # the load really is imbalanced
+    sim = CacheSim(w.E, w.S, w.blob_bytes)
+    sim.prefetch(range(w.S))
+    sim.serve(np.nonzero(counts)[0])
+    assert r["stats"] == {**sim.counters(), "layer_calls": 1}
+    assert r["state"] == sim.slot_expert
+
+
+def decode_case(gpu, oracle, w, n_layers, steps):
+    """Decode steps with trace-driven routing, the linear predictor one layer ahead, prefetch and
+    re-fetch; every layer call is checked against the oracle, the counters against the simulator."""
+    from oracle.cache_sim import CacheSim
+    H, B = gpu["harness"], gpu["binding"]
+    w = replace(w, L=n_layers, steps=steps)
+    pred = torch.cuda.Stream()
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, n_layers, w.S, w.I_shared)
+    pools = [H.HostPool(w, l) for l in range(n_layers)]
+    init = list(range(w.S))
+    lays = [H.DeviceLayer(ctx, w, l, pools[l], init) for l in range(n_layers)]
+    wps_np = [S.predictor_weight(w, l) for l in range(n_layers)]
+    wps = [H.np_to_dev(a) for a in wps_np]
+    sims = [CacheSim(w.E, w.S, w.blob_bytes, init) for _ in range(n_layers)]
+    trace = S.markov_trace(w)
+    buf = H.Buffers(ctx, w.T)
+    top = torch.zeros(w.top_m, dtype=torch.int32).pin_memory()
+    for s in range(steps):
+        for l in range(n_layers):
+            x_np = S.activations(w, l, s)
+            x = H.np_to_dev(x_np)
+            bias_np = S.trace_route_bias(trace[s, l], w.E)
+            bias = torch.from_numpy(bias_np).cuda()
+            if l + 1 < n_layers:
+                ctx.predictor_score(x, w.T, wps[l + 1], w.top_m, top, pred)
+            ctx.moe_decode_layer(l, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, w.E)
+            gpu["compute"].synchronize()
+            out = H.dev_to_np_u16(buf.y)
+            routing = buf.routing(ctx, gpu["compute"])
+            ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k,
+                                   bias=bias_np, shared_blob=lays[l].shared_np, I=w.I, I_shared=w.I_shared)
+            for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
+                np.testing.assert_array_equal(routing[key], ref[key], err_msg=f"{key} step {s} layer {l}")
+            assert np.array_equal(np.sort(ref["ids"], 1), np.sort(trace[s, l], 1))  # the trace drives routing
+            check_out(out, ref["out_f64"], f"{w.name} step {s} layer {l}")
+            sims[l].serve(np.nonzero(ref["counts"])[0])
+            if l + 1 < n_layers:
+                pred.synchronize()
+                _, ref_top = oracle.predictor_score(x_np, wps_np[l + 1], w.top_m)
+                np.testing.assert_array_equal(top.numpy(), ref_top)
+                ctx.expert_cache_prefetch(l + 1, top.tolist(), gpu["copy"])
+                sims[l + 1].prefetch(ref_top)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        st = ctx.moe_get_stats(l)
+        assert st == {**sims[l].counters(), "layer_calls": steps}, f"layer {l}"
+        assert ctx.moe_cache_state(l) == sims[l].slot_expert
+    ctx.close()
+
+
+def test_c3_mixtral_decode_steps(gpu, oracle):
+    decode_case(gpu, oracle, S.WORKLOADS["c3_mixtral_decode"], n_layers=2, steps=3)
+
+
+def test_c5_qwen_decode_steps(gpu, oracle):
+    decode_case(gpu, oracle, S.WORKLOADS["c5_qwen_decode"], n_layers=3, steps=3)
