@@ -34,9 +34,8 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def prefill_resident(args, torch, B, H, S, w):
+def prefill_resident(args, torch, B, H, S, w, compute, copy):
     """Kernel regime of the prefill layer: S = E slots, every expert resident."""
-    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared)
     t0 = time.time()
     pool = H.HostPool(w, 0)
@@ -75,11 +74,10 @@ def prefill_resident(args, torch, B, H, S, w):
                 routing=routing, compute=compute, copy=copy)
 
 
-def prefill_offloaded(args, torch, B, H, S, w, pool, x, steps=3):
+def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6):
     """Offloaded regime: S = w.S slots, experts fetched from pinned memory on the copy stream; a
     stand-in attention block (4 bf16 GEMMs T x d x d) runs on the compute stream while the first
     experts are prefetched.  Returns T_copy-alone, T_compute-alone and T_pipelined per layer."""
-    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared)
     lay = H.DeviceLayer(ctx, w, 0, pool, None)
     buf = H.Buffers(ctx, w.T)
@@ -126,13 +124,12 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, steps=3):
                 timed=timed)
 
 
-def decode_regime(args, torch, B, H, S, w, n_layers, steps):
+def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred):
     """Decode: per-layer latency with the predictor-guided cache (S slots per layer) and with all
     experts resident (hit path only); expert-GEMV HBM GB/s from HIP events."""
     import numpy as np
     from dataclasses import replace
     wl = replace(w, L=n_layers, steps=steps)
-    compute, copy, pred = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     t0 = time.time()
     pools = [H.HostPool(wl, l) for l in range(n_layers)]
     log(f"[bench] decode host pools {n_layers * wl.E * wl.blob_bytes / 1e9:.1f} GB in {time.time() - t0:.1f}s")
@@ -228,7 +225,10 @@ def main():
     torch.cuda.set_device(0)
     w = S.WORKLOADS[args.workload]
 
-    res = prefill_resident(args, torch, B, H, S, w)
+    # one compute, one copy and one prediction stream for the whole run: HIP multiplexes streams
+    # onto 4 hardware queues, and two streams that land on the same queue serialise
+    compute, copy, pred = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    res = prefill_resident(args, torch, B, H, S, w, compute, copy)
     ms = res["ms"]
     tok_s = w.T / (ms * 1e-3)
     k = res["kern_ms"]
@@ -257,7 +257,7 @@ def main():
     }
 
     if not args.no_offloaded and w.S and w.S < w.E:
-        off = prefill_offloaded(args, torch, B, H, S, w, res["pool"], res["x"])
+        off = prefill_offloaded(args, torch, B, H, S, w, res["pool"], res["x"], compute, copy)
         t_attn = off["timed"](off["attention"], 5)
         t_k = ms + t_attn
         t_c, t_p = off["t_copy_ms"], off["t_pipelined_ms"]
@@ -272,7 +272,7 @@ def main():
 
     if not args.no_decode:
         wd = S.WORKLOADS["c3_mixtral_decode"]
-        dec = decode_regime(args, torch, B, H, S, wd, args.decode_layers, args.decode_steps)
+        dec = decode_regime(args, torch, B, H, S, wd, args.decode_layers, args.decode_steps, compute, copy, pred)
         bytes_layer = wd.k * wd.blob_bytes  # batch 1: k distinct experts streamed once
         r = dec["resident"]
         gemv_ms = r["gemv1_ms"] + r["gemv2_ms"]

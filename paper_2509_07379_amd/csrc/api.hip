@@ -418,18 +418,39 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
           L.stats.prefetch_useful++;
           L.prefetched[s] = 0;
         }
-        if (L.copy_pending[s]) {
-          HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
-          L.copy_pending[s] = 0;
-        }
       }
     L.stats.misses += (int32_t)misses.size();
-    if (n_hits) {
+    auto wait_copied = [&](int s) -> int {
+      if (L.copy_pending[s]) {
+        HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
+        L.copy_pending[s] = 0;
+      }
+      return MOE_OK;
+    };
+    if (n_hits && misses.empty()) {
+      for (int e = 0; e < E; ++e)
+        if ((hit_mask >> e) & 1ull) {
+          rc = wait_copied(L.expert_slot[e]);
+          if (rc) return rc;
+        }
       rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(L.group_done, cs));
       for (int e = 0; e < E; ++e)
         if ((hit_mask >> e) & 1ull) L.use_kind[L.expert_slot[e]] = 2;
+    } else if (n_hits) {
+      // Misses will reuse these slots: run the hits one by one, each with its own "last reader"
+      // event, so that the first fetch can start as soon as the first hit has been computed.
+      for (int e = 0; e < E; ++e) {
+        if (!((hit_mask >> e) & 1ull)) continue;
+        const int s = L.expert_slot[e];
+        rc = wait_copied(s);  // only this expert's fetch: the next one may still be in flight
+        if (rc) return rc;
+        rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(L.used[s], cs));
+        L.use_kind[s] = 1;
+      }
     }
     // Misses stream through the slots in ascending id: fetch on the copy stream (behind the
     // victim's last reader), compute as soon as the copy has landed.
