@@ -290,15 +290,16 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
 
 // Both expert matmuls of the groups in `mask`, on the compute stream.
 int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
-                int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream) {
+                int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream,
+                const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr) {
   a1.group_mask = a2.group_mask = mask;
   if (decode) {
     {
       Timer t(ctx, stream, MOE_K_GEMV1);
-      HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, max_rows_per_group, n_groups, stream));
+      HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, max_rows_per_group, n_groups, stream, s1));
     }
     Timer t(ctx, stream, MOE_K_GEMV2);
-    HIP_TRY(launch_grouped_gemv(GEMM_PLAIN_F32, a2, max_rows_per_group, n_groups, stream));
+    HIP_TRY(launch_grouped_gemv(GEMM_PLAIN_F32, a2, max_rows_per_group, n_groups, stream, s2));
   } else {
     {
       Timer t(ctx, stream, MOE_K_GEMM1);
@@ -335,6 +336,11 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 
   bool all_resident = true;
   for (int e = 0; e < E; ++e) all_resident &= L.expert_slot[e] >= 0;
+  // Enqueue everything without looking at the gate's result only when that result cannot change the
+  // launch: all experts resident and, for the mat-vec path, one token (every active expert then has
+  // exactly one row).  A decode batch takes the other path: the per-expert row counts pick a much
+  // leaner mat-vec variant, and the shared experts' launch covers the host's wait.
+  const bool enqueue_blind = all_resident && (!decode || T == 1);
 
   // ---- gate, Top-k, grouping
   {
@@ -356,17 +362,23 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   }
   HIP_TRY(hipEventRecord(ctx->routed, cs));
 
-  // ---- shared experts: independent of the routing, they also cover the host's wait below
+  // ---- shared experts: independent of the routing.  When the host has to wait for the gate they
+  // run first and cover that wait; in an all-resident decode call they ride in the routed launches.
+  GemmArgs s1{}, s2{};
+  const bool shared_in_routed_launch = c.I_shared && decode && enqueue_blind;
   if (c.I_shared) {
-    GemmArgs s1 = shared_args(ctx, L, ws, W, T, false, dev_x), s2 = shared_args(ctx, L, ws, W, T, true, dev_x);
-    rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, cs);
-    if (rc) return rc;
+    s1 = shared_args(ctx, L, ws, W, T, false, dev_x);
+    s2 = shared_args(ctx, L, ws, W, T, true, dev_x);
+    if (!shared_in_routed_launch) {
+      rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, cs);
+      if (rc) return rc;
+    }
   }
 
   GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
   L.stats.layer_calls++;
 
-  if (all_resident) {
+  if (enqueue_blind) {
     // Every expert is in a slot: nothing to decide on the host, one grouped launch.
     for (int s = 0; s < S; ++s)
       if (L.copy_pending[s]) {
@@ -374,7 +386,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         L.copy_pending[s] = 0;
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
-    rc = run_experts(ctx, decode, a1, a2, mask, E, n, T, cs);
+    rc = run_experts(ctx, decode, a1, a2, mask, E, n, T, cs, shared_in_routed_launch ? &s1 : nullptr,
+                     shared_in_routed_launch ? &s2 : nullptr);
     if (rc) return rc;
     HIP_TRY(hipEventRecord(L.group_done, cs));
     for (int s = 0; s < S; ++s) L.use_kind[s] = 2;

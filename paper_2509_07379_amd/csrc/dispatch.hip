@@ -1,6 +1,7 @@
 // Grouping of the tokens by assigned expert (Section V-B of the paper): a stable counting sort
-// of the T*k assignments a = t*k + j by expert id.  Three small kernels, no ranks taken from
-// atomics, so the permutation is the unique stable one:
+// of the T*k assignments a = t*k + j by expert id.  Three small kernels (one block doing all three
+// phases for decode-sized inputs), no ranks taken from atomics, so the permutation is the unique
+// stable one:
 //   1. per-block histogram (LDS integer atomics only count),
 //   2. one wave scans the block histograms per expert and the experts' totals,
 //   3. every block ranks its own assignments with wave ballots and scatters.
@@ -85,11 +86,80 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_scatter_kernel(
   }
 }
 
+
+// Decode-sized inputs (n <= kSmallDispatch assignments): the three phases in one block.
+constexpr int kSmallDispatch = 2048;
+
+__global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
+    const int32_t *__restrict__ ids, int n, int E, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
+    int32_t *__restrict__ host_counts) {
+  constexpr int kWaves = kDispatchChunk / 64;
+  __shared__ int hist[kMaxExperts];
+  __shared__ int base[kMaxExperts];       // next free sorted position of each expert
+  __shared__ int wave_cnt[kWaves][kMaxExperts];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < kMaxExperts) hist[tid] = 0;
+  __syncthreads();
+  for (int a = tid; a < n; a += kDispatchChunk) atomicAdd(&hist[ids[a]], 1);
+  __syncthreads();
+  if (wave == 0) {
+    int run = lane < E ? hist[lane] : 0;
+    int incl = run;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      int o = __shfl_up(incl, s);
+      if (lane >= s) incl += o;
+    }
+    if (lane < E) {
+      counts[lane] = run;
+      offsets[lane] = incl - run;
+      base[lane] = incl - run;
+      if (host_counts) host_counts[lane] = run;
+    }
+    if (lane == E - 1) offsets[E] = incl;
+  }
+  for (int c0 = 0; c0 < n; c0 += kDispatchChunk) {
+    for (int i = tid; i < kWaves * kMaxExperts; i += kDispatchChunk) (&wave_cnt[0][0])[i] = 0;
+    __syncthreads();  // also publishes base[] (first round) / its update (later rounds)
+    const int a = c0 + tid;
+    const bool valid = a < n;
+    const int e = valid ? ids[a] : 0;
+    unsigned long long peers = __ballot(valid);
+#pragma unroll
+    for (int bit = 0; bit < 6; ++bit) {
+      unsigned long long b = __ballot((e >> bit) & 1);
+      peers &= ((e >> bit) & 1) ? b : ~b;
+    }
+    const int rank_in_wave = __popcll(peers & ((1ull << lane) - 1ull));
+    if (valid && rank_in_wave == 0) wave_cnt[wave][e] = __popcll(peers);
+    __syncthreads();
+    if (valid) {
+      int p = base[e] + rank_in_wave;
+      for (int wv = 0; wv < wave; ++wv) p += wave_cnt[wv][e];
+      perm[p] = a;
+      inv_perm[a] = p;
+    }
+    __syncthreads();
+    if (tid < E) {
+      int add = 0;
+      for (int wv = 0; wv < kWaves; ++wv) add += wave_cnt[wv][tid];
+      base[tid] += add;
+    }
+    __syncthreads();  // base[] is final and wave_cnt[] has been read before the next round clears it
+  }
+}
+
 }  // namespace
 
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                            int32_t *host_counts, hipStream_t stream) {
+  if (n <= kSmallDispatch) {
+    hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kDispatchChunk), 0, stream, ids, n, E, counts, offsets,
+                       perm, inv_perm, host_counts);
+    return hipGetLastError();
+  }
   const int nblk = (n + kDispatchChunk - 1) / kDispatchChunk;
   hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
                      blk_hist);

@@ -18,7 +18,6 @@ namespace {
 
 constexpr int GV_THREADS = 256;
 constexpr int GV_WAVES = GV_THREADS / 64;
-constexpr int GV_R = 4;        // weight rows per wave
 constexpr int GV_MAXTOK = 8;   // tokens per pass over the weights
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -35,7 +34,7 @@ __device__ __forceinline__ float dot8(const u32x4 &xv, const u32x4 &wv, float ac
   return acc;
 }
 
-template <int MODE, int NT, int NTMAX>
+template <int MODE, int NT, int NTMAX, int GV_R>
 __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg_chunks,
                                            const u32x4 *const (&w0)[GV_R], const u32x4 *const (&w1)[GV_R],
                                            int lane, float (&acc0)[GV_R][NTMAX],
@@ -60,9 +59,18 @@ __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg
   }
 }
 
+// Weight rows per wave: 4 while few tokens share a pass, 2 when up to 8 do (accumulators are
+// rows x tokens x {gate, up}: the kernel has to keep at least two waves per SIMD).
+template <int NTMAX>
+struct GvRows { static constexpr int value = NTMAX <= 2 ? 4 : 2; };
+
 template <int MODE, int NTMAX>
-__global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs args, int kseg,
-                                                                     int ntcap) {
+__global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
+                                                                     int has_extra, int kseg, int ntcap) {
+  // the last blockIdx.y of a launch with has_extra works on the second problem (the always-on
+  // shared experts), so that one launch streams both weight sets
+  const GemmArgs &args = (has_extra && blockIdx.y == gridDim.y - 1) ? extra : routed;
+  constexpr int GV_R = GvRows<NTMAX>::value;
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -82,6 +90,7 @@ __global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs
   const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
   const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
   const int n_first = (blockIdx.x * GV_WAVES + wave) * GV_R;
+  if ((int)blockIdx.x * GV_WAVES * GV_R >= args.N) return;  // grid.x covers the larger of the two problems
 
   for (int tok0 = 0; tok0 < cnt; tok0 += ntcap) {
     const int ntok = min(ntcap, cnt - tok0);  // ntcap <= NTMAX tokens fit the LDS buffer
@@ -111,7 +120,7 @@ __global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs
       }
 #define MOE_GEMV_CASE(NT)                                                             \
   if constexpr (NT <= NTMAX) {                                                        \
-    if (ntok == NT) accumulate<MODE, NT, NTMAX>(xs, seg_chunks, w0, w1, lane, acc0, acc1); \
+    if (ntok == NT) accumulate<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, lane, acc0, acc1); \
   }
       MOE_GEMV_CASE(1) MOE_GEMV_CASE(2) MOE_GEMV_CASE(3) MOE_GEMV_CASE(4)
       MOE_GEMV_CASE(5) MOE_GEMV_CASE(6) MOE_GEMV_CASE(7) MOE_GEMV_CASE(8)
@@ -141,13 +150,25 @@ __global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs
 }  // namespace
 
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
-                               int n_groups_in_mask, hipStream_t stream) {
-  if (n_groups_in_mask <= 0 || max_rows_per_group <= 0) return hipSuccess;
-  const int ntcap = max_rows_per_group < GV_MAXTOK ? max_rows_per_group : GV_MAXTOK;
+                               int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra) {
+  if (n_groups_in_mask <= 0 || max_rows_per_group <= 0) {
+    if (!extra) return hipSuccess;
+    return launch_grouped_gemv(mode, *extra, extra->single_rows, 1, stream, nullptr);
+  }
+  int max_tok = max_rows_per_group, max_n = args.N, max_k = args.K;
+  if (extra) {
+    if (extra->single_rows > max_tok) max_tok = extra->single_rows;
+    if (extra->N > max_n) max_n = extra->N;
+    if (extra->K > max_k) max_k = extra->K;
+  }
+  const int ntcap = max_tok < GV_MAXTOK ? max_tok : GV_MAXTOK;
   int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
-  if (kseg >= args.K) kseg = args.K;
+  if (kseg >= max_k) kseg = max_k;
   const size_t smem = (size_t)ntcap * kseg * 2;
-  dim3 grid((args.N + GV_WAVES * GV_R - 1) / (GV_WAVES * GV_R), n_groups_in_mask);
+  const int rows_per_block = GV_WAVES * (ntcap <= 2 ? 4 : 2);
+  dim3 grid((max_n + rows_per_block - 1) / rows_per_block, n_groups_in_mask + (extra ? 1 : 0));
+  const int has_extra = extra ? 1 : 0;
+  const GemmArgs &extra_args = extra ? *extra : args;
 #define MOE_GEMV_LAUNCH(MODE, NTMAX)                                                          \
   do {                                                                                        \
     auto kern = grouped_gemv_kernel<MODE, NTMAX>;                                             \
@@ -158,7 +179,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
       if (e != hipSuccess) return e;                                                          \
       attr_set = true;                                                                        \
     }                                                                                         \
-    hipLaunchKernelGGL(kern, grid, dim3(GV_THREADS), smem, stream, args, kseg, ntcap);        \
+    hipLaunchKernelGGL(kern, grid, dim3(GV_THREADS), smem, stream, args, extra_args, has_extra, kseg, ntcap);        \
   } while (0)
   if (mode == GEMM_SWIGLU) {
     if (ntcap == 1) MOE_GEMV_LAUNCH(GEMM_SWIGLU, 1);

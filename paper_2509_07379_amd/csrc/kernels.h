@@ -62,8 +62,9 @@ void set_gemm_variant(int mode, int variant);
 
 // ---- decode: bandwidth-bound expert mat-vec --------------------------------------------
 // Same argument block; rows per group are few (decode batch).  SWIGLU -> bf16 h, PLAIN_F32 -> fp32 y.
+// extra: optional second single-group problem (the shared experts) streamed by the same launch.
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
-                               int n_groups_in_mask, hipStream_t stream);
+                               int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra = nullptr);
 
 // ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----
 hipError_t launch_combine(const float *Y, int y_planes, long long y_plane_stride, const float *w,

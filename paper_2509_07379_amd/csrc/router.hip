@@ -55,8 +55,8 @@ __device__ __forceinline__ void wave_select(float v, int E, int n_sel, float &se
   }
 }
 
-template <int TPB>
-__global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
+template <int TPB, int NWAVES>
+__global__ __launch_bounds__(64 * NWAVES) void router_topk_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr, const float *__restrict__ bias,
     int bias_stride, int T, int d, int E, int k, int renormalize, float *__restrict__ logits,
     int32_t *__restrict__ ids, float *__restrict__ w) {
@@ -67,14 +67,14 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
   const int t0 = blockIdx.x * TPB;
   const int nchunk = d >> 3;
 
-  for (int c = tid; c < TPB * nchunk; c += kRouterThreads) {
+  for (int c = tid; c < TPB * nchunk; c += 64 * NWAVES) {
     int tok = c / nchunk, cc = c - tok * nchunk;
     int t = min(t0 + tok, T - 1);
     xs[c] = reinterpret_cast<const uint4 *>(x + (size_t)t * d)[cc];
   }
   __syncthreads();
 
-  for (int e = wave; e < E; e += kRouterWaves) {
+  for (int e = wave; e < E; e += NWAVES) {
     float acc[TPB];
 #pragma unroll
     for (int q = 0; q < TPB; ++q) acc[q] = 0.0f;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
   }
   __syncthreads();
 
-  for (int q = wave; q < TPB; q += kRouterWaves) {
+  for (int q = wave; q < TPB; q += NWAVES) {
     int t = t0 + q;
     if (t >= T) break;
     float v = lane < E ? lg[q * 64 + lane] : -INFINITY;
@@ -154,18 +154,19 @@ __global__ __launch_bounds__(64) void predictor_topm_kernel(const float *__restr
 hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
                               int bias_stride, int T, int d, int E, int k, int renormalize,
                               float *logits, int32_t *ids, float *w, hipStream_t stream) {
-  // 4 tokens per block share one pass over Wr; small batches use 1 token per block.
+  // 4 tokens per block share one pass over Wr; small batches (decode) use one token per block and
+  // 16 waves, so that the E dot products of a token run side by side.
   if (T >= 64) {
     constexpr int TPB = 4;
     size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
     int grid = (T + TPB - 1) / TPB;
-    hipLaunchKernelGGL(router_topk_kernel<TPB>, dim3(grid), dim3(kRouterThreads), smem, stream, x, wr,
-                       bias, bias_stride, T, d, E, k, renormalize, logits, ids, w);
+    hipLaunchKernelGGL((router_topk_kernel<TPB, 4>), dim3(grid), dim3(256), smem, stream, x, wr, bias,
+                       bias_stride, T, d, E, k, renormalize, logits, ids, w);
   } else {
     constexpr int TPB = 1;
     size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
-    hipLaunchKernelGGL(router_topk_kernel<TPB>, dim3(T), dim3(kRouterThreads), smem, stream, x, wr,
-                       bias, bias_stride, T, d, E, k, renormalize, logits, ids, w);
+    hipLaunchKernelGGL((router_topk_kernel<TPB, 16>), dim3(T), dim3(1024), smem, stream, x, wr, bias,
+                       bias_stride, T, d, E, k, renormalize, logits, ids, w);
   }
   return hipGetLastError();
 }
