@@ -446,6 +446,211 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_ring_kern
 }
 
 // ---------------------------------------------------------------------------------------------
+// Ping-pong kernel: 256 x 256 x 64 tiles in a two-stage LDS ring, eight waves in two groups of
+// four.  Waves w and w+4 of a block sit on the same SIMD; the two groups run the same loop one
+// barrier interval ("tick") apart, so while one wave of a SIMD issues 16 MFMAs, its partner pulls
+// its next fragments out of LDS and requests global->LDS loads.  Every wait (LDS latency, load
+// completion) falls into a tick in which the SIMD's matrix pipe is fed by the other wave.
+//
+// A wave owns 4 x 2 fragments of 32 x 32.  One K step of 64 is two M/C tick pairs:
+//   M1: read B (both fragments, 4 K slices) and A fragments 0,1      C1: 16 MFMAs on them
+//   M2: read A fragments 2,3 (B stays in registers)                   C2: 16 MFMAs
+//   group 0:  M1(0) C1(0) M2(0) C2(0) M1(1) ...
+//   group 1:    -   M1(0) C1(0) M2(0) C2(0) ...
+// The B rows of a stage are free after both groups' M1, the lower 128 A rows likewise, the upper
+// 128 A rows after both M2.  Refills are spread so that every M tick requests four wave-wide loads
+// per wave and each load has four to six ticks to land, although only two stages fit into LDS:
+//   M2(H): B rows of stage H+2 (each group one half)
+//   M1(H): group 0 the lower A rows, group 1 the upper A rows of stage H+1
+// Loads move whole 128-byte lines (8 tile rows per wave-wide load): half lines would halve the L1
+// fill rate.  Needs K % 64 == 0.
+template <int MODE>
+__global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs args) {
+  constexpr int BM = 256, BN = 256, WARPS_M = 2, WARPS_N = 4;
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr int FM = 4, FN = 2;
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int STAGE = (BM + BN) * ROW_BYTES;   // 64 KB
+  constexpr int NL = 4;                          // wave-wide loads per wave and M tick
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;          // the two waves of a SIMD are in different groups
+  const int wm = grp, wn = wave & 3;
+
+  TileInfo t;
+  if (!decode_tile<BM, BN_OUT>(args, t)) return;
+
+  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride;
+  const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
+  const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
+  const int kt_total = args.K / BK;
+  const int kt_begin = (int)((long long)kt_total * t.ks / args.splitk);
+  const int kt_end = (int)((long long)kt_total * (t.ks + 1) / args.splitk);
+  const int nk = kt_end - kt_begin;
+
+  // Row group g (0..63) is tile rows 8g..8g+7 of a stage (A rows 0..255, then B rows 0..255) and
+  // one wave-wide load: lane l lands at row 8g + l/8, chunk position l%8, and fetches the chunk the
+  // swizzle maps there.  Group 0 loads the lower A rows and the first half of B, group 1 the rest.
+  // Sources are 32-bit byte offsets into two buffer resources (A, and the blob from its gate/down
+  // rows on), so a load needs one VGPR and the K advance is a scalar offset.
+  const __amdgpu_buffer_rsrc_t a_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(args.A), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t b_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(B0), 0, 0x7FFFFFFF, 0x00020000);
+  uint32_t src[2 * NL];          // [0, NL): A row groups, [NL, 2 NL): B row groups
+  int dst[2 * NL];               // LDS byte offset of the row group inside a stage
+#pragma unroll
+  for (int i = 0; i < 2 * NL; ++i) {
+    const int g = (i / NL) * 32 + grp * 16 + (i % NL) * 4 + (wave & 3);
+    const int row = g * 8 + (lane >> 3);
+    const int kc = (lane & 7) ^ ((row >> 1) & 7);
+    dst[i] = g * 1024;
+    if (i < NL) {
+      int rr = row < t.rows_valid ? row : 0;
+      int p = t.row0 + t.tile_row0 + rr;
+      long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
+      src[i] = (uint32_t)((srow * args.lda + kc * 8) * 2);
+    } else {
+      int r = row - BM;
+      long long up = 0;
+      if (MODE == GEMM_SWIGLU && r >= BN / 2) { up = args.b1_off - args.b0_off; r -= BN / 2; }
+      int n = t.n0 + r;
+      if (n >= args.N) n = args.N - 1;
+      src[i] = (uint32_t)(up + ((long long)n * args.ldb + kc * 8) * 2);
+    }
+  }
+
+  int fm_valid = 0;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < t.rows_valid) ? 1 : 0;
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // LDS byte offset of this lane's 16 bytes of K slice 0 inside a stage; slice ks is at ^ (ks << 5)
+  // (the swizzle XORs the chunk index, and slice ks only changes bits 1..2 of it).
+  const int lrow = lane & 31, lk = lane >> 5;
+  int a_addr[FM], b_addr[FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a_addr[i] = swz((i * WARPS_M + wm) * 32 + lrow, lk);
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
+                                           : (j * WARPS_N + wn) * 32 + lrow;
+    b_addr[j] = BM * ROW_BYTES + swz(brow, lk);
+  }
+
+  // this wave's A (WHICH_ = 0) or B (WHICH_ = 1) loads of stage q_
+#define MOE_PISSUE(q_, WHICH_)                                                                       \
+  do {                                                                                               \
+    _Pragma("unroll") for (int i_ = (WHICH_) * NL; i_ < (WHICH_) * NL + NL; ++i_)                    \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds((WHICH_) ? b_rsrc : a_rsrc,                           \
+                                               (lds_ptr_t)(smem + ((q_) & 1) * STAGE + dst[i_]), 16, \
+                                               (int)src[i_], (kt_begin + (q_)) * ROW_BYTES, 0, 0);   \
+  } while (0)
+#define MOE_PVMCNT(n_) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n_) & 15) | (((n_) >> 4) << 14))
+#define MOE_PBARRIER()                                                                               \
+  do {                                                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+    __builtin_amdgcn_s_barrier();                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+  } while (0)
+#define MOE_PREAD_A(I0_, I1_)                                                                        \
+  _Pragma("unroll") for (int i_ = (I0_); i_ < (I1_); ++i_)                                           \
+    _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                              \
+      af_[i_ & 1][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (a_addr[i_] ^ (ks_ << 5)))
+#define MOE_PMMA(I0_, I1_)                                                                           \
+  do {                                                                                               \
+    __builtin_amdgcn_s_setprio(1);                                                                   \
+    _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                              \
+      _Pragma("unroll") for (int i_ = (I0_); i_ < (I1_); ++i_)                                       \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
+          acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i_ & 1][ks_], bf_[j_][ks_],      \
+                                                                acc[i_][j_], 0, 0, 0);               \
+    __builtin_amdgcn_s_setprio(0);                                                                   \
+  } while (0)
+// One K step of one wave.  FMV: valid A fragments.  iss1_ / iss2_: the upper-or-lower A rows of
+// stage H+1 / the B rows of stage H+2 are requested here (M1(0) requests nothing: the prologue
+// already has); next_: stage H+1 exists.  A wave's loads complete in order: after M2(H) its
+// youngest are [B(H+1)] [A(H+1)] [B(H+2)].  Group 1 has to certify its share at the end of its M
+// ticks (group 0 reads in the next tick); group 0 can wait until the end of C2, right before its
+// own M1(H+1).  The flags are wave-uniform, so the branches are scalar.
+#define MOE_PP_STEP(FMV, iss1_, iss2_, next_)                                                        \
+  do {                                                                                               \
+    const unsigned char *st_ = smem + (H & 1) * STAGE;                                               \
+    /* M1 */                                                                                         \
+    if (FMV > 0) {                                                                                   \
+      _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                              \
+        _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                          \
+          bf_[j_][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (b_addr[j_] ^ (ks_ << 5)));         \
+      MOE_PREAD_A(0, (FMV < 2 ? FMV : 2));                                                           \
+    }                                                                                                \
+    if (iss1_) MOE_PISSUE(H + 1, 0);                                                                 \
+    if (grp) { if (next_) MOE_PVMCNT(2 * NL); else MOE_PVMCNT(0); }  /* upper A rows of stage H */   \
+    __builtin_amdgcn_s_waitcnt(0xC07F);  /* lgkmcnt(0): fragments are in */                          \
+    MOE_PBARRIER();                                                                                  \
+    /* C1 */                                                                                         \
+    if (FMV > 0) MOE_PMMA(0, (FMV < 2 ? FMV : 2));                                                   \
+    MOE_PBARRIER();                                                                                  \
+    /* M2 */                                                                                         \
+    if (FMV > 2) MOE_PREAD_A(2, FMV);                                                                \
+    if (iss2_) MOE_PISSUE(H + 2, 1);                                                                 \
+    if (grp) { if (iss2_) MOE_PVMCNT(2 * NL); else if (next_) MOE_PVMCNT(NL); else MOE_PVMCNT(0); }  \
+    __builtin_amdgcn_s_waitcnt(0xC07F);                                                              \
+    MOE_PBARRIER();                                                                                  \
+    /* C2 */                                                                                         \
+    if (FMV > 2) MOE_PMMA(2, FMV);                                                                   \
+    if (!grp) { if (iss2_) MOE_PVMCNT(NL); else MOE_PVMCNT(0); }     /* all of stage H+1 */          \
+    MOE_PBARRIER();                                                                                  \
+  } while (0)
+#define MOE_PP_LOOP(FMV)                                                                             \
+  do {                                                                                               \
+    bf16x8 af_[2][4], bf_[FN][4];                                                                    \
+    int H = 0;                                                                                       \
+    for (; H < nk - 2; ++H) MOE_PP_STEP(FMV, H > 0, true, true);                                     \
+    for (; H < nk; ++H) MOE_PP_STEP(FMV, (H > 0 && H + 1 < nk), false, (H + 1 < nk));                \
+  } while (0)
+
+  if (nk > 0) {
+    MOE_PISSUE(0, 1);
+    MOE_PISSUE(0, 0);
+    if (nk > 1) {
+      MOE_PISSUE(1, 1);
+      MOE_PISSUE(1, 0);
+      MOE_PVMCNT(2 * NL);   // stage 0 has landed
+    } else {
+      MOE_PVMCNT(0);
+    }
+    MOE_PBARRIER();
+    if (grp == 1) MOE_PBARRIER();   // group 1 runs one tick behind
+    switch (fm_valid) {
+      case 0: MOE_PP_LOOP(0); break;
+      case 1: MOE_PP_LOOP(1); break;
+      case 2: MOE_PP_LOOP(2); break;
+      case 3: MOE_PP_LOOP(3); break;
+      default: MOE_PP_LOOP(4); break;
+    }
+    if (grp == 0) MOE_PBARRIER();   // same number of barriers for both groups
+  }
+#undef MOE_PP_LOOP
+#undef MOE_PP_STEP
+#undef MOE_PMMA
+#undef MOE_PREAD_A
+#undef MOE_PBARRIER
+#undef MOE_PVMCNT
+#undef MOE_PISSUE
+
+  store_tile<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Register-staged kernel with zero fill of the K tail (K % 8 == 0 is enough).
 template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_ktail_kernel(const GemmArgs args) {
@@ -607,6 +812,29 @@ hipError_t launch_ring(const GemmArgs &args, int max_rows, int n_groups_in_mask,
 }
 
 template <int MODE>
+hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  constexpr int BM = 256, BN = 256;
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES;
+  auto kern = grouped_gemm_pp_kernel<MODE>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const long long n_tiles_n = (args.N + BN_OUT - 1) / BN_OUT;
+  const long long m_tiles_ub = (long long)max_rows / BM + n_groups_in_mask;
+  long long ub = m_tiles_ub * n_tiles_n * args.splitk;
+  if (ub <= 0) return hipSuccess;
+  ub = (ub + 7) / 8 * 8;
+  if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)ub), dim3(512), smem, stream, args);
+  return hipGetLastError();
+}
+
+template <int MODE>
 hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BM = 128, BN = 128;
   constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
@@ -635,12 +863,17 @@ template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.K % BK != 0) return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
   int v = g_variant[MODE];
+  // the ping-pong kernel addresses A and the blob with 31-bit byte offsets
+  const bool pp_ok = (long long)max_rows * args.lda * 2 < 0x7FFFFFFFll &&
+                     (args.b1_off - args.b0_off) + (long long)args.N * args.ldb * 2 < 0x7FFFFFFFll &&
+                     args.b1_off >= args.b0_off;
   if (v == 0) {
-    // 256 x 256 tiles (8 waves, each 128 x 64) unless the groups are small on average, where the
-    // finer 128 x 128 tiles waste less of the matrix cores on empty rows
+    // 256 x 256 ping-pong tiles unless the groups are small on average, where the finer 128 x 128
+    // tiles waste less of the matrix cores on empty rows
     const long long avg_rows = n_groups_in_mask > 0 ? (long long)max_rows / n_groups_in_mask : max_rows;
-    v = avg_rows > 96 ? 6 : 1;
+    v = avg_rows > 96 ? (pp_ok ? 12 : 6) : 1;
   }
+  if (v == 12 && !pp_ok) v = 6;
   switch (v) {
     case 2: return launch_cfg<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 3: return launch_cfg<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
@@ -652,6 +885,7 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
     case 9: return launch_ring<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 10: return launch_ring<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 11: return launch_ring<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    case 12: return launch_pp<MODE>(args, max_rows, n_groups_in_mask, stream);
     default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
   }
 }
