@@ -27,6 +27,11 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+// Timing hook for a measurement harness that includes this file: expands to nothing in the library.
+#ifndef MOE_GEMM_PROBE
+#define MOE_GEMM_PROBE(point_)
+#endif
+
 namespace moe {
 
 namespace {
@@ -34,6 +39,8 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;           // K elements per stage (128 bytes per row)
 constexpr int ROW_BYTES = BK * 2;
@@ -94,34 +101,173 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs &args, TileInfo &t) {
   return t.rows_valid > 0;
 }
 
+// The same tile numbering for a kernel whose blocks walk over several tiles: count once, then
+// decode logical tile l.
+template <int BM, int BN_OUT>
+__device__ __forceinline__ int count_tiles(const GemmArgs &args) {
+  const int per_m = ((args.N + BN_OUT - 1) / BN_OUT) * args.splitk;
+  if (!args.offsets) return ((args.single_rows + BM - 1) / BM) * per_m;
+  int total = 0;
+  for (int e = 0; e < args.n_groups; ++e)
+    if ((args.group_mask >> e) & 1ull) {
+      int cnt = args.offsets[e + 1] - args.offsets[e];
+      total += ((cnt + BM - 1) / BM) * per_m;
+    }
+  return total;
+}
+
+template <int BM, int BN_OUT>
+__device__ __forceinline__ bool decode_logical_tile(const GemmArgs &args, int l, TileInfo &t) {
+  const int per_m = ((args.N + BN_OUT - 1) / BN_OUT) * args.splitk;
+  int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
+  if (args.offsets) {
+    for (int e = 0; e < args.n_groups; ++e) {
+      if (!((args.group_mask >> e) & 1ull)) continue;
+      int o = args.offsets[e], c = args.offsets[e + 1] - o;
+      int tiles = ((c + BM - 1) / BM) * per_m;
+      if (l < tiles) { grp = e; row0 = o; cnt = c; break; }
+      l -= tiles;
+    }
+  }
+  const int mt = (cnt + BM - 1) / BM;
+  const int m_idx = l % mt;
+  const int rest = l / mt;
+  t.ks = rest % args.splitk;
+  const int n_idx = rest / args.splitk;
+  int rpt = (((cnt + mt - 1) / mt) + 31) & ~31;   // balanced tile height
+  if (rpt > BM) rpt = BM;
+  t.grp = grp;
+  t.row0 = row0;
+  t.tile_row0 = m_idx * rpt;
+  t.rows_valid = min(rpt, cnt - t.tile_row0);
+  t.n0 = n_idx * BN_OUT;
+  return t.rows_valid > 0;
+}
+
+// A value the optimiser cannot trace back: what is computed from it inside a loop stays inside.
+__device__ __forceinline__ int opaque(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
+// fp32 -> bf16 by the hardware conversion (round to nearest even).
+__device__ __forceinline__ uint16_t cvt_bf16(float f) {
+  return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
+}
+
+template <int MODE>
+__device__ __forceinline__ void store_value(char *ptr, float v, float v_up) {
+  if (MODE == GEMM_SWIGLU)
+    *reinterpret_cast<uint16_t *>(ptr) = cvt_bf16(silu(v) * v_up);
+  else if (MODE == GEMM_PLAIN_F32)
+    *reinterpret_cast<float *>(ptr) = v;
+  else
+    *reinterpret_cast<uint16_t *>(ptr) = cvt_bf16(v);
+}
+
 // Epilogue.  C fragment layout of the 32x32 MFMA: lane holds column (lane % 32) and rows
-// 8*(r/4) + 4*(lane/32) + r%4 for its 16 registers r.
+// 8*(r/4) + 4*(lane/32) + r%4 for its 16 registers r.  Per fragment the address is a wave-uniform
+// base plus one per-lane offset that is the same for every store of the kernel, and a fragment
+// that lies completely inside the tile and the matrix is stored without per-lane tests.
 template <int MODE, int FM, int FN, int WARPS_M, int WARPS_N>
 __device__ __forceinline__ void store_tile(const GemmArgs &args, const TileInfo &t, int wm, int wn, int lane,
-                                           int fm_valid, floatx16 (&acc)[FM][FN]) {
+                                           int fm_valid, floatx16 (&acc)[FM][FN], int i_begin = 0,
+                                           int i_end = FM) {
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int ESIZE = (MODE == GEMM_PLAIN_F32) ? 4 : 2;
+  lane = opaque(lane);   // the per-lane values below are re-derived per call instead of being kept alive
   const int lrow = lane & 31, lk = lane >> 5;
+  const uint32_t lane_off = (uint32_t)((4 * lk) * args.ldo + lrow) * ESIZE;   // bytes
+  char *plane = reinterpret_cast<char *>(args.out) +
+                (MODE == GEMM_PLAIN_F32 ? (long long)t.ks * args.out_split_stride * ESIZE : 0ll);
   const long long out_row_base = (long long)t.row0 + t.tile_row0;
+  const long long row_step = (long long)args.ldo * ESIZE;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
-    if (i >= fm_valid) continue;
-    const int frow = (i * WARPS_M + wm) * 32;
+    if (i < i_begin || i >= i_end || i >= fm_valid) continue;
+    const int frow = (i * WARPS_M + wm) * 32;   // uniform
 #pragma unroll
     for (int j = 0; j < FNH; ++j) {
-      const int col = t.n0 + (j * WARPS_N + wn) * 32 + lrow;
-      if (col >= args.N) continue;
+      const int col0 = t.n0 + (j * WARPS_N + wn) * 32;   // uniform
+      if (col0 >= args.N) continue;
+      char *sp = plane + ((out_row_base + frow) * args.ldo + col0) * ESIZE;   // uniform, walks down the rows
+      const bool full = frow + 32 <= t.rows_valid && col0 + 32 <= args.N;
+      if (full) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = frow + 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (row >= t.rows_valid) continue;
-        const long long o = (out_row_base + row) * args.ldo + col;
-        if (MODE == GEMM_SWIGLU) {
-          float h = silu(acc[i][j][r]) * acc[i][j + FNH][r];
-          reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(h);
-        } else if (MODE == GEMM_PLAIN_F32) {
-          reinterpret_cast<float *>(args.out)[(long long)t.ks * args.out_split_stride + o] = acc[i][j][r];
-        } else {
-          reinterpret_cast<uint16_t *>(args.out)[o] = f32_to_bf16(acc[i][j][r]);
+        for (int r = 0; r < 16; ++r) {
+          store_value<MODE>(sp + lane_off, acc[i][j][r], acc[i][(MODE == GEMM_SWIGLU) ? j + FNH : j][r]);
+          sp += ((r & 3) == 3 ? 5ll : 1ll) * row_step;   // rows 0..3, 8..11, 16..19, 24..27
+        }
+      } else {
+        const bool col_ok = col0 + lrow < args.N;
+        const int rows_left = t.rows_valid - frow - 4 * lk;   // the lane's row 8*(r/4) + r%4 must be below
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (col_ok && 8 * (r >> 2) + (r & 3) < rows_left)
+            store_value<MODE>(sp + lane_off, acc[i][j][r], acc[i][(MODE == GEMM_SWIGLU) ? j + FNH : j][r]);
+          sp += ((r & 3) == 3 ? 5ll : 1ll) * row_step;
+        }
+      }
+    }
+  }
+}
+
+// Epilogue for accumulators of transposed fragments (MFMA called with the B fragment as first
+// operand): lane holds output row (lane % 32) and the columns 8*(r/4) + 4*(lane/32) + r%4 of the
+// fragment, i.e. four groups of four consecutive columns, so a fragment leaves in four stores of
+// 8 (bf16) or 16 (fp32) bytes per lane that share one address and differ in the immediate offset.
+template <int MODE, int FM, int FN, int WARPS_M, int WARPS_N>
+__device__ __forceinline__ void store_tile_cols(const GemmArgs &args, const TileInfo &t, int wm, int wn, int lane,
+                                                int fm_valid, floatx16 (&acc)[FM][FN], int i_begin, int i_end) {
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int ESIZE = (MODE == GEMM_PLAIN_F32) ? 4 : 2;
+  lane = opaque(lane);   // the per-lane values below are re-derived per call instead of being kept alive
+  const int lrow = lane & 31, lk = lane >> 5;
+  const uint32_t lane_off = (uint32_t)(lrow * args.ldo + 4 * lk) * ESIZE;   // bytes
+  char *plane = reinterpret_cast<char *>(args.out) +
+                (MODE == GEMM_PLAIN_F32 ? (long long)t.ks * args.out_split_stride * ESIZE : 0ll);
+  const long long out_row_base = (long long)t.row0 + t.tile_row0;
+  const bool aligned = (args.ldo * ESIZE) % 16 == 0 && (reinterpret_cast<uintptr_t>(args.out) & 15) == 0 &&
+                       (MODE != GEMM_PLAIN_F32 || (args.out_split_stride * ESIZE) % 16 == 0);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    if (i < i_begin || i >= i_end || i >= fm_valid) continue;
+    const int frow = (i * WARPS_M + wm) * 32;   // uniform
+#pragma unroll
+    for (int j = 0; j < FNH; ++j) {
+      const int col0 = t.n0 + (j * WARPS_N + wn) * 32;   // uniform
+      if (col0 >= args.N) continue;
+      char *sp = plane + ((out_row_base + frow) * args.ldo + col0) * ESIZE;   // uniform
+      float v[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        v[r] = (MODE == GEMM_SWIGLU) ? silu(acc[i][j][r]) * acc[i][j + FNH][r] : acc[i][j][r];
+      const bool full = frow + 32 <= t.rows_valid && col0 + 32 <= args.N && aligned;
+      if (full) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          char *ptr = sp + lane_off + g * 8 * ESIZE;
+          // plain (cached) stores: streaming stores were several times slower here
+          if (MODE == GEMM_PLAIN_F32) {
+            f32x4 o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+            *reinterpret_cast<f32x4 *>(ptr) = o;
+          } else {
+            u32x2 o;
+            o.x = (uint32_t)cvt_bf16(v[4 * g]) | ((uint32_t)cvt_bf16(v[4 * g + 1]) << 16);
+            o.y = (uint32_t)cvt_bf16(v[4 * g + 2]) | ((uint32_t)cvt_bf16(v[4 * g + 3]) << 16);
+            *reinterpret_cast<u32x2 *>(ptr) = o;
+          }
+        }
+      } else if (frow + lrow < t.rows_valid) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = 8 * (r >> 2) + 4 * lk + (r & 3);
+          if (col0 + c >= args.N) continue;
+          char *ptr = sp + ((long long)lrow * args.ldo + c) * ESIZE;
+          if (MODE == GEMM_PLAIN_F32)
+            *reinterpret_cast<float *>(ptr) = v[r];
+          else
+            *reinterpret_cast<uint16_t *>(ptr) = cvt_bf16(v[r]);
         }
       }
     }
@@ -479,16 +625,21 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   const int grp = wave >> 2;          // the two waves of a SIMD are in different groups
   const int wm = grp, wn = wave & 3;
 
-  TileInfo t;
-  if (!decode_tile<BM, BN_OUT>(args, t)) return;
+  // A block walks over the tiles (b % 8) * chunk + b / 8 + i * (blocks / 8), i = 0, 1, ...: the blocks
+  // of one XCD (every 8th) work on consecutive logical tiles at any time, and the metadata and first
+  // loads of the next tile are requested before the current tile's results are stored.
+  const int total = count_tiles<BM, BN_OUT>(args);
+  const int chunk = (total + 7) >> 3;
+  const int xbase = ((int)blockIdx.x & 7) * chunk;
+  const int nslots = (int)gridDim.x >> 3;
+  int slot = (int)blockIdx.x >> 3;
+  if (slot >= chunk || xbase + slot >= total) return;
 
-  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride;
-  const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
-  const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
-  const int kt_total = args.K / BK;
-  const int kt_begin = (int)((long long)kt_total * t.ks / args.splitk);
-  const int kt_end = (int)((long long)kt_total * (t.ks + 1) / args.splitk);
-  const int nk = kt_end - kt_begin;
+  // The last column tile is moved back so that it ends at column N - 1 (the overlap is computed
+  // twice, to the same bits): every B row of a tile exists, and its offset is affine in the row.
+  TileInfo t;
+  decode_logical_tile<BM, BN_OUT>(args, xbase + slot, t);
+  t.n0 = min(t.n0, args.N - BN_OUT);
 
   // Row group g (0..63) is tile rows 8g..8g+7 of a stage (A rows 0..255, then B rows 0..255) and
   // one wave-wide load: lane l lands at row 8g + l/8, chunk position l%8, and fetches the chunk the
@@ -497,63 +648,72 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   // rows on), so a load needs one VGPR and the K advance is a scalar offset.
   const __amdgpu_buffer_rsrc_t a_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(args.A), 0, 0x7FFFFFFF, 0x00020000);
-  const __amdgpu_buffer_rsrc_t b_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(B0), 0, 0x7FFFFFFF, 0x00020000);
-  uint32_t src[2 * NL];          // [0, NL): A row groups, [NL, 2 NL): B row groups
-  int dst[2 * NL];               // LDS byte offset of the row group inside a stage
-#pragma unroll
-  for (int i = 0; i < 2 * NL; ++i) {
-    const int g = (i / NL) * 32 + grp * 16 + (i % NL) * 4 + (wave & 3);
-    const int row = g * 8 + (lane >> 3);
-    const int kc = (lane & 7) ^ ((row >> 1) & 7);
-    dst[i] = g * 1024;
-    if (i < NL) {
-      int rr = row < t.rows_valid ? row : 0;
-      int p = t.row0 + t.tile_row0 + rr;
-      long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
-      src[i] = (uint32_t)((srow * args.lda + kc * 8) * 2);
-    } else {
-      int r = row - BM;
-      long long up = 0;
-      if (MODE == GEMM_SWIGLU && r >= BN / 2) { up = args.b1_off - args.b0_off; r -= BN / 2; }
-      int n = t.n0 + r;
-      if (n >= args.N) n = args.N - 1;
-      src[i] = (uint32_t)(up + ((long long)n * args.ldb + kc * 8) * 2);
-    }
+#define MOE_PGROUP(i_) (((i_) / NL) * 32 + grp * 16 + ((i_) % NL) * 4 + (wave & 3))
+
+  // Gathered source rows of this lane's A loads of tile tt_ (requested; used by MOE_PSRC), and the
+  // byte offsets of its eight loads.  (row >> 1) & 7 of a lane's row 8g + l/8 is 4 (g & 1) + l/16,
+  // and g & 1 = wave & 1 for all of a wave's row groups: one chunk offset serves all eight.
+#define MOE_PPERM(tt_, out_)                                                                         \
+  _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                                \
+    const int row_ = MOE_PGROUP(i_) * 8 + (lane_s >> 3);                                             \
+    const int rr_ = row_ < (tt_).rows_valid ? row_ : 0;                                              \
+    const int p_ = (tt_).row0 + (tt_).tile_row0 + rr_;                                               \
+    (out_)[i_] = args.perm ? args.perm[p_] : p_;                                                     \
   }
+#define MOE_PSRC(tt_, prow_)                                                                         \
+  do {                                                                                               \
+    const int kc16_ = ((lane_s & 7) ^ ((wave & 1) * 4 + (lane_s >> 4))) * 16;                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
+      const long long srow_ =                                                                        \
+          args.perm ? (long long)((prow_)[i_] / args.k_top) : (long long)(prow_)[i_];                \
+      src[i_] = (uint32_t)(srow_ * args.lda * 2 + kc16_);                                            \
+    }                                                                                                \
+    /* B rows are n0 + 8 g + l/8: one per-lane offset, the row group's part is scalar */             \
+    src[NL] = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16_);                                      \
+    _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
+      int r_ = MOE_PGROUP(NL + i_) * 8 - BM;                                                         \
+      long long up_ = 0;                                                                             \
+      if (MODE == GEMM_SWIGLU && r_ >= BN / 2) { up_ = args.b1_off - args.b0_off; r_ -= BN / 2; }    \
+      b_soff[i_] = (int)(up_ + (long long)((tt_).n0 + r_) * args.ldb * 2);                           \
+    }                                                                                                \
+  } while (0)
+#define MOE_PTILE_SETUP(tt_)                                                                         \
+  do {                                                                                               \
+    const char *wptr_ = args.wbase + (long long)args.slot[(tt_).grp] * args.wstride + args.b0_off;   \
+    b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(wptr_), 0, 0x7FFFFFFF, 0x00020000); \
+    const int kt_total_ = args.K / BK;                                                               \
+    kt_begin = (int)((long long)kt_total_ * (tt_).ks / args.splitk);                                 \
+    nk = (int)((long long)kt_total_ * ((tt_).ks + 1) / args.splitk) - kt_begin;                      \
+    fm_valid = 0;                                                                                    \
+    _Pragma("unroll") for (int i_ = 0; i_ < FM; ++i_)                                                \
+      fm_valid += ((i_ * WARPS_M + wm) * 32 < (tt_).rows_valid) ? 1 : 0;                             \
+  } while (0)
 
-  int fm_valid = 0;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < t.rows_valid) ? 1 : 0;
-
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  // LDS byte offset of this lane's 16 bytes of K slice 0 inside a stage; slice ks is at ^ (ks << 5)
-  // (the swizzle XORs the chunk index, and slice ks only changes bits 1..2 of it).
-  const int lrow = lane & 31, lk = lane >> 5;
-  int a_addr[FM], b_addr[FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i) a_addr[i] = swz((i * WARPS_M + wm) * 32 + lrow, lk);
-#pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
-                                           : (j * WARPS_N + wn) * 32 + lrow;
-    b_addr[j] = BM * ROW_BYTES + swz(brow, lk);
+  __amdgpu_buffer_rsrc_t b_rsrc;
+  int kt_begin, nk, fm_valid;
+  uint32_t src[NL + 1];          // per-lane byte offsets: the A row groups, then one for all B rows
+  int b_soff[NL];                // scalar byte offsets of the B row groups
+  {
+    const int lane_s = opaque(lane);
+    int prow[NL];
+    MOE_PPERM(t, prow);
+    MOE_PSRC(t, prow);
   }
+  MOE_PTILE_SETUP(t);
 
   // this wave's A (WHICH_ = 0) or B (WHICH_ = 1) loads of stage q_
 #define MOE_PISSUE(q_, WHICH_)                                                                       \
   do {                                                                                               \
-    _Pragma("unroll") for (int i_ = (WHICH_) * NL; i_ < (WHICH_) * NL + NL; ++i_)                    \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds((WHICH_) ? b_rsrc : a_rsrc,                           \
-                                               (lds_ptr_t)(smem + ((q_) & 1) * STAGE + dst[i_]), 16, \
-                                               (int)src[i_], (kt_begin + (q_)) * ROW_BYTES, 0, 0);   \
+    _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
+      if (WHICH_)                                                                                    \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
+            b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + MOE_PGROUP(NL + i_) * 1024), 16,         \
+            (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * ROW_BYTES, 0, 0);                         \
+      else                                                                                           \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
+            a_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + MOE_PGROUP(i_) * 1024), 16,              \
+            (int)src[i_], (kt_begin + (q_)) * ROW_BYTES, 0, 0);                                      \
+    }                                                                                                \
   } while (0)
 #define MOE_PVMCNT(n_) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n_) & 15) | (((n_) >> 4) << 14))
 #define MOE_PBARRIER()                                                                               \
@@ -563,25 +723,28 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define MOE_PREAD_A(I0_, I1_)                                                                        \
-  _Pragma("unroll") for (int i_ = (I0_); i_ < (I1_); ++i_)                                           \
-    _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                              \
-      af_[i_ & 1][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (a_addr[i_] ^ (ks_ << 5)))
+  do {                                                                                               \
+    _Pragma("unroll") for (int i_ = (I0_); i_ < (I1_); ++i_)                                         \
+      _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                            \
+        af_[i_ & 1][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (a_addr[i_] ^ (ks_ << 5)));       \
+  } while (0)
 #define MOE_PMMA(I0_, I1_)                                                                           \
   do {                                                                                               \
     __builtin_amdgcn_s_setprio(1);                                                                   \
     _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                              \
       _Pragma("unroll") for (int i_ = (I0_); i_ < (I1_); ++i_)                                       \
         _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
-          acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i_ & 1][ks_], bf_[j_][ks_],      \
+          acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[j_][ks_], af_[i_ & 1][ks_],      \
                                                                 acc[i_][j_], 0, 0, 0);               \
     __builtin_amdgcn_s_setprio(0);                                                                   \
   } while (0)
-// One K step of one wave.  FMV: valid A fragments.  iss1_ / iss2_: the upper-or-lower A rows of
-// stage H+1 / the B rows of stage H+2 are requested here (M1(0) requests nothing: the prologue
-// already has); next_: stage H+1 exists.  A wave's loads complete in order: after M2(H) its
-// youngest are [B(H+1)] [A(H+1)] [B(H+2)].  Group 1 has to certify its share at the end of its M
-// ticks (group 0 reads in the next tick); group 0 can wait until the end of C2, right before its
-// own M1(H+1).  The flags are wave-uniform, so the branches are scalar.
+// One K step of one wave.  FMV of the wave's A fragments are valid: the others are neither read
+// nor multiplied (the loop is instantiated per count, so a tick stays straight-line code).
+// iss1_ / iss2_: the upper-or-lower A rows of stage H+1 / the B rows of stage H+2 are requested
+// here (M1(0) requests nothing: the prologue already has); next_: stage H+1 exists.  A wave's loads
+// complete in order: after M2(H) its youngest are [B(H+1)] [A(H+1)] [B(H+2)].  Group 1 has to
+// certify its share at the end of its M ticks (group 0 reads in the next tick); group 0 can wait
+// until the end of C2, right before its own M1(H+1).  The flags are wave-uniform: scalar branches.
 #define MOE_PP_STEP(FMV, iss1_, iss2_, next_)                                                        \
   do {                                                                                               \
     const unsigned char *st_ = smem + (H & 1) * STAGE;                                               \
@@ -613,22 +776,60 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 #define MOE_PP_LOOP(FMV)                                                                             \
   do {                                                                                               \
     bf16x8 af_[2][4], bf_[FN][4];                                                                    \
-    int H = 0;                                                                                       \
-    for (; H < nk - 2; ++H) MOE_PP_STEP(FMV, H > 0, true, true);                                     \
-    for (; H < nk; ++H) MOE_PP_STEP(FMV, (H > 0 && H + 1 < nk), false, (H + 1 < nk));                \
+    for (int H = 0; H < nk; ++H) MOE_PP_STEP(FMV, (H > 0 && H + 1 < nk), (H + 2 < nk), (H + 1 < nk)); \
   } while (0)
 
-  if (nk > 0) {
-    MOE_PISSUE(0, 1);
-    MOE_PISSUE(0, 0);
-    if (nk > 1) {
-      MOE_PISSUE(1, 1);
-      MOE_PISSUE(1, 0);
-      MOE_PVMCNT(2 * NL);   // stage 0 has landed
-    } else {
-      MOE_PVMCNT(0);
+// both stages' first loads of the tile set up last (stage 1 only if the tile has a second K step)
+#define MOE_PPROLOGUE()                                                                              \
+  do {                                                                                               \
+    MOE_PISSUE(0, 1);                                                                                \
+    MOE_PISSUE(0, 0);                                                                                \
+    if (nk > 1) {                                                                                    \
+      MOE_PISSUE(1, 1);                                                                              \
+      MOE_PISSUE(1, 0);                                                                              \
+    }                                                                                                \
+  } while (0)
+
+  MOE_PPROLOGUE();
+  for (;;) {
+    const int nslot = slot + nslots;
+    const bool has_next = nslot < chunk && xbase + nslot < total;
+    TileInfo tn = t;
+    if (has_next) {
+      decode_logical_tile<BM, BN_OUT>(args, xbase + nslot, tn);
+      tn.n0 = min(tn.n0, args.N - BN_OUT);
     }
+    MOE_GEMM_PROBE(0);
+    MOE_PVMCNT(0);   // this tile's first loads have landed (and the previous tile's stores are out)
+    MOE_GEMM_PROBE(1);
+
+    // LDS byte offset of this lane's 16 bytes of K slice 0 inside a stage; slice ks is at ^ (ks << 5)
+    // (the swizzle XORs the chunk index, and slice ks only changes bits 1..2 of it).  Derived from
+    // an opaque copy of the lane id so that they live only as long as the K loop.
+    int a_addr[FM], b_addr[FN];
+    {
+      const int lane_k = opaque(lane);
+      const int lrow = lane_k & 31, lk = lane_k >> 5;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) a_addr[i] = swz((i * WARPS_M + wm) * 32 + lrow, lk);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
+                                               : (j * WARPS_N + wn) * 32 + lrow;
+        b_addr[j] = BM * ROW_BYTES + swz(brow, lk);
+      }
+    }
+
+    floatx16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
     MOE_PBARRIER();
+    MOE_GEMM_PROBE(4);
     if (grp == 1) MOE_PBARRIER();   // group 1 runs one tick behind
     switch (fm_valid) {
       case 0: MOE_PP_LOOP(0); break;
@@ -637,8 +838,33 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       case 3: MOE_PP_LOOP(3); break;
       default: MOE_PP_LOOP(4); break;
     }
-    if (grp == 0) MOE_PBARRIER();   // same number of barriers for both groups
+    if (grp == 0) MOE_PBARRIER();   // same number of barriers for both groups; LDS is free now
+    MOE_GEMM_PROBE(2);
+
+    // The next tile's gathered rows are requested, half of this tile is stored while they arrive,
+    // then the next tile's first loads go out and fly while the other half is stored.
+    const int fm_cur = fm_valid;
+    const int lane_s = opaque(lane);
+    int prow_n[NL];
+    if (has_next) {
+      MOE_PPERM(tn, prow_n);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) prow_n[i] = 0;
+    }
+    store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, 0, FM / 2);
+    if (has_next) {
+      MOE_PSRC(tn, prow_n);
+      MOE_PTILE_SETUP(tn);
+      MOE_PPROLOGUE();
+    }
+    store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, FM / 2, FM);
+    MOE_GEMM_PROBE(3);
+    if (!has_next) break;
+    t = tn;
+    slot = nslot;
   }
+#undef MOE_PPROLOGUE
 #undef MOE_PP_LOOP
 #undef MOE_PP_STEP
 #undef MOE_PMMA
@@ -646,8 +872,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 #undef MOE_PBARRIER
 #undef MOE_PVMCNT
 #undef MOE_PISSUE
-
-  store_tile<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc);
+#undef MOE_PTILE_SETUP
+#undef MOE_PSRC
+#undef MOE_PPERM
+#undef MOE_PGROUP
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -811,6 +1039,19 @@ hipError_t launch_ring(const GemmArgs &args, int max_rows, int n_groups_in_mask,
   return hipGetLastError();
 }
 
+// One block per compute unit (128 KB of LDS each); the blocks walk over the tiles.
+static int pp_grid_blocks() {
+  static int blocks = 0;
+  if (!blocks) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+      cus = 256;
+    blocks = cus / 8 * 8;
+  }
+  return blocks;
+}
+
 template <int MODE>
 hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BM = 256, BN = 256;
@@ -830,7 +1071,8 @@ hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, h
   if (ub <= 0) return hipSuccess;
   ub = (ub + 7) / 8 * 8;
   if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(kern, dim3((unsigned)ub), dim3(512), smem, stream, args);
+  const long long grid = ub < pp_grid_blocks() ? ub : pp_grid_blocks();
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), smem, stream, args);
   return hipGetLastError();
 }
 
@@ -866,7 +1108,7 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
   // the ping-pong kernel addresses A and the blob with 31-bit byte offsets
   const bool pp_ok = (long long)max_rows * args.lda * 2 < 0x7FFFFFFFll &&
                      (args.b1_off - args.b0_off) + (long long)args.N * args.ldb * 2 < 0x7FFFFFFFll &&
-                     args.b1_off >= args.b0_off;
+                     args.b1_off >= args.b0_off && args.N >= (MODE == GEMM_SWIGLU ? 128 : 256);
   if (v == 0) {
     // 256 x 256 ping-pong tiles unless the groups are small on average, where the finer 128 x 128
     // tiles waste less of the matrix cores on empty rows
