@@ -28,6 +28,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 PEAK_PCIE_GBS = 64.0        # PCIe Gen5 x16 per direction
+# HBM bytes per launch of the gate/up GEMM on the headline workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 256 MiB device copy
+# (x2.000 and x1.000); the summary with the commands is profiles/prefill_c2_mixtral_gemm_counters.txt.
+# Algorithmic bytes of that launch: 1879 MB of weights + 16.8 MB of activations read, 117.4 MB written.
+MEASURED_TRAFFIC_BYTES = {"c2_mixtral_prefill": 2351.7e6 + 117.5e6}
 
 
 def log(*a):
@@ -203,10 +208,13 @@ def cpu_baseline(args, S, w, res, n_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps; the device needs ~15 layer calls after idle to settle its clocks")
     ap.add_argument("--workload", default="c2_mixtral_prefill")
-    ap.add_argument("--cpu-tokens", type=int, default=192, help="tokens of the workload the CPU oracle computes")
+    ap.add_argument("--cpu-tokens", type=int, default=1536, help="tokens of the workload the CPU oracle computes")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (a reference for hardware byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offloaded", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
@@ -229,6 +237,15 @@ def main():
     # onto 4 hardware queues, and two streams that land on the same queue serialise
     compute, copy, pred = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     res = prefill_resident(args, torch, B, H, S, w, compute, copy)
+    if args.calibration_copy:
+        # a copy kernel of known size: FETCH_SIZE / WRITE_SIZE of the GEMM launches are scaled by what the
+        # same counters read for these 256 MiB in and 256 MiB out
+        src = torch.full((64 << 20,), 3, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ms = res["ms"]
     tok_s = w.T / (ms * 1e-3)
     k = res["kern_ms"]
@@ -250,7 +267,8 @@ def main():
                                f"experts resident in HBM (S=E)", "counts": res["routing"]["counts"].tolist()},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm SwiGLU (gate+up)", "achieved": tf1,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tf1 / PEAK_BF16_TFLOPS,
-                     "traffic": None, "flops_per_launch": flops1, "avg_launch_ms": k["gemm1"]},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "traffic_unit": "bytes/launch",
+                     "flops_per_launch": flops1, "avg_launch_ms": k["gemm1"]},
         "kernels_ms": k,
         "gemm2": {"achieved": tf2, "unit": "TFLOP/s", "frac": tf2 / PEAK_BF16_TFLOPS},
         "mfma_util_layer": (flops1 + flops2) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
