@@ -103,6 +103,7 @@ struct Layer {
   std::vector<char> copy_pending;    // a copy into the slot was enqueued; compute has not waited yet
   std::vector<char> use_kind;        // 0: never read, 1: read behind used[slot], 2: read behind group_done
   std::vector<hipEvent_t> copied, used;
+  std::vector<hipEvent_t> copied_up;  // a split fetch has landed its gate / up matrices
   hipEvent_t group_done = nullptr;
   unsigned long long clock = 0;
   moe_stats stats{};
@@ -194,12 +195,34 @@ int pick_victim(const Layer &L, unsigned long long protected_mask) {
   return best;
 }
 
-// Enqueue the copy of expert e into slot s on the copy stream, behind the slot's last reader.
-int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t copy_stream) {
+// The copy stream waits for the last reader of slot s (nothing to wait for if it was never read).
+int wait_slot_free(Layer &L, int s, hipStream_t copy_stream) {
   if (L.use_kind[s] == 1) HIP_TRY(hipStreamWaitEvent(copy_stream, L.used[s], 0));
   if (L.use_kind[s] == 2) HIP_TRY(hipStreamWaitEvent(copy_stream, L.group_done, 0));
-  HIP_TRY(hipMemcpyAsync(L.slots + (size_t)s * ctx->blob_bytes, L.host_blob[e], ctx->blob_bytes,
-                         hipMemcpyHostToDevice, copy_stream));
+  return MOE_OK;
+}
+
+// Enqueue the copy of expert e into slot s on the copy stream, behind the slot's last reader
+// (waited: that wait is already on the stream).  split: the gate / up matrices and the down
+// matrix travel as two copies, with copied_up[s] recorded in between, so that the first matmul
+// can start while the down matrix is still on the link.
+int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t copy_stream,
+          bool waited = false, bool split = false) {
+  if (!waited) {
+    int rc = wait_slot_free(L, s, copy_stream);
+    if (rc) return rc;
+  }
+  char *dst = L.slots + (size_t)s * ctx->blob_bytes;
+  const char *src = static_cast<const char *>(L.host_blob[e]);
+  if (split) {
+    const size_t up_bytes = ctx->blob_bytes / 3 * 2;   // [W_gate; W_up], then W_down
+    HIP_TRY(hipMemcpyAsync(dst, src, up_bytes, hipMemcpyHostToDevice, copy_stream));
+    HIP_TRY(hipEventRecord(L.copied_up[s], copy_stream));
+    HIP_TRY(hipMemcpyAsync(dst + up_bytes, src + up_bytes, ctx->blob_bytes - up_bytes, hipMemcpyHostToDevice,
+                           copy_stream));
+  } else {
+    HIP_TRY(hipMemcpyAsync(dst, src, ctx->blob_bytes, hipMemcpyHostToDevice, copy_stream));
+  }
   HIP_TRY(hipEventRecord(L.copied[s], copy_stream));
   if (L.slot_expert[s] >= 0) L.expert_slot[L.slot_expert[s]] = -1;
   L.slot_expert[s] = e;
@@ -291,13 +314,15 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
 // Both expert matmuls of the groups in `mask`, on the compute stream.
 int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
                 int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream,
-                const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr) {
+                const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr,
+                hipEvent_t before_second = nullptr) {
   a1.group_mask = a2.group_mask = mask;
   if (decode) {
     {
       Timer t(ctx, stream, MOE_K_GEMV1);
       HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, max_rows_per_group, n_groups, stream, s1));
     }
+    if (before_second) HIP_TRY(hipStreamWaitEvent(stream, before_second, 0));
     Timer t(ctx, stream, MOE_K_GEMV2);
     HIP_TRY(launch_grouped_gemv(GEMM_PLAIN_F32, a2, max_rows_per_group, n_groups, stream, s2));
   } else {
@@ -305,6 +330,7 @@ int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned lo
       Timer t(ctx, stream, MOE_K_GEMM1);
       HIP_TRY(launch_grouped_gemm(GEMM_SWIGLU, a1, max_rows, n_groups, stream));
     }
+    if (before_second) HIP_TRY(hipStreamWaitEvent(stream, before_second, 0));
     Timer t(ctx, stream, MOE_K_GEMM2);
     HIP_TRY(launch_grouped_gemm(GEMM_PLAIN_F32, a2, max_rows, n_groups, stream));
   }
@@ -466,15 +492,21 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       }
     }
     // Misses stream through the slots in ascending id: fetch on the copy stream (behind the
-    // victim's last reader), compute as soon as the copy has landed.
-    for (int e : misses) {
-      int s = pick_victim(L, 0ull);
-      rc = place(ctx, L, e, s, false, ks);
+    // victim's last reader), compute as soon as the copy has landed.  The last fetch is split so
+    // that only the down projection and the weighted sum run after it.  (The copy stream's wait
+    // for a victim's reader cannot be moved ahead of the previous copy: that reader runs right
+    // after the previous copy, so the wait would hold the copy back as well.)
+    for (size_t i = 0; i < misses.size(); ++i) {
+      const int e = misses[i];
+      const int s = pick_victim(L, 0ull);
+      const bool last = i + 1 == misses.size();
+      rc = place(ctx, L, e, s, false, ks, false, last);
       if (rc) return rc;
-      HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
+      HIP_TRY(hipStreamWaitEvent(cs, last ? L.copied_up[s] : L.copied[s], 0));
       L.copy_pending[s] = 0;
       a1.slot[e] = a2.slot[e] = (signed char)s;
-      rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
+      rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs, nullptr, nullptr,
+                       last ? L.copied[s] : nullptr);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(L.used[s], cs));
       L.use_kind[s] = 1;
@@ -527,6 +559,7 @@ int moe_destroy(moe_ctx *ctx) {
   (void)hipDeviceSynchronize();
   for (Layer &L : ctx->layers) {
     for (hipEvent_t e : L.copied) (void)hipEventDestroy(e);
+    for (hipEvent_t e : L.copied_up) (void)hipEventDestroy(e);
     for (hipEvent_t e : L.used) (void)hipEventDestroy(e);
     if (L.group_done) (void)hipEventDestroy(L.group_done);
   }
@@ -572,9 +605,11 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
   Layer &L = *Lp;
   if (!L.bound) {
     L.copied.resize(S);
+    L.copied_up.resize(S);
     L.used.resize(S);
     for (int s = 0; s < S; ++s) {
       HIP_TRY(hipEventCreateWithFlags(&L.copied[s], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&L.copied_up[s], hipEventDisableTiming));
       HIP_TRY(hipEventCreateWithFlags(&L.used[s], hipEventDisableTiming));
     }
     HIP_TRY(hipEventCreateWithFlags(&L.group_done, hipEventDisableTiming));
