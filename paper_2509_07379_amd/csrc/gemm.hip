@@ -728,14 +728,30 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                            \
         af_[i_ & 1][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (a_addr[i_] ^ (ks_ << 5)));       \
   } while (0)
-#define MOE_PMMA(I0_, I1_)                                                                           \
+// MFMAs of fragment i_ for K slices [KS0_, KS1_) against both B fragments
+#define MOE_PMMA1(i_, ks_)                                                                           \
+  _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                                  \
+    acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[j_][ks_], af_[(i_) & 1][ks_], acc[i_][j_], 0, 0, 0)
+// The two compute ticks of a K step, for FMV valid fragments, with the MFMAs split evenly:
+//   4: {0,1} | {2,3}     3: 0 and the first half of 1 | second half of 1 and 2
+//   2: 0 | 1             1: first half of 0 | second half of 0
+// (fragments 0,1 are read in M1 and 2,3 in M2, whatever tick multiplies them)
+#define MOE_PMMA(FMV, TICK_)                                                                         \
   do {                                                                                               \
     __builtin_amdgcn_s_setprio(1);                                                                   \
-    _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                              \
-      _Pragma("unroll") for (int i_ = (I0_); i_ < (I1_); ++i_)                                       \
-        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
-          acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[j_][ks_], af_[i_ & 1][ks_],      \
-                                                                acc[i_][j_], 0, 0, 0);               \
+    _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_) {                                            \
+      if (FMV == 4) {                                                                                \
+        MOE_PMMA1(2 * (TICK_), ks_);                                                                 \
+        MOE_PMMA1(2 * (TICK_) + 1, ks_);                                                             \
+      } else if (FMV == 3) {                                                                         \
+        if ((TICK_) == 0) { MOE_PMMA1(0, ks_); if (ks_ < 2) MOE_PMMA1(1, ks_); }                     \
+        else { if (ks_ >= 2) MOE_PMMA1(1, ks_); MOE_PMMA1(2, ks_); }                                 \
+      } else if (FMV == 2) {                                                                         \
+        MOE_PMMA1((TICK_), ks_);                                                                     \
+      } else if (FMV == 1) {                                                                         \
+        if ((ks_ >> 1) == (TICK_)) MOE_PMMA1(0, ks_);                                                \
+      }                                                                                              \
+    }                                                                                                \
     __builtin_amdgcn_s_setprio(0);                                                                   \
   } while (0)
 // One K step of one wave.  FMV of the wave's A fragments are valid: the others are neither read
@@ -760,7 +776,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     __builtin_amdgcn_s_waitcnt(0xC07F);  /* lgkmcnt(0): fragments are in */                          \
     MOE_PBARRIER();                                                                                  \
     /* C1 */                                                                                         \
-    if (FMV > 0) MOE_PMMA(0, (FMV < 2 ? FMV : 2));                                                   \
+    if (FMV > 0) MOE_PMMA(FMV, 0);                                                                   \
     MOE_PBARRIER();                                                                                  \
     /* M2 */                                                                                         \
     if (FMV > 2) MOE_PREAD_A(2, FMV);                                                                \
@@ -769,7 +785,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     __builtin_amdgcn_s_waitcnt(0xC07F);                                                              \
     MOE_PBARRIER();                                                                                  \
     /* C2 */                                                                                         \
-    if (FMV > 2) MOE_PMMA(2, FMV);                                                                   \
+    if (FMV > 0) MOE_PMMA(FMV, 1);                                                                   \
     if (!grp) { if (iss2_) MOE_PVMCNT(NL); else MOE_PVMCNT(0); }     /* all of stage H+1 */          \
     MOE_PBARRIER();                                                                                  \
   } while (0)
@@ -868,6 +884,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 #undef MOE_PP_LOOP
 #undef MOE_PP_STEP
 #undef MOE_PMMA
+#undef MOE_PMMA1
 #undef MOE_PREAD_A
 #undef MOE_PBARRIER
 #undef MOE_PVMCNT
