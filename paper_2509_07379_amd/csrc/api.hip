@@ -791,7 +791,13 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
 }
 
 int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 3 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 4 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode == 4) {
+    if (variant != 0 && variant != 1 && variant != 2 && variant != 4)
+      return fail(MOE_E_ARG, "rows per wave of the mat-vec kernels: 0 (by shape), 1, 2 or 4");
+    set_gemv_rows(variant);
+    return MOE_OK;
+  }
   if (mode == 3) {
     if (variant > 8) return fail(MOE_E_ARG, "at most 8 K slices");
     g_splitk_override = variant;

@@ -59,18 +59,15 @@ __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg
   }
 }
 
-// Weight rows per wave: 4 while few tokens share a pass, 2 when up to 8 do (accumulators are
-// rows x tokens x {gate, up}: the kernel has to keep at least two waves per SIMD).
-template <int NTMAX>
-struct GvRows { static constexpr int value = NTMAX <= 2 ? 4 : 2; };
-
-template <int MODE, int NTMAX>
+// GV_R weight rows per wave.  Measured on MI355X: the more, smaller waves stream the weights, the
+// closer the kernel gets to the HBM rate (one row per wave for rows of 4 KB and more, two for
+// shorter rows); blocks that walk over several row groups were slower in every shape.
+template <int MODE, int NTMAX, int GV_R>
 __global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
                                                                      int has_extra, int kseg, int ntcap) {
   // the last blockIdx.y of a launch with has_extra works on the second problem (the always-on
   // shared experts), so that one launch streams both weight sets
   const GemmArgs &args = (has_extra && blockIdx.y == gridDim.y - 1) ? extra : routed;
-  constexpr int GV_R = GvRows<NTMAX>::value;
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -149,6 +146,9 @@ __global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs
 
 }  // namespace
 
+static int g_gemv_rows = 0;   // tuning hook: rows per wave (0 = by shape)
+void set_gemv_rows(int rows) { g_gemv_rows = rows; }
+
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra) {
   if (n_groups_in_mask <= 0 || max_rows_per_group <= 0) {
@@ -165,13 +165,22 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
   if (kseg >= max_k) kseg = max_k;
   const size_t smem = (size_t)ntcap * kseg * 2;
-  const int rows_per_block = GV_WAVES * (ntcap <= 2 ? 4 : 2);
+  int rows_per_wave = max_k >= 2048 ? 1 : 2;
+  if (g_gemv_rows > 0) rows_per_wave = g_gemv_rows;
+  if (ntcap > 2 && rows_per_wave > 2) rows_per_wave = 2;   // accumulators: rows x tokens x {gate, up}
+  const int rows_per_block = GV_WAVES * rows_per_wave;
   dim3 grid((max_n + rows_per_block - 1) / rows_per_block, n_groups_in_mask + (extra ? 1 : 0));
   const int has_extra = extra ? 1 : 0;
   const GemmArgs &extra_args = extra ? *extra : args;
 #define MOE_GEMV_LAUNCH(MODE, NTMAX)                                                          \
   do {                                                                                        \
-    auto kern = grouped_gemv_kernel<MODE, NTMAX>;                                             \
+    if (rows_per_wave == 4) MOE_GEMV_LAUNCH_R(MODE, NTMAX, (NTMAX <= 2 ? 4 : 2));             \
+    else if (rows_per_wave >= 2) MOE_GEMV_LAUNCH_R(MODE, NTMAX, 2);                           \
+    else MOE_GEMV_LAUNCH_R(MODE, NTMAX, 1);                                                   \
+  } while (0)
+#define MOE_GEMV_LAUNCH_R(MODE, NTMAX, R)                                                     \
+  do {                                                                                        \
+    auto kern = grouped_gemv_kernel<MODE, NTMAX, R>;                                          \
     static bool attr_set = false;                                                             \
     if (!attr_set) {                                                                          \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                \
@@ -193,6 +202,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     else MOE_GEMV_LAUNCH(GEMM_PLAIN_F32, 8);
   }
 #undef MOE_GEMV_LAUNCH
+#undef MOE_GEMV_LAUNCH_R
   return hipGetLastError();
 }
 

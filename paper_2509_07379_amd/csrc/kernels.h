@@ -66,6 +66,8 @@ void set_gemm_variant(int mode, int variant);
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra = nullptr);
 
+void set_gemv_rows(int rows);   // tuning hook: weight rows per wave (0 = choose by shape)
+
 // ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----
 hipError_t launch_combine(const float *Y, int y_planes, long long y_plane_stride, const float *w,
                           const int32_t *inv_perm, const float *Yshared, int ys_planes,
