@@ -285,6 +285,8 @@ def main():
             "h2d_GBps": off["bytes_per_layer"] / (t_c * 1e-3) / 1e9,
             "h2d_frac_of_pcie5_x16": off["bytes_per_layer"] / (t_c * 1e-3) / 1e9 / PEAK_PCIE_GBS,
             "overlap": (t_c + t_k - t_p) / min(t_c, t_k), "exposed_copy_frac": (t_p - t_k) / t_c,
+            # share of the pipelined layer during which the host link moves expert bytes at its measured rate
+            "link_busy_frac": t_c / t_p,
         }
         log(f"[bench] offloaded: {line['offloaded']}")
 
