@@ -79,6 +79,44 @@ def prefill_resident(args, torch, B, H, S, w, compute, copy):
                 routing=routing, compute=compute, copy=copy)
 
 
+def prefill_large_batch(args, torch, B, H, S, w, res, rep):
+    """The same layer on rep x the tokens (the batch of rep sequences prefilled together): more row
+    tiles per expert, so the GEMMs run at the rate the kernel reaches when tiles are plentiful."""
+    from dataclasses import replace
+    wl = replace(w, T=w.T * rep)
+    ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, 1, wl.E, wl.I_shared)
+    lay = H.DeviceLayer(ctx, wl, 0, res["pool"], list(range(wl.E)))
+    buf = H.Buffers(ctx, wl.T)
+    x = res["x"].repeat(rep, 1).contiguous()
+    compute, copy = res["compute"], res["copy"]
+
+    def step():
+        ctx.moe_prefill_layer(0, x, wl.T, buf.y, buf.ws, compute, copy, res["bias"], 0)
+
+    n = 4
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    ctx.moe_set_profiling(True)
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    times = ctx.moe_get_kernel_times()
+    ctx.close()
+    g1 = times["gemm1"][0] / times["gemm1"][1]
+    g2 = times["gemm2"][0] / times["gemm2"][1]
+    rows = wl.T * wl.k
+    return {"workload": f"{w.name} shape with T={wl.T}", "ms_per_layer": ms, "tokens_per_s": wl.T / (ms * 1e-3),
+            "gemm1_TFLOPs": 4.0 * rows * wl.d * wl.I / (g1 * 1e-3) / 1e12,
+            "gemm1_frac_of_mfma_peak": 4.0 * rows * wl.d * wl.I / (g1 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "gemm2_TFLOPs": 2.0 * rows * wl.d * wl.I / (g2 * 1e-3) / 1e12}
+
+
 def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6):
     """Offloaded regime: S = w.S slots, experts fetched from pinned memory on the copy stream; a
     stand-in attention block (4 bf16 GEMMs T x d x d) runs on the compute stream while the first
@@ -215,6 +253,8 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=1536, help="tokens of the workload the CPU oracle computes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a reference for hardware byte counters)")
+    ap.add_argument("--large-batch", type=int, default=16,
+                    help="also time the layer on this many times the workload's tokens (0 or 1: skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offloaded", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
@@ -273,6 +313,10 @@ def main():
         "gemm2": {"achieved": tf2, "unit": "TFLOP/s", "frac": tf2 / PEAK_BF16_TFLOPS},
         "mfma_util_layer": (flops1 + flops2) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
     }
+
+    if args.large_batch > 1:
+        line["large_batch"] = prefill_large_batch(args, torch, B, H, S, w, res, args.large_batch)
+        log(f"[bench] large batch: {line['large_batch']}")
 
     if not args.no_offloaded and w.S and w.S < w.E:
         off = prefill_offloaded(args, torch, B, H, S, w, res["pool"], res["x"], compute, copy)

@@ -129,9 +129,17 @@ __device__ __forceinline__ bool decode_logical_tile(const GemmArgs &args, int l,
       l -= tiles;
     }
   }
+  // Row tiles are numbered in panels of 8: inside a panel the row tile runs fastest, then the
+  // column tile.  The 32 blocks of an XCD that work side by side then cover 8 row tiles x 4 column
+  // tiles, and their L2 fetches each operand tile once for 4 (A) or 8 (B) of them; a group of at
+  // most 8 row tiles is one panel (equalising the panels' heights measured no better).
+  constexpr int PANEL = 8;
   const int mt = (cnt + BM - 1) / BM;
-  const int m_idx = l % mt;
-  const int rest = l / mt;
+  const int panel = l / (PANEL * per_m);
+  const int q = l - panel * (PANEL * per_m);
+  const int pm = min(PANEL, mt - panel * PANEL);
+  const int m_idx = panel * PANEL + q % pm;
+  const int rest = q / pm;
   t.ks = rest % args.splitk;
   const int n_idx = rest / args.splitk;
   int rpt = (((cnt + mt - 1) / mt) + 31) & ~31;   // balanced tile height
@@ -646,7 +654,9 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   // swizzle maps there.  Group 0 loads the lower A rows and the first half of B, group 1 the rest.
   // Sources are 32-bit byte offsets into two buffer resources (A, and the blob from its gate/down
   // rows on), so a load needs one VGPR and the K advance is a scalar offset.
-  const __amdgpu_buffer_rsrc_t a_rsrc =
+  // Gathered rows (perm) are addressed from the start of A; rows in place from the tile's first row,
+  // so that only a gathered source has to fit 31 bits of byte offset.
+  __amdgpu_buffer_rsrc_t a_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(args.A), 0, 0x7FFFFFFF, 0x00020000);
 #define MOE_PGROUP(i_) (((i_) / NL) * 32 + grp * 16 + ((i_) % NL) * 4 + (wave & 3))
 
@@ -658,7 +668,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     const int row_ = MOE_PGROUP(i_) * 8 + (lane_s >> 3);                                             \
     const int rr_ = row_ < (tt_).rows_valid ? row_ : 0;                                              \
     const int p_ = (tt_).row0 + (tt_).tile_row0 + rr_;                                               \
-    (out_)[i_] = args.perm ? args.perm[p_] : p_;                                                     \
+    (out_)[i_] = args.perm ? args.perm[p_] : rr_;                                                    \
   }
 #define MOE_PSRC(tt_, prow_)                                                                         \
   do {                                                                                               \
@@ -668,6 +678,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
           args.perm ? (long long)((prow_)[i_] / args.k_top) : (long long)(prow_)[i_];                \
       src[i_] = (uint32_t)(srow_ * args.lda * 2 + kc16_);                                            \
     }                                                                                                \
+    if (!args.perm)                                                                                  \
+      a_rsrc = __builtin_amdgcn_make_buffer_rsrc(                                                    \
+          const_cast<uint16_t *>(args.A + (long long)((tt_).row0 + (tt_).tile_row0) * args.lda), 0,  \
+          0x7FFFFFFF, 0x00020000);                                                                   \
     /* B rows are n0 + 8 g + l/8: one per-lane offset, the row group's part is scalar */             \
     src[NL] = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16_);                                      \
     _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
@@ -1122,8 +1136,9 @@ template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.K % BK != 0) return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
   int v = g_variant[MODE];
-  // the ping-pong kernel addresses A and the blob with 31-bit byte offsets
-  const bool pp_ok = (long long)max_rows * args.lda * 2 < 0x7FFFFFFFll &&
+  // the ping-pong kernel addresses a gathered A (or the 256 rows of a tile of an A used in place)
+  // and the blob with 31-bit byte offsets
+  const bool pp_ok = (long long)(args.perm ? max_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
                      (args.b1_off - args.b0_off) + (long long)args.N * args.ldb * 2 < 0x7FFFFFFFll &&
                      args.b1_off >= args.b0_off && args.N >= (MODE == GEMM_SWIGLU ? 128 : 256);
   if (v == 0) {

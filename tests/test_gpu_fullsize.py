@@ -78,6 +78,18 @@ def test_c2_mixtral_prefill_two_slots_matches_resident(gpu, oracle):
     assert off["stats"]["bytes_h2d"] == w.E * w.blob_bytes  # every expert fetched exactly once
 
 
+def test_c2_shape_large_batch_rows_beyond_2gib(gpu, oracle):
+    """A prefill batch of 20 sequences: the sorted intermediate rows H span more than 2 GiB, so the
+    down projection's tiles sit past the reach of a 31-bit byte offset from the start of H."""
+    w = replace(S.WORKLOADS["c2_mixtral_prefill"], name="c2_shape_T40960", T=40960)
+    assert w.T * w.k * w.I * 2 > 2 ** 31
+    r = prefill_case(gpu, oracle, w, w.E, 16)
+    assert r["routing"]["offsets"][-1] == w.T * w.k
+    # sampled tokens include rows of the last experts, which lie in the upper part of H
+    last_rows = r["routing"]["inv_perm"].reshape(w.T, w.k)[sample_tokens(w.T, 16)].max()
+    assert int(last_rows) * w.I * 2 > 2 ** 31
+
+
 def test_c4_deepseek_prefill_layer(gpu, oracle):
     """64 routed experts top-6 with Zipf-skewed popularity + shared experts, 16 slots."""
     from oracle.cache_sim import CacheSim

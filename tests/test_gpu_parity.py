@@ -64,7 +64,12 @@ def run_layer(gpu, w, T, x_np, S_slots, initial, decode=False, bias=None, prefet
 
 
 # ---------------------------------------------------------------- the MFMA tile itself
-@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 136, 192), (8, 8, 8), (513, 264, 1096)])
+# The last five shapes take the persistent 256 x 256 kernel: a single K step, two K steps, a last
+# column tile that overlaps its neighbour, row tiles with 1..4 fragments per wave, and more tiles
+# than blocks (so blocks walk over several tiles).
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 136, 192), (8, 8, 8), (513, 264, 1096),
+                                   (300, 256, 64), (257, 511, 128), (1000, 300, 512), (97, 2048, 192),
+                                   (4136, 4360, 128)])
 def test_dense_gemm_matches_matmul(gpu, M, N, K):
     a = S.normal_bf16((M, K), 1, 100 + M, 1.0)
     b = S.normal_bf16((N, K), 1, 200 + N, 1.0)
@@ -103,7 +108,9 @@ def test_c1_decode_kernels_same_layer(gpu, oracle):
 
 # ---------------------------------------------------------------- ragged shapes, biases, shared experts
 @pytest.mark.parametrize("d,I,E,k,T,Ish", [(256, 384, 60, 4, 333, 0), (512, 128, 64, 6, 777, 256),
-                                           (128, 64, 8, 2, 1, 0), (256, 192, 5, 5, 37, 64)])
+                                           (128, 64, 8, 2, 1, 0), (256, 192, 5, 5, 37, 64),
+                                           # large groups of unequal height: the persistent GEMM's ragged tiles
+                                           (512, 640, 4, 2, 1500, 384), (256, 320, 8, 2, 2900, 0)])
 @pytest.mark.parametrize("decode", [False, True])
 def test_ragged_shapes(gpu, oracle, d, I, E, k, T, Ish, decode):
     if decode and T > 64:
