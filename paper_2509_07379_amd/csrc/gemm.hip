@@ -31,6 +31,10 @@
 #ifndef MOE_GEMM_PROBE
 #define MOE_GEMM_PROBE(point_)
 #endif
+#ifndef MOE_GEMM_TICK   // before (0) and after (1) every barrier of the ping-pong kernel
+#define MOE_GEMM_TICK(after_)
+#define MOE_GEMM_TICK_DECL
+#endif
 
 namespace moe {
 
@@ -224,19 +228,33 @@ __device__ __forceinline__ void store_tile(const GemmArgs &args, const TileInfo 
 // operand): lane holds output row (lane % 32) and the columns 8*(r/4) + 4*(lane/32) + r%4 of the
 // fragment, i.e. four groups of four consecutive columns, so a fragment leaves in four stores of
 // 8 (bf16) or 16 (fp32) bytes per lane that share one address and differ in the immediate offset.
+//
+// With a wave-private 4 KB LDS buffer (xp) a full fragment is first turned round in LDS: it is written
+// as 32 rows of 64 (bf16) or 128 (fp32) bytes and read back so that 4 or 8 neighbouring lanes hold one
+// whole row segment.  A store instruction then covers 16 or 8 rows with contiguous 64 / 128 bytes each
+// instead of 32 rows with 16 / 32 bytes each; the memory pipeline takes about one cycle per cache
+// line an instruction touches, and the epilogue is bound by exactly that.  16-byte pieces of a row are
+// XOR-swizzled against the row number (at most 2-way bank conflicts on the 8-byte writes).
 template <int MODE, int FM, int FN, int WARPS_M, int WARPS_N>
 __device__ __forceinline__ void store_tile_cols(const GemmArgs &args, const TileInfo &t, int wm, int wn, int lane,
-                                                int fm_valid, floatx16 (&acc)[FM][FN], int i_begin, int i_end) {
+                                                int fm_valid, floatx16 (&acc)[FM][FN], int i_begin, int i_end,
+                                                unsigned char *xp = nullptr) {
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
   constexpr int ESIZE = (MODE == GEMM_PLAIN_F32) ? 4 : 2;
+  constexpr int PPR = 2 * ESIZE;          // 16-byte pieces per fragment row: 4 (bf16) or 8 (fp32)
+  constexpr int RPP = 64 / PPR;           // rows per store instruction: 16 or 8
   lane = opaque(lane);   // the per-lane values below are re-derived per call instead of being kept alive
   const int lrow = lane & 31, lk = lane >> 5;
   const uint32_t lane_off = (uint32_t)(lrow * args.ldo + 4 * lk) * ESIZE;   // bytes
+  // turned-round layout: this lane's row and piece of a pass, as LDS and as global byte offsets
+  const int xrow = lane / PPR, xq = lane % PPR;
+  const uint32_t xlane_off = (uint32_t)(xrow * args.ldo) * ESIZE + xq * 16;
   char *plane = reinterpret_cast<char *>(args.out) +
                 (MODE == GEMM_PLAIN_F32 ? (long long)t.ks * args.out_split_stride * ESIZE : 0ll);
   const long long out_row_base = (long long)t.row0 + t.tile_row0;
   const bool aligned = (args.ldo * ESIZE) % 16 == 0 && (reinterpret_cast<uintptr_t>(args.out) & 15) == 0 &&
                        (MODE != GEMM_PLAIN_F32 || (args.out_split_stride * ESIZE) % 16 == 0);
+  const long long row_bytes = (long long)args.ldo * ESIZE;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     if (i < i_begin || i >= i_end || i >= fm_valid) continue;
@@ -251,7 +269,29 @@ __device__ __forceinline__ void store_tile_cols(const GemmArgs &args, const Tile
       for (int r = 0; r < 16; ++r)
         v[r] = (MODE == GEMM_SWIGLU) ? silu(acc[i][j][r]) * acc[i][j + FNH][r] : acc[i][j][r];
       const bool full = frow + 32 <= t.rows_valid && col0 + 32 <= args.N && aligned;
-      if (full) {
+      if (full && xp) {
+        // row pitch 16 * PPR bytes; piece index XORed with (row >> 1) & 7 (fp32: 8 pieces, two rows per
+        // 64 banks) or (row >> 2) & 3 (bf16: 4 pieces, four rows per 64 banks)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          if (MODE == GEMM_PLAIN_F32) {
+            f32x4 o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+            *reinterpret_cast<f32x4 *>(xp + lrow * 128 + (((2 * g + lk) ^ ((lrow >> 1) & 7)) << 4)) = o;
+          } else {
+            u32x2 o;
+            o.x = (uint32_t)cvt_bf16(v[4 * g]) | ((uint32_t)cvt_bf16(v[4 * g + 1]) << 16);
+            o.y = (uint32_t)cvt_bf16(v[4 * g + 2]) | ((uint32_t)cvt_bf16(v[4 * g + 3]) << 16);
+            *reinterpret_cast<u32x2 *>(xp + lrow * 64 + ((g ^ ((lrow >> 2) & 3)) << 4) + lk * 8) = o;
+          }
+        }
+#pragma unroll
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+          const int row = pass * RPP + xrow;
+          const int sw = (MODE == GEMM_PLAIN_F32) ? ((row >> 1) & 7) : ((row >> 2) & 3);
+          const f32x4 o = *reinterpret_cast<const f32x4 *>(xp + row * (16 * PPR) + ((xq ^ sw) << 4));
+          *reinterpret_cast<f32x4 *>(sp + (long long)pass * RPP * row_bytes + xlane_off) = o;
+        }
+      } else if (full) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           char *ptr = sp + lane_off + g * 8 * ESIZE;
@@ -630,6 +670,8 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  MOE_GEMM_TICK_DECL
+  unsigned char *xpose = smem + 2 * STAGE + wave * 4096;   // this wave's epilogue buffer
   const int grp = wave >> 2;          // the two waves of a SIMD are in different groups
   const int wm = grp, wn = wave & 3;
 
@@ -733,7 +775,9 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 #define MOE_PBARRIER()                                                                               \
   do {                                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                               \
+    MOE_GEMM_TICK(0);                                                                                \
     __builtin_amdgcn_s_barrier();                                                                    \
+    MOE_GEMM_TICK(1);                                                                                \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define MOE_PREAD_A(I0_, I1_)                                                                        \
@@ -882,13 +926,13 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 #pragma unroll
       for (int i = 0; i < NL; ++i) prow_n[i] = 0;
     }
-    store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, 0, FM / 2);
+    store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, 0, FM / 2, xpose);
     if (has_next) {
       MOE_PSRC(tn, prow_n);
       MOE_PTILE_SETUP(tn);
       MOE_PPROLOGUE();
     }
-    store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, FM / 2, FM);
+    store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, FM / 2, FM, xpose);
     MOE_GEMM_PROBE(3);
     if (!has_next) break;
     t = tn;
@@ -1087,7 +1131,8 @@ template <int MODE>
 hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BM = 256, BN = 256;
   constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
-  constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES;
+  // two stages of A and B tiles + 4 KB per wave for the epilogue's transposition
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES + 8 * 4096;
   auto kern = grouped_gemm_pp_kernel<MODE>;
   static bool attr_set = false;
   if (!attr_set) {
