@@ -123,6 +123,10 @@ struct moe_ctx {
   std::vector<Layer> layers;
   int32_t *pinned_counts = nullptr;   // [E] mailbox the dispatch kernel fills
   hipEvent_t routed = nullptr;
+  // prefill with shared experts: they run on a stream of the library's own, beside the gate, the
+  // grouping and the routed experts (fork at the start of the call, join before the weighted sum)
+  hipStream_t side = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
   float *dev_scores = nullptr;        // [64] scratch for predictor_score without dev_scores
   bool profiling = false;
   std::vector<TimedLaunch> timed;
@@ -368,6 +372,15 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // leaner mat-vec variant, and the shared experts' launch covers the host's wait.
   const bool enqueue_blind = all_resident && (!decode || T == 1);
 
+  // A prefill batch of some size: the shared experts get the library's side stream.  Their two
+  // launches need nothing but x, so they fill the compute units that the gate and the grouping leave
+  // idle, and their last, partly filled round of tiles overlaps the routed experts' first.
+  const bool shared_on_side = c.I_shared && !decode && T >= 256;
+  if (shared_on_side) {
+    HIP_TRY(hipEventRecord(ctx->fork, cs));   // after everything the caller queued before (x, the last call)
+    HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
+  }
+
   // ---- gate, Top-k, grouping
   {
     Timer t(ctx, cs, MOE_K_ROUTER);
@@ -395,7 +408,11 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   if (c.I_shared) {
     s1 = shared_args(ctx, L, ws, W, T, false, dev_x);
     s2 = shared_args(ctx, L, ws, W, T, true, dev_x);
-    if (!shared_in_routed_launch) {
+    if (shared_on_side) {
+      rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, ctx->side);
+      if (rc) return rc;
+      HIP_TRY(hipEventRecord(ctx->join, ctx->side));
+    } else if (!shared_in_routed_launch) {
       rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, cs);
       if (rc) return rc;
     }
@@ -514,6 +531,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   }
 
   // ---- weighted sum per token (+ shared experts)
+  if (shared_on_side) HIP_TRY(hipStreamWaitEvent(cs, ctx->join, 0));
   {
     Timer t(ctx, cs, MOE_K_COMBINE);
     HIP_TRY(launch_combine(reinterpret_cast<const float *>(ws + W.Y), W.splitk, (long long)n * c.d,
@@ -549,6 +567,11 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), kMaxExperts * sizeof(int32_t), 0));
   memset(ctx->pinned_counts, 0, kMaxExperts * sizeof(int32_t));
   HIP_TRY(hipEventCreateWithFlags(&ctx->routed, hipEventDisableTiming));
+  if (cfg->I_shared) {
+    HIP_TRY(hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming));
+  }
   HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ctx->dev_scores), kMaxExperts * sizeof(float)));
   *out = ctx;
   return MOE_OK;
@@ -569,6 +592,12 @@ int moe_destroy(moe_ctx *ctx) {
   }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
   if (ctx->routed) (void)hipEventDestroy(ctx->routed);
+  if (ctx->fork) (void)hipEventDestroy(ctx->fork);
+  if (ctx->join) (void)hipEventDestroy(ctx->join);
+  if (ctx->side) {
+    (void)hipStreamSynchronize(ctx->side);
+    (void)hipStreamDestroy(ctx->side);
+  }
   if (ctx->pinned_counts) (void)hipHostFree(ctx->pinned_counts);
   if (ctx->dev_scores) (void)hipFree(ctx->dev_scores);
   delete ctx;
