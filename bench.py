@@ -32,7 +32,7 @@ PEAK_PCIE_GBS = 64.0        # PCIe Gen5 x16 per direction
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 256 MiB device copy
 # (x2.000 and x1.000); the summary with the commands is profiles/prefill_c2_mixtral_gemm_counters.txt.
 # Algorithmic bytes of that launch: 1879 MB of weights + 16.8 MB of activations read, 117.4 MB written.
-MEASURED_TRAFFIC_BYTES = {"c2_mixtral_prefill": 2351.7e6 + 117.5e6}
+MEASURED_TRAFFIC_BYTES = {"c2_mixtral_prefill": 2353.4e6 + 117.4e6}
 
 
 def log(*a):
