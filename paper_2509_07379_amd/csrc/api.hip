@@ -375,7 +375,10 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // A prefill batch of some size: the shared experts get the library's side stream.  Their two
   // launches need nothing but x, so they fill the compute units that the gate and the grouping leave
   // idle, and their last, partly filled round of tiles overlaps the routed experts' first.
-  const bool shared_on_side = c.I_shared && !decode && T >= 256;
+  // A decode batch (several tokens, so the host looks at the gate's result before it launches the
+  // routed experts) does the same: the shared experts' mat-vecs, arithmetic-bound at 8 tokens, then
+  // run beside the bandwidth-bound routed ones instead of in front of them.
+  const bool shared_on_side = c.I_shared && (decode ? !(all_resident && T == 1) : T >= 256);
   if (shared_on_side) {
     HIP_TRY(hipEventRecord(ctx->fork, cs));   // after everything the caller queued before (x, the last call)
     HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
