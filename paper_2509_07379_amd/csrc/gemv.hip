@@ -22,15 +22,19 @@ constexpr int GV_MAXTOK = 8;   // tokens per pass over the weights
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Eight bf16 products added to an fp32 sum with four two-element dot instructions
+// (v_dot2c_f32_bf16): no unpacking of the operands, a third of the vector instructions of an
+// fma chain.  With eight tokens per pass the fma chain, not HBM, bounded the kernel.
+__device__ __forceinline__ float dot2(uint32_t x, uint32_t w, float acc) {   // by value: plain scalars
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x), __builtin_bit_cast(bf16x2, w), acc, false);
+}
 __device__ __forceinline__ float dot8(const u32x4 &xv, const u32x4 &wv, float acc) {
-  acc = fmaf(bf16_lo(xv.x), bf16_lo(wv.x), acc);
-  acc = fmaf(bf16_hi(xv.x), bf16_hi(wv.x), acc);
-  acc = fmaf(bf16_lo(xv.y), bf16_lo(wv.y), acc);
-  acc = fmaf(bf16_hi(xv.y), bf16_hi(wv.y), acc);
-  acc = fmaf(bf16_lo(xv.z), bf16_lo(wv.z), acc);
-  acc = fmaf(bf16_hi(xv.z), bf16_hi(wv.z), acc);
-  acc = fmaf(bf16_lo(xv.w), bf16_lo(wv.w), acc);
-  acc = fmaf(bf16_hi(xv.w), bf16_hi(wv.w), acc);
+  acc = dot2(xv.x, wv.x, acc);
+  acc = dot2(xv.y, wv.y, acc);
+  acc = dot2(xv.z, wv.z, acc);
+  acc = dot2(xv.w, wv.w, acc);
   return acc;
 }
 
