@@ -12,6 +12,8 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <atomic>
+#include <chrono>
 #include <vector>
 
 #include "../../include/moe_offload.h"
@@ -121,7 +123,8 @@ struct moe_ctx {
   int device = 0;
   size_t blob_bytes = 0;
   std::vector<Layer> layers;
-  int32_t *pinned_counts = nullptr;   // [E] mailbox the dispatch kernel fills
+  int32_t *pinned_counts = nullptr;   // mailbox the dispatch kernel fills: [kMaxExperts] counts, then the call's number
+  int32_t mailbox_seq = 0;
   hipEvent_t routed = nullptr;
   // prefill with shared experts: they run on a stream of the library's own, beside the gate, the
   // grouping and the routed experts (fork at the start of the call, join before the weighted sum)
@@ -316,6 +319,24 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
 }
 
 // Both expert matmuls of the groups in `mask`, on the compute stream.
+// The host needs the gate's per-expert counts.  Waking up on the event costs 10-20 us; the dispatch
+// kernel writes the call's number behind the counts in pinned, host-coherent memory, so the host
+// first polls that word for a while (the kernel is a few microseconds away) and only then blocks.
+hipError_t wait_for_counts(moe_ctx *ctx) {
+  volatile const int32_t *flag = ctx->pinned_counts + kMaxExperts;
+  const auto t0 = std::chrono::steady_clock::now();
+  for (int spin = 0;; ++spin) {
+    if (*flag == ctx->mailbox_seq) {
+      std::atomic_thread_fence(std::memory_order_acquire);
+      return hipSuccess;
+    }
+    if ((spin & 255) == 255 &&
+        std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300))
+      break;
+  }
+  return hipEventSynchronize(ctx->routed);
+}
+
 int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
                 int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream,
                 const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr,
@@ -400,7 +421,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                             reinterpret_cast<int32_t *>(ws + W.counts),
                             reinterpret_cast<int32_t *>(ws + W.offsets),
                             reinterpret_cast<int32_t *>(ws + W.perm),
-                            reinterpret_cast<int32_t *>(ws + W.inv_perm), ctx->pinned_counts, cs));
+                            reinterpret_cast<int32_t *>(ws + W.inv_perm), ctx->pinned_counts,
+                            ++ctx->mailbox_seq, cs));
   }
   HIP_TRY(hipEventRecord(ctx->routed, cs));
 
@@ -438,7 +460,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     HIP_TRY(hipEventRecord(L.group_done, cs));
     for (int s = 0; s < S; ++s) L.use_kind[s] = 2;
     // counters need the counts: read them once the routing kernels are done
-    HIP_TRY(hipEventSynchronize(ctx->routed));
+    HIP_TRY(wait_for_counts(ctx));
     for (int e = 0; e < E; ++e)
       if (ctx->pinned_counts[e] > 0) {
         int s = L.expert_slot[e];
@@ -451,7 +473,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       }
   } else {
     // "Synchronisation point 1": the gate's choice is compared with the cache.
-    HIP_TRY(hipEventSynchronize(ctx->routed));
+    HIP_TRY(wait_for_counts(ctx));
     int counts[kMaxExperts];
     unsigned long long hit_mask = 0;
     int n_hits = 0, hit_rows = 0, hit_max = 0;
@@ -567,8 +589,8 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   ctx->blob_bytes = (size_t)6 * cfg->d * cfg->I;
   HIP_TRY(hipGetDevice(&ctx->device));
   ctx->layers.resize(cfg->n_layers);
-  HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), kMaxExperts * sizeof(int32_t), 0));
-  memset(ctx->pinned_counts, 0, kMaxExperts * sizeof(int32_t));
+  HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), (kMaxExperts + 1) * sizeof(int32_t), 0));
+  memset(ctx->pinned_counts, 0, (kMaxExperts + 1) * sizeof(int32_t));
   HIP_TRY(hipEventCreateWithFlags(&ctx->routed, hipEventDisableTiming));
   if (cfg->I_shared) {
     HIP_TRY(hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));

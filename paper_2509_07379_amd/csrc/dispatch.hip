@@ -30,7 +30,7 @@ __global__ __launch_bounds__(64) void dispatch_scan_kernel(const int32_t *__rest
                                                            int32_t *__restrict__ blk_base,
                                                            int32_t *__restrict__ counts,
                                                            int32_t *__restrict__ offsets,
-                                                           int32_t *__restrict__ host_counts) {
+                                                           int32_t *__restrict__ host_counts, int seq) {
   const int e = threadIdx.x;
   int run = 0;
   if (e < E) {
@@ -53,6 +53,11 @@ __global__ __launch_bounds__(64) void dispatch_scan_kernel(const int32_t *__rest
     if (host_counts) host_counts[e] = run;
   }
   if (e == E - 1) offsets[E] = incl;
+  // the host polls this word: it may trust the counts once it reads the call's sequence number
+  if (host_counts) {
+    __threadfence_system();
+    if (e == 0) host_counts[kMaxExperts] = seq;
+  }
 }
 
 __global__ __launch_bounds__(kDispatchChunk) void dispatch_scatter_kernel(
@@ -93,7 +98,7 @@ constexpr int kSmallDispatch = 2048;
 __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
     const int32_t *__restrict__ ids, int n, int E, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-    int32_t *__restrict__ host_counts) {
+    int32_t *__restrict__ host_counts, int seq) {
   constexpr int kWaves = kDispatchChunk / 64;
   __shared__ int hist[kMaxExperts];
   __shared__ int base[kMaxExperts];       // next free sorted position of each expert
@@ -118,6 +123,10 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
       if (host_counts) host_counts[lane] = run;
     }
     if (lane == E - 1) offsets[E] = incl;
+    if (host_counts) {   // the host polls this word (see dispatch_scan_kernel)
+      __threadfence_system();
+      if (lane == 0) host_counts[kMaxExperts] = seq;
+    }
   }
   for (int c0 = 0; c0 < n; c0 += kDispatchChunk) {
     for (int i = tid; i < kWaves * kMaxExperts; i += kDispatchChunk) (&wave_cnt[0][0])[i] = 0;
@@ -154,17 +163,17 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
 
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, hipStream_t stream) {
+                           int32_t *host_counts, int seq, hipStream_t stream) {
   if (n <= kSmallDispatch) {
     hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kDispatchChunk), 0, stream, ids, n, E, counts, offsets,
-                       perm, inv_perm, host_counts);
+                       perm, inv_perm, host_counts, seq);
     return hipGetLastError();
   }
   const int nblk = (n + kDispatchChunk - 1) / kDispatchChunk;
   hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
                      blk_hist);
   hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(64), 0, stream, blk_hist, nblk, E, blk_base,
-                     counts, offsets, host_counts);
+                     counts, offsets, host_counts, seq);
   hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
                      blk_base, offsets, perm, inv_perm);
   return hipGetLastError();

@@ -23,10 +23,11 @@ hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d,
 
 // ---- dispatch: stable counting sort of the T*k assignments by expert ------------------
 // blk_hist / blk_base: [ceil(n/kDispatchChunk) * E] scratch.  counts [E], offsets [E+1],
-// perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned).
+// perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned,
+// kMaxExperts + 1 words): after the counts the kernel writes seq into word kMaxExperts.
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, hipStream_t stream);
+                           int32_t *host_counts, int seq, hipStream_t stream);
 
 // ---- grouped GEMM on bf16 MFMA --------------------------------------------------------
 struct GemmArgs {
