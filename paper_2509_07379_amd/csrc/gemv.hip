@@ -16,8 +16,6 @@ namespace moe {
 
 namespace {
 
-constexpr int GV_THREADS = 256;
-constexpr int GV_WAVES = GV_THREADS / 64;
 constexpr int GV_MAXTOK = 8;   // tokens per pass over the weights
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -66,9 +64,13 @@ __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg
 // GV_R weight rows per wave.  Measured on MI355X: the more, smaller waves stream the weights, the
 // closer the kernel gets to the HBM rate (one row per wave for rows of 4 KB and more, two for
 // shorter rows); blocks that walk over several row groups were slower in every shape.
-template <int MODE, int NTMAX, int GV_R>
-__global__ __launch_bounds__(GV_THREADS) void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
-                                                                     int has_extra, int kseg, int ntcap) {
+// NTHR threads per block: 256, or 1024 when many tokens share a pass (every block stages the token
+// vectors of a K segment in LDS first, which for 8 tokens is as many bytes as a 4-wave block's share
+// of the weights; 16 waves share one copy).
+template <int MODE, int NTMAX, int GV_R, int NTHR>
+__global__ __launch_bounds__(NTHR) void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
+                                                             int has_extra, int kseg, int ntcap) {
+  constexpr int GV_THREADS = NTHR, GV_WAVES = NTHR / 64;
   // the last blockIdx.y of a launch with has_extra works on the second problem (the always-on
   // shared experts), so that one launch streams both weight sets
   const GemmArgs &args = (has_extra && blockIdx.y == gridDim.y - 1) ? extra : routed;
@@ -172,7 +174,8 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   int rows_per_wave = max_k >= 2048 ? 1 : 2;
   if (g_gemv_rows > 0) rows_per_wave = g_gemv_rows;
   if (ntcap > 2 && rows_per_wave > 2) rows_per_wave = 2;   // accumulators: rows x tokens x {gate, up}
-  const int rows_per_block = GV_WAVES * rows_per_wave;
+  const int threads = ntcap > 4 ? 1024 : 256;
+  const int rows_per_block = (threads / 64) * rows_per_wave;
   dim3 grid((max_n + rows_per_block - 1) / rows_per_block, n_groups_in_mask + (extra ? 1 : 0));
   const int has_extra = extra ? 1 : 0;
   const GemmArgs &extra_args = extra ? *extra : args;
@@ -184,7 +187,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   } while (0)
 #define MOE_GEMV_LAUNCH_R(MODE, NTMAX, R)                                                     \
   do {                                                                                        \
-    auto kern = grouped_gemv_kernel<MODE, NTMAX, R>;                                          \
+    auto kern = grouped_gemv_kernel<MODE, NTMAX, R, (NTMAX > 4 ? 1024 : 256)>;                \
     static bool attr_set = false;                                                             \
     if (!attr_set) {                                                                          \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                \
@@ -192,7 +195,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
       if (e != hipSuccess) return e;                                                          \
       attr_set = true;                                                                        \
     }                                                                                         \
-    hipLaunchKernelGGL(kern, grid, dim3(GV_THREADS), smem, stream, args, extra_args, has_extra, kseg, ntcap);        \
+    hipLaunchKernelGGL(kern, grid, dim3(threads), smem, stream, args, extra_args, has_extra, kseg, ntcap); \
   } while (0)
   if (mode == GEMM_SWIGLU) {
     if (ntcap == 1) MOE_GEMV_LAUNCH(GEMM_SWIGLU, 1);
