@@ -183,7 +183,9 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * gate/up GEMM (mode 0), the down GEMM (mode 1) or the dense GEMM (mode 2); mode 3 forces the
  * number of K slices of the down GEMM (0 = heuristic; changes moe_workspace_bytes, so set it
  * before sizing workspaces); mode 4 forces the weight rows per wave of the decode mat-vec
- * kernels (0 = heuristic, 1, 2 or 4).  Process-wide.
+ * kernels (0 = heuristic, 1, 2 or 4); mode 5 sets the largest expert count for which a one-token
+ * decode call with every expert resident is enqueued without the host looking at the gate's
+ * result (default 16).  Process-wide.
  */
 int moe_set_gemm_variant(int mode, int variant);
 

@@ -47,6 +47,7 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // 256 x 256 on 256 CUs) leave most of the last round idle; slicing K makes the tiles finer.
 // The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
 int g_splitk_override = 0;  // tuning hook (moe_set_gemm_variant mode 3); 0 = heuristic
+int g_blind_max_experts = 16;  // tuning hook (mode 5): with more experts than this a one-token decode call waits for the gate and launches only the active experts
 
 int choose_splitk(const moe_config &cfg, int T) {
   if (g_splitk_override > 0) return g_splitk_override;
@@ -389,9 +390,11 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   for (int e = 0; e < E; ++e) all_resident &= L.expert_slot[e] >= 0;
   // Enqueue everything without looking at the gate's result only when that result cannot change the
   // launch: all experts resident and, for the mat-vec path, one token (every active expert then has
-  // exactly one row).  A decode batch takes the other path: the per-expert row counts pick a much
-  // leaner mat-vec variant, and the shared experts' launch covers the host's wait.
-  const bool enqueue_blind = all_resident && (!decode || T == 1);
+  // exactly one row) and few experts (a launch over all of them starts blocks for the idle ones too:
+  // with 60 experts and 4 active that cost 100 us against 76 us for the host's look at the gate).
+  // A decode batch takes the other path: the per-expert row counts pick a much leaner mat-vec
+  // variant, and the shared experts' launch covers the host's wait.
+  const bool enqueue_blind = all_resident && (!decode || (T == 1 && E <= g_blind_max_experts));
 
   // A prefill batch of some size: the shared experts get the library's side stream.  Their two
   // launches need nothing but x, so they fill the compute units that the gate and the grouping leave
@@ -399,7 +402,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // A decode batch (several tokens, so the host looks at the gate's result before it launches the
   // routed experts) does the same: the shared experts' mat-vecs, arithmetic-bound at 8 tokens, then
   // run beside the bandwidth-bound routed ones instead of in front of them.
-  const bool shared_on_side = c.I_shared && (decode ? !(all_resident && T == 1) : T >= 256);
+  const bool shared_on_side = c.I_shared && (decode ? !enqueue_blind : T >= 256);
   if (shared_on_side) {
     HIP_TRY(hipEventRecord(ctx->fork, cs));   // after everything the caller queued before (x, the last call)
     HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
@@ -845,7 +848,11 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
 }
 
 int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 4 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 5 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode == 5) {
+    g_blind_max_experts = variant;
+    return MOE_OK;
+  }
   if (mode == 4) {
     if (variant != 0 && variant != 1 && variant != 2 && variant != 4)
       return fail(MOE_E_ARG, "rows per wave of the mat-vec kernels: 0 (by shape), 1, 2 or 4");

@@ -67,22 +67,33 @@ __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg
 // NTHR threads per block: 256, or 1024 when many tokens share a pass (every block stages the token
 // vectors of a K segment in LDS first, which for 8 tokens is as many bytes as a 4-wave block's share
 // of the weights; 16 waves share one copy).
+// (at least 6 waves per SIMD for the 4-wave blocks: left alone, the register allocator of the
+// multi-token variants wanders between 76 and 100 registers with unrelated edits)
 template <int MODE, int NTMAX, int GV_R, int NTHR>
-__global__ __launch_bounds__(NTHR) void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
-                                                             int has_extra, int kseg, int ntcap) {
+__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(NTHR == 256 ? 6 : 4)))
+void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
+                                                             int has_extra, int kseg, int ntcap, int n_extra_y) {
   constexpr int GV_THREADS = NTHR, GV_WAVES = NTHR / 64;
-  // the last blockIdx.y of a launch with has_extra works on the second problem (the always-on
-  // shared experts), so that one launch streams both weight sets
-  const GemmArgs &args = (has_extra && blockIdx.y == gridDim.y - 1) ? extra : routed;
+  // Grid: x = block of weight rows (as many as the routed problem needs), y = selected group of
+  // the routed problem; with has_extra, the last n_extra_y values of y are further runs of gridDim.x
+  // blocks for the second problem (the always-on shared experts), so that one launch streams both
+  // weight sets and neither pays for the other's row count.
+  // (the test is written against gridDim.y: the form with the count of routed groups costs this
+  // compiler 22 more vector registers and a third of the occupancy)
+  const bool is_extra = has_extra && blockIdx.y + (unsigned)n_extra_y >= gridDim.y;
+  const GemmArgs &args = is_extra ? extra : routed;
+  const unsigned sel = blockIdx.y;                                           // which selected group
+  const unsigned bx = is_extra ? (blockIdx.y + (unsigned)n_extra_y - gridDim.y) * gridDim.x + blockIdx.x : blockIdx.x;
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // group of this block: the blockIdx.y-th expert of the mask
+  // group of this block: the sel-th expert of the mask
   int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
   if (args.offsets) {
     unsigned long long m = args.group_mask;
-    for (unsigned i = 0; i < blockIdx.y; ++i) m &= m - 1;
+    for (unsigned i = 0; i < sel; ++i) m &= m - 1;
+    if (m == 0) return;   // fewer groups in the mask than the launch was sized for
     grp = __ffsll((long long)m) - 1;
     row0 = args.offsets[grp];
     cnt = args.offsets[grp + 1] - row0;
@@ -92,8 +103,8 @@ __global__ __launch_bounds__(NTHR) void grouped_gemv_kernel(const GemmArgs route
   const char *wptr = args.wbase + (long long)args.slot[grp] * args.wstride;
   const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
   const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
-  const int n_first = (blockIdx.x * GV_WAVES + wave) * GV_R;
-  if ((int)blockIdx.x * GV_WAVES * GV_R >= args.N) return;  // grid.x covers the larger of the two problems
+  const int n_first = (bx * GV_WAVES + wave) * GV_R;
+  if ((int)bx * GV_WAVES * GV_R >= args.N) return;
 
   for (int tok0 = 0; tok0 < cnt; tok0 += ntcap) {
     const int ntok = min(ntcap, cnt - tok0);  // ntcap <= NTMAX tokens fit the LDS buffer
@@ -176,7 +187,10 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   if (ntcap > 2 && rows_per_wave > 2) rows_per_wave = 2;   // accumulators: rows x tokens x {gate, up}
   const int threads = ntcap > 4 ? 1024 : 256;
   const int rows_per_block = (threads / 64) * rows_per_wave;
-  dim3 grid((max_n + rows_per_block - 1) / rows_per_block, n_groups_in_mask + (extra ? 1 : 0));
+  const int bpg = (args.N + rows_per_block - 1) / rows_per_block;
+  const int extra_blocks = extra ? (extra->N + rows_per_block - 1) / rows_per_block : 0;
+  const int n_extra_y = (extra_blocks + bpg - 1) / bpg;
+  dim3 grid(bpg, n_groups_in_mask + n_extra_y);
   const int has_extra = extra ? 1 : 0;
   const GemmArgs &extra_args = extra ? *extra : args;
 #define MOE_GEMV_LAUNCH(MODE, NTMAX)                                                          \
@@ -195,7 +209,8 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
       if (e != hipSuccess) return e;                                                          \
       attr_set = true;                                                                        \
     }                                                                                         \
-    hipLaunchKernelGGL(kern, grid, dim3(threads), smem, stream, args, extra_args, has_extra, kseg, ntcap); \
+    hipLaunchKernelGGL(kern, grid, dim3(threads), smem, stream, args, extra_args, has_extra, kseg, ntcap, \
+                       n_extra_y);                                                            \
   } while (0)
   if (mode == GEMM_SWIGLU) {
     if (ntcap == 1) MOE_GEMV_LAUNCH(GEMM_SWIGLU, 1);
