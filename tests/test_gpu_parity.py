@@ -110,7 +110,10 @@ def test_c1_decode_kernels_same_layer(gpu, oracle):
 @pytest.mark.parametrize("d,I,E,k,T,Ish", [(256, 384, 60, 4, 333, 0), (512, 128, 64, 6, 777, 256),
                                            (128, 64, 8, 2, 1, 0), (256, 192, 5, 5, 37, 64),
                                            # large groups of unequal height: the persistent GEMM's ragged tiles
-                                           (512, 640, 4, 2, 1500, 384), (256, 320, 8, 2, 2900, 0)])
+                                           (512, 640, 4, 2, 1500, 384), (256, 320, 8, 2, 2900, 0),
+                                           # one token: many experts (only the active ones are launched) and few
+                                           # (one launch for all, the wider shared expert in further grid rows)
+                                           (256, 384, 60, 4, 1, 256), (256, 192, 8, 2, 1, 320)])
 @pytest.mark.parametrize("decode", [False, True])
 def test_ragged_shapes(gpu, oracle, d, I, E, k, T, Ish, decode):
     if decode and T > 64:
