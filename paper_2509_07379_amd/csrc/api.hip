@@ -437,6 +437,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     s1 = shared_args(ctx, L, ws, W, T, false, dev_x);
     s2 = shared_args(ctx, L, ws, W, T, true, dev_x);
     if (shared_on_side) {
+      // beside the gate and the grouping: their blocks need a little LDS on some compute unit
+      s1.spare_cus = s2.spare_cus = 32;
       rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, ctx->side);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(ctx->join, ctx->side));

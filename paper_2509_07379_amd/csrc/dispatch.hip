@@ -34,10 +34,18 @@ __global__ __launch_bounds__(64) void dispatch_scan_kernel(const int32_t *__rest
   const int e = threadIdx.x;
   int run = 0;
   if (e < E) {
-    for (int b = 0; b < nblk; ++b) {
-      int h = blk_hist[(size_t)b * E + e];
-      blk_base[(size_t)b * E + e] = run;
-      run += h;
+    // 16 independent loads in flight per lane: one load per step made this one-block kernel a chain
+    // of memory latencies (45 us for 96 blocks beside a running GEMM)
+    for (int b0 = 0; b0 < nblk; b0 += 16) {
+      int h[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) h[j] = b0 + j < nblk ? blk_hist[(size_t)(b0 + j) * E + e] : 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (b0 + j < nblk) {
+          blk_base[(size_t)(b0 + j) * E + e] = run;
+          run += h[j];
+        }
     }
   }
   // inclusive scan over the experts (lanes)

@@ -1147,7 +1147,11 @@ hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, h
   if (ub <= 0) return hipSuccess;
   ub = (ub + 7) / 8 * 8;
   if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
-  const long long grid = ub < pp_grid_blocks() ? ub : pp_grid_blocks();
+  // blocks are a multiple of 8 (one per compute unit, spread over the 8 XCDs); a launch that runs
+  // beside other streams' small kernels leaves them some units, whose LDS it would otherwise fill
+  int cap = pp_grid_blocks() - (args.spare_cus > 0 ? (args.spare_cus + 7) / 8 * 8 : 0);
+  if (cap < 8) cap = 8;
+  const long long grid = ub < cap ? ub : cap;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), smem, stream, args);
   return hipGetLastError();
 }

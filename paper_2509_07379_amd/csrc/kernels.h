@@ -50,6 +50,7 @@ struct GemmArgs {
   int ldo;
   int splitk;             // K slices, each written to its own output plane
   long long out_split_stride;  // elements between planes
+  int spare_cus;          // persistent GEMM: compute units to leave to kernels of other streams
 };
 
 enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
