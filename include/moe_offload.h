@@ -179,7 +179,8 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
                         void *stream);
 
 /*
- * Tuning hook: forces MFMA tile variant `variant` (0 = chosen by shape, the default) for the
+ * Tuning and test hook: forces GEMM kernel `variant` (0 = chosen by shape, the default; 1 = 128 x 128
+ * tiles, 6 = 256 x 256 tiles of the single-phase kernel, 12 = the persistent ping-pong kernel) for the
  * gate/up GEMM (mode 0), the down GEMM (mode 1) or the dense GEMM (mode 2); mode 3 forces the
  * number of K slices of the down GEMM (0 = heuristic; changes moe_workspace_bytes, so set it
  * before sizing workspaces); mode 4 forces the weight rows per wave of the decode mat-vec

@@ -866,6 +866,8 @@ int moe_set_gemm_variant(int mode, int variant) {
     g_splitk_override = variant;
     return MOE_OK;
   }
+  if (variant != 0 && variant != 1 && variant != 6 && variant != 12)
+    return fail(MOE_E_ARG, "GEMM variants: 0 (by shape), 1, 6, 12");
   set_gemm_variant(mode, variant);
   return MOE_OK;
 }

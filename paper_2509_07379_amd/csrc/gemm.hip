@@ -479,167 +479,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_dma_kerne
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ring kernel: K steps of 32, four LDS stages, loads three steps ahead.  The barrier of step kt
-// certifies the data of step kt+1, so the first fragments of the next step are requested before
-// the step ends and no MFMA ever waits right behind a barrier.  Needs K % 32 == 0.
-constexpr int RK = 32;               // K elements per ring stage (64 bytes per row)
-constexpr int RROW = RK * 2;
-constexpr int RSTAGES = 4;
-// chunk kc (0..3) of a 64-byte row sits at kc ^ ((row >> 2) & 3): four rows share a 256-byte LDS
-// line, and the 16 rows of one read phase must cover its 16 chunk positions.
-__device__ __forceinline__ int swz32(int row, int kc) { return row * RROW + ((kc ^ ((row >> 2) & 3)) << 4); }
-
-template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_ring_kernel(const GemmArgs args) {
-  constexpr int NW = WARPS_M * WARPS_N;
-  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
-  constexpr int FM = BM / (32 * WARPS_M);
-  constexpr int FN = BN / (32 * WARPS_N);
-  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
-  constexpr int STAGE = (BM + BN) * RROW;
-  constexpr int GROUPS = (BM + BN) / 16;  // 16 tile rows = 1 KB = one wave-wide 16-byte load
-  constexpr int GPW = GROUPS / NW;
-  static_assert(GROUPS % NW == 0 && BM % 16 == 0, "load split mismatch");
-  static_assert(MODE != GEMM_SWIGLU || FN % 2 == 0, "SwiGLU needs gate and up fragments");
-  static_assert(FM <= 4, "fragment-count dispatch covers up to 4 row fragments per wave");
-
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave % WARPS_M, wn = wave / WARPS_M;
-
-  TileInfo t;
-  if (!decode_tile<BM, BN_OUT>(args, t)) return;
-
-  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride;
-  const uint16_t *B0 = reinterpret_cast<const uint16_t *>(wptr + args.b0_off);
-  const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
-  const int kt_total = args.K / RK;
-  const int kt_begin = (int)((long long)kt_total * t.ks / args.splitk);
-  const int kt_end = (int)((long long)kt_total * (t.ks + 1) / args.splitk);
-  const int nk = kt_end - kt_begin;
-
-  // load g fills tile rows 16g..16g+15; lane l lands at row 16g + l/4, chunk position l%4
-  const uint16_t *src[GPW];
-#pragma unroll
-  for (int i = 0; i < GPW; ++i) {
-    const int g = i * NW + wave;
-    const int row = g * 16 + (lane >> 2);
-    const int kc = (lane & 3) ^ ((row >> 2) & 3);
-    if (g * 16 < BM) {
-      int rr = row < t.rows_valid ? row : 0;
-      int p = t.row0 + t.tile_row0 + rr;
-      long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
-      src[i] = args.A + srow * args.lda + kc * 8;
-    } else {
-      int r = row - BM;
-      const uint16_t *base = B0;
-      if (MODE == GEMM_SWIGLU && r >= BN / 2) { base = B1; r -= BN / 2; }
-      int n = t.n0 + r;
-      if (n >= args.N) n = args.N - 1;
-      src[i] = base + (long long)n * args.ldb + kc * 8;
-    }
-  }
-
-  int fm_valid = 0;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < t.rows_valid) ? 1 : 0;
-
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  int a_off[FM], b_off[FN];
-  const int lrow = lane & 31, lk = lane >> 5;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) a_off[i] = (i * WARPS_M + wm) * 32 + lrow;
-#pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    if (MODE == GEMM_SWIGLU)
-      b_off[j] = (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow;
-    else
-      b_off[j] = (j * WARPS_N + wn) * 32 + lrow;
-  }
-
-  // loads of relative step q (clamped to the last step: a harmless re-load into a free stage)
-#define MOE_RISSUE(q_)                                                                               \
-  do {                                                                                               \
-    const int qq_ = (q_) < nk ? (q_) : nk - 1;                                                       \
-    const int st_ = (q_) & (RSTAGES - 1);                                                            \
-    _Pragma("unroll") for (int i_ = 0; i_ < GPW; ++i_) {                                             \
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src[i_] + (long long)(kt_begin + qq_) * RK),      \
-                                       (lds_ptr_t)(smem + st_ * STAGE + (i_ * NW + wave) * 1024),    \
-                                       16, 0, 0);                                                    \
-    }                                                                                                \
-  } while (0)
-#define MOE_RREAD(FMV, buf_, q_, kk_)                                                                \
-  do {                                                                                               \
-    const unsigned char *sa_ = smem + ((q_) & (RSTAGES - 1)) * STAGE;                                \
-    const unsigned char *sb_ = sa_ + BM * RROW;                                                      \
-    const int kc_ = (kk_) * 2 + lk;                                                                  \
-    _Pragma("unroll") for (int i_ = 0; i_ < FMV; ++i_)                                               \
-      af_[buf_][i_] = *reinterpret_cast<const bf16x8 *>(sa_ + swz32(a_off[i_], kc_));                \
-    _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                                \
-      bf_[buf_][j_] = *reinterpret_cast<const bf16x8 *>(sb_ + swz32(b_off[j_], kc_));                \
-  } while (0)
-#define MOE_RMMA(FMV, buf_)                                                                          \
-  do {                                                                                               \
-    _Pragma("unroll") for (int i_ = 0; i_ < FMV; ++i_)                                               \
-      _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                              \
-        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[buf_][i_], bf_[buf_][j_], acc[i_][j_], 0, 0, 0); \
-  } while (0)
-  // vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt[3:0] | [15:14], expcnt, lgkmcnt)
-#define MOE_VMCNT(n_) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n_) & 15) | (((n_) >> 4) << 14))
-#define MOE_RING_LOOP(FMV)                                                                           \
-  do {                                                                                               \
-    bf16x8 af_[2][FMV > 0 ? FMV : 1], bf_[2][FN];                                                    \
-    MOE_VMCNT(2 * GPW);                                                                              \
-    __syncthreads();                                                                                 \
-    if (FMV > 0) MOE_RREAD(FMV, 0, 0, 0);                                                            \
-    for (int q = 0; q < nk; ++q) {                                                                   \
-      MOE_VMCNT(GPW);   /* this wave's loads of step q+1 have landed */                              \
-      __syncthreads();  /* everybody's have, and everybody is done with the stage of step q-1 */    \
-      MOE_RISSUE(q + 3);                                                                             \
-      if (FMV > 0) {                                                                                 \
-        MOE_RREAD(FMV, 1, q, 1);                                                                     \
-        MOE_RMMA(FMV, 0);                                                                            \
-        MOE_RMMA(FMV, 1);                                                                            \
-        MOE_RREAD(FMV, 0, q + 1, 0);                                                                 \
-        __builtin_amdgcn_sched_group_barrier(0x020, GPW, 0);                                         \
-        __builtin_amdgcn_sched_group_barrier(0x100, FMV + FN, 0);                                    \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * FMV * FN, 0);                                \
-        __builtin_amdgcn_sched_group_barrier(0x100, FMV + FN, 0);                                    \
-      }                                                                                              \
-    }                                                                                                \
-  } while (0)
-
-  if (nk > 0) {
-    MOE_RISSUE(0);
-    MOE_RISSUE(1);
-    MOE_RISSUE(2);
-    switch (fm_valid) {
-      case 0: MOE_RING_LOOP(0); break;
-      case 1: MOE_RING_LOOP(1); break;
-      case 2: if constexpr (FM >= 2) MOE_RING_LOOP(2); break;
-      case 3: if constexpr (FM >= 3) MOE_RING_LOOP(3); break;
-      default: if constexpr (FM >= 4) MOE_RING_LOOP(4); break;
-    }
-    MOE_VMCNT(0);  // the clamped tail loads must not outlive the block's LDS
-  }
-#undef MOE_RING_LOOP
-#undef MOE_VMCNT
-#undef MOE_RMMA
-#undef MOE_RREAD
-#undef MOE_RISSUE
-
-  store_tile<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Ping-pong kernel: 256 x 256 x 64 tiles in a two-stage LDS ring, eight waves in two groups of
 // four.  Waves w and w+4 of a block sit on the same SIMD; the two groups run the same loop one
 // barrier interval ("tick") apart, so while one wave of a SIMD issues 16 MFMAs, its partner pulls
@@ -1091,30 +930,6 @@ hipError_t launch_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, 
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
-hipError_t launch_ring(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
-  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
-  constexpr int NTHR = 64 * WARPS_M * WARPS_N;
-  constexpr size_t smem = RSTAGES * (size_t)(BM + BN) * RROW;
-  auto kern = grouped_gemm_ring_kernel<BM, BN, WARPS_M, WARPS_N, MODE>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  const long long n_tiles_n = (args.N + BN_OUT - 1) / BN_OUT;
-  const long long m_tiles_ub = (long long)max_rows / BM + n_groups_in_mask;
-  long long ub = m_tiles_ub * n_tiles_n * args.splitk;
-  if (ub <= 0) return hipSuccess;
-  ub = (ub + 7) / 8 * 8;
-  if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(kern, dim3((unsigned)ub), dim3(NTHR), smem, stream, args);
-  return hipGetLastError();
-}
-
-// One block per compute unit (128 KB of LDS each); the blocks walk over the tiles.
 static int pp_grid_blocks() {
   static int blocks = 0;
   if (!blocks) {
@@ -1174,7 +989,8 @@ hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask
 
 }  // namespace
 
-// Tile shapes.  Variant 0 picks by shape; 1.. force one (tuning hook).
+// Variant 0 picks by shape; a test or tuning run forces one: 1 = 128 x 128 tiles, 6 = 256 x 256 tiles
+// of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
 static int g_variant[3] = {0, 0, 0};
 
 void set_gemm_variant(int mode, int variant) {
@@ -1198,16 +1014,7 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
   }
   if (v == 12 && !pp_ok) v = 6;
   switch (v) {
-    case 2: return launch_cfg<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 3: return launch_cfg<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 4: return launch_cfg<128, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 5: return launch_cfg<256, 128, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 6: return launch_cfg<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 7: return launch_cfg<128, 256, 1, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 8: return launch_cfg<256, 256, 4, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 9: return launch_ring<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 10: return launch_ring<256, 256, 4, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
-    case 11: return launch_ring<256, 256, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 12: return launch_pp<MODE>(args, max_rows, n_groups_in_mask, stream);
     default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
   }

@@ -82,6 +82,26 @@ def test_dense_gemm_matches_matmul(gpu, M, N, K):
     assert np.all(np.abs(got - want) <= 2.0 ** -7 * np.abs(want) + 1e-3 * np.sqrt(K))
 
 
+@pytest.mark.parametrize("variant", [1, 6, 12])
+def test_every_gemm_kernel_on_one_layer(gpu, oracle, variant):
+    """The shape heuristic picks one GEMM kernel per launch; here each of them is forced onto the same
+    layer (groups of unequal height, shared experts, K a multiple of 64) and checked against the oracle."""
+    B = gpu["binding"]
+    w = S.Workload("variants", d=256, I=384, E=6, k=2, T=1100, I_shared=256, seed=33, zipf_s=1.1)
+    x = S.activations(w)
+    bias = S.zipf_route_bias(w, 0)
+    try:
+        for mode in (0, 1):
+            B.moe_set_gemm_variant(mode, variant)
+        r = run_layer(gpu, w, w.T, x, w.E, list(range(w.E)), bias=bias)
+    finally:
+        for mode in (0, 1):
+            B.moe_set_gemm_variant(mode, 0)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias, shared=r["lay"].shared_np)
+    np.testing.assert_array_equal(r["routing"]["perm"], ref["perm"])
+    check_out(r["out"], ref["out_f64"], f"gemm variant {variant}")
+
+
 # ---------------------------------------------------------------- config 1, all resident
 def test_c1_routing_bit_exact_and_output(gpu, oracle):
     w = S.WORKLOADS["c1_tiny"]
