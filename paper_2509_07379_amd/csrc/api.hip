@@ -408,15 +408,19 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
   }
 
-  // ---- gate, Top-k, grouping
+  // ---- gate, Top-k, grouping (one token: the gate's kernel writes the grouping tables itself)
+  SingleTokenDispatch one{reinterpret_cast<int32_t *>(ws + W.counts), reinterpret_cast<int32_t *>(ws + W.offsets),
+                          reinterpret_cast<int32_t *>(ws + W.perm), reinterpret_cast<int32_t *>(ws + W.inv_perm),
+                          ctx->pinned_counts, 0};
+  if (T == 1) one.seq = ++ctx->mailbox_seq;
   {
     Timer t(ctx, cs, MOE_K_ROUTER);
     HIP_TRY(launch_router_topk(reinterpret_cast<const uint16_t *>(dev_x), L.router_w, bias, bias_stride, T,
                                c.d, E, c.k, c.renormalize, reinterpret_cast<float *>(ws + W.logits),
                                reinterpret_cast<int32_t *>(ws + W.ids), reinterpret_cast<float *>(ws + W.w),
-                               cs));
+                               cs, T == 1 ? &one : nullptr));
   }
-  {
+  if (T != 1) {
     Timer t(ctx, cs, MOE_K_DISPATCH);
     HIP_TRY(launch_dispatch(reinterpret_cast<const int32_t *>(ws + W.ids), n, E,
                             reinterpret_cast<int32_t *>(ws + W.blk_hist),

@@ -12,9 +12,16 @@ constexpr int kDispatchChunk = 256;  // assignments per dispatch block
 // ---- gate: logits (fixed fp32 summation order), top-k, gate values -------------------
 // x [T,d] bf16, wr [E,d] bf16, bias NULL or fp32 [t*bias_stride + e].
 // Outputs: ids [T,k] (descending logit, lower id on ties), w [T,k] fp32, logits [T,E] (may be NULL).
+// one (T == 1 only, else NULL): the grouping tables of launch_dispatch, written by the gate's kernel
+// itself; host_counts (may be NULL) as there.
+struct SingleTokenDispatch {
+  int32_t *counts, *offsets, *perm, *inv_perm, *host_counts;
+  int seq;
+};
 hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
                               int bias_stride, int T, int d, int E, int k, int renormalize,
-                              float *logits, int32_t *ids, float *w, hipStream_t stream);
+                              float *logits, int32_t *ids, float *w, hipStream_t stream,
+                              const SingleTokenDispatch *one = nullptr);
 
 // Predictor stand-in: scores[e] = sum_t x[t].wp[e] (same summation order per token, tokens
 // ascending), top-m ids to `top_out` (device-visible, e.g. pinned host memory).

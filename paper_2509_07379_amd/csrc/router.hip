@@ -59,7 +59,7 @@ template <int TPB, int NWAVES>
 __global__ __launch_bounds__(64 * NWAVES) void router_topk_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr, const float *__restrict__ bias,
     int bias_stride, int T, int d, int E, int k, int renormalize, float *__restrict__ logits,
-    int32_t *__restrict__ ids, float *__restrict__ w) {
+    int32_t *__restrict__ ids, float *__restrict__ w, const SingleTokenDispatch one) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint4 *xs = reinterpret_cast<uint4 *>(smem);                           // [TPB][d/8]
   float *lg = reinterpret_cast<float *>(smem + (size_t)TPB * d * 2);     // [TPB][64]
@@ -117,6 +117,34 @@ __global__ __launch_bounds__(64 * NWAVES) void router_topk_kernel(
       ids[(size_t)t * k + lane] = si;
       w[(size_t)t * k + lane] = wj;
     }
+    // One token: grouping its k assignments by expert is a rank computation inside this wave (the
+    // k experts are distinct), so the call needs no grouping kernel.  Same tables as launch_dispatch.
+    if (one.counts) {
+      int c = 0;
+      for (int j = 0; j < k; ++j) c += (__shfl(si, j) == lane) ? 1 : 0;   // lane = expert
+      int incl = c;
+#pragma unroll
+      for (int sft = 1; sft < 64; sft <<= 1) {
+        const int o = __shfl_up(incl, sft);
+        if (lane >= sft) incl += o;
+      }
+      const int excl = incl - c;
+      if (lane < E) {
+        one.counts[lane] = c;
+        one.offsets[lane] = excl;
+        if (one.host_counts) one.host_counts[lane] = c;
+      }
+      if (lane == E - 1) one.offsets[E] = incl;
+      const int pos = __shfl(excl, lane < k ? si : 0);   // sorted position of assignment `lane`
+      if (lane < k) {
+        one.perm[pos] = lane;
+        one.inv_perm[lane] = pos;
+      }
+      if (one.host_counts) {
+        __threadfence_system();
+        if (lane == 0) one.host_counts[kMaxExperts] = one.seq;
+      }
+    }
   }
 }
 
@@ -153,20 +181,23 @@ __global__ __launch_bounds__(64) void predictor_topm_kernel(const float *__restr
 
 hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
                               int bias_stride, int T, int d, int E, int k, int renormalize,
-                              float *logits, int32_t *ids, float *w, hipStream_t stream) {
+                              float *logits, int32_t *ids, float *w, hipStream_t stream,
+                              const SingleTokenDispatch *one) {
   // 4 tokens per block share one pass over Wr; small batches (decode) use one token per block and
   // 16 waves, so that the E dot products of a token run side by side.
+  SingleTokenDispatch none{};
+  if (one && T != 1) return hipErrorInvalidValue;
   if (T >= 64) {
     constexpr int TPB = 4;
     size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
     int grid = (T + TPB - 1) / TPB;
     hipLaunchKernelGGL((router_topk_kernel<TPB, 4>), dim3(grid), dim3(256), smem, stream, x, wr, bias,
-                       bias_stride, T, d, E, k, renormalize, logits, ids, w);
+                       bias_stride, T, d, E, k, renormalize, logits, ids, w, none);
   } else {
     constexpr int TPB = 1;
     size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
     hipLaunchKernelGGL((router_topk_kernel<TPB, 16>), dim3(T), dim3(1024), smem, stream, x, wr, bias,
-                       bias_stride, T, d, E, k, renormalize, logits, ids, w);
+                       bias_stride, T, d, E, k, renormalize, logits, ids, w, one ? *one : none);
   }
   return hipGetLastError();
 }
