@@ -53,6 +53,9 @@ typedef struct {
   int32_t cache_slots; /* S: GPU expert cache slots per layer, >= 1 (Section V-A) */
   int32_t I_shared;    /* 0, or total intermediate size of the always-on shared experts */
   int32_t renormalize; /* 1: gate values = softmax over the k selected; 0: over all E */
+  int32_t shared_slots;/* 0: every layer has its own cache of cache_slots slots; 1: ONE cache of
+                          cache_slots slots serves all layers in turn (Section V-A: a GPU expert
+                          cache of k experts, refilled layer after layer) */
 } moe_config;
 
 /* Cache counters (host side).  hits/misses count active experts per layer call. */
@@ -84,7 +87,8 @@ size_t moe_workspace_bytes(const moe_config *cfg, int T);
  *                       row-major bf16, one contiguous blob per expert (= one DMA per expert).
  *  dev_router_w         [E, d] bf16 gate weight.
  *  dev_shared_blob      NULL, or 6*d*I_shared bytes in the same layout (always resident).
- *  dev_slots            S * 6*d*I bytes: the layer's GPU expert cache.
+ *  dev_slots            S * 6*d*I bytes: the layer's GPU expert cache (with shared_slots: the one
+ *                       cache, the same pointer for every layer).
  *  initial_resident     NULL (all slots empty) or [S] expert ids / -1: slot s already holds
  *                       that expert's blob (the caller copied it there).
  * The pointers are read, not copied.

@@ -26,7 +26,7 @@ EXPORTS = [
 
 class MoeConfig(Structure):
     _fields_ = [(n, c_int32) for n in
-                ("d", "I", "E", "k", "n_layers", "cache_slots", "I_shared", "renormalize")]
+                ("d", "I", "E", "k", "n_layers", "cache_slots", "I_shared", "renormalize", "shared_slots")]
 
 
 class MoeStats(Structure):
@@ -110,10 +110,11 @@ def _stream(s):
 class MoeContext:
     """Owner of a moe_ctx handle; methods carry the C function names."""
 
-    def __init__(self, d, I, E, k, n_layers=1, cache_slots=None, I_shared=0, renormalize=True):
+    def __init__(self, d, I, E, k, n_layers=1, cache_slots=None, I_shared=0, renormalize=True,
+                 shared_slots=False):
         self.lib = load()
         self.cfg = MoeConfig(d, I, E, k, n_layers, E if cache_slots is None else cache_slots, I_shared,
-                             1 if renormalize else 0)
+                             1 if renormalize else 0, 1 if shared_slots else 0)
         self._h = c_void_p()
         _check(self.lib.moe_create(byref(self.cfg), byref(self._h)))
         self._keep = {}

@@ -11,6 +11,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <atomic>
 #include <chrono>
@@ -94,13 +95,12 @@ WsLayout ws_layout(const moe_config &c, int T) {
   return L;
 }
 
-struct Layer {
-  bool bound = false;
-  std::vector<const void *> host_blob;
-  const uint16_t *router_w = nullptr;
-  const char *shared_blob = nullptr;
+// One GPU expert cache: S slots of one blob each, with the events that order the copy stream
+// against the compute stream.  Each layer has its own, or (cfg.shared_slots) all layers share one,
+// the paper's cache of k experts that is refilled layer after layer (Section V-A).
+struct SlotSet {
   char *slots = nullptr;
-  std::vector<int> slot_expert, expert_slot;
+  std::vector<int> slot_expert, slot_layer;   // what a slot holds: expert of which layer (-1: empty)
   std::vector<unsigned long long> stamp;
   std::vector<char> prefetched;      // slot filled by a prefetch and not yet served
   std::vector<char> copy_pending;    // a copy into the slot was enqueued; compute has not waited yet
@@ -109,6 +109,17 @@ struct Layer {
   std::vector<hipEvent_t> copied_up;  // a split fetch has landed its gate / up matrices
   hipEvent_t group_done = nullptr;
   unsigned long long clock = 0;
+};
+
+struct Layer {
+  bool bound = false;
+  int index = 0;
+  std::vector<const void *> host_blob;
+  const uint16_t *router_w = nullptr;
+  const char *shared_blob = nullptr;
+  SlotSet *set = nullptr;            // own.get(), or the context's shared set
+  std::unique_ptr<SlotSet> own;
+  std::vector<int> expert_slot;      // this layer's experts -> slot of `set` (-1: not resident)
   moe_stats stats{};
 };
 
@@ -124,6 +135,7 @@ struct moe_ctx {
   int device = 0;
   size_t blob_bytes = 0;
   std::vector<Layer> layers;
+  std::unique_ptr<SlotSet> shared_set;   // cfg.shared_slots: the one cache all layers use
   int32_t *pinned_counts = nullptr;   // mailbox the dispatch kernel fills: [kMaxExperts] counts, then the call's number
   int32_t mailbox_seq = 0;
   hipEvent_t routed = nullptr;
@@ -189,24 +201,25 @@ struct Timer {
 };
 
 // ---- cache bookkeeping --------------------------------------------------------------------
-void touch(Layer &L, int s) { L.stamp[s] = ++L.clock; }
+void touch(Layer &L, int s) { L.set->stamp[s] = ++L.set->clock; }
 
 int pick_victim(const Layer &L, unsigned long long protected_mask) {
-  const int S = (int)L.slot_expert.size();
+  const int S = (int)L.set->slot_expert.size();
   for (int s = 0; s < S; ++s)
-    if (L.slot_expert[s] < 0) return s;
+    if (L.set->slot_expert[s] < 0) return s;
   int best = -1;
   for (int s = 0; s < S; ++s) {
-    if ((protected_mask >> L.slot_expert[s]) & 1ull) continue;
-    if (best < 0 || L.stamp[s] < L.stamp[best]) best = s;
+    // (another layer's expert in a shared cache is never protected: its readers are ordered by events)
+    if (L.set->slot_layer[s] == L.index && ((protected_mask >> L.set->slot_expert[s]) & 1ull)) continue;
+    if (best < 0 || L.set->stamp[s] < L.set->stamp[best]) best = s;
   }
   return best;
 }
 
 // The copy stream waits for the last reader of slot s (nothing to wait for if it was never read).
 int wait_slot_free(Layer &L, int s, hipStream_t copy_stream) {
-  if (L.use_kind[s] == 1) HIP_TRY(hipStreamWaitEvent(copy_stream, L.used[s], 0));
-  if (L.use_kind[s] == 2) HIP_TRY(hipStreamWaitEvent(copy_stream, L.group_done, 0));
+  if (L.set->use_kind[s] == 1) HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->used[s], 0));
+  if (L.set->use_kind[s] == 2) HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->group_done, 0));
   return MOE_OK;
 }
 
@@ -220,24 +233,25 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     int rc = wait_slot_free(L, s, copy_stream);
     if (rc) return rc;
   }
-  char *dst = L.slots + (size_t)s * ctx->blob_bytes;
+  char *dst = L.set->slots + (size_t)s * ctx->blob_bytes;
   const char *src = static_cast<const char *>(L.host_blob[e]);
   if (split) {
     const size_t up_bytes = ctx->blob_bytes / 3 * 2;   // [W_gate; W_up], then W_down
     HIP_TRY(hipMemcpyAsync(dst, src, up_bytes, hipMemcpyHostToDevice, copy_stream));
-    HIP_TRY(hipEventRecord(L.copied_up[s], copy_stream));
+    HIP_TRY(hipEventRecord(L.set->copied_up[s], copy_stream));
     HIP_TRY(hipMemcpyAsync(dst + up_bytes, src + up_bytes, ctx->blob_bytes - up_bytes, hipMemcpyHostToDevice,
                            copy_stream));
   } else {
     HIP_TRY(hipMemcpyAsync(dst, src, ctx->blob_bytes, hipMemcpyHostToDevice, copy_stream));
   }
-  HIP_TRY(hipEventRecord(L.copied[s], copy_stream));
-  if (L.slot_expert[s] >= 0) L.expert_slot[L.slot_expert[s]] = -1;
-  L.slot_expert[s] = e;
+  HIP_TRY(hipEventRecord(L.set->copied[s], copy_stream));
+  if (L.set->slot_expert[s] >= 0) ctx->layers[L.set->slot_layer[s]].expert_slot[L.set->slot_expert[s]] = -1;
+  L.set->slot_expert[s] = e;
+  L.set->slot_layer[s] = L.index;
   L.expert_slot[e] = s;
-  L.prefetched[s] = by_prefetch;
-  L.copy_pending[s] = 1;
-  L.use_kind[s] = 0;
+  L.set->prefetched[s] = by_prefetch;
+  L.set->copy_pending[s] = 1;
+  L.set->use_kind[s] = 0;
   touch(L, s);
   L.stats.bytes_h2d += (int64_t)ctx->blob_bytes;
   return MOE_OK;
@@ -250,7 +264,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   a.k_top = c.k;
   a.offsets = reinterpret_cast<const int32_t *>(ws + W.offsets);
   a.n_groups = c.E;
-  a.wbase = L.slots;
+  a.wbase = L.set->slots;
   a.wstride = (long long)ctx->blob_bytes;
   for (int e = 0; e < c.E; ++e) a.slot[e] = (signed char)(L.expert_slot[e] < 0 ? 0 : L.expert_slot[e]);
   a.splitk = 1;
@@ -458,16 +472,17 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   if (enqueue_blind) {
     // Every expert is in a slot: nothing to decide on the host, one grouped launch.
     for (int s = 0; s < S; ++s)
-      if (L.copy_pending[s]) {
-        HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
-        L.copy_pending[s] = 0;
+      if (L.set->copy_pending[s] && L.set->slot_layer[s] == L.index) {
+        HIP_TRY(hipStreamWaitEvent(cs, L.set->copied[s], 0));
+        L.set->copy_pending[s] = 0;
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
     rc = run_experts(ctx, decode, a1, a2, mask, E, n, T, cs, shared_in_routed_launch ? &s1 : nullptr,
                      shared_in_routed_launch ? &s2 : nullptr);
     if (rc) return rc;
-    HIP_TRY(hipEventRecord(L.group_done, cs));
-    for (int s = 0; s < S; ++s) L.use_kind[s] = 2;
+    HIP_TRY(hipEventRecord(L.set->group_done, cs));
+    for (int s = 0; s < S; ++s)
+      if (L.set->slot_layer[s] == L.index) L.set->use_kind[s] = 2;
     // counters need the counts: read them once the routing kernels are done
     HIP_TRY(wait_for_counts(ctx));
     for (int e = 0; e < E; ++e)
@@ -475,9 +490,9 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         int s = L.expert_slot[e];
         L.stats.hits++;
         touch(L, s);
-        if (L.prefetched[s]) {
+        if (L.set->prefetched[s]) {
           L.stats.prefetch_useful++;
-          L.prefetched[s] = 0;
+          L.set->prefetched[s] = 0;
         }
       }
   } else {
@@ -504,16 +519,16 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         int s = L.expert_slot[e];
         touch(L, s);
         L.stats.hits++;
-        if (L.prefetched[s]) {
+        if (L.set->prefetched[s]) {
           L.stats.prefetch_useful++;
-          L.prefetched[s] = 0;
+          L.set->prefetched[s] = 0;
         }
       }
     L.stats.misses += (int32_t)misses.size();
     auto wait_copied = [&](int s) -> int {
-      if (L.copy_pending[s]) {
-        HIP_TRY(hipStreamWaitEvent(cs, L.copied[s], 0));
-        L.copy_pending[s] = 0;
+      if (L.set->copy_pending[s]) {
+        HIP_TRY(hipStreamWaitEvent(cs, L.set->copied[s], 0));
+        L.set->copy_pending[s] = 0;
       }
       return MOE_OK;
     };
@@ -525,9 +540,9 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         }
       rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs);
       if (rc) return rc;
-      HIP_TRY(hipEventRecord(L.group_done, cs));
+      HIP_TRY(hipEventRecord(L.set->group_done, cs));
       for (int e = 0; e < E; ++e)
-        if ((hit_mask >> e) & 1ull) L.use_kind[L.expert_slot[e]] = 2;
+        if ((hit_mask >> e) & 1ull) L.set->use_kind[L.expert_slot[e]] = 2;
     } else if (n_hits) {
       // Misses will reuse these slots: run the hits one by one, each with its own "last reader"
       // event, so that the first fetch can start as soon as the first hit has been computed.
@@ -538,8 +553,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         if (rc) return rc;
         rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
         if (rc) return rc;
-        HIP_TRY(hipEventRecord(L.used[s], cs));
-        L.use_kind[s] = 1;
+        HIP_TRY(hipEventRecord(L.set->used[s], cs));
+        L.set->use_kind[s] = 1;
       }
     }
     // Misses stream through the slots in ascending id: fetch on the copy stream (behind the
@@ -553,14 +568,14 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       const bool last = i + 1 == misses.size();
       rc = place(ctx, L, e, s, false, ks, false, last);
       if (rc) return rc;
-      HIP_TRY(hipStreamWaitEvent(cs, last ? L.copied_up[s] : L.copied[s], 0));
-      L.copy_pending[s] = 0;
+      HIP_TRY(hipStreamWaitEvent(cs, last ? L.set->copied_up[s] : L.set->copied[s], 0));
+      L.set->copy_pending[s] = 0;
       a1.slot[e] = a2.slot[e] = (signed char)s;
       rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs, nullptr, nullptr,
-                       last ? L.copied[s] : nullptr);
+                       last ? L.set->copied[s] : nullptr);
       if (rc) return rc;
-      HIP_TRY(hipEventRecord(L.used[s], cs));
-      L.use_kind[s] = 1;
+      HIP_TRY(hipEventRecord(L.set->used[s], cs));
+      L.set->use_kind[s] = 1;
     }
   }
 
@@ -614,12 +629,15 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
 int moe_destroy(moe_ctx *ctx) {
   if (!ctx) return MOE_OK;
   (void)hipDeviceSynchronize();
-  for (Layer &L : ctx->layers) {
-    for (hipEvent_t e : L.copied) (void)hipEventDestroy(e);
-    for (hipEvent_t e : L.copied_up) (void)hipEventDestroy(e);
-    for (hipEvent_t e : L.used) (void)hipEventDestroy(e);
-    if (L.group_done) (void)hipEventDestroy(L.group_done);
-  }
+  auto destroy_set = [](SlotSet *set) {
+    if (!set) return;
+    for (hipEvent_t e : set->copied) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : set->copied_up) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : set->used) if (e) (void)hipEventDestroy(e);
+    if (set->group_done) (void)hipEventDestroy(set->group_done);
+  };
+  for (Layer &L : ctx->layers) destroy_set(L.own.get());
+  destroy_set(ctx->shared_set.get());
   for (auto &t : ctx->timed) {
     (void)hipEventDestroy(t.start);
     (void)hipEventDestroy(t.stop);
@@ -666,33 +684,58 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
     }
   }
   Layer &L = *Lp;
-  if (!L.bound) {
-    L.copied.resize(S);
-    L.copied_up.resize(S);
-    L.used.resize(S);
+  L.index = layer;
+  const bool shared = c.shared_slots != 0;
+  if (shared && ctx->shared_set && ctx->shared_set->slots != reinterpret_cast<char *>(dev_slots))
+    return fail(MOE_E_ARG, "shared_slots: every layer must be bound to the same dev_slots");
+  std::unique_ptr<SlotSet> &holder = shared ? ctx->shared_set : L.own;
+  const bool fresh = !holder;
+  if (fresh) {
+    holder.reset(new (std::nothrow) SlotSet());
+    if (!holder) return fail(MOE_E_HIP, "out of host memory");
+    SlotSet &set = *holder;
+    set.copied.assign(S, nullptr);
+    set.copied_up.assign(S, nullptr);
+    set.used.assign(S, nullptr);
     for (int s = 0; s < S; ++s) {
-      HIP_TRY(hipEventCreateWithFlags(&L.copied[s], hipEventDisableTiming));
-      HIP_TRY(hipEventCreateWithFlags(&L.copied_up[s], hipEventDisableTiming));
-      HIP_TRY(hipEventCreateWithFlags(&L.used[s], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&set.copied[s], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&set.copied_up[s], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&set.used[s], hipEventDisableTiming));
     }
-    HIP_TRY(hipEventCreateWithFlags(&L.group_done, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&set.group_done, hipEventDisableTiming));
   }
+  L.set = holder.get();
+  SlotSet &set = *L.set;
   L.host_blob.assign(host_expert_blob, host_expert_blob + c.E);
   L.router_w = reinterpret_cast<const uint16_t *>(dev_router_w);
   L.shared_blob = reinterpret_cast<const char *>(dev_shared_blob);
-  L.slots = reinterpret_cast<char *>(dev_slots);
-  L.slot_expert.assign(S, -1);
   L.expert_slot.assign(c.E, -1);
-  L.stamp.assign(S, 0);
-  L.prefetched.assign(S, 0);
-  L.copy_pending.assign(S, 0);
-  L.use_kind.assign(S, 0);
-  L.clock = 0;
   L.stats = moe_stats{};
+  if (fresh || !shared) {
+    // (re)binding a layer of its own cache resets that cache; a shared cache is set up by the first
+    // layer that is bound and only claimed slot by slot by the others
+    set.slots = reinterpret_cast<char *>(dev_slots);
+    set.slot_expert.assign(S, -1);
+    set.slot_layer.assign(S, -1);
+    set.stamp.assign(S, 0);
+    set.prefetched.assign(S, 0);
+    set.copy_pending.assign(S, 0);
+    set.use_kind.assign(S, 0);
+    set.clock = 0;
+  } else {
+    for (int s = 0; s < S; ++s)   // rebinding a layer of a shared cache drops what it held there
+      if (set.slot_layer[s] == layer) {
+        set.slot_expert[s] = set.slot_layer[s] = -1;
+        set.prefetched[s] = 0;
+        set.stamp[s] = 0;
+      }
+  }
   if (initial_resident)
     for (int s = 0; s < S; ++s)
       if (initial_resident[s] >= 0) {
-        L.slot_expert[s] = initial_resident[s];
+        if (set.slot_expert[s] >= 0) ctx->layers[set.slot_layer[s]].expert_slot[set.slot_expert[s]] = -1;
+        set.slot_expert[s] = initial_resident[s];
+        set.slot_layer[s] = layer;
         L.expert_slot[initial_resident[s]] = s;
       }
   L.bound = true;
@@ -810,11 +853,12 @@ int moe_cache_invalidate(moe_ctx *ctx, int layer) {
   int rc = get_layer(ctx, layer, &Lp);
   if (rc) return rc;
   Layer &L = *Lp;
-  for (size_t s = 0; s < L.slot_expert.size(); ++s) {
-    if (L.slot_expert[s] >= 0) L.expert_slot[L.slot_expert[s]] = -1;
-    L.slot_expert[s] = -1;
-    L.prefetched[s] = 0;
-    L.stamp[s] = 0;
+  for (size_t s = 0; s < L.set->slot_expert.size(); ++s) {
+    if (L.set->slot_layer[s] != L.index) continue;   // a shared cache: only what this layer holds
+    L.expert_slot[L.set->slot_expert[s]] = -1;
+    L.set->slot_expert[s] = L.set->slot_layer[s] = -1;
+    L.set->prefetched[s] = 0;
+    L.set->stamp[s] = 0;
   }
   return MOE_OK;
 }
@@ -824,7 +868,8 @@ int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert) {
   int rc = get_layer(ctx, layer, &Lp);
   if (rc) return rc;
   if (!host_slot_expert) return fail(MOE_E_ARG, "NULL argument");
-  for (int s = 0; s < ctx->cfg.cache_slots; ++s) host_slot_expert[s] = Lp->slot_expert[s];
+  for (int s = 0; s < ctx->cfg.cache_slots; ++s)
+    host_slot_expert[s] = Lp->set->slot_layer[s] == layer ? Lp->set->slot_expert[s] : -1;
   return MOE_OK;
 }
 
