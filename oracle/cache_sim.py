@@ -115,3 +115,94 @@ class CacheSim:
         return dict(hits=self.hits, misses=self.misses, prefetch_issued=self.prefetch_issued,
                     prefetch_useful=self.prefetch_useful, prefetch_dropped=self.prefetch_dropped,
                     bytes_h2d=self.bytes_h2d)
+
+
+class SharedCacheSim:
+    """The same rules for ONE cache of S slots that serves all layers in turn (Section V-A: the GPU
+    expert cache holds as many experts as a token activates and is refilled layer after layer).
+
+    A slot holds (layer, expert).  Residency, hits and misses are per layer; the use counter and
+    the victim rule K2 are the cache's: an empty slot first, else the least recently used slot whose
+    content is not protected, where only experts of the layer that is asking can be protected.
+    Counters are kept per layer, as the per-layer caches keep them.
+    """
+
+    def __init__(self, n_layers: int, E: int, S: int, blob_bytes: int):
+        assert S >= 1 and E >= 1 and n_layers >= 1
+        self.L, self.E, self.S, self.blob_bytes = n_layers, E, S, blob_bytes
+        self.slot = [None] * S          # (layer, expert) or None
+        self.stamp = [0] * S
+        self.prefetched = [False] * S
+        self.clock = 0
+        self.ctr = [dict(hits=0, misses=0, prefetch_issued=0, prefetch_useful=0, prefetch_dropped=0,
+                         bytes_h2d=0) for _ in range(n_layers)]
+        self.copies = []                # (layer, expert, slot) in issue order
+
+    def slot_of(self, layer: int, e: int) -> int:
+        return self.slot.index((layer, e)) if (layer, e) in self.slot else -1
+
+    def state(self, layer: int):
+        return [c[1] if c is not None and c[0] == layer else -1 for c in self.slot]
+
+    def _touch(self, s: int) -> None:
+        self.clock += 1
+        self.stamp[s] = self.clock
+
+    def _victim(self, layer: int, protected) -> int:
+        for s in range(self.S):
+            if self.slot[s] is None:
+                return s
+        best = -1
+        for s in range(self.S):
+            if self.slot[s][0] == layer and self.slot[s][1] in protected:
+                continue
+            if best < 0 or self.stamp[s] < self.stamp[best]:
+                best = s
+        return best
+
+    def _place(self, layer: int, e: int, s: int, prefetched: bool) -> None:
+        self.slot[s] = (layer, e)
+        self.prefetched[s] = prefetched
+        self._touch(s)
+        self.ctr[layer]["bytes_h2d"] += self.blob_bytes
+        self.copies.append((layer, e, s))
+
+    def prefetch(self, layer: int, ids):
+        protected = set(int(i) for i in ids)
+        seen = set()
+        for e in ids:
+            e = int(e)
+            assert 0 <= e < self.E
+            if e in seen:
+                continue
+            seen.add(e)
+            s = self.slot_of(layer, e)
+            if s >= 0:
+                self._touch(s)
+                continue
+            s = self._victim(layer, protected)
+            if s < 0:
+                self.ctr[layer]["prefetch_dropped"] += 1
+                continue
+            self._place(layer, e, s, True)
+            self.ctr[layer]["prefetch_issued"] += 1
+
+    def serve(self, layer: int, active):
+        active = sorted(set(int(e) for e in active))
+        hits = [e for e in active if self.slot_of(layer, e) >= 0]
+        misses = [e for e in active if self.slot_of(layer, e) < 0]
+        for e in hits:
+            s = self.slot_of(layer, e)
+            self._touch(s)
+            if self.prefetched[s]:
+                self.ctr[layer]["prefetch_useful"] += 1
+                self.prefetched[s] = False
+        self.ctr[layer]["hits"] += len(hits)
+        self.ctr[layer]["misses"] += len(misses)
+        for e in misses:
+            s = self._victim(layer, ())
+            self._place(layer, e, s, False)
+        return hits, misses
+
+    def counters(self, layer: int):
+        return dict(self.ctr[layer])

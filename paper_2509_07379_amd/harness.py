@@ -49,15 +49,17 @@ class DeviceLayer:
     """Device-side memory of one layer, bound to `ctx` as layer `layer`."""
 
     def __init__(self, ctx: MoeContext, w: S.Workload, layer: int, pool: HostPool, initial=None,
-                 device="cuda:0", poison: bool = False):
+                 device="cuda:0", poison: bool = False, slots=None):
+        """slots: an existing slot tensor to bind (contexts with shared_slots: one for all layers)."""
         self.ctx, self.w, self.layer, self.pool = ctx, w, layer, pool
         Sslots = ctx.cfg.cache_slots
         self.router_np = S.router_weight(w, layer)
         self.router = np_to_dev(self.router_np, device)
         self.shared_np = S.shared_blob(w, layer)
         self.shared = np_to_dev(self.shared_np, device) if self.shared_np is not None else None
-        self.slots = torch.empty((Sslots, w.blob_elems), dtype=torch.int16, device=device)
-        if poison:
+        own = slots is None
+        self.slots = torch.empty((Sslots, w.blob_elems), dtype=torch.int16, device=device) if own else slots
+        if poison and own:
             self.slots.fill_(0x7FC0)  # bf16 NaN pattern: any read of an unfilled slot shows up
         if initial is not None:
             for s, e in enumerate(initial):

@@ -102,3 +102,52 @@ def test_more_active_than_slots_streams_all():
     assert victims[:12] == [1, 2, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13]
     assert victims[12:15] == [0, 3, 14]
     assert len(set(e for e, _ in fetched)) == 17
+
+
+# ---------------------------------------------------------------- one cache for all layers (Section V-A)
+def test_shared_cache_of_k_is_refilled_layer_after_layer():
+    """A cache of k = 2 experts serving 3 layers: right predictions are hits, each expert is fetched once
+    per layer visit, and the slot of the expert that was used first is the first one refilled."""
+    from oracle.cache_sim import SharedCacheSim
+    sim = SharedCacheSim(3, 8, 2, 100)
+    sim.prefetch(0, [1, 5])
+    assert sim.state(0) == [1, 5] and sim.state(1) == [-1, -1]
+    hits, misses = sim.serve(0, [5, 1])
+    assert hits == [1, 5] and misses == []
+    sim.prefetch(1, [2, 7])                       # evicts layer 0's experts in the order they were used
+    assert sim.copies[-2:] == [(1, 2, 0), (1, 7, 1)]
+    assert sim.state(0) == [-1, -1] and sim.state(1) == [2, 7]
+    hits, misses = sim.serve(1, [2, 3])           # 7 was a wrong guess: 3 is fetched again into the LRU slot
+    assert hits == [2] and misses == [3] and sim.state(1) == [2, 3]
+    assert sim.counters(1) == dict(hits=1, misses=1, prefetch_issued=2, prefetch_useful=1, prefetch_dropped=0,
+                                   bytes_h2d=300)
+    assert sim.counters(0)["bytes_h2d"] == 200 and sim.counters(0)["prefetch_useful"] == 2
+
+
+def test_shared_cache_reduces_to_per_layer_cache_for_one_layer():
+    """With a single layer the shared cache is the per-layer cache: same copies, same counters."""
+    import random
+    from oracle.cache_sim import CacheSim, SharedCacheSim
+    rng = random.Random(5)
+    a, b = CacheSim(8, 3, 10), SharedCacheSim(1, 8, 3, 10)
+    for _ in range(200):
+        ids = rng.sample(range(8), rng.randint(1, 4))
+        if rng.random() < 0.5:
+            a.prefetch(ids); b.prefetch(0, ids)
+        else:
+            a.serve(ids); b.serve(0, ids)
+        assert a.slot_expert == b.state(0)
+    assert a.counters() == b.counters(0)
+    assert [(e, s) for _, e, s in b.copies] == a.copies
+
+
+def test_shared_cache_protects_only_the_asking_layer():
+    """Full cache, every slot holds the asking layer's own request: nothing to evict, the rest is dropped;
+    another layer's entries are fair game."""
+    from oracle.cache_sim import SharedCacheSim
+    sim = SharedCacheSim(2, 8, 2, 1)
+    sim.prefetch(0, [0, 1])
+    sim.prefetch(0, [0, 1, 2])
+    assert sim.counters(0)["prefetch_dropped"] == 1 and sim.state(0) == [0, 1]
+    sim.prefetch(1, [0, 1])                       # same ids, other layer: both slots change owner
+    assert sim.state(0) == [-1, -1] and sim.state(1) == [0, 1]

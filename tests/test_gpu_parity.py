@@ -196,6 +196,81 @@ def test_wrong_prediction_is_refetched_not_used(gpu, oracle):
     assert off["stats"]["misses"] == 2 and off["stats"]["prefetch_useful"] == 0
 
 
+# ---------------------------------------------------------------- one GPU expert cache for all layers
+@pytest.mark.parametrize("slots", [2, 3])
+def test_shared_cache_decode_steps(gpu, oracle, slots):
+    """Section V-A / V-C with the paper's cache size: ONE cache of k (or k + 1) experts serves every
+    layer of a decode step in turn; the predictor of layer l + 1 runs on a third stream, its choice is
+    prefetched into the slots that layer l frees, wrong guesses are fetched again.  Every layer call
+    is checked against the oracle, counters and slot contents against the shared-cache simulator."""
+    from oracle.cache_sim import SharedCacheSim
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("shared_cache", d=256, I=128, E=8, k=2, T=1, seed=17, L=4, steps=5, p_stay=0.6, top_m=2)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, slots, 0, True, shared_slots=True)
+    pools = [H.HostPool(w, l) for l in range(w.L)]
+    cache = torch.full((slots, w.blob_elems), 0x7FC0, dtype=torch.int16, device="cuda")  # NaN until filled
+    lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
+    wps_np = [S.predictor_weight(w, l) for l in range(w.L)]
+    wps = [H.np_to_dev(a) for a in wps_np]
+    sim = SharedCacheSim(w.L, w.E, slots, w.blob_bytes)
+    trace = S.markov_trace(w)
+    buf = H.Buffers(ctx, w.T)
+    pred = torch.cuda.Stream()
+    top = torch.zeros(w.top_m, dtype=torch.int32).pin_memory()
+    for s in range(w.steps):
+        for l in range(w.L):
+            x_np = S.activations(w, l, s)
+            x = H.np_to_dev(x_np)
+            bias_np = S.trace_route_bias(trace[s, l], w.E)
+            bias = torch.from_numpy(bias_np).cuda()
+            nxt = l + 1                              # the first layer of a step has no prediction:
+            if nxt < w.L:                            # its experts are fetched after the gate has chosen
+                ctx.predictor_score(x, w.T, wps[nxt], w.top_m, top, pred)
+            ctx.moe_decode_layer(l, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, w.E)
+            gpu["compute"].synchronize()
+            ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k,
+                                   bias=bias_np, I=w.I)
+            np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
+            check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"shared cache step {s} layer {l}")
+            sim.serve(l, np.nonzero(ref["counts"])[0])
+            assert ctx.moe_cache_state(l) == sim.state(l), f"step {s} layer {l}"
+            if nxt == w.L:
+                continue
+            pred.synchronize()
+            _, ref_top = oracle.predictor_score(x_np, wps_np[nxt], w.top_m)
+            np.testing.assert_array_equal(top.numpy(), ref_top)
+            ctx.expert_cache_prefetch(nxt, top.tolist(), gpu["copy"])
+            sim.prefetch(nxt, ref_top)
+            assert ctx.moe_cache_state(nxt) == sim.state(nxt)
+    torch.cuda.synchronize()
+    for l in range(w.L):
+        assert ctx.moe_get_stats(l) == {**sim.counters(l), "layer_calls": w.steps}, f"layer {l}"
+    ctx.close()
+
+
+def test_shared_cache_prefill_streams_every_layer_through_two_slots(gpu, oracle):
+    """Section V-B: the two slots of the one cache are in turn computed on and fetched into, layer after
+    layer; each expert with tokens is fetched exactly once per layer and the output is the all-resident one."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("shared_prefill", d=256, I=128, E=8, k=2, T=96, seed=23, L=3)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, 2, 0, True, shared_slots=True)
+    pools = [H.HostPool(w, l) for l in range(w.L)]
+    cache = torch.full((2, w.blob_elems), 0x7FC0, dtype=torch.int16, device="cuda")
+    lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
+    buf = H.Buffers(ctx, w.T)
+    for l in range(w.L):
+        x_np = S.activations(w, l, 0)
+        ctx.expert_cache_prefetch(l, [0, 1], gpu["copy"])
+        ctx.moe_prefill_layer(l, H.np_to_dev(x_np), w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+        gpu["compute"].synchronize()
+        ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k, I=w.I)
+        check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"shared cache prefill layer {l}")
+        active = int((ref["counts"] > 0).sum())
+        extra = sum(1 for e in (0, 1) if ref["counts"][e] == 0)   # speculative fetches without tokens
+        assert ctx.moe_get_stats(l)["bytes_h2d"] == (active + extra) * w.blob_bytes
+    ctx.close()
+
+
 # ---------------------------------------------------------------- predictor stand-in
 @pytest.mark.parametrize("B,d,E,m", [(1, 4096, 8, 3), (8, 2048, 60, 8), (3, 256, 64, 64)])
 def test_predictor_scores_and_topm(gpu, oracle, B, d, E, m):
