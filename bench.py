@@ -178,24 +178,30 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
     log(f"[bench] decode host pools {n_layers * wl.E * wl.blob_bytes / 1e9:.1f} GB in {time.time() - t0:.1f}s")
     trace = S.markov_trace(wl)
     out = {}
-    for label, slots in (("cached", wl.S), ("resident", wl.E)):
-        ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, slots, wl.I_shared)
-        init = list(range(slots))
-        layers = [H.DeviceLayer(ctx, wl, l, pools[l], init) for l in range(n_layers)]
+    # "cached": S slots per layer (the configuration named in BASELINE.json); "shared_k": the paper's
+    # cache, ONE set of k slots for all layers, predictor top-k; "resident": kernels only
+    for label, slots in (("cached", wl.S), ("shared_k", wl.k), ("resident", wl.E)):
+        shared = label == "shared_k"
+        ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, slots, wl.I_shared, True, shared_slots=shared)
+        init = None if shared else list(range(slots))
+        cache = torch.empty((slots, wl.blob_elems), dtype=torch.int16, device="cuda") if shared else None
+        layers = [H.DeviceLayer(ctx, wl, l, pools[l], init, slots=cache) for l in range(n_layers)]
+        top_m = wl.k if shared else wl.top_m
         wps = [H.np_to_dev(S.predictor_weight(wl, l)) for l in range(n_layers)]
         buf = H.Buffers(ctx, wl.T)
         xs = [H.np_to_dev(S.activations(wl, l, 0)) for l in range(n_layers)]
         biases = [[torch.from_numpy(S.trace_route_bias(trace[s, l], wl.E)).cuda() for l in range(n_layers)]
                   for s in range(steps)]
-        top = torch.zeros(max(1, wl.top_m), dtype=torch.int32).pin_memory()
+        top = torch.zeros(max(1, top_m), dtype=torch.int32).pin_memory()
+        predict = label != "resident"
 
         def one_step(s):
             for l in range(n_layers):
-                if label == "cached" and l + 1 < n_layers:
+                if predict and l + 1 < n_layers:
                     # predictor for the next layer on its own stream (Section V-C)
-                    ctx.predictor_score(xs[l], wl.T, wps[l + 1], wl.top_m, top, pred)
+                    ctx.predictor_score(xs[l], wl.T, wps[l + 1], top_m, top, pred)
                 ctx.moe_decode_layer(l, xs[l], wl.T, buf.y, buf.ws, compute, copy, biases[s][l], wl.E)
-                if label == "cached" and l + 1 < n_layers:
+                if predict and l + 1 < n_layers:
                     pred.synchronize()
                     ctx.expert_cache_prefetch(l + 1, top.tolist(), copy)
 
@@ -219,7 +225,7 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
         out[label] = dict(us_per_layer=us_layer, stats=st, gemv1_ms=g1, gemv2_ms=g2,
                           launches=(kt["gemv1"][1], kt["gemv2"][1]))
         ctx.close()
-        del layers
+        del layers, cache
     return out
 
 
@@ -350,6 +356,9 @@ def main():
             "layer_HBM_GBps": bytes_layer / (r["us_per_layer"] * 1e-6) / 1e9,
             "cached_us_per_layer": dec["cached"]["us_per_layer"], "cached_slots": wd.S,
             "cached_stats": dec["cached"]["stats"],
+            # the paper's cache: one set of k slots for all layers, predictor top-k, first layer on demand
+            "shared_k_us_per_layer": dec["shared_k"]["us_per_layer"], "shared_k_slots": wd.k,
+            "shared_k_stats": dec["shared_k"]["stats"],
         }
         log(f"[bench] decode: {line['decode']}")
 
