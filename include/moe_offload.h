@@ -117,6 +117,48 @@ int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, 
                     float *dev_scores, int32_t *pinned_topm, void *stream);
 
 /*
+ * The paper's predictor, ExpertMLP (Section IV-B), for one state vector: n_fc fully connected
+ * layers of sizes host_dims[0] -> host_dims[1] -> ... -> host_dims[n_fc] (= number of experts).
+ * Every layer but the last is followed by batch normalisation in inference form (per neuron
+ * z * scale + shift) and ReLU; dropout is the identity at inference.  The last layer's outputs
+ * are the experts' logits (their sigmoid is the predicted activation probability, which ranks
+ * the same): the m best go to pinned_topm[m], all of them to dev_scores if != NULL.
+ *   state       fp32 [host_dims[0]], device-visible (device or pinned host memory).
+ *   dev_w[l]    bf16 [host_dims[l+1], host_dims[l]] row-major; dev_bias[l] fp32 [host_dims[l+1]];
+ *   dev_scale[l], dev_shift[l]  fp32, for l < n_fc - 1 (the entries for the last layer are ignored).
+ *   dev_act     fp32 scratch, 2 * max(host_dims) elements.
+ * The host arrays of pointers are read during the call only.  2 <= n_fc <= 16.  Does not block.
+ */
+int predictor_mlp_score(moe_ctx *ctx, const float *state, const int32_t *host_dims, int n_fc,
+                        const void *const *dev_w, const float *const *dev_bias,
+                        const float *const *dev_scale, const float *const *dev_shift, float *dev_act,
+                        int m, float *dev_scores, int32_t *pinned_topm, void *stream);
+
+/*
+ * State Constructor (Sections IV-A, IV-B, V-C): keeps the experts selected at each layer of the
+ * current decode step and builds the predictor's input s_l = [h_l, p_l, a_{l-1,l}] as one fp32
+ * vector of moe_state_dim() = L*k + M + k*M entries:
+ *   h_l        the ids selected at layers 0 .. l-1, in the order recorded, each id i stored as
+ *              (i + 1) / M, zero-padded to L*k entries;
+ *   p_l        row l of the popularity matrix (Eq. 2);
+ *   a_{l-1,l}  for each of the k experts recorded at layer l-1, its row of the affinity matrix
+ *              between layers l-1 and l (Eq. 3); zeros for l = 0.
+ * host_popularity [L, M] and host_affinity [L-1, M, M] (fp32, from the preprocessing phase) are
+ * copied.  moe_state_record stores the k ids of a layer (any order of layers; a layer can be
+ * recorded again), moe_state_clear forgets all of them (after each decode round),
+ * moe_state_vector writes s_layer to host_out (plain or pinned host memory) and fails with
+ * MOE_E_ARG if one of the layers 0 .. layer-1 has not been recorded.  Host-only; no GPU work.
+ */
+typedef struct moe_state moe_state;
+int moe_state_create(int n_layers, int n_experts, int k, const float *host_popularity,
+                     const float *host_affinity, moe_state **out);
+int moe_state_destroy(moe_state *st);
+int moe_state_dim(const moe_state *st);
+int moe_state_record(moe_state *st, int layer, const int32_t *host_ids);
+int moe_state_clear(moe_state *st);
+int moe_state_vector(const moe_state *st, int layer, float *host_out);
+
+/*
  * One MoE layer in the prefill stage (Section V-B): gate -> Top-k -> tokens grouped by
  * expert -> every active expert as a grouped bf16 MFMA GEMM from its cache slot -> weighted
  * sum (+ shared experts) -> dev_y [T, d] bf16.  Experts that are not resident stream

@@ -41,6 +41,8 @@ def _load():
         lib.ref_expert_ffn.argtypes = [vp, vp, ci, ci, vp]
         lib.ref_moe_tokens.argtypes = [vp, ci, ci, ci, vp, vp, ci, vp, vp, vp, ci, vp, vp]
         lib.ref_predictor_score.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+        lib.ref_mlp_forward.argtypes = [vp, vp, ci, vp, vp, vp, vp, vp, vp]
+        lib.ref_mlp_forward.restype = None
         lib.ref_bf16_from_f64.argtypes = [ctypes.c_double]
         lib.ref_bf16_from_f64.restype = ctypes.c_uint16
         for f in ("ref_router_logits", "ref_topk_weights", "ref_dispatch", "ref_expert_ffn",
@@ -168,3 +170,37 @@ def predictor_score(x, wp, m):
     top = np.empty(m, dtype=np.int32)
     _load().ref_predictor_score(_p(x), _p(wp), B, d, E, m, _p(scores), _p(top))
     return scores, top
+
+
+def mlp_forward(s, weights, biases, scales, shifts):
+    """ExpertMLP forward (Section IV-B).  weights[l]: uint16 (bf16 bits) [out, in]; biases[l] fp32
+    [out]; scales[l], shifts[l] fp32 [out] for every layer but the last.  Returns the experts'
+    logits in the fixed fp32 order and in fp64."""
+    n_fc = len(weights)
+    ws = [_u16(w) for w in weights]
+    dims = np.array([ws[0].shape[1]] + [w.shape[0] for w in ws], dtype=np.int32)
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert s.shape == (dims[0],)
+    bs = [np.ascontiguousarray(b, dtype=np.float32) for b in biases]
+    sc = [np.ascontiguousarray(a, dtype=np.float32) for a in scales]
+    sh = [np.ascontiguousarray(a, dtype=np.float32) for a in shifts]
+    assert len(bs) == n_fc and len(sc) == n_fc - 1 and len(sh) == n_fc - 1
+
+    def parr(arrs, n):
+        out = (ctypes.c_void_p * n)()
+        for i, a in enumerate(arrs):
+            out[i] = a.ctypes.data
+        return out
+
+    pw, pb, psc, psh = parr(ws, n_fc), parr(bs, n_fc), parr(sc, n_fc), parr(sh, n_fc)
+    l32 = np.empty(dims[-1], dtype=np.float32)
+    l64 = np.empty(dims[-1], dtype=np.float64)
+    _load().ref_mlp_forward(_p(s), _p(dims), n_fc, ctypes.cast(pw, ctypes.c_void_p), ctypes.cast(pb, ctypes.c_void_p),
+                            ctypes.cast(psc, ctypes.c_void_p), ctypes.cast(psh, ctypes.c_void_p), _p(l32), _p(l64))
+    return l32, l64
+
+
+def top_m(scores, m):
+    """The m best (score descending, lower index on ties)."""
+    order = sorted(range(len(scores)), key=lambda e: (-float(scores[e]), e))
+    return np.array(order[:m], dtype=np.int32)

@@ -253,3 +253,67 @@ void ref_predictor_score(const uint16_t *x, const uint16_t *wp, int B, int d, in
     top[j] = best;
   }
 }
+
+/*
+ * ExpertMLP forward pass (Section IV-B): n_fc fully connected layers; every layer but the last is
+ * followed by batch normalisation (inference form: an affine map per neuron, scale and shift) and
+ * ReLU (dropout is the identity at inference); the last one yields one logit per expert, whose
+ * sigmoid is the predicted activation probability.  Weights W[l] are bf16 [dims[l+1], dims[l]],
+ * bias / scale / shift fp32.
+ *   logits64 (may be NULL): the definition in fp64.
+ *   logits32 (may be NULL): fp32 in a fixed order, which decides the top-m: element i of a dot
+ *   product belongs to bin i mod 64, each bin adds its products in ascending i with one fused
+ *   multiply-add per element, the 64 bins are summed by the butterfly (bit 5 first), then
+ *   z = acc + bias and, for a hidden layer, z = max(0, fma(z, scale, shift)).
+ */
+void ref_mlp_forward(const float *s, const int32_t *dims, int n_fc, const uint16_t *const *W,
+                     const float *const *bias, const float *const *scale, const float *const *shift,
+                     float *logits32, double *logits64) {
+  int maxd = 0;
+  for (int l = 0; l <= n_fc; ++l)
+    if (dims[l] > maxd) maxd = dims[l];
+  if (logits64) {
+    double *a = (double *)malloc(sizeof(double) * (size_t)maxd), *b = (double *)malloc(sizeof(double) * (size_t)maxd);
+    for (int i = 0; i < dims[0]; ++i) a[i] = (double)s[i];
+    for (int l = 0; l < n_fc; ++l) {
+      const int in = dims[l], out = dims[l + 1];
+      for (int n = 0; n < out; ++n) {
+        double acc = 0.0;
+        for (int i = 0; i < in; ++i) acc += a[i] * (double)bf16_f32(W[l][(size_t)n * in + i]);
+        acc += (double)bias[l][n];
+        if (l + 1 < n_fc) {
+          acc = acc * (double)scale[l][n] + (double)shift[l][n];
+          if (acc < 0.0) acc = 0.0;
+        }
+        b[n] = acc;
+      }
+      double *t = a; a = b; b = t;
+    }
+    for (int n = 0; n < dims[n_fc]; ++n) logits64[n] = a[n];
+    free(a); free(b);
+  }
+  if (logits32) {
+    float *a = (float *)malloc(sizeof(float) * (size_t)maxd), *b = (float *)malloc(sizeof(float) * (size_t)maxd);
+    for (int i = 0; i < dims[0]; ++i) a[i] = s[i];
+    for (int l = 0; l < n_fc; ++l) {
+      const int in = dims[l], out = dims[l + 1];
+      for (int n = 0; n < out; ++n) {
+        float bin[64];
+        for (int q = 0; q < 64; ++q) bin[q] = 0.0f;
+        for (int i = 0; i < in; ++i) bin[i & 63] = fmaf(a[i], bf16_f32(W[l][(size_t)n * in + i]), bin[i & 63]);
+        for (int m = 32; m >= 1; m >>= 1)
+          for (int q = 0; q < 64; ++q)
+            if ((q & m) == 0) bin[q] = bin[q] + bin[q | m];
+        float z = bin[0] + bias[l][n];
+        if (l + 1 < n_fc) {
+          z = fmaf(z, scale[l][n], shift[l][n]);
+          if (!(z > 0.0f)) z = 0.0f;
+        }
+        b[n] = z;
+      }
+      float *t = a; a = b; b = t;
+    }
+    for (int n = 0; n < dims[n_fc]; ++n) logits32[n] = a[n];
+    free(a); free(b);
+  }
+}

@@ -21,6 +21,8 @@ EXPORTS = [
     "expert_cache_prefetch", "predictor_score", "moe_prefill_layer", "moe_decode_layer",
     "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_invalidate", "moe_cache_state", "moe_set_profiling",
     "moe_get_kernel_times", "moe_dense_gemm_bf16", "moe_set_gemm_variant",
+    "predictor_mlp_score", "moe_state_create", "moe_state_destroy", "moe_state_dim", "moe_state_record",
+    "moe_state_clear", "moe_state_vector",
 ]
 
 
@@ -78,6 +80,14 @@ def load():
     lib.moe_get_kernel_times.argtypes = [vp, POINTER(c_float), POINTER(c_int32)]
     lib.moe_dense_gemm_bf16.argtypes = [vp, vp, vp, c_int, c_int, c_int, vp]
     lib.moe_set_gemm_variant.argtypes = [c_int, c_int]
+    lib.predictor_mlp_score.argtypes = [vp, vp, POINTER(c_int32), c_int, POINTER(vp), POINTER(vp), POINTER(vp),
+                                        POINTER(vp), vp, c_int, vp, vp, vp]
+    lib.moe_state_create.argtypes = [c_int, c_int, c_int, POINTER(c_float), POINTER(c_float), POINTER(vp)]
+    lib.moe_state_destroy.argtypes = [vp]
+    lib.moe_state_dim.argtypes = [vp]
+    lib.moe_state_record.argtypes = [vp, c_int, POINTER(c_int32)]
+    lib.moe_state_clear.argtypes = [vp]
+    lib.moe_state_vector.argtypes = [vp, c_int, vp]
     for name in EXPORTS:
         if name not in ("moe_last_error", "moe_workspace_bytes"):
             getattr(lib, name).restype = c_int
@@ -152,6 +162,23 @@ class MoeContext:
         _check(self.lib.predictor_score(self._h, _ptr(x), T, _ptr(wp), m, _ptr(scores), _ptr(pinned_topm),
                                         _stream(stream)))
 
+    def predictor_mlp_score(self, state, dims, weights, biases, scales, shifts, act, m, pinned_topm, stream,
+                            scores=None):
+        """state / act / scores / pinned_topm: tensors; weights / biases / scales / shifts: lists of
+        device tensors, one per layer (scales, shifts: one per hidden layer)."""
+        n_fc = len(weights)
+        dims_a = (c_int32 * (n_fc + 1))(*[int(v) for v in dims])
+
+        def parr(ts):
+            a = (c_void_p * n_fc)()
+            for i, t in enumerate(ts):
+                a[i] = t.data_ptr()
+            return a
+
+        _check(self.lib.predictor_mlp_score(self._h, _ptr(state), dims_a, n_fc, parr(weights), parr(biases),
+                                            parr(scales), parr(shifts), _ptr(act), m, _ptr(scores),
+                                            _ptr(pinned_topm), _stream(stream)))
+
     def _layer(self, fn, layer, x, T, y, ws, compute_stream, copy_stream, route_bias, bias_stride):
         _check(fn(self._h, layer, _ptr(x), T, _ptr(route_bias), bias_stride, _ptr(y), _ptr(ws),
                   ws.numel() * ws.element_size(), _stream(compute_stream), _stream(copy_stream)))
@@ -204,3 +231,37 @@ def moe_dense_gemm_bf16(a, b, c, M, N, K, stream=None):
 
 def moe_set_gemm_variant(mode: int, variant: int):
     _check(load().moe_set_gemm_variant(mode, variant))
+
+
+class MoeState:
+    """State Constructor handle (host bookkeeping of the selections of one decode round)."""
+
+    def __init__(self, n_layers, n_experts, k, popularity, affinity):
+        import numpy as np
+        self.lib = load()
+        P = np.ascontiguousarray(popularity, dtype=np.float32)
+        A = np.ascontiguousarray(affinity, dtype=np.float32)
+        assert P.shape == (n_layers, n_experts) and A.shape == (max(n_layers - 1, 0), n_experts, n_experts)
+        self._h = c_void_p()
+        _check(self.lib.moe_state_create(n_layers, n_experts, k, P.ctypes.data_as(POINTER(c_float)),
+                                         A.ctypes.data_as(POINTER(c_float)), byref(self._h)))
+        self.k = k
+
+    def close(self):
+        if self._h:
+            self.lib.moe_state_destroy(self._h)
+            self._h = c_void_p()
+
+    def moe_state_dim(self) -> int:
+        return int(self.lib.moe_state_dim(self._h))
+
+    def moe_state_record(self, layer, ids):
+        arr = (c_int32 * self.k)(*[int(i) for i in ids])
+        _check(self.lib.moe_state_record(self._h, layer, arr))
+
+    def moe_state_clear(self):
+        _check(self.lib.moe_state_clear(self._h))
+
+    def moe_state_vector(self, layer, out):
+        """out: a host tensor (plain or pinned) of moe_state_dim() fp32 values."""
+        _check(self.lib.moe_state_vector(self._h, layer, _ptr(out)))

@@ -790,6 +790,106 @@ int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, 
   return MOE_OK;
 }
 
+int predictor_mlp_score(moe_ctx *ctx, const float *state, const int32_t *host_dims, int n_fc,
+                        const void *const *dev_w, const float *const *dev_bias,
+                        const float *const *dev_scale, const float *const *dev_shift, float *dev_act,
+                        int m, float *dev_scores, int32_t *pinned_topm, void *stream) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  if (!state || !host_dims || !dev_w || !dev_bias || !dev_scale || !dev_shift || !dev_act || !pinned_topm)
+    return fail(MOE_E_ARG, "NULL pointer in predictor_mlp_score");
+  if (n_fc < 2 || n_fc > 16) return fail(MOE_E_ARG, "n_fc = %d, need 2..16", n_fc);
+  int maxd = 0;
+  for (int l = 0; l <= n_fc; ++l) {
+    if (host_dims[l] <= 0) return fail(MOE_E_ARG, "host_dims[%d] = %d", l, host_dims[l]);
+    if (host_dims[l] > maxd) maxd = host_dims[l];
+  }
+  if (host_dims[n_fc] > kMaxExperts) return fail(MOE_E_UNSUPPORTED, "more than %d outputs", kMaxExperts);
+  if (m <= 0 || m > host_dims[n_fc]) return fail(MOE_E_ARG, "need 1 <= m <= number of outputs");
+  const uint16_t *w[16];
+  for (int l = 0; l < n_fc; ++l) {
+    if (!dev_w[l] || !dev_bias[l] || (l + 1 < n_fc && (!dev_scale[l] || !dev_shift[l])))
+      return fail(MOE_E_ARG, "NULL parameter pointer of layer %d", l);
+    w[l] = reinterpret_cast<const uint16_t *>(dev_w[l]);
+  }
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  Timer t(ctx, s, MOE_K_PREDICTOR);
+  HIP_TRY(launch_mlp_predictor(state, host_dims, n_fc, w, dev_bias, dev_scale, dev_shift, dev_act, dev_act + maxd, m,
+                               dev_scores ? dev_scores : ctx->dev_scores, pinned_topm, s));
+  return MOE_OK;
+}
+
+// ---- State Constructor: host bookkeeping only ---------------------------------------------
+}  // extern "C"
+struct moe_state {
+  int L = 0, M = 0, k = 0;
+  std::vector<float> P, A;          // [L, M], [L-1, M, M]
+  std::vector<int32_t> ids;         // [L, k]
+  std::vector<char> have;           // [L]
+};
+extern "C" {
+
+int moe_state_create(int n_layers, int n_experts, int k, const float *host_popularity,
+                     const float *host_affinity, moe_state **out) {
+  if (!out || !host_popularity || (n_layers > 1 && !host_affinity)) return fail(MOE_E_ARG, "NULL argument");
+  if (n_layers <= 0 || n_experts <= 0 || k <= 0 || k > n_experts) return fail(MOE_E_ARG, "bad sizes");
+  moe_state *st = new (std::nothrow) moe_state();
+  if (!st) return fail(MOE_E_HIP, "out of host memory");
+  st->L = n_layers;
+  st->M = n_experts;
+  st->k = k;
+  st->P.assign(host_popularity, host_popularity + (size_t)n_layers * n_experts);
+  if (n_layers > 1)
+    st->A.assign(host_affinity, host_affinity + (size_t)(n_layers - 1) * n_experts * n_experts);
+  st->ids.assign((size_t)n_layers * k, 0);
+  st->have.assign(n_layers, 0);
+  *out = st;
+  return MOE_OK;
+}
+
+int moe_state_destroy(moe_state *st) {
+  delete st;
+  return MOE_OK;
+}
+
+int moe_state_dim(const moe_state *st) { return st ? st->L * st->k + st->M + st->k * st->M : 0; }
+
+int moe_state_record(moe_state *st, int layer, const int32_t *host_ids) {
+  if (!st || !host_ids) return fail(MOE_E_ARG, "NULL argument");
+  if (layer < 0 || layer >= st->L) return fail(MOE_E_ARG, "layer %d out of range", layer);
+  for (int q = 0; q < st->k; ++q)
+    if (host_ids[q] < 0 || host_ids[q] >= st->M) return fail(MOE_E_ARG, "expert id %d out of range", host_ids[q]);
+  for (int q = 0; q < st->k; ++q) st->ids[(size_t)layer * st->k + q] = host_ids[q];
+  st->have[layer] = 1;
+  return MOE_OK;
+}
+
+int moe_state_clear(moe_state *st) {
+  if (!st) return fail(MOE_E_ARG, "NULL argument");
+  st->have.assign(st->L, 0);
+  return MOE_OK;
+}
+
+int moe_state_vector(const moe_state *st, int layer, float *host_out) {
+  if (!st || !host_out) return fail(MOE_E_ARG, "NULL argument");
+  if (layer < 0 || layer >= st->L) return fail(MOE_E_ARG, "layer %d out of range", layer);
+  for (int j = 0; j < layer; ++j)
+    if (!st->have[j]) return fail(MOE_E_ARG, "layer %d has not been recorded in this round", j);
+  const int L = st->L, M = st->M, k = st->k;
+  const int dim = L * k + M + k * M;
+  for (int i = 0; i < dim; ++i) host_out[i] = 0.0f;
+  for (int j = 0; j < layer; ++j)
+    for (int q = 0; q < k; ++q)
+      host_out[j * k + q] = (float)((double)(st->ids[(size_t)j * k + q] + 1) / (double)M);
+  for (int i = 0; i < M; ++i) host_out[L * k + i] = st->P[(size_t)layer * M + i];
+  if (layer > 0)
+    for (int q = 0; q < k; ++q) {
+      const int e = st->ids[(size_t)(layer - 1) * k + q];
+      const float *row = st->A.data() + ((size_t)(layer - 1) * M + e) * M;
+      for (int i = 0; i < M; ++i) host_out[L * k + M + q * M + i] = row[i];
+    }
+  return MOE_OK;
+}
+
 int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
                       int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
                       void *compute_stream, void *copy_stream) {

@@ -25,6 +25,13 @@ hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float
 
 // Predictor stand-in: scores[e] = sum_t x[t].wp[e] (same summation order per token, tokens
 // ascending), top-m ids to `top_out` (device-visible, e.g. pinned host memory).
+// ExpertMLP predictor (Section IV-B): n_fc layers, dims[0..n_fc]; w[l] bf16 [dims[l+1], dims[l]],
+// bias / scale / shift fp32 (scale, shift: hidden layers only); state fp32 [dims[0]] (device-visible);
+// act0 / act1: fp32 scratch of max(dims) each; scores [dims[n_fc]]; top_out [m] (device-visible).
+hipError_t launch_mlp_predictor(const float *state, const int32_t *dims, int n_fc, const uint16_t *const *w,
+                                const float *const *bias, const float *const *scale, const float *const *shift,
+                                float *act0, float *act1, int m, float *scores, int32_t *top_out,
+                                hipStream_t stream);
 hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
                             float *scores, int32_t *top_out, hipStream_t stream);
 

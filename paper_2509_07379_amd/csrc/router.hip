@@ -167,6 +167,30 @@ __global__ __launch_bounds__(kRouterThreads) void predictor_scores_kernel(
   if (lane == 0) scores[e] = s;
 }
 
+// One fully connected layer of the ExpertMLP predictor (Section IV-B) for one input vector:
+// out[n] = act(W[n,:] . in + bias[n]), act = ReLU(scale * z + shift) for hidden layers (batch
+// normalisation in inference form), identity for the last.  One wave per neuron; the fp32 sum is
+// taken in a fixed order that a scalar replay can follow: element i belongs to lane i mod 64, each
+// lane adds its products in ascending i with one fused multiply-add per element, then the butterfly.
+// in / out are fp32; `in` may live in pinned host memory (the state vector is built on the host).
+__global__ __launch_bounds__(kRouterThreads) void mlp_layer_kernel(
+    const float *__restrict__ in, const uint16_t *__restrict__ w, const float *__restrict__ bias,
+    const float *__restrict__ scale, const float *__restrict__ shift, int n_in, int n_out,
+    float *__restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * kRouterWaves + (threadIdx.x >> 6);
+  if (n >= n_out) return;
+  const uint16_t *wrow = w + (size_t)n * n_in;
+  float acc = 0.0f;
+  for (int i = lane; i < n_in; i += 64) acc = fmaf(in[i], bf16_to_f32(wrow[i]), acc);
+  float z = wave_sum_tree(acc) + bias[n];
+  if (scale) {
+    z = fmaf(z, scale[n], shift[n]);
+    if (!(z > 0.0f)) z = 0.0f;
+  }
+  if (lane == 0) out[n] = z;
+}
+
 __global__ __launch_bounds__(64) void predictor_topm_kernel(const float *__restrict__ scores, int E,
                                                             int m, int32_t *__restrict__ top_out) {
   const int lane = threadIdx.x;
@@ -199,6 +223,25 @@ hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float
     hipLaunchKernelGGL((router_topk_kernel<TPB, 16>), dim3(T), dim3(1024), smem, stream, x, wr, bias,
                        bias_stride, T, d, E, k, renormalize, logits, ids, w, one ? *one : none);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_mlp_predictor(const float *state, const int32_t *dims, int n_fc, const uint16_t *const *w,
+                                const float *const *bias, const float *const *scale, const float *const *shift,
+                                float *act0, float *act1, int m, float *scores, int32_t *top_out,
+                                hipStream_t stream) {
+  const float *in = state;
+  for (int l = 0; l < n_fc; ++l) {
+    const bool last = l + 1 == n_fc;
+    float *out = last ? scores : ((l & 1) ? act1 : act0);
+    const int grid = (dims[l + 1] + kRouterWaves - 1) / kRouterWaves;
+    hipLaunchKernelGGL(mlp_layer_kernel, dim3(grid), dim3(kRouterThreads), 0, stream, in, w[l], bias[l],
+                       last ? nullptr : scale[l], last ? nullptr : shift[l], dims[l], dims[l + 1], out);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    in = out;
+  }
+  hipLaunchKernelGGL(predictor_topm_kernel, dim3(1), dim3(64), 0, stream, scores, dims[n_fc], m, top_out);
   return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ def _load():
 # ---------------------------------------------------------------------------
 # stream ids: one Gaussian stream per (tensor kind, layer, expert)
 # ---------------------------------------------------------------------------
-KIND_X, KIND_ROUTER, KIND_EXPERT, KIND_SHARED, KIND_PREDICTOR, KIND_ATTN = range(6)
+KIND_X, KIND_ROUTER, KIND_EXPERT, KIND_SHARED, KIND_PREDICTOR, KIND_ATTN, KIND_MLP = range(7)
 
 
 def stream_id(kind: int, layer: int = 0, index: int = 0, step: int = 0) -> int:
@@ -218,3 +218,29 @@ def trace_route_bias(ids_tk: np.ndarray, E: int, boost: float = 64.0) -> np.ndar
     b = np.zeros((T, E), dtype=np.float32)
     b[np.arange(T)[:, None], ids_tk] = boost
     return b
+
+
+# ---------------------------------------------------------------------------
+# ExpertMLP predictor (Section IV-B): shapes and seeded, untrained parameters
+# ---------------------------------------------------------------------------
+MLP_HIDDEN = (2048, 1024, 512, 256, 128, 64, 64)   # seven hidden layers, 2048 down to 64
+
+
+def mlp_dims(L: int, E: int, k: int):
+    """Layer sizes: state vector (L*k + E + k*E) -> seven hidden layers -> E logits."""
+    return [L * k + E + k * E, *MLP_HIDDEN, E]
+
+
+def mlp_params(dims, seed: int, layer: int = 0):
+    """He-scaled bf16 weights [out, in], small fp32 biases, batch-norm affine (scale near 1, small
+    shift) for every layer but the last.  Returns (weights, biases, scales, shifts)."""
+    ws, bs, sc, sh = [], [], [], []
+    n_fc = len(dims) - 1
+    for l in range(n_fc):
+        fan_in, out = dims[l], dims[l + 1]
+        ws.append(normal_bf16((out, fan_in), seed, stream_id(KIND_MLP, layer, 4 * l), float(np.sqrt(2.0 / fan_in))))
+        bs.append(normal_f32((out,), seed, stream_id(KIND_MLP, layer, 4 * l + 1), 0.05))
+        if l + 1 < n_fc:
+            sc.append((1.0 + normal_f32((out,), seed, stream_id(KIND_MLP, layer, 4 * l + 2), 0.1)).astype(np.float32))
+            sh.append(normal_f32((out,), seed, stream_id(KIND_MLP, layer, 4 * l + 3), 0.1))
+    return ws, bs, sc, sh

@@ -1,4 +1,5 @@
 """The C-ABI library loads without a GPU and exports every function the header declares."""
+import pytest
 import ctypes
 import os
 import re
@@ -34,3 +35,34 @@ def test_argument_errors_without_gpu():
     assert lib.moe_workspace_bytes(ctypes.byref(cfg), 4) == 0
     ok = binding.MoeConfig(4096, 14336, 8, 2, 1, 2, 0, 1)
     assert lib.moe_workspace_bytes(ctypes.byref(ok), 2048) > 2048 * 2 * 14336 * 2
+
+
+def test_state_constructor_matches_the_oracle():
+    """Host-only bookkeeping (no GPU call): the predictor's input vector, Eq. 4-5."""
+    import numpy as np
+    import torch
+    from oracle import predictor as P
+    from paper_2509_07379_amd import binding, synth as S
+    w = S.Workload("state", d=64, I=64, E=8, k=2, T=1, seed=9, L=5, steps=300, p_stay=0.6)
+    trace = S.markov_trace(w)
+    trace = trace[:, :, 0, :] if trace.ndim == 4 else trace
+    pop, aff = P.popularity(trace, w.E), P.affinity(trace, w.E)
+    st = binding.MoeState(w.L, w.E, w.k, pop, aff)
+    dim = st.moe_state_dim()
+    assert dim == P.state_dim(w.L, w.E, w.k)
+    out = torch.zeros(dim, dtype=torch.float32)
+    pop32, aff32 = pop.astype(np.float32).astype(np.float64), aff.astype(np.float32).astype(np.float64)
+    for episode in (3, 17):
+        st.moe_state_clear()
+        with pytest.raises(binding.MoeError):
+            st.moe_state_vector(1, out)              # layer 0 not recorded yet in this round
+        history = []
+        for l in range(w.L):
+            st.moe_state_vector(l, out)
+            want = P.state_vector(history, l, pop32, aff32, w.k)
+            np.testing.assert_array_equal(out.numpy(), want)
+            st.moe_state_record(l, trace[episode, l])
+            history.append(list(trace[episode, l]))
+    with pytest.raises(binding.MoeError):
+        st.moe_state_record(0, [0, w.E])             # id out of range
+    st.close()

@@ -1,4 +1,6 @@
 """Parity of the HIP path (through the C ABI) with the CPU oracle.  Needs an MI355X."""
+from dataclasses import replace
+
 import numpy as np
 import pytest
 
@@ -268,6 +270,103 @@ def test_shared_cache_prefill_streams_every_layer_through_two_slots(gpu, oracle)
         active = int((ref["counts"] > 0).sum())
         extra = sum(1 for e in (0, 1) if ref["counts"][e] == 0)   # speculative fetches without tokens
         assert ctx.moe_get_stats(l)["bytes_h2d"] == (active + extra) * w.blob_bytes
+    ctx.close()
+
+
+# ---------------------------------------------------------------- ExpertMLP predictor (Section IV-B)
+def mlp_on_device(H, dims, params):
+    ws, bs, sc, sh = params
+    dev = lambda arrs: [H.np_to_dev(a) for a in arrs]
+    act = torch.empty(2 * max(dims), dtype=torch.float32, device="cuda")
+    return dev(ws), dev(bs), dev(sc), dev(sh), act
+
+
+@pytest.mark.parametrize("L,E,k,m", [(32, 8, 2, 2), (24, 60, 4, 8), (3, 64, 6, 64)])
+def test_mlp_predictor_scores_bit_exact(gpu, oracle, L, E, k, m):
+    """Seven hidden layers 2048 .. 64 and E logits: the fp32 sums follow the documented order, so the
+    logits equal the oracle's replay bit for bit and the top-m is the same list."""
+    H, B = gpu["harness"], gpu["binding"]
+    dims = S.mlp_dims(L, E, k)
+    params = S.mlp_params(dims, 41 + E)
+    ws, bs, sc, sh, act = mlp_on_device(H, dims, params)
+    ctx = B.MoeContext(256, 128, E, k, 1, E)
+    scores = torch.empty(E, dtype=torch.float32, device="cuda")
+    top = torch.zeros(m, dtype=torch.int32).pin_memory()
+    pred = torch.cuda.Stream()
+    for trial in range(3):
+        state_np = np.abs(S.normal_f32((dims[0],), 7, 500 + trial, 0.3))
+        state = torch.from_numpy(state_np).pin_memory()          # the state vector is built on the host
+        ctx.predictor_mlp_score(state, dims, ws, bs, sc, sh, act, m, top, pred, scores)
+        pred.synchronize()
+        l32, l64 = oracle.mlp_forward(state_np, *params)
+        np.testing.assert_array_equal(scores.cpu().numpy(), l32)
+        np.testing.assert_array_equal(top.numpy(), oracle.top_m(l32, m))
+        assert np.abs(l32 - l64).max() <= 1e-4 * max(1.0, np.abs(l64).max())
+    ctx.close()
+
+
+def test_paper_decode_flow_state_constructor_mlp_and_one_cache(gpu, oracle):
+    """Section V-C end to end on a small model: the first layer of a step is served on demand; every
+    layer's selection goes to the State Constructor; its vector for the next layer feeds ExpertMLP on a
+    third stream; the predicted experts are prefetched into the one cache of k slots; wrong guesses are
+    fetched again; the state is cleared after the round.  Checked against oracle and simulator."""
+    from oracle import predictor as P
+    from oracle.cache_sim import SharedCacheSim
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("paper_flow", d=256, I=128, E=8, k=2, T=1, seed=29, L=4, steps=4, p_stay=0.6)
+    history_trace = S.markov_trace(replace(w, seed=30, steps=500))     # the "preprocessing" traces
+    history_trace = history_trace[:, :, 0, :] if history_trace.ndim == 4 else history_trace
+    pop = P.popularity(history_trace, w.E).astype(np.float32)
+    aff = P.affinity(history_trace, w.E).astype(np.float32)
+    st = B.MoeState(w.L, w.E, w.k, pop, aff)
+    dims = S.mlp_dims(w.L, w.E, w.k)
+    params = [S.mlp_params(dims, 77, l) for l in range(w.L)]           # one predictor per target layer
+    dev_params = [mlp_on_device(H, dims, p) for p in params]
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, w.k, 0, True, shared_slots=True)
+    pools = [H.HostPool(w, l) for l in range(w.L)]
+    cache = torch.full((w.k, w.blob_elems), 0x7FC0, dtype=torch.int16, device="cuda")
+    lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
+    sim = SharedCacheSim(w.L, w.E, w.k, w.blob_bytes)
+    trace = S.markov_trace(w)
+    buf = H.Buffers(ctx, w.T)
+    pred = torch.cuda.Stream()
+    top = torch.zeros(w.k, dtype=torch.int32).pin_memory()
+    state = torch.zeros(st.moe_state_dim(), dtype=torch.float32).pin_memory()
+    for s in range(w.steps):
+        history = []
+        for l in range(w.L):
+            x_np = S.activations(w, l, s)
+            bias_np = S.trace_route_bias(trace[s, l], w.E)
+            ctx.moe_decode_layer(l, H.np_to_dev(x_np), w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"],
+                                 torch.from_numpy(bias_np).cuda(), w.E)
+            gpu["compute"].synchronize()
+            ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k,
+                                   bias=bias_np, I=w.I)
+            ids = buf.routing(ctx, gpu["compute"])["ids"][0]
+            np.testing.assert_array_equal(ids, ref["ids"][0])
+            check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"paper flow step {s} layer {l}")
+            sim.serve(l, ref["ids"][0])
+            assert ctx.moe_cache_state(l) == sim.state(l)
+            st.moe_state_record(l, ids)
+            history.append([int(i) for i in ref["ids"][0]])
+            if l + 1 == w.L:
+                continue
+            st.moe_state_vector(l + 1, state)
+            want_state = P.state_vector(history, l + 1, pop.astype(np.float64), aff.astype(np.float64), w.k)
+            np.testing.assert_array_equal(state.numpy(), want_state)
+            dws, dbs, dsc, dsh, act = dev_params[l + 1]
+            ctx.predictor_mlp_score(state, dims, dws, dbs, dsc, dsh, act, w.k, top, pred)
+            pred.synchronize()
+            l32, _ = oracle.mlp_forward(want_state, *params[l + 1])
+            np.testing.assert_array_equal(top.numpy(), oracle.top_m(l32, w.k))
+            ctx.expert_cache_prefetch(l + 1, top.tolist(), gpu["copy"])
+            sim.prefetch(l + 1, oracle.top_m(l32, w.k))
+        st.moe_state_clear()
+    torch.cuda.synchronize()
+    for l in range(w.L):
+        assert ctx.moe_get_stats(l) == {**sim.counters(l), "layer_calls": w.steps}
+    assert ctx.moe_get_stats(0)["hits"] == 0          # no prediction for the first layer: always on demand
+    st.close()
     ctx.close()
 
 
