@@ -229,6 +229,32 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
     return out
 
 
+def mlp_predictor_latency(torch, B, H, S, w, pred):
+    """One ExpertMLP prediction (Section IV-B) for the decode workload's model: state vector in pinned
+    memory, eight fully connected layers and the top-k on the prediction stream; microseconds each."""
+    import numpy as np
+    dims = S.mlp_dims(w.L, w.E, w.k)
+    ws, bs, sc, sh = S.mlp_params(dims, w.seed)
+    dev = lambda arrs: [H.np_to_dev(a) for a in arrs]
+    dws, dbs, dsc, dsh = dev(ws), dev(bs), dev(sc), dev(sh)
+    act = torch.empty(2 * max(dims), dtype=torch.float32, device="cuda")
+    state = torch.from_numpy(np.abs(S.normal_f32((dims[0],), w.seed, 12345, 0.3))).pin_memory()
+    top = torch.zeros(w.k, dtype=torch.int32).pin_memory()
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E)
+    for _ in range(10):
+        ctx.predictor_mlp_score(state, dims, dws, dbs, dsc, dsh, act, w.k, top, pred)
+    pred.synchronize()
+    t0 = time.perf_counter()
+    n = 200
+    for _ in range(n):
+        ctx.predictor_mlp_score(state, dims, dws, dbs, dsc, dsh, act, w.k, top, pred)
+    pred.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / n
+    ctx.close()
+    params_mb = sum(a.nbytes for a in ws + bs + sc + sh) / 1e6
+    return {"us_per_prediction": us, "layers": dims, "parameter_MB": params_mb}
+
+
 def cpu_baseline(args, S, w, res, n_tokens):
     """The CPU oracle on a bounded sample: full routing + dispatch, expert math on n_tokens tokens."""
     import numpy as np
@@ -359,6 +385,7 @@ def main():
             # the paper's cache: one set of k slots for all layers, predictor top-k, first layer on demand
             "shared_k_us_per_layer": dec["shared_k"]["us_per_layer"], "shared_k_slots": wd.k,
             "shared_k_stats": dec["shared_k"]["stats"],
+            "mlp_predictor": mlp_predictor_latency(torch, B, H, S, wd, pred),
         }
         log(f"[bench] decode: {line['decode']}")
 
