@@ -4,6 +4,7 @@
  * One Mixture-of-Experts FFN layer served from an offloaded expert pool, after the
  * inference runtime of DuoServe-MoE (Section V of the paper): every expert lives in
  * a pinned "CPU expert cache", a small "GPU expert cache" of S slots per layer is
+ * (or, with cfg.shared_slots, of S slots for all layers) is
  * filled by a communication stream just before the experts run (Section V-A), the
  * prefill stage pipelines "compute expert i / fetch expert i+1" (Section V-B) and the
  * decode stage prefetches the experts a per-layer predictor names and re-fetches on
@@ -17,7 +18,10 @@
  *    the library owns only bookkeeping (slot tables, events, a few KB of pinned
  *    mailboxes).  bf16 tensors are raw 16-bit patterns, row-major.
  *  - Streams are hipStream_t handles passed as void* (NULL = the default stream).
- *    Calls enqueue work and return; they block the host only where stated.
+ *    Calls enqueue work and return; they block the host only where stated.  A layer
+ *    call may run part of its work (the shared experts) on a stream of the library's
+ *    own, forked from and joined back into compute_stream inside the call: everything
+ *    a call enqueues is complete when compute_stream reaches the end of the call.
  *  - Every function returns 0 on success or a negative MOE_E_* code and never throws
  *    or aborts; moe_last_error() returns a thread-local message for the last failure.
  *  - One ctx serves one (compute stream, copy stream) pair at a time; calls on the
@@ -179,7 +183,9 @@ int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
  * One MoE layer in the decode stage (Section V-C), T = batch (small).  Same contract and
  * results as moe_prefill_layer; experts run as bandwidth-bound GEMVs.  The gate's choice is
  * compared with the cache ("synchronisation point 1"): hits run first, misses are
- * re-fetched on copy_stream and run as they land.
+ * re-fetched on copy_stream and run as they land.  The host looks at the gate's counts
+ * (a short wait on a pinned mailbox) unless every expert is resident, T = 1 and E <= 16,
+ * in which case the call only enqueues.
  */
 int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
                      const float *dev_route_bias, int bias_stride, void *dev_y,
