@@ -60,7 +60,20 @@ typedef struct {
   int32_t shared_slots;/* 0: every layer has its own cache of cache_slots slots; 1: ONE cache of
                           cache_slots slots serves all layers in turn (Section V-A: a GPU expert
                           cache of k experts, refilled layer after layer) */
+  int32_t host_format; /* MOE_FMT_*: how an expert is stored in the CPU expert cache and travels
+                          over the host link */
 } moe_config;
+
+/* moe_config.host_format.
+ * MOE_FMT_BF16: the blob is the three bf16 matrices, copied straight into a slot.
+ * MOE_FMT_E4M3_ROWS: 8-bit weights (the paper serves quantised models, Section VI; the format is this
+ *   library's): [scale fp32: 2I rows of W_gate/W_up, then d rows of W_down][W_gate codes I x d]
+ *   [W_up codes I x d][W_down codes d x I], codes = OCP e4m3 (1-4-3 bits, bias 7, max 448, 0x7F NaN).
+ *   A fetched expert lands in a staging area behind the slots and is expanded into its slot on the
+ *   copy stream: weight = bf16 nearest-even of fp32(value(code) * scale[row]).  Slots, matmuls and
+ *   results are those of MOE_FMT_BF16 run on the expanded weights; the link carries half the bytes. */
+#define MOE_FMT_BF16 0
+#define MOE_FMT_E4M3_ROWS 1
 
 /* Cache counters (host side).  hits/misses count active experts per layer call. */
 typedef struct {
@@ -82,19 +95,26 @@ int moe_create(const moe_config *cfg, moe_ctx **out);
  * device is idle. */
 int moe_destroy(moe_ctx *ctx);
 
+/* Bytes of one expert in the CPU expert cache: 6*d*I (bf16) or 4*(2I+d) + 3*d*I (e4m3 rows). */
+size_t moe_host_blob_bytes(const moe_config *cfg);
+/* Bytes of one GPU expert cache (dev_slots of moe_bind_layer): cache_slots slots of 6*d*I bytes,
+ * followed, for an 8-bit host format, by one staging area per slot. */
+size_t moe_cache_bytes(const moe_config *cfg);
+
 /* Bytes of device workspace a layer call on T tokens needs (256-byte aligned base). */
 size_t moe_workspace_bytes(const moe_config *cfg, int T);
 
 /*
  * Attaches a layer's memory (Section V-A: CPU expert cache, GPU expert cache).
- *  host_expert_blob[E]  pinned; each 6*d*I bytes: W_gate (I x d), W_up (I x d), W_down (d x I),
- *                       row-major bf16, one contiguous blob per expert (= one DMA per expert).
+ *  host_expert_blob[E]  pinned; each moe_host_blob_bytes: W_gate (I x d), W_up (I x d), W_down (d x I),
+ *                       row-major bf16 (or the 8-bit layout of cfg.host_format), one contiguous
+ *                       blob per expert (= one DMA per expert).
  *  dev_router_w         [E, d] bf16 gate weight.
  *  dev_shared_blob      NULL, or 6*d*I_shared bytes in the same layout (always resident).
- *  dev_slots            S * 6*d*I bytes: the layer's GPU expert cache (with shared_slots: the one
- *                       cache, the same pointer for every layer).
+ *  dev_slots            moe_cache_bytes: the layer's GPU expert cache, slot s at s * 6*d*I (with
+ *                       shared_slots: the one cache, the same pointer for every layer).
  *  initial_resident     NULL (all slots empty) or [S] expert ids / -1: slot s already holds
- *                       that expert's blob (the caller copied it there).
+ *                       that expert's bf16 blob (the caller put it there).
  * The pointers are read, not copied.
  */
 int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,

@@ -43,6 +43,10 @@ def _load():
         lib.ref_predictor_score.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
         lib.ref_mlp_forward.argtypes = [vp, vp, ci, vp, vp, vp, vp, vp, vp]
         lib.ref_mlp_forward.restype = None
+        lib.ref_e4m3_value.argtypes = [ci]
+        lib.ref_e4m3_value.restype = ctypes.c_float
+        lib.ref_dequant_e4m3_rows.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
+        lib.ref_dequant_e4m3_rows.restype = None
         lib.ref_bf16_from_f64.argtypes = [ctypes.c_double]
         lib.ref_bf16_from_f64.restype = ctypes.c_uint16
         for f in ("ref_router_logits", "ref_topk_weights", "ref_dispatch", "ref_expert_ffn",
@@ -204,3 +208,22 @@ def top_m(scores, m):
     """The m best (score descending, lower index on ties)."""
     order = sorted(range(len(scores)), key=lambda e: (-float(scores[e]), e))
     return np.array(order[:m], dtype=np.int32)
+
+
+def e4m3_value(code: int) -> float:
+    return float(_load().ref_e4m3_value(int(code)))
+
+
+def dequant_blob(qblob, d: int, I: int) -> np.ndarray:
+    """8-bit expert blob ([scales fp32: 2I, d][W_gate codes][W_up codes][W_down codes]) -> the bf16 blob
+    ([W_gate; W_up] (2I x d), W_down (d x I)) the layer computes with."""
+    q = np.ascontiguousarray(qblob).view(np.uint8).ravel()
+    sb = 4 * (2 * I + d)
+    assert q.size == sb + 3 * d * I
+    scales = q[:sb].view(np.float32)
+    out = np.empty(3 * d * I, dtype=np.uint16)
+    codes = q[sb:]
+    lib = _load()
+    lib.ref_dequant_e4m3_rows(_p(codes[:2 * I * d]), _p(scales[:2 * I]), 2 * I, d, _p(out[:2 * I * d]))
+    lib.ref_dequant_e4m3_rows(_p(codes[2 * I * d:]), _p(scales[2 * I:]), d, I, _p(out[2 * I * d:]))
+    return out

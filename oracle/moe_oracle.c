@@ -317,3 +317,29 @@ void ref_mlp_forward(const float *s, const int32_t *dims, int n_fc, const uint16
     free(a); free(b);
   }
 }
+
+/*
+ * Expert weights that travel over the host link as 8-bit floats (the paper evaluates quantised
+ * models, Section VI; the format here is this build's reading: OCP e4m3 codes with one fp32 scale
+ * per output row).  A weight is  bf16_rne( fp32( value(code) * scale ) ):  the code's value is exact
+ * in fp32, the product is rounded once to fp32 and once more to bf16, in that order.
+ *   value(code): sign s, exponent field e (4 bits, bias 7), mantissa field m (3 bits):
+ *     e > 0: (-1)^s * 2^(e-7) * (1 + m/8);   e = 0: (-1)^s * 2^-6 * (m/8);   e = 15, m = 7: NaN.
+ */
+float ref_e4m3_value(int code) {
+  int s = (code >> 7) & 1, e = (code >> 3) & 15, m = code & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m / 8.0, -6);
+  else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return (float)(s ? -v : v);
+}
+
+void ref_dequant_e4m3_rows(const uint8_t *q, const float *scales, int64_t rows, int64_t cols, uint16_t *out_bf16) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      float prod = ref_e4m3_value(q[r * cols + c]) * scales[r];
+      out_bf16[r * cols + c] = bf16_from_f64((double)prod);
+    }
+}

@@ -22,13 +22,13 @@ EXPORTS = [
     "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_invalidate", "moe_cache_state", "moe_set_profiling",
     "moe_get_kernel_times", "moe_dense_gemm_bf16", "moe_set_gemm_variant",
     "predictor_mlp_score", "moe_state_create", "moe_state_destroy", "moe_state_dim", "moe_state_record",
-    "moe_state_clear", "moe_state_vector",
+    "moe_state_clear", "moe_state_vector", "moe_host_blob_bytes", "moe_cache_bytes",
 ]
 
 
 class MoeConfig(Structure):
     _fields_ = [(n, c_int32) for n in
-                ("d", "I", "E", "k", "n_layers", "cache_slots", "I_shared", "renormalize", "shared_slots")]
+                ("d", "I", "E", "k", "n_layers", "cache_slots", "I_shared", "renormalize", "shared_slots", "host_format")]
 
 
 class MoeStats(Structure):
@@ -88,8 +88,11 @@ def load():
     lib.moe_state_record.argtypes = [vp, c_int, POINTER(c_int32)]
     lib.moe_state_clear.argtypes = [vp]
     lib.moe_state_vector.argtypes = [vp, c_int, vp]
+    for name in ("moe_host_blob_bytes", "moe_cache_bytes"):
+        getattr(lib, name).argtypes = [POINTER(MoeConfig)]
+        getattr(lib, name).restype = c_size_t
     for name in EXPORTS:
-        if name not in ("moe_last_error", "moe_workspace_bytes"):
+        if name not in ("moe_last_error", "moe_workspace_bytes", "moe_host_blob_bytes", "moe_cache_bytes"):
             getattr(lib, name).restype = c_int
     _lib = lib
     return lib
@@ -121,10 +124,10 @@ class MoeContext:
     """Owner of a moe_ctx handle; methods carry the C function names."""
 
     def __init__(self, d, I, E, k, n_layers=1, cache_slots=None, I_shared=0, renormalize=True,
-                 shared_slots=False):
+                 shared_slots=False, host_format=0):
         self.lib = load()
         self.cfg = MoeConfig(d, I, E, k, n_layers, E if cache_slots is None else cache_slots, I_shared,
-                             1 if renormalize else 0, 1 if shared_slots else 0)
+                             1 if renormalize else 0, 1 if shared_slots else 0, int(host_format))
         self._h = c_void_p()
         _check(self.lib.moe_create(byref(self.cfg), byref(self._h)))
         self._keep = {}
@@ -142,6 +145,12 @@ class MoeContext:
 
     def moe_workspace_bytes(self, T: int) -> int:
         return int(self.lib.moe_workspace_bytes(byref(self.cfg), T))
+
+    def moe_host_blob_bytes(self) -> int:
+        return int(self.lib.moe_host_blob_bytes(byref(self.cfg)))
+
+    def moe_cache_bytes(self) -> int:
+        return int(self.lib.moe_cache_bytes(byref(self.cfg)))
 
     def moe_bind_layer(self, layer, host_blob_ptrs, router_w, shared_blob, slots, initial_resident=None):
         E, S = self.cfg.E, self.cfg.cache_slots

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_offload.so")
-SOURCES = ["router.hip", "dispatch.hip", "gemm.hip", "gemv.hip", "combine.hip", "api.hip"]
+SOURCES = ["router.hip", "dispatch.hip", "gemm.hip", "gemv.hip", "combine.hip", "dequant.hip", "api.hip"]
 # packed fp32 instructions stay off (the flag is a device-side target feature; the host pass
 # prints a harmless "not a recognized feature" note)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -133,7 +133,9 @@ struct TimedLaunch {
 struct moe_ctx {
   moe_config cfg{};
   int device = 0;
-  size_t blob_bytes = 0;
+  size_t blob_bytes = 0;        // one slot: the bf16 blob, 6*d*I
+  size_t host_blob_bytes = 0;   // one expert in the CPU expert cache (bf16: the same; e4m3: scales + codes)
+  size_t stage_stride = 0;      // e4m3: bytes of one slot's staging area behind the slots (256-aligned)
   std::vector<Layer> layers;
   std::unique_ptr<SlotSet> shared_set;   // cfg.shared_slots: the one cache all layers use
   int32_t *pinned_counts = nullptr;   // mailbox the dispatch kernel fills: [kMaxExperts] counts, then the call's number
@@ -160,6 +162,8 @@ int check_cfg(const moe_config *c) {
   if (c->E > kMaxExperts) return fail(MOE_E_UNSUPPORTED, "E = %d > %d experts", c->E, kMaxExperts);
   if (c->d % 8 || c->I % 8 || c->I_shared % 8)
     return fail(MOE_E_UNSUPPORTED, "d, I and I_shared must be multiples of 8");
+  if (c->host_format != MOE_FMT_BF16 && c->host_format != MOE_FMT_E4M3_ROWS)
+    return fail(MOE_E_ARG, "host_format = %d is not a known format", c->host_format);
   return MOE_OK;
 }
 
@@ -235,7 +239,28 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   }
   char *dst = L.set->slots + (size_t)s * ctx->blob_bytes;
   const char *src = static_cast<const char *>(L.host_blob[e]);
-  if (split) {
+  const moe_config &c = ctx->cfg;
+  if (c.host_format == MOE_FMT_E4M3_ROWS) {
+    // [scales: 2I gate/up rows, d down rows][gate codes][up codes][down codes] lands in the slot's
+    // staging area; a kernel behind each copy, on the same stream, expands it into the slot.  The
+    // stream's order also keeps the next copy into this staging area behind that expansion.
+    char *stage = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes + (size_t)s * ctx->stage_stride;
+    const size_t scale_bytes = (size_t)4 * (2 * c.I + c.d), up_codes = (size_t)2 * c.I * c.d;
+    const float *scales = reinterpret_cast<const float *>(stage);
+    const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + scale_bytes);
+    uint16_t *w = reinterpret_cast<uint16_t *>(dst);
+    if (split) {
+      HIP_TRY(hipMemcpyAsync(stage, src, scale_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
+      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, copy_stream));
+      HIP_TRY(hipEventRecord(L.set->copied_up[s], copy_stream));
+      HIP_TRY(hipMemcpyAsync(stage + scale_bytes + up_codes, src + scale_bytes + up_codes,
+                             ctx->host_blob_bytes - scale_bytes - up_codes, hipMemcpyHostToDevice, copy_stream));
+    } else {
+      HIP_TRY(hipMemcpyAsync(stage, src, ctx->host_blob_bytes, hipMemcpyHostToDevice, copy_stream));
+      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, copy_stream));
+    }
+    HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + up_codes, copy_stream));
+  } else if (split) {
     const size_t up_bytes = ctx->blob_bytes / 3 * 2;   // [W_gate; W_up], then W_down
     HIP_TRY(hipMemcpyAsync(dst, src, up_bytes, hipMemcpyHostToDevice, copy_stream));
     HIP_TRY(hipEventRecord(L.set->copied_up[s], copy_stream));
@@ -253,7 +278,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   L.set->copy_pending[s] = 1;
   L.set->use_kind[s] = 0;
   touch(L, s);
-  L.stats.bytes_h2d += (int64_t)ctx->blob_bytes;
+  L.stats.bytes_h2d += (int64_t)ctx->host_blob_bytes;
   return MOE_OK;
 }
 
@@ -611,6 +636,8 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   if (!ctx) return fail(MOE_E_ARG, "out of host memory");
   ctx->cfg = *cfg;
   ctx->blob_bytes = (size_t)6 * cfg->d * cfg->I;
+  ctx->host_blob_bytes = moe_host_blob_bytes(cfg);
+  ctx->stage_stride = cfg->host_format == MOE_FMT_E4M3_ROWS ? (ctx->host_blob_bytes + 255) / 256 * 256 : 0;
   HIP_TRY(hipGetDevice(&ctx->device));
   ctx->layers.resize(cfg->n_layers);
   HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), (kMaxExperts + 1) * sizeof(int32_t), 0));
@@ -654,6 +681,19 @@ int moe_destroy(moe_ctx *ctx) {
   if (ctx->dev_scores) (void)hipFree(ctx->dev_scores);
   delete ctx;
   return MOE_OK;
+}
+
+size_t moe_host_blob_bytes(const moe_config *cfg) {
+  if (check_cfg(cfg)) return 0;
+  const size_t dI = (size_t)cfg->d * cfg->I;
+  return cfg->host_format == MOE_FMT_E4M3_ROWS ? (size_t)4 * (2 * cfg->I + cfg->d) + 3 * dI : 6 * dI;
+}
+
+size_t moe_cache_bytes(const moe_config *cfg) {
+  if (check_cfg(cfg)) return 0;
+  const size_t slot = (size_t)6 * cfg->d * cfg->I;
+  const size_t stage = cfg->host_format == MOE_FMT_E4M3_ROWS ? (moe_host_blob_bytes(cfg) + 255) / 256 * 256 : 0;
+  return (size_t)cfg->cache_slots * (slot + stage);
 }
 
 size_t moe_workspace_bytes(const moe_config *cfg, int T) {

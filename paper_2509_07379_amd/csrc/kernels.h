@@ -32,6 +32,9 @@ hipError_t launch_mlp_predictor(const float *state, const int32_t *dims, int n_f
                                 const float *const *bias, const float *const *scale, const float *const *shift,
                                 float *act0, float *act1, int m, float *scores, int32_t *top_out,
                                 hipStream_t stream);
+// 8-bit expert weights -> bf16: out[r, c] = bf16_rne(value_e4m3(q[r, c]) * scales[r]); cols % 8 == 0.
+hipError_t launch_dequant_e4m3_rows(const uint8_t *q, const float *scales, long long rows, int cols,
+                                    uint16_t *out, hipStream_t stream);
 hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
                             float *scores, int32_t *top_out, hipStream_t stream);
 

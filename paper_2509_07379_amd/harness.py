@@ -23,26 +23,35 @@ def dev_to_np_u16(t: torch.Tensor) -> np.ndarray:
 
 
 class HostPool:
-    """All experts of one layer in pinned host memory: the CPU expert cache (Section V-A)."""
+    """All experts of one layer in pinned host memory: the CPU expert cache (Section V-A).
+    q8: experts stored as e4m3 codes with per-row scales (quantised from the seeded bf16 blobs)."""
 
-    def __init__(self, w: S.Workload, layer: int, fill: bool = True, share_from: "HostPool | None" = None):
-        self.w, self.layer = w, layer
+    def __init__(self, w: S.Workload, layer: int, fill: bool = True, share_from: "HostPool | None" = None,
+                 q8: bool = False):
+        self.w, self.layer, self.q8 = w, layer, q8
+        self.bytes_per_expert = S.q8_blob_bytes(w.d, w.I) if q8 else w.blob_bytes
         if share_from is not None:
+            assert share_from.q8 == q8
             self.buf = share_from.buf
         else:
-            self.buf = torch.empty((w.E, w.blob_elems), dtype=torch.int16, pin_memory=True)
+            self.buf = torch.empty((w.E, self.bytes_per_expert), dtype=torch.uint8, pin_memory=True)
             if fill:
                 for e in range(w.E):
-                    S.expert_blob_into(self.ptr(e), w, layer, e)
+                    if q8:
+                        S.quantize_blob_into(self.ptr(e), S.expert_blob(w, layer, e), w.d, w.I)
+                    else:
+                        S.expert_blob_into(self.ptr(e), w, layer, e)
 
     def ptr(self, e: int) -> int:
-        return self.buf.data_ptr() + e * self.w.blob_bytes
+        return self.buf.data_ptr() + e * self.bytes_per_expert
 
     def ptrs(self):
         return [self.ptr(e) for e in range(self.w.E)]
 
     def blob_np(self, e: int) -> np.ndarray:
-        return self.buf[e].numpy().view(np.uint16)
+        """The stored bytes of expert e: bf16 bit patterns, or (q8) the raw 8-bit blob."""
+        raw = self.buf[e].numpy()
+        return raw if self.q8 else raw.view(np.uint16)
 
 
 class DeviceLayer:
@@ -58,14 +67,17 @@ class DeviceLayer:
         self.shared_np = S.shared_blob(w, layer)
         self.shared = np_to_dev(self.shared_np, device) if self.shared_np is not None else None
         own = slots is None
-        self.slots = torch.empty((Sslots, w.blob_elems), dtype=torch.int16, device=device) if own else slots
+        # the cache: Sslots slots of one bf16 blob each, then (8-bit host format) the staging areas
+        self.cache = torch.empty(ctx.moe_cache_bytes() // 2, dtype=torch.int16, device=device) if own else slots
+        self.slots = self.cache.view(-1)[:Sslots * w.blob_elems].view(Sslots, w.blob_elems)
         if poison and own:
-            self.slots.fill_(0x7FC0)  # bf16 NaN pattern: any read of an unfilled slot shows up
+            self.cache.fill_(0x7FC0)  # bf16 NaN pattern: any read of an unfilled slot shows up
         if initial is not None:
+            assert not pool.q8, "initial residents are bf16 blobs"
             for s, e in enumerate(initial):
                 if e >= 0:
-                    self.slots[s].copy_(pool.buf[e], non_blocking=False)
-        ctx.moe_bind_layer(layer, pool.ptrs(), self.router, self.shared, self.slots, initial)
+                    self.slots[s].copy_(pool.buf[e].view(torch.int16), non_blocking=False)
+        ctx.moe_bind_layer(layer, pool.ptrs(), self.router, self.shared, self.cache, initial)
 
 
 class Buffers:

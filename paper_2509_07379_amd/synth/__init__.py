@@ -42,6 +42,9 @@ def _load():
             fn.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64,
                            ctypes.c_float, ptr]
             fn.restype = None
+        lib.synth_quantize_e4m3_rows.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        lib.synth_quantize_e4m3_rows.restype = None
         _lib = lib
     return _lib
 
@@ -244,3 +247,24 @@ def mlp_params(dims, seed: int, layer: int = 0):
             sc.append((1.0 + normal_f32((out,), seed, stream_id(KIND_MLP, layer, 4 * l + 2), 0.1)).astype(np.float32))
             sh.append(normal_f32((out,), seed, stream_id(KIND_MLP, layer, 4 * l + 3), 0.1))
     return ws, bs, sc, sh
+
+
+# ---------------------------------------------------------------------------
+# expert blobs quantised for the host link: e4m3 codes + one fp32 scale per output row
+# ---------------------------------------------------------------------------
+def q8_blob_bytes(d: int, I: int) -> int:
+    """[scales fp32: 2I gate/up rows, d down rows][W_gate codes I x d][W_up codes I x d][W_down codes d x I]"""
+    return 4 * (2 * I + d) + 3 * d * I
+
+
+def quantize_blob_into(ptr: int, blob_bf16: np.ndarray, d: int, I: int) -> None:
+    """Quantise a bf16 expert blob ([W_gate; W_up] (2I x d), W_down (d x I)) into the byte layout
+    above at raw host address ptr (offline preparation of the CPU expert cache)."""
+    blob_bf16 = np.ascontiguousarray(blob_bf16, dtype=np.uint16)
+    assert blob_bf16.size == 3 * d * I
+    lib = _load()
+    scales_bytes = 4 * (2 * I + d)
+    lib.synth_quantize_e4m3_rows(ctypes.c_void_p(blob_bf16.ctypes.data), 2 * I, d, ctypes.c_void_p(ptr),
+                                 ctypes.c_void_p(ptr + scales_bytes))
+    lib.synth_quantize_e4m3_rows(ctypes.c_void_p(blob_bf16.ctypes.data + 2 * (2 * I * d)), d, I,
+                                 ctypes.c_void_p(ptr + 4 * 2 * I), ctypes.c_void_p(ptr + scales_bytes + 2 * I * d))

@@ -68,3 +68,54 @@ void synth_normal_f32(uint64_t seed, uint64_t stream, int64_t first, int64_t n,
     if (i1 >= first && i1 < last) out[i1 - first] = sigma * z1;
   }
 }
+
+/*
+ * Offline 8-bit quantiser for expert blobs that travel over the host link in fp8 (OCP e4m3:
+ * 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest finite value 448, no infinities).
+ * Input preparation only: per row, scale = max|w| / 448 (1 for an all-zero row) and each weight
+ * becomes the e4m3 code nearest to w / scale (ties to the even code, saturating at +-448).
+ * w_bf16 [rows, cols] bf16 bits -> scales [rows] fp32, q [rows, cols] bytes.
+ */
+static inline float bf16_to_float(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+static inline float e4m3_value(int code) { /* code 0..126: the non-negative finite values, ascending */
+  int e = code >> 3, m = code & 7;
+  return e == 0 ? ldexpf((float)m, -9) : ldexpf(1.0f + (float)m / 8.0f, e - 7);
+}
+
+static inline uint8_t e4m3_nearest(float x) {
+  uint8_t sign = x < 0.0f ? 0x80 : 0;
+  float a = fabsf(x);
+  if (!(a < 448.0f)) return (uint8_t)(sign | 0x7E);
+  int lo = 0, hi = 126; /* largest code with value <= a */
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (e4m3_value(mid) <= a) lo = mid; else hi = mid - 1;
+  }
+  int code = lo;
+  if (lo < 126) {
+    float dl = a - e4m3_value(lo), dh = e4m3_value(lo + 1) - a;
+    if (dh < dl || (dh == dl && (lo & 1))) code = lo + 1;
+  }
+  return (uint8_t)(sign | code);
+}
+
+void synth_quantize_e4m3_rows(const uint16_t *w_bf16, int64_t rows, int64_t cols, float *scales, uint8_t *q) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r) {
+    const uint16_t *w = w_bf16 + r * cols;
+    float amax = 0.0f;
+    for (int64_t c = 0; c < cols; ++c) {
+      float a = fabsf(bf16_to_float(w[c]));
+      if (a > amax) amax = a;
+    }
+    float scale = amax > 0.0f ? amax / 448.0f : 1.0f;
+    scales[r] = scale;
+    for (int64_t c = 0; c < cols; ++c) q[r * cols + c] = e4m3_nearest(bf16_to_float(w[c]) / scale);
+  }
+}

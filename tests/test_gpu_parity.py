@@ -37,15 +37,17 @@ def gpu():
 
 def oracle_layer(oracle, w, x, router, pool, bias=None, sel=None, shared=None):
     blobs = [pool.blob_np(e) for e in range(w.E)]
+    if pool.q8:   # 8-bit CPU expert cache: the layer computes with the oracle's expansion of it
+        blobs = [oracle.dequant_blob(b, w.d, w.I) for b in blobs]
     return oracle.moe_layer(x, router, blobs, w.k, bias=bias, sel=sel, shared_blob=shared, I=w.I,
                             I_shared=w.I_shared)
 
 
 def run_layer(gpu, w, T, x_np, S_slots, initial, decode=False, bias=None, prefetch=None, poison=False,
-              pool=None):
+              pool=None, q8=False):
     H, B = gpu["harness"], gpu["binding"]
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True)
-    pool = pool or H.HostPool(w, 0)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True, host_format=1 if q8 else 0)
+    pool = pool or H.HostPool(w, 0, q8=q8)
     lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=poison)
     buf = H.Buffers(ctx, T)
     x = H.np_to_dev(x_np)
@@ -271,6 +273,60 @@ def test_shared_cache_prefill_streams_every_layer_through_two_slots(gpu, oracle)
         extra = sum(1 for e in (0, 1) if ref["counts"][e] == 0)   # speculative fetches without tokens
         assert ctx.moe_get_stats(l)["bytes_h2d"] == (active + extra) * w.blob_bytes
     ctx.close()
+
+
+# ---------------------------------------------------------------- 8-bit experts on the host link
+def test_q8_fetch_expands_into_slots_bit_exact(gpu, oracle):
+    """Experts stored as e4m3 codes with per-row scales: every fetched expert's slot holds, bit for
+    bit, the oracle's expansion; the layer's output is the oracle's on those weights; the link
+    carried the 8-bit blobs only."""
+    w = S.Workload("q8_slots", d=264, I=136, E=6, k=2, T=300, I_shared=64, seed=51)
+    x = S.activations(w)
+    r = run_layer(gpu, w, w.T, x, w.E, None, poison=True, q8=True)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], shared=r["lay"].shared_np)
+    np.testing.assert_array_equal(r["routing"]["perm"], ref["perm"])
+    check_out(r["out"], ref["out_f64"], "q8 prefill")
+    slots = r["lay"].slots.cpu().numpy().view(np.uint16)
+    active = [e for e in range(w.E) if ref["counts"][e] > 0]
+    assert len(active) >= 4
+    for e in active:
+        s = r["state"].index(e)
+        np.testing.assert_array_equal(slots[s], oracle.dequant_blob(r["pool"].blob_np(e), w.d, w.I), err_msg=f"expert {e}")
+    assert r["stats"]["bytes_h2d"] == len(active) * S.q8_blob_bytes(w.d, w.I)
+    assert r["stats"]["misses"] == len(active)
+
+
+@pytest.mark.parametrize("T,decode", [(700, False), (3, True)])
+def test_q8_streaming_through_two_slots(gpu, oracle, T, decode):
+    """Two slots (and their two staging areas) are reused expert after expert, the last fetch split in
+    two pieces; prefill streams all active experts, decode is served after a wrong prefetch."""
+    from oracle.cache_sim import CacheSim
+    w = S.Workload("q8_stream", d=256, I=192, E=8, k=2, T=T, seed=52, zipf_s=0.8)
+    x = S.activations(w)
+    bias = S.zipf_route_bias(w, 0)
+    r = run_layer(gpu, w, T, x, 2, None, decode=decode, bias=bias, prefetch=[7, 6], poison=True, q8=True)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias)
+    np.testing.assert_array_equal(r["routing"]["ids"], ref["ids"])
+    check_out(r["out"], ref["out_f64"], f"q8 streaming T={T}")
+    sim = CacheSim(w.E, 2, S.q8_blob_bytes(w.d, w.I))
+    sim.prefetch([7, 6])
+    sim.serve(np.nonzero(ref["counts"])[0])
+    assert r["stats"] == {**sim.counters(), "layer_calls": 1}
+    assert r["state"] == sim.slot_expert
+
+
+def test_q8_and_bf16_pools_of_the_same_weights_agree_within_the_format_error(gpu, oracle):
+    """The 8-bit path is the bf16 path run on rounded weights: on the same seeded experts the two
+    outputs differ by what 3 mantissa bits cost (a few per cent of the output's rms), not more."""
+    w = S.Workload("q8_vs_bf16", d=512, I=256, E=8, k=2, T=64, seed=53)
+    x = S.activations(w)
+    a = run_layer(gpu, w, w.T, x, w.E, None, q8=True)
+    b = run_layer(gpu, w, w.T, x, w.E, None)
+    np.testing.assert_array_equal(a["routing"]["ids"], b["routing"]["ids"])
+    ya, yb = S.bf16_to_f32(a["out"]).astype(np.float64), S.bf16_to_f32(b["out"]).astype(np.float64)
+    rms = np.sqrt(np.mean(yb ** 2))
+    rel = np.sqrt(np.mean((ya - yb) ** 2)) / rms
+    assert 1e-3 < rel < 0.1, rel
 
 
 # ---------------------------------------------------------------- ExpertMLP predictor (Section IV-B)
