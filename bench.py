@@ -122,7 +122,7 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, 
     stand-in attention block (4 bf16 GEMMs T x d x d) runs on the compute stream while the first
     experts are prefetched.  Returns T_copy-alone, T_compute-alone and T_pipelined per layer.
     q8: the CPU expert cache holds the same experts as e4m3 codes with per-row scales (half the
-    bytes on the link, expanded into the bf16 slots on the copy stream)."""
+    bytes on the link, expanded into the bf16 slots by a kernel behind each copy)."""
     if q8:
         t0 = time.time()
         pool = H.HostPool(w, 0, q8=True)
@@ -382,7 +382,7 @@ def main():
             o8 = prefill_offloaded(args, torch, B, H, S, w, None, res["x"], compute, copy, q8=True)
             t_c, t_p = o8["t_copy_ms"], o8["t_pipelined_ms"]
             line["offloaded_q8"] = {
-                "host_format": "e4m3 codes + fp32 scale per row, expanded to bf16 slots on the copy stream",
+                "host_format": "e4m3 codes + fp32 scale per row, expanded into the bf16 slots by a kernel behind each copy",
                 "slots": w.S, "ms_per_layer": t_p, "tokens_per_s": w.T / (t_p * 1e-3), "t_copy_alone_ms": t_c,
                 "bytes_per_layer": o8["bytes_per_layer"], "h2d_GBps": o8["bytes_per_layer"] / (t_c * 1e-3) / 1e9,
                 "overlap": (t_c + t_k - t_p) / min(t_c, t_k), "link_busy_frac": t_c / t_p,

@@ -69,8 +69,11 @@ typedef struct {
  * MOE_FMT_E4M3_ROWS: 8-bit weights (the paper serves quantised models, Section VI; the format is this
  *   library's): [scale fp32: 2I rows of W_gate/W_up, then d rows of W_down][W_gate codes I x d]
  *   [W_up codes I x d][W_down codes d x I], codes = OCP e4m3 (1-4-3 bits, bias 7, max 448, 0x7F NaN).
- *   A fetched expert lands in a staging area behind the slots and is expanded into its slot on the
- *   copy stream: weight = bf16 nearest-even of fp32(value(code) * scale[row]).  Slots, matmuls and
+ *   A fetched expert lands in a staging area behind the slots and a kernel expands it into its slot:
+ *   weight = bf16 nearest-even of fp32(value(code) * scale[row]).  The kernels run on a stream of the
+ *   library's own, each behind the copy it reads, so that the next copy does not wait for them; every
+ *   call that fetched makes copy_stream wait for the last of them before it returns, so a
+ *   synchronised copy_stream still means "the experts are in their slots".  Slots, matmuls and
  *   results are those of MOE_FMT_BF16 run on the expanded weights; the link carries half the bytes. */
 #define MOE_FMT_BF16 0
 #define MOE_FMT_E4M3_ROWS 1

@@ -107,6 +107,9 @@ struct SlotSet {
   std::vector<char> use_kind;        // 0: never read, 1: read behind used[slot], 2: read behind group_done
   std::vector<hipEvent_t> copied, used;
   std::vector<hipEvent_t> copied_up;  // a split fetch has landed its gate / up matrices
+  // 8-bit host format: the bytes of a fetch (its first piece, all of it) are in the staging area
+  std::vector<hipEvent_t> landed_up, landed;
+  std::vector<char> staged;          // the slot's staging area has been written before
   hipEvent_t group_done = nullptr;
   unsigned long long clock = 0;
 };
@@ -145,6 +148,11 @@ struct moe_ctx {
   // grouping and the routed experts (fork at the start of the call, join before the weighted sum)
   hipStream_t side = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
+  // 8-bit host format: fetched experts are expanded into their slots on this stream, so that the
+  // next copy does not queue behind the expansion; expand_tail is the completion event of the last
+  // expansion no API call has joined into the copy stream yet
+  hipStream_t expand = nullptr;
+  hipEvent_t expand_tail = nullptr;
   float *dev_scores = nullptr;        // [64] scratch for predictor_score without dev_scores
   bool profiling = false;
   std::vector<TimedLaunch> timed;
@@ -242,24 +250,37 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   const moe_config &c = ctx->cfg;
   if (c.host_format == MOE_FMT_E4M3_ROWS) {
     // [scales: 2I gate/up rows, d down rows][gate codes][up codes][down codes] lands in the slot's
-    // staging area; a kernel behind each copy, on the same stream, expands it into the slot.  The
-    // stream's order also keeps the next copy into this staging area behind that expansion.
-    char *stage = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes + (size_t)s * ctx->stage_stride;
+    // staging area on the copy stream; kernels on the expansion stream, each behind the copy it
+    // reads, write the slot.  copied_up / copied are recorded there, after the expansion.
+    SlotSet &set = *L.set;
+    hipStream_t xs = ctx->expand;
+    char *stage = set.slots + (size_t)c.cache_slots * ctx->blob_bytes + (size_t)s * ctx->stage_stride;
     const size_t scale_bytes = (size_t)4 * (2 * c.I + c.d), up_codes = (size_t)2 * c.I * c.d;
     const float *scales = reinterpret_cast<const float *>(stage);
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + scale_bytes);
     uint16_t *w = reinterpret_cast<uint16_t *>(dst);
+    // the staging area's last expansion must be over before new bytes land in it
+    if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
+    set.staged[s] = 1;
     if (split) {
       HIP_TRY(hipMemcpyAsync(stage, src, scale_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
-      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, copy_stream));
-      HIP_TRY(hipEventRecord(L.set->copied_up[s], copy_stream));
+      HIP_TRY(hipEventRecord(set.landed_up[s], copy_stream));
       HIP_TRY(hipMemcpyAsync(stage + scale_bytes + up_codes, src + scale_bytes + up_codes,
                              ctx->host_blob_bytes - scale_bytes - up_codes, hipMemcpyHostToDevice, copy_stream));
+      HIP_TRY(hipEventRecord(set.landed[s], copy_stream));
+      HIP_TRY(hipStreamWaitEvent(xs, set.landed_up[s], 0));
+      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
+      HIP_TRY(hipEventRecord(set.copied_up[s], xs));
+      HIP_TRY(hipStreamWaitEvent(xs, set.landed[s], 0));
     } else {
       HIP_TRY(hipMemcpyAsync(stage, src, ctx->host_blob_bytes, hipMemcpyHostToDevice, copy_stream));
-      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, copy_stream));
+      HIP_TRY(hipEventRecord(set.landed[s], copy_stream));
+      HIP_TRY(hipStreamWaitEvent(xs, set.landed[s], 0));
+      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
     }
-    HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + up_codes, copy_stream));
+    HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + up_codes, xs));
+    HIP_TRY(hipEventRecord(set.copied[s], xs));
+    ctx->expand_tail = set.copied[s];
   } else if (split) {
     const size_t up_bytes = ctx->blob_bytes / 3 * 2;   // [W_gate; W_up], then W_down
     HIP_TRY(hipMemcpyAsync(dst, src, up_bytes, hipMemcpyHostToDevice, copy_stream));
@@ -269,7 +290,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   } else {
     HIP_TRY(hipMemcpyAsync(dst, src, ctx->blob_bytes, hipMemcpyHostToDevice, copy_stream));
   }
-  HIP_TRY(hipEventRecord(L.set->copied[s], copy_stream));
+  if (c.host_format == MOE_FMT_BF16) HIP_TRY(hipEventRecord(L.set->copied[s], copy_stream));
   if (L.set->slot_expert[s] >= 0) ctx->layers[L.set->slot_layer[s]].expert_slot[L.set->slot_expert[s]] = -1;
   L.set->slot_expert[s] = e;
   L.set->slot_layer[s] = L.index;
@@ -279,6 +300,15 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   L.set->use_kind[s] = 0;
   touch(L, s);
   L.stats.bytes_h2d += (int64_t)ctx->host_blob_bytes;
+  return MOE_OK;
+}
+
+// The copy stream waits for every expansion enqueued so far: a caller that has synchronised the
+// copy stream may then rely on the experts being in their slots.
+int join_expand(moe_ctx *ctx, hipStream_t copy_stream) {
+  if (!ctx->expand_tail) return MOE_OK;
+  HIP_TRY(hipStreamWaitEvent(copy_stream, ctx->expand_tail, 0));
+  ctx->expand_tail = nullptr;
   return MOE_OK;
 }
 
@@ -648,6 +678,7 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
     HIP_TRY(hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming));
   }
+  if (cfg->host_format != MOE_FMT_BF16) HIP_TRY(hipStreamCreateWithFlags(&ctx->expand, hipStreamNonBlocking));
   HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ctx->dev_scores), kMaxExperts * sizeof(float)));
   *out = ctx;
   return MOE_OK;
@@ -661,6 +692,8 @@ int moe_destroy(moe_ctx *ctx) {
     for (hipEvent_t e : set->copied) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : set->copied_up) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : set->used) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : set->landed_up) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : set->landed) if (e) (void)hipEventDestroy(e);
     if (set->group_done) (void)hipEventDestroy(set->group_done);
   };
   for (Layer &L : ctx->layers) destroy_set(L.own.get());
@@ -677,6 +710,7 @@ int moe_destroy(moe_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamDestroy(ctx->side);
   }
+  if (ctx->expand) (void)hipStreamDestroy(ctx->expand);
   if (ctx->pinned_counts) (void)hipHostFree(ctx->pinned_counts);
   if (ctx->dev_scores) (void)hipFree(ctx->dev_scores);
   delete ctx;
@@ -743,6 +777,15 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
       HIP_TRY(hipEventCreateWithFlags(&set.used[s], hipEventDisableTiming));
     }
     HIP_TRY(hipEventCreateWithFlags(&set.group_done, hipEventDisableTiming));
+    set.staged.assign(S, 0);
+    if (c.host_format != MOE_FMT_BF16) {
+      set.landed_up.assign(S, nullptr);
+      set.landed.assign(S, nullptr);
+      for (int s = 0; s < S; ++s) {
+        HIP_TRY(hipEventCreateWithFlags(&set.landed_up[s], hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags(&set.landed[s], hipEventDisableTiming));
+      }
+    }
   }
   L.set = holder.get();
   SlotSet &set = *L.set;
@@ -813,7 +856,7 @@ int expert_cache_prefetch(moe_ctx *ctx, int layer, const int32_t *host_ids, int 
     if (rc) return rc;
     L.stats.prefetch_issued++;
   }
-  return MOE_OK;
+  return join_expand(ctx, ks);
 }
 
 int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, int m, float *dev_scores,
@@ -933,15 +976,17 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out) {
 int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
                       int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
                       void *compute_stream, void *copy_stream) {
-  return run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
-                   compute_stream, copy_stream, false);
+  int rc = run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
+                     compute_stream, copy_stream, false);
+  return rc ? rc : join_expand(ctx, reinterpret_cast<hipStream_t>(copy_stream));
 }
 
 int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
                      int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
                      void *compute_stream, void *copy_stream) {
-  return run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
-                   compute_stream, copy_stream, true);
+  int rc = run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
+                     compute_stream, copy_stream, true);
+  return rc ? rc : join_expand(ctx, reinterpret_cast<hipStream_t>(copy_stream));
 }
 
 int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *dev_ids, float *dev_w,
