@@ -224,6 +224,11 @@ int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *d
                       float *dev_w, int32_t *dev_counts, int32_t *dev_offsets, int32_t *dev_perm,
                       int32_t *dev_inv_perm, void *stream);
 
+/* Parity hook: the gate logits (bias included) of the last layer call, [T, E] fp32, copied from
+ * `dev_workspace` on `stream`.  The Top-k is an integer decision taken on these values, so they are
+ * defined bit for bit (Section II-A; fixed summation order, see the kernel's header). */
+int moe_debug_logits(moe_ctx *ctx, const void *dev_workspace, int T, float *dev_logits, void *stream);
+
 /* Cache counters of `layer` (or summed over all layers if layer < 0). */
 int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out);
 int moe_reset_stats(moe_ctx *ctx);

@@ -22,7 +22,7 @@ EXPORTS = [
     "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_invalidate", "moe_cache_state", "moe_set_profiling",
     "moe_get_kernel_times", "moe_dense_gemm_bf16", "moe_set_gemm_variant",
     "predictor_mlp_score", "moe_state_create", "moe_state_destroy", "moe_state_dim", "moe_state_record",
-    "moe_state_clear", "moe_state_vector", "moe_host_blob_bytes", "moe_cache_bytes",
+    "moe_state_clear", "moe_state_vector", "moe_host_blob_bytes", "moe_cache_bytes", "moe_debug_logits",
 ]
 
 
@@ -72,6 +72,7 @@ def load():
     lib.moe_prefill_layer.argtypes = layer_args
     lib.moe_decode_layer.argtypes = layer_args
     lib.moe_debug_routing.argtypes = [vp, vp, c_int, vp, vp, vp, vp, vp, vp, vp]
+    lib.moe_debug_logits.argtypes = [vp, vp, c_int, vp, vp]
     lib.moe_get_stats.argtypes = [vp, c_int, POINTER(MoeStats)]
     lib.moe_reset_stats.argtypes = [vp]
     lib.moe_cache_state.argtypes = [vp, c_int, POINTER(c_int32)]
@@ -206,6 +207,9 @@ class MoeContext:
                           inv_perm=None, stream=None):
         _check(self.lib.moe_debug_routing(self._h, _ptr(ws), T, _ptr(ids), _ptr(w), _ptr(counts),
                                           _ptr(offsets), _ptr(perm), _ptr(inv_perm), _stream(stream)))
+
+    def moe_debug_logits(self, ws, T, logits, stream=None):
+        _check(self.lib.moe_debug_logits(self._h, _ptr(ws), T, _ptr(logits), _stream(stream)))
 
     def moe_get_stats(self, layer=-1) -> dict:
         st = MoeStats()

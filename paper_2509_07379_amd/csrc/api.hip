@@ -1008,6 +1008,14 @@ int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *d
   return MOE_OK;
 }
 
+int moe_debug_logits(moe_ctx *ctx, const void *dev_workspace, int T, float *dev_logits, void *stream) {
+  if (!ctx || !dev_workspace || !dev_logits || T <= 0) return fail(MOE_E_ARG, "bad argument to moe_debug_logits");
+  const WsLayout W = ws_layout(ctx->cfg, T);
+  HIP_TRY(hipMemcpyAsync(dev_logits, reinterpret_cast<const char *>(dev_workspace) + W.logits,
+                         (size_t)T * ctx->cfg.E * 4, hipMemcpyDeviceToDevice, reinterpret_cast<hipStream_t>(stream)));
+  return MOE_OK;
+}
+
 int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out) {
   if (!ctx || !out) return fail(MOE_E_ARG, "NULL argument");
   moe_stats acc{};

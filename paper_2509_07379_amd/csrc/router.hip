@@ -84,11 +84,17 @@ __global__ __launch_bounds__(64 * NWAVES) void router_topk_kernel(
 #pragma unroll
       for (int q = 0; q < TPB; ++q) acc[q] = dot8_ordered(xs[q * nchunk + c], wv, acc[q]);
     }
+    // the TPB butterflies side by side: each level's exchanges are in flight together
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+#pragma unroll
+      for (int q = 0; q < TPB; ++q) acc[q] = acc[q] + __shfl_xor(acc[q], m);
+    }
 #pragma unroll
     for (int q = 0; q < TPB; ++q) {
-      float s = wave_sum_tree(acc[q]);
       int t = t0 + q;
       if (lane == 0 && t < T) {
+        float s = acc[q];
         if (bias) s = s + bias[(size_t)t * bias_stride + e];
         lg[q * 64 + e] = s;
       }
@@ -203,19 +209,22 @@ __global__ __launch_bounds__(64) void predictor_topm_kernel(const float *__restr
 
 }  // namespace
 
+
 hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
                               int bias_stride, int T, int d, int E, int k, int renormalize,
                               float *logits, int32_t *ids, float *w, hipStream_t stream,
                               const SingleTokenDispatch *one) {
-  // 4 tokens per block share one pass over Wr; small batches (decode) use one token per block and
-  // 16 waves, so that the E dot products of a token run side by side.
+  // 4 tokens per block share one pass over Wr, 8 waves take the experts in turn (a wave's time is a
+  // chain of dependent loads and exchanges per expert, so more waves per token group means a shorter
+  // chain); small batches (decode) use one token per block and 16 waves, so that the E dot products
+  // of a token run side by side.
   SingleTokenDispatch none{};
   if (one && T != 1) return hipErrorInvalidValue;
   if (T >= 64) {
     constexpr int TPB = 4;
     size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
     int grid = (T + TPB - 1) / TPB;
-    hipLaunchKernelGGL((router_topk_kernel<TPB, 4>), dim3(grid), dim3(256), smem, stream, x, wr, bias,
+    hipLaunchKernelGGL((router_topk_kernel<TPB, 8>), dim3(grid), dim3(512), smem, stream, x, wr, bias,
                        bias_stride, T, d, E, k, renormalize, logits, ids, w, none);
   } else {
     constexpr int TPB = 1;

@@ -106,6 +106,33 @@ def test_every_gemm_kernel_on_one_layer(gpu, oracle, variant):
     check_out(r["out"], ref["out_f64"], f"gemm variant {variant}")
 
 
+# ---------------------------------------------------------------- gate logits, bit for bit
+@pytest.mark.parametrize("d,E,k,T", [(4096, 8, 2, 70), (2048, 64, 6, 131), (1024, 60, 4, 97), (264, 6, 2, 80),
+                                     (4096, 8, 2, 5), (2048, 64, 6, 1)])
+def test_gate_logits_bit_exact(gpu, oracle, d, E, k, T):
+    """Both gate launches (four tokens per block for 64 tokens or more, one block per token for small
+    batches) sum in the documented order: the logits equal the oracle's scalar replay bit for bit,
+    with a per-token bias added last."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("logits", d=d, I=64, E=E, k=k, T=T, seed=61)
+    x = S.activations(w)
+    bias = S.normal_f32((T, E), 61, 900, 0.5)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E)
+    pool = H.HostPool(w, 0)
+    lay = H.DeviceLayer(ctx, w, 0, pool, list(range(E)))
+    buf = H.Buffers(ctx, T)
+    got = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    ctx.moe_prefill_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"],
+                          torch.from_numpy(bias).cuda(), E)
+    ctx.moe_debug_logits(buf.ws, T, got, gpu["compute"])
+    gpu["compute"].synchronize()
+    want = oracle.router_logits(x, lay.router_np, bias)
+    np.testing.assert_array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    ids, _ = oracle.topk_weights(want, k)
+    np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ids)
+    ctx.close()
+
+
 # ---------------------------------------------------------------- config 1, all resident
 def test_c1_routing_bit_exact_and_output(gpu, oracle):
     w = S.WORKLOADS["c1_tiny"]
