@@ -241,6 +241,50 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
     return out
 
 
+def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy):
+    """Kernel regime of decode with the 8-bit host pool: every expert fetched once through the library
+    (so its 8-bit copy sits in the staging area next to its bf16 slot), then steady-state steps in
+    which the mat-vec kernels stream the 8-bit copies."""
+    from dataclasses import replace
+    wl = replace(w, L=n_layers, steps=steps)
+    t0 = time.time()
+    pools = [H.HostPool(wl, l, q8=True) for l in range(n_layers)]
+    log(f"[bench] decode 8-bit host pools {n_layers * wl.E * pools[0].bytes_per_expert / 1e9:.1f} GB in {time.time() - t0:.1f}s")
+    trace = S.markov_trace(wl)
+    ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, wl.E, wl.I_shared, True, host_format=1)
+    layers = [H.DeviceLayer(ctx, wl, l, pools[l], None) for l in range(n_layers)]
+    for l in range(n_layers):
+        ctx.expert_cache_prefetch(l, list(range(wl.E)), copy)
+    torch.cuda.synchronize()
+    buf = H.Buffers(ctx, wl.T)
+    xs = [H.np_to_dev(S.activations(wl, l, 0)) for l in range(n_layers)]
+    biases = [[torch.from_numpy(S.trace_route_bias(trace[s, l], wl.E)).cuda() for l in range(n_layers)]
+              for s in range(steps)]
+
+    def one_step(s):
+        for l in range(n_layers):
+            ctx.moe_decode_layer(l, xs[l], wl.T, buf.y, buf.ws, compute, copy, biases[s][l], wl.E)
+
+    one_step(0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        one_step(s)
+    torch.cuda.synchronize()
+    us_layer = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
+    ctx.moe_set_profiling(True)
+    for s in range(min(steps, 8)):
+        one_step(s)
+    torch.cuda.synchronize()
+    kt = ctx.moe_get_kernel_times()
+    ctx.close()
+    g = kt["gemv1"][0] / max(1, kt["gemv1"][1]) + kt["gemv2"][0] / max(1, kt["gemv2"][1])
+    code_bytes = wl.k * 3 * wl.d * wl.I
+    return {"us_per_layer": us_layer, "gemv_us_per_layer": g * 1e3, "layers": n_layers,
+            "gemv_HBM_GBps": code_bytes / (g * 1e-3) / 1e9 if g else 0.0,
+            "gemv_frac_of_hbm_peak": code_bytes / (g * 1e-3) / 1e9 / PEAK_HBM_GBS if g else 0.0}
+
+
 def mlp_predictor_latency(torch, B, H, S, w, pred):
     """One ExpertMLP prediction (Section IV-B) for the decode workload's model: state vector in pinned
     memory, eight fully connected layers and the top-k on the prediction stream; microseconds each."""
@@ -410,6 +454,10 @@ def main():
             "shared_k_stats": dec["shared_k"]["stats"],
             "mlp_predictor": mlp_predictor_latency(torch, B, H, S, wd, pred),
         }
+        if not args.no_q8:
+            # the same kernel regime with experts fetched from an 8-bit host pool: the mat-vecs stream the codes
+            line["decode"]["resident_q8"] = decode_resident_q8(args, torch, B, H, S, wd, min(2, args.decode_layers),
+                                                               args.decode_steps, compute, copy)
         log(f"[bench] decode: {line['decode']}")
 
     if not args.no_cpu_baseline:

@@ -74,7 +74,11 @@ typedef struct {
  *   library's own, each behind the copy it reads, so that the next copy does not wait for them; every
  *   call that fetched makes copy_stream wait for the last of them before it returns, so a
  *   synchronised copy_stream still means "the experts are in their slots".  Slots, matmuls and
- *   results are those of MOE_FMT_BF16 run on the expanded weights; the link carries half the bytes. */
+ *   results are those of MOE_FMT_BF16 run on the expanded weights; the link carries half the bytes.
+ *   The decode mat-vec kernels stream a fetched expert's 8-bit form from its staging area (half the
+ *   HBM bytes) and expand it in registers to the same weight values when the experts are large
+ *   enough for that to pay (16 M weights per matrix; d and I multiples of 16); otherwise, and for
+ *   experts the caller placed with initial_resident, they read the bf16 slot. */
 #define MOE_FMT_BF16 0
 #define MOE_FMT_E4M3_ROWS 1
 
@@ -266,7 +270,9 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * before sizing workspaces); mode 4 forces the weight rows per wave of the decode mat-vec
  * kernels (0 = heuristic, 1, 2 or 4); mode 5 sets the largest expert count for which a one-token
  * decode call with every expert resident is enqueued without the host looking at the gate's
- * result (default 16).  Process-wide.
+ * result (default 16); mode 6 chooses what the decode mat-vec kernels read where an 8-bit copy of an
+ * expert exists (MOE_FMT_E4M3_ROWS): 0 = the copy if the experts are large enough for it to pay
+ * (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy.  Process-wide.
  */
 int moe_set_gemm_variant(int mode, int variant);
 

@@ -48,6 +48,7 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // 256 x 256 on 256 CUs) leave most of the last round idle; slicing K makes the tiles finer.
 // The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
 int g_splitk_override = 0;  // tuning hook (moe_set_gemm_variant mode 3); 0 = heuristic
+int g_no_q8_matvec = 0;  // tuning hook (mode 6): 1 = mat-vecs read the expanded bf16 slots even when an 8-bit copy exists
 int g_blind_max_experts = 16;  // tuning hook (mode 5): with more experts than this a one-token decode call waits for the gate and launches only the active experts
 
 int choose_splitk(const moe_config &cfg, int T) {
@@ -110,6 +111,7 @@ struct SlotSet {
   // 8-bit host format: the bytes of a fetch (its first piece, all of it) are in the staging area
   std::vector<hipEvent_t> landed_up, landed;
   std::vector<char> staged;          // the slot's staging area has been written before
+  std::vector<char> q_valid;         // the staging area holds the 8-bit form of what the slot holds
   hipEvent_t group_done = nullptr;
   unsigned long long clock = 0;
 };
@@ -262,6 +264,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     // the staging area's last expansion must be over before new bytes land in it
     if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
     set.staged[s] = 1;
+    set.q_valid[s] = 1;
     if (split) {
       HIP_TRY(hipMemcpyAsync(stage, src, scale_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
       HIP_TRY(hipEventRecord(set.landed_up[s], copy_stream));
@@ -323,6 +326,19 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   a.wstride = (long long)ctx->blob_bytes;
   for (int e = 0; e < c.E; ++e) a.slot[e] = (signed char)(L.expert_slot[e] < 0 ? 0 : L.expert_slot[e]);
   a.splitk = 1;
+  if (c.host_format == MOE_FMT_E4M3_ROWS && c.d % 16 == 0 && c.I % 16 == 0 && !g_no_q8_matvec) {
+    // the mat-vec kernels stream the 8-bit copy that a fetch left in the slot's staging area (half
+    // the bytes; the same weight values as the expanded slot)
+    const long long scale_bytes = (long long)4 * (2 * c.I + c.d), Id = (long long)c.I * c.d;
+    a.qbase = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes;
+    a.qstride = (long long)ctx->stage_stride;
+    a.q_b0_off = scale_bytes + (second ? 2 * Id : 0);
+    a.q_b1_off = scale_bytes + (second ? 2 * Id : Id);
+    a.q_s0_off = second ? (long long)4 * 2 * c.I : 0;
+    a.q_s1_off = second ? (long long)4 * 2 * c.I : (long long)4 * c.I;
+    for (int e = 0; e < c.E; ++e)
+      if (L.expert_slot[e] >= 0 && L.set->q_valid[L.expert_slot[e]]) a.q8_mask |= 1ull << e;
+  }
   if (!second) {
     a.A = reinterpret_cast<const uint16_t *>(x);
     a.lda = c.d;
@@ -626,6 +642,10 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       HIP_TRY(hipStreamWaitEvent(cs, last ? L.set->copied_up[s] : L.set->copied[s], 0));
       L.set->copy_pending[s] = 0;
       a1.slot[e] = a2.slot[e] = (signed char)s;
+      if (a1.qbase) {   // fetched just now: its 8-bit copy is in the staging area
+        a1.q8_mask |= 1ull << e;
+        a2.q8_mask |= 1ull << e;
+      }
       rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs, nullptr, nullptr,
                        last ? L.set->copied[s] : nullptr);
       if (rc) return rc;
@@ -778,6 +798,7 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
     }
     HIP_TRY(hipEventCreateWithFlags(&set.group_done, hipEventDisableTiming));
     set.staged.assign(S, 0);
+    set.q_valid.assign(S, 0);
     if (c.host_format != MOE_FMT_BF16) {
       set.landed_up.assign(S, nullptr);
       set.landed.assign(S, nullptr);
@@ -819,6 +840,7 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
         if (set.slot_expert[s] >= 0) ctx->layers[set.slot_layer[s]].expert_slot[set.slot_expert[s]] = -1;
         set.slot_expert[s] = initial_resident[s];
         set.slot_layer[s] = layer;
+        set.q_valid[s] = 0;   // the caller put the bf16 blob there; no 8-bit copy
         L.expert_slot[initial_resident[s]] = s;
       }
   L.bound = true;
@@ -1092,7 +1114,13 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
 }
 
 int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 5 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 6 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode == 6) {
+    if (variant > 2) return fail(MOE_E_ARG, "8-bit mat-vec source: 0 (by expert size), 1 (never) or 2 (always)");
+    g_no_q8_matvec = variant == 1;
+    set_gemv_q8_always(variant == 2);
+    return MOE_OK;
+  }
   if (mode == 5) {
     g_blind_max_experts = variant;
     return MOE_OK;

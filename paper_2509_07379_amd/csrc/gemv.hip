@@ -61,6 +61,60 @@ __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg
   }
 }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Four e4m3 codes (one 32-bit word, element 0 in the low byte) and their row's scale -> the four
+// bf16 weights bf16_rne(value(code) * scale), packed in pairs: the hardware conversions of gfx950
+// (OCP e4m3 to fp32, exact; fp32 to bf16, nearest even) around one fp32 multiply.
+struct Pair32 { uint32_t w01, w23; };
+__device__ __forceinline__ Pair32 expand4(uint32_t codes, float scale) {   // by value: plain scalars
+  f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes, false);
+  f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes, true);
+  a *= scale;
+  b *= scale;
+  Pair32 p;
+  p.w01 = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
+  p.w23 = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
+  return p;
+}
+__device__ __forceinline__ void expand16(const u32x4 &q, float scale, u32x4 &lo, u32x4 &hi) {
+  const uint32_t qx = q.x, qy = q.y, qz = q.z, qw = q.w;
+  const Pair32 a = expand4(qx, scale), b = expand4(qy, scale), c = expand4(qz, scale), d = expand4(qw, scale);
+  lo = u32x4{a.w01, a.w23, b.w01, b.w23};
+  hi = u32x4{c.w01, c.w23, d.w01, d.w23};
+}
+
+// The same sums from 8-bit weights: a lane's 16-byte piece holds 16 codes, i.e. two of the token
+// vectors' 8-element pieces; the codes are expanded once per piece and used for all NT tokens.
+template <int MODE, int NT, int NTMAX, int GV_R>
+__device__ __forceinline__ void accumulate_q8(const u32x4 *__restrict__ xs, int seg_chunks,
+                                              const u32x4 *const (&w0)[GV_R], const u32x4 *const (&w1)[GV_R],
+                                              const float (&s0)[GV_R], const float (&s1)[GV_R], int lane,
+                                              float (&acc0)[GV_R][NTMAX], float (&acc1)[GV_R][NTMAX]) {
+  const int pieces = seg_chunks >> 1;
+#pragma unroll 2
+  for (int c = lane; c < pieces; c += 64) {
+    u32x4 q0[GV_R], q1[GV_R];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      q0[r] = __builtin_nontemporal_load(w0[r] + c);
+      if (MODE == GEMM_SWIGLU) q1[r] = __builtin_nontemporal_load(w1[r] + c);
+    }
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      u32x4 lo0, hi0, lo1, hi1;
+      expand16(q0[r], s0[r], lo0, hi0);
+      if (MODE == GEMM_SWIGLU) expand16(q1[r], s1[r], lo1, hi1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const u32x4 xlo = xs[t * seg_chunks + 2 * c], xhi = xs[t * seg_chunks + 2 * c + 1];
+        acc0[r][t] = dot8(xhi, hi0, dot8(xlo, lo0, acc0[r][t]));
+        if (MODE == GEMM_SWIGLU) acc1[r][t] = dot8(xhi, hi1, dot8(xlo, lo1, acc1[r][t]));
+      }
+    }
+  }
+}
+
 // GV_R weight rows per wave.  Measured on MI355X: the more, smaller waves stream the weights, the
 // closer the kernel gets to the HBM rate (one row per wave for rows of 4 KB and more, two for
 // shorter rows); blocks that walk over several row groups were slower in every shape.
@@ -69,8 +123,10 @@ __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg
 // of the weights; 16 waves share one copy).
 // (at least 6 waves per SIMD for the 4-wave blocks: left alone, the register allocator of the
 // multi-token variants wanders between 76 and 100 registers with unrelated edits)
-template <int MODE, int NTMAX, int GV_R, int NTHR>
-__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(NTHR == 256 ? 6 : 4)))
+// Q8: experts named in routed.q8_mask are streamed from their 8-bit copies (the second problem, the
+// shared experts, is always bf16); without Q8 the mask is ignored.
+template <int MODE, int NTMAX, int GV_R, int NTHR, bool Q8>
+__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(NTHR == 256 ? ((Q8 && (NTMAX > 1 || GV_R > 1)) ? 4 : 6) : 4)))
 void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
                                                              int has_extra, int kseg, int ntcap, int n_extra_y) {
   constexpr int GV_THREADS = NTHR, GV_WAVES = NTHR / 64;
@@ -105,6 +161,17 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
   const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
   const int n_first = (bx * GV_WAVES + wave) * GV_R;
   if ((int)bx * GV_WAVES * GV_R >= args.N) return;
+  const bool q8 = Q8 && !is_extra && ((args.q8_mask >> grp) & 1ull);
+  const char *qptr = args.qbase + (long long)args.slot[grp] * args.qstride;
+  float s0[GV_R], s1[GV_R];
+  if (Q8) {
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      const int n = min(n_first + r, args.N - 1);
+      s0[r] = q8 ? reinterpret_cast<const float *>(qptr + args.q_s0_off)[n] : 0.0f;
+      s1[r] = q8 ? reinterpret_cast<const float *>(qptr + args.q_s1_off)[n] : 0.0f;
+    }
+  }
 
   for (int tok0 = 0; tok0 < cnt; tok0 += ntcap) {
     const int ntok = min(ntcap, cnt - tok0);  // ntcap <= NTMAX tokens fit the LDS buffer
@@ -132,9 +199,20 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
         w0[r] = reinterpret_cast<const u32x4 *>(B0 + (long long)n * args.ldb + k0);
         w1[r] = reinterpret_cast<const u32x4 *>(B1 + (long long)n * args.ldb + k0);
       }
+      if (Q8 && q8) {   // the same rows in the 8-bit copy: K bytes per row
+#pragma unroll
+        for (int r = 0; r < GV_R; ++r) {
+          const int n = min(n_first + r, args.N - 1);
+          w0[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b0_off + (long long)n * args.ldb + k0);
+          w1[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b1_off + (long long)n * args.ldb + k0);
+        }
+      }
 #define MOE_GEMV_CASE(NT)                                                             \
   if constexpr (NT <= NTMAX) {                                                        \
-    if (ntok == NT) accumulate<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, lane, acc0, acc1); \
+    if (ntok == NT) {                                                                 \
+      if (Q8 && q8) accumulate_q8<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, s0, s1, lane, acc0, acc1); \
+      else accumulate<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, lane, acc0, acc1); \
+    }                                                                                 \
   }
       MOE_GEMV_CASE(1) MOE_GEMV_CASE(2) MOE_GEMV_CASE(3) MOE_GEMV_CASE(4)
       MOE_GEMV_CASE(5) MOE_GEMV_CASE(6) MOE_GEMV_CASE(7) MOE_GEMV_CASE(8)
@@ -165,6 +243,8 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
 
 static int g_gemv_rows = 0;   // tuning hook: rows per wave (0 = by shape)
 void set_gemv_rows(int rows) { g_gemv_rows = rows; }
+static int g_gemv_q8_always = 0;   // test hook: 8-bit copies are used whatever the experts' size
+void set_gemv_q8_always(int on) { g_gemv_q8_always = on; }
 
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra) {
@@ -178,11 +258,18 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     if (extra->N > max_n) max_n = extra->N;
     if (extra->K > max_k) max_k = extra->K;
   }
+  // 8-bit copies pay where the launch is bound by the bytes it streams: experts of 16 M weights per
+  // matrix and more (Mixtral-sized: 1.4 to 1.5 times faster at 1 to 6 tokens).  Small experts
+  // (Qwen-sized, 3 M) are bound by the launch itself at 1 or 2 tokens and by arithmetic above; there
+  // the expansion only adds instructions.
+  const bool use_q8 = args.q8_mask != 0 && args.qbase != nullptr && args.K % 16 == 0 &&
+                      ((long long)args.N * args.K >= (1ll << 24) || g_gemv_q8_always);
   const int ntcap = max_tok < GV_MAXTOK ? max_tok : GV_MAXTOK;
   int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
   if (kseg >= max_k) kseg = max_k;
   const size_t smem = (size_t)ntcap * kseg * 2;
   int rows_per_wave = max_k >= 2048 ? 1 : 2;
+  if (use_q8 && max_k >= 2048) rows_per_wave = 2;   // a row is half as many bytes: two per wave keep as much in flight
   if (g_gemv_rows > 0) rows_per_wave = g_gemv_rows;
   if (ntcap > 2 && rows_per_wave > 2) rows_per_wave = 2;   // accumulators: rows x tokens x {gate, up}
   const int threads = ntcap > 4 ? 1024 : 256;
@@ -201,7 +288,12 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   } while (0)
 #define MOE_GEMV_LAUNCH_R(MODE, NTMAX, R)                                                     \
   do {                                                                                        \
-    auto kern = grouped_gemv_kernel<MODE, NTMAX, R, (NTMAX > 4 ? 1024 : 256)>;                \
+    if (use_q8) MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, true);                                      \
+    else MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, false);                                            \
+  } while (0)
+#define MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, Q)                                                  \
+  do {                                                                                        \
+    auto kern = grouped_gemv_kernel<MODE, NTMAX, R, (NTMAX > 4 ? 1024 : 256), Q>;             \
     static bool attr_set = false;                                                             \
     if (!attr_set) {                                                                          \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                \
@@ -225,6 +317,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   }
 #undef MOE_GEMV_LAUNCH
 #undef MOE_GEMV_LAUNCH_R
+#undef MOE_GEMV_LAUNCH_Q
   return hipGetLastError();
 }
 

@@ -68,6 +68,14 @@ struct GemmArgs {
   int splitk;             // K slices, each written to its own output plane
   long long out_split_stride;  // elements between planes
   int spare_cus;          // persistent GEMM: compute units to leave to kernels of other streams
+  // Mat-vec kernels only: 8-bit copies of the same weights (e4m3 codes, one fp32 scale per B row).
+  // Expert e with bit e of q8_mask set is streamed from qbase + slot[e] * qstride instead of its bf16
+  // blob: codes of the B rows at q_b0_off / q_b1_off (K bytes per row), their scales at q_s0_off /
+  // q_s1_off.  The weight used is bf16_rne(value(code) * scale), the bf16 blob's value.  K % 16 == 0.
+  unsigned long long q8_mask;
+  const char *qbase;
+  long long qstride;
+  long long q_b0_off, q_b1_off, q_s0_off, q_s1_off;
 };
 
 enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
@@ -85,6 +93,7 @@ void set_gemm_variant(int mode, int variant);
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra = nullptr);
 
+void set_gemv_q8_always(int on);   // test hook: use the 8-bit copies whatever the experts' size
 void set_gemv_rows(int rows);   // tuning hook: weight rows per wave (0 = choose by shape)
 
 // ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----

@@ -331,7 +331,11 @@ def test_q8_streaming_through_two_slots(gpu, oracle, T, decode):
     w = S.Workload("q8_stream", d=256, I=192, E=8, k=2, T=T, seed=52, zipf_s=0.8)
     x = S.activations(w)
     bias = S.zipf_route_bias(w, 0)
-    r = run_layer(gpu, w, T, x, 2, None, decode=decode, bias=bias, prefetch=[7, 6], poison=True, q8=True)
+    try:
+        gpu["binding"].moe_set_gemm_variant(6, 2)    # small experts: force the mat-vecs onto the 8-bit copies
+        r = run_layer(gpu, w, T, x, 2, None, decode=decode, bias=bias, prefetch=[7, 6], poison=True, q8=True)
+    finally:
+        gpu["binding"].moe_set_gemm_variant(6, 0)
     ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias)
     np.testing.assert_array_equal(r["routing"]["ids"], ref["ids"])
     check_out(r["out"], ref["out_f64"], f"q8 streaming T={T}")
@@ -340,6 +344,43 @@ def test_q8_streaming_through_two_slots(gpu, oracle, T, decode):
     sim.serve(np.nonzero(ref["counts"])[0])
     assert r["stats"] == {**sim.counters(), "layer_calls": 1}
     assert r["state"] == sim.slot_expert
+
+
+@pytest.mark.parametrize("d,I,I_shared,T", [(256, 192, 64, 1), (256, 192, 64, 2), (256, 192, 0, 5), (256, 192, 64, 8),
+                                            (256, 192, 64, 11), (2048, 96, 0, 1), (2048, 96, 32, 3), (4096, 64, 0, 8),
+                                            (264, 136, 0, 2)])
+def test_q8_decode_streams_the_8bit_copies(gpu, oracle, d, I, I_shared, T):
+    """Decode on experts the library fetched in 8-bit form: the mat-vec kernels read the codes and
+    scales from the staging areas and expand them in registers to the same bf16 weights the slots hold
+    (hardware e4m3 conversion, one fp32 multiply, nearest-even bf16), so the output is the oracle's on
+    the expanded weights.  To show where the weights came from, the bf16 slots are overwritten with
+    NaN patterns after the fetch.  Shared experts (bf16) ride in the same launches.  d = 264 is not a
+    multiple of 16: there the kernels must take the bf16 slots (left intact), also when forced."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("q8_decode", d=d, I=I, E=6, k=2, T=T, I_shared=I_shared, seed=54 + T)
+    x = S.activations(w)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=1)
+    pool = H.HostPool(w, 0, q8=True)
+    lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
+    buf = H.Buffers(ctx, T)
+    ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
+    torch.cuda.synchronize()
+    from_copies = d % 16 == 0
+    if from_copies:
+        lay.slots.fill_(0x7FC0)
+        torch.cuda.synchronize()
+    try:
+        B.moe_set_gemm_variant(6, 2)     # these experts are small: force the 8-bit source
+        ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+        gpu["compute"].synchronize()
+    finally:
+        B.moe_set_gemm_variant(6, 0)
+    ref = oracle_layer(oracle, w, x, lay.router_np, pool, shared=lay.shared_np)
+    np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
+    check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"q8 decode T={T}")
+    st = ctx.moe_get_stats(0)
+    assert st["misses"] == 0 and st["prefetch_issued"] == w.E
+    ctx.close()
 
 
 def test_q8_and_bf16_pools_of_the_same_weights_agree_within_the_format_error(gpu, oracle):
