@@ -13,9 +13,11 @@ from .binding import MoeContext
 
 def np_to_dev(a: np.ndarray, device="cuda:0") -> torch.Tensor:
     """uint16 (bf16 bits) / float32 / int32 numpy array -> device tensor with the same bits."""
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16)).to(device)
-    return torch.from_numpy(a).to(device)
+    t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(device)
+    # the copy is ordered on torch's current stream only; the library's streams are independent of it,
+    # so the tensor must have landed before it is handed to a call
+    torch.cuda.current_stream(t.device).synchronize()
+    return t
 
 
 def dev_to_np_u16(t: torch.Tensor) -> np.ndarray:

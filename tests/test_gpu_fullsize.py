@@ -31,7 +31,7 @@ def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=
     x_np = S.activations(w)
     x = H.np_to_dev(x_np)
     bias_np = S.zipf_route_bias(w, 0) if w.zipf_s > 0 else None
-    bias = None if bias_np is None else torch.from_numpy(bias_np).cuda()
+    bias = None if bias_np is None else H.np_to_dev(bias_np)
     torch.cuda.synchronize()
     if prefetch is not None:
         ctx.expert_cache_prefetch(0, prefetch, gpu["copy"])
@@ -126,7 +126,7 @@ def decode_case(gpu, oracle, w, n_layers, steps):
             x_np = S.activations(w, l, s)
             x = H.np_to_dev(x_np)
             bias_np = S.trace_route_bias(trace[s, l], w.E)
-            bias = torch.from_numpy(bias_np).cuda()
+            bias = H.np_to_dev(bias_np)
             if l + 1 < n_layers:
                 ctx.predictor_score(x, w.T, wps[l + 1], w.top_m, top, pred)
             ctx.moe_decode_layer(l, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, w.E)

@@ -51,7 +51,7 @@ def run_layer(gpu, w, T, x_np, S_slots, initial, decode=False, bias=None, prefet
     lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=poison)
     buf = H.Buffers(ctx, T)
     x = H.np_to_dev(x_np)
-    bias_t = None if bias is None else torch.from_numpy(bias).cuda()
+    bias_t = None if bias is None else H.np_to_dev(bias)
     stride = 0 if bias is None or bias.ndim == 1 else w.E
     torch.cuda.synchronize()
     if prefetch is not None:
@@ -123,7 +123,7 @@ def test_gate_logits_bit_exact(gpu, oracle, d, E, k, T):
     buf = H.Buffers(ctx, T)
     got = torch.empty((T, E), dtype=torch.float32, device="cuda")
     ctx.moe_prefill_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"],
-                          torch.from_numpy(bias).cuda(), E)
+                          H.np_to_dev(bias), E)
     ctx.moe_debug_logits(buf.ws, T, got, gpu["compute"])
     gpu["compute"].synchronize()
     want = oracle.router_logits(x, lay.router_np, bias)
@@ -253,7 +253,7 @@ def test_shared_cache_decode_steps(gpu, oracle, slots):
             x_np = S.activations(w, l, s)
             x = H.np_to_dev(x_np)
             bias_np = S.trace_route_bias(trace[s, l], w.E)
-            bias = torch.from_numpy(bias_np).cuda()
+            bias = H.np_to_dev(bias_np)
             nxt = l + 1                              # the first layer of a step has no prediction:
             if nxt < w.L:                            # its experts are fetched after the gate has chosen
                 ctx.predictor_score(x, w.T, wps[nxt], w.top_m, top, pred)
@@ -462,7 +462,7 @@ def test_paper_decode_flow_state_constructor_mlp_and_one_cache(gpu, oracle):
             x_np = S.activations(w, l, s)
             bias_np = S.trace_route_bias(trace[s, l], w.E)
             ctx.moe_decode_layer(l, H.np_to_dev(x_np), w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"],
-                                 torch.from_numpy(bias_np).cuda(), w.E)
+                                 H.np_to_dev(bias_np), w.E)
             gpu["compute"].synchronize()
             ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k,
                                    bias=bias_np, I=w.I)
