@@ -22,6 +22,9 @@
  *    call may run part of its work (the shared experts) on a stream of the library's
  *    own, forked from and joined back into compute_stream inside the call: everything
  *    a call enqueues is complete when compute_stream reaches the end of the call.
+ *    Device inputs (activations, route bias, predictor inputs) are read on the stream the call is
+ *    given: whatever produced them on another stream (an upload on a framework's own stream, say)
+ *    must be ordered before that stream by the caller.
  *  - Every function returns 0 on success or a negative MOE_E_* code and never throws
  *    or aborts; moe_last_error() returns a thread-local message for the last failure.
  *  - One ctx serves one (compute stream, copy stream) pair at a time; calls on the
