@@ -25,6 +25,16 @@ def check_out(got_bits, ref_f64, tag=""):
     assert np.all(err <= RTOL * np.abs(ref_f64) + RTOL * rms), f"{tag}: max err {err.max()} rms {rms}"
 
 
+@pytest.fixture(autouse=True)
+def _default_hooks():
+    """The tuning hooks are process-wide: whatever a test sets is back at its default for the next one."""
+    yield
+    from paper_2509_07379_amd import binding
+    if torch.cuda.is_available():
+        for mode in range(7):
+            binding.moe_set_gemm_variant(mode, 16 if mode == 5 else 0)
+
+
 @pytest.fixture(scope="module")
 def gpu():
     if not torch.cuda.is_available():
@@ -228,8 +238,8 @@ def test_wrong_prediction_is_refetched_not_used(gpu, oracle):
 
 
 # ---------------------------------------------------------------- one GPU expert cache for all layers
-@pytest.mark.parametrize("slots", [2, 3])
-def test_shared_cache_decode_steps(gpu, oracle, slots):
+@pytest.mark.parametrize("slots,q8", [(2, False), (3, False), (2, True)])
+def test_shared_cache_decode_steps(gpu, oracle, slots, q8):
     """Section V-A / V-C with the paper's cache size: ONE cache of k (or k + 1) experts serves every
     layer of a decode step in turn; the predictor of layer l + 1 runs on a third stream, its choice is
     prefetched into the slots that layer l frees, wrong guesses are fetched again.  Every layer call
@@ -237,13 +247,14 @@ def test_shared_cache_decode_steps(gpu, oracle, slots):
     from oracle.cache_sim import SharedCacheSim
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("shared_cache", d=256, I=128, E=8, k=2, T=1, seed=17, L=4, steps=5, p_stay=0.6, top_m=2)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, slots, 0, True, shared_slots=True)
-    pools = [H.HostPool(w, l) for l in range(w.L)]
-    cache = torch.full((slots, w.blob_elems), 0x7FC0, dtype=torch.int16, device="cuda")  # NaN until filled
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, slots, 0, True, shared_slots=True, host_format=1 if q8 else 0)
+    pools = [H.HostPool(w, l, q8=q8) for l in range(w.L)]
+    cache = torch.full((ctx.moe_cache_bytes() // 2,), 0x7FC0, dtype=torch.int16, device="cuda")  # NaN until filled
     lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
     wps_np = [S.predictor_weight(w, l) for l in range(w.L)]
     wps = [H.np_to_dev(a) for a in wps_np]
-    sim = SharedCacheSim(w.L, w.E, slots, w.blob_bytes)
+    sim = SharedCacheSim(w.L, w.E, slots, pools[0].bytes_per_expert)
+    B.moe_set_gemm_variant(6, 2 if q8 else 0)     # 8-bit pools: small experts, force the mat-vecs onto the copies
     trace = S.markov_trace(w)
     buf = H.Buffers(ctx, w.T)
     pred = torch.cuda.Stream()
@@ -259,8 +270,7 @@ def test_shared_cache_decode_steps(gpu, oracle, slots):
                 ctx.predictor_score(x, w.T, wps[nxt], w.top_m, top, pred)
             ctx.moe_decode_layer(l, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, w.E)
             gpu["compute"].synchronize()
-            ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k,
-                                   bias=bias_np, I=w.I)
+            ref = oracle_layer(oracle, w, x_np, lays[l].router_np, pools[l], bias=bias_np)
             np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
             check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"shared cache step {s} layer {l}")
             sim.serve(l, np.nonzero(ref["counts"])[0])
@@ -274,6 +284,7 @@ def test_shared_cache_decode_steps(gpu, oracle, slots):
             sim.prefetch(nxt, ref_top)
             assert ctx.moe_cache_state(nxt) == sim.state(nxt)
     torch.cuda.synchronize()
+    B.moe_set_gemm_variant(6, 0)
     for l in range(w.L):
         assert ctx.moe_get_stats(l) == {**sim.counters(l), "layer_calls": w.steps}, f"layer {l}"
     ctx.close()
