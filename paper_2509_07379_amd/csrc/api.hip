@@ -978,7 +978,7 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out) {
   if (!st || !host_out) return fail(MOE_E_ARG, "NULL argument");
   if (layer < 0 || layer >= st->L) return fail(MOE_E_ARG, "layer %d out of range", layer);
   for (int j = 0; j < layer; ++j)
-    if (!st->have[j]) return fail(MOE_E_ARG, "layer %d has not been recorded in this round", j);
+    if (!st->have[j]) return fail(MOE_E_ARG, "layer %d has not been recorded in this decode step", j);
   const int L = st->L, M = st->M, k = st->k;
   const int dim = L * k + M + k * M;
   for (int i = 0; i < dim; ++i) host_out[i] = 0.0f;

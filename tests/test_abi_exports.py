@@ -55,7 +55,7 @@ def test_state_constructor_matches_the_oracle():
     for episode in (3, 17):
         st.moe_state_clear()
         with pytest.raises(binding.MoeError):
-            st.moe_state_vector(1, out)              # layer 0 not recorded yet in this round
+            st.moe_state_vector(1, out)              # layer 0 not recorded yet in this decode step
         history = []
         for l in range(w.L):
             st.moe_state_vector(l, out)
