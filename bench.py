@@ -117,17 +117,19 @@ def prefill_large_batch(args, torch, B, H, S, w, res, rep):
             "gemm2_TFLOPs": 2.0 * rows * wl.d * wl.I / (g2 * 1e-3) / 1e12}
 
 
-def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, q8=False):
+def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, fmt=0):
     """Offloaded regime: S = w.S slots, experts fetched from pinned memory on the copy stream; a
     stand-in attention block (4 bf16 GEMMs T x d x d) runs on the compute stream while the first
     experts are prefetched.  Returns T_copy-alone, T_compute-alone and T_pipelined per layer.
-    q8: the CPU expert cache holds the same experts as e4m3 codes with per-row scales (half the
-    bytes on the link, expanded into the bf16 slots by a kernel behind each copy)."""
+    fmt 1 / 2: the CPU expert cache holds the same experts as e4m3 codes with per-row scales / as 4-bit
+    codes in groups of 128 (half / about a quarter of the bytes on the link, expanded into the bf16
+    slots by a kernel behind each copy)."""
+    q8 = fmt != 0
     if q8:
         t0 = time.time()
-        pool = H.HostPool(w, 0, q8=True)
-        log(f"[bench] 8-bit host pool {w.E * pool.bytes_per_expert / 1e9:.2f} GB quantised in {time.time() - t0:.1f}s")
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared, host_format=1 if q8 else 0)
+        pool = H.HostPool(w, 0, fmt=fmt)
+        log(f"[bench] {8 if fmt == 1 else 4}-bit host pool {w.E * pool.bytes_per_expert / 1e9:.2f} GB quantised in {time.time() - t0:.1f}s")
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared, host_format=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, None)
     buf = H.Buffers(ctx, w.T)
     wa = H.np_to_dev(S.normal_bf16((4, w.d, w.d), w.seed, S.stream_id(S.KIND_ATTN), 0.02))
@@ -376,7 +378,7 @@ def main():
                     help="also time the layer on this many times the workload's tokens (0 or 1: skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offloaded", action="store_true")
-    ap.add_argument("--no-q8", action="store_true", help="skip the 8-bit-host-pool leg of the offloaded regime")
+    ap.add_argument("--no-q8", action="store_true", help="skip the legs with quantised host pools")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--decode-layers", type=int, default=8, help="layers of the decode workload held in memory")
     ap.add_argument("--decode-steps", type=int, default=32)
@@ -453,16 +455,18 @@ def main():
             "link_busy_frac": t_c / t_p,
         }
         log(f"[bench] offloaded: {line['offloaded']}")
-        if not args.no_q8:
-            o8 = prefill_offloaded(args, torch, B, H, S, w, None, res["x"], compute, copy, q8=True)
-            t_c, t_p = o8["t_copy_ms"], o8["t_pipelined_ms"]
-            line["offloaded_q8"] = {
-                "host_format": "e4m3 codes + fp32 scale per row, expanded into the bf16 slots by a kernel behind each copy",
+        formats = {"offloaded_q8": (1, "e4m3 codes + fp32 scale per row"),
+                   "offloaded_q4": (2, "4-bit codes in groups of 128 + fp32 scale and zero point per group")}
+        for key, (fmt, what) in ({} if args.no_q8 else formats).items():
+            oq = prefill_offloaded(args, torch, B, H, S, w, None, res["x"], compute, copy, fmt=fmt)
+            t_c, t_p = oq["t_copy_ms"], oq["t_pipelined_ms"]
+            line[key] = {
+                "host_format": what + ", expanded into the bf16 slots by a kernel behind each copy",
                 "slots": w.S, "ms_per_layer": t_p, "tokens_per_s": w.T / (t_p * 1e-3), "t_copy_alone_ms": t_c,
-                "bytes_per_layer": o8["bytes_per_layer"], "h2d_GBps": o8["bytes_per_layer"] / (t_c * 1e-3) / 1e9,
+                "bytes_per_layer": oq["bytes_per_layer"], "h2d_GBps": oq["bytes_per_layer"] / (t_c * 1e-3) / 1e9,
                 "overlap": (t_c + t_k - t_p) / min(t_c, t_k), "link_busy_frac": t_c / t_p,
             }
-            log(f"[bench] offloaded_q8: {line['offloaded_q8']}")
+            log(f"[bench] {key}: {line[key]}")
 
     if not args.no_decode:
         wd = S.WORKLOADS["c3_mixtral_decode"]

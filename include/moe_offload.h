@@ -84,6 +84,14 @@ typedef struct {
  *   experts the caller placed with initial_resident, they read the bf16 slot. */
 #define MOE_FMT_BF16 0
 #define MOE_FMT_E4M3_ROWS 1
+/* MOE_FMT_INT4_G128: 4-bit weights, the storage form of AWQ / GPTQ-style quantisation: unsigned 4-bit
+ *   codes, two per byte (even column in the low nibble), in groups of 128 along a row with one fp32
+ *   scale and one zero point (a byte, 0..15) per group; d and I multiples of 128.  Blob:
+ *   [scales of [W_gate; W_up] (2I x d/128 fp32)][scales of W_down (d x I/128 fp32)][zero points, same
+ *   order (bytes)][padding to a multiple of 16][codes of [W_gate; W_up] (2I x d/2)][codes of W_down
+ *   (d x I/2)].  Fetched and expanded like MOE_FMT_E4M3_ROWS:
+ *   weight = bf16 nearest-even of fp32((code - zero) * scale).  The mat-vec kernels read the bf16 slots. */
+#define MOE_FMT_INT4_G128 2
 
 /* Cache counters (host side).  hits/misses count active experts per layer call. */
 typedef struct {
@@ -105,7 +113,8 @@ int moe_create(const moe_config *cfg, moe_ctx **out);
  * device is idle. */
 int moe_destroy(moe_ctx *ctx);
 
-/* Bytes of one expert in the CPU expert cache: 6*d*I (bf16) or 4*(2I+d) + 3*d*I (e4m3 rows). */
+/* Bytes of one expert in the CPU expert cache: 6*d*I (bf16), 4*(2I+d) + 3*d*I (e4m3 rows) or
+ * 15*d*I/128 rounded up to 16, plus 3*d*I/2 (int4 groups). */
 size_t moe_host_blob_bytes(const moe_config *cfg);
 /* Bytes of one GPU expert cache (dev_slots of moe_bind_layer): cache_slots slots of 6*d*I bytes,
  * followed, for an 8-bit host format, by one staging area per slot. */

@@ -47,6 +47,8 @@ def _load():
         lib.ref_e4m3_value.restype = ctypes.c_float
         lib.ref_dequant_e4m3_rows.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         lib.ref_dequant_e4m3_rows.restype = None
+        lib.ref_dequant_int4_g128_rows.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
+        lib.ref_dequant_int4_g128_rows.restype = None
         lib.ref_bf16_from_f64.argtypes = [ctypes.c_double]
         lib.ref_bf16_from_f64.restype = ctypes.c_uint16
         for f in ("ref_router_logits", "ref_topk_weights", "ref_dispatch", "ref_expert_ffn",
@@ -226,4 +228,22 @@ def dequant_blob(qblob, d: int, I: int) -> np.ndarray:
     lib = _load()
     lib.ref_dequant_e4m3_rows(_p(codes[:2 * I * d]), _p(scales[:2 * I]), 2 * I, d, _p(out[:2 * I * d]))
     lib.ref_dequant_e4m3_rows(_p(codes[2 * I * d:]), _p(scales[2 * I:]), d, I, _p(out[2 * I * d:]))
+    return out
+
+
+def dequant4_blob(qblob, d: int, I: int) -> np.ndarray:
+    """4-bit expert blob -> the bf16 blob the layer computes with.  Layout: fp32 scales of [W_gate; W_up]
+    (2I x d/128) and of W_down (d x I/128), their zero points (bytes, same shapes), padding to 16 bytes,
+    then the codes of [W_gate; W_up] (2I x d/2 bytes) and of W_down (d x I/2 bytes)."""
+    q = np.ascontiguousarray(qblob).view(np.uint8).ravel()
+    n_up, n_dn = 2 * I * (d // 128), d * (I // 128)
+    meta = (5 * (n_up + n_dn) + 15) // 16 * 16
+    assert d % 128 == 0 and I % 128 == 0 and q.size == meta + 3 * d * I // 2
+    scales = q[:4 * (n_up + n_dn)].view(np.float32)
+    zeros = q[4 * (n_up + n_dn):5 * (n_up + n_dn)]
+    codes = q[meta:]
+    out = np.empty(3 * d * I, dtype=np.uint16)
+    lib = _load()
+    lib.ref_dequant_int4_g128_rows(_p(codes[:I * d]), _p(scales[:n_up]), _p(zeros[:n_up]), 2 * I, d, _p(out[:2 * I * d]))
+    lib.ref_dequant_int4_g128_rows(_p(codes[I * d:]), _p(scales[n_up:]), _p(zeros[n_up:]), d, I, _p(out[2 * I * d:]))
     return out

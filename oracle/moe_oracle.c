@@ -343,3 +343,24 @@ void ref_dequant_e4m3_rows(const uint8_t *q, const float *scales, int64_t rows, 
       out_bf16[r * cols + c] = bf16_from_f64((double)prod);
     }
 }
+
+/*
+ * 4-bit expert weights on the host link (Section VI serves quantised models; the format is this
+ * build's reading: unsigned 4-bit integers, groups of 128 along a row, one fp32 scale and one zero
+ * point per group).  A weight is  bf16_rne( fp32( (code - zero) * scale ) ):  the integer difference
+ * (-15..15) is exact in fp32, the product is rounded once to fp32 and once more to bf16.
+ * codes: two per byte, the even column in the low nibble.  cols % 128 == 0.
+ */
+void ref_dequant_int4_g128_rows(const uint8_t *codes, const float *scales, const uint8_t *zeros, int64_t rows,
+                                int64_t cols, uint16_t *out_bf16) {
+  const int64_t groups = cols / 128;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      const uint8_t byte = codes[(r * cols + c) / 2];
+      const int code = (c & 1) ? (byte >> 4) : (byte & 15);
+      const int64_t g = r * groups + c / 128;
+      const float prod = (float)(code - (int)zeros[g]) * scales[g];
+      out_bf16[r * cols + c] = bf16_from_f64((double)prod);
+    }
+}

@@ -172,8 +172,10 @@ int check_cfg(const moe_config *c) {
   if (c->E > kMaxExperts) return fail(MOE_E_UNSUPPORTED, "E = %d > %d experts", c->E, kMaxExperts);
   if (c->d % 8 || c->I % 8 || c->I_shared % 8)
     return fail(MOE_E_UNSUPPORTED, "d, I and I_shared must be multiples of 8");
-  if (c->host_format != MOE_FMT_BF16 && c->host_format != MOE_FMT_E4M3_ROWS)
+  if (c->host_format != MOE_FMT_BF16 && c->host_format != MOE_FMT_E4M3_ROWS && c->host_format != MOE_FMT_INT4_G128)
     return fail(MOE_E_ARG, "host_format = %d is not a known format", c->host_format);
+  if (c->host_format == MOE_FMT_INT4_G128 && (c->d % 128 || c->I % 128))
+    return fail(MOE_E_UNSUPPORTED, "MOE_FMT_INT4_G128 needs d and I to be multiples of 128");
   return MOE_OK;
 }
 
@@ -250,38 +252,60 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   char *dst = L.set->slots + (size_t)s * ctx->blob_bytes;
   const char *src = static_cast<const char *>(L.host_blob[e]);
   const moe_config &c = ctx->cfg;
-  if (c.host_format == MOE_FMT_E4M3_ROWS) {
-    // [scales: 2I gate/up rows, d down rows][gate codes][up codes][down codes] lands in the slot's
-    // staging area on the copy stream; kernels on the expansion stream, each behind the copy it
-    // reads, write the slot.  copied_up / copied are recorded there, after the expansion.
+  if (c.host_format != MOE_FMT_BF16) {
+    // The quantised blob ([scales and zero points][gate codes][up codes][down codes]) lands in the
+    // slot's staging area on the copy stream; kernels on the expansion stream, each behind the copy
+    // it reads, write the slot.  copied_up / copied are recorded there, after the expansion.
     SlotSet &set = *L.set;
     hipStream_t xs = ctx->expand;
     char *stage = set.slots + (size_t)c.cache_slots * ctx->blob_bytes + (size_t)s * ctx->stage_stride;
-    const size_t scale_bytes = (size_t)4 * (2 * c.I + c.d), up_codes = (size_t)2 * c.I * c.d;
-    const float *scales = reinterpret_cast<const float *>(stage);
-    const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + scale_bytes);
+    const size_t Id = (size_t)c.I * c.d;
     uint16_t *w = reinterpret_cast<uint16_t *>(dst);
+    size_t meta_bytes, up_codes;   // bytes in front of the codes; bytes of the gate and up codes
+    if (c.host_format == MOE_FMT_E4M3_ROWS) {
+      meta_bytes = (size_t)4 * (2 * c.I + c.d);
+      up_codes = 2 * Id;
+    } else {
+      meta_bytes = (15 * Id / 128 + 15) / 16 * 16;
+      up_codes = Id;
+    }
+    const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + meta_bytes);
+    auto expand = [&](bool down) -> int {
+      if (c.host_format == MOE_FMT_E4M3_ROWS) {
+        const float *scales = reinterpret_cast<const float *>(stage);
+        if (!down) HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
+        else HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + 2 * Id, xs));
+      } else {
+        const size_t n_up = 2 * Id / 128, n_dn = Id / 128;
+        const float *scales = reinterpret_cast<const float *>(stage);
+        const uint8_t *zeros = reinterpret_cast<const uint8_t *>(stage + 4 * (n_up + n_dn));
+        if (!down) HIP_TRY(launch_dequant_int4_g128(codes, scales, zeros, 2 * c.I, c.d, w, xs));
+        else HIP_TRY(launch_dequant_int4_g128(codes + up_codes, scales + n_up, zeros + n_up, c.d, c.I, w + 2 * Id, xs));
+      }
+      return MOE_OK;
+    };
     // the staging area's last expansion must be over before new bytes land in it
     if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
     set.staged[s] = 1;
-    set.q_valid[s] = 1;
+    set.q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS;   // the mat-vec kernels can read this form
+    int rc = MOE_OK;
     if (split) {
-      HIP_TRY(hipMemcpyAsync(stage, src, scale_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
+      HIP_TRY(hipMemcpyAsync(stage, src, meta_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
       HIP_TRY(hipEventRecord(set.landed_up[s], copy_stream));
-      HIP_TRY(hipMemcpyAsync(stage + scale_bytes + up_codes, src + scale_bytes + up_codes,
-                             ctx->host_blob_bytes - scale_bytes - up_codes, hipMemcpyHostToDevice, copy_stream));
+      HIP_TRY(hipMemcpyAsync(stage + meta_bytes + up_codes, src + meta_bytes + up_codes,
+                             ctx->host_blob_bytes - meta_bytes - up_codes, hipMemcpyHostToDevice, copy_stream));
       HIP_TRY(hipEventRecord(set.landed[s], copy_stream));
       HIP_TRY(hipStreamWaitEvent(xs, set.landed_up[s], 0));
-      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
+      if ((rc = expand(false))) return rc;
       HIP_TRY(hipEventRecord(set.copied_up[s], xs));
       HIP_TRY(hipStreamWaitEvent(xs, set.landed[s], 0));
     } else {
       HIP_TRY(hipMemcpyAsync(stage, src, ctx->host_blob_bytes, hipMemcpyHostToDevice, copy_stream));
       HIP_TRY(hipEventRecord(set.landed[s], copy_stream));
       HIP_TRY(hipStreamWaitEvent(xs, set.landed[s], 0));
-      HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
+      if ((rc = expand(false))) return rc;
     }
-    HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + up_codes, xs));
+    if ((rc = expand(true))) return rc;
     HIP_TRY(hipEventRecord(set.copied[s], xs));
     ctx->expand_tail = set.copied[s];
   } else if (split) {
@@ -687,7 +711,7 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   ctx->cfg = *cfg;
   ctx->blob_bytes = (size_t)6 * cfg->d * cfg->I;
   ctx->host_blob_bytes = moe_host_blob_bytes(cfg);
-  ctx->stage_stride = cfg->host_format == MOE_FMT_E4M3_ROWS ? (ctx->host_blob_bytes + 255) / 256 * 256 : 0;
+  ctx->stage_stride = cfg->host_format != MOE_FMT_BF16 ? (ctx->host_blob_bytes + 255) / 256 * 256 : 0;
   HIP_TRY(hipGetDevice(&ctx->device));
   ctx->layers.resize(cfg->n_layers);
   HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), (kMaxExperts + 1) * sizeof(int32_t), 0));
@@ -740,13 +764,15 @@ int moe_destroy(moe_ctx *ctx) {
 size_t moe_host_blob_bytes(const moe_config *cfg) {
   if (check_cfg(cfg)) return 0;
   const size_t dI = (size_t)cfg->d * cfg->I;
-  return cfg->host_format == MOE_FMT_E4M3_ROWS ? (size_t)4 * (2 * cfg->I + cfg->d) + 3 * dI : 6 * dI;
+  if (cfg->host_format == MOE_FMT_E4M3_ROWS) return (size_t)4 * (2 * cfg->I + cfg->d) + 3 * dI;
+  if (cfg->host_format == MOE_FMT_INT4_G128) return (15 * dI / 128 + 15) / 16 * 16 + 3 * dI / 2;
+  return 6 * dI;
 }
 
 size_t moe_cache_bytes(const moe_config *cfg) {
   if (check_cfg(cfg)) return 0;
   const size_t slot = (size_t)6 * cfg->d * cfg->I;
-  const size_t stage = cfg->host_format == MOE_FMT_E4M3_ROWS ? (moe_host_blob_bytes(cfg) + 255) / 256 * 256 : 0;
+  const size_t stage = cfg->host_format != MOE_FMT_BF16 ? (moe_host_blob_bytes(cfg) + 255) / 256 * 256 : 0;
   return (size_t)cfg->cache_slots * (slot + stage);
 }
 

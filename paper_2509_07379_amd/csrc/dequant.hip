@@ -1,5 +1,6 @@
-// Expansion of 8-bit expert weights (OCP e4m3 codes, one fp32 scale per output row) into the bf16
-// matrices the GPU expert cache holds.  The paper evaluates quantised models (Section VI); in this
+// Expansion of 8-bit expert weights (OCP e4m3 codes, one fp32 scale per output row) and of 4-bit ones
+// (unsigned integers in groups of 128 with scale and zero point) into the bf16 matrices the GPU
+// expert cache holds.  The paper evaluates quantised models (Section VI); in this
 // library only the copy over the host link is 8-bit: a fetched expert lands in a staging area next
 // to the cache and this kernel writes its slot, so every matmul kernel reads bf16 as before.
 //   weight = bf16_rne( fp32( value(code) * scale[row] ) )
@@ -54,7 +55,52 @@ __global__ __launch_bounds__(kThreads) void dequant_e4m3_rows_kernel(const uint8
   }
 }
 
+// 4-bit codes (unsigned, two per byte, even column in the low nibble), groups of 128 along a row with
+// one fp32 scale and one zero point each:  out = bf16_rne(fp32((code - zero) * scale)).
+// One lane expands 16 codes (one 8-byte load, two 16-byte stores); cols % 128 == 0.
+__global__ __launch_bounds__(kThreads) void dequant_int4_g128_kernel(const uint8_t *__restrict__ codes,
+                                                                     const float *__restrict__ scales,
+                                                                     const uint8_t *__restrict__ zeros,
+                                                                     long long rows, int cols,
+                                                                     uint16_t *__restrict__ out) {
+  const int per_row = cols >> 4;          // 16-code pieces per row
+  const int groups = cols >> 7;
+  const long long pieces = rows * per_row;
+  for (long long c = (long long)blockIdx.x * kThreads + threadIdx.x; c < pieces;
+       c += (long long)gridDim.x * kThreads) {
+    const long long row = c / per_row;
+    const int piece = (int)(c - row * per_row);
+    const long long g = row * groups + (piece >> 3);
+    const float s = scales[g];
+    const int z = zeros[g];
+    const uint2 q = *reinterpret_cast<const uint2 *>(codes + c * 8);
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t byte = ((j < 4 ? q.x : q.y) >> ((j & 3) * 8)) & 0xFFu;
+      const float lo = (float)((int)(byte & 15u) - z) * s;
+      const float hi = (float)((int)(byte >> 4) - z) * s;
+      w[j] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    }
+    uint4 *dst = reinterpret_cast<uint4 *>(out + c * 16);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_dequant_int4_g128(const uint8_t *codes, const float *scales, const uint8_t *zeros,
+                                    long long rows, int cols, uint16_t *out, hipStream_t stream) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (cols % 128) return hipErrorInvalidValue;
+  const long long pieces = rows * (cols >> 4);
+  long long blocks = (pieces + kThreads - 1) / kThreads;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(dequant_int4_g128_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, codes, scales,
+                     zeros, rows, cols, out);
+  return hipGetLastError();
+}
 
 hipError_t launch_dequant_e4m3_rows(const uint8_t *q, const float *scales, long long rows, int cols,
                                     uint16_t *out, hipStream_t stream) {

@@ -26,21 +26,26 @@ def dev_to_np_u16(t: torch.Tensor) -> np.ndarray:
 
 class HostPool:
     """All experts of one layer in pinned host memory: the CPU expert cache (Section V-A).
-    q8: experts stored as e4m3 codes with per-row scales (quantised from the seeded bf16 blobs)."""
+    fmt 0: bf16 blobs; 1 (or q8=True): e4m3 codes with per-row scales; 2: 4-bit codes in groups of 128 with
+    scale and zero point -- both quantised from the seeded bf16 blobs."""
 
     def __init__(self, w: S.Workload, layer: int, fill: bool = True, share_from: "HostPool | None" = None,
-                 q8: bool = False):
-        self.w, self.layer, self.q8 = w, layer, q8
-        self.bytes_per_expert = S.q8_blob_bytes(w.d, w.I) if q8 else w.blob_bytes
+                 q8: bool = False, fmt: "int | None" = None):
+        self.fmt = (1 if q8 else 0) if fmt is None else fmt
+        self.w, self.layer, self.q8 = w, layer, self.fmt != 0     # q8: "holds a quantised form"
+        self.bytes_per_expert = (w.blob_bytes, S.q8_blob_bytes(w.d, w.I),
+                                 S.q4_blob_bytes(w.d, w.I) if self.fmt == 2 else 0)[self.fmt]
         if share_from is not None:
-            assert share_from.q8 == q8
+            assert share_from.fmt == self.fmt
             self.buf = share_from.buf
         else:
             self.buf = torch.empty((w.E, self.bytes_per_expert), dtype=torch.uint8, pin_memory=True)
             if fill:
                 for e in range(w.E):
-                    if q8:
+                    if self.fmt == 1:
                         S.quantize_blob_into(self.ptr(e), S.expert_blob(w, layer, e), w.d, w.I)
+                    elif self.fmt == 2:
+                        S.quantize4_blob_into(self.ptr(e), S.expert_blob(w, layer, e), w.d, w.I)
                     else:
                         S.expert_blob_into(self.ptr(e), w, layer, e)
 

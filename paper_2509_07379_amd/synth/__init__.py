@@ -45,6 +45,9 @@ def _load():
         lib.synth_quantize_e4m3_rows.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                                  ctypes.c_void_p]
         lib.synth_quantize_e4m3_rows.restype = None
+        lib.synth_quantize_int4_g128.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                                 ctypes.c_void_p, ctypes.c_void_p]
+        lib.synth_quantize_int4_g128.restype = None
         _lib = lib
     return _lib
 
@@ -268,3 +271,35 @@ def quantize_blob_into(ptr: int, blob_bf16: np.ndarray, d: int, I: int) -> None:
                                  ctypes.c_void_p(ptr + scales_bytes))
     lib.synth_quantize_e4m3_rows(ctypes.c_void_p(blob_bf16.ctypes.data + 2 * (2 * I * d)), d, I,
                                  ctypes.c_void_p(ptr + 4 * 2 * I), ctypes.c_void_p(ptr + scales_bytes + 2 * I * d))
+
+
+# ---------------------------------------------------------------------------
+# expert blobs in 4 bits: unsigned codes in groups of 128 along a row, fp32 scale + zero point per group
+# ---------------------------------------------------------------------------
+def q4_layout(d: int, I: int) -> dict:
+    """Byte offsets inside a 4-bit blob:
+    [scales of [W_gate; W_up] (2I x d/128 fp32)][scales of W_down (d x I/128 fp32)]
+    [zero points of [W_gate; W_up] (bytes)][zero points of W_down (bytes)][pad to 16]
+    [codes of [W_gate; W_up] (2I x d/2 bytes)][codes of W_down (d x I/2 bytes)]"""
+    assert d % 128 == 0 and I % 128 == 0
+    n_up, n_dn = 2 * I * (d // 128), d * (I // 128)
+    lay = dict(scales_up=0, scales_down=4 * n_up, zeros_up=4 * (n_up + n_dn), zeros_down=4 * (n_up + n_dn) + n_up)
+    meta = (5 * (n_up + n_dn) + 15) // 16 * 16
+    lay.update(meta=meta, codes_up=meta, codes_down=meta + I * d, total=meta + 3 * d * I // 2)
+    return lay
+
+
+def q4_blob_bytes(d: int, I: int) -> int:
+    return q4_layout(d, I)["total"]
+
+
+def quantize4_blob_into(ptr: int, blob_bf16: np.ndarray, d: int, I: int) -> None:
+    """Quantise a bf16 expert blob into the 4-bit layout at raw host address ptr (offline preparation)."""
+    blob_bf16 = np.ascontiguousarray(blob_bf16, dtype=np.uint16)
+    assert blob_bf16.size == 3 * d * I
+    lib, lay = _load(), q4_layout(d, I)
+    vp = ctypes.c_void_p
+    lib.synth_quantize_int4_g128(vp(blob_bf16.ctypes.data), 2 * I, d, vp(ptr + lay["scales_up"]),
+                                 vp(ptr + lay["zeros_up"]), vp(ptr + lay["codes_up"]))
+    lib.synth_quantize_int4_g128(vp(blob_bf16.ctypes.data + 2 * (2 * I * d)), d, I, vp(ptr + lay["scales_down"]),
+                                 vp(ptr + lay["zeros_down"]), vp(ptr + lay["codes_down"]))

@@ -119,3 +119,41 @@ void synth_quantize_e4m3_rows(const uint16_t *w_bf16, int64_t rows, int64_t cols
     for (int64_t c = 0; c < cols; ++c) q[r * cols + c] = e4m3_nearest(bf16_to_float(w[c]) / scale);
   }
 }
+
+/*
+ * Offline 4-bit quantiser: unsigned 4-bit integers in groups of 128 along a row, one fp32 scale and
+ * one zero point (0..15) per group, the storage form of AWQ / GPTQ-style weight quantisation
+ * (input preparation only).  Per group: scale = (max - min) / 15 (1 if the group is constant),
+ * zero = round(-min / scale) clamped to 0..15, code = round(w / scale) + zero clamped to 0..15;
+ * min and max include 0 so that a zero weight is representable.  Two codes per byte, the even
+ * column in the low nibble.  cols % 128 == 0.
+ * w_bf16 [rows, cols] -> scales [rows, cols/128] fp32, zeros [rows, cols/128] bytes, codes [rows, cols/2] bytes.
+ */
+void synth_quantize_int4_g128(const uint16_t *w_bf16, int64_t rows, int64_t cols, float *scales, uint8_t *zeros,
+                              uint8_t *codes) {
+  const int64_t groups = cols / 128;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t g = 0; g < groups; ++g) {
+      const uint16_t *w = w_bf16 + r * cols + g * 128;
+      float lo = 0.0f, hi = 0.0f;
+      for (int i = 0; i < 128; ++i) {
+        float v = bf16_to_float(w[i]);
+        if (v < lo) lo = v;
+        if (v > hi) hi = v;
+      }
+      float scale = hi > lo ? (hi - lo) / 15.0f : 1.0f;
+      float zf = nearbyintf(-lo / scale);
+      int zero = zf < 0.0f ? 0 : (zf > 15.0f ? 15 : (int)zf);
+      scales[r * groups + g] = scale;
+      zeros[r * groups + g] = (uint8_t)zero;
+      for (int i = 0; i < 128; i += 2) {
+        int q[2];
+        for (int j = 0; j < 2; ++j) {
+          float t = nearbyintf(bf16_to_float(w[i + j]) / scale) + (float)zero;
+          q[j] = t < 0.0f ? 0 : (t > 15.0f ? 15 : (int)t);
+        }
+        codes[(r * cols + g * 128 + i) / 2] = (uint8_t)(q[0] | (q[1] << 4));
+      }
+    }
+}

@@ -47,17 +47,19 @@ def gpu():
 
 def oracle_layer(oracle, w, x, router, pool, bias=None, sel=None, shared=None):
     blobs = [pool.blob_np(e) for e in range(w.E)]
-    if pool.q8:   # 8-bit CPU expert cache: the layer computes with the oracle's expansion of it
-        blobs = [oracle.dequant_blob(b, w.d, w.I) for b in blobs]
+    if pool.q8:   # quantised CPU expert cache: the layer computes with the oracle's expansion of it
+        expand = oracle.dequant4_blob if pool.fmt == 2 else oracle.dequant_blob
+        blobs = [expand(b, w.d, w.I) for b in blobs]
     return oracle.moe_layer(x, router, blobs, w.k, bias=bias, sel=sel, shared_blob=shared, I=w.I,
                             I_shared=w.I_shared)
 
 
 def run_layer(gpu, w, T, x_np, S_slots, initial, decode=False, bias=None, prefetch=None, poison=False,
-              pool=None, q8=False):
+              pool=None, q8=False, fmt=None):
     H, B = gpu["harness"], gpu["binding"]
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True, host_format=1 if q8 else 0)
-    pool = pool or H.HostPool(w, 0, q8=q8)
+    fmt = (1 if q8 else 0) if fmt is None else fmt
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True, host_format=fmt)
+    pool = pool or H.HostPool(w, 0, fmt=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=poison)
     buf = H.Buffers(ctx, T)
     x = H.np_to_dev(x_np)
@@ -332,6 +334,34 @@ def test_q8_fetch_expands_into_slots_bit_exact(gpu, oracle):
         np.testing.assert_array_equal(slots[s], oracle.dequant_blob(r["pool"].blob_np(e), w.d, w.I), err_msg=f"expert {e}")
     assert r["stats"]["bytes_h2d"] == len(active) * S.q8_blob_bytes(w.d, w.I)
     assert r["stats"]["misses"] == len(active)
+
+
+def test_q4_fetch_expands_into_slots_bit_exact(gpu, oracle):
+    """4-bit experts (groups of 128, scale and zero point): slots hold the oracle's expansion bit for
+    bit, the output is the oracle's on those weights, the link carried the 4-bit blobs; prefill through
+    all slots, then streaming through two with a wrong prefetch (prefill and decode)."""
+    from oracle.cache_sim import CacheSim
+    w = S.Workload("q4_slots", d=256, I=384, E=6, k=2, T=300, I_shared=64, seed=57)
+    x = S.activations(w)
+    r = run_layer(gpu, w, w.T, x, w.E, None, poison=True, fmt=2)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], shared=r["lay"].shared_np)
+    np.testing.assert_array_equal(r["routing"]["perm"], ref["perm"])
+    check_out(r["out"], ref["out_f64"], "q4 prefill")
+    slots = r["lay"].slots.cpu().numpy().view(np.uint16)
+    active = [e for e in range(w.E) if ref["counts"][e] > 0]
+    assert len(active) >= 4
+    for e in active:
+        np.testing.assert_array_equal(slots[r["state"].index(e)], oracle.dequant4_blob(r["pool"].blob_np(e), w.d, w.I),
+                                      err_msg=f"expert {e}")
+    assert r["stats"]["bytes_h2d"] == len(active) * S.q4_blob_bytes(w.d, w.I)
+    for T, decode in ((300, False), (3, True)):
+        r2 = run_layer(gpu, w, T, x[:T], 2, None, decode=decode, prefetch=[5, 4], poison=True, fmt=2, pool=r["pool"])
+        ref2 = oracle_layer(oracle, w, x[:T], r2["lay"].router_np, r2["pool"], shared=r2["lay"].shared_np)
+        check_out(r2["out"], ref2["out_f64"], f"q4 streaming T={T}")
+        sim = CacheSim(w.E, 2, S.q4_blob_bytes(w.d, w.I))
+        sim.prefetch([5, 4])
+        sim.serve(np.nonzero(ref2["counts"])[0])
+        assert r2["stats"] == {**sim.counters(), "layer_calls": 1}
 
 
 @pytest.mark.parametrize("T,decode", [(700, False), (3, True)])

@@ -116,3 +116,65 @@ def test_dequantised_weights_stay_within_the_format_error_bound():
     # the two roundings that follow (fp32 product, bf16) add at most 2^-8 relative
     bound = np.maximum(np.abs(a) * 2.0 ** -4, row_scale * 2.0 ** -10) * (1 + 2.0 ** -7) + np.abs(a) * 2.0 ** -8
     assert np.all(np.abs(a - b) <= bound)
+
+
+# ---------------------------------------------------------------- 4-bit integers, groups of 128
+def test_int4_dequant_by_hand():
+    """One row of 256 columns = two groups.  Group 0: scale 0.5, zero 8, codes 0..15 repeating -> values
+    (code - 8) / 2; group 1: scale 0.25, zero 0.  Two codes per byte, the even column in the low nibble."""
+    import ctypes
+    cols = 256
+    code = np.arange(cols) % 16
+    packed = (code[0::2] | (code[1::2] << 4)).astype(np.uint8)
+    scales = np.array([0.5, 0.25], dtype=np.float32)
+    zeros = np.array([8, 0], dtype=np.uint8)
+    out = np.empty(cols, dtype=np.uint16)
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    oracle._load().ref_dequant_int4_g128_rows(vp(packed), vp(scales), vp(zeros), 1, cols, vp(out))
+    got = S.bf16_to_f32(out)
+    want = np.concatenate([(code[:128] - 8) * 0.5, code[128:] * 0.25]).astype(np.float32)
+    np.testing.assert_array_equal(got, want)
+    assert got[1] == -3.5 and got[0] == -4.0          # column 1 came from the HIGH nibble of byte 0
+
+
+def test_int4_blob_layout_and_rounding_against_torch():
+    d, I = 256, 128
+    blob = S.normal_bf16((3 * d * I,), 8, 4, 0.03)
+    raw = np.zeros(S.q4_blob_bytes(d, I), dtype=np.uint8)
+    S.quantize4_blob_into(raw.ctypes.data, blob, d, I)
+    got = oracle.dequant4_blob(raw, d, I)
+    lay = S.q4_layout(d, I)
+    n_up, n_dn = 2 * I * (d // 128), d * (I // 128)
+
+    def expand(codes_off, rows, cols, scales_off, zeros_off, n):
+        b = torch.from_numpy(raw[codes_off:codes_off + rows * cols // 2].astype(np.int32))
+        q = torch.stack([b & 15, b >> 4], dim=1).reshape(rows, cols)          # even column = low nibble
+        s = torch.from_numpy(raw[scales_off:scales_off + 4 * n].view(np.float32).copy()).reshape(rows, cols // 128)
+        z = torch.from_numpy(raw[zeros_off:zeros_off + n].astype(np.int32)).reshape(rows, cols // 128)
+        val = (q - z.repeat_interleave(128, dim=1)).float() * s.repeat_interleave(128, dim=1)   # fp32 product
+        return val.to(torch.bfloat16).reshape(-1)
+
+    up = expand(lay["codes_up"], 2 * I, d, lay["scales_up"], lay["zeros_up"], n_up)
+    down = expand(lay["codes_down"], d, I, lay["scales_down"], lay["zeros_down"], n_dn)
+    want = torch.cat([up, down]).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_int4_quantiser_error_bound_and_exact_zero():
+    d, I = 128, 256
+    blob = S.normal_bf16((3 * d * I,), 2, 7, 0.02)
+    blob[5:40] = 0                                               # zero weights must come back as zero
+    raw = np.zeros(S.q4_blob_bytes(d, I), dtype=np.uint8)
+    S.quantize4_blob_into(raw.ctypes.data, blob, d, I)
+    a = S.bf16_to_f32(blob).astype(np.float64)
+    b = S.bf16_to_f32(oracle.dequant4_blob(raw, d, I)).astype(np.float64)
+    assert np.all(b[5:40] == 0.0)
+    lay = S.q4_layout(d, I)
+    n_up, n_dn = 2 * I * (d // 128), d * (I // 128)
+    scales = raw[:4 * (n_up + n_dn)].view(np.float32).astype(np.float64)
+    per_w = np.concatenate([np.repeat(scales[:n_up], 128), np.repeat(scales[n_up:], 128)])
+    # round-to-nearest on a grid of step `scale` that covers [min, max] up to the zero point's own rounding
+    # (half a step more at the ends); the fp32 and bf16 roundings add 2^-8 relative
+    assert np.all(np.abs(a - b) <= per_w * 1.0 + np.abs(a) * 2.0 ** -7)
+    assert np.sqrt(np.mean((a - b) ** 2)) < 0.4 * np.mean(per_w)   # typical error is step / sqrt(12)
+    assert lay["total"] == raw.size and lay["meta"] % 16 == 0
