@@ -223,8 +223,9 @@ int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
  * results as moe_prefill_layer; experts run as bandwidth-bound GEMVs.  The gate's choice is
  * compared with the cache ("synchronisation point 1"): hits run first, misses are
  * re-fetched on copy_stream and run as they land.  The host looks at the gate's counts
- * (a short wait on a pinned mailbox) unless every expert is resident, T = 1 and E <= 16,
- * in which case the call only enqueues.
+ * (a short wait on a pinned mailbox) unless every expert is resident and T = 1: then the
+ * mat-vec launches read the token's k experts from the gate's id list on the device and the
+ * call only enqueues (its cache counters are filled in when the mailbox arrives).
  */
 int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
                      const float *dev_route_bias, int bias_stride, void *dev_y,
@@ -280,9 +281,10 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * gate/up GEMM (mode 0), the down GEMM (mode 1) or the dense GEMM (mode 2); mode 3 forces the
  * number of K slices of the down GEMM (0 = heuristic; changes moe_workspace_bytes, so set it
  * before sizing workspaces); mode 4 forces the weight rows per wave of the decode mat-vec
- * kernels (0 = heuristic, 1, 2 or 4); mode 5 sets the largest expert count for which a one-token
- * decode call with every expert resident is enqueued without the host looking at the gate's
- * result (default 16); mode 6 chooses what the decode mat-vec kernels read where an 8-bit copy of an
+ * kernels (0 = heuristic, 1, 2 or 4); mode 5 with variant 0 makes a one-token decode call
+ * with every expert resident wait for the gate's result on the host like any other call (default 1:
+ * it is enqueued at once, the mat-vec launches take the k experts from the gate's id list on the
+ * device); mode 6 chooses what the decode mat-vec kernels read where an 8-bit copy of an
  * expert exists (MOE_FMT_E4M3_ROWS): 0 = the copy if the experts are large enough for it to pay
  * (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy.  Process-wide.
  */

@@ -49,7 +49,7 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
 int g_splitk_override = 0;  // tuning hook (moe_set_gemm_variant mode 3); 0 = heuristic
 int g_no_q8_matvec = 0;  // tuning hook (mode 6): 1 = mat-vecs read the expanded bf16 slots even when an 8-bit copy exists
-int g_blind_max_experts = 16;  // tuning hook (mode 5): with more experts than this a one-token decode call waits for the gate and launches only the active experts
+int g_blind_one_token = 1;  // tuning hook (mode 5): 0 = a one-token decode call always waits for the gate on the host
 
 int choose_splitk(const moe_config &cfg, int T) {
   if (g_splitk_override > 0) return g_splitk_override;
@@ -503,7 +503,10 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // with 60 experts and 4 active that cost 100 us against 76 us for the host's look at the gate).
   // A decode batch takes the other path: the per-expert row counts pick a much leaner mat-vec
   // variant, and the shared experts' launch covers the host's wait.
-  const bool enqueue_blind = all_resident && (!decode || (T == 1 && E <= g_blind_max_experts));
+  // One token with every expert resident: the mat-vec launches take the k experts from the gate's own
+  // id list on the device, so the host neither waits for the gate nor launches blocks for the others.
+  const bool blind_one = decode && T == 1 && g_blind_one_token;
+  const bool enqueue_blind = all_resident && (!decode || blind_one);
 
   // A prefill batch of some size: the shared experts get the library's side stream.  Their two
   // launches need nothing but x, so they fill the compute units that the gate and the grouping leave
@@ -572,8 +575,9 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         L.set->copy_pending[s] = 0;
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
-    rc = run_experts(ctx, decode, a1, a2, mask, E, n, T, cs, shared_in_routed_launch ? &s1 : nullptr,
-                     shared_in_routed_launch ? &s2 : nullptr);
+    if (blind_one) a1.sel_ids = a2.sel_ids = reinterpret_cast<const int32_t *>(ws + W.ids);
+    rc = run_experts(ctx, decode, a1, a2, mask, blind_one ? c.k : E, n, T, cs,
+                     shared_in_routed_launch ? &s1 : nullptr, shared_in_routed_launch ? &s2 : nullptr);
     if (rc) return rc;
     HIP_TRY(hipEventRecord(L.set->group_done, cs));
     for (int s = 0; s < S; ++s)
@@ -1148,7 +1152,7 @@ int moe_set_gemm_variant(int mode, int variant) {
     return MOE_OK;
   }
   if (mode == 5) {
-    g_blind_max_experts = variant;
+    g_blind_one_token = variant != 0;
     return MOE_OK;
   }
   if (mode == 4) {

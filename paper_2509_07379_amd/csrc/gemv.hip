@@ -147,10 +147,14 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
   // group of this block: the sel-th expert of the mask
   int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
   if (args.offsets) {
-    unsigned long long m = args.group_mask;
-    for (unsigned i = 0; i < sel; ++i) m &= m - 1;
-    if (m == 0) return;   // fewer groups in the mask than the launch was sized for
-    grp = __ffsll((long long)m) - 1;
+    if (args.sel_ids) {
+      grp = args.sel_ids[sel];   // the gate's own list (one token: its k experts, all distinct)
+    } else {
+      unsigned long long m = args.group_mask;
+      for (unsigned i = 0; i < sel; ++i) m &= m - 1;
+      if (m == 0) return;   // fewer groups in the mask than the launch was sized for
+      grp = __ffsll((long long)m) - 1;
+    }
     row0 = args.offsets[grp];
     cnt = args.offsets[grp + 1] - row0;
   }

@@ -59,6 +59,8 @@ struct GemmArgs {
   const int32_t *offsets; // device [n_groups+1] sorted-row offsets; NULL = one group
   int single_row0, single_rows;   // the one group when offsets == NULL
   unsigned long long group_mask;  // experts that take part (bit e)
+  const int32_t *sel_ids;         // mat-vec kernels: non-NULL = device list of the groups that take part
+                                  // (launch index -> expert), used instead of group_mask
   int n_groups;
   const char *wbase;      // expert e's blob at wbase + slot[e] * wstride
   long long wstride;

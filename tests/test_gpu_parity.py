@@ -32,7 +32,7 @@ def _default_hooks():
     from paper_2509_07379_amd import binding
     if torch.cuda.is_available():
         for mode in range(7):
-            binding.moe_set_gemm_variant(mode, 16 if mode == 5 else 0)
+            binding.moe_set_gemm_variant(mode, 1 if mode == 5 else 0)
 
 
 @pytest.fixture(scope="module")
@@ -189,6 +189,29 @@ def test_ragged_shapes(gpu, oracle, d, I, E, k, T, Ish, decode):
     for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
         np.testing.assert_array_equal(r["routing"][key], ref[key], err_msg=key)
     check_out(r["out"], ref["out_f64"], f"ragged decode={decode}")
+
+
+@pytest.mark.parametrize("E,k,Ish", [(60, 4, 128), (8, 2, 0), (64, 6, 0)])
+def test_one_token_decode_enqueued_from_the_gates_id_list(gpu, oracle, E, k, Ish):
+    """One token, every expert resident: the call does not wait for the gate; the mat-vec launches
+    take the k experts from the id list the gate wrote on the device.  Same output, routing tables and
+    counters as the path in which the host looks at the counts first."""
+    B = gpu["binding"]
+    w = S.Workload("one_token", d=512, I=256, E=E, k=k, T=1, I_shared=Ish, seed=71)
+    got = []
+    for host_path in (0, 1):
+        B.moe_set_gemm_variant(5, 0 if host_path else 1)
+        for step in range(3):                       # different tokens choose different experts
+            x = S.activations(w, 0, step)
+            r = run_layer(gpu, w, 1, x, E, list(range(E)), decode=True)
+            ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], shared=r["lay"].shared_np)
+            for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
+                np.testing.assert_array_equal(r["routing"][key], ref[key], err_msg=key)
+            check_out(r["out"], ref["out_f64"], f"one token, host_path={host_path}")
+            assert r["stats"]["hits"] == k and r["stats"]["misses"] == 0
+            got.append(r["out"])
+    for a, b in zip(got[:3], got[3:]):
+        np.testing.assert_array_equal(a, b)          # the same kernels on the same experts: the same bits
 
 
 def test_per_token_bias_forces_trace(gpu, oracle):
