@@ -452,7 +452,9 @@ int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned lo
                 const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr,
                 hipEvent_t before_second = nullptr) {
   a1.group_mask = a2.group_mask = mask;
-  if (decode) {
+  // The mat-vec kernels pass over an expert's weights once per 8 of its tokens: a decode batch that
+  // gives some expert more than that goes to the MFMA kernels, which stream the weights once.
+  if (decode && max_rows_per_group <= 8) {
     {
       Timer t(ctx, stream, MOE_K_GEMV1);
       HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, max_rows_per_group, n_groups, stream, s1));
