@@ -206,8 +206,10 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out);
  * expert -> every active expert as a grouped bf16 MFMA GEMM from its cache slot -> weighted
  * sum (+ shared experts) -> dev_y [T, d] bf16.  Experts that are not resident stream
  * through the slots in ascending id, each fetched once on copy_stream while the previous
- * one computes.  When some routed expert is not resident the call blocks the host once,
- * until the gate's counts are known.
+ * one computes.  Groups of any size run on the MFMA kernels: for a handful of tokens
+ * moe_decode_layer gives the same result faster (and itself moves to the MFMA kernels when some
+ * expert receives more than 8 tokens).  When some routed expert is not resident the call
+ * blocks the host once, until the gate's counts are known.
  *  dev_route_bias  NULL, or fp32 added to the gate logits: element [t*bias_stride + e]
  *                  (bias_stride 0 = one row for all tokens, E = one row per token).
  *  dev_workspace   >= moe_workspace_bytes(cfg, T), 256-byte aligned; holds the routing
@@ -222,7 +224,8 @@ int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
  * One MoE layer in the decode stage (Section V-C), T = batch (small).  Same contract and
  * results as moe_prefill_layer; experts run as bandwidth-bound GEMVs.  The gate's choice is
  * compared with the cache ("synchronisation point 1"): hits run first, misses are
- * re-fetched on copy_stream and run as they land.  The host looks at the gate's counts
+ * re-fetched on copy_stream and run as they land.  Experts with at most 8 tokens run as
+ * mat-vecs; a batch that gives some expert more goes to the MFMA kernels.  The host looks at the gate's counts
  * (a short wait on a pinned mailbox) unless every expert is resident and T = 1: then the
  * mat-vec launches read the token's k experts from the gate's id list on the device and the
  * call only enqueues (its cache counters are filled in when the mailbox arrives).
