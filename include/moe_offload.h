@@ -92,6 +92,16 @@ typedef struct {
  *   (d x I/2)].  Fetched and expanded like MOE_FMT_E4M3_ROWS:
  *   weight = bf16 nearest-even of fp32((code - zero) * scale).  The mat-vec kernels read the bf16 slots. */
 #define MOE_FMT_INT4_G128 2
+/* MOE_FMT_MXFP4: the OCP microscaling 4-bit format: e2m1 codes (bit 3 sign, bits 2..1 exponent, bit 0
+ *   mantissa: 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte (even column in the low nibble); 32 consecutive
+ *   values of a row share the scale 2^(s - 127), s one byte in 1..254; d and I multiples of 32.  Blob:
+ *   [scale bytes of [W_gate; W_up] (2I x d/32)][scale bytes of W_down (d x I/32)][padding to a multiple
+ *   of 16][codes of [W_gate; W_up] (2I x d/2)][codes of W_down (d x I/2)].  weight = value(code) *
+ *   2^(s - 127), exact in bf16.  Fetched and expanded like the others; the decode mat-vec kernels
+ *   stream a fetched expert's 4-bit form from its staging area (a quarter of the HBM bytes) and expand
+ *   it in registers with the hardware's scaled fp4 conversion, under the same conditions as for
+ *   MOE_FMT_E4M3_ROWS. */
+#define MOE_FMT_MXFP4 3
 
 /* Cache counters (host side).  hits/misses count active experts per layer call. */
 typedef struct {
@@ -114,7 +124,8 @@ int moe_create(const moe_config *cfg, moe_ctx **out);
 int moe_destroy(moe_ctx *ctx);
 
 /* Bytes of one expert in the CPU expert cache: 6*d*I (bf16), 4*(2I+d) + 3*d*I (e4m3 rows) or
- * 15*d*I/128 rounded up to 16, plus 3*d*I/2 (int4 groups). */
+ * 15*d*I/128 rounded up to 16, plus 3*d*I/2 (int4 groups), or 3*d*I/32 rounded up to 16, plus
+ * 3*d*I/2 (MXFP4). */
 size_t moe_host_blob_bytes(const moe_config *cfg);
 /* Bytes of one GPU expert cache (dev_slots of moe_bind_layer): cache_slots slots of 6*d*I bytes,
  * followed, for an 8-bit host format, by one staging area per slot. */

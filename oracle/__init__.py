@@ -49,6 +49,10 @@ def _load():
         lib.ref_dequant_e4m3_rows.restype = None
         lib.ref_dequant_int4_g128_rows.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         lib.ref_dequant_int4_g128_rows.restype = None
+        lib.ref_e2m1_value.argtypes = [ci]
+        lib.ref_e2m1_value.restype = ctypes.c_double
+        lib.ref_dequant_mxfp4_rows.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
+        lib.ref_dequant_mxfp4_rows.restype = None
         lib.ref_bf16_from_f64.argtypes = [ctypes.c_double]
         lib.ref_bf16_from_f64.restype = ctypes.c_uint16
         for f in ("ref_router_logits", "ref_topk_weights", "ref_dispatch", "ref_expert_ffn",
@@ -246,4 +250,24 @@ def dequant4_blob(qblob, d: int, I: int) -> np.ndarray:
     lib = _load()
     lib.ref_dequant_int4_g128_rows(_p(codes[:I * d]), _p(scales[:n_up]), _p(zeros[:n_up]), 2 * I, d, _p(out[:2 * I * d]))
     lib.ref_dequant_int4_g128_rows(_p(codes[I * d:]), _p(scales[n_up:]), _p(zeros[n_up:]), d, I, _p(out[2 * I * d:]))
+    return out
+
+
+def e2m1_value(code: int) -> float:
+    return float(_load().ref_e2m1_value(int(code)))
+
+
+def dequant_mx4_blob(qblob, d: int, I: int) -> np.ndarray:
+    """MXFP4 expert blob -> the bf16 blob the layer computes with (exact: no rounding).  Layout: scale
+    bytes of [W_gate; W_up] (2I x d/32) and of W_down (d x I/32), padding to 16 bytes, then the codes of
+    [W_gate; W_up] (2I x d/2 bytes) and of W_down (d x I/2 bytes)."""
+    q = np.ascontiguousarray(qblob).view(np.uint8).ravel()
+    n_up, n_dn = 2 * I * (d // 32), d * (I // 32)
+    meta = (n_up + n_dn + 15) // 16 * 16
+    assert d % 32 == 0 and I % 32 == 0 and q.size == meta + 3 * d * I // 2
+    scales, codes = q[:n_up + n_dn], q[meta:]
+    out = np.empty(3 * d * I, dtype=np.uint16)
+    lib = _load()
+    lib.ref_dequant_mxfp4_rows(_p(codes[:I * d]), _p(scales[:n_up]), 2 * I, d, _p(out[:2 * I * d]))
+    lib.ref_dequant_mxfp4_rows(_p(codes[I * d:]), _p(scales[n_up:]), d, I, _p(out[2 * I * d:]))
     return out

@@ -364,3 +364,29 @@ void ref_dequant_int4_g128_rows(const uint8_t *codes, const float *scales, const
       out_bf16[r * cols + c] = bf16_from_f64((double)prod);
     }
 }
+
+/*
+ * MXFP4 expert weights (OCP microscaling formats: 32 consecutive values of a row share the scale
+ * 2^(s - 127), s one byte; each value is an e2m1 code: bit 3 sign, bits 2..1 exponent e, bit 0
+ * mantissa m; e = 0: m / 2;  e > 0: 2^(e - 1) * (1 + m / 2)  ->  0, 0.5, 1, 1.5, 2, 3, 4, 6).
+ * A weight is value(code) * 2^(s - 127): one mantissa bit times a power of two, exact in bf16, so
+ * the expansion involves no rounding (1 <= s <= 254 here).  Two codes per byte, even column low.
+ */
+double ref_e2m1_value(int code) {
+  int s = (code >> 3) & 1, e = (code >> 1) & 3, m = code & 1;
+  double v = e == 0 ? 0.5 * m : ldexp(1.0 + 0.5 * m, e - 1);
+  return s ? -v : v;
+}
+
+void ref_dequant_mxfp4_rows(const uint8_t *codes, const uint8_t *scales, int64_t rows, int64_t cols,
+                            uint16_t *out_bf16) {
+  const int64_t blocks = cols / 32;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      const uint8_t byte = codes[(r * cols + c) / 2];
+      const int code = (c & 1) ? (byte >> 4) : (byte & 15);
+      const int s = scales[r * blocks + c / 32];
+      out_bf16[r * cols + c] = bf16_from_f64(ldexp(ref_e2m1_value(code), s - 127));
+    }
+}

@@ -172,8 +172,10 @@ int check_cfg(const moe_config *c) {
   if (c->E > kMaxExperts) return fail(MOE_E_UNSUPPORTED, "E = %d > %d experts", c->E, kMaxExperts);
   if (c->d % 8 || c->I % 8 || c->I_shared % 8)
     return fail(MOE_E_UNSUPPORTED, "d, I and I_shared must be multiples of 8");
-  if (c->host_format != MOE_FMT_BF16 && c->host_format != MOE_FMT_E4M3_ROWS && c->host_format != MOE_FMT_INT4_G128)
+  if (c->host_format < MOE_FMT_BF16 || c->host_format > MOE_FMT_MXFP4)
     return fail(MOE_E_ARG, "host_format = %d is not a known format", c->host_format);
+  if (c->host_format == MOE_FMT_MXFP4 && (c->d % 32 || c->I % 32))
+    return fail(MOE_E_UNSUPPORTED, "MOE_FMT_MXFP4 needs d and I to be multiples of 32");
   if (c->host_format == MOE_FMT_INT4_G128 && (c->d % 128 || c->I % 128))
     return fail(MOE_E_UNSUPPORTED, "MOE_FMT_INT4_G128 needs d and I to be multiples of 128");
   return MOE_OK;
@@ -265,8 +267,11 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     if (c.host_format == MOE_FMT_E4M3_ROWS) {
       meta_bytes = (size_t)4 * (2 * c.I + c.d);
       up_codes = 2 * Id;
-    } else {
+    } else if (c.host_format == MOE_FMT_INT4_G128) {
       meta_bytes = (15 * Id / 128 + 15) / 16 * 16;
+      up_codes = Id;
+    } else {
+      meta_bytes = (3 * Id / 32 + 15) / 16 * 16;
       up_codes = Id;
     }
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + meta_bytes);
@@ -275,6 +280,10 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
         const float *scales = reinterpret_cast<const float *>(stage);
         if (!down) HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
         else HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + 2 * Id, xs));
+      } else if (c.host_format == MOE_FMT_MXFP4) {
+        const uint8_t *scales = reinterpret_cast<const uint8_t *>(stage);
+        if (!down) HIP_TRY(launch_dequant_mxfp4(codes, scales, 2 * c.I, c.d, w, xs));
+        else HIP_TRY(launch_dequant_mxfp4(codes + up_codes, scales + 2 * Id / 32, c.d, c.I, w + 2 * Id, xs));
       } else {
         const size_t n_up = 2 * Id / 128, n_dn = Id / 128;
         const float *scales = reinterpret_cast<const float *>(stage);
@@ -287,7 +296,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     // the staging area's last expansion must be over before new bytes land in it
     if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
     set.staged[s] = 1;
-    set.q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS;   // the mat-vec kernels can read this form
+    set.q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS || c.host_format == MOE_FMT_MXFP4;   // forms the mat-vec kernels read
     int rc = MOE_OK;
     if (split) {
       HIP_TRY(hipMemcpyAsync(stage, src, meta_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
@@ -354,15 +363,27 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
     // the mat-vec kernels stream the 8-bit copy that a fetch left in the slot's staging area (half
     // the bytes; the same weight values as the expanded slot)
     const long long scale_bytes = (long long)4 * (2 * c.I + c.d), Id = (long long)c.I * c.d;
+    a.qfmt = 1;
     a.qbase = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes;
     a.qstride = (long long)ctx->stage_stride;
     a.q_b0_off = scale_bytes + (second ? 2 * Id : 0);
     a.q_b1_off = scale_bytes + (second ? 2 * Id : Id);
     a.q_s0_off = second ? (long long)4 * 2 * c.I : 0;
     a.q_s1_off = second ? (long long)4 * 2 * c.I : (long long)4 * c.I;
+  } else if (c.host_format == MOE_FMT_MXFP4 && !g_no_q8_matvec) {
+    // likewise the MXFP4 copy (a quarter of the bytes): codes K/2 bytes per row, scales K/32
+    const long long Id = (long long)c.I * c.d, meta = (3 * Id / 32 + 15) / 16 * 16;
+    a.qfmt = 2;
+    a.qbase = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes;
+    a.qstride = (long long)ctx->stage_stride;
+    a.q_b0_off = meta + (second ? Id : 0);
+    a.q_b1_off = meta + (second ? Id : Id / 2);
+    a.q_s0_off = second ? 2 * Id / 32 : 0;
+    a.q_s1_off = second ? 2 * Id / 32 : Id / 32;
+  }
+  if (a.qbase)
     for (int e = 0; e < c.E; ++e)
       if (L.expert_slot[e] >= 0 && L.set->q_valid[L.expert_slot[e]]) a.q8_mask |= 1ull << e;
-  }
   if (!second) {
     a.A = reinterpret_cast<const uint16_t *>(x);
     a.lda = c.d;
@@ -772,6 +793,7 @@ size_t moe_host_blob_bytes(const moe_config *cfg) {
   const size_t dI = (size_t)cfg->d * cfg->I;
   if (cfg->host_format == MOE_FMT_E4M3_ROWS) return (size_t)4 * (2 * cfg->I + cfg->d) + 3 * dI;
   if (cfg->host_format == MOE_FMT_INT4_G128) return (15 * dI / 128 + 15) / 16 * 16 + 3 * dI / 2;
+  if (cfg->host_format == MOE_FMT_MXFP4) return (3 * dI / 32 + 15) / 16 * 16 + 3 * dI / 2;
   return 6 * dI;
 }
 

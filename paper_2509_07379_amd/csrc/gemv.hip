@@ -115,6 +115,68 @@ __device__ __forceinline__ void accumulate_q8(const u32x4 *__restrict__ xs, int 
   }
 }
 
+// 32 MXFP4 codes (one 16-byte piece = one scale block; element 0 in the low nibble of byte 0) ->
+// 32 bf16 weights value(code) * scale, exact: the hardware conversion of gfx950 takes the two codes
+// of one byte and the scale's exponent and returns the packed pair.
+__device__ __forceinline__ uint32_t mx4_pair(uint32_t word, float scale, int byte) {   // by value: plain scalars
+  bf16x2 p;
+  if (byte == 0) p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 0);
+  else if (byte == 1) p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 1);
+  else if (byte == 2) p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 2);
+  else p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 3);
+  return __builtin_bit_cast(uint32_t, p);
+}
+__device__ __forceinline__ u32x4 mx4_expand8(uint32_t word, float scale) {
+  return u32x4{mx4_pair(word, scale, 0), mx4_pair(word, scale, 1), mx4_pair(word, scale, 2), mx4_pair(word, scale, 3)};
+}
+
+// The same sums from MXFP4 weights: a lane's 16-byte piece holds the 32 codes of one scale block, i.e.
+// four of the token vectors' 8-element pieces.  sc0 / sc1: the rows' scale bytes for this K segment.
+template <int MODE, int NT, int NTMAX, int GV_R>
+__device__ __forceinline__ void accumulate_mx4(const u32x4 *__restrict__ xs, int seg_chunks,
+                                               const u32x4 *const (&w0)[GV_R], const u32x4 *const (&w1)[GV_R],
+                                               const uint8_t *const (&sc0)[GV_R], const uint8_t *const (&sc1)[GV_R],
+                                               int lane, float (&acc0)[GV_R][NTMAX], float (&acc1)[GV_R][NTMAX]) {
+  const int pieces = seg_chunks >> 2;
+#pragma unroll NT <= 2 ? 2 : 1
+  for (int c = lane; c < pieces; c += 64) {
+    u32x4 q0[GV_R], q1[GV_R];
+    float f0[GV_R], f1[GV_R];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      q0[r] = __builtin_nontemporal_load(w0[r] + c);
+      f0[r] = __uint_as_float((uint32_t)sc0[r][c] << 23);
+      if (MODE == GEMM_SWIGLU) {
+        q1[r] = __builtin_nontemporal_load(w1[r] + c);
+        f1[r] = __uint_as_float((uint32_t)sc1[r][c] << 23);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      {   // gate (or down) row: expand, use for all tokens, then the up row (half as many live registers)
+        const uint32_t a0 = q0[r].x, a1 = q0[r].y, a2 = q0[r].z, a3 = q0[r].w;
+        const u32x4 g0 = mx4_expand8(a0, f0[r]), g1 = mx4_expand8(a1, f0[r]), g2 = mx4_expand8(a2, f0[r]),
+                    g3 = mx4_expand8(a3, f0[r]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const u32x4 *xp = xs + t * seg_chunks + 4 * c;
+          acc0[r][t] = dot8(xp[3], g3, dot8(xp[2], g2, dot8(xp[1], g1, dot8(xp[0], g0, acc0[r][t]))));
+        }
+      }
+      if (MODE == GEMM_SWIGLU) {
+        const uint32_t b0 = q1[r].x, b1 = q1[r].y, b2 = q1[r].z, b3 = q1[r].w;
+        const u32x4 u0 = mx4_expand8(b0, f1[r]), u1 = mx4_expand8(b1, f1[r]), u2 = mx4_expand8(b2, f1[r]),
+                    u3 = mx4_expand8(b3, f1[r]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const u32x4 *xp = xs + t * seg_chunks + 4 * c;
+          acc1[r][t] = dot8(xp[3], u3, dot8(xp[2], u2, dot8(xp[1], u1, dot8(xp[0], u0, acc1[r][t]))));
+        }
+      }
+    }
+  }
+}
+
 // GV_R weight rows per wave.  Measured on MI355X: the more, smaller waves stream the weights, the
 // closer the kernel gets to the HBM rate (one row per wave for rows of 4 KB and more, two for
 // shorter rows); blocks that walk over several row groups were slower in every shape.
@@ -123,10 +185,11 @@ __device__ __forceinline__ void accumulate_q8(const u32x4 *__restrict__ xs, int 
 // of the weights; 16 waves share one copy).
 // (at least 6 waves per SIMD for the 4-wave blocks: left alone, the register allocator of the
 // multi-token variants wanders between 76 and 100 registers with unrelated edits)
-// Q8: experts named in routed.q8_mask are streamed from their 8-bit copies (the second problem, the
-// shared experts, is always bf16); without Q8 the mask is ignored.
-template <int MODE, int NTMAX, int GV_R, int NTHR, bool Q8>
-__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(NTHR == 256 ? ((Q8 && (NTMAX > 1 || GV_R > 1)) ? 4 : 6) : 4)))
+// QF: 0, or the format (GemmArgs::qfmt) of the quantised copies from which the experts named in
+// routed.q8_mask are streamed (the second problem, the shared experts, is always bf16); with QF = 0
+// the mask is ignored.
+template <int MODE, int NTMAX, int GV_R, int NTHR, int QF>
+__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(NTHR == 256 ? ((QF == 2 || (QF && (NTMAX > 1 || GV_R > 1))) ? 4 : 6) : 4)))
 void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
                                                              int has_extra, int kseg, int ntcap, int n_extra_y) {
   constexpr int GV_THREADS = NTHR, GV_WAVES = NTHR / 64;
@@ -165,10 +228,10 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
   const uint16_t *B1 = reinterpret_cast<const uint16_t *>(wptr + args.b1_off);
   const int n_first = (bx * GV_WAVES + wave) * GV_R;
   if ((int)bx * GV_WAVES * GV_R >= args.N) return;
-  const bool q8 = Q8 && !is_extra && ((args.q8_mask >> grp) & 1ull);
+  const bool q8 = QF != 0 && !is_extra && ((args.q8_mask >> grp) & 1ull);
   const char *qptr = args.qbase + (long long)args.slot[grp] * args.qstride;
   float s0[GV_R], s1[GV_R];
-  if (Q8) {
+  if (QF == 1) {
 #pragma unroll
     for (int r = 0; r < GV_R; ++r) {
       const int n = min(n_first + r, args.N - 1);
@@ -203,7 +266,8 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
         w0[r] = reinterpret_cast<const u32x4 *>(B0 + (long long)n * args.ldb + k0);
         w1[r] = reinterpret_cast<const u32x4 *>(B1 + (long long)n * args.ldb + k0);
       }
-      if (Q8 && q8) {   // the same rows in the 8-bit copy: K bytes per row
+      const uint8_t *sc0[GV_R], *sc1[GV_R];
+      if (QF == 1 && q8) {   // the same rows in the 8-bit copy: K bytes per row
 #pragma unroll
         for (int r = 0; r < GV_R; ++r) {
           const int n = min(n_first + r, args.N - 1);
@@ -211,10 +275,21 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
           w1[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b1_off + (long long)n * args.ldb + k0);
         }
       }
+      if (QF == 2 && q8) {   // MXFP4 copy: K / 2 bytes of codes and K / 32 scale bytes per row
+#pragma unroll
+        for (int r = 0; r < GV_R; ++r) {
+          const long long n = min(n_first + r, args.N - 1);
+          w0[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b0_off + ((n * args.ldb + k0) >> 1));
+          w1[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b1_off + ((n * args.ldb + k0) >> 1));
+          sc0[r] = reinterpret_cast<const uint8_t *>(qptr + args.q_s0_off) + ((n * args.ldb + k0) >> 5);
+          sc1[r] = reinterpret_cast<const uint8_t *>(qptr + args.q_s1_off) + ((n * args.ldb + k0) >> 5);
+        }
+      }
 #define MOE_GEMV_CASE(NT)                                                             \
   if constexpr (NT <= NTMAX) {                                                        \
     if (ntok == NT) {                                                                 \
-      if (Q8 && q8) accumulate_q8<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, s0, s1, lane, acc0, acc1); \
+      if (QF == 1 && q8) accumulate_q8<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, s0, s1, lane, acc0, acc1); \
+      else if (QF == 2 && q8) accumulate_mx4<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, sc0, sc1, lane, acc0, acc1); \
       else accumulate<MODE, NT, NTMAX, GV_R>(xs, seg_chunks, w0, w1, lane, acc0, acc1); \
     }                                                                                 \
   }
@@ -266,7 +341,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   // matrix and more (Mixtral-sized: 1.4 to 1.5 times faster at 1 to 6 tokens).  Small experts
   // (Qwen-sized, 3 M) are bound by the launch itself at 1 or 2 tokens and by arithmetic above; there
   // the expansion only adds instructions.
-  const bool use_q8 = args.q8_mask != 0 && args.qbase != nullptr && args.K % 16 == 0 &&
+  const bool use_q8 = args.q8_mask != 0 && args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0 &&
                       ((long long)args.N * args.K >= (1ll << 24) || g_gemv_q8_always);
   const int ntcap = max_tok < GV_MAXTOK ? max_tok : GV_MAXTOK;
   int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
@@ -292,8 +367,9 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   } while (0)
 #define MOE_GEMV_LAUNCH_R(MODE, NTMAX, R)                                                     \
   do {                                                                                        \
-    if (use_q8) MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, true);                                      \
-    else MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, false);                                            \
+    if (use_q8 && args.qfmt == 2) MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, 2);                       \
+    else if (use_q8) MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, 1);                                    \
+    else MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, 0);                                                \
   } while (0)
 #define MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, Q)                                                  \
   do {                                                                                        \

@@ -39,6 +39,10 @@ hipError_t launch_dequant_e4m3_rows(const uint8_t *q, const float *scales, long 
 // two codes per byte, even column in the low nibble; cols % 128 == 0.
 hipError_t launch_dequant_int4_g128(const uint8_t *codes, const float *scales, const uint8_t *zeros,
                                     long long rows, int cols, uint16_t *out, hipStream_t stream);
+// MXFP4 expert weights -> bf16: out[r, c] = value_e2m1(code[r, c]) * 2^(scales[r, c/32] - 127), exact;
+// two codes per byte, even column in the low nibble; cols % 32 == 0.
+hipError_t launch_dequant_mxfp4(const uint8_t *codes, const uint8_t *scales, long long rows, int cols,
+                                uint16_t *out, hipStream_t stream);
 hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
                             float *scores, int32_t *top_out, hipStream_t stream);
 
@@ -78,6 +82,10 @@ struct GemmArgs {
   // Expert e with bit e of q8_mask set is streamed from qbase + slot[e] * qstride instead of its bf16
   // blob: codes of the B rows at q_b0_off / q_b1_off (K bytes per row), their scales at q_s0_off /
   // q_s1_off.  The weight used is bf16_rne(value(code) * scale), the bf16 blob's value.  K % 16 == 0.
+  // qfmt 2: MXFP4 copies instead (e2m1 codes, two per byte, K / 2 bytes per row at q_b*_off; one scale
+  // byte per 32 columns, K / 32 bytes per row at q_s*_off; weight = value(code) * 2^(scale - 127), exact
+  // in bf16).  K % 32 == 0.
+  int qfmt;               // 0 none, 1 e4m3 with row scales, 2 MXFP4
   unsigned long long q8_mask;
   const char *qbase;
   long long qstride;

@@ -27,14 +27,14 @@ def dev_to_np_u16(t: torch.Tensor) -> np.ndarray:
 class HostPool:
     """All experts of one layer in pinned host memory: the CPU expert cache (Section V-A).
     fmt 0: bf16 blobs; 1 (or q8=True): e4m3 codes with per-row scales; 2: 4-bit codes in groups of 128 with
-    scale and zero point -- both quantised from the seeded bf16 blobs."""
+    scale and zero point; 3: MXFP4 -- all quantised from the seeded bf16 blobs."""
 
     def __init__(self, w: S.Workload, layer: int, fill: bool = True, share_from: "HostPool | None" = None,
                  q8: bool = False, fmt: "int | None" = None):
         self.fmt = (1 if q8 else 0) if fmt is None else fmt
         self.w, self.layer, self.q8 = w, layer, self.fmt != 0     # q8: "holds a quantised form"
-        self.bytes_per_expert = (w.blob_bytes, S.q8_blob_bytes(w.d, w.I),
-                                 S.q4_blob_bytes(w.d, w.I) if self.fmt == 2 else 0)[self.fmt]
+        self.bytes_per_expert = {0: lambda: w.blob_bytes, 1: lambda: S.q8_blob_bytes(w.d, w.I),
+                                 2: lambda: S.q4_blob_bytes(w.d, w.I), 3: lambda: S.mx4_blob_bytes(w.d, w.I)}[self.fmt]()
         if share_from is not None:
             assert share_from.fmt == self.fmt
             self.buf = share_from.buf
@@ -46,6 +46,8 @@ class HostPool:
                         S.quantize_blob_into(self.ptr(e), S.expert_blob(w, layer, e), w.d, w.I)
                     elif self.fmt == 2:
                         S.quantize4_blob_into(self.ptr(e), S.expert_blob(w, layer, e), w.d, w.I)
+                    elif self.fmt == 3:
+                        S.quantize_mx4_blob_into(self.ptr(e), S.expert_blob(w, layer, e), w.d, w.I)
                     else:
                         S.expert_blob_into(self.ptr(e), w, layer, e)
 

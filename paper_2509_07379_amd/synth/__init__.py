@@ -48,6 +48,9 @@ def _load():
         lib.synth_quantize_int4_g128.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                                  ctypes.c_void_p, ctypes.c_void_p]
         lib.synth_quantize_int4_g128.restype = None
+        lib.synth_quantize_mxfp4.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                             ctypes.c_void_p]
+        lib.synth_quantize_mxfp4.restype = None
         _lib = lib
     return _lib
 
@@ -303,3 +306,32 @@ def quantize4_blob_into(ptr: int, blob_bf16: np.ndarray, d: int, I: int) -> None
                                  vp(ptr + lay["zeros_up"]), vp(ptr + lay["codes_up"]))
     lib.synth_quantize_int4_g128(vp(blob_bf16.ctypes.data + 2 * (2 * I * d)), d, I, vp(ptr + lay["scales_down"]),
                                  vp(ptr + lay["zeros_down"]), vp(ptr + lay["codes_down"]))
+
+
+# ---------------------------------------------------------------------------
+# expert blobs in MXFP4: e2m1 codes, blocks of 32 along a row share a power-of-two scale (one byte)
+# ---------------------------------------------------------------------------
+def mx4_layout(d: int, I: int) -> dict:
+    """Byte offsets inside an MXFP4 blob:
+    [scales of [W_gate; W_up] (2I x d/32 bytes)][scales of W_down (d x I/32 bytes)][pad to 16]
+    [codes of [W_gate; W_up] (2I x d/2 bytes)][codes of W_down (d x I/2 bytes)]"""
+    assert d % 32 == 0 and I % 32 == 0
+    n_up, n_dn = 2 * I * (d // 32), d * (I // 32)
+    meta = (n_up + n_dn + 15) // 16 * 16
+    return dict(scales_up=0, scales_down=n_up, meta=meta, codes_up=meta, codes_down=meta + I * d,
+                total=meta + 3 * d * I // 2)
+
+
+def mx4_blob_bytes(d: int, I: int) -> int:
+    return mx4_layout(d, I)["total"]
+
+
+def quantize_mx4_blob_into(ptr: int, blob_bf16: np.ndarray, d: int, I: int) -> None:
+    """Quantise a bf16 expert blob into the MXFP4 layout at raw host address ptr (offline preparation)."""
+    blob_bf16 = np.ascontiguousarray(blob_bf16, dtype=np.uint16)
+    assert blob_bf16.size == 3 * d * I
+    lib, lay = _load(), mx4_layout(d, I)
+    vp = ctypes.c_void_p
+    lib.synth_quantize_mxfp4(vp(blob_bf16.ctypes.data), 2 * I, d, vp(ptr + lay["scales_up"]), vp(ptr + lay["codes_up"]))
+    lib.synth_quantize_mxfp4(vp(blob_bf16.ctypes.data + 2 * (2 * I * d)), d, I, vp(ptr + lay["scales_down"]),
+                             vp(ptr + lay["codes_down"]))

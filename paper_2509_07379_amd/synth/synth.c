@@ -157,3 +157,52 @@ void synth_quantize_int4_g128(const uint16_t *w_bf16, int64_t rows, int64_t cols
       }
     }
 }
+
+/*
+ * Offline quantiser to the OCP microscaling format MXFP4 (input preparation only): blocks of 32
+ * values along a row share one scale 2^(s - 127) (s = one byte, E8M0), each value is an e2m1 code
+ * (1 sign, 2 exponent, 1 mantissa bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6).  Per block: s - 127 =
+ * floor(log2(max|w|)) - 2 (the largest e2m1 exponent), clamped to [-126, 127]; an all-zero block gets
+ * s = 127; each value is rounded to the nearest code (ties to the even code), saturating at +-6.
+ * Two codes per byte, the even column in the low nibble.  cols % 32 == 0.
+ * w_bf16 [rows, cols] -> scales [rows, cols/32] bytes, codes [rows, cols/2] bytes.
+ */
+static const float kE2M1[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+
+static inline uint8_t e2m1_nearest(float x) {
+  uint8_t sign = x < 0.0f ? 8 : 0;
+  float a = fabsf(x);
+  int best = 0;
+  for (int c = 1; c < 8; ++c) {
+    float db = fabsf(a - kE2M1[best]), dc = fabsf(a - kE2M1[c]);
+    if (dc < db || (dc == db && !(c & 1))) best = c;
+  }
+  return (uint8_t)(sign | best);
+}
+
+void synth_quantize_mxfp4(const uint16_t *w_bf16, int64_t rows, int64_t cols, uint8_t *scales, uint8_t *codes) {
+  const int64_t blocks = cols / 32;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t b = 0; b < blocks; ++b) {
+      const uint16_t *w = w_bf16 + r * cols + b * 32;
+      float amax = 0.0f;
+      for (int i = 0; i < 32; ++i) {
+        float a = fabsf(bf16_to_float(w[i]));
+        if (a > amax) amax = a;
+      }
+      int e = 0;
+      if (amax > 0.0f) {
+        (void)frexpf(amax, &e);   /* amax = m * 2^e, m in [0.5, 1): floor(log2(amax)) = e - 1 */
+        e = e - 1 - 2;
+        if (e < -126) e = -126;
+        if (e > 127) e = 127;
+      }
+      scales[r * blocks + b] = (uint8_t)(e + 127);
+      const float inv = ldexpf(1.0f, -e);
+      for (int i = 0; i < 32; i += 2) {
+        uint8_t lo = e2m1_nearest(bf16_to_float(w[i]) * inv), hi = e2m1_nearest(bf16_to_float(w[i + 1]) * inv);
+        codes[(r * cols + b * 32 + i) / 2] = (uint8_t)(lo | (hi << 4));
+      }
+    }
+}

@@ -75,12 +75,12 @@ def test_blob_and_cache_sizes_per_host_format():
     from paper_2509_07379_amd import binding, synth as S
     lib = binding.load()
     d, I, slots = 256, 384, 3
-    for fmt, want in ((0, 6 * d * I), (1, S.q8_blob_bytes(d, I)), (2, S.q4_blob_bytes(d, I))):
+    for fmt, want in ((0, 6 * d * I), (1, S.q8_blob_bytes(d, I)), (2, S.q4_blob_bytes(d, I)), (3, S.mx4_blob_bytes(d, I))):
         cfg = binding.MoeConfig(d, I, 8, 2, 1, slots, 0, 1, 0, fmt)
         assert lib.moe_host_blob_bytes(C.byref(cfg)) == want
         stage = 0 if fmt == 0 else (want + 255) // 256 * 256
         assert lib.moe_cache_bytes(C.byref(cfg)) == slots * (6 * d * I + stage)
-    assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(d, I, 8, 2, 1, slots, 0, 1, 0, 3))) == 0
+    assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(d, I, 8, 2, 1, slots, 0, 1, 0, 4))) == 0
     assert b"not a known format" in lib.moe_last_error()
     assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(264, I, 8, 2, 1, slots, 0, 1, 0, 2))) == 0
     assert b"multiples of 128" in lib.moe_last_error()

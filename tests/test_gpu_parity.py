@@ -48,7 +48,7 @@ def gpu():
 def oracle_layer(oracle, w, x, router, pool, bias=None, sel=None, shared=None):
     blobs = [pool.blob_np(e) for e in range(w.E)]
     if pool.q8:   # quantised CPU expert cache: the layer computes with the oracle's expansion of it
-        expand = oracle.dequant4_blob if pool.fmt == 2 else oracle.dequant_blob
+        expand = {1: oracle.dequant_blob, 2: oracle.dequant4_blob, 3: oracle.dequant_mx4_blob}[pool.fmt]
         blobs = [expand(b, w.d, w.I) for b in blobs]
     return oracle.moe_layer(x, router, blobs, w.k, bias=bias, sel=sel, shared_blob=shared, I=w.I,
                             I_shared=w.I_shared)
@@ -445,6 +445,65 @@ def test_q8_decode_streams_the_8bit_copies(gpu, oracle, d, I, I_shared, T):
     st = ctx.moe_get_stats(0)
     assert st["misses"] == 0 and st["prefetch_issued"] == w.E
     ctx.close()
+
+
+def test_mxfp4_fetch_expands_into_slots_bit_exact(gpu, oracle):
+    """MXFP4 experts: slots hold the oracle's (exact) expansion bit for bit, outputs are the oracle's on
+    those weights, the link carried the 4-bit blobs; prefill, then streaming through two slots."""
+    from oracle.cache_sim import CacheSim
+    w = S.Workload("mx4_slots", d=256, I=160, E=6, k=2, T=300, I_shared=64, seed=58)
+    x = S.activations(w)
+    r = run_layer(gpu, w, w.T, x, w.E, None, poison=True, fmt=3)
+    ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], shared=r["lay"].shared_np)
+    check_out(r["out"], ref["out_f64"], "mxfp4 prefill")
+    slots = r["lay"].slots.cpu().numpy().view(np.uint16)
+    active = [e for e in range(w.E) if ref["counts"][e] > 0]
+    assert len(active) >= 4
+    for e in active:
+        np.testing.assert_array_equal(slots[r["state"].index(e)], oracle.dequant_mx4_blob(r["pool"].blob_np(e), w.d, w.I),
+                                      err_msg=f"expert {e}")
+    assert r["stats"]["bytes_h2d"] == len(active) * S.mx4_blob_bytes(w.d, w.I)
+    r2 = run_layer(gpu, w, w.T, x, 2, None, prefetch=[5, 4], poison=True, fmt=3, pool=r["pool"])
+    check_out(r2["out"], ref["out_f64"], "mxfp4 streaming")
+    sim = CacheSim(w.E, 2, S.mx4_blob_bytes(w.d, w.I))
+    sim.prefetch([5, 4])
+    sim.serve(np.nonzero(ref["counts"])[0])
+    assert r2["stats"] == {**sim.counters(), "layer_calls": 1}
+
+
+@pytest.mark.parametrize("d,I,I_shared,T", [(256, 192, 64, 1), (256, 192, 0, 2), (256, 192, 64, 4), (256, 192, 64, 7),
+                                            (256, 192, 0, 11), (2048, 96, 32, 1), (2048, 96, 0, 3), (4096, 64, 0, 8)])
+def test_mxfp4_decode_streams_the_4bit_copies(gpu, oracle, d, I, I_shared, T):
+    """Decode on experts fetched in MXFP4: the mat-vec kernels read codes and scale bytes from the staging
+    areas and expand them with the hardware's scaled fp4 conversion to the bf16 weights the slots hold.
+    The bf16 slots are overwritten with NaN patterns after the fetch: a correct output proves where the
+    weights came from (and the nibble and byte order of the conversion).  Also through two slots with a
+    wrong prefetch (misses fetched, expanded and read in the same call)."""
+    from oracle.cache_sim import CacheSim
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("mx4_decode", d=d, I=I, E=6, k=2, T=T, I_shared=I_shared, seed=64 + T)
+    x = S.activations(w)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=3)
+    pool = H.HostPool(w, 0, fmt=3)
+    lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
+    buf = H.Buffers(ctx, T)
+    ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
+    torch.cuda.synchronize()
+    lay.slots.fill_(0x7FC0)
+    torch.cuda.synchronize()
+    B.moe_set_gemm_variant(6, 2)     # these experts are small: force the 4-bit source
+    ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+    gpu["compute"].synchronize()
+    ref = oracle_layer(oracle, w, x, lay.router_np, pool, shared=lay.shared_np)
+    np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
+    check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"mxfp4 decode T={T}")
+    ctx.close()
+    r2 = run_layer(gpu, w, T, x, 2, None, decode=True, prefetch=[5, 4], poison=True, fmt=3, pool=pool)
+    check_out(r2["out"], ref["out_f64"], f"mxfp4 decode through two slots T={T}")
+    sim = CacheSim(w.E, 2, S.mx4_blob_bytes(w.d, w.I))
+    sim.prefetch([5, 4])
+    sim.serve(np.nonzero(ref["counts"])[0])
+    assert r2["stats"] == {**sim.counters(), "layer_calls": 1}
 
 
 def test_q8_and_bf16_pools_of_the_same_weights_agree_within_the_format_error(gpu, oracle):

@@ -178,3 +178,77 @@ def test_int4_quantiser_error_bound_and_exact_zero():
     assert np.all(np.abs(a - b) <= per_w * 1.0 + np.abs(a) * 2.0 ** -7)
     assert np.sqrt(np.mean((a - b) ** 2)) < 0.4 * np.mean(per_w)   # typical error is step / sqrt(12)
     assert lay["total"] == raw.size and lay["meta"] % 16 == 0
+
+
+# ---------------------------------------------------------------- MXFP4 (e2m1 codes, blocks of 32, 2^k scales)
+def test_e2m1_values_the_format_fixes():
+    # OCP microscaling formats, FP4 E2M1: exponent bias 1, max normal 6.0 = S.11.1, min normal 1.0, subnormal 0.5
+    want = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    assert [oracle.e2m1_value(c) for c in range(8)] == want
+    assert [oracle.e2m1_value(8 + c) for c in range(1, 8)] == [-v for v in want[1:]]
+    assert math.copysign(1.0, oracle.e2m1_value(8)) == -1.0 and oracle.e2m1_value(8) == 0.0   # negative zero
+
+
+def test_mxfp4_dequant_by_hand_and_exactness():
+    """One row of 64 columns = two blocks: scale bytes 128 (x 2) and 120 (x 2^-7); codes 0..15 repeating.
+    Every product is one mantissa bit times a power of two: exact in bf16, no rounding anywhere."""
+    import ctypes
+    cols = 64
+    code = np.arange(cols) % 16
+    packed = (code[0::2] | (code[1::2] << 4)).astype(np.uint8)
+    scales = np.array([128, 120], dtype=np.uint8)
+    out = np.empty(cols, dtype=np.uint16)
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    oracle._load().ref_dequant_mxfp4_rows(vp(packed), vp(scales), 1, cols, vp(out))
+    table = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0.0, -.5, -1, -1.5, -2, -3, -4, -6])
+    want = table[code] * np.repeat([2.0, 2.0 ** -7], 32)
+    got = S.bf16_to_f32(out).astype(np.float64)
+    np.testing.assert_array_equal(got, want)                     # exact, not "close"
+    assert got[1] == 1.0 and got[2] == 2.0                       # column 1 = high nibble of byte 0: 0.5 * 2
+    assert out[8] == 0x8000                                      # code 8 stays a negative zero
+
+
+def test_mxfp4_blob_layout_against_numpy():
+    d, I = 128, 96
+    blob = S.normal_bf16((3 * d * I,), 8, 4, 0.03)
+    raw = np.zeros(S.mx4_blob_bytes(d, I), dtype=np.uint8)
+    S.quantize_mx4_blob_into(raw.ctypes.data, blob, d, I)
+    got = S.bf16_to_f32(oracle.dequant_mx4_blob(raw, d, I)).astype(np.float64)
+    lay = S.mx4_layout(d, I)
+    table = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0.0, -.5, -1, -1.5, -2, -3, -4, -6])
+
+    def expand(codes_off, rows, cols, scales_off):
+        b = raw[codes_off:codes_off + rows * cols // 2].astype(np.int64)
+        q = np.stack([b & 15, b >> 4], axis=1).reshape(rows, cols)
+        s = raw[scales_off:scales_off + rows * cols // 32].astype(np.float64).reshape(rows, cols // 32)
+        return (table[q] * np.repeat(2.0 ** (s - 127), 32, axis=1)).ravel()
+
+    want = np.concatenate([expand(lay["codes_up"], 2 * I, d, lay["scales_up"]),
+                           expand(lay["codes_down"], d, I, lay["scales_down"])])
+    np.testing.assert_array_equal(got, want)
+
+
+def test_mxfp4_quantiser_scale_rule_and_nearest_code():
+    rows, cols = 3, 128
+    w = S.normal_bf16((rows * cols,), 4, 6, 0.05)
+    w[40:72] = 0                                                   # an all-zero block
+    import ctypes
+    scales = np.empty(rows * cols // 32, dtype=np.uint8)
+    codes = np.empty(rows * cols // 2, dtype=np.uint8)
+    vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+    S._load().synth_quantize_mxfp4(vp(w), rows, cols, vp(scales), vp(codes))
+    wf = S.bf16_to_f32(w).astype(np.float64).reshape(-1, 32)
+    q = np.stack([codes & 15, codes >> 4], axis=1).reshape(-1, 32)
+    table = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+    for blk in range(wf.shape[0]):
+        amax = np.abs(wf[blk]).max()
+        if amax == 0:
+            assert scales[blk] == 127 and np.all((q[blk] & 7) == 0)
+            continue
+        assert int(scales[blk]) - 127 == math.floor(math.log2(amax)) - 2      # the block maximum lands in [4, 8) -> code 6 or 7
+        x = np.abs(wf[blk]) / 2.0 ** (int(scales[blk]) - 127)
+        for i in range(32):
+            dist = np.abs(table - x[i])
+            assert dist[q[blk, i] & 7] == dist.min()
+            assert (q[blk, i] >> 3) == (1 if wf[blk, i] < 0 else 0)
+        assert (q[blk] & 7).max() >= 6
