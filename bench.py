@@ -243,17 +243,17 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
     return out
 
 
-def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy):
-    """Kernel regime of decode with the 8-bit host pool: every expert fetched once through the library
-    (so its 8-bit copy sits in the staging area next to its bf16 slot), then steady-state steps in
-    which the mat-vec kernels stream the 8-bit copies."""
+def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy, fmt=1):
+    """Kernel regime of decode with a quantised host pool (fmt 1: e4m3 rows, 3: MXFP4): every expert
+    fetched once through the library (so its quantised copy sits in the staging area next to its bf16
+    slot), then steady-state steps in which the mat-vec kernels stream the quantised copies."""
     from dataclasses import replace
     wl = replace(w, L=n_layers, steps=steps)
     t0 = time.time()
-    pools = [H.HostPool(wl, l, q8=True) for l in range(n_layers)]
-    log(f"[bench] decode 8-bit host pools {n_layers * wl.E * pools[0].bytes_per_expert / 1e9:.1f} GB in {time.time() - t0:.1f}s")
+    pools = [H.HostPool(wl, l, fmt=fmt) for l in range(n_layers)]
+    log(f"[bench] decode host pools in format {fmt}: {n_layers * wl.E * pools[0].bytes_per_expert / 1e9:.1f} GB in {time.time() - t0:.1f}s")
     trace = S.markov_trace(wl)
-    ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, wl.E, wl.I_shared, True, host_format=1)
+    ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, wl.E, wl.I_shared, True, host_format=fmt)
     layers = [H.DeviceLayer(ctx, wl, l, pools[l], None) for l in range(n_layers)]
     for l in range(n_layers):
         ctx.expert_cache_prefetch(l, list(range(wl.E)), copy)
@@ -281,7 +281,7 @@ def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy):
     kt = ctx.moe_get_kernel_times()
     ctx.close()
     g = kt["gemv1"][0] / max(1, kt["gemv1"][1]) + kt["gemv2"][0] / max(1, kt["gemv2"][1])
-    code_bytes = wl.k * 3 * wl.d * wl.I
+    code_bytes = wl.k * pools[0].bytes_per_expert
     out = {"us_per_layer": us_layer, "gemv_us_per_layer": g * 1e3, "layers": n_layers,
            "gemv_HBM_GBps": code_bytes / (g * 1e-3) / 1e9 if g else 0.0,
            "gemv_frac_of_hbm_peak": code_bytes / (g * 1e-3) / 1e9 / PEAK_HBM_GBS if g else 0.0}
@@ -289,7 +289,7 @@ def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy):
 
     # the paper's decode flow on the same 8-bit pools: one cache of k slots for all layers, first layer
     # on demand, the next layer's experts predicted and prefetched, wrong guesses fetched again
-    ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, wl.k, wl.I_shared, True, shared_slots=True, host_format=1)
+    ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, wl.k, wl.I_shared, True, shared_slots=True, host_format=fmt)
     cache = torch.empty(ctx.moe_cache_bytes() // 2, dtype=torch.int16, device="cuda")
     layers = [H.DeviceLayer(ctx, wl, l, pools[l], None, slots=cache) for l in range(n_layers)]
     wps = [H.np_to_dev(S.predictor_weight(wl, l)) for l in range(n_layers)]
@@ -493,6 +493,9 @@ def main():
             # the same kernel regime with experts fetched from an 8-bit host pool: the mat-vecs stream the codes
             line["decode"]["resident_q8"] = decode_resident_q8(args, torch, B, H, S, wd, min(2, args.decode_layers),
                                                                args.decode_steps, compute, copy)
+            # and from an MXFP4 pool (the mat-vecs stream 4-bit codes and block scales)
+            line["decode"]["resident_mxfp4"] = decode_resident_q8(args, torch, B, H, S, wd, min(2, args.decode_layers),
+                                                                  args.decode_steps, compute, copy, fmt=3)
         log(f"[bench] decode: {line['decode']}")
 
     if not args.no_cpu_baseline:
