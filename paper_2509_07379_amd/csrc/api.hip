@@ -111,7 +111,8 @@ struct SlotSet {
   // 8-bit host format: the bytes of a fetch (its first piece, all of it) are in the staging area
   std::vector<hipEvent_t> landed_up, landed;
   std::vector<char> staged;          // the slot's staging area has been written before
-  std::vector<char> q_valid;         // the staging area holds the 8-bit form of what the slot holds
+  std::vector<char> q_valid;         // the staging area holds the quantised form of what the slot holds
+  std::vector<char> expand_pending;  // the expansion into the slot was enqueued; compute has not waited for it yet
   hipEvent_t group_done = nullptr;
   unsigned long long clock = 0;
 };
@@ -296,6 +297,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     // the staging area's last expansion must be over before new bytes land in it
     if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
     set.staged[s] = 1;
+    set.expand_pending[s] = 1;
     set.q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS || c.host_format == MOE_FMT_MXFP4;   // forms the mat-vec kernels read
     int rc = MOE_OK;
     if (split) {
@@ -345,6 +347,22 @@ int join_expand(moe_ctx *ctx, hipStream_t copy_stream) {
   if (!ctx->expand_tail) return MOE_OK;
   HIP_TRY(hipStreamWaitEvent(copy_stream, ctx->expand_tail, 0));
   ctx->expand_tail = nullptr;
+  return MOE_OK;
+}
+
+// The compute stream waits until slot s can be read: its quantised copy in the staging area
+// (from_copy: the bytes have landed) or the bf16 slot itself (landed and, for a quantised pool,
+// expanded).
+int wait_ready(SlotSet &set, int s, bool from_copy, hipStream_t cs) {
+  if (from_copy) {
+    if (set.copy_pending[s]) {
+      HIP_TRY(hipStreamWaitEvent(cs, set.landed[s], 0));
+      set.copy_pending[s] = 0;
+    }
+  } else if (set.copy_pending[s] || set.expand_pending[s]) {
+    HIP_TRY(hipStreamWaitEvent(cs, set.copied[s], 0));
+    set.copy_pending[s] = set.expand_pending[s] = 0;
+  }
   return MOE_OK;
 }
 
@@ -589,13 +607,19 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 
   GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
   L.stats.layer_calls++;
+  // Will the launch that runs expert e (its largest group having `rows` rows) read the quantised
+  // copy in the staging area?  Then it only needs the bytes to have landed, not the expansion.
+  const bool copies_possible = decode && gemv_reads_copies(a1) && gemv_reads_copies(a2);
+  auto reads_copy = [&](int e, int rows) {
+    return copies_possible && rows <= 8 && e >= 0 && ((a1.q8_mask >> e) & 1ull);
+  };
 
   if (enqueue_blind) {
     // Every expert is in a slot: nothing to decide on the host, one grouped launch.
     for (int s = 0; s < S; ++s)
-      if (L.set->copy_pending[s] && L.set->slot_layer[s] == L.index) {
-        HIP_TRY(hipStreamWaitEvent(cs, L.set->copied[s], 0));
-        L.set->copy_pending[s] = 0;
+      if (L.set->slot_layer[s] == L.index) {
+        rc = wait_ready(*L.set, s, reads_copy(L.set->slot_expert[s], T), cs);
+        if (rc) return rc;
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
     if (blind_one) a1.sel_ids = a2.sel_ids = reinterpret_cast<const int32_t *>(ws + W.ids);
@@ -647,17 +671,10 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         }
       }
     L.stats.misses += (int32_t)misses.size();
-    auto wait_copied = [&](int s) -> int {
-      if (L.set->copy_pending[s]) {
-        HIP_TRY(hipStreamWaitEvent(cs, L.set->copied[s], 0));
-        L.set->copy_pending[s] = 0;
-      }
-      return MOE_OK;
-    };
     if (n_hits && misses.empty()) {
       for (int e = 0; e < E; ++e)
         if ((hit_mask >> e) & 1ull) {
-          rc = wait_copied(L.expert_slot[e]);
+          rc = wait_ready(*L.set, L.expert_slot[e], reads_copy(e, hit_max), cs);
           if (rc) return rc;
         }
       rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs);
@@ -671,7 +688,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       for (int e = 0; e < E; ++e) {
         if (!((hit_mask >> e) & 1ull)) continue;
         const int s = L.expert_slot[e];
-        rc = wait_copied(s);  // only this expert's fetch: the next one may still be in flight
+        rc = wait_ready(*L.set, s, reads_copy(e, counts[e]), cs);  // only this expert's fetch: the next one may still be in flight
         if (rc) return rc;
         rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
         if (rc) return rc;
@@ -690,15 +707,19 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       const bool last = i + 1 == misses.size();
       rc = place(ctx, L, e, s, false, ks, false, last);
       if (rc) return rc;
-      HIP_TRY(hipStreamWaitEvent(cs, last ? L.set->copied_up[s] : L.set->copied[s], 0));
-      L.set->copy_pending[s] = 0;
       a1.slot[e] = a2.slot[e] = (signed char)s;
-      if (a1.qbase) {   // fetched just now: its 8-bit copy is in the staging area
+      if (a1.qbase && L.set->q_valid[s]) {   // fetched just now: its quantised copy is in the staging area
         a1.q8_mask |= 1ull << e;
         a2.q8_mask |= 1ull << e;
       }
+      const bool from_copy = reads_copy(e, counts[e]);   // then the expansion need not be waited for
+      SlotSet &set = *L.set;
+      HIP_TRY(hipStreamWaitEvent(cs, from_copy ? (last ? set.landed_up[s] : set.landed[s])
+                                               : (last ? set.copied_up[s] : set.copied[s]), 0));
+      set.copy_pending[s] = 0;
+      if (!from_copy) set.expand_pending[s] = 0;
       rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs, nullptr, nullptr,
-                       last ? L.set->copied[s] : nullptr);
+                       last ? (from_copy ? set.landed[s] : set.copied[s]) : nullptr);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(L.set->used[s], cs));
       L.set->use_kind[s] = 1;
@@ -853,6 +874,7 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
     HIP_TRY(hipEventCreateWithFlags(&set.group_done, hipEventDisableTiming));
     set.staged.assign(S, 0);
     set.q_valid.assign(S, 0);
+    set.expand_pending.assign(S, 0);
     if (c.host_format != MOE_FMT_BF16) {
       set.landed_up.assign(S, nullptr);
       set.landed.assign(S, nullptr);

@@ -325,6 +325,15 @@ void set_gemv_rows(int rows) { g_gemv_rows = rows; }
 static int g_gemv_q8_always = 0;   // test hook: 8-bit copies are used whatever the experts' size
 void set_gemv_q8_always(int on) { g_gemv_q8_always = on; }
 
+// 8-bit and 4-bit copies pay where the launch is bound by the bytes it streams: experts of 16 M weights
+// per matrix and more (Mixtral-sized: 1.4 to 2 times faster at 1 to 8 tokens).  Small experts
+// (Qwen-sized, 3 M) are bound by the launch itself at 1 or 2 tokens and by arithmetic above; there
+// the expansion only adds instructions.
+bool gemv_reads_copies(const GemmArgs &args) {
+  return args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0 &&
+         ((long long)args.N * args.K >= (1ll << 24) || g_gemv_q8_always);
+}
+
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra) {
   if (n_groups_in_mask <= 0 || max_rows_per_group <= 0) {
@@ -337,12 +346,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     if (extra->N > max_n) max_n = extra->N;
     if (extra->K > max_k) max_k = extra->K;
   }
-  // 8-bit copies pay where the launch is bound by the bytes it streams: experts of 16 M weights per
-  // matrix and more (Mixtral-sized: 1.4 to 1.5 times faster at 1 to 6 tokens).  Small experts
-  // (Qwen-sized, 3 M) are bound by the launch itself at 1 or 2 tokens and by arithmetic above; there
-  // the expansion only adds instructions.
-  const bool use_q8 = args.q8_mask != 0 && args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0 &&
-                      ((long long)args.N * args.K >= (1ll << 24) || g_gemv_q8_always);
+  const bool use_q8 = args.q8_mask != 0 && gemv_reads_copies(args);
   const int ntcap = max_tok < GV_MAXTOK ? max_tok : GV_MAXTOK;
   int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
   if (kseg >= max_k) kseg = max_k;

@@ -107,6 +107,9 @@ void set_gemm_variant(int mode, int variant);
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra = nullptr);
 
+// Whether launch_grouped_gemv streams quantised copies for the experts of args.q8_mask (format,
+// alignment, expert size or the test hook), whatever the mask and the token count.
+bool gemv_reads_copies(const GemmArgs &args);
 void set_gemv_q8_always(int on);   // test hook: use the 8-bit copies whatever the experts' size
 void set_gemv_rows(int rows);   // tuning hook: weight rows per wave (0 = choose by shape)
 

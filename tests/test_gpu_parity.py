@@ -506,6 +506,31 @@ def test_mxfp4_decode_streams_the_4bit_copies(gpu, oracle, d, I, I_shared, T):
     assert r2["stats"] == {**sim.counters(), "layer_calls": 1}
 
 
+@pytest.mark.parametrize("fmt", [1, 3])
+def test_quantised_decode_then_prefill_without_a_pause(gpu, oracle, fmt):
+    """A decode call that reads the quantised copies waits only for the bytes to land; the prefill call
+    enqueued right behind it reads the bf16 slots and must wait for their expansion.  Both against the
+    oracle, on experts that are fetched by the first call itself."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("q_then_prefill", d=512, I=256, E=6, k=2, T=96, seed=59)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, 0, True, host_format=fmt)
+    pool = H.HostPool(w, 0, fmt=fmt)
+    lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
+    xd_np, xp_np = S.activations(w, 0, 1)[:2], S.activations(w, 0, 2)
+    xd, xp = H.np_to_dev(xd_np), H.np_to_dev(xp_np)
+    bd, bp = H.Buffers(ctx, 2), H.Buffers(ctx, w.T)
+    B.moe_set_gemm_variant(6, 2)
+    ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])           # copies still in flight
+    ctx.moe_decode_layer(0, xd, 2, bd.y, bd.ws, gpu["compute"], gpu["copy"])
+    ctx.moe_prefill_layer(0, xp, w.T, bp.y, bp.ws, gpu["compute"], gpu["copy"])
+    gpu["compute"].synchronize()
+    for x_np, buf, tag in ((xd_np, bd, "decode"), (xp_np, bp, "prefill")):
+        ref = oracle_layer(oracle, w, x_np, lay.router_np, pool)
+        check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"format {fmt}: {tag}")
+    assert ctx.moe_get_stats(0)["misses"] == 0
+    ctx.close()
+
+
 def test_q8_and_bf16_pools_of_the_same_weights_agree_within_the_format_error(gpu, oracle):
     """The 8-bit path is the bf16 path run on rounded weights: on the same seeded experts the two
     outputs differ by what 3 mantissa bits cost (a few per cent of the output's rms), not more."""
