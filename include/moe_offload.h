@@ -298,9 +298,10 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * kernels (0 = heuristic, 1, 2 or 4); mode 5 with variant 0 makes a one-token decode call
  * with every expert resident wait for the gate's result on the host like any other call (default 1:
  * it is enqueued at once, the mat-vec launches take the k experts from the gate's id list on the
- * device); mode 6 chooses what the decode mat-vec kernels read where an 8-bit copy of an
- * expert exists (MOE_FMT_E4M3_ROWS): 0 = the copy if the experts are large enough for it to pay
- * (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy.  Process-wide.
+ * device); mode 6 chooses what the decode mat-vec kernels read where a quantised copy of an
+ * expert exists (MOE_FMT_E4M3_ROWS, MOE_FMT_MXFP4): 0 = the copy if the experts are large enough for
+ * it to pay (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy.
+ * Process-wide.
  */
 int moe_set_gemm_variant(int mode, int variant);
 
