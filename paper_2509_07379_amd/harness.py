@@ -86,6 +86,9 @@ class DeviceLayer:
             for s, e in enumerate(initial):
                 if e >= 0:
                     self.slots[s].copy_(pool.buf[e].view(torch.int16), non_blocking=False)
+        # fills and uploads above ran on torch's current stream; the library's streams are independent
+        # of it, so everything must have landed before the layer is used
+        torch.cuda.current_stream(self.cache.device).synchronize()
         ctx.moe_bind_layer(layer, pool.ptrs(), self.router, self.shared, self.cache, initial)
 
 

@@ -160,3 +160,50 @@ def test_c3_mixtral_decode_steps(gpu, oracle):
 
 def test_c5_qwen_decode_steps(gpu, oracle):
     decode_case(gpu, oracle, S.WORKLOADS["c5_qwen_decode"], n_layers=3, steps=3)
+
+
+@pytest.mark.parametrize("fmt", [1, 3])
+def test_c2_shape_quantised_host_pool(gpu, oracle, fmt):
+    """The Mixtral-shaped layer served from an 8-bit (e4m3 rows) or MXFP4 CPU expert cache at full size:
+    prefill through two slots (every expert fetched, expanded and used once), then decode on resident
+    experts, where the mat-vec kernels stream the quantised copies (rows of 4096 and 14336 weights, the
+    size at which the copies are used without a hook).  Outputs on sampled tokens against the oracle
+    run on its own expansion of the same blobs."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.WORKLOADS["c2_mixtral_prefill"]
+    pool = H.HostPool(w, 0, fmt=fmt)
+    expand = {1: oracle.dequant_blob, 3: oracle.dequant_mx4_blob}[fmt]
+    blobs = [expand(pool.blob_np(e), w.d, w.I) for e in range(w.E)]
+    x_np = S.activations(w)
+
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, 2, 0, True, host_format=fmt)
+    lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
+    buf = H.Buffers(ctx, w.T)
+    x = H.np_to_dev(x_np)
+    ctx.expert_cache_prefetch(0, [0, 1], gpu["copy"])
+    ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+    gpu["compute"].synchronize()
+    sel = sample_tokens(w.T, 12)
+    ref = oracle.moe_layer(x_np, lay.router_np, blobs, w.k, sel=sel, I=w.I)
+    routing = buf.routing(ctx, gpu["compute"])
+    for key in ("ids", "counts", "perm"):
+        np.testing.assert_array_equal(routing[key], ref[key], err_msg=key)
+    check_out(H.dev_to_np_u16(buf.y)[sel], ref["out_f64"], f"format {fmt} prefill through two slots")
+    st = ctx.moe_get_stats(0)
+    assert st["bytes_h2d"] == w.E * pool.bytes_per_expert and st["misses"] == w.E - 2
+    ctx.close()
+
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, 0, True, host_format=fmt)
+    lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
+    ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
+    torch.cuda.synchronize()
+    lay.slots.fill_(0x7FC0)          # decode must not need the bf16 slots
+    torch.cuda.synchronize()
+    for T in (1, 4):
+        buf = H.Buffers(ctx, T)
+        ctx.moe_decode_layer(0, H.np_to_dev(x_np[:T]), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+        gpu["compute"].synchronize()
+        ref = oracle.moe_layer(x_np[:T], lay.router_np, blobs, w.k, I=w.I)
+        np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
+        check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"format {fmt} decode T={T}")
+    ctx.close()
