@@ -48,6 +48,7 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // 256 x 256 on 256 CUs) leave most of the last round idle; slicing K makes the tiles finer.
 // The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
 int g_splitk_override = 0;  // tuning hook (moe_set_gemm_variant mode 3); 0 = heuristic
+int g_no_fused_down = 0;  // tuning hook (mode 7): 1 = a one-token call runs the down mat-vec and the weighted sum as two launches
 int g_no_q8_matvec = 0;  // tuning hook (mode 6): 1 = mat-vecs read the expanded bf16 slots even when an 8-bit copy exists
 int g_blind_one_token = 1;  // tuning hook (mode 5): 0 = a one-token decode call always waits for the gate on the host
 
@@ -606,6 +607,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   }
 
   GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
+  bool combined = false;   // the weighted sum has been done by the down projection's launch
   L.stats.layer_calls++;
   // Will the launch that runs expert e (its largest group having `rows` rows) read the quantised
   // copy in the staging area?  Then it only needs the bytes to have landed, not the expansion.
@@ -623,9 +625,22 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
     if (blind_one) a1.sel_ids = a2.sel_ids = reinterpret_cast<const int32_t *>(ws + W.ids);
-    rc = run_experts(ctx, decode, a1, a2, mask, blind_one ? c.k : E, n, T, cs,
-                     shared_in_routed_launch ? &s1 : nullptr, shared_in_routed_launch ? &s2 : nullptr);
-    if (rc) return rc;
+    if (blind_one && !c.I_shared && (size_t)c.I * 2 <= 65536 && !g_no_fused_down) {
+      // one token, no shared experts: the down mat-vec adds the k experts' rows up itself
+      a1.group_mask = a2.group_mask = mask;
+      {
+        Timer t(ctx, cs, MOE_K_GEMV1);
+        HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, 1, c.k, cs, nullptr));
+      }
+      Timer t(ctx, cs, MOE_K_GEMV2);
+      HIP_TRY(launch_fused_down_combine(a2, reinterpret_cast<const float *>(ws + W.w), c.k,
+                                        reinterpret_cast<uint16_t *>(dev_y), cs));
+      combined = true;
+    } else {
+      rc = run_experts(ctx, decode, a1, a2, mask, blind_one ? c.k : E, n, T, cs,
+                       shared_in_routed_launch ? &s1 : nullptr, shared_in_routed_launch ? &s2 : nullptr);
+      if (rc) return rc;
+    }
     HIP_TRY(hipEventRecord(L.set->group_done, cs));
     for (int s = 0; s < S; ++s)
       if (L.set->slot_layer[s] == L.index) L.set->use_kind[s] = 2;
@@ -728,7 +743,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 
   // ---- weighted sum per token (+ shared experts)
   if (shared_on_side) HIP_TRY(hipStreamWaitEvent(cs, ctx->join, 0));
-  {
+  if (!combined) {
     Timer t(ctx, cs, MOE_K_COMBINE);
     HIP_TRY(launch_combine(reinterpret_cast<const float *>(ws + W.Y), W.splitk, (long long)n * c.d,
                            reinterpret_cast<const float *>(ws + W.w),
@@ -1190,7 +1205,11 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
 }
 
 int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 6 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 7 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode == 7) {
+    g_no_fused_down = variant != 0;
+    return MOE_OK;
+  }
   if (mode == 6) {
     if (variant > 2) return fail(MOE_E_ARG, "8-bit mat-vec source: 0 (by expert size), 1 (never) or 2 (always)");
     g_no_q8_matvec = variant == 1;

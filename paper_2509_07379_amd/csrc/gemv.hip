@@ -318,6 +318,71 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
   }
 }
 
+// One token, down projection and weighted sum in one launch (no shared experts): a wave owns GV_R output
+// columns and walks over the token's k experts (ids from the gate's list on the device); per expert
+// the same row sums as grouped_gemv_kernel<GEMM_PLAIN_F32> (same staging, same lane order, so the
+// same bits), then out[c] = bf16(fma(w_j, y_j[c], ...)) in the order j = 0 .. k-1 of the weighted-sum
+// kernel.  Saves the fp32 round trip of y and one launch.  K * 2 bytes of the expert's h fit the LDS
+// buffer; all 256 threads stage it.
+template <int GV_R, int QF>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QF ? 4 : 6)))
+void fused_down_combine_kernel(const GemmArgs args, const float *__restrict__ gate_w, int k_top,
+                               uint16_t *__restrict__ out) {
+  constexpr int GV_WAVES = 4;
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_first = (blockIdx.x * GV_WAVES + wave) * GV_R;
+  const int seg_chunks = args.K >> 3;
+  float total[GV_R];
+#pragma unroll
+  for (int r = 0; r < GV_R; ++r) total[r] = 0.0f;
+  for (int j = 0; j < k_top; ++j) {
+    const int grp = args.sel_ids[j];
+    const int row = args.offsets[grp];   // the sorted row of this (token, expert) pair: its h vector
+    __syncthreads();                     // the previous expert's vector is fully consumed
+    for (int c = tid; c < seg_chunks; c += 256)
+      xs[c] = *reinterpret_cast<const u32x4 *>(args.A + (long long)row * args.lda + c * 8);
+    __syncthreads();
+    const bool q8 = QF != 0 && ((args.q8_mask >> grp) & 1ull);
+    const char *wptr = args.wbase + (long long)args.slot[grp] * args.wstride;
+    const char *qptr = args.qbase + (long long)args.slot[grp] * args.qstride;
+    const u32x4 *w0[GV_R];
+    const uint8_t *sc0[GV_R];
+    float s0[GV_R];
+    float acc0[GV_R][1], acc1[GV_R][1];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      const long long n = min(n_first + r, args.N - 1);
+      acc0[r][0] = acc1[r][0] = 0.0f;
+      s0[r] = 0.0f;
+      sc0[r] = nullptr;
+      w0[r] = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(wptr + args.b0_off) + n * args.ldb);
+      if (QF == 1 && q8) {
+        w0[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b0_off + n * args.ldb);
+        s0[r] = reinterpret_cast<const float *>(qptr + args.q_s0_off)[n];
+      }
+      if (QF == 2 && q8) {
+        w0[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b0_off + ((n * args.ldb) >> 1));
+        sc0[r] = reinterpret_cast<const uint8_t *>(qptr + args.q_s0_off) + ((n * args.ldb) >> 5);
+      }
+    }
+    if (QF == 1 && q8) accumulate_q8<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, seg_chunks, w0, w0, s0, s0, lane, acc0, acc1);
+    else if (QF == 2 && q8) accumulate_mx4<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, seg_chunks, w0, w0, sc0, sc0, lane, acc0, acc1);
+    else accumulate<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, seg_chunks, w0, w0, lane, acc0, acc1);
+    const float wj = gate_w[j];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      // y = 0 + (the one plane's value), then fma(w_j, y, sum): the weighted-sum kernel's operations
+      const float y = 0.0f + wave_sum_tree(acc0[r][0]);
+      total[r] = fmaf(wj, y, total[r]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < GV_R; ++r)
+    if (lane == 0 && n_first + r < args.N) out[n_first + r] = f32_to_bf16(total[r]);
+}
+
 }  // namespace
 
 static int g_gemv_rows = 0;   // tuning hook: rows per wave (0 = by shape)
@@ -332,6 +397,40 @@ void set_gemv_q8_always(int on) { g_gemv_q8_always = on; }
 bool gemv_reads_copies(const GemmArgs &args) {
   return args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0 &&
          ((long long)args.N * args.K >= (1ll << 24) || g_gemv_q8_always);
+}
+
+// One token (its row in the sorted order is offsets[expert]), args = the down projection's arguments
+// with sel_ids set, gate_w [k] the token's gate values, out [N] bf16.  Requires K * 2 <= 64 KB.
+hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, int k_top, uint16_t *out,
+                                     hipStream_t stream) {
+  if (!args.sel_ids || !args.offsets || args.K % 8 || (size_t)args.K * 2 > 65536) return hipErrorInvalidValue;
+  const bool use_q = args.q8_mask != 0 && gemv_reads_copies(args);
+  const int rows_per_wave = (use_q && args.K >= 2048) ? 2 : (args.K >= 2048 ? 1 : 2);
+  const int rows_per_block = 4 * rows_per_wave;
+  const dim3 grid((args.N + rows_per_block - 1) / rows_per_block);
+  const size_t smem = (size_t)args.K * 2;
+#define MOE_FUSED_LAUNCH(R, Q)                                                                \
+  do {                                                                                        \
+    auto kern = fused_down_combine_kernel<R, Q>;                                              \
+    static bool attr_set = false;                                                             \
+    if (!attr_set) {                                                                          \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 65536);  \
+      if (e != hipSuccess) return e;                                                          \
+      attr_set = true;                                                                        \
+    }                                                                                         \
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, args, gate_w, k_top, out);        \
+  } while (0)
+  const int q = use_q ? args.qfmt : 0;
+  if (rows_per_wave == 2) {
+    if (q == 2) MOE_FUSED_LAUNCH(2, 2);
+    else if (q == 1) MOE_FUSED_LAUNCH(2, 1);
+    else MOE_FUSED_LAUNCH(2, 0);
+  } else {
+    MOE_FUSED_LAUNCH(1, 0);
+  }
+#undef MOE_FUSED_LAUNCH
+  return hipGetLastError();
 }
 
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,

@@ -214,6 +214,31 @@ def test_one_token_decode_enqueued_from_the_gates_id_list(gpu, oracle, E, k, Ish
         np.testing.assert_array_equal(a, b)          # the same kernels on the same experts: the same bits
 
 
+@pytest.mark.parametrize("fmt", [0, 1, 3])
+@pytest.mark.parametrize("d,I,E,k", [(512, 256, 8, 2), (4096, 64, 64, 6), (264, 136, 5, 5)])
+def test_one_token_down_projection_and_weighted_sum_in_one_launch(gpu, oracle, fmt, d, I, E, k):
+    """One token without shared experts: the down mat-vec walks over the token's k experts and applies
+    the gate values itself.  The same bits as the two-launch path (same row sums, same order of the
+    weighted sum), for bf16 slots and for the quantised copies; and the oracle's output."""
+    B = gpu["binding"]
+    if fmt and (d % 32 or I % 32):
+        pytest.skip("quantised copies need multiples of 32")
+    w = S.Workload("fused_down", d=d, I=I, E=E, k=k, T=1, seed=91)
+    outs = []
+    for two_launches in (0, 1):
+        B.moe_set_gemm_variant(7, two_launches)
+        B.moe_set_gemm_variant(6, 2 if fmt else 0)
+        for step in range(2):
+            x = S.activations(w, 0, step)
+            r = run_layer(gpu, w, 1, x, E, None if fmt else list(range(E)), decode=True,
+                          prefetch=list(range(E)) if fmt else None, fmt=fmt)
+            ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"])
+            check_out(r["out"], ref["out_f64"], f"fused down, format {fmt}, two_launches={two_launches}")
+            outs.append(r["out"])
+    np.testing.assert_array_equal(outs[0], outs[2])
+    np.testing.assert_array_equal(outs[1], outs[3])
+
+
 def test_per_token_bias_forces_trace(gpu, oracle):
     w = S.Workload("trace", d=256, I=128, E=60, k=4, T=8, seed=5, L=3, steps=2, p_stay=0.5)
     trace = S.markov_trace(w)
