@@ -301,8 +301,9 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * device); mode 6 chooses what the decode mat-vec kernels read where a quantised copy of an
  * expert exists (MOE_FMT_E4M3_ROWS, MOE_FMT_MXFP4): 0 = the copy if the experts are large enough for
  * it to pay (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy;
- * mode 7 with variant 1 makes a one-token decode call without shared experts run the down mat-vec
- * and the weighted sum as two launches instead of one (the same bits either way).  Process-wide.
+ * mode 7 with variant 1 makes a one-token decode call with every expert resident run the down
+ * mat-vec and the weighted sum as two launches instead of one (the same bits either way).
+ * Process-wide.
  */
 int moe_set_gemm_variant(int mode, int variant);
 

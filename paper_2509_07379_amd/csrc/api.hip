@@ -625,16 +625,17 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
     if (blind_one) a1.sel_ids = a2.sel_ids = reinterpret_cast<const int32_t *>(ws + W.ids);
-    if (blind_one && !c.I_shared && (size_t)c.I * 2 <= 65536 && !g_no_fused_down) {
-      // one token, no shared experts: the down mat-vec adds the k experts' rows up itself
+    if (blind_one && (size_t)c.I * 2 <= 65536 && (size_t)c.I_shared * 2 <= 65536 && !g_no_fused_down) {
+      // one token: the down mat-vec adds the k experts' rows (and the shared experts') up itself
       a1.group_mask = a2.group_mask = mask;
       {
         Timer t(ctx, cs, MOE_K_GEMV1);
-        HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, 1, c.k, cs, nullptr));
+        HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, 1, c.k, cs, shared_in_routed_launch ? &s1 : nullptr));
       }
       Timer t(ctx, cs, MOE_K_GEMV2);
       HIP_TRY(launch_fused_down_combine(a2, reinterpret_cast<const float *>(ws + W.w), c.k,
-                                        reinterpret_cast<uint16_t *>(dev_y), cs));
+                                        reinterpret_cast<uint16_t *>(dev_y), cs,
+                                        shared_in_routed_launch ? &s2 : nullptr));
       combined = true;
     } else {
       rc = run_experts(ctx, decode, a1, a2, mask, blind_one ? c.k : E, n, T, cs,

@@ -318,7 +318,7 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
   }
 }
 
-// One token, down projection and weighted sum in one launch (no shared experts): a wave owns GV_R output
+// One token, down projection and weighted sum in one launch: a wave owns GV_R output
 // columns and walks over the token's k experts (ids from the gate's list on the device); per expert
 // the same row sums as grouped_gemv_kernel<GEMM_PLAIN_F32> (same staging, same lane order, so the
 // same bits), then out[c] = bf16(fma(w_j, y_j[c], ...)) in the order j = 0 .. k-1 of the weighted-sum
@@ -326,8 +326,8 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
 // buffer; all 256 threads stage it.
 template <int GV_R, int QF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QF ? 4 : 6)))
-void fused_down_combine_kernel(const GemmArgs args, const float *__restrict__ gate_w, int k_top,
-                               uint16_t *__restrict__ out) {
+void fused_down_combine_kernel(const GemmArgs args, const GemmArgs extra, int has_extra,
+                               const float *__restrict__ gate_w, int k_top, uint16_t *__restrict__ out) {
   constexpr int GV_WAVES = 4;
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
@@ -378,6 +378,27 @@ void fused_down_combine_kernel(const GemmArgs args, const float *__restrict__ ga
       total[r] = fmaf(wj, y, total[r]);
     }
   }
+  if (has_extra) {
+    // the shared experts (one always-on group of bf16 weights, its h vector in extra.A): their down
+    // rows for the same columns, added after the routed sum as the weighted-sum kernel adds them
+    const int chunks = extra.K >> 3;
+    __syncthreads();
+    for (int c = tid; c < chunks; c += 256)
+      xs[c] = *reinterpret_cast<const u32x4 *>(extra.A + (long long)extra.single_row0 * extra.lda + c * 8);
+    __syncthreads();
+    const char *wptr = extra.wbase + (long long)extra.slot[0] * extra.wstride;
+    const u32x4 *w0[GV_R];
+    float acc0[GV_R][1], acc1[GV_R][1];
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) {
+      const long long n = min(n_first + r, extra.N - 1);
+      acc0[r][0] = acc1[r][0] = 0.0f;
+      w0[r] = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(wptr + extra.b0_off) + n * extra.ldb);
+    }
+    accumulate<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, chunks, w0, w0, lane, acc0, acc1);
+#pragma unroll
+    for (int r = 0; r < GV_R; ++r) total[r] = total[r] + wave_sum_tree(acc0[r][0]);
+  }
 #pragma unroll
   for (int r = 0; r < GV_R; ++r)
     if (lane == 0 && n_first + r < args.N) out[n_first + r] = f32_to_bf16(total[r]);
@@ -400,15 +421,21 @@ bool gemv_reads_copies(const GemmArgs &args) {
 }
 
 // One token (its row in the sorted order is offsets[expert]), args = the down projection's arguments
-// with sel_ids set, gate_w [k] the token's gate values, out [N] bf16.  Requires K * 2 <= 64 KB.
+// with sel_ids set, gate_w [k] the token's gate values, out [N] bf16; extra: the shared experts' down
+// projection (one group of one row), added last.  Requires K * 2 <= 64 KB for both.
 hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, int k_top, uint16_t *out,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, const GemmArgs *extra) {
   if (!args.sel_ids || !args.offsets || args.K % 8 || (size_t)args.K * 2 > 65536) return hipErrorInvalidValue;
+  if (extra && (extra->N != args.N || extra->K % 8 || (size_t)extra->K * 2 > 65536 || extra->single_rows != 1))
+    return hipErrorInvalidValue;
+  const int max_k = extra && extra->K > args.K ? extra->K : args.K;
+  const GemmArgs &extra_args = extra ? *extra : args;
+  const int has_extra = extra ? 1 : 0;
   const bool use_q = args.q8_mask != 0 && gemv_reads_copies(args);
   const int rows_per_wave = (use_q && args.K >= 2048) ? 2 : (args.K >= 2048 ? 1 : 2);
   const int rows_per_block = 4 * rows_per_wave;
   const dim3 grid((args.N + rows_per_block - 1) / rows_per_block);
-  const size_t smem = (size_t)args.K * 2;
+  const size_t smem = (size_t)max_k * 2;
 #define MOE_FUSED_LAUNCH(R, Q)                                                                \
   do {                                                                                        \
     auto kern = fused_down_combine_kernel<R, Q>;                                              \
@@ -419,7 +446,7 @@ hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, 
       if (e != hipSuccess) return e;                                                          \
       attr_set = true;                                                                        \
     }                                                                                         \
-    hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, args, gate_w, k_top, out);        \
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, args, extra_args, has_extra, gate_w, k_top, out); \
   } while (0)
   const int q = use_q ? args.qfmt : 0;
   if (rows_per_wave == 2) {

@@ -107,11 +107,12 @@ void set_gemm_variant(int mode, int variant);
 hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows_per_group,
                                int n_groups_in_mask, hipStream_t stream, const GemmArgs *extra = nullptr);
 
-// One token without shared experts: the down projection of its k experts (args.sel_ids, device) and the
-// weighted sum in one launch; gate_w [k] fp32 (device), out [N] bf16.  The same bits as
-// launch_grouped_gemv(GEMM_PLAIN_F32) followed by launch_combine.  Requires K * 2 <= 64 KB.
+// One token: the down projection of its k experts (args.sel_ids, device), of the shared experts
+// (extra, may be NULL: a single group of one row) and the weighted sum in one launch; gate_w [k] fp32
+// (device), out [N] bf16.  The same bits as launch_grouped_gemv(GEMM_PLAIN_F32) followed by
+// launch_combine.  Requires K * 2 <= 64 KB for both problems.
 hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, int k_top, uint16_t *out,
-                                     hipStream_t stream);
+                                     hipStream_t stream, const GemmArgs *extra = nullptr);
 // Whether launch_grouped_gemv streams quantised copies for the experts of args.q8_mask (format,
 // alignment, expert size or the test hook), whatever the mask and the token count.
 bool gemv_reads_copies(const GemmArgs &args);

@@ -214,15 +214,17 @@ def test_one_token_decode_enqueued_from_the_gates_id_list(gpu, oracle, E, k, Ish
         np.testing.assert_array_equal(a, b)          # the same kernels on the same experts: the same bits
 
 
-@pytest.mark.parametrize("fmt,d,I,E,k", [(f, d, I, E, k) for f in (0, 1, 3)
-                                         for d, I, E, k in ((512, 256, 8, 2), (4096, 64, 64, 6), (264, 136, 5, 5))
-                                         if f == 0 or (d % 32 == 0 and I % 32 == 0)])
-def test_one_token_down_projection_and_weighted_sum_in_one_launch(gpu, oracle, fmt, d, I, E, k):
-    """One token without shared experts: the down mat-vec walks over the token's k experts and applies
-    the gate values itself.  The same bits as the two-launch path (same row sums, same order of the
-    weighted sum), for bf16 slots and for the quantised copies; and the oracle's output."""
+@pytest.mark.parametrize("fmt,d,I,E,k,Ish", [(f, d, I, E, k, Ish) for f in (0, 1, 3)
+                                             for d, I, E, k, Ish in ((512, 256, 8, 2, 0), (4096, 64, 64, 6, 0),
+                                                                     (264, 136, 5, 5, 0), (512, 256, 60, 4, 384),
+                                                                     (256, 64, 8, 2, 2048))
+                                             if f == 0 or (d % 32 == 0 and I % 32 == 0)])
+def test_one_token_down_projection_and_weighted_sum_in_one_launch(gpu, oracle, fmt, d, I, E, k, Ish):
+    """One token: the down mat-vec walks over the token's k experts, applies the gate values itself and
+    adds the shared experts' rows.  The same bits as the two-launch path (same row sums, same order of
+    the weighted sum), for bf16 slots and for the quantised copies; and the oracle's output."""
     B = gpu["binding"]
-    w = S.Workload("fused_down", d=d, I=I, E=E, k=k, T=1, seed=91)
+    w = S.Workload("fused_down", d=d, I=I, E=E, k=k, T=1, I_shared=Ish, seed=91)
     outs = []
     for two_launches in (0, 1):
         B.moe_set_gemm_variant(7, two_launches)
@@ -231,7 +233,7 @@ def test_one_token_down_projection_and_weighted_sum_in_one_launch(gpu, oracle, f
             x = S.activations(w, 0, step)
             r = run_layer(gpu, w, 1, x, E, None if fmt else list(range(E)), decode=True,
                           prefetch=list(range(E)) if fmt else None, fmt=fmt)
-            ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"])
+            ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], shared=r["lay"].shared_np)
             check_out(r["out"], ref["out_f64"], f"fused down, format {fmt}, two_launches={two_launches}")
             outs.append(r["out"])
     np.testing.assert_array_equal(outs[0], outs[2])
