@@ -36,12 +36,12 @@ __device__ __forceinline__ float dot8(const u32x4 &xv, const u32x4 &wv, float ac
   return acc;
 }
 
-template <int MODE, int NT, int NTMAX, int GV_R>
+template <int MODE, int NT, int NTMAX, int GV_R, int UNR = 2>
 __device__ __forceinline__ void accumulate(const u32x4 *__restrict__ xs, int seg_chunks,
                                            const u32x4 *const (&w0)[GV_R], const u32x4 *const (&w1)[GV_R],
                                            int lane, float (&acc0)[GV_R][NTMAX],
                                            float (&acc1)[GV_R][NTMAX]) {
-#pragma unroll 2
+#pragma unroll UNR
   for (int c = lane; c < seg_chunks; c += 64) {
     u32x4 wv0[GV_R], wv1[GV_R];
 #pragma unroll
@@ -320,44 +320,116 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
 
 // One token, down projection and weighted sum in one launch: a wave owns GV_R output
 // columns and walks over the token's k experts (ids from the gate's list on the device); per expert
-// the same row sums as grouped_gemv_kernel<GEMM_PLAIN_F32> (same staging, same lane order, so the
-// same bits), then out[c] = bf16(fma(w_j, y_j[c], ...)) in the order j = 0 .. k-1 of the weighted-sum
-// kernel.  Saves the fp32 round trip of y and one launch.  K * 2 bytes of the expert's h fit the LDS
-// buffer; all 256 threads stage it.
+// the same row sums as grouped_gemv_kernel<GEMM_PLAIN_F32> (same lane order, so the same bits), then
+// out[c] = bf16(fma(w_j, y_j[c], ...)) in the order j = 0 .. k-1 of the weighted-sum kernel.  Saves
+// the fp32 round trip of y and one launch.
+// The h vectors (one per expert, then the shared experts') pass through LDS.  stage_all: all of them
+// fit the buffer side by side and are staged once, before the first weight row is streamed.
+// Otherwise one vector at a time: the next one is fetched into registers (FUSED_PF pieces per thread)
+// while the current expert's rows are streamed, so that the hand-over between two experts costs two
+// barriers and an LDS write instead of a round trip to L2 during which no weight is in flight.
+constexpr int FUSED_PF = 8;   // 16-byte pieces per thread held for the next vector: K <= 16384
 template <int GV_R, int QF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QF ? 4 : 6)))
 void fused_down_combine_kernel(const GemmArgs args, const GemmArgs extra, int has_extra,
-                               const float *__restrict__ gate_w, int k_top, uint16_t *__restrict__ out) {
+                               const float *__restrict__ gate_w, int k_top, uint16_t *__restrict__ out,
+                               int stage_all) {
   constexpr int GV_WAVES = 4;
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_first = (blockIdx.x * GV_WAVES + wave) * GV_R;
   const int seg_chunks = args.K >> 3;
+  const int n_phases = k_top + (has_extra ? 1 : 0);
+  // phase p < k_top: expert sel_ids[p], its h vector is the sorted row offsets[expert];
+  // phase k_top: the shared experts' h vector
+  // lane j < k of every wave looks up expert j once (id, sorted row, slot, gate value); the phases
+  // read them back with a lane read, so no phase waits for a chain of dependent lookups
+  int my_grp = 0, my_row = 0, my_slot = 0;
+  float my_w = 0.0f;
+  if (lane < k_top) {
+    my_grp = args.sel_ids[lane];
+    my_row = args.offsets[my_grp];
+    my_slot = args.slot[my_grp];
+    my_w = gate_w[lane];
+  }
+  auto vector_of = [&](int p, int &chunks) -> const u32x4 * {
+    if (p < k_top) {
+      chunks = seg_chunks;
+      return reinterpret_cast<const u32x4 *>(args.A + (long long)__builtin_amdgcn_readlane(my_row, p) * args.lda);
+    }
+    chunks = extra.K >> 3;
+    return reinterpret_cast<const u32x4 *>(extra.A + (long long)extra.single_row0 * extra.lda);
+  };
+  const bool prefetch = !stage_all && seg_chunks <= FUSED_PF * 256 && (!has_extra || (extra.K >> 3) <= FUSED_PF * 256);
+  u32x4 pf[FUSED_PF];
+  if (stage_all) {
+    int base = 0;
+    for (int p = 0; p < n_phases; ++p) {
+      int chunks;
+      const u32x4 *v = vector_of(p, chunks);
+      for (int c = tid; c < chunks; c += 256) xs[base + c] = v[c];
+      base += chunks;
+    }
+    __syncthreads();
+  } else if (prefetch) {
+    int chunks;
+    const u32x4 *v = vector_of(0, chunks);
+#pragma unroll
+    for (int i = 0; i < FUSED_PF; ++i)
+      if (tid + i * 256 < chunks) pf[i] = v[tid + i * 256];
+  }
   float total[GV_R];
 #pragma unroll
   for (int r = 0; r < GV_R; ++r) total[r] = 0.0f;
-  for (int j = 0; j < k_top; ++j) {
-    const int grp = args.sel_ids[j];
-    const int row = args.offsets[grp];   // the sorted row of this (token, expert) pair: its h vector
-    __syncthreads();                     // the previous expert's vector is fully consumed
-    for (int c = tid; c < seg_chunks; c += 256)
-      xs[c] = *reinterpret_cast<const u32x4 *>(args.A + (long long)row * args.lda + c * 8);
-    __syncthreads();
-    const bool q8 = QF != 0 && ((args.q8_mask >> grp) & 1ull);
-    const char *wptr = args.wbase + (long long)args.slot[grp] * args.wstride;
-    const char *qptr = args.qbase + (long long)args.slot[grp] * args.qstride;
+  int xs_base = 0;
+  for (int p = 0; p < n_phases; ++p) {
+    const bool shared_phase = p >= k_top;
+    // (field by field: choosing between the two argument blocks as a whole puts both on the stack)
+    const int chunks = (shared_phase ? extra.K : args.K) >> 3;
+    const int n_rows = shared_phase ? extra.N : args.N;
+    const long long ldb = shared_phase ? extra.ldb : args.ldb;
+    const u32x4 *xv = xs;
+    if (stage_all) {
+      xv = xs + xs_base;
+      xs_base += chunks;
+    } else {
+      __syncthreads();                     // the previous vector is fully consumed
+      if (prefetch) {
+#pragma unroll
+        for (int i = 0; i < FUSED_PF; ++i)
+          if (tid + i * 256 < chunks) xs[tid + i * 256] = pf[i];
+      } else {
+        int ch;
+        const u32x4 *v = vector_of(p, ch);
+        for (int c = tid; c < chunks; c += 256) xs[c] = v[c];
+      }
+      __syncthreads();
+      if (prefetch && p + 1 < n_phases) {
+        int ch;
+        const u32x4 *v = vector_of(p + 1, ch);
+#pragma unroll
+        for (int i = 0; i < FUSED_PF; ++i)
+          if (tid + i * 256 < ch) pf[i] = v[tid + i * 256];
+      }
+    }
+    const int grp = shared_phase ? 0 : __builtin_amdgcn_readlane(my_grp, p);
+    const int slot = shared_phase ? 0 : __builtin_amdgcn_readlane(my_slot, p);
+    const bool q8 = QF != 0 && !shared_phase && ((args.q8_mask >> grp) & 1ull);
+    const char *wptr = shared_phase ? extra.wbase + (long long)extra.slot[0] * extra.wstride + extra.b0_off
+                                    : args.wbase + (long long)slot * args.wstride + args.b0_off;
+    const char *qptr = args.qbase + (long long)slot * args.qstride;
     const u32x4 *w0[GV_R];
     const uint8_t *sc0[GV_R];
     float s0[GV_R];
     float acc0[GV_R][1], acc1[GV_R][1];
 #pragma unroll
     for (int r = 0; r < GV_R; ++r) {
-      const long long n = min(n_first + r, args.N - 1);
+      const long long n = min(n_first + r, n_rows - 1);
       acc0[r][0] = acc1[r][0] = 0.0f;
       s0[r] = 0.0f;
       sc0[r] = nullptr;
-      w0[r] = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(wptr + args.b0_off) + n * args.ldb);
+      w0[r] = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(wptr) + n * ldb);
       if (QF == 1 && q8) {
         w0[r] = reinterpret_cast<const u32x4 *>(qptr + args.q_b0_off + n * args.ldb);
         s0[r] = reinterpret_cast<const float *>(qptr + args.q_s0_off)[n];
@@ -367,37 +439,23 @@ void fused_down_combine_kernel(const GemmArgs args, const GemmArgs extra, int ha
         sc0[r] = reinterpret_cast<const uint8_t *>(qptr + args.q_s0_off) + ((n * args.ldb) >> 5);
       }
     }
-    if (QF == 1 && q8) accumulate_q8<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, seg_chunks, w0, w0, s0, s0, lane, acc0, acc1);
-    else if (QF == 2 && q8) accumulate_mx4<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, seg_chunks, w0, w0, sc0, sc0, lane, acc0, acc1);
-    else accumulate<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, seg_chunks, w0, w0, lane, acc0, acc1);
-    const float wj = gate_w[j];
+    if (QF == 1 && q8) accumulate_q8<GEMM_PLAIN_F32, 1, 1, GV_R>(xv, chunks, w0, w0, s0, s0, lane, acc0, acc1);
+    else if (QF == 2 && q8) accumulate_mx4<GEMM_PLAIN_F32, 1, 1, GV_R>(xv, chunks, w0, w0, sc0, sc0, lane, acc0, acc1);
+    else accumulate<GEMM_PLAIN_F32, 1, 1, GV_R>(xv, chunks, w0, w0, lane, acc0, acc1);
+    if (!shared_phase) {
+      const float wj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_w), p));
 #pragma unroll
-    for (int r = 0; r < GV_R; ++r) {
-      // y = 0 + (the one plane's value), then fma(w_j, y, sum): the weighted-sum kernel's operations
-      const float y = 0.0f + wave_sum_tree(acc0[r][0]);
-      total[r] = fmaf(wj, y, total[r]);
+      for (int r = 0; r < GV_R; ++r) {
+        // y = 0 + (the one plane's value), then fma(w_j, y, sum): the weighted-sum kernel's operations
+        const float y = 0.0f + wave_sum_tree(acc0[r][0]);
+        total[r] = fmaf(wj, y, total[r]);
+      }
+    } else {
+      // the shared experts (one always-on group of bf16 weights): their down rows for the same
+      // columns, added after the routed sum as the weighted-sum kernel adds them
+#pragma unroll
+      for (int r = 0; r < GV_R; ++r) total[r] = total[r] + wave_sum_tree(acc0[r][0]);
     }
-  }
-  if (has_extra) {
-    // the shared experts (one always-on group of bf16 weights, its h vector in extra.A): their down
-    // rows for the same columns, added after the routed sum as the weighted-sum kernel adds them
-    const int chunks = extra.K >> 3;
-    __syncthreads();
-    for (int c = tid; c < chunks; c += 256)
-      xs[c] = *reinterpret_cast<const u32x4 *>(extra.A + (long long)extra.single_row0 * extra.lda + c * 8);
-    __syncthreads();
-    const char *wptr = extra.wbase + (long long)extra.slot[0] * extra.wstride;
-    const u32x4 *w0[GV_R];
-    float acc0[GV_R][1], acc1[GV_R][1];
-#pragma unroll
-    for (int r = 0; r < GV_R; ++r) {
-      const long long n = min(n_first + r, extra.N - 1);
-      acc0[r][0] = acc1[r][0] = 0.0f;
-      w0[r] = reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(wptr + extra.b0_off) + n * extra.ldb);
-    }
-    accumulate<GEMM_PLAIN_F32, 1, 1, GV_R>(xs, chunks, w0, w0, lane, acc0, acc1);
-#pragma unroll
-    for (int r = 0; r < GV_R; ++r) total[r] = total[r] + wave_sum_tree(acc0[r][0]);
   }
 #pragma unroll
   for (int r = 0; r < GV_R; ++r)
@@ -425,17 +483,22 @@ bool gemv_reads_copies(const GemmArgs &args) {
 // projection (one group of one row), added last.  Requires K * 2 <= 64 KB for both.
 hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, int k_top, uint16_t *out,
                                      hipStream_t stream, const GemmArgs *extra) {
-  if (!args.sel_ids || !args.offsets || args.K % 8 || (size_t)args.K * 2 > 65536) return hipErrorInvalidValue;
+  if (!args.sel_ids || !args.offsets || args.K % 8 || (size_t)args.K * 2 > 65536 || k_top < 1 || k_top > 64)
+    return hipErrorInvalidValue;
   if (extra && (extra->N != args.N || extra->K % 8 || (size_t)extra->K * 2 > 65536 || extra->single_rows != 1))
     return hipErrorInvalidValue;
   const int max_k = extra && extra->K > args.K ? extra->K : args.K;
   const GemmArgs &extra_args = extra ? *extra : args;
   const int has_extra = extra ? 1 : 0;
   const bool use_q = args.q8_mask != 0 && gemv_reads_copies(args);
-  const int rows_per_wave = (use_q && args.K >= 2048) ? 2 : (args.K >= 2048 ? 1 : 2);
+  int rows_per_wave = (use_q && args.K >= 2048) ? 2 : (args.K >= 2048 ? 1 : 2);
+  if (!use_q && args.N < 4096) rows_per_wave = 1;   // a wave walks the experts one after the other: few columns, few waves
   const int rows_per_block = 4 * rows_per_wave;
   const dim3 grid((args.N + rows_per_block - 1) / rows_per_block);
-  const size_t smem = (size_t)max_k * 2;
+  // all h vectors side by side when that leaves room for five blocks per compute unit
+  const size_t all_bytes = ((size_t)k_top * args.K + (extra ? extra->K : 0)) * 2;
+  const int stage_all = all_bytes <= 28672 ? 1 : 0;
+  const size_t smem = stage_all ? all_bytes : (size_t)max_k * 2;
 #define MOE_FUSED_LAUNCH(R, Q)                                                                \
   do {                                                                                        \
     auto kern = fused_down_combine_kernel<R, Q>;                                              \
@@ -446,7 +509,7 @@ hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, 
       if (e != hipSuccess) return e;                                                          \
       attr_set = true;                                                                        \
     }                                                                                         \
-    hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, args, extra_args, has_extra, gate_w, k_top, out); \
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, args, extra_args, has_extra, gate_w, k_top, out, stage_all); \
   } while (0)
   const int q = use_q ? args.qfmt : 0;
   if (rows_per_wave == 2) {
