@@ -218,8 +218,8 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out);
  * sum (+ shared experts) -> dev_y [T, d] bf16.  Experts that are not resident stream
  * through the slots in ascending id, each fetched once on copy_stream while the previous
  * one computes.  Groups of any size run on the MFMA kernels: for a handful of tokens
- * moe_decode_layer gives the same result faster (and itself moves to the MFMA kernels when some
- * expert receives more than 8 tokens).  When some routed expert is not resident the call
+ * moe_decode_layer gives the same result faster (and itself moves to the GEMM kernels when some
+ * expert receives more than 16 tokens, 32 where the mat-vecs read quantised copies).  When some routed expert is not resident the call
  * blocks the host once, until the gate's counts are known.
  *  dev_route_bias  NULL, or fp32 added to the gate logits: element [t*bias_stride + e]
  *                  (bias_stride 0 = one row for all tokens, E = one row per token).
@@ -235,8 +235,10 @@ int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
  * One MoE layer in the decode stage (Section V-C), T = batch (small).  Same contract and
  * results as moe_prefill_layer; experts run as bandwidth-bound GEMVs.  The gate's choice is
  * compared with the cache ("synchronisation point 1"): hits run first, misses are
- * re-fetched on copy_stream and run as they land.  Experts with at most 8 tokens run as
- * mat-vecs; a batch that gives some expert more goes to the MFMA kernels.  The host looks at the gate's counts
+ * re-fetched on copy_stream and run as they land.  Experts with at most 16 tokens (32 where
+ * quantised copies are read) run as mat-vecs: per-token dot products for a few tokens, 16x16x32
+ * MFMAs over the same single pass for more; a batch that gives some expert more goes to the GEMM
+ * kernels.  The host looks at the gate's counts
  * (a short wait on a pinned mailbox) unless every expert is resident and T = 1: then the
  * mat-vec launches read the token's k experts from the gate's id list on the device and the
  * call only enqueues (its cache counters are filled in when the mailbox arrives).
@@ -302,7 +304,12 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * expert exists (MOE_FMT_E4M3_ROWS, MOE_FMT_MXFP4): 0 = the copy if the experts are large enough for
  * it to pay (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy;
  * mode 7 with variant 1 makes a one-token decode call with every expert resident run the down
- * mat-vec and the weighted sum as two launches instead of one (the same bits either way).
+ * mat-vec and the weighted sum as two launches instead of one (the same bits either way);
+ * mode 8 sets the token count per expert from which a mat-vec launch may use the matrix-core
+ * kernel (0 = default 3, where measurement says it pays; 1 = wherever the shapes allow it; a
+ * large value = never); mode 9 the largest group a decode call still gives to the mat-vec
+ * launches (0 = default: 16, or 32 on quantised copies); mode 10 the K slices (waves) per block
+ * of the matrix-core mat-vec (0 = by shape, 1..8).
  * Process-wide.
  */
 int moe_set_gemm_variant(int mode, int variant);

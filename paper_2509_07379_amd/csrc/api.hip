@@ -487,14 +487,22 @@ hipError_t wait_for_counts(moe_ctx *ctx) {
   return hipEventSynchronize(ctx->routed);
 }
 
+// Decode groups up to this many tokens use the mat-vec launches (one pass over the weights per 16
+// tokens through the matrix cores), larger ones the GEMM kernels; quantised copies are only read by
+// the mat-vec launches, which stay ahead of the bf16 GEMM for longer.
+constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsCopies = 32;
+int g_matvec_max_rows = 0;   // tuning hook: 0 = the limits above
+
 int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
                 int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream,
                 const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr,
                 hipEvent_t before_second = nullptr) {
   a1.group_mask = a2.group_mask = mask;
-  // The mat-vec kernels pass over an expert's weights once per 8 of its tokens: a decode batch that
-  // gives some expert more than that goes to the MFMA kernels, which stream the weights once.
-  if (decode && max_rows_per_group <= 8) {
+  // The mat-vec kernels pass over an expert's weights once per 16 of its tokens: a decode batch that
+  // gives some expert many more goes to the GEMM kernels, which stream the weights once.
+  const bool from_copies = a1.q8_mask != 0 && gemv_reads_copies(a1);
+  const int matvec_limit = g_matvec_max_rows > 0 ? g_matvec_max_rows : (from_copies ? kMatvecMaxRowsCopies : kMatvecMaxRows);
+  if (decode && max_rows_per_group <= matvec_limit) {
     {
       Timer t(ctx, stream, MOE_K_GEMV1);
       HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, max_rows_per_group, n_groups, stream, s1));
@@ -1206,7 +1214,19 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
 }
 
 int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 7 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 10 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode == 10) {
+    set_gemv_skinny_waves(variant);
+    return MOE_OK;
+  }
+  if (mode == 8) {
+    set_gemv_skinny_min(variant);
+    return MOE_OK;
+  }
+  if (mode == 9) {
+    g_matvec_max_rows = variant;
+    return MOE_OK;
+  }
   if (mode == 7) {
     g_no_fused_down = variant != 0;
     return MOE_OK;

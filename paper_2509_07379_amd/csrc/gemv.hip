@@ -462,10 +462,250 @@ void fused_down_combine_kernel(const GemmArgs args, const GemmArgs extra, int ha
     if (lane == 0 && n_first + r < args.N) out[n_first + r] = f32_to_bf16(total[r]);
 }
 
+// Several tokens per expert: the same pass over the weights with the sums taken by the matrix cores
+// instead of per-token dot products, which at 8 tokens, and with 4-bit weights from 3, cost more
+// issue time than the bytes take to arrive.  v_mfma_f32_16x16x32_bf16 multiplies 16 weight rows by up
+// to 16 token vectors: lane l supplies 8 consecutive k of weight row l % 16 and of token l % 16 (lane
+// group l / 16 selects which 8 of the 32), and receives the sums of rows 4 (l / 16) + i, i = 0..3,
+// for token l % 16.  A block owns one pair of row tiles (the gate and up rows of 16 columns of h, or
+// 32 columns of y); its waves cut K into slices, one each, and add their partial sums through LDS
+// in wave order, so that the launch consists of many short, equal pieces.  A lane streams 32 bytes
+// per row tile and step, four lanes one whole 128-byte line of a row; quantised rows are expanded to
+// the same bf16 values as in the per-token kernels.  The token vectors are read from global memory
+// as they are needed (a few KB per slice, shared by every block: they stay in the caches).  The sums
+// are fp32 in the matrix core's order, so results agree with the per-token kernels to rounding, not
+// bit for bit.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int SK_TOK = 16;       // tokens per pass over the weights
+constexpr int SK_MAXWAVES = 8;   // K slices per block
+
+__device__ __forceinline__ f32x4 mfma16(const u32x4 &w, const u32x4 &x, const f32x4 &acc) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc, 0, 0, 0);
+}
+
+// One K slice of one row tile pair.  F: format of the rows (0 bf16, 1 e4m3 + row scale, 2 MXFP4).
+// pa / pb: this lane's row in the two tiles at the slice's first k, already advanced to the lane
+// group's share; xl: this lane's token vector, likewise; sca / scb: MXFP4 scale bytes, likewise.
+template <int F>
+__device__ __forceinline__ void skinny_segment(const char *__restrict__ pa, const char *__restrict__ pb,
+                                               const uint8_t *__restrict__ sca, const uint8_t *__restrict__ scb,
+                                               float sa, float sb, const char *__restrict__ xl, int seg,
+                                               f32x4 &acc_a, f32x4 &acc_b) {
+  constexpr int KL = F == 0 ? 16 : (F == 1 ? 32 : 64);   // k per lane and step: 32 bytes of the row
+  constexpr int STEP = 4 * KL;                           // k per wave and step
+  constexpr int NX = KL / 8;                             // 16-byte pieces of the token vector per step
+  constexpr int D = F == 0 ? 3 : 2;                      // steps whose loads are in flight or in use
+  // The registers of a step.  The loads of step s + D - 1 are issued before the products of step s
+  // are taken, each into its own registers: left to itself the compiler reuses one set and waits
+  // for every load of a turn before it issues the next turn's.
+  struct Regs {
+    u32x4 a0, a1, b0, b1, x[NX];
+    uint32_t sc;   // MXFP4: the four scale bytes of the step (tile a: bytes 0, 1; tile b: bytes 2, 3)
+  };
+  auto load = [&](int ks, Regs &R) {
+    const u32x4 *x = reinterpret_cast<const u32x4 *>(xl + ks * 2);   // first: they arrive first
+#pragma unroll
+    for (int i = 0; i < NX; ++i) R.x[i] = x[i];
+    const u32x4 *wa = reinterpret_cast<const u32x4 *>(pa + (F == 0 ? ks * 2 : (F == 1 ? ks : ks >> 1)));
+    const u32x4 *wb = reinterpret_cast<const u32x4 *>(pb + (F == 0 ? ks * 2 : (F == 1 ? ks : ks >> 1)));
+    R.a0 = __builtin_nontemporal_load(wa);
+    R.a1 = __builtin_nontemporal_load(wa + 1);
+    R.b0 = __builtin_nontemporal_load(wb);
+    R.b1 = __builtin_nontemporal_load(wb + 1);
+    if (F == 2) {
+      const int blk = ks >> 5;   // two scale blocks of 32 codes per lane, row tile and step
+      R.sc = (uint32_t)sca[blk] | ((uint32_t)sca[blk + 1] << 8) | ((uint32_t)scb[blk] << 16) | ((uint32_t)scb[blk + 1] << 24);
+    }
+  };
+  auto compute = [&](const Regs &R) {
+    if (F == 0) {
+      acc_a = mfma16(R.a0, R.x[0], acc_a);
+      acc_b = mfma16(R.b0, R.x[0], acc_b);
+      acc_a = mfma16(R.a1, R.x[1], acc_a);
+      acc_b = mfma16(R.b1, R.x[1], acc_b);
+    } else if (F == 1) {
+      u32x4 lo, hi;
+      expand16(R.a0, sa, lo, hi);
+      acc_a = mfma16(lo, R.x[0], acc_a);
+      acc_a = mfma16(hi, R.x[1], acc_a);
+      expand16(R.b0, sb, lo, hi);
+      acc_b = mfma16(lo, R.x[0], acc_b);
+      acc_b = mfma16(hi, R.x[1], acc_b);
+      expand16(R.a1, sa, lo, hi);
+      acc_a = mfma16(lo, R.x[2], acc_a);
+      acc_a = mfma16(hi, R.x[3], acc_a);
+      expand16(R.b1, sb, lo, hi);
+      acc_b = mfma16(lo, R.x[2], acc_b);
+      acc_b = mfma16(hi, R.x[3], acc_b);
+    } else {
+      const float fa0 = __uint_as_float((R.sc & 0xffu) << 23), fa1 = __uint_as_float(((R.sc >> 8) & 0xffu) << 23);
+      const float fb0 = __uint_as_float(((R.sc >> 16) & 0xffu) << 23), fb1 = __uint_as_float((R.sc >> 24) << 23);
+      const uint32_t a00 = R.a0.x, a01 = R.a0.y, a02 = R.a0.z, a03 = R.a0.w, a10 = R.a1.x, a11 = R.a1.y, a12 = R.a1.z, a13 = R.a1.w;
+      const uint32_t b00 = R.b0.x, b01 = R.b0.y, b02 = R.b0.z, b03 = R.b0.w, b10 = R.b1.x, b11 = R.b1.y, b12 = R.b1.z, b13 = R.b1.w;
+      acc_a = mfma16(mx4_expand8(a00, fa0), R.x[0], acc_a); acc_b = mfma16(mx4_expand8(b00, fb0), R.x[0], acc_b);
+      acc_a = mfma16(mx4_expand8(a01, fa0), R.x[1], acc_a); acc_b = mfma16(mx4_expand8(b01, fb0), R.x[1], acc_b);
+      acc_a = mfma16(mx4_expand8(a02, fa0), R.x[2], acc_a); acc_b = mfma16(mx4_expand8(b02, fb0), R.x[2], acc_b);
+      acc_a = mfma16(mx4_expand8(a03, fa0), R.x[3], acc_a); acc_b = mfma16(mx4_expand8(b03, fb0), R.x[3], acc_b);
+      acc_a = mfma16(mx4_expand8(a10, fa1), R.x[4], acc_a); acc_b = mfma16(mx4_expand8(b10, fb1), R.x[4], acc_b);
+      acc_a = mfma16(mx4_expand8(a11, fa1), R.x[5], acc_a); acc_b = mfma16(mx4_expand8(b11, fb1), R.x[5], acc_b);
+      acc_a = mfma16(mx4_expand8(a12, fa1), R.x[6], acc_a); acc_b = mfma16(mx4_expand8(b12, fb1), R.x[6], acc_b);
+      acc_a = mfma16(mx4_expand8(a13, fa1), R.x[7], acc_a); acc_b = mfma16(mx4_expand8(b13, fb1), R.x[7], acc_b);
+    }
+  };
+  // n >= 1 steps.  Start-up and the turns of the main loop issue their loads unconditionally (the
+  // counts of loads in flight that the compiler derives for its waits are then the same on every
+  // path); the last 2 D - 2 steps at most are drained with conditions.
+  const int n = seg / STEP;
+  Regs R[D];
+#pragma unroll
+  for (int i = 0; i < D - 1; ++i) load(min(i, n - 1) * STEP, R[i]);
+  int s = 0;
+  for (; s + 2 * D - 2 < n; s += D) {
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      load((s + i + D - 1) * STEP, R[(i + D - 1) % D]);
+      compute(R[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2 * D - 2; ++i) {
+    if (s + i < n) {
+      if (s + i + D - 1 < n) load((s + i + D - 1) * STEP, R[(i + D - 1) % D]);
+      compute(R[i % D]);
+    }
+  }
+}
+
+// Grid: x = row tile pair, y = selected group, the shared experts in further runs of y (as
+// grouped_gemv_kernel).  blockDim.x / 64 <= SK_MAXWAVES waves = K slices.
+// Requires N % 16 == 0 and K % 64 == 0 (bf16), 128 (e4m3), 256 (MXFP4).
+template <int MODE, int QF>
+__global__ __launch_bounds__(SK_MAXWAVES * 64) void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
+                                                                          int has_extra, int n_extra_y) {
+  constexpr int ROWS = MODE == GEMM_SWIGLU ? 16 : 32;   // output columns per block
+  const bool is_extra = has_extra && blockIdx.y + (unsigned)n_extra_y >= gridDim.y;
+  // (field by field: choosing between the two argument blocks as a whole puts both on the stack)
+#define SK_ARG(f) (is_extra ? extra.f : routed.f)
+  const int N = SK_ARG(N), K = SK_ARG(K), k_top = SK_ARG(k_top);
+  const long long lda = SK_ARG(lda), ldb = SK_ARG(ldb), ldo = SK_ARG(ldo);
+  const uint16_t *A = SK_ARG(A);
+  const int32_t *perm = SK_ARG(perm), *offsets = SK_ARG(offsets);
+  void *outp = SK_ARG(out);
+  const unsigned sel = blockIdx.y;
+  const unsigned bx = is_extra ? (blockIdx.y + (unsigned)n_extra_y - gridDim.y) * gridDim.x + blockIdx.x : blockIdx.x;
+  __shared__ float red[SK_MAXWAVES][8][64];
+  const int tid = threadIdx.x, lane = tid & 63, waves = blockDim.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: the slice bounds stay scalar
+  const int r = lane & 15, g = lane >> 4;
+
+  int grp = 0, row0 = SK_ARG(single_row0), cnt = SK_ARG(single_rows);
+  if (offsets) {
+    if (!is_extra && routed.sel_ids) {
+      grp = routed.sel_ids[sel];
+    } else {
+      unsigned long long m = SK_ARG(group_mask);
+      for (unsigned i = 0; i < sel; ++i) m &= m - 1;
+      if (m == 0) return;
+      grp = __ffsll((long long)m) - 1;
+    }
+    row0 = offsets[grp];
+    cnt = offsets[grp + 1] - row0;
+  }
+  if (cnt <= 0) return;
+  const int n0 = bx * ROWS;
+  if (n0 >= N) return;   // the whole block, before any barrier
+
+  const bool q = QF != 0 && !is_extra && ((routed.q8_mask >> grp) & 1ull);
+  const int kl = !q ? 16 : (QF == 1 ? 32 : 64);
+  // this wave's K slice: whole steps of 4 kl, shared out as evenly as they go
+  const int steps = K / (4 * kl);
+  const int k_begin = (int)((long long)steps * wave / waves) * (4 * kl);
+  const int k_len = (int)((long long)steps * (wave + 1) / waves) * (4 * kl) - k_begin;
+  const long long na = n0 + r;   // N % 16 == 0: both tiles are whole
+  const long long nb = MODE == GEMM_SWIGLU ? na : min(n0 + 16 + r, N - 1);
+  const int slot = is_extra ? extra.slot[grp] : routed.slot[grp];
+  const char *wptr = SK_ARG(wbase) + (long long)slot * SK_ARG(wstride);
+  const char *qptr = routed.qbase + (long long)slot * routed.qstride;   // used with q only
+  const long long b0_off = SK_ARG(b0_off);
+  const long long b_off = MODE == GEMM_SWIGLU ? SK_ARG(b1_off) : b0_off;
+  const long long qb_off = MODE == GEMM_SWIGLU ? routed.q_b1_off : routed.q_b0_off;
+  const long long qs_off = MODE == GEMM_SWIGLU ? routed.q_s1_off : routed.q_s0_off;
+  const long long ka = na * ldb + k_begin + g * kl, kb = nb * ldb + k_begin + g * kl;   // first element
+  const char *rowa, *rowb;
+  const uint8_t *sca = nullptr, *scb = nullptr;
+  float sa = 0.0f, sb = 0.0f;
+  if (!q) {
+    rowa = wptr + b0_off + ka * 2;
+    rowb = wptr + b_off + kb * 2;
+  } else if (QF == 1) {
+    rowa = qptr + routed.q_b0_off + ka;
+    rowb = qptr + qb_off + kb;
+    sa = reinterpret_cast<const float *>(qptr + routed.q_s0_off)[na];
+    sb = reinterpret_cast<const float *>(qptr + qs_off)[nb];
+  } else {
+    rowa = qptr + routed.q_b0_off + (ka >> 1);
+    rowb = qptr + qb_off + (kb >> 1);
+    sca = reinterpret_cast<const uint8_t *>(qptr + routed.q_s0_off) + (ka >> 5);
+    scb = reinterpret_cast<const uint8_t *>(qptr + qs_off) + (kb >> 5);
+  }
+
+  for (int tok0 = 0; tok0 < cnt; tok0 += SK_TOK) {
+    const int ntok = min(SK_TOK, cnt - tok0);
+    // lanes past the last token read the last token's vector again; their sums are not stored
+    const int p = row0 + tok0 + min(r, ntok - 1);
+    const long long srow = perm ? (long long)(perm[p] / k_top) : (long long)p;
+    const char *xl = reinterpret_cast<const char *>(A + srow * lda + k_begin + g * kl);
+    f32x4 acc_a = {0.0f, 0.0f, 0.0f, 0.0f}, acc_b = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (k_len <= 0) {}   // more waves than steps: nothing to add
+    else if (!q) skinny_segment<0>(rowa, rowb, sca, scb, sa, sb, xl, k_len, acc_a, acc_b);
+    else if (QF == 1) skinny_segment<1>(rowa, rowb, sca, scb, sa, sb, xl, k_len, acc_a, acc_b);
+    else skinny_segment<2>(rowa, rowb, sca, scb, sa, sb, xl, k_len, acc_a, acc_b);
+    if (tok0) __syncthreads();   // the previous pass's partial sums are consumed
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      red[wave][i][lane] = acc_a[i];
+      red[wave][4 + i][lane] = acc_b[i];
+    }
+    __syncthreads();
+    // wave 0: the slices' sums in wave order; lane: token r, output columns 4 g .. 4 g + 3 of each tile
+    if (wave == 0 && r < ntok) {
+      float sum[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        sum[i] = red[0][i][lane];
+        for (int w = 1; w < waves; ++w) sum[i] += red[w][i][lane];
+      }
+      const long long orow = (long long)(row0 + tok0 + r) * ldo;
+      const int ca = n0 + 4 * g;
+      if (MODE == GEMM_SWIGLU) {
+        uint2 o;
+        o.x = pack_bf16x2(silu(sum[0]) * sum[4], silu(sum[1]) * sum[5]);
+        o.y = pack_bf16x2(silu(sum[2]) * sum[6], silu(sum[3]) * sum[7]);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(outp) + orow + ca) = o;
+      } else {
+        float *y = reinterpret_cast<float *>(outp) + orow;
+        *reinterpret_cast<float4 *>(y + ca) = float4{sum[0], sum[1], sum[2], sum[3]};
+        if (ca + 16 < N) *reinterpret_cast<float4 *>(y + ca + 16) = float4{sum[4], sum[5], sum[6], sum[7]};
+      }
+    }
+  }
+#undef SK_ARG
+}
+
 }  // namespace
 
 static int g_gemv_rows = 0;   // tuning hook: rows per wave (0 = by shape)
 void set_gemv_rows(int rows) { g_gemv_rows = rows; }
+static int g_skinny_min_tok = 3;   // tuning hook: tokens per expert from which the matrix-core kernel is used
+static int g_skinny_forced = 0;    // test hook: the matrix-core kernel wherever the shapes allow it
+static int g_skinny_waves = 0;     // tuning hook: K slices (waves) per block, 0 = by shape
+void set_gemv_skinny_min(int tokens) {
+  g_skinny_min_tok = tokens > 0 ? tokens : 3;
+  g_skinny_forced = tokens == 1;   // 1: every launch with a token or more, whatever the format
+}
+void set_gemv_skinny_waves(int waves) { g_skinny_waves = waves >= 1 && waves <= SK_MAXWAVES ? waves : 0; }
 static int g_gemv_q8_always = 0;   // test hook: 8-bit copies are used whatever the experts' size
 void set_gemv_q8_always(int on) { g_gemv_q8_always = on; }
 
@@ -536,6 +776,47 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     if (extra->K > max_k) max_k = extra->K;
   }
   const bool use_q8 = args.q8_mask != 0 && gemv_reads_copies(args);
+  {
+    // several tokens per expert: the matrix-core kernel, where the shapes allow its steps
+    const int kmul = !use_q8 ? 64 : (args.qfmt == 2 ? 256 : 128);
+    const bool shapes_ok = args.N % 16 == 0 && args.K % kmul == 0 && (!extra || (extra->N % 16 == 0 && extra->K % 64 == 0));
+    // Where it pays (measured, Mixtral- and Qwen-shaped experts): quantised rows from 3 tokens (the
+    // per-token kernels are bound by their dot products there), e4m3 down projections from 5; bf16
+    // rows only in down projections with long rows, or past the per-token kernels' 8 tokens.
+    bool pays;
+    if (use_q8) pays = !(args.qfmt == 1 && mode == GEMM_PLAIN_F32 && max_tok < 5);
+    else pays = max_tok > GV_MAXTOK || (mode == GEMM_PLAIN_F32 && args.K >= 4096);
+    if (g_skinny_forced) pays = true;
+    if (max_tok >= g_skinny_min_tok && shapes_ok && pays) {
+      const int rows_per_block = mode == GEMM_SWIGLU ? 16 : 32;
+      const int bpg = (args.N + rows_per_block - 1) / rows_per_block;
+      const int extra_blocks = extra ? (extra->N + rows_per_block - 1) / rows_per_block : 0;
+      const int n_extra_y = (extra_blocks + bpg - 1) / bpg;
+      const dim3 grid(bpg, n_groups_in_mask + n_extra_y);
+      const int has_extra = extra ? 1 : 0;
+      const GemmArgs &extra_args = extra ? *extra : args;
+      const int qf = use_q8 ? args.qfmt : 0;
+      // K slices (waves) per block: at least 8 steps each, 4 at most
+      const int steps = args.K / (use_q8 ? (args.qfmt == 2 ? 256 : 128) : 64);
+      int slices = steps / 8 < 1 ? 1 : (steps / 8 > 4 ? 4 : steps / 8);
+      if (g_skinny_waves > 0) slices = g_skinny_waves;
+      const int threads = 64 * slices;
+#define MOE_SKINNY_LAUNCH(MODE, Q)                                                                         \
+  hipLaunchKernelGGL((grouped_skinny_kernel<MODE, Q>), grid, dim3(threads), 0, stream, args, extra_args, \
+                     has_extra, n_extra_y)
+      if (mode == GEMM_SWIGLU) {
+        if (qf == 2) MOE_SKINNY_LAUNCH(GEMM_SWIGLU, 2);
+        else if (qf == 1) MOE_SKINNY_LAUNCH(GEMM_SWIGLU, 1);
+        else MOE_SKINNY_LAUNCH(GEMM_SWIGLU, 0);
+      } else {
+        if (qf == 2) MOE_SKINNY_LAUNCH(GEMM_PLAIN_F32, 2);
+        else if (qf == 1) MOE_SKINNY_LAUNCH(GEMM_PLAIN_F32, 1);
+        else MOE_SKINNY_LAUNCH(GEMM_PLAIN_F32, 0);
+      }
+#undef MOE_SKINNY_LAUNCH
+      return hipGetLastError();
+    }
+  }
   const int ntcap = max_tok < GV_MAXTOK ? max_tok : GV_MAXTOK;
   int kseg = (65536 / (ntcap * 2)) / 512 * 512;   // token vectors of one K segment fit 64 KB of LDS
   if (kseg >= max_k) kseg = max_k;

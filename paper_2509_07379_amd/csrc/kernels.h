@@ -116,7 +116,9 @@ hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, 
 // Whether launch_grouped_gemv streams quantised copies for the experts of args.q8_mask (format,
 // alignment, expert size or the test hook), whatever the mask and the token count.
 bool gemv_reads_copies(const GemmArgs &args);
-void set_gemv_q8_always(int on);   // test hook: use the 8-bit copies whatever the experts' size
+void set_gemv_q8_always(int on);
+void set_gemv_skinny_min(int tokens);   // 0 = default
+void set_gemv_skinny_waves(int waves);  // 0 = default   // test hook: use the 8-bit copies whatever the experts' size
 void set_gemv_rows(int rows);   // tuning hook: weight rows per wave (0 = choose by shape)
 
 // ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----

@@ -31,7 +31,7 @@ def _default_hooks():
     yield
     from paper_2509_07379_amd import binding
     if torch.cuda.is_available():
-        for mode in range(7):
+        for mode in range(10):
             binding.moe_set_gemm_variant(mode, 1 if mode == 5 else 0)
 
 
@@ -530,6 +530,43 @@ def test_mxfp4_decode_streams_the_4bit_copies(gpu, oracle, d, I, I_shared, T):
     sim.prefetch([5, 4])
     sim.serve(np.nonzero(ref["counts"])[0])
     assert r2["stats"] == {**sim.counters(), "layer_calls": 1}
+
+
+@pytest.mark.parametrize("fmt", [0, 1, 3])
+@pytest.mark.parametrize("d,I,I_shared,T", [(256, 512, 0, 6), (512, 256, 256, 9), (256, 768, 64, 20), (2304, 256, 0, 40)])
+def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I_shared, T):
+    """Decode groups of three tokens and more take the mat-vec kernel that forms the sums with 16x16x32
+    MFMAs (16 weight rows by up to 16 tokens per instruction): bf16 slots, e4m3 and MXFP4 copies
+    (slots overwritten with NaN patterns, so a correct output proves where the weights came from),
+    shared experts in the same launch, K cut into several LDS segments (d = 2304 at 16 tokens per
+    pass), groups of more than 16 tokens in several passes (the mat-vec limit is raised so that the
+    GEMM kernels do not take them), and the same layer through the per-token kernels for comparison."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("skinny", d=d, I=I, E=5, k=2, T=T, I_shared=I_shared, seed=70 + T + fmt, zipf_s=0.8)
+    x = S.activations(w)
+    bias = S.zipf_route_bias(w, 0)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
+    pool = H.HostPool(w, 0, fmt=fmt)
+    lay = H.DeviceLayer(ctx, w, 0, pool, None if fmt else list(range(w.E)), poison=bool(fmt))
+    buf = H.Buffers(ctx, T)
+    if fmt:
+        ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
+        torch.cuda.synchronize()
+        lay.slots.fill_(0x7FC0)
+        torch.cuda.synchronize()
+    ref = oracle_layer(oracle, w, x, lay.router_np, pool, bias=bias, shared=lay.shared_np)
+    assert ref["counts"].max() >= 3 and (T < 20 or ref["counts"].max() > 16)
+    outs = {}
+    for name, min_tok in (("mfma", 1), ("per-token", 1 << 20)):    # 1: wherever the shapes allow it
+        B.moe_set_gemm_variant(6, 2 if fmt else 0)    # small experts: force the quantised source
+        B.moe_set_gemm_variant(8, min_tok)
+        B.moe_set_gemm_variant(9, 64)
+        ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"], H.np_to_dev(bias), 0)
+        gpu["compute"].synchronize()
+        np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["perm"], ref["perm"])
+        outs[name] = H.dev_to_np_u16(buf.y)
+        check_out(outs[name], ref["out_f64"], f"{name} fmt={fmt} T={T}")
+    ctx.close()
 
 
 @pytest.mark.parametrize("fmt", [1, 3])
