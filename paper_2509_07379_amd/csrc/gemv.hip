@@ -582,7 +582,8 @@ __device__ __forceinline__ void skinny_segment(const char *__restrict__ pa, cons
 // grouped_gemv_kernel).  blockDim.x / 64 <= SK_MAXWAVES waves = K slices.
 // Requires N % 16 == 0 and K % 64 == 0 (bf16), 128 (e4m3), 256 (MXFP4).
 template <int MODE, int QF>
-__global__ __launch_bounds__(SK_MAXWAVES * 64) void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
+__global__ __launch_bounds__(SK_MAXWAVES * 64) __attribute__((amdgpu_waves_per_eu(QF == 2 ? 3 : 4)))
+void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
                                                                           int has_extra, int n_extra_y) {
   constexpr int ROWS = MODE == GEMM_SWIGLU ? 16 : 32;   // output columns per block
   const bool is_extra = has_extra && blockIdx.y + (unsigned)n_extra_y >= gridDim.y;
