@@ -181,6 +181,31 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, 
                 timed=timed)
 
 
+def decode_batch_us(torch, H, S, ctx, wl, n_layers, batch, compute, copy, steps=8):
+    """Per-layer latency of the same resident layers at a decode batch of `batch` tokens (the paper's
+    batching study, Section VI): one warm-up pass over the trace (every launch variant loaded), one timed."""
+    from dataclasses import replace
+    import numpy as np
+    wb = replace(wl, T=batch, steps=steps)
+    trace = S.markov_trace(wb)
+    buf = H.Buffers(ctx, batch)
+    xs = [H.np_to_dev(S.activations(wb, l, 0)) for l in range(n_layers)]
+    biases = [[H.np_to_dev(S.trace_route_bias(trace[s, l], wb.E)) for l in range(n_layers)] for s in range(steps)]
+
+    def one_pass():
+        for s in range(steps):
+            for l in range(n_layers):
+                ctx.moe_decode_layer(l, xs[l], batch, buf.y, buf.ws, compute, copy, biases[s][l], wb.E)
+        torch.cuda.synchronize()
+
+    one_pass()
+    t0 = time.perf_counter()
+    one_pass()
+    us = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
+    distinct = float(np.mean([len(set(trace[s, l].ravel().tolist())) for s in range(steps) for l in range(n_layers)]))
+    return {"us_per_layer": us, "distinct_experts_per_layer": distinct}
+
+
 def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred):
     """Decode: per-layer latency with the predictor-guided cache (S slots per layer) and with all
     experts resident (hit path only); expert-GEMV HBM GB/s from HIP events."""
@@ -238,6 +263,8 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
         g2 = kt["gemv2"][0] / max(1, kt["gemv2"][1])
         out[label] = dict(us_per_layer=us_layer, stats=st, gemv1_ms=g1, gemv2_ms=g2,
                           launches=(kt["gemv1"][1], kt["gemv2"][1]))
+        if label == "resident":
+            out[label]["batch8"] = decode_batch_us(torch, H, S, ctx, wl, n_layers, 8, compute, copy)
         ctx.close()
         del layers, cache
     return out
@@ -279,12 +306,15 @@ def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy, 
         one_step(s)
     torch.cuda.synchronize()
     kt = ctx.moe_get_kernel_times()
+    ctx.moe_set_profiling(False)
+    batch8 = decode_batch_us(torch, H, S, ctx, wl, n_layers, 8, compute, copy)
     ctx.close()
     g = kt["gemv1"][0] / max(1, kt["gemv1"][1]) + kt["gemv2"][0] / max(1, kt["gemv2"][1])
     code_bytes = wl.k * pools[0].bytes_per_expert
     out = {"us_per_layer": us_layer, "gemv_us_per_layer": g * 1e3, "layers": n_layers,
            "gemv_HBM_GBps": code_bytes / (g * 1e-3) / 1e9 if g else 0.0,
-           "gemv_frac_of_hbm_peak": code_bytes / (g * 1e-3) / 1e9 / PEAK_HBM_GBS if g else 0.0}
+           "gemv_frac_of_hbm_peak": code_bytes / (g * 1e-3) / 1e9 / PEAK_HBM_GBS if g else 0.0,
+           "batch8": batch8}
     del layers
 
     # the paper's decode flow on the same 8-bit pools: one cache of k slots for all layers, first layer
@@ -482,6 +512,7 @@ def main():
             "gemv_HBM_GBps": bytes_layer / (gemv_ms * 1e-3) / 1e9 if gemv_ms else 0.0,
             "gemv_frac_of_hbm_peak": bytes_layer / (gemv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if gemv_ms else 0.0,
             "layer_HBM_GBps": bytes_layer / (r["us_per_layer"] * 1e-6) / 1e9,
+            "resident_batch8": r["batch8"],
             "cached_us_per_layer": dec["cached"]["us_per_layer"], "cached_slots": wd.S,
             "cached_stats": dec["cached"]["stats"],
             # the paper's cache: one set of k slots for all layers, predictor top-k, first layer on demand
