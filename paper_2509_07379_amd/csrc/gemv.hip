@@ -829,7 +829,12 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   // quantised rows are short (K or K / 2 bytes): with several tokens 16 waves share one staged copy of
   // the token vectors (4 tokens, Mixtral shape: MXFP4 241 -> 201 us per layer, e4m3 255 -> 234 us; one
   // token is as fast with 4 waves)
-  const int threads = (ntcap > 4 || (use_q8 && ntcap > 1)) ? 1024 : 256;
+  // bf16 rows with 3 or 4 tokens: a 4-wave block stages as many bytes of token vectors as half its
+  // share of the weights; with large experts 16 waves per staged copy win (Mixtral shape, 8 tokens in
+  // groups of at most 4: gate/up 315 -> 276 us), with small ones the finer blocks do (Qwen shape,
+  // 8 tokens: 130 against 143 us per layer)
+  const bool big_rows = (long long)args.N * args.K >= (1ll << 24);
+  const int threads = (ntcap > 4 || (ntcap > 2 && big_rows) || (use_q8 && ntcap > 1)) ? 1024 : 256;
   const int rows_per_block = (threads / 64) * rows_per_wave;
   const int bpg = (args.N + rows_per_block - 1) / rows_per_block;
   const int extra_blocks = extra ? (extra->N + rows_per_block - 1) / rows_per_block : 0;
@@ -851,7 +856,13 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   } while (0)
 #define MOE_GEMV_LAUNCH_Q(MODE, NTMAX, R, Q)                                                  \
   do {                                                                                        \
-    auto kern = grouped_gemv_kernel<MODE, NTMAX, R, ((NTMAX > 4 || (Q != 0 && NTMAX > 1)) ? 1024 : 256), Q>; \
+    /* 3 or 4 tokens on bf16 rows exist with 4 and with 16 waves; every other case with one of them */ \
+    if (threads == 1024) MOE_GEMV_LAUNCH_T(MODE, NTMAX, R, Q, ((NTMAX > 2 || (Q != 0 && NTMAX > 1)) ? 1024 : 256)); \
+    else MOE_GEMV_LAUNCH_T(MODE, NTMAX, R, Q, ((NTMAX > 4 || (Q != 0 && NTMAX > 1)) ? 1024 : 256)); \
+  } while (0)
+#define MOE_GEMV_LAUNCH_T(MODE, NTMAX, R, Q, NTHR)                                            \
+  do {                                                                                        \
+    auto kern = grouped_gemv_kernel<MODE, NTMAX, R, NTHR, Q>;                                  \
     static bool attr_set = false;                                                             \
     if (!attr_set) {                                                                          \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                \
@@ -876,6 +887,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
 #undef MOE_GEMV_LAUNCH
 #undef MOE_GEMV_LAUNCH_R
 #undef MOE_GEMV_LAUNCH_Q
+#undef MOE_GEMV_LAUNCH_T
   return hipGetLastError();
 }
 
