@@ -5,10 +5,14 @@
 //   GEMM_SWIGLU     h[p, n] = bf16( silu(x_p . Wg[n]) * (x_p . Wu[n]) )
 //   GEMM_PLAIN_F32  y[p, c] = h_p . Wd[c]
 //
-// One wave owns R consecutive weight rows: each lane streams 16-byte pieces of those rows
-// (R or 2R independent loads in flight per step), multiplies them with the group's token
-// vectors held in LDS, and the 64 partial sums are reduced with a butterfly at the end.
-// Up to 8 tokens share one pass over the weights; the token count selects the unrolling.
+// Per-token kernels (grouped_gemv_kernel, fused_down_combine_kernel): one wave owns R consecutive
+// weight rows, each lane streams 16-byte pieces of those rows (R or 2R independent loads in flight
+// per step), multiplies them with the group's token vectors held in LDS, and the 64 partial sums
+// are reduced with a butterfly at the end.  Up to 8 tokens share one pass over the weights; the
+// token count selects the unrolling.
+// Matrix-core kernel (grouped_skinny_kernel): the same single pass for up to 16 tokens per expert
+// with 16x16x32 MFMAs; it takes over where the per-token kernels are bound by their arithmetic
+// (several tokens on quantised rows, long bf16 down rows, more than 8 tokens).
 #include "device_utils.h"
 #include "kernels.h"
 
