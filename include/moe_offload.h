@@ -306,7 +306,8 @@ int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M
  * mode 7 with variant 1 makes a one-token decode call with every expert resident run the down
  * mat-vec and the weighted sum as two launches instead of one (the same bits either way);
  * mode 8 sets the token count per expert from which a mat-vec launch may use the matrix-core
- * kernel (0 = default 3, where measurement says it pays; 1 = wherever the shapes allow it; a
+ * kernel (0 = default: 3, or 2 for quantised gate/up rows, and only where measurement says it
+ * pays; 1 = wherever the shapes allow it; a
  * large value = never); mode 9 the largest group a decode call still gives to the mat-vec
  * launches (0 = default: 16, or 32 on quantised copies); mode 10 the K slices (waves) per block
  * of the matrix-core mat-vec (0 = by shape, 1..8).

@@ -703,11 +703,11 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
 
 static int g_gemv_rows = 0;   // tuning hook: rows per wave (0 = by shape)
 void set_gemv_rows(int rows) { g_gemv_rows = rows; }
-static int g_skinny_min_tok = 3;   // tuning hook: tokens per expert from which the matrix-core kernel is used
+static int g_skinny_min_tok = 0;   // tuning hook: tokens per expert from which the matrix-core kernel is used, 0 = by rule
 static int g_skinny_forced = 0;    // test hook: the matrix-core kernel wherever the shapes allow it
 static int g_skinny_waves = 0;     // tuning hook: K slices (waves) per block, 0 = by shape
 void set_gemv_skinny_min(int tokens) {
-  g_skinny_min_tok = tokens > 0 ? tokens : 3;
+  g_skinny_min_tok = tokens > 0 ? tokens : 0;
   g_skinny_forced = tokens == 1;   // 1: every launch with a token or more, whatever the format
 }
 void set_gemv_skinny_waves(int waves) { g_skinny_waves = waves >= 1 && waves <= SK_MAXWAVES ? waves : 0; }
@@ -785,14 +785,17 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     // several tokens per expert: the matrix-core kernel, where the shapes allow its steps
     const int kmul = !use_q8 ? 64 : (args.qfmt == 2 ? 256 : 128);
     const bool shapes_ok = args.N % 16 == 0 && args.K % kmul == 0 && (!extra || (extra->N % 16 == 0 && extra->K % 64 == 0));
-    // Where it pays (measured, Mixtral- and Qwen-shaped experts): quantised rows from 3 tokens (the
-    // per-token kernels are bound by their dot products there), e4m3 down projections from 5; bf16
+    // Where it pays (measured, Mixtral- and Qwen-shaped experts): quantised rows (the per-token
+    // kernels are bound by their dot products there), e4m3 down projections from 5 tokens; bf16
     // rows only in down projections with long rows, or past the per-token kernels' 8 tokens.
     bool pays;
     if (use_q8) pays = !(args.qfmt == 1 && mode == GEMM_PLAIN_F32 && max_tok < 5);
     else pays = max_tok > GV_MAXTOK || (mode == GEMM_PLAIN_F32 && args.K >= 4096);
     if (g_skinny_forced) pays = true;
-    if (max_tok >= g_skinny_min_tok && shapes_ok && pays) {
+    // from 3 tokens per expert; quantised gate/up rows from 2 (MXFP4, Mixtral shape, 2 tokens: 57
+    // against 70 us per launch; one token is faster per token: 37 against 41 us)
+    const int min_tok = g_skinny_min_tok > 0 ? g_skinny_min_tok : ((use_q8 && mode == GEMM_SWIGLU) ? 2 : 3);
+    if (max_tok >= min_tok && shapes_ok && pays) {
       const int rows_per_block = mode == GEMM_SWIGLU ? 16 : 32;
       const int bpg = (args.N + rows_per_block - 1) / rows_per_block;
       const int extra_blocks = extra ? (extra->N + rows_per_block - 1) / rows_per_block : 0;
