@@ -489,73 +489,92 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4 &w, const u32x4 &x, const f3
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc, 0, 0, 0);
 }
 
-// One K slice of one row tile pair.  F: format of the rows (0 bf16, 1 e4m3 + row scale, 2 MXFP4).
-// pa / pb: this lane's row in the two tiles at the slice's first k, already advanced to the lane
-// group's share; xl: this lane's token vector, likewise; sca / scb: MXFP4 scale bytes, likewise.
-template <int F>
-__device__ __forceinline__ void skinny_segment(const char *__restrict__ pa, const char *__restrict__ pb,
-                                               const uint8_t *__restrict__ sca, const uint8_t *__restrict__ scb,
-                                               float sa, float sb, const char *__restrict__ xl, int seg,
-                                               f32x4 &acc_a, f32x4 &acc_b) {
+// One K slice of NP row tile pairs.  F: format of the rows (0 bf16, 1 e4m3 + row scale, 2 MXFP4).
+// pa / pb: this lane's row in the two tiles of each pair at the slice's first k, already advanced to
+// the lane group's share; xl: this lane's token vector, likewise; sca / scb: MXFP4 scale bytes,
+// likewise.  The token pieces of a step are loaded once and used for all 2 NP tiles: with quantised
+// rows they are 2 (e4m3) or 4 (MXFP4) times the bytes of a tile's codes, and with one pair per wave
+// those launches were bound by the token reads from L2, not by HBM.
+template <int NP>
+struct SkTiles {
+  const char *pa[NP], *pb[NP];
+  const uint8_t *sca[NP], *scb[NP];
+  float sa[NP], sb[NP];
+  f32x4 acc_a[NP], acc_b[NP];
+};
+
+template <int F, int NP>
+__device__ __forceinline__ void skinny_segment(SkTiles<NP> &T, const char *__restrict__ xl, int seg) {
   constexpr int KL = F == 0 ? 16 : (F == 1 ? 32 : 64);   // k per lane and step: 32 bytes of the row
   constexpr int STEP = 4 * KL;                           // k per wave and step
   constexpr int NX = KL / 8;                             // 16-byte pieces of the token vector per step
-  constexpr int D = F == 0 ? 3 : 2;                      // steps whose loads are in flight or in use
+  constexpr int D = (F == 0 && NP == 1) ? 3 : 2;         // steps whose loads are in flight or in use
   // The registers of a step.  The loads of step s + D - 1 are issued before the products of step s
   // are taken, each into its own registers: left to itself the compiler reuses one set and waits
   // for every load of a turn before it issues the next turn's.
   struct Regs {
-    u32x4 a0, a1, b0, b1, x[NX];
-    uint32_t sc;   // MXFP4: the four scale bytes of the step (tile a: bytes 0, 1; tile b: bytes 2, 3)
+    u32x4 a0[NP], a1[NP], b0[NP], b1[NP], x[NX];
+    uint32_t sc[NP];   // MXFP4: the four scale bytes of the step (tile a: bytes 0, 1; tile b: bytes 2, 3)
   };
   auto load = [&](int ks, Regs &R) {
     const u32x4 *x = reinterpret_cast<const u32x4 *>(xl + ks * 2);   // first: they arrive first
 #pragma unroll
     for (int i = 0; i < NX; ++i) R.x[i] = x[i];
-    const u32x4 *wa = reinterpret_cast<const u32x4 *>(pa + (F == 0 ? ks * 2 : (F == 1 ? ks : ks >> 1)));
-    const u32x4 *wb = reinterpret_cast<const u32x4 *>(pb + (F == 0 ? ks * 2 : (F == 1 ? ks : ks >> 1)));
-    R.a0 = __builtin_nontemporal_load(wa);
-    R.a1 = __builtin_nontemporal_load(wa + 1);
-    R.b0 = __builtin_nontemporal_load(wb);
-    R.b1 = __builtin_nontemporal_load(wb + 1);
-    if (F == 2) {
-      const int blk = ks >> 5;   // two scale blocks of 32 codes per lane, row tile and step
-      R.sc = (uint32_t)sca[blk] | ((uint32_t)sca[blk + 1] << 8) | ((uint32_t)scb[blk] << 16) | ((uint32_t)scb[blk + 1] << 24);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const u32x4 *wa = reinterpret_cast<const u32x4 *>(T.pa[p] + (F == 0 ? ks * 2 : (F == 1 ? ks : ks >> 1)));
+      const u32x4 *wb = reinterpret_cast<const u32x4 *>(T.pb[p] + (F == 0 ? ks * 2 : (F == 1 ? ks : ks >> 1)));
+      R.a0[p] = __builtin_nontemporal_load(wa);
+      R.a1[p] = __builtin_nontemporal_load(wa + 1);
+      R.b0[p] = __builtin_nontemporal_load(wb);
+      R.b1[p] = __builtin_nontemporal_load(wb + 1);
+      if (F == 2) {
+        const int blk = ks >> 5;   // two scale blocks of 32 codes per lane, row tile and step
+        R.sc[p] = (uint32_t)T.sca[p][blk] | ((uint32_t)T.sca[p][blk + 1] << 8) | ((uint32_t)T.scb[p][blk] << 16) |
+                  ((uint32_t)T.scb[p][blk + 1] << 24);
+      }
     }
   };
   auto compute = [&](const Regs &R) {
-    if (F == 0) {
-      acc_a = mfma16(R.a0, R.x[0], acc_a);
-      acc_b = mfma16(R.b0, R.x[0], acc_b);
-      acc_a = mfma16(R.a1, R.x[1], acc_a);
-      acc_b = mfma16(R.b1, R.x[1], acc_b);
-    } else if (F == 1) {
-      u32x4 lo, hi;
-      expand16(R.a0, sa, lo, hi);
-      acc_a = mfma16(lo, R.x[0], acc_a);
-      acc_a = mfma16(hi, R.x[1], acc_a);
-      expand16(R.b0, sb, lo, hi);
-      acc_b = mfma16(lo, R.x[0], acc_b);
-      acc_b = mfma16(hi, R.x[1], acc_b);
-      expand16(R.a1, sa, lo, hi);
-      acc_a = mfma16(lo, R.x[2], acc_a);
-      acc_a = mfma16(hi, R.x[3], acc_a);
-      expand16(R.b1, sb, lo, hi);
-      acc_b = mfma16(lo, R.x[2], acc_b);
-      acc_b = mfma16(hi, R.x[3], acc_b);
-    } else {
-      const float fa0 = __uint_as_float((R.sc & 0xffu) << 23), fa1 = __uint_as_float(((R.sc >> 8) & 0xffu) << 23);
-      const float fb0 = __uint_as_float(((R.sc >> 16) & 0xffu) << 23), fb1 = __uint_as_float((R.sc >> 24) << 23);
-      const uint32_t a00 = R.a0.x, a01 = R.a0.y, a02 = R.a0.z, a03 = R.a0.w, a10 = R.a1.x, a11 = R.a1.y, a12 = R.a1.z, a13 = R.a1.w;
-      const uint32_t b00 = R.b0.x, b01 = R.b0.y, b02 = R.b0.z, b03 = R.b0.w, b10 = R.b1.x, b11 = R.b1.y, b12 = R.b1.z, b13 = R.b1.w;
-      acc_a = mfma16(mx4_expand8(a00, fa0), R.x[0], acc_a); acc_b = mfma16(mx4_expand8(b00, fb0), R.x[0], acc_b);
-      acc_a = mfma16(mx4_expand8(a01, fa0), R.x[1], acc_a); acc_b = mfma16(mx4_expand8(b01, fb0), R.x[1], acc_b);
-      acc_a = mfma16(mx4_expand8(a02, fa0), R.x[2], acc_a); acc_b = mfma16(mx4_expand8(b02, fb0), R.x[2], acc_b);
-      acc_a = mfma16(mx4_expand8(a03, fa0), R.x[3], acc_a); acc_b = mfma16(mx4_expand8(b03, fb0), R.x[3], acc_b);
-      acc_a = mfma16(mx4_expand8(a10, fa1), R.x[4], acc_a); acc_b = mfma16(mx4_expand8(b10, fb1), R.x[4], acc_b);
-      acc_a = mfma16(mx4_expand8(a11, fa1), R.x[5], acc_a); acc_b = mfma16(mx4_expand8(b11, fb1), R.x[5], acc_b);
-      acc_a = mfma16(mx4_expand8(a12, fa1), R.x[6], acc_a); acc_b = mfma16(mx4_expand8(b12, fb1), R.x[6], acc_b);
-      acc_a = mfma16(mx4_expand8(a13, fa1), R.x[7], acc_a); acc_b = mfma16(mx4_expand8(b13, fb1), R.x[7], acc_b);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      f32x4 &acc_a = T.acc_a[p], &acc_b = T.acc_b[p];
+      if (F == 0) {
+        acc_a = mfma16(R.a0[p], R.x[0], acc_a);
+        acc_b = mfma16(R.b0[p], R.x[0], acc_b);
+        acc_a = mfma16(R.a1[p], R.x[1], acc_a);
+        acc_b = mfma16(R.b1[p], R.x[1], acc_b);
+      } else if (F == 1) {
+        const float sa = T.sa[p], sb = T.sb[p];
+        u32x4 lo, hi;
+        expand16(R.a0[p], sa, lo, hi);
+        acc_a = mfma16(lo, R.x[0], acc_a);
+        acc_a = mfma16(hi, R.x[1], acc_a);
+        expand16(R.b0[p], sb, lo, hi);
+        acc_b = mfma16(lo, R.x[0], acc_b);
+        acc_b = mfma16(hi, R.x[1], acc_b);
+        expand16(R.a1[p], sa, lo, hi);
+        acc_a = mfma16(lo, R.x[2], acc_a);
+        acc_a = mfma16(hi, R.x[3], acc_a);
+        expand16(R.b1[p], sb, lo, hi);
+        acc_b = mfma16(lo, R.x[2], acc_b);
+        acc_b = mfma16(hi, R.x[3], acc_b);
+      } else {
+        const uint32_t sc = R.sc[p];
+        const float fa0 = __uint_as_float((sc & 0xffu) << 23), fa1 = __uint_as_float(((sc >> 8) & 0xffu) << 23);
+        const float fb0 = __uint_as_float(((sc >> 16) & 0xffu) << 23), fb1 = __uint_as_float((sc >> 24) << 23);
+        const u32x4 qa0 = R.a0[p], qa1 = R.a1[p], qb0 = R.b0[p], qb1 = R.b1[p];
+        const uint32_t a00 = qa0.x, a01 = qa0.y, a02 = qa0.z, a03 = qa0.w, a10 = qa1.x, a11 = qa1.y, a12 = qa1.z, a13 = qa1.w;
+        const uint32_t b00 = qb0.x, b01 = qb0.y, b02 = qb0.z, b03 = qb0.w, b10 = qb1.x, b11 = qb1.y, b12 = qb1.z, b13 = qb1.w;
+        acc_a = mfma16(mx4_expand8(a00, fa0), R.x[0], acc_a); acc_b = mfma16(mx4_expand8(b00, fb0), R.x[0], acc_b);
+        acc_a = mfma16(mx4_expand8(a01, fa0), R.x[1], acc_a); acc_b = mfma16(mx4_expand8(b01, fb0), R.x[1], acc_b);
+        acc_a = mfma16(mx4_expand8(a02, fa0), R.x[2], acc_a); acc_b = mfma16(mx4_expand8(b02, fb0), R.x[2], acc_b);
+        acc_a = mfma16(mx4_expand8(a03, fa0), R.x[3], acc_a); acc_b = mfma16(mx4_expand8(b03, fb0), R.x[3], acc_b);
+        acc_a = mfma16(mx4_expand8(a10, fa1), R.x[4], acc_a); acc_b = mfma16(mx4_expand8(b10, fb1), R.x[4], acc_b);
+        acc_a = mfma16(mx4_expand8(a11, fa1), R.x[5], acc_a); acc_b = mfma16(mx4_expand8(b11, fb1), R.x[5], acc_b);
+        acc_a = mfma16(mx4_expand8(a12, fa1), R.x[6], acc_a); acc_b = mfma16(mx4_expand8(b12, fb1), R.x[6], acc_b);
+        acc_a = mfma16(mx4_expand8(a13, fa1), R.x[7], acc_a); acc_b = mfma16(mx4_expand8(b13, fb1), R.x[7], acc_b);
+      }
     }
   };
   // n >= 1 steps.  Start-up and the turns of the main loop issue their loads unconditionally (the
@@ -582,14 +601,15 @@ __device__ __forceinline__ void skinny_segment(const char *__restrict__ pa, cons
   }
 }
 
-// Grid: x = row tile pair, y = selected group, the shared experts in further runs of y (as
+// Grid: x = NP row tile pairs, y = selected group, the shared experts in further runs of y (as
 // grouped_gemv_kernel).  blockDim.x / 64 <= SK_MAXWAVES waves = K slices.
 // Requires N % 16 == 0 and K % 64 == 0 (bf16), 128 (e4m3), 256 (MXFP4).
-template <int MODE, int QF>
-__global__ __launch_bounds__(SK_MAXWAVES * 64) __attribute__((amdgpu_waves_per_eu(QF == 2 ? 3 : 4)))
+template <int MODE, int QF, int NP>
+__global__ __launch_bounds__(SK_MAXWAVES * 64) __attribute__((amdgpu_waves_per_eu(QF == 2 ? 2 : (QF == 1 ? 3 : 4))))
 void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
                                                                           int has_extra, int n_extra_y) {
-  constexpr int ROWS = MODE == GEMM_SWIGLU ? 16 : 32;   // output columns per block
+  constexpr int PAIR = MODE == GEMM_SWIGLU ? 16 : 32;   // output columns per tile pair
+  constexpr int ROWS = NP * PAIR;                       // output columns per block
   const bool is_extra = has_extra && blockIdx.y + (unsigned)n_extra_y >= gridDim.y;
   // (field by field: choosing between the two argument blocks as a whole puts both on the stack)
 #define SK_ARG(f) (is_extra ? extra.f : routed.f)
@@ -600,7 +620,7 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
   void *outp = SK_ARG(out);
   const unsigned sel = blockIdx.y;
   const unsigned bx = is_extra ? (blockIdx.y + (unsigned)n_extra_y - gridDim.y) * gridDim.x + blockIdx.x : blockIdx.x;
-  __shared__ float red[SK_MAXWAVES][8][64];
+  __shared__ float red[SK_MAXWAVES][8 * NP][64];
   const int tid = threadIdx.x, lane = tid & 63, waves = blockDim.x >> 6;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: the slice bounds stay scalar
   const int r = lane & 15, g = lane >> 4;
@@ -628,8 +648,6 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
   const int steps = K / (4 * kl);
   const int k_begin = (int)((long long)steps * wave / waves) * (4 * kl);
   const int k_len = (int)((long long)steps * (wave + 1) / waves) * (4 * kl) - k_begin;
-  const long long na = n0 + r;   // N % 16 == 0: both tiles are whole
-  const long long nb = MODE == GEMM_SWIGLU ? na : min(n0 + 16 + r, N - 1);
   const int slot = is_extra ? extra.slot[grp] : routed.slot[grp];
   const char *wptr = SK_ARG(wbase) + (long long)slot * SK_ARG(wstride);
   const char *qptr = routed.qbase + (long long)slot * routed.qstride;   // used with q only
@@ -637,23 +655,30 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
   const long long b_off = MODE == GEMM_SWIGLU ? SK_ARG(b1_off) : b0_off;
   const long long qb_off = MODE == GEMM_SWIGLU ? routed.q_b1_off : routed.q_b0_off;
   const long long qs_off = MODE == GEMM_SWIGLU ? routed.q_s1_off : routed.q_s0_off;
-  const long long ka = na * ldb + k_begin + g * kl, kb = nb * ldb + k_begin + g * kl;   // first element
-  const char *rowa, *rowb;
-  const uint8_t *sca = nullptr, *scb = nullptr;
-  float sa = 0.0f, sb = 0.0f;
-  if (!q) {
-    rowa = wptr + b0_off + ka * 2;
-    rowb = wptr + b_off + kb * 2;
-  } else if (QF == 1) {
-    rowa = qptr + routed.q_b0_off + ka;
-    rowb = qptr + qb_off + kb;
-    sa = reinterpret_cast<const float *>(qptr + routed.q_s0_off)[na];
-    sb = reinterpret_cast<const float *>(qptr + qs_off)[nb];
-  } else {
-    rowa = qptr + routed.q_b0_off + (ka >> 1);
-    rowb = qptr + qb_off + (kb >> 1);
-    sca = reinterpret_cast<const uint8_t *>(qptr + routed.q_s0_off) + (ka >> 5);
-    scb = reinterpret_cast<const uint8_t *>(qptr + qs_off) + (kb >> 5);
+  SkTiles<NP> T;
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    // rows of the pair's two tiles held by this lane (clamped: tiles past the last column compute a
+    // copy of the last row and store nothing)
+    const long long na = min(n0 + p * PAIR + r, N - 1);
+    const long long nb = MODE == GEMM_SWIGLU ? na : min(n0 + p * PAIR + 16 + r, N - 1);
+    const long long ka = na * ldb + k_begin + g * kl, kb = nb * ldb + k_begin + g * kl;   // first element
+    T.sca[p] = T.scb[p] = nullptr;
+    T.sa[p] = T.sb[p] = 0.0f;
+    if (!q) {
+      T.pa[p] = wptr + b0_off + ka * 2;
+      T.pb[p] = wptr + b_off + kb * 2;
+    } else if (QF == 1) {
+      T.pa[p] = qptr + routed.q_b0_off + ka;
+      T.pb[p] = qptr + qb_off + kb;
+      T.sa[p] = reinterpret_cast<const float *>(qptr + routed.q_s0_off)[na];
+      T.sb[p] = reinterpret_cast<const float *>(qptr + qs_off)[nb];
+    } else {
+      T.pa[p] = qptr + routed.q_b0_off + (ka >> 1);
+      T.pb[p] = qptr + qb_off + (kb >> 1);
+      T.sca[p] = reinterpret_cast<const uint8_t *>(qptr + routed.q_s0_off) + (ka >> 5);
+      T.scb[p] = reinterpret_cast<const uint8_t *>(qptr + qs_off) + (kb >> 5);
+    }
   }
 
   for (int tok0 = 0; tok0 < cnt; tok0 += SK_TOK) {
@@ -662,37 +687,45 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
     const int p = row0 + tok0 + min(r, ntok - 1);
     const long long srow = perm ? (long long)(perm[p] / k_top) : (long long)p;
     const char *xl = reinterpret_cast<const char *>(A + srow * lda + k_begin + g * kl);
-    f32x4 acc_a = {0.0f, 0.0f, 0.0f, 0.0f}, acc_b = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int p = 0; p < NP; ++p) T.acc_a[p] = T.acc_b[p] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     if (k_len <= 0) {}   // more waves than steps: nothing to add
-    else if (!q) skinny_segment<0>(rowa, rowb, sca, scb, sa, sb, xl, k_len, acc_a, acc_b);
-    else if (QF == 1) skinny_segment<1>(rowa, rowb, sca, scb, sa, sb, xl, k_len, acc_a, acc_b);
-    else skinny_segment<2>(rowa, rowb, sca, scb, sa, sb, xl, k_len, acc_a, acc_b);
+    else if (!q) skinny_segment<0, NP>(T, xl, k_len);
+    else if (QF == 1) skinny_segment<1, NP>(T, xl, k_len);
+    else skinny_segment<2, NP>(T, xl, k_len);
     if (tok0) __syncthreads();   // the previous pass's partial sums are consumed
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      red[wave][i][lane] = acc_a[i];
-      red[wave][4 + i][lane] = acc_b[i];
-    }
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        red[wave][8 * p + i][lane] = T.acc_a[p][i];
+        red[wave][8 * p + 4 + i][lane] = T.acc_b[p][i];
+      }
     __syncthreads();
     // wave 0: the slices' sums in wave order; lane: token r, output columns 4 g .. 4 g + 3 of each tile
     if (wave == 0 && r < ntok) {
-      float sum[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        sum[i] = red[0][i][lane];
-        for (int w = 1; w < waves; ++w) sum[i] += red[w][i][lane];
-      }
       const long long orow = (long long)(row0 + tok0 + r) * ldo;
-      const int ca = n0 + 4 * g;
-      if (MODE == GEMM_SWIGLU) {
-        uint2 o;
-        o.x = pack_bf16x2(silu(sum[0]) * sum[4], silu(sum[1]) * sum[5]);
-        o.y = pack_bf16x2(silu(sum[2]) * sum[6], silu(sum[3]) * sum[7]);
-        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(outp) + orow + ca) = o;
-      } else {
-        float *y = reinterpret_cast<float *>(outp) + orow;
-        *reinterpret_cast<float4 *>(y + ca) = float4{sum[0], sum[1], sum[2], sum[3]};
-        if (ca + 16 < N) *reinterpret_cast<float4 *>(y + ca + 16) = float4{sum[4], sum[5], sum[6], sum[7]};
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        float sum[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          sum[i] = red[0][8 * p + i][lane];
+          for (int w = 1; w < waves; ++w) sum[i] += red[w][8 * p + i][lane];
+        }
+        const int ca = n0 + p * PAIR + 4 * g;
+        if (MODE == GEMM_SWIGLU) {
+          if (ca < N) {
+            uint2 o;
+            o.x = pack_bf16x2(silu(sum[0]) * sum[4], silu(sum[1]) * sum[5]);
+            o.y = pack_bf16x2(silu(sum[2]) * sum[6], silu(sum[3]) * sum[7]);
+            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(outp) + orow + ca) = o;
+          }
+        } else {
+          float *y = reinterpret_cast<float *>(outp) + orow;
+          if (ca < N) *reinterpret_cast<float4 *>(y + ca) = float4{sum[0], sum[1], sum[2], sum[3]};
+          if (ca + 16 < N) *reinterpret_cast<float4 *>(y + ca + 16) = float4{sum[4], sum[5], sum[6], sum[7]};
+        }
       }
     }
   }
@@ -796,7 +829,11 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     // against 70 us per launch; one token is faster per token: 37 against 41 us)
     const int min_tok = g_skinny_min_tok > 0 ? g_skinny_min_tok : ((use_q8 && mode == GEMM_SWIGLU) ? 2 : 3);
     if (max_tok >= min_tok && shapes_ok && pays) {
-      const int rows_per_block = mode == GEMM_SWIGLU ? 16 : 32;
+      // row tile pairs per block: quantised rows share their token pieces between two pairs, except in
+      // down projections with few tokens, where the launch would be left with too few blocks
+      // (MXFP4, Mixtral shape, 4 tokens: 59 against 52 us; 32 tokens: 85 against 96 us)
+      const int pairs = use_q8 && (mode == GEMM_SWIGLU || max_tok > 8) ? 2 : 1;
+      const int rows_per_block = pairs * (mode == GEMM_SWIGLU ? 16 : 32);
       const int bpg = (args.N + rows_per_block - 1) / rows_per_block;
       const int extra_blocks = extra ? (extra->N + rows_per_block - 1) / rows_per_block : 0;
       const int n_extra_y = (extra_blocks + bpg - 1) / bpg;
@@ -810,8 +847,14 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
       if (g_skinny_waves > 0) slices = g_skinny_waves;
       const int threads = 64 * slices;
 #define MOE_SKINNY_LAUNCH(MODE, Q)                                                                         \
-  hipLaunchKernelGGL((grouped_skinny_kernel<MODE, Q>), grid, dim3(threads), 0, stream, args, extra_args, \
-                     has_extra, n_extra_y)
+  do {                                                                                                     \
+    if (pairs == 2)                                                                                        \
+      hipLaunchKernelGGL((grouped_skinny_kernel<MODE, Q, (Q != 0 ? 2 : 1)>), grid, dim3(threads), 0, stream, args, \
+                         extra_args, has_extra, n_extra_y);                                                \
+    else                                                                                                   \
+      hipLaunchKernelGGL((grouped_skinny_kernel<MODE, Q, 1>), grid, dim3(threads), 0, stream, args, extra_args, \
+                         has_extra, n_extra_y);                                                            \
+  } while (0)
       if (mode == GEMM_SWIGLU) {
         if (qf == 2) MOE_SKINNY_LAUNCH(GEMM_SWIGLU, 2);
         else if (qf == 1) MOE_SKINNY_LAUNCH(GEMM_SWIGLU, 1);
