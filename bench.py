@@ -181,7 +181,7 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, 
                 timed=timed)
 
 
-def decode_batch_us(torch, H, S, ctx, wl, n_layers, batch, compute, copy, steps=8):
+def decode_batch_us(torch, H, S, ctx, wl, n_layers, batch, compute, copy, bytes_per_expert, steps=8):
     """Per-layer latency of the same resident layers at a decode batch of `batch` tokens (the paper's
     batching study, Section VI): one warm-up pass over the trace (every launch variant loaded), one timed."""
     from dataclasses import replace
@@ -203,7 +203,9 @@ def decode_batch_us(torch, H, S, ctx, wl, n_layers, batch, compute, copy, steps=
     one_pass()
     us = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
     distinct = float(np.mean([len(set(trace[s, l].ravel().tolist())) for s in range(steps) for l in range(n_layers)]))
-    return {"us_per_layer": us, "distinct_experts_per_layer": distinct}
+    # the distinct experts' weights (in the form the mat-vecs read) once per layer, over the whole layer time
+    return {"us_per_layer": us, "distinct_experts_per_layer": distinct,
+            "layer_HBM_GBps": distinct * bytes_per_expert / (us * 1e-6) / 1e9}
 
 
 def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred):
@@ -264,7 +266,7 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
         out[label] = dict(us_per_layer=us_layer, stats=st, gemv1_ms=g1, gemv2_ms=g2,
                           launches=(kt["gemv1"][1], kt["gemv2"][1]))
         if label == "resident":
-            out[label]["batch8"] = decode_batch_us(torch, H, S, ctx, wl, n_layers, 8, compute, copy)
+            out[label]["batch8"] = decode_batch_us(torch, H, S, ctx, wl, n_layers, 8, compute, copy, wl.blob_bytes)
         ctx.close()
         del layers, cache
     return out
@@ -307,7 +309,7 @@ def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy, 
     torch.cuda.synchronize()
     kt = ctx.moe_get_kernel_times()
     ctx.moe_set_profiling(False)
-    batch8 = decode_batch_us(torch, H, S, ctx, wl, n_layers, 8, compute, copy)
+    batch8 = decode_batch_us(torch, H, S, ctx, wl, n_layers, 8, compute, copy, pools[0].bytes_per_expert)
     ctx.close()
     g = kt["gemv1"][0] / max(1, kt["gemv1"][1]) + kt["gemv2"][0] / max(1, kt["gemv2"][1])
     code_bytes = wl.k * pools[0].bytes_per_expert
