@@ -533,14 +533,17 @@ def test_mxfp4_decode_streams_the_4bit_copies(gpu, oracle, d, I, I_shared, T):
 
 
 @pytest.mark.parametrize("fmt", [0, 1, 3])
-@pytest.mark.parametrize("d,I,I_shared,T", [(256, 512, 0, 6), (512, 256, 256, 9), (256, 768, 64, 20), (2304, 256, 0, 40)])
+@pytest.mark.parametrize("d,I,I_shared,T", [(512, 256, 256, 1), (256, 512, 0, 2), (256, 512, 0, 6), (512, 256, 256, 9),
+                                            (256, 768, 64, 20), (2304, 256, 0, 40)])
 def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I_shared, T):
     """Decode groups of three tokens and more take the mat-vec kernel that forms the sums with 16x16x32
     MFMAs (16 weight rows by up to 16 tokens per instruction): bf16 slots, e4m3 and MXFP4 copies
     (slots overwritten with NaN patterns, so a correct output proves where the weights came from),
     shared experts in the same launch, K cut into several LDS segments (d = 2304 at 16 tokens per
     pass), groups of more than 16 tokens in several passes (the mat-vec limit is raised so that the
-    GEMM kernels do not take them), and the same layer through the per-token kernels for comparison."""
+    GEMM kernels do not take them), and the same layer through the per-token kernels for comparison.  One
+    token (the launch takes its experts from the gate's id list on the device) and two are forced
+    onto the kernel as well."""
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("skinny", d=d, I=I, E=5, k=2, T=T, I_shared=I_shared, seed=70 + T + fmt, zipf_s=0.8)
     x = S.activations(w)
@@ -555,7 +558,7 @@ def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I
         lay.slots.fill_(0x7FC0)
         torch.cuda.synchronize()
     ref = oracle_layer(oracle, w, x, lay.router_np, pool, bias=bias, shared=lay.shared_np)
-    assert ref["counts"].max() >= 3 and (T < 20 or ref["counts"].max() > 16)
+    assert T < 6 or (ref["counts"].max() >= 3 and (T < 20 or ref["counts"].max() > 16))
     outs = {}
     for name, min_tok in (("mfma", 1), ("per-token", 1 << 20)):    # 1: wherever the shapes allow it
         B.moe_set_gemm_variant(6, 2 if fmt else 0)    # small experts: force the quantised source
