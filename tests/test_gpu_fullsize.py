@@ -199,7 +199,7 @@ def test_c2_shape_quantised_host_pool(gpu, oracle, fmt):
     torch.cuda.synchronize()
     lay.slots.fill_(0x7FC0)          # decode must not need the bf16 slots
     torch.cuda.synchronize()
-    for T in (1, 4):
+    for T in (1, 4, 8, 24):    # 8 and 24: groups of several tokens, the matrix-core mat-vec on the copies
         buf = H.Buffers(ctx, T)
         ctx.moe_decode_layer(0, H.np_to_dev(x_np[:T]), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
         gpu["compute"].synchronize()
@@ -207,3 +207,31 @@ def test_c2_shape_quantised_host_pool(gpu, oracle, fmt):
         np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
         check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"format {fmt} decode T={T}")
     ctx.close()
+
+
+@pytest.mark.parametrize("T", [8, 12])
+def test_c3_shape_decode_batches_resident(gpu, oracle, T):
+    """The Mixtral-shaped decode layer at the batch sizes bench.py also times (and the paper's largest,
+    12), experts resident in bf16 slots: per-token mat-vecs for the gate/up rows, 16x16x32 MFMAs for the
+    long down rows.  Every token against the oracle; routing tables bit for bit."""
+    from dataclasses import replace
+    H, B = gpu["harness"], gpu["binding"]
+    w = replace(S.WORKLOADS["c3_mixtral_decode"], T=T, L=1)
+    pool = H.HostPool(w, 0)
+    x_np = S.activations(w)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True)
+    lay = H.DeviceLayer(ctx, w, 0, pool, list(range(w.E)))
+    buf = H.Buffers(ctx, T)
+    ctx.moe_decode_layer(0, H.np_to_dev(x_np), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+    gpu["compute"].synchronize()
+    blobs = [pool.blob_np(e) for e in range(w.E)]
+    ref = oracle.moe_layer(x_np, lay.router_np, blobs, w.k, I=w.I)
+    routing = buf.routing(ctx, gpu["compute"])
+    for key in ("ids", "counts", "perm"):
+        np.testing.assert_array_equal(routing[key], ref[key], err_msg=key)
+    assert ref["counts"].max() >= 3
+    check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"decode batch {T}")
+    st = ctx.moe_get_stats(0)
+    assert st["misses"] == 0
+    ctx.close()
+
