@@ -31,7 +31,7 @@ def _default_hooks():
     yield
     from paper_2509_07379_amd import binding
     if torch.cuda.is_available():
-        for mode in range(10):
+        for mode in range(11):
             binding.moe_set_gemm_variant(mode, 1 if mode == 5 else 0)
 
 
@@ -570,6 +570,49 @@ def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I
         outs[name] = H.dev_to_np_u16(buf.y)
         check_out(outs[name], ref["out_f64"], f"{name} fmt={fmt} T={T}")
     ctx.close()
+
+
+def test_decode_seeded_random_shapes(gpu, oracle):
+    """Forty seeded random decode layers (format, widths that are whole steps of the matrix-core kernel
+    or not, shared experts of several widths, 3 to 64 experts, top-1 to top-8, 1 to 63 tokens, Zipf or
+    even routing, the matrix-core mat-vec by rule or forced, 1 to 8 K slices per block): routing tables
+    bit for bit, outputs within the bf16 tolerance of the oracle on the same (expanded) weights."""
+    H, B = gpu["harness"], gpu["binding"]
+    rng = np.random.default_rng(4242)
+    for it in range(40):
+        fmt = int(rng.choice([0, 1, 3]))
+        kmul = {0: 64, 1: 128, 3: 256}[fmt]
+        d = int(rng.integers(1, 6)) * kmul * int(rng.choice([1, 2]))
+        I = int(rng.integers(1, 5)) * kmul
+        I_shared = int(rng.choice([0, 40, 64, 192, 320]))
+        E = int(rng.choice([3, 5, 8, 17, 60, 64]))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.choice([1, 2, 3, 4, 7, 9, 16, 21, 40, 63]))
+        forced, slices = int(rng.choice([0, 1])), int(rng.choice([0, 1, 3, 8]))
+        case = f"case {it}: fmt={fmt} d={d} I={I} I_shared={I_shared} E={E} k={k} T={T} forced={forced} slices={slices}"
+        w = S.Workload("random", d=d, I=I, E=E, k=k, T=T, I_shared=I_shared, seed=1000 + it,
+                       zipf_s=float(rng.choice([0.0, 1.0])))
+        x = S.activations(w)
+        bias = S.zipf_route_bias(w, 0)
+        ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
+        pool = H.HostPool(w, 0, fmt=fmt)
+        lay = H.DeviceLayer(ctx, w, 0, pool, None if fmt else list(range(E)), poison=bool(fmt))
+        buf = H.Buffers(ctx, T)
+        if fmt:
+            ctx.expert_cache_prefetch(0, list(range(E)), gpu["copy"])
+            torch.cuda.synchronize()
+            lay.slots.fill_(0x7FC0)
+            torch.cuda.synchronize()
+        B.moe_set_gemm_variant(6, 2 if fmt else 0)
+        B.moe_set_gemm_variant(8, 1 if forced else 0)
+        B.moe_set_gemm_variant(9, 64)
+        B.moe_set_gemm_variant(10, slices)
+        ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"], H.np_to_dev(bias), 0)
+        gpu["compute"].synchronize()
+        ref = oracle_layer(oracle, w, x, lay.router_np, pool, bias=bias, shared=lay.shared_np)
+        np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["perm"], ref["perm"], err_msg=case)
+        check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], case)
+        ctx.close()
 
 
 @pytest.mark.parametrize("fmt", [1, 3])
