@@ -572,6 +572,41 @@ def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I
     ctx.close()
 
 
+def test_prefill_seeded_random_shapes(gpu, oracle):
+    """Thirty seeded random prefill layers: host format, widths (multiples of the format's unit, not of
+    the tiles), shared experts, 3 to 64 experts, top-1 to top-8, up to 1500 tokens, Zipf or even
+    routing, every expert resident or streamed through fewer slots than experts with a partly wrong
+    prefetch.  Routing tables bit for bit, outputs within the bf16 tolerance of the oracle, cache
+    counters equal to the simulator's."""
+    from oracle.cache_sim import CacheSim
+    rng = np.random.default_rng(5151)
+    for it in range(30):
+        fmt = int(rng.choice([0, 0, 1, 2, 3]))
+        unit = {0: 8, 1: 16, 2: 128, 3: 32}[fmt]
+        d = int(rng.integers(1, 5)) * unit * int(rng.choice([1, 3, 8]))
+        I = int(rng.integers(1, 5)) * unit * int(rng.choice([1, 2]))
+        I_shared = int(rng.choice([0, 0, 64, 136]))
+        E = int(rng.choice([3, 6, 8, 17, 64]))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.choice([1, 5, 63, 64, 200, 777, 1500]))
+        slots = E if rng.random() < 0.5 else int(rng.integers(1, E))   # one slot: fetch and compute take turns
+        prefetch = [int(e) for e in rng.permutation(E)[:min(slots, 2)]]
+        case = f"case {it}: fmt={fmt} d={d} I={I} I_shared={I_shared} E={E} k={k} T={T} slots={slots} prefetch={prefetch}"
+        w = S.Workload("random", d=d, I=I, E=E, k=k, T=T, I_shared=I_shared, seed=2000 + it,
+                       zipf_s=float(rng.choice([0.0, 1.1])))
+        x = S.activations(w)
+        bias = S.zipf_route_bias(w, 0)
+        r = run_layer(gpu, w, T, x, slots, None, bias=bias, prefetch=prefetch, poison=True, fmt=fmt)
+        ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias, shared=r["lay"].shared_np)
+        for key in ("ids", "counts", "perm"):
+            np.testing.assert_array_equal(r["routing"][key], ref[key], err_msg=f"{case} {key}")
+        check_out(r["out"], ref["out_f64"], case)
+        sim = CacheSim(E, slots, r["pool"].bytes_per_expert)
+        sim.prefetch(prefetch)
+        sim.serve(np.nonzero(ref["counts"])[0])
+        assert r["stats"] == {**sim.counters(), "layer_calls": 1}, case
+
+
 def test_decode_seeded_random_shapes(gpu, oracle):
     """Forty seeded random decode layers (format, widths that are whole steps of the matrix-core kernel
     or not, shared experts of several widths, 3 to 64 experts, top-1 to top-8, 1 to 63 tokens, Zipf or
