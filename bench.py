@@ -240,7 +240,7 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
             for l in range(n_layers):
                 if predict and l + 1 < n_layers:
                     # predictor for the next layer on its own stream (Section V-C)
-                    ctx.predictor_score(xs[l], wl.T, wps[l + 1], top_m, top, pred)
+                    ctx.predictor_score(l + 1, xs[l], wl.T, wps[l + 1], top_m, top, pred)
                 ctx.moe_decode_layer(l, xs[l], wl.T, buf.y, buf.ws, compute, copy, biases[s][l], wl.E)
                 if predict and l + 1 < n_layers:
                     pred.synchronize()
@@ -331,7 +331,7 @@ def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy, 
     def flow_step(s):
         for l in range(n_layers):
             if l + 1 < n_layers:
-                ctx.predictor_score(xs[l], wl.T, wps[l + 1], wl.k, top, pred)
+                ctx.predictor_score(l + 1, xs[l], wl.T, wps[l + 1], wl.k, top, pred)
             ctx.moe_decode_layer(l, xs[l], wl.T, buf.y, buf.ws, compute, copy, biases[s][l], wl.E)
             if l + 1 < n_layers:
                 pred.synchronize()

@@ -3,9 +3,9 @@
  *
  * One Mixture-of-Experts FFN layer served from an offloaded expert pool, after the
  * inference runtime of DuoServe-MoE (Section V of the paper): every expert lives in
- * a pinned "CPU expert cache", a small "GPU expert cache" of S slots per layer is
- * (or, with cfg.shared_slots, of S slots for all layers) is
- * filled by a communication stream just before the experts run (Section V-A), the
+ * a pinned "CPU expert cache", a small "GPU expert cache" of S slots per layer (or, with
+ * cfg.shared_slots, of S slots for all layers) is filled by a communication stream just
+ * before the experts run (Section V-A), the
  * prefill stage pipelines "compute expert i / fetch expert i+1" (Section V-B) and the
  * decode stage prefetches the experts a per-layer predictor names and re-fetches on
  * a wrong guess (Section V-C).  The numbers a layer produces never depend on the
@@ -42,7 +42,7 @@ extern "C" {
 
 #define MOE_OK 0
 #define MOE_E_ARG (-1)         /* null/unaligned pointer, T <= 0, k > E, cache_slots < 1, bad id ... */
-#define MOE_E_UNSUPPORTED (-2) /* E > 64, d % 8 != 0, I % 8 != 0 ... */
+#define MOE_E_UNSUPPORTED (-2) /* E > 64, d % 8 != 0, I % 8 != 0, d > 16384, cache_slots > 32767 ... */
 #define MOE_E_HIP (-3)         /* a HIP runtime call failed (text in moe_last_error) */
 #define MOE_E_UNBOUND (-4)     /* layer not bound */
 #define MOE_E_WORKSPACE (-5)   /* workspace too small */
@@ -52,12 +52,12 @@ typedef struct moe_ctx moe_ctx;
 /* Shape of the layer family (Fig. 1 of the paper: Top-k of n routed experts plus
  * optional shared experts).  Experts are SwiGLU FFN blocks without biases. */
 typedef struct {
-  int32_t d;           /* hidden size, multiple of 8 */
+  int32_t d;           /* hidden size, multiple of 8, at most 16384 (the gate stages token vectors in LDS) */
   int32_t I;           /* routed-expert intermediate size, multiple of 8 */
   int32_t E;           /* routed experts per layer, 1..64 */
   int32_t k;           /* experts per token, 1..E */
   int32_t n_layers;    /* layers that can be bound */
-  int32_t cache_slots; /* S: GPU expert cache slots per layer, >= 1 (Section V-A) */
+  int32_t cache_slots; /* S: GPU expert cache slots per layer, 1..32767 (Section V-A) */
   int32_t I_shared;    /* 0, or total intermediate size of the always-on shared experts */
   int32_t renormalize; /* 1: gate values = softmax over the k selected; 0: over all E */
   int32_t shared_slots;/* 0: every layer has its own cache of cache_slots slots; 1: ONE cache of
@@ -103,10 +103,18 @@ typedef struct {
  *   MOE_FMT_E4M3_ROWS. */
 #define MOE_FMT_MXFP4 3
 
-/* Cache counters (host side).  hits/misses count active experts per layer call. */
+/* Cache counters (host side).  hits/misses count active experts per layer call.
+ * prefetch_ready / prefetch_stalled: of the prefetched experts a layer call went on to use, how
+ * many had landed in their slot when the call asked for them and how many had not (Section V-C:
+ * a prefetch that is late stalls the computation stream), taken on the host when the call
+ * enqueues its wait.  wait_ms: host time the layer calls spent blocked until the gate's counts
+ * arrived (only calls that have to compare them with the cache block).  compute_ms: kernel time
+ * of the layer's calls, from the events of moe_set_profiling (0 while profiling is off). */
 typedef struct {
   int32_t hits, misses, prefetch_issued, prefetch_useful, prefetch_dropped, layer_calls;
   int64_t bytes_h2d;
+  int32_t prefetch_ready, prefetch_stalled;
+  float wait_ms, compute_ms;
 } moe_stats;
 
 /* Kernel classes timed when profiling is on (moe_set_profiling). */
@@ -166,8 +174,10 @@ int expert_cache_prefetch(moe_ctx *ctx, int layer, const int32_t *host_ids, int 
  * score[e] = sum_t x[t] . Wp[e]; the m best (score descending, lower id on ties) go to
  * pinned_topm[m] (pinned host ints, valid once `stream` has been synchronised) and, if
  * dev_scores != NULL, the E scores to dev_scores.  dev_x [T, d] bf16, dev_wp [E, d] bf16.
+ * `layer` is the layer whose experts are being predicted (0 <= layer < n_layers; it need not be
+ * bound): the predictor is per layer, the caller passes that layer's dev_wp.
  */
-int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, int m,
+int predictor_score(moe_ctx *ctx, int layer, const void *dev_x, int T, const void *dev_wp, int m,
                     float *dev_scores, int32_t *pinned_topm, void *stream);
 
 /*
@@ -225,11 +235,21 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out);
  *                  (bias_stride 0 = one row for all tokens, E = one row per token).
  *  dev_workspace   >= moe_workspace_bytes(cfg, T), 256-byte aligned; holds the routing
  *                  tables afterwards (see moe_debug_routing).
+ *  opt             NULL, or receives this call's own counters (hits, misses, prefetch_useful,
+ *                  prefetch_ready / _stalled, bytes_h2d, wait_ms; layer_calls = 1; compute_ms = 0,
+ *                  kernel times are asynchronous: moe_get_stats).  With opt the call waits for the
+ *                  gate's counts before it returns even when every expert is resident.
+ * When every routed expert is resident the call only enqueues: its cache counters (hits, recency)
+ * are filled in once the gate's counts have reached the host, by the next call that looks at the
+ * cache or its counters (expert_cache_prefetch, a layer call with a miss, moe_get_stats, ...), in
+ * the order of the calls.  If a HIP call fails midway the error is returned, work already enqueued
+ * still runs and the library's side stream is joined back into compute_stream; experts whose copy
+ * had been enqueued count as resident, so the cache stays consistent with what the streams will do.
  */
 int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
                       const float *dev_route_bias, int bias_stride, void *dev_y,
                       void *dev_workspace, size_t ws_bytes, void *compute_stream,
-                      void *copy_stream);
+                      void *copy_stream, moe_stats *opt);
 
 /*
  * One MoE layer in the decode stage (Section V-C), T = batch (small).  Same contract and
@@ -241,12 +261,13 @@ int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
  * kernels.  The host looks at the gate's counts
  * (a short wait on a pinned mailbox) unless every expert is resident and T = 1: then the
  * mat-vec launches read the token's k experts from the gate's id list on the device and the
- * call only enqueues (its cache counters are filled in when the mailbox arrives).
+ * call only enqueues (its cache counters are filled in later, as for moe_prefill_layer; up to 32
+ * such calls can be in flight before a call waits for the oldest one's counts).
  */
 int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
                      const float *dev_route_bias, int bias_stride, void *dev_y,
                      void *dev_workspace, size_t ws_bytes, void *compute_stream,
-                     void *copy_stream);
+                     void *copy_stream, moe_stats *opt);
 
 /*
  * Parity hook: copies the routing tables the last layer call left in `dev_workspace`
@@ -262,7 +283,9 @@ int moe_debug_routing(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *d
  * defined bit for bit (Section II-A; fixed summation order, see the kernel's header). */
 int moe_debug_logits(moe_ctx *ctx, const void *dev_workspace, int T, float *dev_logits, void *stream);
 
-/* Cache counters of `layer` (or summed over all layers if layer < 0). */
+/* Cache counters of `layer` (or summed over all layers if layer < 0).  Blocks until the gate's counts
+ * of every layer call so far have reached the host and, while profiling is on, until the kernels
+ * timed so far have finished. */
 int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out);
 int moe_reset_stats(moe_ctx *ctx);
 /*
@@ -277,8 +300,8 @@ int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert);
 /*
  * Kernel timing.  on != 0: every kernel launch of the layer calls is bracketed by HIP
  * events on its own stream.  moe_get_kernel_times blocks until those events have
- * completed, adds their durations into ms[MOE_K_COUNT] / launches[MOE_K_COUNT] and
- * clears the record.
+ * completed, writes the durations summed since the last call into ms[MOE_K_COUNT] /
+ * launches[MOE_K_COUNT] and clears the record.
  */
 int moe_set_profiling(moe_ctx *ctx, int on);
 int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches);
@@ -290,30 +313,6 @@ int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches);
  */
 int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M, int N, int K,
                         void *stream);
-
-/*
- * Tuning and test hook: forces GEMM kernel `variant` (0 = chosen by shape, the default; 1 = 128 x 128
- * tiles, 6 = 256 x 256 tiles of the single-phase kernel, 12 = the persistent ping-pong kernel) for the
- * gate/up GEMM (mode 0), the down GEMM (mode 1) or the dense GEMM (mode 2); mode 3 forces the
- * number of K slices of the down GEMM (0 = heuristic; changes moe_workspace_bytes, so set it
- * before sizing workspaces); mode 4 forces the weight rows per wave of the decode mat-vec
- * kernels (0 = heuristic, 1, 2 or 4); mode 5 with variant 0 makes a one-token decode call
- * with every expert resident wait for the gate's result on the host like any other call (default 1:
- * it is enqueued at once, the mat-vec launches take the k experts from the gate's id list on the
- * device); mode 6 chooses what the decode mat-vec kernels read where a quantised copy of an
- * expert exists (MOE_FMT_E4M3_ROWS, MOE_FMT_MXFP4): 0 = the copy if the experts are large enough for
- * it to pay (16 M weights per matrix), 1 = always the expanded bf16 slot, 2 = always the copy;
- * mode 7 with variant 1 makes a one-token decode call with every expert resident run the down
- * mat-vec and the weighted sum as two launches instead of one (the same bits either way);
- * mode 8 sets the token count per expert from which a mat-vec launch may use the matrix-core
- * kernel (0 = default: 3, or 2 for quantised gate/up rows, and only where measurement says it
- * pays; 1 = wherever the shapes allow it; a
- * large value = never); mode 9 the largest group a decode call still gives to the mat-vec
- * launches (0 = default: 16, or 32 on quantised copies); mode 10 the K slices (waves) per block
- * of the matrix-core mat-vec (0 = by shape, 1..8).
- * Process-wide.
- */
-int moe_set_gemm_variant(int mode, int variant);
 
 #ifdef __cplusplus
 }

@@ -20,10 +20,12 @@ EXPORTS = [
     "moe_last_error", "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_bind_layer",
     "expert_cache_prefetch", "predictor_score", "moe_prefill_layer", "moe_decode_layer",
     "moe_debug_routing", "moe_get_stats", "moe_reset_stats", "moe_cache_invalidate", "moe_cache_state", "moe_set_profiling",
-    "moe_get_kernel_times", "moe_dense_gemm_bf16", "moe_set_gemm_variant",
+    "moe_get_kernel_times", "moe_dense_gemm_bf16",
     "predictor_mlp_score", "moe_state_create", "moe_state_destroy", "moe_state_dim", "moe_state_record",
     "moe_state_clear", "moe_state_vector", "moe_host_blob_bytes", "moe_cache_bytes", "moe_debug_logits",
 ]
+# exported for the parity tests only, declared in csrc/moe_tuning.h (not part of the public header)
+INTERNAL_EXPORTS = ["moe_tune", "moe_inject_failure", "moe_debug_gemm_choice"]
 
 
 class MoeConfig(Structure):
@@ -32,11 +34,20 @@ class MoeConfig(Structure):
 
 
 class MoeStats(Structure):
-    _fields_ = [(n, c_int32) for n in ("hits", "misses", "prefetch_issued", "prefetch_useful",
-                                       "prefetch_dropped", "layer_calls")] + [("bytes_h2d", c_int64)]
+    _fields_ = ([(n, c_int32) for n in ("hits", "misses", "prefetch_issued", "prefetch_useful",
+                                        "prefetch_dropped", "layer_calls")] + [("bytes_h2d", c_int64)] +
+                [("prefetch_ready", c_int32), ("prefetch_stalled", c_int32), ("wait_ms", c_float),
+                 ("compute_ms", c_float)])
+    CACHE_COUNTERS = ("hits", "misses", "prefetch_issued", "prefetch_useful", "prefetch_dropped", "layer_calls",
+                      "bytes_h2d")
 
-    def as_dict(self):
-        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+    def as_dict(self, full=False):
+        """The cache counters (what the cache simulator also keeps); full: every field."""
+        d = {n: int(getattr(self, n)) for n in self.CACHE_COUNTERS}
+        if full:
+            d.update(prefetch_ready=int(self.prefetch_ready), prefetch_stalled=int(self.prefetch_stalled),
+                     wait_ms=float(self.wait_ms), compute_ms=float(self.compute_ms))
+        return d
 
 
 class MoeError(RuntimeError):
@@ -67,8 +78,8 @@ def load():
     lib.moe_workspace_bytes.restype = c_size_t
     lib.moe_bind_layer.argtypes = [vp, c_int, POINTER(vp), vp, vp, vp, POINTER(c_int32)]
     lib.expert_cache_prefetch.argtypes = [vp, c_int, POINTER(c_int32), c_int, vp]
-    lib.predictor_score.argtypes = [vp, vp, c_int, vp, c_int, vp, vp, vp]
-    layer_args = [vp, c_int, vp, c_int, vp, c_int, vp, vp, c_size_t, vp, vp]
+    lib.predictor_score.argtypes = [vp, c_int, vp, c_int, vp, c_int, vp, vp, vp]
+    layer_args = [vp, c_int, vp, c_int, vp, c_int, vp, vp, c_size_t, vp, vp, POINTER(MoeStats)]
     lib.moe_prefill_layer.argtypes = layer_args
     lib.moe_decode_layer.argtypes = layer_args
     lib.moe_debug_routing.argtypes = [vp, vp, c_int, vp, vp, vp, vp, vp, vp, vp]
@@ -80,7 +91,12 @@ def load():
     lib.moe_set_profiling.argtypes = [vp, c_int]
     lib.moe_get_kernel_times.argtypes = [vp, POINTER(c_float), POINTER(c_int32)]
     lib.moe_dense_gemm_bf16.argtypes = [vp, vp, vp, c_int, c_int, c_int, vp]
-    lib.moe_set_gemm_variant.argtypes = [c_int, c_int]
+    lib.moe_tune.argtypes = [vp, c_int, c_int]
+    lib.moe_tune.restype = c_int
+    lib.moe_inject_failure.argtypes = [c_int]
+    lib.moe_inject_failure.restype = c_int
+    lib.moe_debug_gemm_choice.argtypes = [c_int, c_int, c_int64, c_int, c_int, c_int, c_int, c_int64, c_int, c_int]
+    lib.moe_debug_gemm_choice.restype = c_int
     lib.predictor_mlp_score.argtypes = [vp, vp, POINTER(c_int32), c_int, POINTER(vp), POINTER(vp), POINTER(vp),
                                         POINTER(vp), vp, c_int, vp, vp, vp]
     lib.moe_state_create.argtypes = [c_int, c_int, c_int, POINTER(c_float), POINTER(c_float), POINTER(vp)]
@@ -168,8 +184,8 @@ class MoeContext:
         arr = (c_int32 * max(1, len(ids)))(*ids)
         _check(self.lib.expert_cache_prefetch(self._h, layer, arr, len(ids), _stream(copy_stream)))
 
-    def predictor_score(self, x, T, wp, m, pinned_topm, stream, scores=None):
-        _check(self.lib.predictor_score(self._h, _ptr(x), T, _ptr(wp), m, _ptr(scores), _ptr(pinned_topm),
+    def predictor_score(self, layer, x, T, wp, m, pinned_topm, stream, scores=None):
+        _check(self.lib.predictor_score(self._h, layer, _ptr(x), T, _ptr(wp), m, _ptr(scores), _ptr(pinned_topm),
                                         _stream(stream)))
 
     def predictor_mlp_score(self, state, dims, weights, biases, scales, shifts, act, m, pinned_topm, stream,
@@ -189,19 +205,23 @@ class MoeContext:
                                             parr(scales), parr(shifts), _ptr(act), m, _ptr(scores),
                                             _ptr(pinned_topm), _stream(stream)))
 
-    def _layer(self, fn, layer, x, T, y, ws, compute_stream, copy_stream, route_bias, bias_stride):
+    def _layer(self, fn, layer, x, T, y, ws, compute_stream, copy_stream, route_bias, bias_stride, want_stats):
+        st = MoeStats() if want_stats else None
         _check(fn(self._h, layer, _ptr(x), T, _ptr(route_bias), bias_stride, _ptr(y), _ptr(ws),
-                  ws.numel() * ws.element_size(), _stream(compute_stream), _stream(copy_stream)))
+                  ws.numel() * ws.element_size(), _stream(compute_stream), _stream(copy_stream),
+                  byref(st) if want_stats else None))
+        return st.as_dict(full=True) if want_stats else None
 
     def moe_prefill_layer(self, layer, x, T, y, ws, compute_stream, copy_stream, route_bias=None,
-                          bias_stride=0):
-        self._layer(self.lib.moe_prefill_layer, layer, x, T, y, ws, compute_stream, copy_stream, route_bias,
-                    bias_stride)
+                          bias_stride=0, want_stats=False):
+        """want_stats: pass a moe_stats for this call's own counters and return it as a dict."""
+        return self._layer(self.lib.moe_prefill_layer, layer, x, T, y, ws, compute_stream, copy_stream,
+                           route_bias, bias_stride, want_stats)
 
     def moe_decode_layer(self, layer, x, T, y, ws, compute_stream, copy_stream, route_bias=None,
-                         bias_stride=0):
-        self._layer(self.lib.moe_decode_layer, layer, x, T, y, ws, compute_stream, copy_stream, route_bias,
-                    bias_stride)
+                         bias_stride=0, want_stats=False):
+        return self._layer(self.lib.moe_decode_layer, layer, x, T, y, ws, compute_stream, copy_stream,
+                           route_bias, bias_stride, want_stats)
 
     def moe_debug_routing(self, ws, T, ids=None, w=None, counts=None, offsets=None, perm=None,
                           inv_perm=None, stream=None):
@@ -211,10 +231,14 @@ class MoeContext:
     def moe_debug_logits(self, ws, T, logits, stream=None):
         _check(self.lib.moe_debug_logits(self._h, _ptr(ws), T, _ptr(logits), _stream(stream)))
 
-    def moe_get_stats(self, layer=-1) -> dict:
+    def moe_get_stats(self, layer=-1, full=False) -> dict:
         st = MoeStats()
         _check(self.lib.moe_get_stats(self._h, layer, byref(st)))
-        return st.as_dict()
+        return st.as_dict(full)
+
+    def moe_tune(self, mode: int, variant: int):
+        """Internal test / tuning hook (csrc/moe_tuning.h): forces a kernel variant for this context."""
+        _check(self.lib.moe_tune(self._h, mode, variant))
 
     def moe_reset_stats(self):
         _check(self.lib.moe_reset_stats(self._h))
@@ -240,10 +264,6 @@ class MoeContext:
 
 def moe_dense_gemm_bf16(a, b, c, M, N, K, stream=None):
     _check(load().moe_dense_gemm_bf16(_ptr(a), _ptr(b), _ptr(c), M, N, K, _stream(stream)))
-
-
-def moe_set_gemm_variant(mode: int, variant: int):
-    _check(load().moe_set_gemm_variant(mode, variant))
 
 
 class MoeState:

@@ -19,6 +19,7 @@
 
 #include "../../include/moe_offload.h"
 #include "kernels.h"
+#include "moe_tuning.h"
 
 using namespace moe;
 
@@ -34,8 +35,14 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
+// Test hook (moe_inject_failure): the n-th HIP call of this thread from now on is not made and
+// reports an error instead, so that the state a failed call leaves behind can be examined.
+thread_local int g_fail_countdown = 0;
+
 #define HIP_TRY(expr)                                                                      \
   do {                                                                                     \
+    if (g_fail_countdown > 0 && --g_fail_countdown == 0)                                   \
+      return fail(MOE_E_HIP, "injected failure instead of %s (%s:%d)", #expr, __FILE__, __LINE__); \
     hipError_t _e = (expr);                                                                \
     if (_e != hipSuccess)                                                                  \
       return fail(MOE_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, __LINE__); \
@@ -47,20 +54,25 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // K slices of the down projection.  Few, long tiles (Mixtral-like: K = 14336, ~320 tiles of
 // 256 x 256 on 256 CUs) leave most of the last round idle; slicing K makes the tiles finer.
 // The slices land in separate fp32 planes that the combine kernel adds in a fixed order.
-int g_splitk_override = 0;  // tuning hook (moe_set_gemm_variant mode 3); 0 = heuristic
-int g_no_fused_down = 0;  // tuning hook (mode 7): 1 = a one-token call runs the down mat-vec and the weighted sum as two launches
-int g_no_q8_matvec = 0;  // tuning hook (mode 6): 1 = mat-vecs read the expanded bf16 slots even when an 8-bit copy exists
-int g_blind_one_token = 1;  // tuning hook (mode 5): 0 = a one-token decode call always waits for the gate on the host
+constexpr int kMaxSplitK = 4;
+
+// Host-side tuning and test hooks of one context (moe_tune), beside the launchers' Tune.
+struct ApiTune {
+  int splitk = 0;            // K slices of the down GEMM, 0 = heuristic, at most kMaxSplitK
+  int no_fused_down = 0;     // a one-token call runs the down mat-vec and the weighted sum as two launches
+  int no_q_matvec = 0;       // mat-vecs read the expanded bf16 slots even when a quantised copy exists
+  int host_looks_always = 0; // a one-token decode call waits for the gate on the host like any other
+  int matvec_max_rows = 0;   // largest group a decode call gives to the mat-vec launches, 0 = default
+};
 
 int choose_splitk(const moe_config &cfg, int T) {
-  if (g_splitk_override > 0) return g_splitk_override;
   const long long rows = (long long)T * cfg.k;
   if (rows < 1024) return 1;  // decode-sized calls run the mat-vec path
   const long long tiles = (rows / 256 + (cfg.E + 1) / 2) * ((cfg.d + 255) / 256);
   long long s = (3 * 256 + tiles - 1) / tiles;  // aim at >= 3 rounds of tiles over 256 CUs
   const long long max_by_k = cfg.I / 1024;      // keep every slice >= 16 K steps
   if (s > max_by_k) s = max_by_k;
-  if (s > 4) s = 4;
+  if (s > kMaxSplitK) s = kMaxSplitK;
   return s < 1 ? 1 : (int)s;
 }
 
@@ -69,10 +81,13 @@ struct WsLayout {
   int splitk, nblk;
 };
 
-WsLayout ws_layout(const moe_config &c, int T) {
+// The workspace has the planes the heuristic asks for; forced_splitk (a tuning hook) can only use
+// fewer of them, so the size never depends on it.
+WsLayout ws_layout(const moe_config &c, int T, int forced_splitk = 0) {
   WsLayout L{};
   const size_t n = (size_t)T * c.k;
-  L.splitk = choose_splitk(c, T);
+  const int planes = choose_splitk(c, T);
+  L.splitk = forced_splitk > 0 && forced_splitk < planes ? forced_splitk : planes;
   L.nblk = (int)((n + kDispatchChunk - 1) / kDispatchChunk);
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -91,7 +106,7 @@ WsLayout ws_layout(const moe_config &c, int T) {
   L.inv_perm = take(n * 4);
   L.H = take(n * c.I * 2);
   L.Hs = take((size_t)T * c.I_shared * 2);
-  L.Y = take((size_t)L.splitk * n * c.d * 4);
+  L.Y = take((size_t)planes * n * c.d * 4);
   L.Ys = take(c.I_shared ? (size_t)T * c.d * 4 : 0);
   L.total = off;
   return L;
@@ -106,6 +121,7 @@ struct SlotSet {
   std::vector<unsigned long long> stamp;
   std::vector<char> prefetched;      // slot filled by a prefetch and not yet served
   std::vector<char> copy_pending;    // a copy into the slot was enqueued; compute has not waited yet
+  std::vector<char> pf_landed;       // prefetched slot, when compute first waited for it: 1 = had landed, 2 = had not
   std::vector<char> use_kind;        // 0: never read, 1: read behind used[slot], 2: read behind group_done
   std::vector<hipEvent_t> copied, used;
   std::vector<hipEvent_t> copied_up;  // a split fetch has landed its gate / up matrices
@@ -132,8 +148,16 @@ struct Layer {
 
 struct TimedLaunch {
   hipEvent_t start, stop;
-  int kind;
+  int kind, layer;
 };
+
+// A layer call whose cache counters wait for the gate's per-expert counts: the grouping kernel
+// writes them, followed by the call's number, into mailbox `box` (pinned host memory).
+struct PendingCall {
+  int layer, box, seq;
+};
+constexpr int kMailboxes = 32;
+constexpr int kMailboxWords = kMaxExperts + 1;
 
 }  // namespace
 
@@ -145,9 +169,20 @@ struct moe_ctx {
   size_t stage_stride = 0;      // e4m3: bytes of one slot's staging area behind the slots (256-aligned)
   std::vector<Layer> layers;
   std::unique_ptr<SlotSet> shared_set;   // cfg.shared_slots: the one cache all layers use
-  int32_t *pinned_counts = nullptr;   // mailbox the dispatch kernel fills: [kMaxExperts] counts, then the call's number
-  int32_t mailbox_seq = 0;
-  hipEvent_t routed = nullptr;
+  // Mailboxes the grouping kernel fills, one per layer call in flight: [kMaxExperts] counts, then the
+  // call's number.  A call that needs the counts at once waits for its own; a call that could enqueue
+  // everything without them leaves an entry in `pending`, and its counters are filled in by the next
+  // API call that looks at the cache (or when the mailbox is needed again).
+  int32_t *mailboxes = nullptr;       // [kMailboxes][kMailboxWords], pinned
+  hipEvent_t routed[kMailboxes] = {};
+  int32_t call_no = 0;
+  PendingCall pending[kMailboxes];    // ring, oldest at pend_head (a mailbox has at most one pending call)
+  int pend_head = 0, pend_count = 0;
+  int cur_layer = -1;                 // layer of the call being enqueued (for the kernel timers)
+  Tune tune{};
+  ApiTune api_tune{};
+  float kernel_ms[MOE_K_COUNT] = {};  // harvested kernel durations not yet handed to moe_get_kernel_times
+  int32_t kernel_launches[MOE_K_COUNT] = {};
   // prefill with shared experts: they run on a stream of the library's own, beside the gate, the
   // grouping and the routed experts (fork at the start of the call, join before the weighted sum)
   hipStream_t side = nullptr;
@@ -171,6 +206,10 @@ int check_cfg(const moe_config *c) {
     return fail(MOE_E_ARG, "d, I, E, k, n_layers must be positive (I_shared >= 0)");
   if (c->k > c->E) return fail(MOE_E_ARG, "k = %d exceeds E = %d", c->k, c->E);
   if (c->cache_slots < 1) return fail(MOE_E_ARG, "cache_slots = %d, need >= 1", c->cache_slots);
+  if (c->cache_slots > kMaxCacheSlots)   // the kernels' argument block holds a slot index in 16 bits
+    return fail(MOE_E_UNSUPPORTED, "cache_slots = %d > %d", c->cache_slots, kMaxCacheSlots);
+  if (c->d > kMaxHidden)                 // the gate keeps four token vectors in LDS
+    return fail(MOE_E_UNSUPPORTED, "d = %d > %d", c->d, kMaxHidden);
   if (c->E > kMaxExperts) return fail(MOE_E_UNSUPPORTED, "E = %d > %d experts", c->E, kMaxExperts);
   if (c->d % 8 || c->I % 8 || c->I_shared % 8)
     return fail(MOE_E_UNSUPPORTED, "d, I and I_shared must be multiples of 8");
@@ -216,12 +255,105 @@ struct Timer {
   ~Timer() {
     if (!start || !stop) return;
     (void)hipEventRecord(stop, stream);
-    ctx->timed.push_back({start, stop, kind});
+    ctx->timed.push_back({start, stop, kind, ctx->cur_layer});
   }
 };
 
+// Blocks until the timed launches recorded so far have completed and adds their durations to the
+// context's per-class sums and to their layers' compute_ms.
+int harvest_timers(moe_ctx *ctx) {
+  for (auto &t : ctx->timed) {
+    HIP_TRY(hipEventSynchronize(t.stop));
+    float dt = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&dt, t.start, t.stop));
+    ctx->kernel_ms[t.kind] += dt;
+    ctx->kernel_launches[t.kind]++;
+    if (t.layer >= 0 && t.layer < (int)ctx->layers.size()) ctx->layers[t.layer].stats.compute_ms += dt;
+    ctx->event_pool.push_back(t.start);
+    ctx->event_pool.push_back(t.stop);
+  }
+  ctx->timed.clear();
+  return MOE_OK;
+}
+
 // ---- cache bookkeeping --------------------------------------------------------------------
 void touch(Layer &L, int s) { L.set->stamp[s] = ++L.set->clock; }
+
+// Section V-C, second synchronisation point: had a prefetched expert landed when compute asked for it
+// (1) or does the computation stream have to wait for the copy (2)?  Taken on the host when the wait
+// is enqueued, which is never later than the stream's own wait.
+int prefetch_arrival(SlotSet &set, int s, bool from_copy) {
+  return hipEventQuery(from_copy ? set.landed[s] : set.copied[s]) == hipSuccess ? 1 : 2;
+}
+
+// A served expert that was resident: recency, hit counter and, the first time after a prefetch
+// brought it in, the prefetch counters.
+void account_hit(Layer &L, int s) {
+  SlotSet &set = *L.set;
+  touch(L, s);
+  L.stats.hits++;
+  if (!set.prefetched[s]) return;
+  L.stats.prefetch_useful++;
+  set.prefetched[s] = 0;
+  const int arrival = set.pf_landed[s] ? set.pf_landed[s] : (set.copy_pending[s] ? prefetch_arrival(set, s, false) : 1);
+  if (arrival == 1) L.stats.prefetch_ready++;
+  else L.stats.prefetch_stalled++;
+  set.pf_landed[s] = 0;
+}
+
+
+// The host needs the gate's per-expert counts of the call that owns mailbox `box`.  Waking up on the
+// event costs 10-20 us; the grouping kernel writes the call's number behind the counts in pinned,
+// host-coherent memory, so the host first polls that word for a while (the kernel is a few
+// microseconds away) and only then blocks.
+bool counts_arrived(const moe_ctx *ctx, int box, int seq) {
+  volatile const int32_t *flag = ctx->mailboxes + (size_t)box * kMailboxWords + kMaxExperts;
+  if (*flag != seq) return false;
+  std::atomic_thread_fence(std::memory_order_acquire);
+  return true;
+}
+
+hipError_t wait_for_counts(moe_ctx *ctx, int box, int seq) {
+  const auto t0 = std::chrono::steady_clock::now();
+  for (int spin = 0;; ++spin) {
+    if (counts_arrived(ctx, box, seq)) return hipSuccess;
+    if ((spin & 255) == 255 &&
+        std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300))
+      break;
+  }
+  hipError_t e = hipEventSynchronize(ctx->routed[box]);
+  if (e != hipSuccess) return e;
+  return counts_arrived(ctx, box, seq) ? hipSuccess : hipErrorUnknown;
+}
+
+// Cache counters of a call that was enqueued without looking at the gate's result (every expert was
+// resident): hits, recency stamps and useful prefetches, exactly as if they had been taken at the call.
+void account_resident_call(moe_ctx *ctx, const PendingCall &p) {
+  Layer &L = ctx->layers[p.layer];
+  const int32_t *counts = ctx->mailboxes + (size_t)p.box * kMailboxWords;
+  for (int e = 0; e < ctx->cfg.E; ++e)
+    if (counts[e] > 0) {
+      const int s = L.expert_slot[e];
+      if (s >= 0) account_hit(L, s);   // (always: whatever changes the slots settles the pending calls first)
+    }
+}
+
+// Fills in the counters of pending calls, oldest first.  block: wait for every one of them (anything
+// that reads or changes recency stamps, slot contents or counters does this first, so the order of
+// the stamps is the order of the calls); otherwise stop at the first whose counts are not there yet.
+int settle_pending(moe_ctx *ctx, bool block) {
+  while (ctx->pend_count > 0) {
+    const PendingCall p = ctx->pending[ctx->pend_head];
+    if (!counts_arrived(ctx, p.box, p.seq)) {
+      if (!block) break;
+      HIP_TRY(wait_for_counts(ctx, p.box, p.seq));
+    }
+    account_resident_call(ctx, p);
+    ctx->pend_head = (ctx->pend_head + 1) % kMailboxes;
+    ctx->pend_count--;
+  }
+  return MOE_OK;
+}
 
 int pick_victim(const Layer &L, unsigned long long protected_mask) {
   const int S = (int)L.set->slot_expert.size();
@@ -256,6 +388,12 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   char *dst = L.set->slots + (size_t)s * ctx->blob_bytes;
   const char *src = static_cast<const char *>(L.host_blob[e]);
   const moe_config &c = ctx->cfg;
+  // From here on the slot's old content is gone: should a step below fail, the tables call the slot
+  // empty rather than name an expert whose bytes are being overwritten.
+  if (L.set->slot_expert[s] >= 0) ctx->layers[L.set->slot_layer[s]].expert_slot[L.set->slot_expert[s]] = -1;
+  L.set->slot_expert[s] = L.set->slot_layer[s] = -1;
+  L.set->prefetched[s] = 0;
+  L.set->q_valid[s] = 0;
   if (c.host_format != MOE_FMT_BF16) {
     // The quantised blob ([scales and zero points][gate codes][up codes][down codes]) lands in the
     // slot's staging area on the copy stream; kernels on the expansion stream, each behind the copy
@@ -299,7 +437,6 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
     set.staged[s] = 1;
     set.expand_pending[s] = 1;
-    set.q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS || c.host_format == MOE_FMT_MXFP4;   // forms the mat-vec kernels read
     int rc = MOE_OK;
     if (split) {
       HIP_TRY(hipMemcpyAsync(stage, src, meta_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
@@ -330,12 +467,14 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     HIP_TRY(hipMemcpyAsync(dst, src, ctx->blob_bytes, hipMemcpyHostToDevice, copy_stream));
   }
   if (c.host_format == MOE_FMT_BF16) HIP_TRY(hipEventRecord(L.set->copied[s], copy_stream));
-  if (L.set->slot_expert[s] >= 0) ctx->layers[L.set->slot_layer[s]].expert_slot[L.set->slot_expert[s]] = -1;
+  // forms the mat-vec kernels read straight from the staging area
+  L.set->q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS || c.host_format == MOE_FMT_MXFP4;
   L.set->slot_expert[s] = e;
   L.set->slot_layer[s] = L.index;
   L.expert_slot[e] = s;
   L.set->prefetched[s] = by_prefetch;
   L.set->copy_pending[s] = 1;
+  L.set->pf_landed[s] = 0;
   L.set->use_kind[s] = 0;
   touch(L, s);
   L.stats.bytes_h2d += (int64_t)ctx->host_blob_bytes;
@@ -354,7 +493,9 @@ int join_expand(moe_ctx *ctx, hipStream_t copy_stream) {
 // The compute stream waits until slot s can be read: its quantised copy in the staging area
 // (from_copy: the bytes have landed) or the bf16 slot itself (landed and, for a quantised pool,
 // expanded).
-int wait_ready(SlotSet &set, int s, bool from_copy, hipStream_t cs) {
+int wait_ready(Layer &L, int s, bool from_copy, hipStream_t cs) {
+  SlotSet &set = *L.set;
+  if (set.copy_pending[s] && set.prefetched[s] && !set.pf_landed[s]) set.pf_landed[s] = prefetch_arrival(set, s, from_copy);
   if (from_copy) {
     if (set.copy_pending[s]) {
       HIP_TRY(hipStreamWaitEvent(cs, set.landed[s], 0));
@@ -376,9 +517,10 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   a.n_groups = c.E;
   a.wbase = L.set->slots;
   a.wstride = (long long)ctx->blob_bytes;
-  for (int e = 0; e < c.E; ++e) a.slot[e] = (signed char)(L.expert_slot[e] < 0 ? 0 : L.expert_slot[e]);
+  for (int e = 0; e < c.E; ++e) a.slot[e] = (int16_t)(L.expert_slot[e] < 0 ? 0 : L.expert_slot[e]);
   a.splitk = 1;
-  if (c.host_format == MOE_FMT_E4M3_ROWS && c.d % 16 == 0 && c.I % 16 == 0 && !g_no_q8_matvec) {
+  a.tune = ctx->tune;
+  if (c.host_format == MOE_FMT_E4M3_ROWS && c.d % 16 == 0 && c.I % 16 == 0 && !ctx->api_tune.no_q_matvec) {
     // the mat-vec kernels stream the 8-bit copy that a fetch left in the slot's staging area (half
     // the bytes; the same weight values as the expanded slot)
     const long long scale_bytes = (long long)4 * (2 * c.I + c.d), Id = (long long)c.I * c.d;
@@ -389,7 +531,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
     a.q_b1_off = scale_bytes + (second ? 2 * Id : Id);
     a.q_s0_off = second ? (long long)4 * 2 * c.I : 0;
     a.q_s1_off = second ? (long long)4 * 2 * c.I : (long long)4 * c.I;
-  } else if (c.host_format == MOE_FMT_MXFP4 && !g_no_q8_matvec) {
+  } else if (c.host_format == MOE_FMT_MXFP4 && !ctx->api_tune.no_q_matvec) {
     // likewise the MXFP4 copy (a quarter of the bytes): codes K/2 bytes per row, scales K/32
     const long long Id = (long long)c.I * c.d, meta = (3 * Id / 32 + 15) / 16 * 16;
     a.qfmt = 2;
@@ -406,6 +548,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   if (!second) {
     a.A = reinterpret_cast<const uint16_t *>(x);
     a.lda = c.d;
+    a.a_rows = T;
     a.perm = reinterpret_cast<const int32_t *>(ws + W.perm);
     a.b0_off = 0;
     a.b1_off = (long long)c.I * c.d * 2;
@@ -444,6 +587,7 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   a.wbase = L.shared_blob;
   a.wstride = 0;
   a.splitk = 1;
+  a.tune = ctx->tune;
   if (!second) {
     a.A = reinterpret_cast<const uint16_t *>(x);
     a.lda = c.d;
@@ -468,31 +612,12 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   return a;
 }
 
-// Both expert matmuls of the groups in `mask`, on the compute stream.
-// The host needs the gate's per-expert counts.  Waking up on the event costs 10-20 us; the dispatch
-// kernel writes the call's number behind the counts in pinned, host-coherent memory, so the host
-// first polls that word for a while (the kernel is a few microseconds away) and only then blocks.
-hipError_t wait_for_counts(moe_ctx *ctx) {
-  volatile const int32_t *flag = ctx->pinned_counts + kMaxExperts;
-  const auto t0 = std::chrono::steady_clock::now();
-  for (int spin = 0;; ++spin) {
-    if (*flag == ctx->mailbox_seq) {
-      std::atomic_thread_fence(std::memory_order_acquire);
-      return hipSuccess;
-    }
-    if ((spin & 255) == 255 &&
-        std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300))
-      break;
-  }
-  return hipEventSynchronize(ctx->routed);
-}
-
 // Decode groups up to this many tokens use the mat-vec launches (one pass over the weights per 16
 // tokens through the matrix cores), larger ones the GEMM kernels; quantised copies are only read by
 // the mat-vec launches, which stay ahead of the bf16 GEMM for longer.
 constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsCopies = 32;
-int g_matvec_max_rows = 0;   // tuning hook: 0 = the limits above
 
+// Both expert matmuls of the groups in `mask`, on `stream`.
 int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
                 int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream,
                 const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr,
@@ -501,7 +626,7 @@ int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned lo
   // The mat-vec kernels pass over an expert's weights once per 16 of its tokens: a decode batch that
   // gives some expert many more goes to the GEMM kernels, which stream the weights once.
   const bool from_copies = a1.q8_mask != 0 && gemv_reads_copies(a1);
-  const int matvec_limit = g_matvec_max_rows > 0 ? g_matvec_max_rows : (from_copies ? kMatvecMaxRowsCopies : kMatvecMaxRows);
+  const int matvec_limit = ctx->api_tune.matvec_max_rows > 0 ? ctx->api_tune.matvec_max_rows : (from_copies ? kMatvecMaxRowsCopies : kMatvecMaxRows);
   if (decode && max_rows_per_group <= matvec_limit) {
     {
       Timer t(ctx, stream, MOE_K_GEMV1);
@@ -522,9 +647,22 @@ int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned lo
   return MOE_OK;
 }
 
+// Joins the library's side stream back into the compute stream when a layer call leaves early with
+// an error after the fork: whatever the side stream was given still finishes before anything the
+// caller enqueues next on the compute stream.
+struct SideJoin {
+  moe_ctx *ctx;
+  hipStream_t cs;
+  bool armed = false;
+  ~SideJoin() {
+    if (!armed) return;
+    if (hipEventRecord(ctx->join, ctx->side) == hipSuccess) (void)hipStreamWaitEvent(cs, ctx->join, 0);
+  }
+};
+
 int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bias, int bias_stride,
               void *dev_y, void *dev_ws, size_t ws_bytes, void *compute_stream, void *copy_stream,
-              bool decode) {
+              bool decode, moe_stats *opt) {
   Layer *Lp = nullptr;
   int rc = get_layer(ctx, layer, &Lp);
   if (rc) return rc;
@@ -537,26 +675,39 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   if (!aligned(dev_ws, 256)) return fail(MOE_E_ARG, "dev_workspace needs 256-byte alignment");
   if (bias && bias_stride != 0 && bias_stride != c.E)
     return fail(MOE_E_ARG, "bias_stride must be 0 or E");
-  const WsLayout W = ws_layout(c, T);
+  const WsLayout W = ws_layout(c, T, ctx->api_tune.splitk);
   if (ws_bytes < W.total) return fail(MOE_E_WORKSPACE, "workspace %zu < %zu bytes", ws_bytes, W.total);
   hipStream_t cs = reinterpret_cast<hipStream_t>(compute_stream);
   hipStream_t ks = reinterpret_cast<hipStream_t>(copy_stream);
   char *ws = reinterpret_cast<char *>(dev_ws);
   const int S = c.cache_slots, E = c.E;
   const int n = T * c.k;
+  ctx->cur_layer = layer;
 
   bool all_resident = true;
   for (int e = 0; e < E; ++e) all_resident &= L.expert_slot[e] >= 0;
   // Enqueue everything without looking at the gate's result only when that result cannot change the
   // launch: all experts resident and, for the mat-vec path, one token (every active expert then has
-  // exactly one row) and few experts (a launch over all of them starts blocks for the idle ones too:
-  // with 60 experts and 4 active that cost 100 us against 76 us for the host's look at the gate).
-  // A decode batch takes the other path: the per-expert row counts pick a much leaner mat-vec
-  // variant, and the shared experts' launch covers the host's wait.
+  // exactly one row).  A decode batch takes the other path: the per-expert row counts pick a much
+  // leaner mat-vec variant, and the shared experts' launch covers the host's wait.
   // One token with every expert resident: the mat-vec launches take the k experts from the gate's own
   // id list on the device, so the host neither waits for the gate nor launches blocks for the others.
-  const bool blind_one = decode && T == 1 && g_blind_one_token;
+  const bool blind_one = decode && T == 1 && !ctx->api_tune.host_looks_always;
   const bool enqueue_blind = all_resident && (!decode || blind_one);
+
+  // The counters of earlier calls that were enqueued blind: a call that looks at the cache needs them
+  // all (recency stamps decide its victims); a blind call only takes what has arrived.
+  rc = settle_pending(ctx, !enqueue_blind || opt != nullptr);
+  if (rc) return rc;
+  const moe_stats before = L.stats;
+  // this call's mailbox; the call that used it 32 calls ago must have been accounted for
+  const int seq = ++ctx->call_no;
+  const int box = seq % kMailboxes;
+  if (ctx->pend_count > 0 && ctx->pending[ctx->pend_head].box == box) {   // (the ring is full)
+    rc = settle_pending(ctx, true);
+    if (rc) return rc;
+  }
+  int32_t *mailbox = ctx->mailboxes + (size_t)box * kMailboxWords;
 
   // A prefill batch of some size: the shared experts get the library's side stream.  Their two
   // launches need nothing but x, so they fill the compute units that the gate and the grouping leave
@@ -565,16 +716,17 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // routed experts) does the same: the shared experts' mat-vecs, arithmetic-bound at 8 tokens, then
   // run beside the bandwidth-bound routed ones instead of in front of them.
   const bool shared_on_side = c.I_shared && (decode ? !enqueue_blind : T >= 256);
+  SideJoin side_join{ctx, cs};
   if (shared_on_side) {
     HIP_TRY(hipEventRecord(ctx->fork, cs));   // after everything the caller queued before (x, the last call)
     HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
+    side_join.armed = true;
   }
 
   // ---- gate, Top-k, grouping (one token: the gate's kernel writes the grouping tables itself)
   SingleTokenDispatch one{reinterpret_cast<int32_t *>(ws + W.counts), reinterpret_cast<int32_t *>(ws + W.offsets),
                           reinterpret_cast<int32_t *>(ws + W.perm), reinterpret_cast<int32_t *>(ws + W.inv_perm),
-                          ctx->pinned_counts, 0};
-  if (T == 1) one.seq = ++ctx->mailbox_seq;
+                          mailbox, seq};
   {
     Timer t(ctx, cs, MOE_K_ROUTER);
     HIP_TRY(launch_router_topk(reinterpret_cast<const uint16_t *>(dev_x), L.router_w, bias, bias_stride, T,
@@ -590,10 +742,9 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                             reinterpret_cast<int32_t *>(ws + W.counts),
                             reinterpret_cast<int32_t *>(ws + W.offsets),
                             reinterpret_cast<int32_t *>(ws + W.perm),
-                            reinterpret_cast<int32_t *>(ws + W.inv_perm), ctx->pinned_counts,
-                            ++ctx->mailbox_seq, cs));
+                            reinterpret_cast<int32_t *>(ws + W.inv_perm), mailbox, seq, cs));
   }
-  HIP_TRY(hipEventRecord(ctx->routed, cs));
+  HIP_TRY(hipEventRecord(ctx->routed[box], cs));
 
   // ---- shared experts: independent of the routing.  When the host has to wait for the gate they
   // run first and cover that wait; in an all-resident decode call they ride in the routed launches.
@@ -608,11 +759,21 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, ctx->side);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(ctx->join, ctx->side));
+      side_join.armed = false;   // from here on the ordinary join before the weighted sum does it
     } else if (!shared_in_routed_launch) {
       rc = run_experts(ctx, decode, s1, s2, 1ull, 1, T, T, cs);
       if (rc) return rc;
     }
   }
+  // (an error below still has to join: the event is recorded, only the wait is missing)
+  struct JoinOnExit {
+    moe_ctx *ctx;
+    hipStream_t cs;
+    bool armed;
+    ~JoinOnExit() {
+      if (armed) (void)hipStreamWaitEvent(cs, ctx->join, 0);
+    }
+  } join_on_exit{ctx, cs, shared_on_side};
 
   GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
   bool combined = false;   // the weighted sum has been done by the down projection's launch
@@ -628,12 +789,12 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     // Every expert is in a slot: nothing to decide on the host, one grouped launch.
     for (int s = 0; s < S; ++s)
       if (L.set->slot_layer[s] == L.index) {
-        rc = wait_ready(*L.set, s, reads_copy(L.set->slot_expert[s], T), cs);
+        rc = wait_ready(L, s, reads_copy(L.set->slot_expert[s], T), cs);
         if (rc) return rc;
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
     if (blind_one) a1.sel_ids = a2.sel_ids = reinterpret_cast<const int32_t *>(ws + W.ids);
-    if (blind_one && (size_t)c.I * 2 <= 65536 && (size_t)c.I_shared * 2 <= 65536 && !g_no_fused_down) {
+    if (blind_one && (size_t)c.I * 2 <= 65536 && (size_t)c.I_shared * 2 <= 65536 && !ctx->api_tune.no_fused_down) {
       // one token: the down mat-vec adds the k experts' rows (and the shared experts') up itself
       a1.group_mask = a2.group_mask = mask;
       {
@@ -653,27 +814,23 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     HIP_TRY(hipEventRecord(L.set->group_done, cs));
     for (int s = 0; s < S; ++s)
       if (L.set->slot_layer[s] == L.index) L.set->use_kind[s] = 2;
-    // counters need the counts: read them once the routing kernels are done
-    HIP_TRY(wait_for_counts(ctx));
-    for (int e = 0; e < E; ++e)
-      if (ctx->pinned_counts[e] > 0) {
-        int s = L.expert_slot[e];
-        L.stats.hits++;
-        touch(L, s);
-        if (L.set->prefetched[s]) {
-          L.stats.prefetch_useful++;
-          L.set->prefetched[s] = 0;
-        }
-      }
+    // The counters need the gate's counts, the launches did not: they are filled in when the mailbox
+    // has arrived, by whichever later call looks at the cache (or right here if the caller wants them).
+    ctx->pending[(ctx->pend_head + ctx->pend_count) % kMailboxes] = {layer, box, seq};
+    ctx->pend_count++;
   } else {
     // "Synchronisation point 1": the gate's choice is compared with the cache.
-    HIP_TRY(wait_for_counts(ctx));
+    {
+      const auto t0 = std::chrono::steady_clock::now();
+      HIP_TRY(wait_for_counts(ctx, box, seq));
+      L.stats.wait_ms += std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    }
     int counts[kMaxExperts];
     unsigned long long hit_mask = 0;
     int n_hits = 0, hit_rows = 0, hit_max = 0;
-    std::vector<int> misses;
+    int misses[kMaxExperts], n_miss = 0;
     for (int e = 0; e < E; ++e) {
-      counts[e] = ctx->pinned_counts[e];
+      counts[e] = mailbox[e];
       if (counts[e] <= 0) continue;
       if (L.expert_slot[e] >= 0) {
         hit_mask |= 1ull << e;
@@ -681,24 +838,16 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         hit_rows += counts[e];
         if (counts[e] > hit_max) hit_max = counts[e];
       } else {
-        misses.push_back(e);
+        misses[n_miss++] = e;
       }
     }
     for (int e = 0; e < E; ++e)
-      if ((hit_mask >> e) & 1ull) {
-        int s = L.expert_slot[e];
-        touch(L, s);
-        L.stats.hits++;
-        if (L.set->prefetched[s]) {
-          L.stats.prefetch_useful++;
-          L.set->prefetched[s] = 0;
-        }
-      }
-    L.stats.misses += (int32_t)misses.size();
-    if (n_hits && misses.empty()) {
+      if ((hit_mask >> e) & 1ull) account_hit(L, L.expert_slot[e]);
+    L.stats.misses += n_miss;
+    if (n_hits && n_miss == 0) {
       for (int e = 0; e < E; ++e)
         if ((hit_mask >> e) & 1ull) {
-          rc = wait_ready(*L.set, L.expert_slot[e], reads_copy(e, hit_max), cs);
+          rc = wait_ready(L, L.expert_slot[e], reads_copy(e, hit_max), cs);
           if (rc) return rc;
         }
       rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs);
@@ -712,7 +861,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       for (int e = 0; e < E; ++e) {
         if (!((hit_mask >> e) & 1ull)) continue;
         const int s = L.expert_slot[e];
-        rc = wait_ready(*L.set, s, reads_copy(e, counts[e]), cs);  // only this expert's fetch: the next one may still be in flight
+        rc = wait_ready(L, s, reads_copy(e, counts[e]), cs);  // only this expert's fetch: the next one may still be in flight
         if (rc) return rc;
         rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
         if (rc) return rc;
@@ -725,13 +874,13 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     // that only the down projection and the weighted sum run after it.  (The copy stream's wait
     // for a victim's reader cannot be moved ahead of the previous copy: that reader runs right
     // after the previous copy, so the wait would hold the copy back as well.)
-    for (size_t i = 0; i < misses.size(); ++i) {
+    for (int i = 0; i < n_miss; ++i) {
       const int e = misses[i];
       const int s = pick_victim(L, 0ull);
-      const bool last = i + 1 == misses.size();
+      const bool last = i + 1 == n_miss;
       rc = place(ctx, L, e, s, false, ks, false, last);
       if (rc) return rc;
-      a1.slot[e] = a2.slot[e] = (signed char)s;
+      a1.slot[e] = a2.slot[e] = (int16_t)s;
       if (a1.qbase && L.set->q_valid[s]) {   // fetched just now: its quantised copy is in the staging area
         a1.q8_mask |= 1ull << e;
         a2.q8_mask |= 1ull << e;
@@ -751,7 +900,10 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   }
 
   // ---- weighted sum per token (+ shared experts)
-  if (shared_on_side) HIP_TRY(hipStreamWaitEvent(cs, ctx->join, 0));
+  if (shared_on_side) {
+    join_on_exit.armed = false;
+    HIP_TRY(hipStreamWaitEvent(cs, ctx->join, 0));
+  }
   if (!combined) {
     Timer t(ctx, cs, MOE_K_COMBINE);
     HIP_TRY(launch_combine(reinterpret_cast<const float *>(ws + W.Y), W.splitk, (long long)n * c.d,
@@ -759,6 +911,21 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                            reinterpret_cast<const int32_t *>(ws + W.inv_perm),
                            c.I_shared ? reinterpret_cast<const float *>(ws + W.Ys) : nullptr, 1, 0, T, c.d,
                            c.k, reinterpret_cast<uint16_t *>(dev_y), cs));
+  }
+  if (opt) {
+    // the caller wants this call's counters now: wait for the gate's counts if they are still out
+    rc = settle_pending(ctx, true);
+    if (rc) return rc;
+    const moe_stats &a = L.stats;
+    *opt = moe_stats{};
+    opt->hits = a.hits - before.hits;
+    opt->misses = a.misses - before.misses;
+    opt->prefetch_useful = a.prefetch_useful - before.prefetch_useful;
+    opt->prefetch_ready = a.prefetch_ready - before.prefetch_ready;
+    opt->prefetch_stalled = a.prefetch_stalled - before.prefetch_stalled;
+    opt->layer_calls = 1;
+    opt->bytes_h2d = a.bytes_h2d - before.bytes_h2d;
+    opt->wait_ms = a.wait_ms - before.wait_ms;
   }
   return MOE_OK;
 }
@@ -769,6 +936,23 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 extern "C" {
 
 const char *moe_last_error(void) { return g_err; }
+
+static int create_parts(moe_ctx *ctx, const moe_config *cfg) {
+  HIP_TRY(hipGetDevice(&ctx->device));
+  ctx->layers.resize(cfg->n_layers);
+  HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->mailboxes),
+                        (size_t)kMailboxes * kMailboxWords * sizeof(int32_t), 0));
+  memset(ctx->mailboxes, 0, (size_t)kMailboxes * kMailboxWords * sizeof(int32_t));
+  for (int i = 0; i < kMailboxes; ++i) HIP_TRY(hipEventCreateWithFlags(&ctx->routed[i], hipEventDisableTiming));
+  if (cfg->I_shared) {
+    HIP_TRY(hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming));
+  }
+  if (cfg->host_format != MOE_FMT_BF16) HIP_TRY(hipStreamCreateWithFlags(&ctx->expand, hipStreamNonBlocking));
+  HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ctx->dev_scores), kMaxExperts * sizeof(float)));
+  return MOE_OK;
+}
 
 int moe_create(const moe_config *cfg, moe_ctx **out) {
   if (!out) return fail(MOE_E_ARG, "out is NULL");
@@ -784,18 +968,15 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   ctx->blob_bytes = (size_t)6 * cfg->d * cfg->I;
   ctx->host_blob_bytes = moe_host_blob_bytes(cfg);
   ctx->stage_stride = cfg->host_format != MOE_FMT_BF16 ? (ctx->host_blob_bytes + 255) / 256 * 256 : 0;
-  HIP_TRY(hipGetDevice(&ctx->device));
-  ctx->layers.resize(cfg->n_layers);
-  HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->pinned_counts), (kMaxExperts + 1) * sizeof(int32_t), 0));
-  memset(ctx->pinned_counts, 0, (kMaxExperts + 1) * sizeof(int32_t));
-  HIP_TRY(hipEventCreateWithFlags(&ctx->routed, hipEventDisableTiming));
-  if (cfg->I_shared) {
-    HIP_TRY(hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming));
-    HIP_TRY(hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming));
+  rc = create_parts(ctx, cfg);
+  if (rc) {
+    // what has been created so far is released again; the message of the failure is kept
+    char msg[sizeof(g_err)];
+    memcpy(msg, g_err, sizeof(msg));
+    (void)moe_destroy(ctx);
+    memcpy(g_err, msg, sizeof(msg));
+    return rc;
   }
-  if (cfg->host_format != MOE_FMT_BF16) HIP_TRY(hipStreamCreateWithFlags(&ctx->expand, hipStreamNonBlocking));
-  HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ctx->dev_scores), kMaxExperts * sizeof(float)));
   *out = ctx;
   return MOE_OK;
 }
@@ -803,6 +984,7 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
 int moe_destroy(moe_ctx *ctx) {
   if (!ctx) return MOE_OK;
   (void)hipDeviceSynchronize();
+  ctx->pend_count = 0;
   auto destroy_set = [](SlotSet *set) {
     if (!set) return;
     for (hipEvent_t e : set->copied) if (e) (void)hipEventDestroy(e);
@@ -819,7 +1001,7 @@ int moe_destroy(moe_ctx *ctx) {
     (void)hipEventDestroy(t.stop);
   }
   for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
-  if (ctx->routed) (void)hipEventDestroy(ctx->routed);
+  for (hipEvent_t e : ctx->routed) if (e) (void)hipEventDestroy(e);
   if (ctx->fork) (void)hipEventDestroy(ctx->fork);
   if (ctx->join) (void)hipEventDestroy(ctx->join);
   if (ctx->side) {
@@ -827,7 +1009,7 @@ int moe_destroy(moe_ctx *ctx) {
     (void)hipStreamDestroy(ctx->side);
   }
   if (ctx->expand) (void)hipStreamDestroy(ctx->expand);
-  if (ctx->pinned_counts) (void)hipHostFree(ctx->pinned_counts);
+  if (ctx->mailboxes) (void)hipHostFree(ctx->mailboxes);
   if (ctx->dev_scores) (void)hipFree(ctx->dev_scores);
   delete ctx;
   return MOE_OK;
@@ -867,6 +1049,8 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
   for (int e = 0; e < c.E; ++e)
     if (!host_expert_blob[e]) return fail(MOE_E_ARG, "host_expert_blob[%d] is NULL", e);
   const int S = c.cache_slots;
+  rc = settle_pending(ctx, true);
+  if (rc) return rc;
   if (initial_resident) {
     unsigned long long seen = 0;
     for (int s = 0; s < S; ++s) {
@@ -924,7 +1108,11 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
     set.stamp.assign(S, 0);
     set.prefetched.assign(S, 0);
     set.copy_pending.assign(S, 0);
+    set.pf_landed.assign(S, 0);
     set.use_kind.assign(S, 0);
+    set.q_valid.assign(S, 0);
+    // (staged / expand_pending keep their values: they order new copies behind expansions that may
+    // still be running on the library's own stream, whatever the slots are taken to hold now)
     set.clock = 0;
   } else {
     for (int s = 0; s < S; ++s)   // rebinding a layer of a shared cache drops what it held there
@@ -953,6 +1141,8 @@ int expert_cache_prefetch(moe_ctx *ctx, int layer, const int32_t *host_ids, int 
   if (rc) return rc;
   Layer &L = *Lp;
   if (n < 0 || (n > 0 && !host_ids)) return fail(MOE_E_ARG, "bad id list");
+  rc = settle_pending(ctx, true);   // the victims depend on the recency stamps of every call so far
+  if (rc) return rc;
   unsigned long long protected_mask = 0;
   for (int i = 0; i < n; ++i) {
     if (host_ids[i] < 0 || host_ids[i] >= ctx->cfg.E) return fail(MOE_E_ARG, "expert id %d out of range", host_ids[i]);
@@ -981,9 +1171,11 @@ int expert_cache_prefetch(moe_ctx *ctx, int layer, const int32_t *host_ids, int 
   return join_expand(ctx, ks);
 }
 
-int predictor_score(moe_ctx *ctx, const void *dev_x, int T, const void *dev_wp, int m, float *dev_scores,
-                    int32_t *pinned_topm, void *stream) {
+int predictor_score(moe_ctx *ctx, int layer, const void *dev_x, int T, const void *dev_wp, int m,
+                    float *dev_scores, int32_t *pinned_topm, void *stream) {
   if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(MOE_E_ARG, "layer %d out of range", layer);
+  ctx->cur_layer = layer;
   if (!dev_x || !dev_wp || !pinned_topm) return fail(MOE_E_ARG, "NULL pointer in predictor_score");
   if (T <= 0 || m <= 0 || m > ctx->cfg.E) return fail(MOE_E_ARG, "need T > 0 and 1 <= m <= E");
   if (!aligned(dev_x, 16) || !aligned(dev_wp, 16)) return fail(MOE_E_ARG, "16-byte alignment needed");
@@ -1097,17 +1289,17 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out) {
 
 int moe_prefill_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
                       int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
-                      void *compute_stream, void *copy_stream) {
+                      void *compute_stream, void *copy_stream, moe_stats *opt) {
   int rc = run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
-                     compute_stream, copy_stream, false);
+                     compute_stream, copy_stream, false, opt);
   return rc ? rc : join_expand(ctx, reinterpret_cast<hipStream_t>(copy_stream));
 }
 
 int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
                      int bias_stride, void *dev_y, void *dev_workspace, size_t ws_bytes,
-                     void *compute_stream, void *copy_stream) {
+                     void *compute_stream, void *copy_stream, moe_stats *opt) {
   int rc = run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
-                     compute_stream, copy_stream, true);
+                     compute_stream, copy_stream, true, opt);
   return rc ? rc : join_expand(ctx, reinterpret_cast<hipStream_t>(copy_stream));
 }
 
@@ -1140,8 +1332,11 @@ int moe_debug_logits(moe_ctx *ctx, const void *dev_workspace, int T, float *dev_
 
 int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out) {
   if (!ctx || !out) return fail(MOE_E_ARG, "NULL argument");
-  moe_stats acc{};
   if (layer >= ctx->cfg.n_layers) return fail(MOE_E_ARG, "layer %d out of range", layer);
+  int rc = settle_pending(ctx, true);
+  if (rc) return rc;
+  if ((rc = harvest_timers(ctx))) return rc;
+  moe_stats acc{};
   for (int l = 0; l < ctx->cfg.n_layers; ++l) {
     if (layer >= 0 && l != layer) continue;
     const moe_stats &s = ctx->layers[l].stats;
@@ -1152,6 +1347,10 @@ int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out) {
     acc.prefetch_dropped += s.prefetch_dropped;
     acc.layer_calls += s.layer_calls;
     acc.bytes_h2d += s.bytes_h2d;
+    acc.prefetch_ready += s.prefetch_ready;
+    acc.prefetch_stalled += s.prefetch_stalled;
+    acc.wait_ms += s.wait_ms;
+    acc.compute_ms += s.compute_ms;
   }
   *out = acc;
   return MOE_OK;
@@ -1159,6 +1358,9 @@ int moe_get_stats(moe_ctx *ctx, int layer, moe_stats *out) {
 
 int moe_reset_stats(moe_ctx *ctx) {
   if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  int rc = settle_pending(ctx, true);
+  if (rc) return rc;
+  if ((rc = harvest_timers(ctx))) return rc;
   for (Layer &L : ctx->layers) L.stats = moe_stats{};
   return MOE_OK;
 }
@@ -1168,6 +1370,8 @@ int moe_cache_invalidate(moe_ctx *ctx, int layer) {
   int rc = get_layer(ctx, layer, &Lp);
   if (rc) return rc;
   Layer &L = *Lp;
+  rc = settle_pending(ctx, true);
+  if (rc) return rc;
   for (size_t s = 0; s < L.set->slot_expert.size(); ++s) {
     if (L.set->slot_layer[s] != L.index) continue;   // a shared cache: only what this layer holds
     L.expert_slot[L.set->slot_expert[s]] = -1;
@@ -1183,6 +1387,8 @@ int moe_cache_state(moe_ctx *ctx, int layer, int32_t *host_slot_expert) {
   int rc = get_layer(ctx, layer, &Lp);
   if (rc) return rc;
   if (!host_slot_expert) return fail(MOE_E_ARG, "NULL argument");
+  rc = settle_pending(ctx, true);
+  if (rc) return rc;
   for (int s = 0; s < ctx->cfg.cache_slots; ++s)
     host_slot_expert[s] = Lp->set->slot_layer[s] == layer ? Lp->set->slot_expert[s] : -1;
   return MOE_OK;
@@ -1196,66 +1402,70 @@ int moe_set_profiling(moe_ctx *ctx, int on) {
 
 int moe_get_kernel_times(moe_ctx *ctx, float *ms, int32_t *launches) {
   if (!ctx || !ms || !launches) return fail(MOE_E_ARG, "NULL argument");
+  int rc = harvest_timers(ctx);
+  if (rc) return rc;
   for (int i = 0; i < MOE_K_COUNT; ++i) {
-    ms[i] = 0.0f;
-    launches[i] = 0;
+    ms[i] = ctx->kernel_ms[i];
+    launches[i] = ctx->kernel_launches[i];
+    ctx->kernel_ms[i] = 0.0f;
+    ctx->kernel_launches[i] = 0;
   }
-  for (auto &t : ctx->timed) {
-    HIP_TRY(hipEventSynchronize(t.stop));
-    float dt = 0.0f;
-    HIP_TRY(hipEventElapsedTime(&dt, t.start, t.stop));
-    ms[t.kind] += dt;
-    launches[t.kind]++;
-    ctx->event_pool.push_back(t.start);
-    ctx->event_pool.push_back(t.stop);
-  }
-  ctx->timed.clear();
   return MOE_OK;
 }
 
-int moe_set_gemm_variant(int mode, int variant) {
-  if (mode < 0 || mode > 10 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
-  if (mode == 10) {
-    set_gemv_skinny_waves(variant);
-    return MOE_OK;
-  }
-  if (mode == 8) {
-    set_gemv_skinny_min(variant);
-    return MOE_OK;
-  }
-  if (mode == 9) {
-    g_matvec_max_rows = variant;
-    return MOE_OK;
-  }
-  if (mode == 7) {
-    g_no_fused_down = variant != 0;
-    return MOE_OK;
-  }
-  if (mode == 6) {
-    if (variant > 2) return fail(MOE_E_ARG, "8-bit mat-vec source: 0 (by expert size), 1 (never) or 2 (always)");
-    g_no_q8_matvec = variant == 1;
-    set_gemv_q8_always(variant == 2);
-    return MOE_OK;
-  }
-  if (mode == 5) {
-    g_blind_one_token = variant != 0;
-    return MOE_OK;
-  }
-  if (mode == 4) {
-    if (variant != 0 && variant != 1 && variant != 2 && variant != 4)
-      return fail(MOE_E_ARG, "rows per wave of the mat-vec kernels: 0 (by shape), 1, 2 or 4");
-    set_gemv_rows(variant);
-    return MOE_OK;
-  }
-  if (mode == 3) {
-    if (variant > 8) return fail(MOE_E_ARG, "at most 8 K slices");
-    g_splitk_override = variant;
-    return MOE_OK;
-  }
-  if (variant != 0 && variant != 1 && variant != 6 && variant != 12)
-    return fail(MOE_E_ARG, "GEMM variants: 0 (by shape), 1, 6, 12");
-  set_gemm_variant(mode, variant);
+int moe_inject_failure(int nth_hip_call) {
+  g_fail_countdown = nth_hip_call > 0 ? nth_hip_call : 0;
   return MOE_OK;
+}
+
+int moe_debug_gemm_choice(int mode, int gathered, long long a_rows, int lda, int N, int ldb, int K,
+                          long long b1_minus_b0, int max_rows, int n_groups) {
+  GemmArgs a{};
+  static const int32_t some_perm = 0;
+  a.perm = gathered ? &some_perm : nullptr;
+  a.a_rows = (int)a_rows;
+  a.lda = lda;
+  a.N = N;
+  a.ldb = ldb;
+  a.K = K;
+  a.b0_off = 0;
+  a.b1_off = b1_minus_b0;
+  if (mode < 0 || mode > 2) return fail(MOE_E_ARG, "mode %d", mode);
+  return gemm_kernel_choice((GemmMode)mode, a, max_rows, n_groups);
+}
+
+int moe_tune(moe_ctx *ctx, int mode, int variant) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  if (mode < 0 || mode > 10 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  switch (mode) {
+    case 10: ctx->tune.skinny_waves = variant; return MOE_OK;
+    case 9: ctx->api_tune.matvec_max_rows = variant; return MOE_OK;
+    case 8:
+      ctx->tune.skinny_min_tok = variant;
+      ctx->tune.skinny_forced = variant == 1;   // 1: every launch with a token or more, whatever the format
+      return MOE_OK;
+    case 7: ctx->api_tune.no_fused_down = variant != 0; return MOE_OK;
+    case 6:
+      if (variant > 2) return fail(MOE_E_ARG, "mat-vec source: 0 (by expert size), 1 (never the copy) or 2 (always)");
+      ctx->api_tune.no_q_matvec = variant == 1;
+      ctx->tune.q_always = variant == 2;
+      return MOE_OK;
+    case 5: ctx->api_tune.host_looks_always = variant == 0; return MOE_OK;
+    case 4:
+      if (variant != 0 && variant != 1 && variant != 2 && variant != 4)
+        return fail(MOE_E_ARG, "rows per wave of the mat-vec kernels: 0 (by shape), 1, 2 or 4");
+      ctx->tune.gemv_rows = variant;
+      return MOE_OK;
+    case 3:
+      if (variant > kMaxSplitK) return fail(MOE_E_ARG, "at most %d K slices", kMaxSplitK);
+      ctx->api_tune.splitk = variant;
+      return MOE_OK;
+    default:
+      if (variant != 0 && variant != 1 && variant != 6 && variant != 12)
+        return fail(MOE_E_ARG, "GEMM variants: 0 (by shape), 1, 6, 12");
+      ctx->tune.gemm_variant[mode] = variant;
+      return MOE_OK;
+  }
 }
 
 int moe_dense_gemm_bf16(const void *dev_a, const void *dev_b, void *dev_c, int M, int N, int K, void *stream) {

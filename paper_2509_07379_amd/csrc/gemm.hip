@@ -27,15 +27,6 @@
 #include "device_utils.h"
 #include "kernels.h"
 
-// Timing hook for a measurement harness that includes this file: expands to nothing in the library.
-#ifndef MOE_GEMM_PROBE
-#define MOE_GEMM_PROBE(point_)
-#endif
-#ifndef MOE_GEMM_TICK   // before (0) and after (1) every barrier of the ping-pong kernel
-#define MOE_GEMM_TICK(after_)
-#define MOE_GEMM_TICK_DECL
-#endif
-
 namespace moe {
 
 namespace {
@@ -509,7 +500,6 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  MOE_GEMM_TICK_DECL
   unsigned char *xpose = smem + 2 * STAGE + wave * 4096;   // this wave's epilogue buffer
   const int grp = wave >> 2;          // the two waves of a SIMD are in different groups
   const int wm = grp, wn = wave & 3;
@@ -614,9 +604,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 #define MOE_PBARRIER()                                                                               \
   do {                                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                               \
-    MOE_GEMM_TICK(0);                                                                                \
     __builtin_amdgcn_s_barrier();                                                                    \
-    MOE_GEMM_TICK(1);                                                                                \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define MOE_PREAD_A(I0_, I1_)                                                                        \
@@ -712,9 +700,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       decode_logical_tile<BM, BN_OUT>(args, xbase + nslot, tn);
       tn.n0 = min(tn.n0, args.N - BN_OUT);
     }
-    MOE_GEMM_PROBE(0);
     MOE_PVMCNT(0);   // this tile's first loads have landed (and the previous tile's stores are out)
-    MOE_GEMM_PROBE(1);
 
     // LDS byte offset of this lane's 16 bytes of K slice 0 inside a stage; slice ks is at ^ (ks << 5)
     // (the swizzle XORs the chunk index, and slice ks only changes bits 1..2 of it).  Derived from
@@ -742,7 +728,6 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     MOE_PBARRIER();
-    MOE_GEMM_PROBE(4);
     if (grp == 1) MOE_PBARRIER();   // group 1 runs one tick behind
     switch (fm_valid) {
       case 0: MOE_PP_LOOP(0); break;
@@ -752,7 +737,6 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       default: MOE_PP_LOOP(4); break;
     }
     if (grp == 0) MOE_PBARRIER();   // same number of barriers for both groups; LDS is free now
-    MOE_GEMM_PROBE(2);
 
     // The next tile's gathered rows are requested, half of this tile is stored while they arrive,
     // then the next tile's first loads go out and fly while the other half is stored.
@@ -772,7 +756,6 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       MOE_PPROLOGUE();
     }
     store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, FM / 2, FM, xpose);
-    MOE_GEMM_PROBE(3);
     if (!has_next) break;
     t = tn;
     slot = nslot;
@@ -989,23 +972,17 @@ hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask
 
 }  // namespace
 
-// Variant 0 picks by shape; a test or tuning run forces one: 1 = 128 x 128 tiles, 6 = 256 x 256 tiles
-// of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
-static int g_variant[3] = {0, 0, 0};
-
-void set_gemm_variant(int mode, int variant) {
-  if (mode >= 0 && mode < 3) g_variant[mode] = variant;
-}
-
-template <int MODE>
-static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
-  if (args.K % BK != 0) return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
-  int v = g_variant[MODE];
-  // the ping-pong kernel addresses a gathered A (or the 256 rows of a tile of an A used in place)
-  // and the blob with 31-bit byte offsets
-  const bool pp_ok = (long long)(args.perm ? max_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
+// args.tune.gemm_variant: 0 picks by shape; a test or tuning run forces 1 = 128 x 128 tiles, 6 = 256 x 256
+// tiles of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
+int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask) {
+  if (args.K % BK != 0) return 100;
+  int v = args.tune.gemm_variant[mode];
+  // The ping-pong kernel addresses a gathered A from its first row (any of its a_rows rows can be
+  // named by the permutation), an A used in place from the tile's first row (256 rows), and the
+  // blob from its first B row, all with 31-bit byte offsets.
+  const bool pp_ok = (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
                      (args.b1_off - args.b0_off) + (long long)args.N * args.ldb * 2 < 0x7FFFFFFFll &&
-                     args.b1_off >= args.b0_off && args.N >= (MODE == GEMM_SWIGLU ? 128 : 256);
+                     args.b1_off >= args.b0_off && args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
   if (v == 0) {
     // 256 x 256 ping-pong tiles unless the groups are small on average, where the finer 128 x 128
     // tiles waste less of the matrix cores on empty rows
@@ -1013,7 +990,13 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
     v = avg_rows > 96 ? (pp_ok ? 12 : 6) : 1;
   }
   if (v == 12 && !pp_ok) v = 6;
-  switch (v) {
+  return v == 6 || v == 12 ? v : 1;
+}
+
+template <int MODE>
+static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  switch (gemm_kernel_choice((GemmMode)MODE, args, max_rows, n_groups_in_mask)) {
+    case 100: return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
     case 6: return launch_cfg<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
     case 12: return launch_pp<MODE>(args, max_rows, n_groups_in_mask, stream);
     default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);

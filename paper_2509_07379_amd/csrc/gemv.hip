@@ -734,26 +734,13 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
 
 }  // namespace
 
-static int g_gemv_rows = 0;   // tuning hook: rows per wave (0 = by shape)
-void set_gemv_rows(int rows) { g_gemv_rows = rows; }
-static int g_skinny_min_tok = 0;   // tuning hook: tokens per expert from which the matrix-core kernel is used, 0 = by rule
-static int g_skinny_forced = 0;    // test hook: the matrix-core kernel wherever the shapes allow it
-static int g_skinny_waves = 0;     // tuning hook: K slices (waves) per block, 0 = by shape
-void set_gemv_skinny_min(int tokens) {
-  g_skinny_min_tok = tokens > 0 ? tokens : 0;
-  g_skinny_forced = tokens == 1;   // 1: every launch with a token or more, whatever the format
-}
-void set_gemv_skinny_waves(int waves) { g_skinny_waves = waves >= 1 && waves <= SK_MAXWAVES ? waves : 0; }
-static int g_gemv_q8_always = 0;   // test hook: 8-bit copies are used whatever the experts' size
-void set_gemv_q8_always(int on) { g_gemv_q8_always = on; }
-
 // 8-bit and 4-bit copies pay where the launch is bound by the bytes it streams: experts of 16 M weights
 // per matrix and more (Mixtral-sized: 1.4 to 2 times faster at 1 to 8 tokens).  Small experts
 // (Qwen-sized, 3 M) are bound by the launch itself at 1 or 2 tokens and by arithmetic above; there
 // the expansion only adds instructions.
 bool gemv_reads_copies(const GemmArgs &args) {
   return args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0 &&
-         ((long long)args.N * args.K >= (1ll << 24) || g_gemv_q8_always);
+         ((long long)args.N * args.K >= (1ll << 24) || args.tune.q_always);
 }
 
 // One token (its row in the sorted order is offsets[expert]), args = the down projection's arguments
@@ -824,10 +811,10 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     bool pays;
     if (use_q8) pays = !(args.qfmt == 1 && mode == GEMM_PLAIN_F32 && max_tok < 5);
     else pays = max_tok > GV_MAXTOK || (mode == GEMM_PLAIN_F32 && args.K >= 4096);
-    if (g_skinny_forced) pays = true;
+    if (args.tune.skinny_forced) pays = true;
     // from 3 tokens per expert; quantised gate/up rows from 2 (MXFP4, Mixtral shape, 2 tokens: 57
     // against 70 us per launch; one token is faster per token: 37 against 41 us)
-    const int min_tok = g_skinny_min_tok > 0 ? g_skinny_min_tok : ((use_q8 && mode == GEMM_SWIGLU) ? 2 : 3);
+    const int min_tok = args.tune.skinny_min_tok > 0 ? args.tune.skinny_min_tok : ((use_q8 && mode == GEMM_SWIGLU) ? 2 : 3);
     if (max_tok >= min_tok && shapes_ok && pays) {
       // row tile pairs per block: quantised rows share their token pieces between two pairs, except in
       // down projections with few tokens, where the launch would be left with too few blocks
@@ -844,7 +831,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
       // K slices (waves) per block: at least 8 steps each, 4 at most
       const int steps = args.K / (use_q8 ? (args.qfmt == 2 ? 256 : 128) : 64);
       int slices = steps / 8 < 1 ? 1 : (steps / 8 > 4 ? 4 : steps / 8);
-      if (g_skinny_waves > 0) slices = g_skinny_waves;
+      if (args.tune.skinny_waves >= 1 && args.tune.skinny_waves <= SK_MAXWAVES) slices = args.tune.skinny_waves;
       const int threads = 64 * slices;
 #define MOE_SKINNY_LAUNCH(MODE, Q)                                                                         \
   do {                                                                                                     \
@@ -874,7 +861,7 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
   const size_t smem = (size_t)ntcap * kseg * 2;
   int rows_per_wave = max_k >= 2048 ? 1 : 2;
   if (use_q8 && max_k >= 2048) rows_per_wave = 2;   // a row is half as many bytes: two per wave keep as much in flight
-  if (g_gemv_rows > 0) rows_per_wave = g_gemv_rows;
+  if (args.tune.gemv_rows > 0) rows_per_wave = args.tune.gemv_rows;
   if (ntcap > 2 && rows_per_wave > 2) rows_per_wave = 2;   // accumulators: rows x tokens x {gate, up}
   // quantised rows are short (K or K / 2 bytes): with several tokens 16 waves share one staged copy of
   // the token vectors (4 tokens, Mixtral shape: MXFP4 241 -> 201 us per layer, e4m3 255 -> 234 us; one

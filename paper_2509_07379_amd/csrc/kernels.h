@@ -1,4 +1,4 @@
-// Internal launcher interface between the host logic (api.cpp) and the gfx950 kernels.
+// Internal launcher interface between the host logic (api.hip) and the gfx950 kernels.
 // Every launcher only enqueues on `stream` and returns the hipError_t of the launch.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -8,6 +8,8 @@ namespace moe {
 
 constexpr int kMaxExperts = 64;   // one lane per expert in the wave-wide top-k
 constexpr int kDispatchChunk = 256;  // assignments per dispatch block
+constexpr int kMaxCacheSlots = 32767;  // GemmArgs::slot is 16 bits wide
+constexpr int kMaxHidden = 16384;      // the gate's kernel stages 4 token vectors (8 d bytes) in LDS
 
 // ---- gate: logits (fixed fp32 summation order), top-k, gate values -------------------
 // x [T,d] bf16, wr [E,d] bf16, bias NULL or fp32 [t*bias_stride + e].
@@ -54,10 +56,22 @@ hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, 
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                            int32_t *host_counts, int seq, hipStream_t stream);
 
+// Tuning and test hooks of one context (moe_tune); all zero = every choice by shape.  Host side only:
+// the launchers read them, the kernels never do.
+struct Tune {
+  int gemm_variant[3];   // per GemmMode: 0 = by shape, 1 = 128 x 128 tiles, 6 = 256 x 256 single-phase, 12 = ping-pong
+  int gemv_rows;         // weight rows per wave of the per-token mat-vec (0 = by shape, 1, 2 or 4)
+  int skinny_min_tok;    // tokens per expert from which the matrix-core mat-vec is used (0 = by rule)
+  int skinny_forced;     // the matrix-core mat-vec wherever the shapes allow it
+  int skinny_waves;      // K slices (waves) per block of the matrix-core mat-vec (0 = by shape)
+  int q_always;          // mat-vecs read quantised copies whatever the experts' size
+};
+
 // ---- grouped GEMM on bf16 MFMA --------------------------------------------------------
 struct GemmArgs {
   const uint16_t *A;      // activations, row-major bf16
   int lda;                // elements between A rows
+  int a_rows;             // rows of A that a gathered read (perm) can reach: the token count
   const int32_t *perm;    // non-NULL: sorted row p reads A row perm[p] / k_top (token gather)
   int k_top;
   const int32_t *offsets; // device [n_groups+1] sorted-row offsets; NULL = one group
@@ -68,7 +82,7 @@ struct GemmArgs {
   int n_groups;
   const char *wbase;      // expert e's blob at wbase + slot[e] * wstride
   long long wstride;
-  signed char slot[kMaxExperts];
+  int16_t slot[kMaxExperts];   // cache slot of expert e (moe_config.cache_slots <= 32767)
   long long b0_off, b1_off;  // byte offsets in the blob of the B rows (gate|down) and (up)
   int ldb;                // elements between B rows (= K)
   int N;                  // output columns (SwiGLU: I; the block reads N gate rows and N up rows)
@@ -90,6 +104,7 @@ struct GemmArgs {
   const char *qbase;
   long long qstride;
   long long q_b0_off, q_b1_off, q_s0_off, q_s1_off;
+  Tune tune;              // host side only
 };
 
 enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
@@ -98,8 +113,10 @@ enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
 hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,
                                hipStream_t stream);
 
-// Tuning hook: force tile variant `variant` (0 = choose by shape) for GemmMode `mode`.
-void set_gemm_variant(int mode, int variant);
+
+// The kernel launch_grouped_gemm picks: 1 = 128 x 128 tiles, 6 = 256 x 256 single-phase, 12 = persistent
+// ping-pong, 100 = the register-staged kernel for K that is no multiple of 64.
+int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask);
 
 // ---- decode: bandwidth-bound expert mat-vec --------------------------------------------
 // Same argument block; rows per group are few (decode batch).  SWIGLU -> bf16 h, PLAIN_F32 -> fp32 y.
@@ -116,10 +133,6 @@ hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, 
 // Whether launch_grouped_gemv streams quantised copies for the experts of args.q8_mask (format,
 // alignment, expert size or the test hook), whatever the mask and the token count.
 bool gemv_reads_copies(const GemmArgs &args);
-void set_gemv_q8_always(int on);
-void set_gemv_skinny_min(int tokens);   // 0 = default
-void set_gemv_skinny_waves(int waves);  // 0 = default   // test hook: use the 8-bit copies whatever the experts' size
-void set_gemv_rows(int rows);   // tuning hook: weight rows per wave (0 = choose by shape)
 
 // ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----
 hipError_t launch_combine(const float *Y, int y_planes, long long y_plane_stride, const float *w,

@@ -224,6 +224,14 @@ hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float
     constexpr int TPB = 4;
     size_t smem = (size_t)TPB * d * 2 + TPB * 64 * sizeof(float);
     int grid = (T + TPB - 1) / TPB;
+    static bool attr_set = false;   // token vectors of d up to kMaxHidden: more than the 64 KB default
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(router_topk_kernel<TPB, 8>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         TPB * kMaxHidden * 2 + TPB * 64 * (int)sizeof(float));
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
     hipLaunchKernelGGL((router_topk_kernel<TPB, 8>), dim3(grid), dim3(512), smem, stream, x, wr, bias,
                        bias_stride, T, d, E, k, renormalize, logits, ids, w, none);
   } else {

@@ -25,6 +25,48 @@ def test_header_functions_are_exported():
     assert sorted(binding.EXPORTS) == names
 
 
+def test_internal_hooks_are_declared_apart_from_the_public_header():
+    from paper_2509_07379_amd import binding
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    text = open(os.path.join(ROOT, "paper_2509_07379_amd", "csrc", "moe_tuning.h")).read()
+    public = declared_functions()
+    for n in binding.INTERNAL_EXPORTS:
+        assert hasattr(lib, n) and re.search(r"\b%s\s*\(" % n, text) and n not in public, n
+
+
+def test_limits_of_the_argument_block_are_refused_at_create():
+    """A slot index travels to the kernels in 16 bits and the gate stages token vectors in LDS: a cache
+    of more slots, or a wider hidden size, is refused before any HIP call (so this runs without a GPU)."""
+    from paper_2509_07379_amd import binding
+    lib = binding.load()
+    h = ctypes.c_void_p()
+    for cfg, word in ((binding.MoeConfig(256, 128, 8, 2, 28, 40000, 0, 1, 1, 0), b"cache_slots"),
+                      (binding.MoeConfig(16392, 128, 8, 2, 1, 8, 0, 1, 0, 0), b"d = 16392")):
+        assert lib.moe_create(ctypes.byref(cfg), ctypes.byref(h)) == -2
+        assert word in lib.moe_last_error()
+        assert lib.moe_workspace_bytes(ctypes.byref(cfg), 4) == 0
+
+
+def test_gemm_kernel_choice_keeps_31_bit_offsets_in_reach():
+    """The ping-pong kernel (12) addresses a gathered activation matrix with 31-bit byte offsets from its
+    first row: every row the permutation can name must be in reach, however few rows one group has."""
+    from paper_2509_07379_amd import binding
+    lib = binding.load()
+    d, I = 4096, 14336
+    pick = lambda mode, gathered, a_rows, lda, N, ldb, K, gap, rows, groups: lib.moe_debug_gemm_choice(
+        mode, gathered, a_rows, lda, N, ldb, K, gap, rows, groups)
+    # gate/up GEMM of one expert with 600 rows out of T tokens
+    assert pick(0, 1, 2048, d, I, d, d, 2 * I * d, 600, 1) == 12
+    assert pick(0, 1, 262143, d, I, d, d, 2 * I * d, 600, 1) == 12      # (T - 1) * d * 2 < 2^31
+    assert pick(0, 1, 262144, d, I, d, d, 2 * I * d, 600, 1) == 6       # one more token: out of reach
+    assert pick(0, 1, 1 << 22, d, I, d, d, 2 * I * d, 600, 1) == 6
+    # the down GEMM reads H in place, tile by tile: any number of rows
+    assert pick(1, 0, 1 << 22, I, d, I, I, 0, 600, 1) == 12
+    # small groups take the 128 x 128 tiles, a ragged K the padding kernel
+    assert pick(0, 1, 2048, d, I, d, d, 2 * I * d, 600, 60) == 1
+    assert pick(1, 0, 2048, 1000, 512, 1000, 1000, 0, 600, 1) == 100
+
+
 def test_argument_errors_without_gpu():
     from paper_2509_07379_amd import binding
     lib = binding.load()

@@ -21,35 +21,58 @@ def sample_tokens(T, n, seed=0):
     return np.sort(rng.choice(T, size=min(n, T), replace=False)).astype(np.int32)
 
 
-def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=False):
+def ids_against_fp64_logits(oracle, x_np, router_np, bias_np, k, gpu_ids, tag):
+    """The Top-k is taken on fp32 logits summed in a fixed order, which the oracle replays.  Independently
+    of that order: wherever the fp64 logits separate the k-th from the (k+1)-th expert by more than
+    1e-4 of the largest logit, the selected SET must be the fp64 one.  Returns the tokens under the margin."""
+    _, l64 = oracle.router_logits(x_np, router_np, bias_np, want_f64=True)
+    E = l64.shape[1]
+    order = np.lexsort((np.broadcast_to(np.arange(E), l64.shape), -l64), axis=1)   # logit descending, id ascending
+    if k == E:
+        return 0
+    srt = np.take_along_axis(l64, order, 1)
+    clear = (srt[:, k - 1] - srt[:, k]) > 1e-4 * np.abs(l64).max()
+    want = np.sort(order[:, :k], 1)
+    got = np.sort(gpu_ids, 1)
+    bad = np.nonzero(clear & np.any(want != got, axis=1))[0]
+    assert bad.size == 0, f"{tag}: tokens {bad[:8]} differ from the fp64 Top-k although the margin is clear"
+    under = int((~clear).sum())
+    print(f"{tag}: {under} of {l64.shape[0]} tokens have a k/(k+1) margin under 1e-4 of the largest logit")
+    return under
+
+
+def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=False, layer=0):
+    """One prefill layer of workload w; `layer` picks the seeded weights, activations and (config 4) the
+    rank permutation of the popularity bias."""
     H, B = gpu["harness"], gpu["binding"]
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, slots, w.I_shared)
-    pool = H.HostPool(w, 0)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, layer + 1, slots, w.I_shared)   # only `layer` is bound
+    pool = H.HostPool(w, layer)
     initial = list(range(w.E)) if slots == w.E else None
-    lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=initial is None)
+    lay = H.DeviceLayer(ctx, w, layer, pool, initial, poison=initial is None)
     buf = H.Buffers(ctx, w.T)
-    x_np = S.activations(w)
+    x_np = S.activations(w, layer, 0)
     x = H.np_to_dev(x_np)
-    bias_np = S.zipf_route_bias(w, 0) if w.zipf_s > 0 else None
+    bias_np = S.zipf_route_bias(w, layer) if w.zipf_s > 0 else None
     bias = None if bias_np is None else H.np_to_dev(bias_np)
     torch.cuda.synchronize()
     if prefetch is not None:
-        ctx.expert_cache_prefetch(0, prefetch, gpu["copy"])
+        ctx.expert_cache_prefetch(layer, prefetch, gpu["copy"])
     if with_attention:  # stand-in non-MoE block the first fetches hide behind (Section V-B)
         wa = H.np_to_dev(S.normal_bf16((w.d, w.d), w.seed, S.stream_id(S.KIND_ATTN), 0.02))
         tmp = torch.empty((w.T, w.d), dtype=torch.int16, device="cuda")
         B.moe_dense_gemm_bf16(x, wa, tmp, w.T, w.d, w.d, gpu["compute"])
-    ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, 0)
+    ctx.moe_prefill_layer(layer, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, 0)
     gpu["compute"].synchronize()
     out = H.dev_to_np_u16(buf.y)
     routing = buf.routing(ctx, gpu["compute"])
-    stats, state = ctx.moe_get_stats(0), ctx.moe_cache_state(0)
+    stats, state = ctx.moe_get_stats(layer), ctx.moe_cache_state(layer)
     ctx.close()
-    sel = sample_tokens(w.T, n_sample)
+    sel = sample_tokens(w.T, n_sample, seed=layer)
     ref = oracle.moe_layer(x_np, lay.router_np, [pool.ptr(e) for e in range(w.E)], w.k, bias=bias_np, sel=sel,
                            shared_blob=lay.shared_np, I=w.I, I_shared=w.I_shared)
     for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
         np.testing.assert_array_equal(routing[key], ref[key], err_msg=key)
+    ids_against_fp64_logits(oracle, x_np, lay.router_np, bias_np, w.k, routing["ids"], f"{w.name} layer {layer}")
     np.testing.assert_allclose(routing["w"], ref["w"], rtol=2e-5, atol=1e-7)
     check_out(out[sel], ref["out_f64"], w.name)
     return dict(out=out, routing=routing, stats=stats, state=state, ref=ref)
@@ -58,7 +81,7 @@ def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=
 def test_c2_mixtral_prefill_resident(gpu, oracle):
     """The configuration bench.py times: all 8 experts resident, one grouped launch."""
     w = S.WORKLOADS["c2_mixtral_prefill"]
-    r = prefill_case(gpu, oracle, w, w.E, 24)
+    r = prefill_case(gpu, oracle, w, w.E, 320)
     assert r["stats"]["misses"] == 0 and r["stats"]["bytes_h2d"] == 0
     assert r["routing"]["counts"].sum() == w.T * w.k
 
@@ -90,11 +113,13 @@ def test_c2_shape_large_batch_rows_beyond_2gib(gpu, oracle):
     assert int(last_rows) * w.I * 2 > 2 ** 31
 
 
-def test_c4_deepseek_prefill_layer(gpu, oracle):
-    """64 routed experts top-6 with Zipf-skewed popularity + shared experts, 16 slots."""
+@pytest.mark.parametrize("layer", [0, 1, 2, 3, 27])
+def test_c4_deepseek_prefill_layer(gpu, oracle, layer):
+    """64 routed experts top-6 with Zipf-skewed popularity + shared experts, 16 slots; five of the 28
+    layers, each with its own weights, activations and rank permutation of the popularity bias."""
     from oracle.cache_sim import CacheSim
     w = S.WORKLOADS["c4_deepseek_prefill"]
-    r = prefill_case(gpu, oracle, w, w.S, 32, prefetch=list(range(w.S)))
+    r = prefill_case(gpu, oracle, w, w.S, 32, prefetch=list(range(w.S)), layer=layer)
     counts = r["routing"]["counts"]
     assert counts.max() > 8 * max(1, counts[counts > 0].min())  # the load really is imbalanced
     sim = CacheSim(w.E, w.S, w.blob_bytes)
@@ -104,9 +129,10 @@ def test_c4_deepseek_prefill_layer(gpu, oracle):
     assert r["state"] == sim.slot_expert
 
 
-def decode_case(gpu, oracle, w, n_layers, steps):
+def decode_case(gpu, oracle, w, n_layers, steps, check_every=1):
     """Decode steps with trace-driven routing, the linear predictor one layer ahead, prefetch and
-    re-fetch; every layer call is checked against the oracle, the counters against the simulator."""
+    re-fetch; routing tables of every layer call and outputs of every check_every-th step are checked
+    against the oracle, the counters and slot contents against the simulator (after every call)."""
     from oracle.cache_sim import CacheSim
     H, B = gpu["harness"], gpu["binding"]
     w = replace(w, L=n_layers, steps=steps)
@@ -128,18 +154,22 @@ def decode_case(gpu, oracle, w, n_layers, steps):
             bias_np = S.trace_route_bias(trace[s, l], w.E)
             bias = H.np_to_dev(bias_np)
             if l + 1 < n_layers:
-                ctx.predictor_score(x, w.T, wps[l + 1], w.top_m, top, pred)
+                ctx.predictor_score(l + 1, x, w.T, wps[l + 1], w.top_m, top, pred)
             ctx.moe_decode_layer(l, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, w.E)
             gpu["compute"].synchronize()
             out = H.dev_to_np_u16(buf.y)
             routing = buf.routing(ctx, gpu["compute"])
+            full = s % check_every == 0 or s == steps - 1
             ref = oracle.moe_layer(x_np, lays[l].router_np, [pools[l].ptr(e) for e in range(w.E)], w.k,
-                                   bias=bias_np, shared_blob=lays[l].shared_np, I=w.I, I_shared=w.I_shared)
+                                   bias=bias_np, shared_blob=lays[l].shared_np, I=w.I, I_shared=w.I_shared,
+                                   sel=None if full else np.zeros(0, dtype=np.int32))
             for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
                 np.testing.assert_array_equal(routing[key], ref[key], err_msg=f"{key} step {s} layer {l}")
             assert np.array_equal(np.sort(ref["ids"], 1), np.sort(trace[s, l], 1))  # the trace drives routing
-            check_out(out, ref["out_f64"], f"{w.name} step {s} layer {l}")
+            if full:
+                check_out(out, ref["out_f64"], f"{w.name} step {s} layer {l}")
             sims[l].serve(np.nonzero(ref["counts"])[0])
+            assert ctx.moe_cache_state(l) == sims[l].slot_expert, f"step {s} layer {l}"
             if l + 1 < n_layers:
                 pred.synchronize()
                 _, ref_top = oracle.predictor_score(x_np, wps_np[l + 1], w.top_m)
@@ -151,15 +181,18 @@ def decode_case(gpu, oracle, w, n_layers, steps):
         st = ctx.moe_get_stats(l)
         assert st == {**sims[l].counters(), "layer_calls": steps}, f"layer {l}"
         assert ctx.moe_cache_state(l) == sims[l].slot_expert
+        full = ctx.moe_get_stats(l, full=True)
+        # every prefetched expert that was used either had landed or made the compute stream wait
+        assert full["prefetch_ready"] + full["prefetch_stalled"] == full["prefetch_useful"]
     ctx.close()
 
 
 def test_c3_mixtral_decode_steps(gpu, oracle):
-    decode_case(gpu, oracle, S.WORKLOADS["c3_mixtral_decode"], n_layers=2, steps=3)
+    decode_case(gpu, oracle, S.WORKLOADS["c3_mixtral_decode"], n_layers=2, steps=32, check_every=4)
 
 
 def test_c5_qwen_decode_steps(gpu, oracle):
-    decode_case(gpu, oracle, S.WORKLOADS["c5_qwen_decode"], n_layers=3, steps=3)
+    decode_case(gpu, oracle, S.WORKLOADS["c5_qwen_decode"], n_layers=3, steps=32, check_every=4)
 
 
 @pytest.mark.parametrize("fmt", [1, 3])

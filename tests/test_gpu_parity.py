@@ -25,14 +25,26 @@ def check_out(got_bits, ref_f64, tag=""):
     assert np.all(err <= RTOL * np.abs(ref_f64) + RTOL * rms), f"{tag}: max err {err.max()} rms {rms}"
 
 
+# Tuning hooks (csrc/moe_tuning.h) belong to a context: a test names the ones it wants with set_tune
+# and every context made by new_ctx gets them; the fixture clears the list after each test.
+TUNE = {}
+
+
+def set_tune(mode, variant):
+    TUNE[mode] = variant
+
+
+def new_ctx(B, *args, **kw):
+    ctx = B.MoeContext(*args, **kw)
+    for mode, variant in TUNE.items():
+        ctx.moe_tune(mode, variant)
+    return ctx
+
+
 @pytest.fixture(autouse=True)
 def _default_hooks():
-    """The tuning hooks are process-wide: whatever a test sets is back at its default for the next one."""
     yield
-    from paper_2509_07379_amd import binding
-    if torch.cuda.is_available():
-        for mode in range(11):
-            binding.moe_set_gemm_variant(mode, 1 if mode == 5 else 0)
+    TUNE.clear()
 
 
 @pytest.fixture(scope="module")
@@ -58,7 +70,7 @@ def run_layer(gpu, w, T, x_np, S_slots, initial, decode=False, bias=None, prefet
               pool=None, q8=False, fmt=None):
     H, B = gpu["harness"], gpu["binding"]
     fmt = (1 if q8 else 0) if fmt is None else fmt
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True, host_format=fmt)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, S_slots, w.I_shared, True, host_format=fmt)
     pool = pool or H.HostPool(w, 0, fmt=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, initial, poison=poison)
     buf = H.Buffers(ctx, T)
@@ -108,11 +120,11 @@ def test_every_gemm_kernel_on_one_layer(gpu, oracle, variant):
     bias = S.zipf_route_bias(w, 0)
     try:
         for mode in (0, 1):
-            B.moe_set_gemm_variant(mode, variant)
+            set_tune(mode, variant)
         r = run_layer(gpu, w, w.T, x, w.E, list(range(w.E)), bias=bias)
     finally:
         for mode in (0, 1):
-            B.moe_set_gemm_variant(mode, 0)
+            set_tune(mode, 0)
     ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias, shared=r["lay"].shared_np)
     np.testing.assert_array_equal(r["routing"]["perm"], ref["perm"])
     check_out(r["out"], ref["out_f64"], f"gemm variant {variant}")
@@ -129,7 +141,7 @@ def test_gate_logits_bit_exact(gpu, oracle, d, E, k, T):
     w = S.Workload("logits", d=d, I=64, E=E, k=k, T=T, seed=61)
     x = S.activations(w)
     bias = S.normal_f32((T, E), 61, 900, 0.5)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E)
     pool = H.HostPool(w, 0)
     lay = H.DeviceLayer(ctx, w, 0, pool, list(range(E)))
     buf = H.Buffers(ctx, T)
@@ -200,7 +212,7 @@ def test_one_token_decode_enqueued_from_the_gates_id_list(gpu, oracle, E, k, Ish
     w = S.Workload("one_token", d=512, I=256, E=E, k=k, T=1, I_shared=Ish, seed=71)
     got = []
     for host_path in (0, 1):
-        B.moe_set_gemm_variant(5, 0 if host_path else 1)
+        set_tune(5, 0 if host_path else 1)
         for step in range(3):                       # different tokens choose different experts
             x = S.activations(w, 0, step)
             r = run_layer(gpu, w, 1, x, E, list(range(E)), decode=True)
@@ -227,8 +239,8 @@ def test_one_token_down_projection_and_weighted_sum_in_one_launch(gpu, oracle, f
     w = S.Workload("fused_down", d=d, I=I, E=E, k=k, T=1, I_shared=Ish, seed=91)
     outs = []
     for two_launches in (0, 1):
-        B.moe_set_gemm_variant(7, two_launches)
-        B.moe_set_gemm_variant(6, 2 if fmt else 0)
+        set_tune(7, two_launches)
+        set_tune(6, 2 if fmt else 0)
         for step in range(2):
             x = S.activations(w, 0, step)
             r = run_layer(gpu, w, 1, x, E, None if fmt else list(range(E)), decode=True,
@@ -298,14 +310,14 @@ def test_shared_cache_decode_steps(gpu, oracle, slots, q8):
     from oracle.cache_sim import SharedCacheSim
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("shared_cache", d=256, I=128, E=8, k=2, T=1, seed=17, L=4, steps=5, p_stay=0.6, top_m=2)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, slots, 0, True, shared_slots=True, host_format=1 if q8 else 0)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, w.L, slots, 0, True, shared_slots=True, host_format=1 if q8 else 0)
     pools = [H.HostPool(w, l, q8=q8) for l in range(w.L)]
     cache = torch.full((ctx.moe_cache_bytes() // 2,), 0x7FC0, dtype=torch.int16, device="cuda")  # NaN until filled
     lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
     wps_np = [S.predictor_weight(w, l) for l in range(w.L)]
     wps = [H.np_to_dev(a) for a in wps_np]
     sim = SharedCacheSim(w.L, w.E, slots, pools[0].bytes_per_expert)
-    B.moe_set_gemm_variant(6, 2 if q8 else 0)     # 8-bit pools: small experts, force the mat-vecs onto the copies
+    ctx.moe_tune(6, 2 if q8 else 0)     # 8-bit pools: small experts, force the mat-vecs onto the copies
     trace = S.markov_trace(w)
     buf = H.Buffers(ctx, w.T)
     pred = torch.cuda.Stream()
@@ -318,7 +330,7 @@ def test_shared_cache_decode_steps(gpu, oracle, slots, q8):
             bias = H.np_to_dev(bias_np)
             nxt = l + 1                              # the first layer of a step has no prediction:
             if nxt < w.L:                            # its experts are fetched after the gate has chosen
-                ctx.predictor_score(x, w.T, wps[nxt], w.top_m, top, pred)
+                ctx.predictor_score(nxt, x, w.T, wps[nxt], w.top_m, top, pred)
             ctx.moe_decode_layer(l, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, w.E)
             gpu["compute"].synchronize()
             ref = oracle_layer(oracle, w, x_np, lays[l].router_np, pools[l], bias=bias_np)
@@ -335,7 +347,7 @@ def test_shared_cache_decode_steps(gpu, oracle, slots, q8):
             sim.prefetch(nxt, ref_top)
             assert ctx.moe_cache_state(nxt) == sim.state(nxt)
     torch.cuda.synchronize()
-    B.moe_set_gemm_variant(6, 0)
+    ctx.moe_tune(6, 0)
     for l in range(w.L):
         assert ctx.moe_get_stats(l) == {**sim.counters(l), "layer_calls": w.steps}, f"layer {l}"
     ctx.close()
@@ -346,7 +358,7 @@ def test_shared_cache_prefill_streams_every_layer_through_two_slots(gpu, oracle)
     layer; each expert with tokens is fetched exactly once per layer and the output is the all-resident one."""
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("shared_prefill", d=256, I=128, E=8, k=2, T=96, seed=23, L=3)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, 2, 0, True, shared_slots=True)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, w.L, 2, 0, True, shared_slots=True)
     pools = [H.HostPool(w, l) for l in range(w.L)]
     cache = torch.full((2, w.blob_elems), 0x7FC0, dtype=torch.int16, device="cuda")
     lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
@@ -422,10 +434,10 @@ def test_q8_streaming_through_two_slots(gpu, oracle, T, decode):
     x = S.activations(w)
     bias = S.zipf_route_bias(w, 0)
     try:
-        gpu["binding"].moe_set_gemm_variant(6, 2)    # small experts: force the mat-vecs onto the 8-bit copies
+        set_tune(6, 2)    # small experts: force the mat-vecs onto the 8-bit copies
         r = run_layer(gpu, w, T, x, 2, None, decode=decode, bias=bias, prefetch=[7, 6], poison=True, q8=True)
     finally:
-        gpu["binding"].moe_set_gemm_variant(6, 0)
+        set_tune(6, 0)
     ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], bias=bias)
     np.testing.assert_array_equal(r["routing"]["ids"], ref["ids"])
     check_out(r["out"], ref["out_f64"], f"q8 streaming T={T}")
@@ -449,7 +461,7 @@ def test_q8_decode_streams_the_8bit_copies(gpu, oracle, d, I, I_shared, T):
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("q8_decode", d=d, I=I, E=6, k=2, T=T, I_shared=I_shared, seed=54 + T)
     x = S.activations(w)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=1)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=1)
     pool = H.HostPool(w, 0, q8=True)
     lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
     buf = H.Buffers(ctx, T)
@@ -460,11 +472,11 @@ def test_q8_decode_streams_the_8bit_copies(gpu, oracle, d, I, I_shared, T):
         lay.slots.fill_(0x7FC0)
         torch.cuda.synchronize()
     try:
-        B.moe_set_gemm_variant(6, 2)     # these experts are small: force the 8-bit source
+        ctx.moe_tune(6, 2)     # these experts are small: force the 8-bit source
         ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
         gpu["compute"].synchronize()
     finally:
-        B.moe_set_gemm_variant(6, 0)
+        ctx.moe_tune(6, 0)
     ref = oracle_layer(oracle, w, x, lay.router_np, pool, shared=lay.shared_np)
     np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
     check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"q8 decode T={T}")
@@ -509,7 +521,7 @@ def test_mxfp4_decode_streams_the_4bit_copies(gpu, oracle, d, I, I_shared, T):
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("mx4_decode", d=d, I=I, E=6, k=2, T=T, I_shared=I_shared, seed=64 + T)
     x = S.activations(w)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=3)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=3)
     pool = H.HostPool(w, 0, fmt=3)
     lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
     buf = H.Buffers(ctx, T)
@@ -517,7 +529,7 @@ def test_mxfp4_decode_streams_the_4bit_copies(gpu, oracle, d, I, I_shared, T):
     torch.cuda.synchronize()
     lay.slots.fill_(0x7FC0)
     torch.cuda.synchronize()
-    B.moe_set_gemm_variant(6, 2)     # these experts are small: force the 4-bit source
+    ctx.moe_tune(6, 2)     # these experts are small: force the 4-bit source
     ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
     gpu["compute"].synchronize()
     ref = oracle_layer(oracle, w, x, lay.router_np, pool, shared=lay.shared_np)
@@ -548,7 +560,7 @@ def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I
     w = S.Workload("skinny", d=d, I=I, E=5, k=2, T=T, I_shared=I_shared, seed=70 + T + fmt, zipf_s=0.8)
     x = S.activations(w)
     bias = S.zipf_route_bias(w, 0)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
     pool = H.HostPool(w, 0, fmt=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, None if fmt else list(range(w.E)), poison=bool(fmt))
     buf = H.Buffers(ctx, T)
@@ -561,9 +573,9 @@ def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I
     assert T < 6 or (ref["counts"].max() >= 3 and (T < 20 or ref["counts"].max() > 16))
     outs = {}
     for name, min_tok in (("mfma", 1), ("per-token", 1 << 20)):    # 1: wherever the shapes allow it
-        B.moe_set_gemm_variant(6, 2 if fmt else 0)    # small experts: force the quantised source
-        B.moe_set_gemm_variant(8, min_tok)
-        B.moe_set_gemm_variant(9, 64)
+        ctx.moe_tune(6, 2 if fmt else 0)    # small experts: force the quantised source
+        ctx.moe_tune(8, min_tok)
+        ctx.moe_tune(9, 64)
         ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"], H.np_to_dev(bias), 0)
         gpu["compute"].synchronize()
         np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["perm"], ref["perm"])
@@ -629,7 +641,7 @@ def test_decode_seeded_random_shapes(gpu, oracle):
                        zipf_s=float(rng.choice([0.0, 1.0])))
         x = S.activations(w)
         bias = S.zipf_route_bias(w, 0)
-        ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
+        ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
         pool = H.HostPool(w, 0, fmt=fmt)
         lay = H.DeviceLayer(ctx, w, 0, pool, None if fmt else list(range(E)), poison=bool(fmt))
         buf = H.Buffers(ctx, T)
@@ -638,10 +650,10 @@ def test_decode_seeded_random_shapes(gpu, oracle):
             torch.cuda.synchronize()
             lay.slots.fill_(0x7FC0)
             torch.cuda.synchronize()
-        B.moe_set_gemm_variant(6, 2 if fmt else 0)
-        B.moe_set_gemm_variant(8, 1 if forced else 0)
-        B.moe_set_gemm_variant(9, 64)
-        B.moe_set_gemm_variant(10, slices)
+        ctx.moe_tune(6, 2 if fmt else 0)
+        ctx.moe_tune(8, 1 if forced else 0)
+        ctx.moe_tune(9, 64)
+        ctx.moe_tune(10, slices)
         ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"], H.np_to_dev(bias), 0)
         gpu["compute"].synchronize()
         ref = oracle_layer(oracle, w, x, lay.router_np, pool, bias=bias, shared=lay.shared_np)
@@ -657,13 +669,13 @@ def test_quantised_decode_then_prefill_without_a_pause(gpu, oracle, fmt):
     oracle, on experts that are fetched by the first call itself."""
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("q_then_prefill", d=512, I=256, E=6, k=2, T=96, seed=59)
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, 0, True, host_format=fmt)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E, 0, True, host_format=fmt)
     pool = H.HostPool(w, 0, fmt=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
     xd_np, xp_np = S.activations(w, 0, 1)[:2], S.activations(w, 0, 2)
     xd, xp = H.np_to_dev(xd_np), H.np_to_dev(xp_np)
     bd, bp = H.Buffers(ctx, 2), H.Buffers(ctx, w.T)
-    B.moe_set_gemm_variant(6, 2)
+    ctx.moe_tune(6, 2)
     ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])           # copies still in flight
     ctx.moe_decode_layer(0, xd, 2, bd.y, bd.ws, gpu["compute"], gpu["copy"])
     ctx.moe_prefill_layer(0, xp, w.T, bp.y, bp.ws, gpu["compute"], gpu["copy"])
@@ -705,7 +717,7 @@ def test_mlp_predictor_scores_bit_exact(gpu, oracle, L, E, k, m):
     dims = S.mlp_dims(L, E, k)
     params = S.mlp_params(dims, 41 + E)
     ws, bs, sc, sh, act = mlp_on_device(H, dims, params)
-    ctx = B.MoeContext(256, 128, E, k, 1, E)
+    ctx = new_ctx(B, 256, 128, E, k, 1, E)
     scores = torch.empty(E, dtype=torch.float32, device="cuda")
     top = torch.zeros(m, dtype=torch.int32).pin_memory()
     pred = torch.cuda.Stream()
@@ -738,7 +750,7 @@ def test_paper_decode_flow_state_constructor_mlp_and_one_cache(gpu, oracle):
     dims = S.mlp_dims(w.L, w.E, w.k)
     params = [S.mlp_params(dims, 77, l) for l in range(w.L)]           # one predictor per target layer
     dev_params = [mlp_on_device(H, dims, p) for p in params]
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, w.L, w.k, 0, True, shared_slots=True)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, w.L, w.k, 0, True, shared_slots=True)
     pools = [H.HostPool(w, l) for l in range(w.L)]
     cache = torch.full((w.k, w.blob_elems), 0x7FC0, dtype=torch.int16, device="cuda")
     lays = [H.DeviceLayer(ctx, w, l, pools[l], None, slots=cache) for l in range(w.L)]
@@ -795,7 +807,7 @@ def test_predictor_scores_and_topm(gpu, oracle, B, d, E, m):
     ctx = Bn.MoeContext(d, 64, E, 1, 1, 1)
     top = torch.zeros(m, dtype=torch.int32).pin_memory()
     scores = torch.empty(E, dtype=torch.float32, device="cuda")
-    ctx.predictor_score(H.np_to_dev(x), B, H.np_to_dev(wp), m, top, gpu["compute"], scores)
+    ctx.predictor_score(0, H.np_to_dev(x), B, H.np_to_dev(wp), m, top, gpu["compute"], scores)
     gpu["compute"].synchronize()
     ref_s, ref_top = oracle.predictor_score(x, wp, m)
     np.testing.assert_array_equal(scores.cpu().numpy(), ref_s)  # same fp32 summation order
@@ -807,18 +819,18 @@ def test_predictor_scores_and_topm(gpu, oracle, B, d, E, m):
 def test_error_codes(gpu):
     B = gpu["binding"]
     with pytest.raises(B.MoeError) as e:
-        B.MoeContext(256, 128, 8, 9)
+        new_ctx(B, 256, 128, 8, 9)
     assert e.value.code == -1
     with pytest.raises(B.MoeError) as e:
-        B.MoeContext(256, 128, 8, 2, 1, 0)
+        new_ctx(B, 256, 128, 8, 2, 1, 0)
     assert e.value.code == -1
     with pytest.raises(B.MoeError) as e:
-        B.MoeContext(256, 128, 65, 2)
+        new_ctx(B, 256, 128, 65, 2)
     assert e.value.code == -2
     with pytest.raises(B.MoeError) as e:
-        B.MoeContext(250, 128, 8, 2)
+        new_ctx(B, 250, 128, 8, 2)
     assert e.value.code == -2
-    ctx = B.MoeContext(256, 128, 8, 2)
+    ctx = new_ctx(B, 256, 128, 8, 2)
     x = torch.zeros((4, 256), dtype=torch.int16, device="cuda")
     y = torch.zeros_like(x)
     ws = torch.empty(ctx.moe_workspace_bytes(4), dtype=torch.uint8, device="cuda")
