@@ -270,6 +270,23 @@ int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T,
                      void *copy_stream, moe_stats *opt);
 
 /*
+ * moe_decode_layer for callers that cannot allocate device memory or have nowhere to keep a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and cache behaviour as moe_decode_layer, but the workspace is a static
+ * array of MOE_STATIC_WORKSPACE_BYTES (8 MiB) that the library holds on every GPU it is loaded on
+ * until the process ends (its device address is taken once per device, in moe_create).  The call
+ * allocates nothing: no hipMalloc / hipFree, no events or streams are created, and kernel timing
+ * (moe_set_profiling) is off for its launches.  A T for which moe_workspace_bytes(cfg, T) exceeds the
+ * static size is refused with MOE_E_WORKSPACE (Mixtral-shaped layers: T <= 93, Qwen-shaped: T <= 131).
+ * No part of the workspace has to start at zero: every table is written before it is read inside a
+ * call, so consecutive calls may differ in T.  All calls on one GPU share the one array, whatever
+ * their context or stream: two that overlap in time race on it.
+ */
+#define MOE_STATIC_WORKSPACE_BYTES (8u << 20)
+int moe_decode_layer_static(moe_ctx *ctx, int layer, const void *dev_x, int T,
+                            const float *dev_route_bias, int bias_stride, void *dev_y,
+                            void *compute_stream, void *copy_stream, moe_stats *opt);
+/*
  * Parity hook: copies the routing tables the last layer call left in `dev_workspace`
  * (T as in that call) to caller device buffers on `stream`; any destination may be NULL.
  * ids [T,k] i32, w [T,k] f32, counts [E], offsets [E+1], perm [T*k], inv_perm [T*k].

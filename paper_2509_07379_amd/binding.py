@@ -23,6 +23,7 @@ EXPORTS = [
     "moe_get_kernel_times", "moe_dense_gemm_bf16",
     "predictor_mlp_score", "moe_state_create", "moe_state_destroy", "moe_state_dim", "moe_state_record",
     "moe_state_clear", "moe_state_vector", "moe_host_blob_bytes", "moe_cache_bytes", "moe_debug_logits",
+    "moe_decode_layer_static",
 ]
 # exported for the parity tests only, declared in csrc/moe_tuning.h (not part of the public header)
 INTERNAL_EXPORTS = ["moe_tune", "moe_inject_failure", "moe_debug_gemm_choice"]
@@ -82,6 +83,7 @@ def load():
     layer_args = [vp, c_int, vp, c_int, vp, c_int, vp, vp, c_size_t, vp, vp, POINTER(MoeStats)]
     lib.moe_prefill_layer.argtypes = layer_args
     lib.moe_decode_layer.argtypes = layer_args
+    lib.moe_decode_layer_static.argtypes = [vp, c_int, vp, c_int, vp, c_int, vp, vp, vp, POINTER(MoeStats)]
     lib.moe_debug_routing.argtypes = [vp, vp, c_int, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_debug_logits.argtypes = [vp, vp, c_int, vp, vp]
     lib.moe_get_stats.argtypes = [vp, c_int, POINTER(MoeStats)]
@@ -222,6 +224,15 @@ class MoeContext:
                          bias_stride=0, want_stats=False):
         return self._layer(self.lib.moe_decode_layer, layer, x, T, y, ws, compute_stream, copy_stream,
                            route_bias, bias_stride, want_stats)
+
+    def moe_decode_layer_static(self, layer, x, T, y, compute_stream, copy_stream, route_bias=None,
+                                bias_stride=0, want_stats=False):
+        """moe_decode_layer on the library's static workspace (no workspace argument, nothing allocated)."""
+        st = MoeStats() if want_stats else None
+        _check(self.lib.moe_decode_layer_static(self._h, layer, _ptr(x), T, _ptr(route_bias), bias_stride, _ptr(y),
+                                                _stream(compute_stream), _stream(copy_stream),
+                                                byref(st) if want_stats else None))
+        return st.as_dict(full=True) if want_stats else None
 
     def moe_debug_routing(self, ws, T, ids=None, w=None, counts=None, offsets=None, perm=None,
                           inv_perm=None, stream=None):

@@ -146,6 +146,14 @@ struct Layer {
   moe_stats stats{};
 };
 
+// Workspace of moe_decode_layer_static: one array per GPU the library is loaded on, for callers that
+// cannot allocate.  Host code never uses the array's name as an address: the device address is taken
+// once per device with hipGetSymbolAddress (moe_create) and kept in g_static_ws.
+constexpr size_t kStaticWorkspaceBytes = MOE_STATIC_WORKSPACE_BYTES;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+void *g_static_ws[kMaxDevices] = {};
+
 struct TimedLaunch {
   hipEvent_t start, stop;
   int kind, layer;
@@ -178,6 +186,7 @@ struct moe_ctx {
   int32_t call_no = 0;
   PendingCall pending[kMailboxes];    // ring, oldest at pend_head (a mailbox has at most one pending call)
   int pend_head = 0, pend_count = 0;
+  bool timers_off = false;            // inside a call that must not create events
   int cur_layer = -1;                 // layer of the call being enqueued (for the kernel timers)
   Tune tune{};
   ApiTune api_tune{};
@@ -237,7 +246,7 @@ struct Timer {
   int kind;
   hipEvent_t start = nullptr, stop = nullptr;
   Timer(moe_ctx *c, hipStream_t s, int k) : ctx(c), stream(s), kind(k) {
-    if (!ctx->profiling) return;
+    if (!ctx->profiling || ctx->timers_off) return;
     auto get = [&]() -> hipEvent_t {
       if (!ctx->event_pool.empty()) {
         hipEvent_t e = ctx->event_pool.back();
@@ -939,6 +948,11 @@ const char *moe_last_error(void) { return g_err; }
 
 static int create_parts(moe_ctx *ctx, const moe_config *cfg) {
   HIP_TRY(hipGetDevice(&ctx->device));
+  if (ctx->device >= 0 && ctx->device < kMaxDevices && !g_static_ws[ctx->device]) {
+    void *p = nullptr;   // this device's copy of the static workspace
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_static_ws[ctx->device] = p;
+  }
   ctx->layers.resize(cfg->n_layers);
   HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->mailboxes),
                         (size_t)kMailboxes * kMailboxWords * sizeof(int32_t), 0));
@@ -1300,6 +1314,24 @@ int moe_decode_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const fl
                      void *compute_stream, void *copy_stream, moe_stats *opt) {
   int rc = run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, dev_workspace, ws_bytes,
                      compute_stream, copy_stream, true, opt);
+  return rc ? rc : join_expand(ctx, reinterpret_cast<hipStream_t>(copy_stream));
+}
+
+int moe_decode_layer_static(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *dev_route_bias,
+                            int bias_stride, void *dev_y, void *compute_stream, void *copy_stream,
+                            moe_stats *opt) {
+  if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
+  if (T <= 0) return fail(MOE_E_ARG, "T = %d, need > 0", T);
+  void *ws = ctx->device >= 0 && ctx->device < kMaxDevices ? g_static_ws[ctx->device] : nullptr;
+  if (!ws) return fail(MOE_E_UNSUPPORTED, "no static workspace on device %d", ctx->device);
+  const size_t need = ws_layout(ctx->cfg, T, ctx->api_tune.splitk).total;
+  if (need > kStaticWorkspaceBytes)
+    return fail(MOE_E_WORKSPACE, "T = %d needs %zu bytes of workspace, the static one holds %zu: use moe_decode_layer",
+                T, need, kStaticWorkspaceBytes);
+  ctx->timers_off = true;   // a timer would have to create events
+  int rc = run_layer(ctx, layer, dev_x, T, dev_route_bias, bias_stride, dev_y, ws, kStaticWorkspaceBytes,
+                     compute_stream, copy_stream, true, opt);
+  ctx->timers_off = false;
   return rc ? rc : join_expand(ctx, reinterpret_cast<hipStream_t>(copy_stream));
 }
 
