@@ -28,10 +28,12 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 PEAK_PCIE_GBS = 64.0        # PCIe Gen5 x16 per direction
-# HBM bytes per launch of the gate/up GEMM on the headline workload, from two rocprofv3 --pmc runs
+# HBM bytes per launch of the gate/up GEMM on the headline workload.  NOT measured by this run: hardware
+# counters need the profiler.  The figure comes from two rocprofv3 --pmc runs of this same command
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 256 MiB device copy
-# (x2.000 and x1.000); the summary with the commands is profiles/prefill_c2_mixtral_gemm_counters.txt.
+# (x2.000 and x1.000); the summary with the commands is the file named here.
 # Algorithmic bytes of that launch: 1879 MB of weights + 16.8 MB of activations read, 117.4 MB written.
+TRAFFIC_PROFILE = "profiles/prefill_c2_mixtral_gemm_counters.txt"
 MEASURED_TRAFFIC_BYTES = {"c2_mixtral_prefill": 2353.4e6 + 117.4e6}
 
 
@@ -56,6 +58,16 @@ def prefill_resident(args, torch, B, H, S, w, compute, copy):
     def step():
         ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy, bias, 0)
 
+    # The device needs a fraction of a second of work after idling before its clocks settle (the first
+    # ~15 layer calls run 15-40 % slower), whatever --warmup says: untimed steps for settle_s seconds,
+    # then the W warm-up steps, then exactly K timed steps.
+    t0 = time.perf_counter()
+    settle_steps = 0
+    while time.perf_counter() - t0 < args.settle_s:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        settle_steps += 8
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -76,7 +88,7 @@ def prefill_resident(args, torch, B, H, S, w, compute, copy):
     kern = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in times.items()}
     routing = buf.routing(ctx, compute)
     return dict(ms=ms, kern_ms=kern, ctx=ctx, pool=pool, lay=lay, buf=buf, x=x, x_np=x_np, bias=bias,
-                routing=routing, compute=compute, copy=copy)
+                routing=routing, compute=compute, copy=copy, settle_steps=settle_steps)
 
 
 def prefill_large_batch(args, torch, B, H, S, w, res, rep):
@@ -221,7 +233,10 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
     out = {}
     # "cached": S slots per layer (the configuration named in BASELINE.json); "shared_k": the paper's
     # cache, ONE set of k slots for all layers, predictor top-k; "resident": kernels only
-    for label, slots in (("cached", wl.S), ("shared_k", wl.k), ("resident", wl.E)):
+    xs0 = [H.np_to_dev(S.activations(wl, l, 0)) for l in range(n_layers)]
+    biases0 = [[H.np_to_dev(S.trace_route_bias(trace[s, l], wl.E)) for l in range(n_layers)] for s in range(steps)]
+    out["cached"] = decode_cached(torch, B, H, S, wl, pools, trace, xs0, biases0, compute, copy, pred)
+    for label, slots in (("shared_k", wl.k), ("resident", wl.E)):
         shared = label == "shared_k"
         ctx = B.MoeContext(wl.d, wl.I, wl.E, wl.k, n_layers, slots, wl.I_shared, True, shared_slots=shared)
         init = None if shared else list(range(slots))
@@ -376,6 +391,286 @@ def mlp_predictor_latency(torch, B, H, S, w, pred):
     return {"us_per_prediction": us, "layers": dims, "parameter_MB": params_mb}
 
 
+def prefill_c4(args, torch, B, H, S, compute, copy, steps=20, n_check=32):
+    """DeepSeek-MoE-shaped prefill layer (64 routed experts top-6 with Zipf popularity, 2 shared experts,
+    4096 tokens): kernel regime with every expert resident, then the configured 16 slots with the
+    experts streaming from pinned memory.  Sampled tokens are checked against the oracle."""
+    import numpy as np
+    import oracle
+    w = S.WORKLOADS["c4_deepseek_prefill"]
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared)
+    pool = H.HostPool(w, 0)
+    lay = H.DeviceLayer(ctx, w, 0, pool, list(range(w.E)))
+    buf = H.Buffers(ctx, w.T)
+    x_np = S.activations(w)
+    x = H.np_to_dev(x_np)
+    bias_np = S.zipf_route_bias(w, 0)
+    bias = H.np_to_dev(bias_np)
+
+    def step():
+        ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy, bias, 0)
+
+    for _ in range(10):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ctx.moe_set_profiling(True)
+    for _ in range(5):
+        step()
+    torch.cuda.synchronize()
+    kt = ctx.moe_get_kernel_times()
+    ctx.moe_set_profiling(False)
+    kern = {k: v[0] / 5 for k, v in kt.items() if v[1]}          # ms per layer call (routed + shared launches)
+    routing = buf.routing(ctx, compute)
+    counts = routing["counts"]
+    sel = np.linspace(0, w.T - 1, n_check).astype(np.int32)
+    ref = oracle.moe_layer(x_np, lay.router_np, [pool.ptr(e) for e in range(w.E)], w.k, bias=bias_np, sel=sel,
+                           shared_blob=lay.shared_np, I=w.I, I_shared=w.I_shared)
+    got = S.bf16_to_f32(H.dev_to_np_u16(buf.y)[sel]).astype(np.float64)
+    err = np.abs(got - ref["out_f64"])
+    ok = bool(np.all(err <= 1e-2 + 2e-2 * np.abs(ref["out_f64"])) and np.array_equal(ref["ids"], routing["ids"]))
+    ctx.close()
+    rows = w.T * w.k
+    fl_routed, fl_shared = 6.0 * rows * w.d * w.I, 6.0 * w.T * w.d * w.I_shared
+    out = {"workload": f"{w.name}: d={w.d} I={w.I} E={w.E} top-{w.k} + shared I={w.I_shared}, T={w.T}, Zipf s={w.zipf_s}, "
+                       f"layer 0 of {w.L}, experts resident",
+           "ms_per_layer": ms, "tokens_per_s": w.T / (ms * 1e-3), "kernels_ms_per_layer": kern,
+           "flops_per_layer": fl_routed + fl_shared,
+           "mfma_frac_layer": (fl_routed + fl_shared) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "gemm1_frac_of_mfma_peak": (fl_routed + fl_shared) * 2 / 3 / (kern["gemm1"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "gemm2_frac_of_mfma_peak": (fl_routed + fl_shared) / 3 / (kern["gemm2"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "rows_per_expert": {"max": int(counts.max()), "median": int(np.median(counts)), "min": int(counts.min()),
+                               "below_256": int((counts < 256).sum())},
+           "parity_on_sample": ok, "sample_tokens": n_check, "max_abs_err_on_sample": float(err.max())}
+
+    # the configured cache of 16 slots: every expert streams through it once per layer
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared)
+    lay2 = H.DeviceLayer(ctx, w, 0, pool, None)
+
+    def pipelined():
+        ctx.moe_cache_invalidate(0)
+        ctx.expert_cache_prefetch(0, list(range(w.S)), copy)
+        ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy, bias, 0)
+
+    pipelined()
+    torch.cuda.synchronize()
+    ctx.moe_reset_stats()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        pipelined()
+    torch.cuda.synchronize()
+    t_p = (time.perf_counter() - t0) * 1e3 / 3
+    st = ctx.moe_get_stats(0)
+    ctx.close()
+    del lay2
+    out["offloaded"] = {"slots": w.S, "ms_per_layer": t_p, "bytes_per_layer": st["bytes_h2d"] / st["layer_calls"],
+                        "link_GBps_over_the_layer": st["bytes_h2d"] / st["layer_calls"] / (t_p * 1e-3) / 1e9}
+    return out
+
+
+def decode_c5(args, torch, B, H, S, compute, copy, pred, n_layers=4, steps=32):
+    """Qwen1.5-MoE-shaped decode (60 routed experts top-4, one shared expert of 5632, batch 8): per-layer
+    latency with every expert resident (kernel regime, HBM fraction of the distinct experts' bytes) and
+    with the configured 15 slots per layer and the linear predictor's top-8 prefetched a layer ahead."""
+    import numpy as np
+    from dataclasses import replace
+    w = replace(S.WORKLOADS["c5_qwen_decode"], L=n_layers, steps=steps)
+    pools = [H.HostPool(w, l) for l in range(n_layers)]
+    trace = S.markov_trace(w)
+    distinct = float(np.mean([len(set(trace[s, l].ravel().tolist())) for s in range(steps) for l in range(n_layers)]))
+    xs = [H.np_to_dev(S.activations(w, l, 0)) for l in range(n_layers)]
+    biases = [[H.np_to_dev(S.trace_route_bias(trace[s, l], w.E)) for l in range(n_layers)] for s in range(steps)]
+    out = {"workload": f"{w.name}: d={w.d} I={w.I} E={w.E} top-{w.k} + shared I={w.I_shared}, batch {w.T}, "
+                       f"{n_layers} of {S.WORKLOADS['c5_qwen_decode'].L} layers in memory, {steps} steps",
+           "distinct_experts_per_layer": distinct}
+
+    # kernel regime
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, n_layers, w.E, w.I_shared)
+    layers = [H.DeviceLayer(ctx, w, l, pools[l], list(range(w.E))) for l in range(n_layers)]
+    buf = H.Buffers(ctx, w.T)
+
+    def resident_pass():
+        for s in range(steps):
+            for l in range(n_layers):
+                ctx.moe_decode_layer(l, xs[l], w.T, buf.y, buf.ws, compute, copy, biases[s][l], w.E)
+        torch.cuda.synchronize()
+
+    resident_pass()
+    t0 = time.perf_counter()
+    resident_pass()
+    us = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
+    ctx.moe_set_profiling(True)
+    resident_pass()
+    kt = ctx.moe_get_kernel_times()
+    ctx.moe_set_profiling(False)
+    calls = steps * n_layers
+    kern_us = {k: v[0] * 1e3 / calls for k, v in kt.items() if v[1]}
+    bytes_layer = distinct * w.blob_bytes + w.shared_blob_bytes
+    out.update({"resident_us_per_layer": us, "kernels_us_per_layer": kern_us,
+                "bytes_per_layer": bytes_layer,
+                "layer_HBM_GBps": bytes_layer / (us * 1e-6) / 1e9,
+                "layer_frac_of_hbm_peak": bytes_layer / (us * 1e-6) / 1e9 / PEAK_HBM_GBS})
+    ctx.close()
+    del layers
+
+    # the configured cache: 15 of 60 experts per layer, predictor top-8 one layer ahead
+    out["cached"] = decode_cached(torch, B, H, S, w, pools, trace, xs, biases, compute, copy, pred)
+    return out
+
+
+def decode_cached(torch, B, H, S, w, pools, trace, xs, biases, compute, copy, pred):
+    """Decode through the configured per-layer slots with predictor-guided prefetch (Section V-C): whole-run
+    latency, counters, the share of used prefetches that had landed when compute asked for them, and the
+    per-layer latency of calls without and with a miss (each call timed to its completion on the host)."""
+    n_layers, steps = len(pools), len(biases)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, n_layers, w.S, w.I_shared)
+    layers = [H.DeviceLayer(ctx, w, l, pools[l], list(range(w.S))) for l in range(n_layers)]
+    wps = [H.np_to_dev(S.predictor_weight(w, l)) for l in range(n_layers)]
+    buf = H.Buffers(ctx, w.T)
+    top = torch.zeros(w.top_m, dtype=torch.int32).pin_memory()
+
+    def one_step(s, per_call=None):
+        for l in range(n_layers):
+            if l + 1 < n_layers:
+                ctx.predictor_score(l + 1, xs[l], w.T, wps[l + 1], w.top_m, top, pred)
+            t0 = time.perf_counter()
+            st = ctx.moe_decode_layer(l, xs[l], w.T, buf.y, buf.ws, compute, copy, biases[s][l], w.E,
+                                      want_stats=per_call is not None)
+            if per_call is not None:
+                compute.synchronize()
+                per_call.append(((time.perf_counter() - t0) * 1e6, st["misses"]))
+            if l + 1 < n_layers:
+                pred.synchronize()
+                ctx.expert_cache_prefetch(l + 1, top.tolist(), copy)
+
+    one_step(0)
+    torch.cuda.synchronize()
+    ctx.moe_reset_stats()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        one_step(s)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
+    st = ctx.moe_get_stats(-1, full=True)
+    per_call = []
+    for s in range(steps):
+        one_step(s, per_call)
+    torch.cuda.synchronize()
+    ctx.close()
+    del layers
+    hit_calls = [t for t, m in per_call if m == 0]
+    miss_calls = [t for t, m in per_call if m > 0]
+    used = st["prefetch_ready"] + st["prefetch_stalled"]
+    mean = lambda v: float(sum(v) / len(v)) if v else None
+    return {"slots": w.S, "predictor_top_m": w.top_m, "us_per_layer": us, "stats": st,
+            "hit_rate": st["hits"] / max(1, st["hits"] + st["misses"]),
+            # of the prefetched experts that were used: landed before compute asked for them (no stall)
+            "prefetch_no_stall_frac": st["prefetch_ready"] / used if used else None,
+            "host_wait_for_gate_ms_per_layer": st["wait_ms"] / max(1, st["layer_calls"]),
+            "calls_without_miss": len(hit_calls), "hit_path_us_per_layer": mean(hit_calls),
+            "calls_with_miss": len(miss_calls), "miss_path_us_per_layer": mean(miss_calls),
+            "misses_per_miss_call": mean([m for _, m in per_call if m > 0])}
+
+
+def batch_sweep(torch, B, H, S, compute, copy, batches=(1, 2, 4, 8, 12), n_layers=2, steps=8):
+    """The paper's batching study (Section VI: batch sizes 1-12 activate more distinct experts per layer):
+    per-layer decode latency of the Mixtral- and the Qwen-shaped layers at each batch size, with every
+    expert resident and through the configured slots per layer without a predictor (every miss a fetch)."""
+    import numpy as np
+    from dataclasses import replace
+    table = {}
+    for name in ("c3_mixtral_decode", "c5_qwen_decode"):
+        w0 = replace(S.WORKLOADS[name], L=n_layers, steps=steps)
+        pools = [H.HostPool(w0, l) for l in range(n_layers)]
+        rows = []
+        for slots in (w0.E, w0.S):
+            ctx = B.MoeContext(w0.d, w0.I, w0.E, w0.k, n_layers, slots, w0.I_shared)
+            layers = [H.DeviceLayer(ctx, w0, l, pools[l], list(range(slots))) for l in range(n_layers)]
+            for bi, batch in enumerate(batches):
+                w = replace(w0, T=batch)
+                trace = S.markov_trace(w)
+                buf = H.Buffers(ctx, batch)
+                xs = [H.np_to_dev(S.activations(w, l, 0)) for l in range(n_layers)]
+                biases = [[H.np_to_dev(S.trace_route_bias(trace[s, l], w.E)) for l in range(n_layers)]
+                          for s in range(steps)]
+
+                def one_pass():
+                    for s in range(steps):
+                        for l in range(n_layers):
+                            ctx.moe_decode_layer(l, xs[l], batch, buf.y, buf.ws, compute, copy, biases[s][l], w.E)
+                    torch.cuda.synchronize()
+
+                one_pass()
+                ctx.moe_reset_stats()
+                t0 = time.perf_counter()
+                one_pass()
+                us = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
+                st = ctx.moe_get_stats(-1)
+                distinct = float(np.mean([len(set(trace[s, l].ravel().tolist()))
+                                          for s in range(steps) for l in range(n_layers)]))
+                if slots == w0.E:
+                    rows.append({"batch": batch, "distinct_experts": distinct, "resident_us": us})
+                else:
+                    rows[bi][f"slots_{slots}_us"] = us
+                    rows[bi][f"slots_{slots}_misses_per_layer"] = st["misses"] / st["layer_calls"]
+            ctx.close()
+            del layers
+        table[name] = rows
+    return table
+
+
+def oracle_single_thread_c1(S):
+    """The oracle on config 1 in full (64 tokens, 8 experts, top-2) on ONE thread: tokens per second."""
+    import ctypes
+    import oracle
+    omp = ctypes.CDLL("libgomp.so.1")
+    before = omp.omp_get_max_threads()
+    w = S.WORKLOADS["c1_tiny"]
+    x = S.activations(w)
+    wr = S.router_weight(w, 0)
+    blobs = [S.expert_blob(w, 0, e) for e in range(w.E)]
+    omp.omp_set_num_threads(1)
+    try:
+        oracle.moe_layer(x, wr, blobs, w.k)
+        t0 = time.perf_counter()
+        n = 3
+        for _ in range(n):
+            oracle.moe_layer(x, wr, blobs, w.k)
+        dt = (time.perf_counter() - t0) / n
+    finally:
+        omp.omp_set_num_threads(before)
+    return {"workload": "c1_tiny in full", "threads": 1, "seconds": dt, "tokens_per_s": w.T / dt}
+
+
+def host_cores():
+    """(threads the OpenMP oracle uses, physical cores, logical CPUs) of this host."""
+    import ctypes
+    logical = os.cpu_count()
+    phys = set()
+    try:
+        pid = cid = None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("physical id"):
+                pid = line.split(":")[1].strip()
+            elif line.startswith("core id"):
+                cid = line.split(":")[1].strip()
+            elif not line.strip():
+                if pid is not None and cid is not None:
+                    phys.add((pid, cid))
+                pid = cid = None
+    except OSError:
+        pass
+    try:
+        threads = int(ctypes.CDLL("libgomp.so.1").omp_get_max_threads())
+    except OSError:
+        threads = int(os.environ.get("OMP_NUM_THREADS", logical))
+    return threads, (len(phys) or None), logical
+
+
 def cpu_baseline(args, S, w, res, n_tokens):
     """The CPU oracle on a bounded sample: full routing + dispatch, expert math on n_tokens tokens."""
     import numpy as np
@@ -414,6 +709,11 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--decode-layers", type=int, default=8, help="layers of the decode workload held in memory")
     ap.add_argument("--decode-steps", type=int, default=32)
+    ap.add_argument("--settle-s", type=float, default=0.5,
+                    help="seconds of untimed steps before the warm-up steps (clock ramp after idle)")
+    ap.add_argument("--no-c4", action="store_true", help="skip the DeepSeek-shaped prefill leg")
+    ap.add_argument("--no-c5", action="store_true", help="skip the Qwen-shaped batch-8 decode leg")
+    ap.add_argument("--no-batch-sweep", action="store_true", help="skip the batch 1-12 decode table")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -455,13 +755,15 @@ def main():
     line = {
         "metric": "MoE-layer prefill tokens/s (MFMA util %) + decode per-layer latency us (HBM GB/s)",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms, "settle_steps_before_warmup": res["settle_steps"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: d={w.d} I={w.I} E={w.E} top-{w.k} T={w.T}, one MoE layer, "
                                f"experts resident in HBM (S=E)", "counts": res["routing"]["counts"].tolist()},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm SwiGLU (gate+up)", "achieved": tf1,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tf1 / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "traffic_unit": "bytes/launch",
+                     "traffic_source": f"{TRAFFIC_PROFILE} (rocprofv3 --pmc of this command; not measured by this run)",
                      "flops_per_launch": flops1, "avg_launch_ms": k["gemm1"]},
         "kernels_ms": k,
         "gemm2": {"achieved": tf2, "unit": "TFLOP/s", "frac": tf2 / PEAK_BF16_TFLOPS},
@@ -500,6 +802,16 @@ def main():
             }
             log(f"[bench] {key}: {line[key]}")
 
+    if not args.no_c4:
+        line["prefill_c4"] = prefill_c4(args, torch, B, H, S, compute, copy)
+        log(f"[bench] prefill_c4: {line['prefill_c4']}")
+    if not args.no_c5:
+        line["decode_c5"] = decode_c5(args, torch, B, H, S, compute, copy, pred)
+        log(f"[bench] decode_c5: {line['decode_c5']}")
+    if not args.no_batch_sweep:
+        line["batch_sweep"] = batch_sweep(torch, B, H, S, compute, copy)
+        log(f"[bench] batch_sweep: {line['batch_sweep']}")
+
     if not args.no_decode:
         wd = S.WORKLOADS["c3_mixtral_decode"]
         dec = decode_regime(args, torch, B, H, S, wd, args.decode_layers, args.decode_steps, compute, copy, pred)
@@ -516,7 +828,7 @@ def main():
             "layer_HBM_GBps": bytes_layer / (r["us_per_layer"] * 1e-6) / 1e9,
             "resident_batch8": r["batch8"],
             "cached_us_per_layer": dec["cached"]["us_per_layer"], "cached_slots": wd.S,
-            "cached_stats": dec["cached"]["stats"],
+            "cached_stats": dec["cached"]["stats"], "cached": dec["cached"],
             # the paper's cache: one set of k slots for all layers, predictor top-k, first layer on demand
             "shared_k_us_per_layer": dec["shared_k"]["us_per_layer"], "shared_k_slots": wd.k,
             "shared_k_stats": dec["shared_k"]["stats"],
@@ -538,9 +850,10 @@ def main():
         err = np.abs(got - cb["out64"])
         ok = bool(np.all(err <= 1e-2 + 2e-2 * np.abs(cb["out64"])) and
                   np.array_equal(cb["ids"], res["routing"]["ids"]))
+        threads, physical, logical = host_cores()
         line["cpu_baseline"] = {
-            "value": cb["value"], "unit": "tokens/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
-            "kind": "oracle",
+            "value": cb["value"], "unit": "tokens/s", "cores": threads, "physical_cores": physical,
+            "logical_cpus": logical, "kind": "oracle", "single_thread": oracle_single_thread_c1(S),
             "sample": f"routing+dispatch on all {w.T} tokens ({cb['t_route_s']:.2f}s), expert math on "
                       f"{args.cpu_tokens} evenly spaced tokens ({cb['t_expert_s']:.1f}s); rate extrapolated",
             "parity_on_sample": ok, "max_abs_err_on_sample": float(err.max()),
