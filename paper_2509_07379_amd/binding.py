@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_decode_layer_static",
 ]
 # exported for the parity tests only, declared in csrc/moe_tuning.h (not part of the public header)
-INTERNAL_EXPORTS = ["moe_tune", "moe_inject_failure", "moe_debug_gemm_choice"]
+INTERNAL_EXPORTS = ["moe_tune", "moe_inject_failure", "moe_debug_gemm_choice", "moe_debug_plans"]
 
 
 class MoeConfig(Structure):
@@ -96,6 +96,8 @@ def load():
     lib.moe_tune.argtypes = [vp, c_int, c_int]
     lib.moe_tune.restype = c_int
     lib.moe_inject_failure.argtypes = [c_int]
+    lib.moe_debug_plans.argtypes = [vp, vp, c_int, POINTER(c_int32), vp]
+    lib.moe_debug_plans.restype = c_int
     lib.moe_inject_failure.restype = c_int
     lib.moe_debug_gemm_choice.argtypes = [c_int, c_int, c_int64, c_int, c_int, c_int, c_int, c_int64, c_int, c_int]
     lib.moe_debug_gemm_choice.restype = c_int
@@ -246,6 +248,18 @@ class MoeContext:
         st = MoeStats()
         _check(self.lib.moe_get_stats(self._h, layer, byref(st)))
         return st.as_dict(full)
+
+    def moe_debug_plans(self, ws, T, stream):
+        """Internal parity hook: the gate/up and down GEMM work plans of the last prefill call, as dicts."""
+        n = 3 + 9 + 65 + 128
+        arr = (c_int32 * (2 * n))()
+        _check(self.lib.moe_debug_plans(self._h, _ptr(ws), T, arr, _stream(stream)))
+        out = []
+        for i in range(2):
+            v = list(arr[i * n:(i + 1) * n])
+            out.append(dict(n_items=v[0], s_full=v[1], s_rem=v[2], xcd_begin=v[3:12], item_begin=v[12:77],
+                            queue=v[77::16][:8]))
+        return out
 
     def moe_tune(self, mode: int, variant: int):
         """Internal test / tuning hook (csrc/moe_tuning.h): forces a kernel variant for this context."""

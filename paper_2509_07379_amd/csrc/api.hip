@@ -63,6 +63,10 @@ struct ApiTune {
   int no_q_matvec = 0;       // mat-vecs read the expanded bf16 slots even when a quantised copy exists
   int host_looks_always = 0; // a one-token decode call waits for the gate on the host like any other
   int matvec_max_rows = 0;   // largest group a decode call gives to the mat-vec launches, 0 = default
+  int down_sched = 0;        // down GEMM: 0 = by shape, 1 = tiles of equal height in a fixed order, 2 = full +
+                             // remainder tiles from the queues, 3 = equal heights from the queues
+  int up_sched = 0;          // gate/up GEMM: 0 = by shape, 1 = equal heights in a fixed order, 2 = full + remainder
+                             // tiles from the queues
 };
 
 int choose_splitk(const moe_config &cfg, int T) {
@@ -77,7 +81,8 @@ int choose_splitk(const moe_config &cfg, int T) {
 }
 
 struct WsLayout {
-  size_t logits, ids, w, counts, offsets, blk_hist, blk_base, perm, inv_perm, H, Hs, Y, Ys, total;
+  size_t logits, ids, w, counts, offsets, blk_hist, blk_base, perm, inv_perm, plans, H, Hs, Y, Ys, total;
+  int planes;   // fp32 planes of Y there is room for
   int splitk, nblk;
 };
 
@@ -86,8 +91,8 @@ struct WsLayout {
 WsLayout ws_layout(const moe_config &c, int T, int forced_splitk = 0) {
   WsLayout L{};
   const size_t n = (size_t)T * c.k;
-  const int planes = choose_splitk(c, T);
-  L.splitk = forced_splitk > 0 && forced_splitk < planes ? forced_splitk : planes;
+  L.planes = choose_splitk(c, T);
+  L.splitk = forced_splitk > 0 && forced_splitk < L.planes ? forced_splitk : L.planes;
   L.nblk = (int)((n + kDispatchChunk - 1) / kDispatchChunk);
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -104,9 +109,10 @@ WsLayout ws_layout(const moe_config &c, int T, int forced_splitk = 0) {
   L.blk_base = take((size_t)L.nblk * c.E * 4);
   L.perm = take(n * 4);
   L.inv_perm = take(n * 4);
+  L.plans = take(2 * sizeof(GemmPlan));
   L.H = take(n * c.I * 2);
   L.Hs = take((size_t)T * c.I_shared * 2);
-  L.Y = take((size_t)planes * n * c.d * 4);
+  L.Y = take((size_t)L.planes * n * c.d * 4);
   L.Ys = take(c.I_shared ? (size_t)T * c.d * 4 : 0);
   L.total = off;
   return L;
@@ -578,6 +584,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
     a.out = const_cast<char *>(ws + W.Y);
     a.ldo = c.d;
     a.splitk = W.splitk;
+    a.max_splitk = W.planes;
     a.out_split_stride = (long long)T * c.k * c.d;
   }
   return a;
@@ -627,11 +634,15 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
 constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsCopies = 32;
 
 // Both expert matmuls of the groups in `mask`, on `stream`.
+// A launch that covers every group with rows (use_queues) takes its items from the plan's queues, if
+// the layer call has a plan (a1.plan, a2.plan).
 int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned long long mask,
                 int n_groups, int max_rows, int max_rows_per_group, hipStream_t stream,
                 const GemmArgs *s1 = nullptr, const GemmArgs *s2 = nullptr,
-                hipEvent_t before_second = nullptr) {
+                hipEvent_t before_second = nullptr, bool use_queues = false) {
   a1.group_mask = a2.group_mask = mask;
+  a1.plan_queue = a1.plan && use_queues;
+  a2.plan_queue = a2.plan && use_queues;
   // The mat-vec kernels pass over an expert's weights once per 16 of its tokens: a decode batch that
   // gives some expert many more goes to the GEMM kernels, which stream the weights once.
   const bool from_copies = a1.q8_mask != 0 && gemv_reads_copies(a1);
@@ -786,6 +797,26 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 
   GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
   bool combined = false;   // the weighted sum has been done by the down projection's launch
+  // A prefill call of some size cuts the down projection's K range into slices chosen on the device from
+  // the groups' sizes (the same whichever experts are resident); a decode call never slices.
+  if (decode) a2.splitk = 1;
+  else if (n >= 1024) {
+    // Two ways to cut the groups into row tiles and to deal the tiles out.  Few, large groups
+    // (Mixtral-like): tiles of equal height in a fixed order; the blocks of an XCD then stay in step and
+    // share what they fetch, and a group's few left-over rows do not become a tile of their own that
+    // waits for its weights alone (measured in one process: 1508 against 1527 us per layer).  Many groups
+    // of very different size (DeepSeek-like, 48 of 64 groups under 256 rows): full tiles plus a short
+    // remainder tile on its deeper pipeline, taken from the queues (730 against 803 us per layer).
+    const int by_shape = E >= 16 ? 2 : 1;
+    const int up = ctx->api_tune.up_sched ? ctx->api_tune.up_sched : by_shape;
+    const int down = ctx->api_tune.down_sched ? ctx->api_tune.down_sched : by_shape;
+    a1.equal_heights = up == 1;
+    a2.equal_heights = down != 2;
+    HIP_TRY(launch_gemm_plans(a1, a2, n, reinterpret_cast<GemmPlan *>(ws + W.plans), ctx->api_tune.splitk, cs));
+    if (up == 1) a1.plan = nullptr;
+    if (down == 1) a2.plan = nullptr;
+  }
+
   L.stats.layer_calls++;
   // Will the launch that runs expert e (its largest group having `rows` rows) read the quantised
   // copy in the staging area?  Then it only needs the bytes to have landed, not the expansion.
@@ -817,7 +848,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       combined = true;
     } else {
       rc = run_experts(ctx, decode, a1, a2, mask, blind_one ? c.k : E, n, T, cs,
-                       shared_in_routed_launch ? &s1 : nullptr, shared_in_routed_launch ? &s2 : nullptr);
+                       shared_in_routed_launch ? &s1 : nullptr, shared_in_routed_launch ? &s2 : nullptr, nullptr,
+                       true);
       if (rc) return rc;
     }
     HIP_TRY(hipEventRecord(L.set->group_done, cs));
@@ -859,7 +891,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
           rc = wait_ready(L, L.expert_slot[e], reads_copy(e, hit_max), cs);
           if (rc) return rc;
         }
-      rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs);
+      rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs, nullptr, nullptr, nullptr,
+                       true);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(L.set->group_done, cs));
       for (int e = 0; e < E; ++e)
@@ -915,7 +948,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   }
   if (!combined) {
     Timer t(ctx, cs, MOE_K_COMBINE);
-    HIP_TRY(launch_combine(reinterpret_cast<const float *>(ws + W.Y), W.splitk, (long long)n * c.d,
+    HIP_TRY(launch_combine(reinterpret_cast<const float *>(ws + W.Y), a2.splitk, (long long)n * c.d,
                            reinterpret_cast<const float *>(ws + W.w),
                            reinterpret_cast<const int32_t *>(ws + W.inv_perm),
                            c.I_shared ? reinterpret_cast<const float *>(ws + W.Ys) : nullptr, 1, 0, T, c.d,
@@ -1466,10 +1499,22 @@ int moe_debug_gemm_choice(int mode, int gathered, long long a_rows, int lda, int
   return gemm_kernel_choice((GemmMode)mode, a, max_rows, n_groups);
 }
 
+int moe_debug_plans(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *host_out, void *stream) {
+  if (!ctx || !dev_workspace || !host_out || T <= 0) return fail(MOE_E_ARG, "bad argument to moe_debug_plans");
+  const WsLayout W = ws_layout(ctx->cfg, T, ctx->api_tune.splitk);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  HIP_TRY(hipMemcpyAsync(host_out, reinterpret_cast<const char *>(dev_workspace) + W.plans, 2 * sizeof(GemmPlan),
+                         hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return MOE_OK;
+}
+
 int moe_tune(moe_ctx *ctx, int mode, int variant) {
   if (!ctx) return fail(MOE_E_ARG, "ctx is NULL");
-  if (mode < 0 || mode > 10 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
+  if (mode < 0 || mode > 12 || variant < 0) return fail(MOE_E_ARG, "bad mode/variant");
   switch (mode) {
+    case 12: ctx->api_tune.up_sched = variant; return MOE_OK;
+    case 11: ctx->api_tune.down_sched = variant; return MOE_OK;
     case 10: ctx->tune.skinny_waves = variant; return MOE_OK;
     case 9: ctx->api_tune.matvec_max_rows = variant; return MOE_OK;
     case 8:

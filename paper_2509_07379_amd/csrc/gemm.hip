@@ -50,6 +50,7 @@ __device__ __forceinline__ int swz(int row, int kc) { return row * ROW_BYTES + (
 // Tile decode shared by both kernels.
 struct TileInfo {
   int grp, row0, tile_row0, rows_valid, n0, ks;
+  int ns;   // K slices of this tile (persistent kernel; the others use args.splitk)
 };
 
 template <int BM, int BN_OUT>
@@ -96,55 +97,88 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs &args, TileInfo &t) {
   return t.rows_valid > 0;
 }
 
-// The same tile numbering for a kernel whose blocks walk over several tiles: count once, then
-// decode logical tile l.
+// Work items of the persistent kernel.  A group of cnt rows is cnt / BM full row tiles and, if rows are
+// left over, one remainder tile (instead of tiles of equal height: a row tile's cost is its weight
+// traffic plus its MFMAs, so two full tiles and a short one are cheaper than three of medium height).
+// A full tile is cut into s_f K slices, a remainder tile into s_r; an item is (row tile, column tile,
+// K slice).  Inside a group the row tiles are numbered in panels of 8 (the remainder tile is the last
+// row tile): inside a panel the row tile runs fastest, then the K slice, then the column tile, so the
+// blocks of an XCD that work side by side share each operand tile through their L2 and walk the
+// same K range at the same time.
+// (args.equal_heights: the other way to cut a group, ceil(cnt / BM) tiles of equal height rounded up to 32
+// rows, all of them "full" tiles as far as the numbering goes.  Equal tiles keep the blocks of an XCD in
+// step with each other, which the down projection, whose both operands stream from HBM, needs more
+// than it needs the cheaper cut.)
 template <int BM, int BN_OUT>
-__device__ __forceinline__ int count_tiles(const GemmArgs &args) {
-  const int per_m = ((args.N + BN_OUT - 1) / BN_OUT) * args.splitk;
-  if (!args.offsets) return ((args.single_rows + BM - 1) / BM) * per_m;
-  int total = 0;
-  for (int e = 0; e < args.n_groups; ++e)
-    if ((args.group_mask >> e) & 1ull) {
-      int cnt = args.offsets[e + 1] - args.offsets[e];
-      total += ((cnt + BM - 1) / BM) * per_m;
-    }
-  return total;
+__device__ __forceinline__ int group_items(const GemmArgs &args, int cnt, int s_f, int s_r) {
+  const int ntn = (args.N + BN_OUT - 1) / BN_OUT;
+  if (args.equal_heights) return ntn * ((cnt + BM - 1) / BM) * s_f;
+  return ntn * ((cnt / BM) * s_f + ((cnt % BM) ? s_r : 0));
 }
 
 template <int BM, int BN_OUT>
-__device__ __forceinline__ bool decode_logical_tile(const GemmArgs &args, int l, TileInfo &t) {
-  const int per_m = ((args.N + BN_OUT - 1) / BN_OUT) * args.splitk;
+__device__ __forceinline__ int count_items(const GemmArgs &args, int s_f, int s_r) {
+  if (!args.offsets) return group_items<BM, BN_OUT>(args, args.single_rows, s_f, s_r);
+  int total = 0;
+  for (int e = 0; e < args.n_groups; ++e)
+    if ((args.group_mask >> e) & 1ull)
+      total += group_items<BM, BN_OUT>(args, args.offsets[e + 1] - args.offsets[e], s_f, s_r);
+  return total;
+}
+
+// Item l of the launch.  plan != NULL: the first item of every group is in plan->item_begin (lane j
+// looks at group j, one ballot finds l's group); otherwise the groups are walked.
+template <int BM, int BN_OUT>
+__device__ __forceinline__ void decode_item(const GemmArgs &args, const GemmPlan *plan, int s_f, int s_r, int lane,
+                                            int l, TileInfo &t) {
+  const int ntn = (args.N + BN_OUT - 1) / BN_OUT;
   int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
   if (args.offsets) {
-    for (int e = 0; e < args.n_groups; ++e) {
-      if (!((args.group_mask >> e) & 1ull)) continue;
-      int o = args.offsets[e], c = args.offsets[e + 1] - o;
-      int tiles = ((c + BM - 1) / BM) * per_m;
-      if (l < tiles) { grp = e; row0 = o; cnt = c; break; }
-      l -= tiles;
+    if (plan) {
+      const int end_j = plan->item_begin[min(lane + 1, kMaxExperts)];
+      grp = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < args.n_groups && end_j <= l)));
+      l -= plan->item_begin[grp];
+      row0 = args.offsets[grp];
+      cnt = args.offsets[grp + 1] - row0;
+    } else {
+      for (int e = 0; e < args.n_groups; ++e) {
+        if (!((args.group_mask >> e) & 1ull)) continue;
+        const int o = args.offsets[e], c = args.offsets[e + 1] - o;
+        const int items = group_items<BM, BN_OUT>(args, c, s_f, s_r);
+        if (l < items) { grp = e; row0 = o; cnt = c; break; }
+        l -= items;
+      }
     }
   }
-  // Row tiles are numbered in panels of 8: inside a panel the row tile runs fastest, then the
-  // column tile.  The 32 blocks of an XCD that work side by side then cover 8 row tiles x 4 column
-  // tiles, and their L2 fetches each operand tile once for 4 (A) or 8 (B) of them; a group of at
-  // most 8 row tiles is one panel (equalising the panels' heights measured no better).
   constexpr int PANEL = 8;
-  const int mt = (cnt + BM - 1) / BM;
-  const int panel = l / (PANEL * per_m);
-  const int q = l - panel * (PANEL * per_m);
-  const int pm = min(PANEL, mt - panel * PANEL);
-  const int m_idx = panel * PANEL + q % pm;
-  const int rest = q / pm;
-  t.ks = rest % args.splitk;
-  const int n_idx = rest / args.splitk;
-  int rpt = (((cnt + mt - 1) / mt) + 31) & ~31;   // balanced tile height
-  if (rpt > BM) rpt = BM;
-  t.grp = grp;
-  t.row0 = row0;
-  t.tile_row0 = m_idx * rpt;
-  t.rows_valid = min(rpt, cnt - t.tile_row0);
-  t.n0 = n_idx * BN_OUT;
-  return t.rows_valid > 0;
+  const int mf = args.equal_heights ? (cnt + BM - 1) / BM : cnt / BM;
+  const int hr = args.equal_heights ? 0 : ((cnt % BM) ? 1 : 0);
+  int height = BM;
+  if (args.equal_heights && mf > 0) height = min(BM, (((cnt + mf - 1) / mf) + 31) & ~31);
+  const int ipp = PANEL * s_f * ntn;              // items of a panel of 8 full tiles
+  const int panel = min(l / ipp, mf / PANEL);
+  l -= panel * ipp;
+  const int pf = min(PANEL, mf - panel * PANEL);  // full tiles of this panel
+  const int pr = (panel == mf / PANEL) ? hr : 0;  // ... and the remainder tile, in the group's last panel
+  const int per_n = pf * s_f + pr * s_r;          // > 0 for every valid item
+  const int n_idx = l / per_n;
+  int r = l - n_idx * per_n;
+  int ks = 0;
+  for (;; ++ks) {
+    const int here = (ks < s_f ? pf : 0) + (ks < s_r ? pr : 0);
+    if (r < here || ks >= 7) break;
+    r -= here;
+  }
+  const bool is_rem = ks < s_f ? r >= pf : true;
+  const int m_idx = panel * PANEL + (is_rem ? pf : r);
+  // (everything here is the same for all lanes: say so, so that it lives in scalar registers)
+  t.grp = __builtin_amdgcn_readfirstlane(grp);
+  t.row0 = __builtin_amdgcn_readfirstlane(row0);
+  t.tile_row0 = __builtin_amdgcn_readfirstlane(m_idx * height);
+  t.rows_valid = __builtin_amdgcn_readfirstlane(min(height, cnt - m_idx * height));
+  t.n0 = __builtin_amdgcn_readfirstlane(n_idx * BN_OUT);
+  t.ks = __builtin_amdgcn_readfirstlane(ks);
+  t.ns = __builtin_amdgcn_readfirstlane(is_rem ? s_r : s_f);
 }
 
 // A value the optimiser cannot trace back: what is computed from it inside a loop stays inside.
@@ -470,6 +504,120 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_dma_kerne
 }
 
 // ---------------------------------------------------------------------------------------------
+// Short row tiles of the persistent kernel: at most 64 rows, i.e. a small group or what a group leaves
+// over after its full tiles.  Such a tile has almost no MFMA work; its time is the 256-row weight tile's
+// way from memory through LDS, and as the only (or first) reader of those weights it waits for HBM,
+// not for L2.  So it gets a pipeline of its own in the same LDS: four stages of 40 KB ([A 64 rows]
+// [B 256 rows], the same 128-byte rows and swizzle), loads three K steps ahead, one barrier per K step,
+// every wave both loading and multiplying (wave (wm, wn) owns rows 32 wm.. and the same two column
+// fragments as in a full tile).  Rows past the tile's last one are never fetched.  The results leave
+// without the LDS transposition (there is little to store).  On entry no load may be in flight and
+// nobody may still use LDS; on exit the same holds.
+constexpr int kSmallTileRows = 64;
+
+template <int MODE>
+__device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileInfo &t, unsigned char *smem,
+                                              int lane, int wave) {
+  constexpr int BN = 256, SA = kSmallTileRows, WARPS_M = 2, WARPS_N = 4, FN = 2;
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int SST = (SA + BN) * ROW_BYTES;   // 40 KB per stage
+  constexpr int NST = 4, NLB = BN / 8 / 8;     // stages; B row groups (wave-wide loads) per wave and stage
+  const int wm = wave >> 2, wn = wave & 3;
+  const int kt_total = args.K / BK;
+  const int kt_begin = (int)((long long)kt_total * t.ks / t.ns);
+  const int nk = (int)((long long)kt_total * (t.ks + 1) / t.ns) - kt_begin;
+
+  // This lane's sources.  A: row group `wave` (rows 8 wave .. 8 wave + 7); B: row groups wave + 8 i.  Lane l
+  // lands at row 8 g + l / 8, chunk position l % 8 and fetches the chunk the swizzle maps there; g & 1 is
+  // wave & 1 for all of them.
+  const int lane_s = opaque(lane);
+  const int kc16 = ((lane_s & 7) ^ ((wave & 1) * 4 + (lane_s >> 4))) * 16;
+  const int a_row = wave * 8 + (lane_s >> 3);
+  const int p = t.row0 + t.tile_row0 + (a_row < t.rows_valid ? a_row : 0);
+  uint32_t a_voff = 0x80000000u;   // beyond the buffer's range: no memory traffic, zeros
+  if (a_row < t.rows_valid) {
+    const long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)a_row;
+    a_voff = (uint32_t)(srow * args.lda * 2 + kc16);
+  }
+  const uint16_t *a_base = args.perm ? args.A : args.A + (long long)(t.row0 + t.tile_row0) * args.lda;
+  __amdgpu_buffer_rsrc_t a_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(a_base), 0, 0x7FFFFFFF, 0x00020000);
+  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride + args.b0_off;
+  __amdgpu_buffer_rsrc_t b_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(wptr), 0, 0x7FFFFFFF, 0x00020000);
+  const uint32_t b_voff = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16);
+  int b_soff[NLB];
+#pragma unroll
+  for (int i = 0; i < NLB; ++i) {
+    int r = (wave + 8 * i) * 8;
+    long long up = 0;
+    if (MODE == GEMM_SWIGLU && r >= BN / 2) { up = args.b1_off - args.b0_off; r -= BN / 2; }
+    b_soff[i] = (int)(up + (long long)(t.n0 + r) * args.ldb * 2);
+  }
+  const int lrow = lane_s & 31, lk = lane_s >> 5;
+  const int a_addr = swz(wm * 32 + lrow, lk);
+  int b_addr[FN];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
+                                           : (j * WARPS_N + wn) * 32 + lrow;
+    b_addr[j] = SA * ROW_BYTES + swz(brow, lk);
+  }
+  const int fm_valid = wm * 32 < t.rows_valid ? 1 : 0;
+
+#define MOE_SISSUE(q_)                                                                               \
+  do {                                                                                               \
+    unsigned char *st_ = smem + ((q_) % NST) * SST;                                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < NLB; ++i_)                                               \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(st_ + SA * ROW_BYTES + (wave + 8 * i_) * 1024), \
+                                               16, (int)b_voff, b_soff[i_] + (kt_begin + (q_)) * ROW_BYTES, 0, 0); \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)(st_ + wave * 1024), 16, (int)a_voff, \
+                                             (kt_begin + (q_)) * ROW_BYTES, 0, 0);                   \
+  } while (0)
+
+  floatx16 acc[1][FN];
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][j][r] = 0.0f;
+
+  for (int q = 0; q < NST - 1; ++q)
+    if (q < nk) MOE_SISSUE(q);
+  for (int H = 0; H < nk; ++H) {
+    // this wave's loads of stage H have landed: the stages requested after it may still be in flight
+    const int later = nk - 1 - H;
+    __builtin_amdgcn_sched_barrier(0);
+    if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (NLB + 1)));
+    else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (NLB + 1));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();   // ... and everybody's; the stage read in the last step is free
+    __builtin_amdgcn_sched_barrier(0);
+    if (H + NST - 1 < nk) MOE_SISSUE(H + NST - 1);
+    if (fm_valid) {
+      const unsigned char *st = smem + (H % NST) * SST;
+      bf16x8 af[4], bf[FN][4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        af[ks] = *reinterpret_cast<const bf16x8 *>(st + (a_addr ^ (ks << 5)));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bf[j][ks] = *reinterpret_cast<const bf16x8 *>(st + (b_addr[j] ^ (ks << 5)));
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j][ks], af[ks], acc[0][j], 0, 0, 0);
+    }
+  }
+#undef MOE_SISSUE
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's fragment reads are done
+  __builtin_amdgcn_s_barrier();         // ... and everybody's: LDS is free
+  __builtin_amdgcn_sched_barrier(0);
+  store_tile_cols<MODE, 1, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc, 0, 1, nullptr);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Ping-pong kernel: 256 x 256 x 64 tiles in a two-stage LDS ring, eight waves in two groups of
 // four.  Waves w and w+4 of a block sit on the same SIMD; the two groups run the same loop one
 // barrier interval ("tick") apart, so while one wave of a SIMD issues 16 MFMAs, its partner pulls
@@ -504,20 +652,75 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   const int grp = wave >> 2;          // the two waves of a SIMD are in different groups
   const int wm = grp, wn = wave & 3;
 
-  // A block walks over the tiles (b % 8) * chunk + b / 8 + i * (blocks / 8), i = 0, 1, ...: the blocks
-  // of one XCD (every 8th) work on consecutive logical tiles at any time, and the metadata and first
-  // loads of the next tile are requested before the current tile's results are stored.
-  const int total = count_tiles<BM, BN_OUT>(args);
-  const int chunk = (total + 7) >> 3;
-  const int xbase = ((int)blockIdx.x & 7) * chunk;
+  // Work items (decode_item).  With a plan the blocks take them from eight queues, one per XCD (blocks
+  // go round-robin over the XCDs, so b % 8 is a block's XCD): item v of a range goes to whoever
+  // increments that range's counter from v, which keeps every block busy until its range is used up,
+  // whatever the tiles cost; then it goes on with the other XCDs' ranges.  Without a plan block b walks
+  // the items (b % 8) * chunk + b / 8 + i * (blocks / 8).  Either way the blocks of one XCD work on
+  // consecutive items at any time, and the metadata and first loads of the next item are requested
+  // before the current item's results are stored.  The item after the next one travels from thread 0
+  // to the block through the first word of wave 0's epilogue buffer (written at the top of an item,
+  // read behind the barrier that follows, long before any wave stores results again).
+  GemmPlan *const plan = args.plan;
+  const bool dyn = plan != nullptr && args.plan_queue;
+  const GemmPlan *const qplan = dyn ? plan : nullptr;   // the groups' first items, for the queues' item numbers
+  const int s_f = __builtin_amdgcn_readfirstlane(plan ? plan->s_full : args.splitk);
+  const int s_r = __builtin_amdgcn_readfirstlane(plan ? plan->s_rem : args.splitk);
+  volatile int *qbox = reinterpret_cast<volatile int *>(smem + 2 * STAGE);
+  const int xcd = (int)blockIdx.x & 7;
   const int nslots = (int)gridDim.x >> 3;
-  int slot = (int)blockIdx.x >> 3;
-  if (slot >= chunk || xbase + slot >= total) return;
+  int own_b = 0, own_len = 0, st_end = 0;   // this XCD's range (plan) / end of this block's range (no plan)
+  int cur, nxt;                             // item being computed, item after it (-1: none)
+  int pend_v = 0;                           // thread 0: its last increment of the own range's counter
+  bool pend_issued = false;
+#define MOE_PTAKE_OWN() __hip_atomic_fetch_add(&plan->queue[xcd * 16], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+  // an item of another XCD's range (own range used up), or -1 when every range is
+  auto steal = [&]() -> int {
+    for (int i = 1; i < 8; ++i) {
+      const int xx = (xcd + i) & 7;
+      const int b = plan->xcd_begin[xx], len = plan->xcd_begin[xx + 1] - b;
+      if (len <= 0) continue;
+      const int v = __hip_atomic_fetch_add(&plan->queue[xx * 16], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (v < len) return b + v;
+    }
+    return -1;
+  };
+  if (dyn) {
+    own_b = __builtin_amdgcn_readfirstlane(plan->xcd_begin[xcd]);
+    own_len = __builtin_amdgcn_readfirstlane(plan->xcd_begin[xcd + 1]) - own_b;
+    if (tid == 0) {
+      int it[2];
+      for (int q = 0; q < 2; ++q) {
+        int v = own_len > 0 ? MOE_PTAKE_OWN() : own_len;
+        it[q] = v < own_len ? own_b + v : steal();
+      }
+      qbox[0] = it[0];
+      qbox[1] = it[1];
+    }
+    __syncthreads();
+    cur = qbox[0];
+    nxt = qbox[1];
+    __syncthreads();
+    if (nxt >= 0 && own_len > 0) {   // the third item: requested now, looked at when the first one starts
+      if (tid == 0) pend_v = MOE_PTAKE_OWN();
+      pend_issued = true;
+    }
+  } else {
+    const int total = count_items<BM, BN_OUT>(args, s_f, s_r);
+    const int chunk = (total + 7) >> 3;
+    const int slot = (int)blockIdx.x >> 3;
+    st_end = min(total, (xcd + 1) * chunk);
+    cur = slot < chunk && xcd * chunk + slot < st_end ? xcd * chunk + slot : -1;
+    nxt = cur >= 0 && cur + nslots < st_end ? cur + nslots : -1;
+  }
+  cur = __builtin_amdgcn_readfirstlane(cur);
+  nxt = __builtin_amdgcn_readfirstlane(nxt);
+  if (cur < 0) return;
 
   // The last column tile is moved back so that it ends at column N - 1 (the overlap is computed
   // twice, to the same bits): every B row of a tile exists, and its offset is affine in the row.
   TileInfo t;
-  decode_logical_tile<BM, BN_OUT>(args, xbase + slot, t);
+  decode_item<BM, BN_OUT>(args, qplan, s_f, s_r, lane, cur, t);
   t.n0 = min(t.n0, args.N - BN_OUT);
 
   // Row group g (0..63) is tile rows 8g..8g+7 of a stage (A rows 0..255, then B rows 0..255) and
@@ -547,7 +750,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
       const long long srow_ =                                                                        \
           args.perm ? (long long)((prow_)[i_] / args.k_top) : (long long)(prow_)[i_];                \
-      src[i_] = (uint32_t)(srow_ * args.lda * 2 + kc16_);                                            \
+      /* rows past the tile's last one: an offset beyond the buffer's range, which costs no memory   \
+         traffic (the load returns zeros; what the MFMAs make of those rows is never stored) */      \
+      src[i_] = MOE_PGROUP(i_) * 8 + (lane_s >> 3) < (tt_).rows_valid                                \
+                    ? (uint32_t)(srow_ * args.lda * 2 + kc16_) : 0x80000000u;                        \
     }                                                                                                \
     if (!args.perm)                                                                                  \
       a_rsrc = __builtin_amdgcn_make_buffer_rsrc(                                                    \
@@ -567,8 +773,8 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     const char *wptr_ = args.wbase + (long long)args.slot[(tt_).grp] * args.wstride + args.b0_off;   \
     b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(wptr_), 0, 0x7FFFFFFF, 0x00020000); \
     const int kt_total_ = args.K / BK;                                                               \
-    kt_begin = (int)((long long)kt_total_ * (tt_).ks / args.splitk);                                 \
-    nk = (int)((long long)kt_total_ * ((tt_).ks + 1) / args.splitk) - kt_begin;                      \
+    kt_begin = (int)((long long)kt_total_ * (tt_).ks / (tt_).ns);                                    \
+    nk = (int)((long long)kt_total_ * ((tt_).ks + 1) / (tt_).ns) - kt_begin;                         \
     fm_valid = 0;                                                                                    \
     _Pragma("unroll") for (int i_ = 0; i_ < FM; ++i_)                                                \
       fm_valid += ((i_ * WARPS_M + wm) * 32 < (tt_).rows_valid) ? 1 : 0;                             \
@@ -691,16 +897,21 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     }                                                                                                \
   } while (0)
 
-  MOE_PPROLOGUE();
+  if (t.rows_valid > kSmallTileRows) MOE_PPROLOGUE();
   for (;;) {
-    const int nslot = slot + nslots;
-    const bool has_next = nslot < chunk && xbase + nslot < total;
+    const bool has_next = nxt >= 0;
     TileInfo tn = t;
     if (has_next) {
-      decode_logical_tile<BM, BN_OUT>(args, xbase + nslot, tn);
+      decode_item<BM, BN_OUT>(args, qplan, s_f, s_r, lane, nxt, tn);
       tn.n0 = min(tn.n0, args.N - BN_OUT);
     }
     MOE_PVMCNT(0);   // this tile's first loads have landed (and the previous tile's stores are out)
+    // the item after the next one: thread 0's increment has come back with the loads
+    if (dyn && tid == 0) {
+      int it = -1;
+      if (has_next) it = pend_issued && pend_v < own_len ? own_b + pend_v : steal();
+      qbox[0] = it;
+    }
 
     // LDS byte offset of this lane's 16 bytes of K slice 0 inside a stage; slice ks is at ^ (ks << 5)
     // (the swizzle XORs the chunk index, and slice ks only changes bits 1..2 of it).  Derived from
@@ -728,6 +939,31 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     MOE_PBARRIER();
+    int after_next;
+    if (dyn) after_next = qbox[0];
+    else after_next = has_next && nxt + nslots < st_end ? nxt + nslots : -1;
+    after_next = __builtin_amdgcn_readfirstlane(after_next);
+    if (t.rows_valid <= kSmallTileRows) {
+      // A short tile (pp_small_tile): no loads were requested for it, and its last stage lies over the
+      // mailbox word, which everybody has to have read first.
+      MOE_PBARRIER();
+      pp_small_tile<MODE>(args, t, smem, lane, wave);
+      if (!has_next) break;
+      pend_issued = dyn && after_next >= 0 && own_len > 0;
+      if (pend_issued && tid == 0) pend_v = MOE_PTAKE_OWN();
+      if (tn.rows_valid > kSmallTileRows) {
+        const int lane_s = opaque(lane);
+        int prow_n[NL];
+        MOE_PPERM(tn, prow_n);
+        MOE_PSRC(tn, prow_n);
+        MOE_PTILE_SETUP(tn);
+        MOE_PPROLOGUE();
+      }
+      t = tn;
+      cur = nxt;
+      nxt = after_next;
+      continue;
+    }
     if (grp == 1) MOE_PBARRIER();   // group 1 runs one tick behind
     switch (fm_valid) {
       case 0: MOE_PP_LOOP(0); break;
@@ -743,7 +979,8 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     const int fm_cur = fm_valid;
     const int lane_s = opaque(lane);
     int prow_n[NL];
-    if (has_next) {
+    const bool next_full = has_next && tn.rows_valid > kSmallTileRows;   // a short tile sets itself up
+    if (next_full) {
       MOE_PPERM(tn, prow_n);
     } else {
 #pragma unroll
@@ -751,6 +988,11 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     }
     store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, 0, FM / 2, xpose);
     if (has_next) {
+      // the request for the item after the next two goes out ahead of the loads, so it is back with them
+      pend_issued = dyn && after_next >= 0 && own_len > 0;
+      if (pend_issued && tid == 0) pend_v = MOE_PTAKE_OWN();
+    }
+    if (next_full) {
       MOE_PSRC(tn, prow_n);
       MOE_PTILE_SETUP(tn);
       MOE_PPROLOGUE();
@@ -758,8 +1000,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     store_tile_cols<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_cur, acc, FM / 2, FM, xpose);
     if (!has_next) break;
     t = tn;
-    slot = nslot;
+    cur = nxt;
+    nxt = after_next;
   }
+#undef MOE_PTAKE_OWN
 #undef MOE_PPROLOGUE
 #undef MOE_PP_LOOP
 #undef MOE_PP_STEP
@@ -925,10 +1169,24 @@ static int pp_grid_blocks() {
   return blocks;
 }
 
+// Blocks of a persistent launch: one per compute unit (a multiple of 8, spread over the 8 XCDs), fewer
+// if there cannot be that many items; a launch that runs beside other streams' small kernels leaves
+// them some units, whose LDS it would otherwise fill.
+static int pp_grid(const GemmArgs &args, GemmMode mode, int max_rows, int n_groups_in_mask, int slices) {
+  const int bn_out = mode == GEMM_SWIGLU ? 128 : 256;
+  const long long n_tiles_n = (args.N + bn_out - 1) / bn_out;
+  const long long m_tiles_ub = (long long)max_rows / kPpTileRows + n_groups_in_mask;
+  long long ub = m_tiles_ub * n_tiles_n * slices;
+  if (ub <= 0) return 0;
+  ub = (ub + 7) / 8 * 8;
+  int cap = pp_grid_blocks() - (args.spare_cus > 0 ? (args.spare_cus + 7) / 8 * 8 : 0);
+  if (cap < 8) cap = 8;
+  return (int)(ub < cap ? ub : cap);
+}
+
 template <int MODE>
 hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BM = 256, BN = 256;
-  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
   // two stages of A and B tiles + 4 KB per wave for the epilogue's transposition
   constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES + 8 * 4096;
   auto kern = grouped_gemm_pp_kernel<MODE>;
@@ -939,19 +1197,103 @@ hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, h
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const long long n_tiles_n = (args.N + BN_OUT - 1) / BN_OUT;
-  const long long m_tiles_ub = (long long)max_rows / BM + n_groups_in_mask;
-  long long ub = m_tiles_ub * n_tiles_n * args.splitk;
-  if (ub <= 0) return hipSuccess;
-  ub = (ub + 7) / 8 * 8;
-  if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
-  // blocks are a multiple of 8 (one per compute unit, spread over the 8 XCDs); a launch that runs
-  // beside other streams' small kernels leaves them some units, whose LDS it would otherwise fill
-  int cap = pp_grid_blocks() - (args.spare_cus > 0 ? (args.spare_cus + 7) / 8 * 8 : 0);
-  if (cap < 8) cap = 8;
-  const long long grid = ub < cap ? ub : cap;
+  const int grid = pp_grid(args, (GemmMode)MODE, max_rows, n_groups_in_mask,
+                           args.plan ? (args.max_splitk > 0 ? args.max_splitk : 1) : args.splitk);
+  if (grid <= 0) return hipSuccess;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), smem, stream, args);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// The plan of a grouped launch (GemmPlan): one wave, lane g looks at group g.
+//   K slices: a full tile costs 1 (its K loop), a remainder tile of r rows c(r) = max(0.26, its share of
+//   the MFMAs): below that the tile is bound by the weight tile it has to pull through LDS.  With G
+//   blocks, n_f full and n_r remainder tiles cut into s_f and s_r slices take about
+//     ceil(n_f s_f / G) / s_f + ceil(n_r s_r / G) c / s_r + eps (ceil(n_f s_f / G) + ceil(n_r s_r / G))
+//   (eps: storing an item's fp32 plane, relative to a whole K loop); the pair that minimises this is
+//   taken, fewer slices on a tie.  Slices keep at least 8 K steps.
+//   Ranges: the item list is cut where the estimated cost reaches 1/8, 2/8, ... of the total.
+struct PlanParams {
+  const int32_t *offsets;
+  unsigned long long mask;
+  int n_groups, ntn, kt_total, smax, force_s, grid, equal_heights;
+  float eps;
+  GemmPlan *out;
+};
+
+__device__ __forceinline__ float wave_sum_f(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+  return v;
+}
+
+__device__ void make_plan(const PlanParams &p, int lane) {
+  GemmPlan *out = p.out;
+  const bool active = lane < p.n_groups && ((p.mask >> lane) & 1ull);
+  const int cnt = active ? p.offsets[lane + 1] - p.offsets[lane] : 0;
+  const int mf = p.equal_heights ? (cnt + kPpTileRows - 1) / kPpTileRows : cnt / kPpTileRows;
+  const int rem = p.equal_heights ? 0 : cnt % kPpTileRows, hr = rem ? 1 : 0;
+  // (measured: a tile of at most 64 rows takes half the time of a full one, bound by the weight tile's
+  // way in from HBM; taller ones are priced by their share of the MFMAs)
+  const float c_r = hr ? fmaxf(0.5f, 0.08f + 0.92f * (float)((rem + 63) / 64) * 0.25f) : 0.0f;
+  const float n_f = wave_sum_f((float)mf) * p.ntn, n_r = wave_sum_f((float)hr) * p.ntn;
+  const float c_avg = n_r > 0.0f ? wave_sum_f(c_r) * p.ntn / n_r : 0.0f;
+  int s_f = 1, s_r = 1;
+  if (p.force_s > 0) {
+    s_f = s_r = p.force_s < p.smax ? p.force_s : p.smax;
+  } else {
+    float best = 3.0e38f;
+    const float G = (float)p.grid;
+    for (int a = 1; a <= p.smax; ++a)
+      for (int b = 1; b <= p.smax; ++b) {
+        const float rf = ceilf(n_f * a / G), rr = ceilf(n_r * b / G);
+        const float m = rf / a + rr * c_avg / b + p.eps * (rf + rr);
+        if (m < best * 0.999f) { best = m; s_f = a; s_r = b; }
+      }
+  }
+  const int items = p.ntn * (mf * s_f + hr * s_r);
+  const float cost = p.ntn * ((float)mf + c_r);
+  int item_end = items;
+  float cost_end = cost;
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) {
+    const int oi = __shfl_up(item_end, s);
+    const float oc = __shfl_up(cost_end, s);
+    if (lane >= s) { item_end += oi; cost_end += oc; }
+  }
+  const int n_items = __shfl(item_end, 63);
+  const float total = __shfl(cost_end, 63);
+  out->item_begin[lane + 1] = item_end;
+  if (lane == 0) {
+    out->item_begin[0] = 0;
+    out->n_items = n_items;
+    out->s_full = s_f;
+    out->s_rem = s_r;
+    out->xcd_begin[0] = 0;
+    out->xcd_begin[8] = n_items;
+  }
+  // boundary j: in the group whose cost range holds j/8 of the total, at the same fraction of its items
+  // (a group's range begins exactly where the one before it ends: no target falls between two groups)
+  const float prev_end = __shfl_up(cost_end, 1);
+  const float cost_begin = lane ? prev_end : 0.0f;
+  for (int j = 1; j < 8; ++j) {
+    const float target = total * (float)j * 0.125f;
+    const bool here = cost > 0.0f && cost_begin <= target && target < cost_end;
+    const unsigned long long who = __ballot(here);
+    if (who == 0) {   // (rounding at the very end of the list, or nothing to do at all)
+      if (lane == 0) out->xcd_begin[j] = n_items;
+    } else if (lane == __ffsll((long long)who) - 1) {
+      int at = item_end - items + (int)((target - cost_begin) / cost * (float)items);
+      out->xcd_begin[j] = at < item_end ? at : item_end;
+    }
+  }
+  out->queue[lane] = 0;
+  out->queue[lane + 64] = 0;
+}
+
+__global__ __launch_bounds__(64) void gemm_plan_kernel(const PlanParams p0, const PlanParams p1) {
+  if (p0.out) make_plan(p0, threadIdx.x);
+  if (p1.out) make_plan(p1, threadIdx.x);
 }
 
 template <int MODE>
@@ -974,15 +1316,20 @@ hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask
 
 // args.tune.gemm_variant: 0 picks by shape; a test or tuning run forces 1 = 128 x 128 tiles, 6 = 256 x 256
 // tiles of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
-int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask) {
-  if (args.K % BK != 0) return 100;
-  int v = args.tune.gemm_variant[mode];
+static bool pp_possible(GemmMode mode, const GemmArgs &args) {
   // The ping-pong kernel addresses a gathered A from its first row (any of its a_rows rows can be
   // named by the permutation), an A used in place from the tile's first row (256 rows), and the
   // blob from its first B row, all with 31-bit byte offsets.
-  const bool pp_ok = (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
-                     (args.b1_off - args.b0_off) + (long long)args.N * args.ldb * 2 < 0x7FFFFFFFll &&
-                     args.b1_off >= args.b0_off && args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
+  return args.K % BK == 0 && (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
+         (args.b1_off - args.b0_off) + (long long)args.N * args.ldb * 2 < 0x7FFFFFFFll &&
+         args.b1_off >= args.b0_off && args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
+}
+
+int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask) {
+  if (args.plan) return 12;   // a layer call that runs from a plan runs on the persistent kernel throughout
+  if (args.K % BK != 0) return 100;
+  int v = args.tune.gemm_variant[mode];
+  const bool pp_ok = pp_possible(mode, args);
   if (v == 0) {
     // 256 x 256 ping-pong tiles unless the groups are small on average, where the finer 128 x 128
     // tiles waste less of the matrix cores on empty rows
@@ -1001,6 +1348,49 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
     case 12: return launch_pp<MODE>(args, max_rows, n_groups_in_mask, stream);
     default: return launch_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
   }
+}
+
+hipError_t launch_gemm_plans(GemmArgs &a1, GemmArgs &a2, int total_rows, GemmPlan *plans, int force_splitk,
+                             hipStream_t stream) {
+  a1.plan = a2.plan = nullptr;
+  a1.plan_queue = a2.plan_queue = 0;
+  if (!plans || !a1.offsets || !a2.offsets) return hipSuccess;
+  GemmArgs *a[2] = {&a1, &a2};
+  const GemmMode mode[2] = {GEMM_SWIGLU, GEMM_PLAIN_F32};
+  for (int i = 0; i < 2; ++i) {
+    const int v = a[i]->tune.gemm_variant[mode[i]];
+    if (!pp_possible(mode[i], *a[i]) || (v != 0 && v != 12)) return hipSuccess;
+  }
+  PlanParams p[2] = {};
+  for (int i = 0; i < 2; ++i) {
+    const int kt_total = a[i]->K / BK;
+    int smax = 1;   // SwiGLU needs whole sums; planes need room in the workspace; a slice keeps 8 K steps
+    if (mode[i] == GEMM_PLAIN_F32) smax = a[i]->splitk;
+    if (smax < 1) smax = 1;
+    a[i]->plan = plans + i;
+    a[i]->max_splitk = smax;
+    const int bn_out = mode[i] == GEMM_SWIGLU ? 128 : 256;
+    p[i].offsets = a[i]->offsets;
+    p[i].mask = a[i]->n_groups >= 64 ? ~0ull : ((1ull << a[i]->n_groups) - 1ull);
+    p[i].n_groups = a[i]->n_groups;
+    p[i].ntn = (a[i]->N + bn_out - 1) / bn_out;
+    p[i].kt_total = kt_total;
+    p[i].smax = smax;
+    // every tile of the down GEMM gets the same K slices (a2.splitk): blocks that work side by side then
+    // walk the same K range, whatever tiles they hold
+    p[i].force_s = mode[i] == GEMM_PLAIN_F32 ? a[i]->splitk : 0;
+    p[i].equal_heights = a[i]->equal_heights;
+    // the whole chip, whatever share of it a launch of this layer call will get: the slices must not
+    // depend on how the call is split into launches
+    p[i].grid = pp_grid_blocks();
+    // an fp32 plane of 256 x 256 leaves in about 20 K cycles, a K step takes about 2.3 K
+    p[i].eps = 20000.0f / (2340.0f * (float)(kt_total > 0 ? kt_total : 1));
+    p[i].out = plans + i;
+  }
+  (void)total_rows;
+  (void)force_splitk;
+  hipLaunchKernelGGL(gemm_plan_kernel, dim3(1), dim3(64), 0, stream, p[0], p[1]);
+  return hipGetLastError();
 }
 
 hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,

@@ -67,6 +67,21 @@ struct Tune {
   int q_always;          // mat-vecs read quantised copies whatever the experts' size
 };
 
+// Work plan of one grouped launch of the persistent GEMM, computed on the device from the groups'
+// sizes (launch_gemm_plans) and read by every block of the launch.
+// A group of cnt rows is cut into cnt / 256 full row tiles and one remainder tile; an item is one
+// (row tile, column tile, K slice).  Blocks take items from eight queues, one per XCD, each a
+// contiguous range of the item list of about equal estimated cost; a block whose own range is used
+// up goes on with its neighbours'.
+constexpr int kPpTileRows = 256;
+struct GemmPlan {
+  int n_items;
+  int s_full, s_rem;                 // K slices (= fp32 output planes) of a full / a remainder row tile
+  int xcd_begin[9];                  // item range of each XCD's queue
+  int item_begin[kMaxExperts + 1];   // first item of each group
+  int queue[8 * 16];                 // items taken from each range so far (one counter per 64-byte line)
+};
+
 // ---- grouped GEMM on bf16 MFMA --------------------------------------------------------
 struct GemmArgs {
   const uint16_t *A;      // activations, row-major bf16
@@ -89,7 +104,13 @@ struct GemmArgs {
   int K;
   void *out;              // rows indexed by sorted position
   int ldo;
-  int splitk;             // K slices, each written to its own output plane
+  int splitk;             // K slices, each written to its own output plane (the same for every tile)
+  int max_splitk;         // with a plan: output planes there are room for (slices are chosen per tile class)
+  GemmPlan *plan;         // device memory, or NULL.  The K slices of a tile come from it (s_full, s_rem) ...
+  int equal_heights;      // persistent kernel: cut a group into row tiles of equal height instead of full tiles
+                          // and a remainder
+  int plan_queue;         // ... and, if set, the items are taken from its queues (the launch covers every group
+                          // with rows, as the plan does); otherwise they are dealt out in a fixed order
   long long out_split_stride;  // elements between planes
   int spare_cus;          // persistent GEMM: compute units to leave to kernels of other streams
   // Mat-vec kernels only: 8-bit copies of the same weights (e4m3 codes, one fp32 scale per B row).
@@ -113,6 +134,16 @@ enum GemmMode { GEMM_SWIGLU = 0, GEMM_PLAIN_F32 = 1, GEMM_PLAIN_BF16 = 2 };
 hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,
                                hipStream_t stream);
 
+
+// The plans of a prefill layer's two grouped GEMMs (gate/up: a1, down: a2, both with their offsets and
+// every group in the mask): if both can run on the persistent kernel, points a1.plan / a2.plan at
+// plans[0] / plans[1] (device memory) and enqueues the kernel that fills them in from the groups'
+// sizes; otherwise leaves both NULL.  Every GEMM launch of the layer call, grouped or one expert at a
+// time, then takes its K slices from the plan, so the summation order of an output element depends on
+// the layer's routing only, never on which experts happened to be resident.  force_splitk > 0 fixes the
+// K slices of every tile of the down GEMM (tuning hook).
+hipError_t launch_gemm_plans(GemmArgs &a1, GemmArgs &a2, int total_rows, GemmPlan *plans, int force_splitk,
+                             hipStream_t stream);
 
 // The kernel launch_grouped_gemm picks: 1 = 128 x 128 tiles, 6 = 256 x 256 single-phase, 12 = persistent
 // ping-pong, 100 = the register-staged kernel for K that is no multiple of 64.

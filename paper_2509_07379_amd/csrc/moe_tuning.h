@@ -37,6 +37,11 @@ int moe_tune(moe_ctx *ctx, int mode, int variant);
  * Used to check what a layer call or a prefetch that fails midway leaves behind. */
 int moe_inject_failure(int nth_hip_call);
 
+/* Parity hook: the two work plans (gate/up GEMM, down GEMM) the last prefill call on T tokens left in
+ * dev_workspace, as 2 x (3 + 9 + 65 + 128) int32: n_items, s_full, s_rem, xcd_begin[9], item_begin[65],
+ * queue[128] (the queue counters as the launches left them).  Blocks until `stream` has drained. */
+int moe_debug_plans(moe_ctx *ctx, const void *dev_workspace, int T, int32_t *host_out, void *stream);
+
 /* Which GEMM kernel the launcher would pick (1, 6, 12, or 100 for the kernel that pads a ragged K)
  * for GemmMode `mode` on an A of a_rows x lda (gathered through a permutation or used in place),
  * B rows of ldb elements with the second B matrix b1_minus_b0 bytes behind the first, N output
