@@ -183,7 +183,7 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, 
     def copies():
         for e in range(w.E):
             s = e % w.S
-            off = w.S * w.blob_bytes + s * stage if q8 else s * w.blob_bytes
+            off = (s * stage if fmt == 1 else w.S * w.blob_bytes + s * stage) if q8 else s * w.blob_bytes
             raw[off:off + hb].copy_(pool.buf[e], non_blocking=True)
 
     with torch.cuda.stream(copy):

@@ -71,17 +71,14 @@ typedef struct {
  * MOE_FMT_BF16: the blob is the three bf16 matrices, copied straight into a slot.
  * MOE_FMT_E4M3_ROWS: 8-bit weights (the paper serves quantised models, Section VI; the format is this
  *   library's): [scale fp32: 2I rows of W_gate/W_up, then d rows of W_down][W_gate codes I x d]
- *   [W_up codes I x d][W_down codes d x I], codes = OCP e4m3 (1-4-3 bits, bias 7, max 448, 0x7F NaN).
- *   A fetched expert lands in a staging area behind the slots and a kernel expands it into its slot:
- *   weight = bf16 nearest-even of fp32(value(code) * scale[row]).  The kernels run on a stream of the
- *   library's own, each behind the copy it reads, so that the next copy does not wait for them; every
- *   call that fetched makes copy_stream wait for the last of them before it returns, so a
- *   synchronised copy_stream still means "the experts are in their slots".  Slots, matmuls and
- *   results are those of MOE_FMT_BF16 run on the expanded weights; the link carries half the bytes.
- *   The decode mat-vec kernels stream a fetched expert's 8-bit form from its staging area (half the
- *   HBM bytes) and expand it in registers to the same weight values when the experts are large
- *   enough for that to pay (16 M weights per matrix; d and I multiples of 16); otherwise, and for
- *   experts the caller placed with initial_resident, they read the bf16 slot. */
+ *   [W_up codes I x d][W_down codes d x I], codes = OCP e4m3 (1-4-3 bits, bias 7, max 448, 0x7F NaN);
+ *   d and I multiples of 64.  A weight is bf16 nearest-even of fp32(value(code) * scale[row]).  The GPU
+ *   expert cache holds an expert in this form and in no other: a slot is moe_host_blob_bytes rounded up
+ *   to 256 bytes, a fetch is one copy (half the bytes of bf16 on the link and in HBM), and every kernel
+ *   reads the codes as they landed.  The prefill GEMMs expand each tile of codes to those bf16 weights
+ *   on its way into LDS, the decode mat-vecs in registers; the results are those of MOE_FMT_BF16 run on
+ *   the expanded weights.  initial_resident names experts whose 8-bit blob the caller has put into the
+ *   slot. */
 #define MOE_FMT_BF16 0
 #define MOE_FMT_E4M3_ROWS 1
 /* MOE_FMT_INT4_G128: 4-bit weights, the storage form of AWQ / GPTQ-style quantisation: unsigned 4-bit
@@ -89,18 +86,23 @@ typedef struct {
  *   scale and one zero point (a byte, 0..15) per group; d and I multiples of 128.  Blob:
  *   [scales of [W_gate; W_up] (2I x d/128 fp32)][scales of W_down (d x I/128 fp32)][zero points, same
  *   order (bytes)][padding to a multiple of 16][codes of [W_gate; W_up] (2I x d/2)][codes of W_down
- *   (d x I/2)].  Fetched and expanded like MOE_FMT_E4M3_ROWS:
- *   weight = bf16 nearest-even of fp32((code - zero) * scale).  The mat-vec kernels read the bf16 slots. */
+ *   (d x I/2)].  weight = bf16 nearest-even of fp32((code - zero) * scale).  A fetched expert lands in
+ *   a staging area behind the bf16 slots and a kernel expands it into its slot.  The kernels run on a
+ *   stream of the library's own, each behind the copy it reads, so that the next copy does not wait for
+ *   them; every call that fetched makes copy_stream wait for the last of them before it returns, so a
+ *   synchronised copy_stream still means "the experts are in their slots".  Slots, matmuls and results
+ *   are those of MOE_FMT_BF16 run on the expanded weights; the link carries a quarter of the bytes. */
 #define MOE_FMT_INT4_G128 2
 /* MOE_FMT_MXFP4: the OCP microscaling 4-bit format: e2m1 codes (bit 3 sign, bits 2..1 exponent, bit 0
  *   mantissa: 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte (even column in the low nibble); 32 consecutive
  *   values of a row share the scale 2^(s - 127), s one byte in 1..254; d and I multiples of 32.  Blob:
  *   [scale bytes of [W_gate; W_up] (2I x d/32)][scale bytes of W_down (d x I/32)][padding to a multiple
  *   of 16][codes of [W_gate; W_up] (2I x d/2)][codes of W_down (d x I/2)].  weight = value(code) *
- *   2^(s - 127), exact in bf16.  Fetched and expanded like the others; the decode mat-vec kernels
+ *   2^(s - 127), exact in bf16.  Fetched and expanded like MOE_FMT_INT4_G128; the decode mat-vec kernels
  *   stream a fetched expert's 4-bit form from its staging area (a quarter of the HBM bytes) and expand
- *   it in registers with the hardware's scaled fp4 conversion, under the same conditions as for
- *   MOE_FMT_E4M3_ROWS. */
+ *   it in registers with the hardware's scaled fp4 conversion when the experts are large enough for
+ *   that to pay (16 M weights per matrix); otherwise, and for experts the caller placed with
+ *   initial_resident, they read the bf16 slot. */
 #define MOE_FMT_MXFP4 3
 
 /* Cache counters (host side).  hits/misses count active experts per layer call.
@@ -135,8 +137,9 @@ int moe_destroy(moe_ctx *ctx);
  * 15*d*I/128 rounded up to 16, plus 3*d*I/2 (int4 groups), or 3*d*I/32 rounded up to 16, plus
  * 3*d*I/2 (MXFP4). */
 size_t moe_host_blob_bytes(const moe_config *cfg);
-/* Bytes of one GPU expert cache (dev_slots of moe_bind_layer): cache_slots slots of 6*d*I bytes,
- * followed, for an 8-bit host format, by one staging area per slot. */
+/* Bytes of one GPU expert cache (dev_slots of moe_bind_layer).  MOE_FMT_BF16: cache_slots slots of 6*d*I
+ * bytes.  MOE_FMT_E4M3_ROWS: cache_slots slots of moe_host_blob_bytes rounded up to 256.  The 4-bit
+ * formats: cache_slots bf16 slots followed by one staging area (the blob, rounded up to 256) per slot. */
 size_t moe_cache_bytes(const moe_config *cfg);
 
 /* Bytes of device workspace a layer call on T tokens needs (256-byte aligned base). */
@@ -149,10 +152,11 @@ size_t moe_workspace_bytes(const moe_config *cfg, int T);
  *                       blob per expert (= one DMA per expert).
  *  dev_router_w         [E, d] bf16 gate weight.
  *  dev_shared_blob      NULL, or 6*d*I_shared bytes in the same layout (always resident).
- *  dev_slots            moe_cache_bytes: the layer's GPU expert cache, slot s at s * 6*d*I (with
+ *  dev_slots            moe_cache_bytes: the layer's GPU expert cache, slot s at s times the slot size (with
  *                       shared_slots: the one cache, the same pointer for every layer).
  *  initial_resident     NULL (all slots empty) or [S] expert ids / -1: slot s already holds
- *                       that expert's bf16 blob (the caller put it there).
+ *                       that expert's blob (the caller put it there): the bf16 matrices, or for
+ *                       MOE_FMT_E4M3_ROWS the 8-bit blob.
  * The pointers are read, not copied.
  */
 int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,

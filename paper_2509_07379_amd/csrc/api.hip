@@ -178,7 +178,8 @@ constexpr int kMailboxWords = kMaxExperts + 1;
 struct moe_ctx {
   moe_config cfg{};
   int device = 0;
-  size_t blob_bytes = 0;        // one slot: the bf16 blob, 6*d*I
+  size_t blob_bytes = 0;        // one slot: the bf16 blob, 6*d*I; 0 where the cache keeps experts in their 8-bit form only
+  bool direct_q = false;        // MOE_FMT_E4M3_ROWS: every kernel reads the 8-bit blob as fetched; no bf16 slot, no expansion
   size_t host_blob_bytes = 0;   // one expert in the CPU expert cache (bf16: the same; e4m3: scales + codes)
   size_t stage_stride = 0;      // e4m3: bytes of one slot's staging area behind the slots (256-aligned)
   std::vector<Layer> layers;
@@ -230,6 +231,8 @@ int check_cfg(const moe_config *c) {
     return fail(MOE_E_UNSUPPORTED, "d, I and I_shared must be multiples of 8");
   if (c->host_format < MOE_FMT_BF16 || c->host_format > MOE_FMT_MXFP4)
     return fail(MOE_E_ARG, "host_format = %d is not a known format", c->host_format);
+  if (c->host_format == MOE_FMT_E4M3_ROWS && (c->d % 64 || c->I % 64))
+    return fail(MOE_E_UNSUPPORTED, "MOE_FMT_E4M3_ROWS needs d and I to be multiples of 64");
   if (c->host_format == MOE_FMT_MXFP4 && (c->d % 32 || c->I % 32))
     return fail(MOE_E_UNSUPPORTED, "MOE_FMT_MXFP4 needs d and I to be multiples of 32");
   if (c->host_format == MOE_FMT_INT4_G128 && (c->d % 128 || c->I % 128))
@@ -432,9 +435,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + meta_bytes);
     auto expand = [&](bool down) -> int {
       if (c.host_format == MOE_FMT_E4M3_ROWS) {
-        const float *scales = reinterpret_cast<const float *>(stage);
-        if (!down) HIP_TRY(launch_dequant_e4m3_rows(codes, scales, 2 * c.I, c.d, w, xs));
-        else HIP_TRY(launch_dequant_e4m3_rows(codes + up_codes, scales + 2 * c.I, c.d, c.I, w + 2 * Id, xs));
+        return MOE_OK;   // (read as fetched; handled below)
       } else if (c.host_format == MOE_FMT_MXFP4) {
         const uint8_t *scales = reinterpret_cast<const uint8_t *>(stage);
         if (!down) HIP_TRY(launch_dequant_mxfp4(codes, scales, 2 * c.I, c.d, w, xs));
@@ -448,6 +449,23 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
       }
       return MOE_OK;
     };
+    if (ctx->direct_q) {
+      // The cache holds the 8-bit blob and nothing else: one copy (or two, split behind the gate / up
+      // codes), and "landed" is "ready" for every kernel.
+      (void)codes;
+      (void)w;
+      if (split) {
+        HIP_TRY(hipMemcpyAsync(stage, src, meta_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
+        HIP_TRY(hipEventRecord(set.landed_up[s], copy_stream));
+        HIP_TRY(hipEventRecord(set.copied_up[s], copy_stream));
+        HIP_TRY(hipMemcpyAsync(stage + meta_bytes + up_codes, src + meta_bytes + up_codes,
+                               ctx->host_blob_bytes - meta_bytes - up_codes, hipMemcpyHostToDevice, copy_stream));
+      } else {
+        HIP_TRY(hipMemcpyAsync(stage, src, ctx->host_blob_bytes, hipMemcpyHostToDevice, copy_stream));
+      }
+      HIP_TRY(hipEventRecord(set.landed[s], copy_stream));
+      HIP_TRY(hipEventRecord(set.copied[s], copy_stream));
+    } else {
     // the staging area's last expansion must be over before new bytes land in it
     if (set.staged[s]) HIP_TRY(hipStreamWaitEvent(copy_stream, set.copied[s], 0));
     set.staged[s] = 1;
@@ -472,6 +490,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     if ((rc = expand(true))) return rc;
     HIP_TRY(hipEventRecord(set.copied[s], xs));
     ctx->expand_tail = set.copied[s];
+    }
   } else if (split) {
     const size_t up_bytes = ctx->blob_bytes / 3 * 2;   // [W_gate; W_up], then W_down
     HIP_TRY(hipMemcpyAsync(dst, src, up_bytes, hipMemcpyHostToDevice, copy_stream));
@@ -535,7 +554,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   for (int e = 0; e < c.E; ++e) a.slot[e] = (int16_t)(L.expert_slot[e] < 0 ? 0 : L.expert_slot[e]);
   a.splitk = 1;
   a.tune = ctx->tune;
-  if (c.host_format == MOE_FMT_E4M3_ROWS && c.d % 16 == 0 && c.I % 16 == 0 && !ctx->api_tune.no_q_matvec) {
+  if (c.host_format == MOE_FMT_E4M3_ROWS) {
     // the mat-vec kernels stream the 8-bit copy that a fetch left in the slot's staging area (half
     // the bytes; the same weight values as the expanded slot)
     const long long scale_bytes = (long long)4 * (2 * c.I + c.d), Id = (long long)c.I * c.d;
@@ -546,6 +565,8 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
     a.q_b1_off = scale_bytes + (second ? 2 * Id : Id);
     a.q_s0_off = second ? (long long)4 * 2 * c.I : 0;
     a.q_s1_off = second ? (long long)4 * 2 * c.I : (long long)4 * c.I;
+    a.b_quant = 1;        // the GEMM kernels expand the codes on their way into LDS
+    a.tune.q_always = 1;  // and the mat-vecs read them whatever the experts' size: there is no bf16 slot
   } else if (c.host_format == MOE_FMT_MXFP4 && !ctx->api_tune.no_q_matvec) {
     // likewise the MXFP4 copy (a quarter of the bytes): codes K/2 bytes per row, scales K/32
     const long long Id = (long long)c.I * c.d, meta = (3 * Id / 32 + 15) / 16 * 16;
@@ -1012,7 +1033,8 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   moe_ctx *ctx = new (std::nothrow) moe_ctx();
   if (!ctx) return fail(MOE_E_ARG, "out of host memory");
   ctx->cfg = *cfg;
-  ctx->blob_bytes = (size_t)6 * cfg->d * cfg->I;
+  ctx->direct_q = cfg->host_format == MOE_FMT_E4M3_ROWS;
+  ctx->blob_bytes = ctx->direct_q ? 0 : (size_t)6 * cfg->d * cfg->I;
   ctx->host_blob_bytes = moe_host_blob_bytes(cfg);
   ctx->stage_stride = cfg->host_format != MOE_FMT_BF16 ? (ctx->host_blob_bytes + 255) / 256 * 256 : 0;
   rc = create_parts(ctx, cfg);
@@ -1073,7 +1095,7 @@ size_t moe_host_blob_bytes(const moe_config *cfg) {
 
 size_t moe_cache_bytes(const moe_config *cfg) {
   if (check_cfg(cfg)) return 0;
-  const size_t slot = (size_t)6 * cfg->d * cfg->I;
+  const size_t slot = cfg->host_format == MOE_FMT_E4M3_ROWS ? 0 : (size_t)6 * cfg->d * cfg->I;
   const size_t stage = cfg->host_format != MOE_FMT_BF16 ? (moe_host_blob_bytes(cfg) + 255) / 256 * 256 : 0;
   return (size_t)cfg->cache_slots * (slot + stage);
 }
@@ -1175,7 +1197,7 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
         if (set.slot_expert[s] >= 0) ctx->layers[set.slot_layer[s]].expert_slot[set.slot_expert[s]] = -1;
         set.slot_expert[s] = initial_resident[s];
         set.slot_layer[s] = layer;
-        set.q_valid[s] = 0;   // the caller put the bf16 blob there; no 8-bit copy
+        set.q_valid[s] = ctx->direct_q ? 1 : 0;   // what the caller put there: the blob as the slots hold it
         L.expert_slot[initial_resident[s]] = s;
       }
   L.bound = true;

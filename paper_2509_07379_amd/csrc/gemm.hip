@@ -504,6 +504,188 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_dma_kerne
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same tile loop on 8-bit experts (MOE_FMT_E4M3_ROWS): the B operand is e4m3 codes with one fp32
+// scale per B row, read from the expert's blob as it came over the host link.  A tile of codes is
+// 64 bytes per row and K step; every lane fetches 16-byte pieces of it into registers one K step
+// ahead, expands them to the bf16 weights bf16_rne(value(code) * scale[row]) (the hardware's e4m3 ->
+// fp32 conversion, one multiply, the hardware's fp32 -> bf16 rounding: the value the format defines,
+// so the products are those of a GEMM on expanded weights) and writes them into the swizzled LDS tile
+// the MFMAs read.  A keeps its direct global -> LDS loads.  The expansion costs some 70 vector
+// instructions per lane and K step, issued while the other waves' MFMAs run.  Needs K % 64 == 0.
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x4 expand8_e4m3(uint32_t c0, uint32_t c1, float scale) {
+  f32x2v a = __builtin_amdgcn_cvt_pk_f32_fp8((int)c0, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)c0, true);
+  f32x2v c = __builtin_amdgcn_cvt_pk_f32_fp8((int)c1, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)c1, true);
+  a *= scale; b *= scale; c *= scale; d *= scale;
+  return u32x4{__builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2v)),
+               __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2v)),
+               __builtin_bit_cast(uint32_t, __builtin_convertvector(c, bf16x2v)),
+               __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2v))};
+}
+
+template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel(const GemmArgs args) {
+  constexpr int NW = WARPS_M * WARPS_N;
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr int FM = BM / (32 * WARPS_M);
+  constexpr int FN = BN / (32 * WARPS_N);
+  constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
+  constexpr int STAGE = (BM + BN) * ROW_BYTES;
+  constexpr int GPA = BM / 8 / NW;    // wave-wide A loads per wave and stage (8 tile rows each)
+  constexpr int NQ = BN / 16 / NW;    // 16-byte pieces of codes per lane and stage (a wave-wide load = 16 B rows)
+  static_assert(BM % (8 * NW) == 0 && BN % (16 * NW) == 0, "load split mismatch");
+  static_assert(FM <= 4, "fragment-count dispatch covers up to 4 row fragments per wave");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WARPS_M, wn = wave / WARPS_M;
+
+  TileInfo t;
+  if (!decode_tile<BM, BN_OUT>(args, t)) return;
+
+  const char *qptr = args.qbase + (long long)args.slot[t.grp] * args.qstride;
+  const int kt_total = args.K / BK;
+  const int kt_begin = (int)((long long)kt_total * t.ks / args.splitk);
+  const int kt_end = (int)((long long)kt_total * (t.ks + 1) / args.splitk);
+
+  // A: load g fills tile rows 8g..8g+7; lane l lands at row 8g + l/8, chunk position l%8
+  const uint16_t *a_src[GPA];
+#pragma unroll
+  for (int i = 0; i < GPA; ++i) {
+    const int g = i * NW + wave;
+    const int row = g * 8 + (lane >> 3);
+    const int kc = (lane & 7) ^ ((row >> 1) & 7);
+    const int rr = row < t.rows_valid ? row : 0;
+    const int p = t.row0 + t.tile_row0 + rr;
+    const long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
+    a_src[i] = args.A + srow * args.lda + kc * 8;
+  }
+  // B: piece i of this lane is 16 codes of tile row 16 (i NW + wave) + l/4, columns 16 (l%4) .. +15 of the
+  // K step; expanded they are the row's bf16 chunks 2 (l%4) and 2 (l%4) + 1
+  const uint8_t *q_src[NQ];
+  float q_scale[NQ];
+  int q_dst[NQ][2];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int r = (i * NW + wave) * 16 + (lane >> 2);
+    const int c4 = lane & 3;
+    long long codes_off = args.q_b0_off, scale_off = args.q_s0_off;
+    int rr = r;
+    if (MODE == GEMM_SWIGLU && r >= BN / 2) { codes_off = args.q_b1_off; scale_off = args.q_s1_off; rr = r - BN / 2; }
+    int n = t.n0 + rr;
+    if (n >= args.N) n = args.N - 1;
+    q_src[i] = reinterpret_cast<const uint8_t *>(qptr + codes_off) + (long long)n * args.K + c4 * 16;
+    q_scale[i] = reinterpret_cast<const float *>(qptr + scale_off)[n];
+    q_dst[i][0] = BM * ROW_BYTES + swz(r, 2 * c4);
+    q_dst[i][1] = BM * ROW_BYTES + swz(r, 2 * c4 + 1);
+  }
+
+  int fm_valid = 0;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) fm_valid += ((i * WARPS_M + wm) * 32 < t.rows_valid) ? 1 : 0;
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  int a_off[FM], b_off[FN];
+  const int lrow = lane & 31, lk = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a_off[i] = (i * WARPS_M + wm) * 32 + lrow;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    if (MODE == GEMM_SWIGLU)
+      b_off[j] = (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow;  // gate half | up half
+    else
+      b_off[j] = (j * WARPS_N + wn) * 32 + lrow;
+  }
+
+  u32x4 cq[NQ];   // codes of the K step after the one in LDS
+#define MOE_Q_LOADA(kt_, stage_)                                                                     \
+  do {                                                                                               \
+    _Pragma("unroll") for (int i_ = 0; i_ < GPA; ++i_)                                               \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_src[i_] + (long long)(kt_) * BK),               \
+                                       (lds_ptr_t)(smem + (stage_) * STAGE + (i_ * NW + wave) * 1024), \
+                                       16, 0, 0);                                                    \
+  } while (0)
+#define MOE_Q_LOADQ(kt_)                                                                             \
+  do {                                                                                               \
+    _Pragma("unroll") for (int i_ = 0; i_ < NQ; ++i_)                                                \
+      cq[i_] = *reinterpret_cast<const u32x4 *>(q_src[i_] + (long long)(kt_) * BK);                  \
+  } while (0)
+#define MOE_Q_EXPAND(stage_)                                                                         \
+  do {                                                                                               \
+    _Pragma("unroll") for (int i_ = 0; i_ < NQ; ++i_) {                                              \
+      const u32x4 c_ = cq[i_];                                                                       \
+      *reinterpret_cast<u32x4 *>(smem + (stage_) * STAGE + q_dst[i_][0]) = expand8_e4m3(c_.x, c_.y, q_scale[i_]); \
+      *reinterpret_cast<u32x4 *>(smem + (stage_) * STAGE + q_dst[i_][1]) = expand8_e4m3(c_.z, c_.w, q_scale[i_]); \
+    }                                                                                                \
+  } while (0)
+#define MOE_Q_MMA(FMV, stage_)                                                                       \
+  do {                                                                                               \
+    const unsigned char *sa_ = smem + (stage_) * STAGE;                                              \
+    const unsigned char *sb_ = sa_ + BM * ROW_BYTES;                                                 \
+    _Pragma("unroll") for (int kk_ = 0; kk_ < BK / 16; ++kk_) {                                      \
+      const int kc_ = kk_ * 2 + lk;                                                                  \
+      bf16x8 af_[FMV > 0 ? FMV : 1], bf_[FN];                                                        \
+      _Pragma("unroll") for (int i_ = 0; i_ < FMV; ++i_)                                             \
+        af_[i_] = *reinterpret_cast<const bf16x8 *>(sa_ + swz(a_off[i_], kc_));                      \
+      _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                              \
+        bf_[j_] = *reinterpret_cast<const bf16x8 *>(sb_ + swz(b_off[j_], kc_));                      \
+      _Pragma("unroll") for (int i_ = 0; i_ < FMV; ++i_)                                             \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
+          acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i_], bf_[j_], acc[i_][j_], 0, 0, 0); \
+    }                                                                                                \
+  } while (0)
+// One K step: the A tile and the codes requested in the step before have arrived; after the barrier
+// nobody reads the other stage any more, so the next step's A loads go out, the codes in registers
+// become its B tile and the codes of the step after that are requested; then this step's MFMAs.
+// (The last step requests and expands itself again: harmless, and the loop body stays branch-free.)
+#define MOE_Q_LOOP(FMV)                                                                              \
+  do {                                                                                               \
+    for (int kt = kt_begin; kt < kt_end; ++kt) {                                                     \
+      const int stage_ = (kt - kt_begin) & 1;                                                        \
+      const int kn_ = kt + 1 < kt_end ? kt + 1 : kt;                                                 \
+      const int kn2_ = kt + 2 < kt_end ? kt + 2 : kn_;                                               \
+      __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's A loads of step kt have landed */ \
+      __syncthreads();   /* ... and everybody's, with the B tile written in the step before */       \
+      MOE_Q_LOADA(kn_, stage_ ^ 1);                                                                  \
+      MOE_Q_EXPAND(stage_ ^ 1);                                                                      \
+      MOE_Q_LOADQ(kn2_);                                                                             \
+      MOE_Q_MMA(FMV, stage_);                                                                        \
+    }                                                                                                \
+  } while (0)
+
+  if (kt_begin < kt_end) {
+    MOE_Q_LOADA(kt_begin, 0);
+    MOE_Q_LOADQ(kt_begin);
+    MOE_Q_EXPAND(0);   // (waits for the codes)
+    MOE_Q_LOADQ(kt_begin + 1 < kt_end ? kt_begin + 1 : kt_begin);
+  }
+  switch (fm_valid) {
+    case 0: MOE_Q_LOOP(0); break;
+    case 1: MOE_Q_LOOP(1); break;
+    case 2: if constexpr (FM >= 2) MOE_Q_LOOP(2); break;
+    case 3: if constexpr (FM >= 3) MOE_Q_LOOP(3); break;
+    default: if constexpr (FM >= 4) MOE_Q_LOOP(4); break;
+  }
+#undef MOE_Q_LOOP
+#undef MOE_Q_MMA
+#undef MOE_Q_EXPAND
+#undef MOE_Q_LOADQ
+#undef MOE_Q_LOADA
+  (void)STAGE;
+  store_tile<MODE, FM, FN, WARPS_M, WARPS_N>(args, t, wm, wn, lane, fm_valid, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Short row tiles of the persistent kernel: at most 64 rows, i.e. a small group or what a group leaves
 // over after its full tiles.  Such a tile has almost no MFMA work; its time is the 256-row weight tile's
 // way from memory through LDS, and as the only (or first) reader of those weights it waits for HBM,
@@ -1157,6 +1339,29 @@ hipError_t launch_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, 
   return hipGetLastError();
 }
 
+template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
+hipError_t launch_q8_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
+  constexpr int NTHR = 64 * WARPS_M * WARPS_N;
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES;
+  auto kern = grouped_gemm_q8_kernel<BM, BN, WARPS_M, WARPS_N, MODE>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const long long n_tiles_n = (args.N + BN_OUT - 1) / BN_OUT;
+  const long long m_tiles_ub = (long long)max_rows / BM + n_groups_in_mask;
+  long long ub = m_tiles_ub * n_tiles_n * args.splitk;
+  if (ub <= 0) return hipSuccess;
+  ub = (ub + 7) / 8 * 8;
+  if (ub > 0x7FFFFFFFll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)ub), dim3(NTHR), smem, stream, args);
+  return hipGetLastError();
+}
+
 static int pp_grid_blocks() {
   static int blocks = 0;
   if (!blocks) {
@@ -1342,6 +1547,15 @@ int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_
 
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
+  if (args.b_quant) {
+    // 8-bit experts: the kernel that expands the codes on their way into LDS, with the tile size by the
+    // groups' average height
+    if (MODE == GEMM_PLAIN_BF16 || args.qfmt != 1 || !args.qbase || args.K % BK != 0) return hipErrorInvalidValue;
+    const long long avg_rows = n_groups_in_mask > 0 ? (long long)max_rows / n_groups_in_mask : max_rows;
+    if (avg_rows > 96 && args.tune.gemm_variant[MODE] != 1)
+      return launch_q8_cfg<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
+    return launch_q8_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+  }
   switch (gemm_kernel_choice((GemmMode)MODE, args, max_rows, n_groups_in_mask)) {
     case 100: return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);
     case 6: return launch_cfg<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);

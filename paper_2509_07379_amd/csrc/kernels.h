@@ -121,6 +121,7 @@ struct GemmArgs {
   // byte per 32 columns, K / 32 bytes per row at q_s*_off; weight = value(code) * 2^(scale - 127), exact
   // in bf16).  K % 32 == 0.
   int qfmt;               // 0 none, 1 e4m3 with row scales, 2 MXFP4
+  int b_quant;            // GEMM kernels: every expert's B operand is its e4m3 copy at qbase (there is no bf16 blob)
   unsigned long long q8_mask;
   const char *qbase;
   long long qstride;

@@ -230,7 +230,7 @@ def test_one_token_decode_enqueued_from_the_gates_id_list(gpu, oracle, E, k, Ish
                                              for d, I, E, k, Ish in ((512, 256, 8, 2, 0), (4096, 64, 64, 6, 0),
                                                                      (264, 136, 5, 5, 0), (512, 256, 60, 4, 384),
                                                                      (256, 64, 8, 2, 2048))
-                                             if f == 0 or (d % 32 == 0 and I % 32 == 0)])
+                                             if f == 0 or (d % 64 == 0 and I % 64 == 0)])
 def test_one_token_down_projection_and_weighted_sum_in_one_launch(gpu, oracle, fmt, d, I, E, k, Ish):
     """One token: the down mat-vec walks over the token's k experts, applies the gate values itself and
     adds the shared experts' rows.  The same bits as the two-launch path (same row sums, same order of
@@ -377,24 +377,56 @@ def test_shared_cache_prefill_streams_every_layer_through_two_slots(gpu, oracle)
 
 
 # ---------------------------------------------------------------- 8-bit experts on the host link
-def test_q8_fetch_expands_into_slots_bit_exact(gpu, oracle):
-    """Experts stored as e4m3 codes with per-row scales: every fetched expert's slot holds, bit for
-    bit, the oracle's expansion; the layer's output is the oracle's on those weights; the link
-    carried the 8-bit blobs only."""
-    w = S.Workload("q8_slots", d=264, I=136, E=6, k=2, T=300, I_shared=64, seed=51)
+def test_q8_cache_holds_the_8bit_blobs_and_prefill_reads_them(gpu, oracle):
+    """Experts stored as e4m3 codes with per-row scales: the GPU expert cache is the 8-bit blobs and nothing
+    else (half the bytes of bf16 slots), every fetched expert's slot holds exactly the bytes of the CPU
+    expert cache, and the prefill GEMMs, which expand the codes on their way into LDS, give the oracle's
+    output on the oracle's expansion.  The rest of the cache is a NaN pattern throughout."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("q8_slots", d=256, I=192, E=6, k=2, T=300, I_shared=64, seed=51)
     x = S.activations(w)
     r = run_layer(gpu, w, w.T, x, w.E, None, poison=True, q8=True)
     ref = oracle_layer(oracle, w, x, r["lay"].router_np, r["pool"], shared=r["lay"].shared_np)
     np.testing.assert_array_equal(r["routing"]["perm"], ref["perm"])
     check_out(r["out"], ref["out_f64"], "q8 prefill")
-    slots = r["lay"].slots.cpu().numpy().view(np.uint16)
+    nbytes = S.q8_blob_bytes(w.d, w.I)
+    assert r["lay"].cache.numel() * 2 == w.E * ((nbytes + 255) // 256 * 256) < w.E * w.blob_bytes * 0.51
+    slots = r["lay"].slots.cpu().numpy().view(np.uint8)
     active = [e for e in range(w.E) if ref["counts"][e] > 0]
     assert len(active) >= 4
     for e in active:
         s = r["state"].index(e)
-        np.testing.assert_array_equal(slots[s], oracle.dequant_blob(r["pool"].blob_np(e), w.d, w.I), err_msg=f"expert {e}")
-    assert r["stats"]["bytes_h2d"] == len(active) * S.q8_blob_bytes(w.d, w.I)
+        np.testing.assert_array_equal(slots[s][:nbytes], r["pool"].blob_np(e), err_msg=f"expert {e}")
+    for s, e in enumerate(r["state"]):
+        if e < 0:
+            assert np.all(slots[s].view(np.uint16) == 0x7FC0)      # never written
+    assert r["stats"]["bytes_h2d"] == len(active) * nbytes
     assert r["stats"]["misses"] == len(active)
+
+
+@pytest.mark.parametrize("d,I,E,k,T,Ish,variant", [(256, 128, 8, 2, 1200, 0, 0), (512, 192, 5, 3, 700, 128, 0),
+                                                   (256, 320, 16, 4, 2500, 0, 0), (256, 128, 8, 2, 1200, 0, 1),
+                                                   (1024, 64, 64, 6, 900, 64, 0), (128, 4096, 3, 1, 150, 0, 0)])
+def test_q8_prefill_gemm_on_codes(gpu, oracle, d, I, E, k, T, Ish, variant):
+    """The GEMM kernels that read e4m3 experts: 256 x 256 and 128 x 128 tiles (by the groups' height, or
+    forced), several K slices of the down projection, ragged groups, resident experts placed by the
+    caller (initial_resident names 8-bit blobs) and experts streaming through three slots: the same bits
+    either way, and the oracle's output on its own expansion of the codes."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("q8_gemm", d=d, I=I, E=E, k=k, T=T, I_shared=Ish, seed=77, zipf_s=0.9)
+    x = S.activations(w)
+    bias = S.zipf_route_bias(w, 0)
+    pool = H.HostPool(w, 0, fmt=1)
+    if variant:
+        set_tune(0, 1)
+        set_tune(1, 1)
+    res = run_layer(gpu, w, T, x, E, list(range(E)), bias=bias, pool=pool, fmt=1)
+    ref = oracle_layer(oracle, w, x, res["lay"].router_np, pool, bias=bias, shared=res["lay"].shared_np)
+    np.testing.assert_array_equal(res["routing"]["perm"], ref["perm"])
+    check_out(res["out"], ref["out_f64"], "resident 8-bit experts")
+    assert res["stats"]["misses"] == 0 and res["stats"]["bytes_h2d"] == 0
+    streamed = run_layer(gpu, w, T, x, 3, None, bias=bias, pool=pool, fmt=1, prefetch=[1, 0], poison=True)
+    np.testing.assert_array_equal(streamed["out"], res["out"])
 
 
 def test_q4_fetch_expands_into_slots_bit_exact(gpu, oracle):
@@ -449,15 +481,12 @@ def test_q8_streaming_through_two_slots(gpu, oracle, T, decode):
 
 
 @pytest.mark.parametrize("d,I,I_shared,T", [(256, 192, 64, 1), (256, 192, 64, 2), (256, 192, 0, 5), (256, 192, 64, 8),
-                                            (256, 192, 64, 11), (2048, 96, 0, 1), (2048, 96, 32, 3), (4096, 64, 0, 8),
-                                            (264, 136, 0, 2)])
-def test_q8_decode_streams_the_8bit_copies(gpu, oracle, d, I, I_shared, T):
-    """Decode on experts the library fetched in 8-bit form: the mat-vec kernels read the codes and
-    scales from the staging areas and expand them in registers to the same bf16 weights the slots hold
+                                            (256, 192, 64, 11), (2048, 128, 0, 1), (2048, 128, 32, 3), (4096, 64, 0, 8)])
+def test_q8_decode_streams_the_8bit_blobs(gpu, oracle, d, I, I_shared, T):
+    """Decode on experts held in 8-bit form (there is no other form in the cache): the mat-vec kernels
+    read the codes and scales and expand them in registers to the bf16 weights the format defines
     (hardware e4m3 conversion, one fp32 multiply, nearest-even bf16), so the output is the oracle's on
-    the expanded weights.  To show where the weights came from, the bf16 slots are overwritten with
-    NaN patterns after the fetch.  Shared experts (bf16) ride in the same launches.  d = 264 is not a
-    multiple of 16: there the kernels must take the bf16 slots (left intact), also when forced."""
+    its own expansion.  Shared experts (bf16) ride in the same launches."""
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("q8_decode", d=d, I=I, E=6, k=2, T=T, I_shared=I_shared, seed=54 + T)
     x = S.activations(w)
@@ -466,17 +495,8 @@ def test_q8_decode_streams_the_8bit_copies(gpu, oracle, d, I, I_shared, T):
     lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
     buf = H.Buffers(ctx, T)
     ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
-    torch.cuda.synchronize()
-    from_copies = d % 16 == 0
-    if from_copies:
-        lay.slots.fill_(0x7FC0)
-        torch.cuda.synchronize()
-    try:
-        ctx.moe_tune(6, 2)     # these experts are small: force the 8-bit source
-        ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
-        gpu["compute"].synchronize()
-    finally:
-        ctx.moe_tune(6, 0)
+    ctx.moe_decode_layer(0, H.np_to_dev(x), T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+    gpu["compute"].synchronize()
     ref = oracle_layer(oracle, w, x, lay.router_np, pool, shared=lay.shared_np)
     np.testing.assert_array_equal(buf.routing(ctx, gpu["compute"])["ids"], ref["ids"])
     check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"q8 decode T={T}")
@@ -567,7 +587,8 @@ def test_decode_batches_through_the_matrix_core_matvec(gpu, oracle, fmt, d, I, I
     if fmt:
         ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
         torch.cuda.synchronize()
-        lay.slots.fill_(0x7FC0)
+        if fmt != 1:                     # (an e4m3 pool has no bf16 slots: the slots are the codes)
+            lay.slots.fill_(0x7FC0)
         torch.cuda.synchronize()
     ref = oracle_layer(oracle, w, x, lay.router_np, pool, bias=bias, shared=lay.shared_np)
     assert T < 6 or (ref["counts"].max() >= 3 and (T < 20 or ref["counts"].max() > 16))
@@ -594,7 +615,7 @@ def test_prefill_seeded_random_shapes(gpu, oracle):
     rng = np.random.default_rng(5151)
     for it in range(30):
         fmt = int(rng.choice([0, 0, 1, 2, 3]))
-        unit = {0: 8, 1: 16, 2: 128, 3: 32}[fmt]
+        unit = {0: 8, 1: 64, 2: 128, 3: 32}[fmt]
         d = int(rng.integers(1, 5)) * unit * int(rng.choice([1, 3, 8]))
         I = int(rng.integers(1, 5)) * unit * int(rng.choice([1, 2]))
         I_shared = int(rng.choice([0, 0, 64, 136]))
@@ -648,7 +669,8 @@ def test_decode_seeded_random_shapes(gpu, oracle):
         if fmt:
             ctx.expert_cache_prefetch(0, list(range(E)), gpu["copy"])
             torch.cuda.synchronize()
-            lay.slots.fill_(0x7FC0)
+            if fmt != 1:                     # (an e4m3 pool has no bf16 slots: the slots are the codes)
+                lay.slots.fill_(0x7FC0)
             torch.cuda.synchronize()
         ctx.moe_tune(6, 2 if fmt else 0)
         ctx.moe_tune(8, 1 if forced else 0)
