@@ -714,6 +714,9 @@ def main():
     ap.add_argument("--no-c4", action="store_true", help="skip the DeepSeek-shaped prefill leg")
     ap.add_argument("--no-c5", action="store_true", help="skip the Qwen-shaped batch-8 decode leg")
     ap.add_argument("--no-batch-sweep", action="store_true", help="skip the batch 1-12 decode table")
+    ap.add_argument("--only", choices=["c4", "c5"], default=None,
+                    help="run just the DeepSeek-shaped prefill leg or the Qwen-shaped decode leg and print it "
+                         "(for profiler runs: rocprofv3 --kernel-trace / --pmc around a short command)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -730,6 +733,11 @@ def main():
     # one compute, one copy and one prediction stream for the whole run: HIP multiplexes streams
     # onto 4 hardware queues, and two streams that land on the same queue serialise
     compute, copy, pred = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    if args.only:
+        leg = (prefill_c4(args, torch, B, H, S, compute, copy) if args.only == "c4"
+               else decode_c5(args, torch, B, H, S, compute, copy, pred))
+        print(json.dumps({"leg": args.only, **leg}), flush=True)
+        return
     res = prefill_resident(args, torch, B, H, S, w, compute, copy)
     if args.calibration_copy:
         # a copy kernel of known size: FETCH_SIZE / WRITE_SIZE of the GEMM launches are scaled by what the

@@ -81,7 +81,7 @@ int choose_splitk(const moe_config &cfg, int T) {
 }
 
 struct WsLayout {
-  size_t logits, ids, w, counts, offsets, blk_hist, blk_base, perm, inv_perm, plans, H, Hs, Y, Ys, total;
+  size_t logits, ids, w, counts, offsets, active, blk_hist, blk_base, perm, inv_perm, plans, H, Hs, Y, Ys, total;
   int planes;   // fp32 planes of Y there is room for
   int splitk, nblk;
 };
@@ -105,6 +105,7 @@ WsLayout ws_layout(const moe_config &c, int T, int forced_splitk = 0) {
   L.w = take(n * 4);
   L.counts = take((size_t)c.E * 4);
   L.offsets = take((size_t)(c.E + 1) * 4);
+  L.active = take((size_t)kMaxExperts * 4);
   L.blk_hist = take((size_t)L.nblk * c.E * 4);
   L.blk_base = take((size_t)L.nblk * c.E * 4);
   L.perm = take(n * 4);
@@ -734,7 +735,15 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // One token with every expert resident: the mat-vec launches take the k experts from the gate's own
   // id list on the device, so the host neither waits for the gate nor launches blocks for the others.
   const bool blind_one = decode && T == 1 && !ctx->api_tune.host_looks_always;
-  const bool enqueue_blind = all_resident && (!decode || blind_one);
+  // A decode batch on a layer of many experts (at most two thirds as many assignments as experts:
+  // nearly every expert that is chosen gets one or two tokens): the launches are sized for min(E, T k)
+  // groups of at most two tokens per pass over the weights, find their experts in the list the grouping
+  // kernel writes, and an expert with more tokens takes a second pass.  The shared experts, which see
+  // every token, keep their own launches on the side stream, beside the gate.  (With few experts the row counts pick a much leaner launch, and the host's
+  // look at them pays: Mixtral shape, 4 tokens, 381 against 398 us.)
+  const bool blind_batch = decode && T > 1 && (long long)n * 3 <= (long long)E * 2 && n <= 2048 &&
+                           !ctx->api_tune.host_looks_always;
+  const bool enqueue_blind = all_resident && (!decode || blind_one || blind_batch);
 
   // The counters of earlier calls that were enqueued blind: a call that looks at the cache needs them
   // all (recency stamps decide its victims); a blind call only takes what has arrived.
@@ -756,7 +765,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   // A decode batch (several tokens, so the host looks at the gate's result before it launches the
   // routed experts) does the same: the shared experts' mat-vecs, arithmetic-bound at 8 tokens, then
   // run beside the bandwidth-bound routed ones instead of in front of them.
-  const bool shared_on_side = c.I_shared && (decode ? !enqueue_blind : T >= 256);
+  const bool shared_on_side = c.I_shared && (decode ? (!enqueue_blind || (blind_batch && !blind_one)) : T >= 256);
   SideJoin side_join{ctx, cs};
   if (shared_on_side) {
     HIP_TRY(hipEventRecord(ctx->fork, cs));   // after everything the caller queued before (x, the last call)
@@ -783,14 +792,15 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                             reinterpret_cast<int32_t *>(ws + W.counts),
                             reinterpret_cast<int32_t *>(ws + W.offsets),
                             reinterpret_cast<int32_t *>(ws + W.perm),
-                            reinterpret_cast<int32_t *>(ws + W.inv_perm), mailbox, seq, cs));
+                            reinterpret_cast<int32_t *>(ws + W.inv_perm), mailbox, seq, cs,
+                            n <= 2048 ? reinterpret_cast<int32_t *>(ws + W.active) : nullptr));
   }
   HIP_TRY(hipEventRecord(ctx->routed[box], cs));
 
   // ---- shared experts: independent of the routing.  When the host has to wait for the gate they
   // run first and cover that wait; in an all-resident decode call they ride in the routed launches.
   GemmArgs s1{}, s2{};
-  const bool shared_in_routed_launch = c.I_shared && decode && enqueue_blind;
+  const bool shared_in_routed_launch = c.I_shared && decode && enqueue_blind && !shared_on_side;
   if (c.I_shared) {
     s1 = shared_args(ctx, L, ws, W, T, false, dev_x);
     s2 = shared_args(ctx, L, ws, W, T, true, dev_x);
@@ -867,6 +877,16 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                                         reinterpret_cast<uint16_t *>(dev_y), cs,
                                         shared_in_routed_launch ? &s2 : nullptr));
       combined = true;
+    } else if (blind_batch && !blind_one) {
+      a1.sel_ids = a2.sel_ids = reinterpret_cast<const int32_t *>(ws + W.active);
+      a1.group_mask = a2.group_mask = mask;
+      const int groups = n < E ? n : E;
+      {
+        Timer t(ctx, cs, MOE_K_GEMV1);
+        HIP_TRY(launch_grouped_gemv(GEMM_SWIGLU, a1, 2, groups, cs, shared_in_routed_launch ? &s1 : nullptr));
+      }
+      Timer t(ctx, cs, MOE_K_GEMV2);
+      HIP_TRY(launch_grouped_gemv(GEMM_PLAIN_F32, a2, 2, groups, cs, shared_in_routed_launch ? &s2 : nullptr));
     } else {
       rc = run_experts(ctx, decode, a1, a2, mask, blind_one ? c.k : E, n, T, cs,
                        shared_in_routed_launch ? &s1 : nullptr, shared_in_routed_launch ? &s2 : nullptr, nullptr,

@@ -106,7 +106,7 @@ constexpr int kSmallDispatch = 2048;
 __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
     const int32_t *__restrict__ ids, int n, int E, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-    int32_t *__restrict__ host_counts, int seq) {
+    int32_t *__restrict__ host_counts, int seq, int32_t *__restrict__ active) {
   constexpr int kWaves = kDispatchChunk / 64;
   __shared__ int hist[kMaxExperts];
   __shared__ int base[kMaxExperts];       // next free sorted position of each expert
@@ -131,6 +131,13 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
       if (host_counts) host_counts[lane] = run;
     }
     if (lane == E - 1) offsets[E] = incl;
+    if (active) {
+      // the experts that have rows, in ascending id, then -1: a launch sized for the most there can be
+      // finds its groups here without the host having looked at the counts
+      const unsigned long long has = __ballot(run > 0);
+      if (run > 0) active[__popcll(has & ((1ull << lane) - 1ull))] = lane;
+      if (lane >= __popcll(has)) active[lane] = -1;
+    }
     if (host_counts) {   // the host polls this word (see dispatch_scan_kernel)
       __threadfence_system();
       if (lane == 0) host_counts[kMaxExperts] = seq;
@@ -171,10 +178,10 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
 
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, int seq, hipStream_t stream) {
+                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active) {
   if (n <= kSmallDispatch) {
     hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kDispatchChunk), 0, stream, ids, n, E, counts, offsets,
-                       perm, inv_perm, host_counts, seq);
+                       perm, inv_perm, host_counts, seq, active);
     return hipGetLastError();
   }
   const int nblk = (n + kDispatchChunk - 1) / kDispatchChunk;

@@ -215,7 +215,10 @@ void grouped_gemv_kernel(const GemmArgs routed, const GemmArgs extra,
   int grp = 0, row0 = args.single_row0, cnt = args.single_rows;
   if (args.offsets) {
     if (args.sel_ids) {
-      grp = args.sel_ids[sel];   // the gate's own list (one token: its k experts, all distinct)
+      // a list on the device: the gate's own id list (one token: its k experts, all distinct), or the
+      // grouping kernel's list of the experts that have rows, padded with -1
+      grp = args.sel_ids[sel];
+      if (grp < 0) return;
     } else {
       unsigned long long m = args.group_mask;
       for (unsigned i = 0; i < sel; ++i) m &= m - 1;
@@ -629,6 +632,7 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
   if (offsets) {
     if (!is_extra && routed.sel_ids) {
       grp = routed.sel_ids[sel];
+      if (grp < 0) return;   // (the list of experts with rows is padded with -1)
     } else {
       unsigned long long m = SK_ARG(group_mask);
       for (unsigned i = 0; i < sel; ++i) m &= m - 1;

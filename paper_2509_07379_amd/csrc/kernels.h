@@ -52,9 +52,11 @@ hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d,
 // blk_hist / blk_base: [ceil(n/kDispatchChunk) * E] scratch.  counts [E], offsets [E+1],
 // perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned,
 // kMaxExperts + 1 words): after the counts the kernel writes seq into word kMaxExperts.
+// active (optional, decode-sized inputs only: n <= 2048): [kMaxExperts] receives the ids of the experts
+// that have rows, ascending, padded with -1.
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, int seq, hipStream_t stream);
+                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active = nullptr);
 
 // Tuning and test hooks of one context (moe_tune); all zero = every choice by shape.  Host side only:
 // the launchers read them, the kernels never do.
