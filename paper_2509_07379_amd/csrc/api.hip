@@ -773,6 +773,37 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     side_join.armed = true;
   }
 
+  // ---- the routed experts' two launches, and how a prefill call of some size deals its tiles out
+  GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
+  PlanParams plan_params[2] = {};
+  bool with_plans = false;
+  if (decode) {
+    a2.splitk = 1;   // a decode call never cuts K into slices
+  } else if (n >= 1024) {
+    // Two ways to cut the groups into row tiles and to deal the tiles out.  Few, large groups
+    // (Mixtral-like): tiles of equal height in a fixed order; the blocks of an XCD then stay in step and
+    // share what they fetch, and a group's few left-over rows do not become a tile of their own that
+    // waits for its weights alone (measured in one process: 1508 against 1527 us per layer).  Many groups
+    // of very different size (DeepSeek-like, 48 of 64 groups under 256 rows): full tiles plus a short
+    // remainder tile on its deeper pipeline, taken from per-XCD queues (730 against 803 us per layer);
+    // the plan of those launches is written by the grouping kernel, which has the groups' sizes.
+    const int by_shape = E >= 16 ? 2 : 1;
+    const int up = ctx->api_tune.up_sched ? ctx->api_tune.up_sched : by_shape;
+    const int down = ctx->api_tune.down_sched ? ctx->api_tune.down_sched : by_shape;
+    a1.equal_heights = up == 1;
+    a2.equal_heights = down != 2;
+    with_plans = prepare_gemm_plans(a1, a2, reinterpret_cast<GemmPlan *>(ws + W.plans), plan_params);
+    if (up == 1) {
+      a1.plan = nullptr;
+      plan_params[0].out = nullptr;
+    }
+    if (down == 1) {
+      a2.plan = nullptr;
+      plan_params[1].out = nullptr;
+    }
+    with_plans = with_plans && (a1.plan || a2.plan);
+  }
+
   // ---- gate, Top-k, grouping (one token: the gate's kernel writes the grouping tables itself)
   SingleTokenDispatch one{reinterpret_cast<int32_t *>(ws + W.counts), reinterpret_cast<int32_t *>(ws + W.offsets),
                           reinterpret_cast<int32_t *>(ws + W.perm), reinterpret_cast<int32_t *>(ws + W.inv_perm),
@@ -793,7 +824,8 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                             reinterpret_cast<int32_t *>(ws + W.offsets),
                             reinterpret_cast<int32_t *>(ws + W.perm),
                             reinterpret_cast<int32_t *>(ws + W.inv_perm), mailbox, seq, cs,
-                            n <= 2048 ? reinterpret_cast<int32_t *>(ws + W.active) : nullptr));
+                            n <= 2048 ? reinterpret_cast<int32_t *>(ws + W.active) : nullptr,
+                            with_plans ? plan_params : nullptr));
   }
   HIP_TRY(hipEventRecord(ctx->routed[box], cs));
 
@@ -826,28 +858,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     }
   } join_on_exit{ctx, cs, shared_on_side};
 
-  GemmArgs a1 = routed_args(ctx, L, ws, W, T, false, dev_x), a2 = routed_args(ctx, L, ws, W, T, true, dev_x);
   bool combined = false;   // the weighted sum has been done by the down projection's launch
-  // A prefill call of some size cuts the down projection's K range into slices chosen on the device from
-  // the groups' sizes (the same whichever experts are resident); a decode call never slices.
-  if (decode) a2.splitk = 1;
-  else if (n >= 1024) {
-    // Two ways to cut the groups into row tiles and to deal the tiles out.  Few, large groups
-    // (Mixtral-like): tiles of equal height in a fixed order; the blocks of an XCD then stay in step and
-    // share what they fetch, and a group's few left-over rows do not become a tile of their own that
-    // waits for its weights alone (measured in one process: 1508 against 1527 us per layer).  Many groups
-    // of very different size (DeepSeek-like, 48 of 64 groups under 256 rows): full tiles plus a short
-    // remainder tile on its deeper pipeline, taken from the queues (730 against 803 us per layer).
-    const int by_shape = E >= 16 ? 2 : 1;
-    const int up = ctx->api_tune.up_sched ? ctx->api_tune.up_sched : by_shape;
-    const int down = ctx->api_tune.down_sched ? ctx->api_tune.down_sched : by_shape;
-    a1.equal_heights = up == 1;
-    a2.equal_heights = down != 2;
-    HIP_TRY(launch_gemm_plans(a1, a2, n, reinterpret_cast<GemmPlan *>(ws + W.plans), ctx->api_tune.splitk, cs));
-    if (up == 1) a1.plan = nullptr;
-    if (down == 1) a2.plan = nullptr;
-  }
-
   L.stats.layer_calls++;
   // Will the launch that runs expert e (its largest group having `rows` rows) read the quantised
   // copy in the staging area?  Then it only needs the bytes to have landed, not the expansion.

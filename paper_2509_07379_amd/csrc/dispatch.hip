@@ -7,6 +7,7 @@
 //   3. every block ranks its own assignments with wave ballots and scatters.
 #include "device_utils.h"
 #include "kernels.h"
+#include "gemm_plan.h"
 
 namespace moe {
 
@@ -25,40 +26,67 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_hist_kernel(const int
   if (tid < E) blk_hist[(size_t)blockIdx.x * E + tid] = hist[tid];
 }
 
-__global__ __launch_bounds__(64) void dispatch_scan_kernel(const int32_t *__restrict__ blk_hist,
-                                                           int nblk, int E,
-                                                           int32_t *__restrict__ blk_base,
-                                                           int32_t *__restrict__ counts,
-                                                           int32_t *__restrict__ offsets,
-                                                           int32_t *__restrict__ host_counts, int seq) {
-  const int e = threadIdx.x;
-  int run = 0;
+// Sixteen waves share the blocks out (lane = expert): each sums its share of the block histograms, the
+// sums are exchanged through LDS, and each writes the running totals of its own blocks; the first wave
+// then has every expert's count in its lanes and writes counts, offsets, the host's mailbox and, if
+// asked, the work plans of the layer's grouped GEMMs (one launch less on the critical path).
+constexpr int kScanWaves = 16;
+__global__ __launch_bounds__(64 * kScanWaves) void dispatch_scan_kernel(const int32_t *__restrict__ blk_hist,
+                                                                        int nblk, int E,
+                                                                        int32_t *__restrict__ blk_base,
+                                                                        int32_t *__restrict__ counts,
+                                                                        int32_t *__restrict__ offsets,
+                                                                        int32_t *__restrict__ host_counts, int seq,
+                                                                        const PlanParams p0, const PlanParams p1) {
+  __shared__ int part[kScanWaves][64];
+  const int e = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int per = (nblk + kScanWaves - 1) / kScanWaves;
+  const int b_lo = min(nblk, w * per), b_hi = min(nblk, b_lo + per);
+  int sum = 0;
   if (e < E) {
-    // 16 independent loads in flight per lane: one load per step made this one-block kernel a chain
-    // of memory latencies (45 us for 96 blocks beside a running GEMM)
-    for (int b0 = 0; b0 < nblk; b0 += 16) {
-      int h[16];
+    // 8 independent loads in flight per lane
+    for (int b0 = b_lo; b0 < b_hi; b0 += 8) {
+      int h[8];
 #pragma unroll
-      for (int j = 0; j < 16; ++j) h[j] = b0 + j < nblk ? blk_hist[(size_t)(b0 + j) * E + e] : 0;
+      for (int j = 0; j < 8; ++j) h[j] = b0 + j < b_hi ? blk_hist[(size_t)(b0 + j) * E + e] : 0;
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (b0 + j < nblk) {
+      for (int j = 0; j < 8; ++j) sum += h[j];
+    }
+  }
+  part[w][e] = sum;
+  __syncthreads();
+  int run = 0, total = 0;
+#pragma unroll
+  for (int v = 0; v < kScanWaves; ++v) {
+    const int s = part[v][e];
+    if (v < w) run += s;
+    total += s;
+  }
+  if (e < E) {
+    for (int b0 = b_lo; b0 < b_hi; b0 += 8) {
+      int h[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) h[j] = b0 + j < b_hi ? blk_hist[(size_t)(b0 + j) * E + e] : 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (b0 + j < b_hi) {
           blk_base[(size_t)(b0 + j) * E + e] = run;
           run += h[j];
         }
     }
   }
+  if (w != 0) return;
   // inclusive scan over the experts (lanes)
-  int incl = run;
+  int incl = total;
 #pragma unroll
   for (int s = 1; s < 64; s <<= 1) {
     int o = __shfl_up(incl, s);
     if (e >= s) incl += o;
   }
   if (e < E) {
-    counts[e] = run;
-    offsets[e] = incl - run;
-    if (host_counts) host_counts[e] = run;
+    counts[e] = total;
+    offsets[e] = incl - total;
+    if (host_counts) host_counts[e] = total;
   }
   if (e == E - 1) offsets[E] = incl;
   // the host polls this word: it may trust the counts once it reads the call's sequence number
@@ -66,6 +94,8 @@ __global__ __launch_bounds__(64) void dispatch_scan_kernel(const int32_t *__rest
     __threadfence_system();
     if (e == 0) host_counts[kMaxExperts] = seq;
   }
+  if (p0.out) make_plan(p0, e, total);
+  if (p1.out) make_plan(p1, e, total);
 }
 
 __global__ __launch_bounds__(kDispatchChunk) void dispatch_scatter_kernel(
@@ -106,7 +136,8 @@ constexpr int kSmallDispatch = 2048;
 __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
     const int32_t *__restrict__ ids, int n, int E, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-    int32_t *__restrict__ host_counts, int seq, int32_t *__restrict__ active) {
+    int32_t *__restrict__ host_counts, int seq, int32_t *__restrict__ active, const PlanParams p0,
+    const PlanParams p1) {
   constexpr int kWaves = kDispatchChunk / 64;
   __shared__ int hist[kMaxExperts];
   __shared__ int base[kMaxExperts];       // next free sorted position of each expert
@@ -142,6 +173,8 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
       __threadfence_system();
       if (lane == 0) host_counts[kMaxExperts] = seq;
     }
+    if (p0.out) make_plan(p0, lane, run);
+    if (p1.out) make_plan(p1, lane, run);
   }
   for (int c0 = 0; c0 < n; c0 += kDispatchChunk) {
     for (int i = tid; i < kWaves * kMaxExperts; i += kDispatchChunk) (&wave_cnt[0][0])[i] = 0;
@@ -178,17 +211,20 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
 
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active) {
+                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active,
+                           const PlanParams *plans) {
+  const PlanParams none{};
+  const PlanParams &p0 = plans ? plans[0] : none, &p1 = plans ? plans[1] : none;
   if (n <= kSmallDispatch) {
     hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kDispatchChunk), 0, stream, ids, n, E, counts, offsets,
-                       perm, inv_perm, host_counts, seq, active);
+                       perm, inv_perm, host_counts, seq, active, p0, p1);
     return hipGetLastError();
   }
   const int nblk = (n + kDispatchChunk - 1) / kDispatchChunk;
   hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
                      blk_hist);
-  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(64), 0, stream, blk_hist, nblk, E, blk_base,
-                     counts, offsets, host_counts, seq);
+  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(64 * kScanWaves), 0, stream, blk_hist, nblk, E, blk_base,
+                     counts, offsets, host_counts, seq, p0, p1);
   hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(nblk), dim3(kDispatchChunk), 0, stream, ids, n, E,
                      blk_base, offsets, perm, inv_perm);
   return hipGetLastError();

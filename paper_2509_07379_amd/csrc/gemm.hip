@@ -26,6 +26,7 @@
 
 #include "device_utils.h"
 #include "kernels.h"
+#include "gemm_plan.h"
 
 namespace moe {
 
@@ -1409,98 +1410,6 @@ hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, h
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------------------------
-// The plan of a grouped launch (GemmPlan): one wave, lane g looks at group g.
-//   K slices: a full tile costs 1 (its K loop), a remainder tile of r rows c(r) = max(0.26, its share of
-//   the MFMAs): below that the tile is bound by the weight tile it has to pull through LDS.  With G
-//   blocks, n_f full and n_r remainder tiles cut into s_f and s_r slices take about
-//     ceil(n_f s_f / G) / s_f + ceil(n_r s_r / G) c / s_r + eps (ceil(n_f s_f / G) + ceil(n_r s_r / G))
-//   (eps: storing an item's fp32 plane, relative to a whole K loop); the pair that minimises this is
-//   taken, fewer slices on a tie.  Slices keep at least 8 K steps.
-//   Ranges: the item list is cut where the estimated cost reaches 1/8, 2/8, ... of the total.
-struct PlanParams {
-  const int32_t *offsets;
-  unsigned long long mask;
-  int n_groups, ntn, kt_total, smax, force_s, grid, equal_heights;
-  float eps;
-  GemmPlan *out;
-};
-
-__device__ __forceinline__ float wave_sum_f(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
-  return v;
-}
-
-__device__ void make_plan(const PlanParams &p, int lane) {
-  GemmPlan *out = p.out;
-  const bool active = lane < p.n_groups && ((p.mask >> lane) & 1ull);
-  const int cnt = active ? p.offsets[lane + 1] - p.offsets[lane] : 0;
-  const int mf = p.equal_heights ? (cnt + kPpTileRows - 1) / kPpTileRows : cnt / kPpTileRows;
-  const int rem = p.equal_heights ? 0 : cnt % kPpTileRows, hr = rem ? 1 : 0;
-  // (measured: a tile of at most 64 rows takes half the time of a full one, bound by the weight tile's
-  // way in from HBM; taller ones are priced by their share of the MFMAs)
-  const float c_r = hr ? fmaxf(0.5f, 0.08f + 0.92f * (float)((rem + 63) / 64) * 0.25f) : 0.0f;
-  const float n_f = wave_sum_f((float)mf) * p.ntn, n_r = wave_sum_f((float)hr) * p.ntn;
-  const float c_avg = n_r > 0.0f ? wave_sum_f(c_r) * p.ntn / n_r : 0.0f;
-  int s_f = 1, s_r = 1;
-  if (p.force_s > 0) {
-    s_f = s_r = p.force_s < p.smax ? p.force_s : p.smax;
-  } else {
-    float best = 3.0e38f;
-    const float G = (float)p.grid;
-    for (int a = 1; a <= p.smax; ++a)
-      for (int b = 1; b <= p.smax; ++b) {
-        const float rf = ceilf(n_f * a / G), rr = ceilf(n_r * b / G);
-        const float m = rf / a + rr * c_avg / b + p.eps * (rf + rr);
-        if (m < best * 0.999f) { best = m; s_f = a; s_r = b; }
-      }
-  }
-  const int items = p.ntn * (mf * s_f + hr * s_r);
-  const float cost = p.ntn * ((float)mf + c_r);
-  int item_end = items;
-  float cost_end = cost;
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) {
-    const int oi = __shfl_up(item_end, s);
-    const float oc = __shfl_up(cost_end, s);
-    if (lane >= s) { item_end += oi; cost_end += oc; }
-  }
-  const int n_items = __shfl(item_end, 63);
-  const float total = __shfl(cost_end, 63);
-  out->item_begin[lane + 1] = item_end;
-  if (lane == 0) {
-    out->item_begin[0] = 0;
-    out->n_items = n_items;
-    out->s_full = s_f;
-    out->s_rem = s_r;
-    out->xcd_begin[0] = 0;
-    out->xcd_begin[8] = n_items;
-  }
-  // boundary j: in the group whose cost range holds j/8 of the total, at the same fraction of its items
-  // (a group's range begins exactly where the one before it ends: no target falls between two groups)
-  const float prev_end = __shfl_up(cost_end, 1);
-  const float cost_begin = lane ? prev_end : 0.0f;
-  for (int j = 1; j < 8; ++j) {
-    const float target = total * (float)j * 0.125f;
-    const bool here = cost > 0.0f && cost_begin <= target && target < cost_end;
-    const unsigned long long who = __ballot(here);
-    if (who == 0) {   // (rounding at the very end of the list, or nothing to do at all)
-      if (lane == 0) out->xcd_begin[j] = n_items;
-    } else if (lane == __ffsll((long long)who) - 1) {
-      int at = item_end - items + (int)((target - cost_begin) / cost * (float)items);
-      out->xcd_begin[j] = at < item_end ? at : item_end;
-    }
-  }
-  out->queue[lane] = 0;
-  out->queue[lane + 64] = 0;
-}
-
-__global__ __launch_bounds__(64) void gemm_plan_kernel(const PlanParams p0, const PlanParams p1) {
-  if (p0.out) make_plan(p0, threadIdx.x);
-  if (p1.out) make_plan(p1, threadIdx.x);
-}
-
 template <int MODE>
 hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BM = 128, BN = 128;
@@ -1564,47 +1473,34 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
   }
 }
 
-hipError_t launch_gemm_plans(GemmArgs &a1, GemmArgs &a2, int total_rows, GemmPlan *plans, int force_splitk,
-                             hipStream_t stream) {
+bool prepare_gemm_plans(GemmArgs &a1, GemmArgs &a2, GemmPlan *plans, PlanParams (&params)[2]) {
   a1.plan = a2.plan = nullptr;
   a1.plan_queue = a2.plan_queue = 0;
-  if (!plans || !a1.offsets || !a2.offsets) return hipSuccess;
+  params[0] = PlanParams{};
+  params[1] = PlanParams{};
+  if (!plans || !a1.offsets || !a2.offsets) return false;
   GemmArgs *a[2] = {&a1, &a2};
   const GemmMode mode[2] = {GEMM_SWIGLU, GEMM_PLAIN_F32};
   for (int i = 0; i < 2; ++i) {
     const int v = a[i]->tune.gemm_variant[mode[i]];
-    if (!pp_possible(mode[i], *a[i]) || (v != 0 && v != 12)) return hipSuccess;
+    if (!pp_possible(mode[i], *a[i]) || (v != 0 && v != 12)) return false;
   }
-  PlanParams p[2] = {};
   for (int i = 0; i < 2; ++i) {
-    const int kt_total = a[i]->K / BK;
-    int smax = 1;   // SwiGLU needs whole sums; planes need room in the workspace; a slice keeps 8 K steps
-    if (mode[i] == GEMM_PLAIN_F32) smax = a[i]->splitk;
-    if (smax < 1) smax = 1;
-    a[i]->plan = plans + i;
-    a[i]->max_splitk = smax;
-    const int bn_out = mode[i] == GEMM_SWIGLU ? 128 : 256;
-    p[i].offsets = a[i]->offsets;
-    p[i].mask = a[i]->n_groups >= 64 ? ~0ull : ((1ull << a[i]->n_groups) - 1ull);
-    p[i].n_groups = a[i]->n_groups;
-    p[i].ntn = (a[i]->N + bn_out - 1) / bn_out;
-    p[i].kt_total = kt_total;
-    p[i].smax = smax;
     // every tile of the down GEMM gets the same K slices (a2.splitk): blocks that work side by side then
-    // walk the same K range, whatever tiles they hold
-    p[i].force_s = mode[i] == GEMM_PLAIN_F32 ? a[i]->splitk : 0;
-    p[i].equal_heights = a[i]->equal_heights;
-    // the whole chip, whatever share of it a launch of this layer call will get: the slices must not
-    // depend on how the call is split into launches
-    p[i].grid = pp_grid_blocks();
-    // an fp32 plane of 256 x 256 leaves in about 20 K cycles, a K step takes about 2.3 K
-    p[i].eps = 20000.0f / (2340.0f * (float)(kt_total > 0 ? kt_total : 1));
-    p[i].out = plans + i;
+    // walk the same K range, whatever tiles they hold; SwiGLU needs whole sums
+    const int s = mode[i] == GEMM_PLAIN_F32 && a[i]->splitk > 1 ? a[i]->splitk : 1;
+    a[i]->plan = plans + i;
+    a[i]->max_splitk = s;
+    const int bn_out = mode[i] == GEMM_SWIGLU ? 128 : 256;
+    PlanParams &p = params[i];
+    p.mask = a[i]->n_groups >= 64 ? ~0ull : ((1ull << a[i]->n_groups) - 1ull);
+    p.n_groups = a[i]->n_groups;
+    p.ntn = (a[i]->N + bn_out - 1) / bn_out;
+    p.slices = s;
+    p.equal_heights = a[i]->equal_heights;
+    p.out = plans + i;
   }
-  (void)total_rows;
-  (void)force_splitk;
-  hipLaunchKernelGGL(gemm_plan_kernel, dim3(1), dim3(64), 0, stream, p[0], p[1]);
-  return hipGetLastError();
+  return true;
 }
 
 hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows, int n_groups_in_mask,

@@ -48,6 +48,8 @@ hipError_t launch_dequant_mxfp4(const uint8_t *codes, const uint8_t *scales, lon
 hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
                             float *scores, int32_t *top_out, hipStream_t stream);
 
+struct PlanParams;
+
 // ---- dispatch: stable counting sort of the T*k assignments by expert ------------------
 // blk_hist / blk_base: [ceil(n/kDispatchChunk) * E] scratch.  counts [E], offsets [E+1],
 // perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned,
@@ -56,7 +58,8 @@ hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d,
 // that have rows, ascending, padded with -1.
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active = nullptr);
+                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active = nullptr,
+                           const PlanParams *plans = nullptr);   // plans: NULL or two PlanParams (see below)
 
 // Tuning and test hooks of one context (moe_tune); all zero = every choice by shape.  Host side only:
 // the launchers read them, the kernels never do.
@@ -138,15 +141,24 @@ hipError_t launch_grouped_gemm(GemmMode mode, const GemmArgs &args, int max_rows
                                hipStream_t stream);
 
 
+// What the grouping kernel needs to know to write the plan of one grouped launch: the launch's shape and
+// where the plan goes (out == NULL: no plan).
+struct PlanParams {
+  unsigned long long mask;   // groups that take part
+  int n_groups;
+  int ntn;                   // column tiles of the launch
+  int slices;                // K slices of every tile
+  int equal_heights;         // how the groups are cut into row tiles (GemmArgs::equal_heights)
+  GemmPlan *out;
+};
+
 // The plans of a prefill layer's two grouped GEMMs (gate/up: a1, down: a2, both with their offsets and
 // every group in the mask): if both can run on the persistent kernel, points a1.plan / a2.plan at
-// plans[0] / plans[1] (device memory) and enqueues the kernel that fills them in from the groups'
-// sizes; otherwise leaves both NULL.  Every GEMM launch of the layer call, grouped or one expert at a
-// time, then takes its K slices from the plan, so the summation order of an output element depends on
-// the layer's routing only, never on which experts happened to be resident.  force_splitk > 0 fixes the
-// K slices of every tile of the down GEMM (tuning hook).
-hipError_t launch_gemm_plans(GemmArgs &a1, GemmArgs &a2, int total_rows, GemmPlan *plans, int force_splitk,
-                             hipStream_t stream);
+// plans[0] / plans[1] (device memory), fills in params for launch_dispatch, which then writes the plans
+// from the groups' sizes, and returns true; otherwise leaves both NULL.  Every tile of the down GEMM is cut
+// into a2.splitk K slices, so the summation order of an output element never depends on which
+// experts happened to be resident.
+bool prepare_gemm_plans(GemmArgs &a1, GemmArgs &a2, GemmPlan *plans, PlanParams (&params)[2]);
 
 // The kernel launch_grouped_gemm picks: 1 = 128 x 128 tiles, 6 = 256 x 256 single-phase, 12 = persistent
 // ping-pong, 100 = the register-staged kernel for K that is no multiple of 64.
