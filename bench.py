@@ -447,6 +447,8 @@ def prefill_c4(args, torch, B, H, S, compute, copy, steps=20, n_check=32):
                                "below_256": int((counts < 256).sum())},
            "parity_on_sample": ok, "sample_tokens": n_check, "max_abs_err_on_sample": float(err.max())}
 
+    if args.no_offloaded:
+        return out
     # the configured cache of 16 slots: every expert streams through it once per layer
     ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared)
     lay2 = H.DeviceLayer(ctx, w, 0, pool, None)
@@ -517,6 +519,8 @@ def decode_c5(args, torch, B, H, S, compute, copy, pred, n_layers=4, steps=32):
     ctx.close()
     del layers
 
+    if args.no_offloaded:
+        return out
     # the configured cache: 15 of 60 experts per layer, predictor top-8 one layer ahead
     out["cached"] = decode_cached(torch, B, H, S, w, pools, trace, xs, biases, compute, copy, pred)
     return out

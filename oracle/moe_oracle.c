@@ -4,8 +4,9 @@
  * tests, the smoke check and the benchmark's cpu_baseline leg may call it.
  *
  * The scheduling side of the method (prefetch, caching, prediction; Section V of the
- * paper) must never change the numbers ("the expert weights used are correct",
- * Section V-C), so the numerical oracle is the plain definition of the layer:
+ * paper) must never change the numbers (Section V-C has the verification step make sure that
+ * the right experts' weights are the ones computed with), so the numerical oracle is the plain
+ * definition of the layer:
  *   - a softmax gate whose values are non-negative and sum to 1 (Section II-A),
  *   - Top-k selection out of n routed experts (Section II-A, Fig. 1),
  *   - grouping the tokens by assigned expert (Section V-B),

@@ -14,8 +14,8 @@ TEST INFRASTRUCTURE ONLY.  Plain definitions:
       a_{l-1,l}  for each of the k experts selected at layer l - 1, its affinity row A[l-1, i, :]
                  (k * M entries); zeros for l = 0
 
-The paper fixes none of the encodings ("flatten ... zero-padding to a fixed length"); the choices
-above are this build's reading.  An episode is one token's pass through all layers.
+The paper fixes none of the encodings (Eq. 4-5 only say that the index history is flattened and
+padded with zeros to a fixed length); the choices above are this build's reading.  An episode is one token's pass through all layers.
 """
 from __future__ import annotations
 

@@ -814,7 +814,10 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
     // rows only in down projections with long rows, or past the per-token kernels' 8 tokens.
     bool pays;
     if (use_q8) pays = !(args.qfmt == 1 && mode == GEMM_PLAIN_F32 && max_tok < 5);
-    else pays = max_tok > GV_MAXTOK || (mode == GEMM_PLAIN_F32 && args.K >= 4096);
+    // (a launch of fewer than 128 blocks of four waves leaves most of the chip without a wave: the
+    // Qwen-shaped shared experts' down projection, 64 blocks, took 41 us there against 10 us per token)
+    else pays = max_tok > GV_MAXTOK ||
+                (mode == GEMM_PLAIN_F32 && args.K >= 4096 && (long long)(args.N / 32) * n_groups_in_mask >= 128);
     if (args.tune.skinny_forced) pays = true;
     // from 3 tokens per expert; quantised gate/up rows from 2 (MXFP4, Mixtral shape, 2 tokens: 57
     // against 70 us per launch; one token is faster per token: 37 against 41 us)
