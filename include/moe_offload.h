@@ -28,7 +28,10 @@
  *  - Every function returns 0 on success or a negative MOE_E_* code and never throws
  *    or aborts; moe_last_error() returns a thread-local message for the last failure.
  *  - One ctx serves one (compute stream, copy stream) pair at a time; calls on the
- *    same ctx must not overlap in time from several host threads.
+ *    same ctx must not overlap in time from several host threads.  The compute stream of a
+ *    layer call must stay alive until the ctx is destroyed or the layer's cache has been used
+ *    again: a later copy into a slot that the call read may record, on that stream, the event
+ *    it then waits for.
  */
 #ifndef MOE_OFFLOAD_H
 #define MOE_OFFLOAD_H

@@ -138,6 +138,8 @@ struct SlotSet {
   std::vector<char> q_valid;         // the staging area holds the quantised form of what the slot holds
   std::vector<char> expand_pending;  // the expansion into the slot was enqueued; compute has not waited for it yet
   hipEvent_t group_done = nullptr;
+  bool done_pending = false;         // group_done still has to be recorded, on done_stream, before it is waited for
+  hipStream_t done_stream = nullptr;
   unsigned long long clock = 0;
 };
 
@@ -390,7 +392,13 @@ int pick_victim(const Layer &L, unsigned long long protected_mask) {
 // The copy stream waits for the last reader of slot s (nothing to wait for if it was never read).
 int wait_slot_free(Layer &L, int s, hipStream_t copy_stream) {
   if (L.set->use_kind[s] == 1) HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->used[s], 0));
-  if (L.set->use_kind[s] == 2) HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->group_done, 0));
+  if (L.set->use_kind[s] == 2) {
+    if (L.set->done_pending) {   // the last grouped launch over resident experts left the recording to us
+      HIP_TRY(hipEventRecord(L.set->group_done, L.set->done_stream));
+      L.set->done_pending = false;
+    }
+    HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->group_done, 0));
+  }
   return MOE_OK;
 }
 
@@ -904,7 +912,11 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                        true);
       if (rc) return rc;
     }
-    HIP_TRY(hipEventRecord(L.set->group_done, cs));
+    // "Every reader of these slots is done" is recorded only when a copy asks for it (wait_slot_free):
+    // an event between two launches holds the second one back by several microseconds, and a layer
+    // whose experts are all resident is rarely copied into.
+    L.set->done_pending = true;
+    L.set->done_stream = cs;
     for (int s = 0; s < S; ++s)
       if (L.set->slot_layer[s] == L.index) L.set->use_kind[s] = 2;
     // The counters need the gate's counts, the launches did not: they are filled in when the mailbox
@@ -947,6 +959,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
                        true);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(L.set->group_done, cs));
+      L.set->done_pending = false;
       for (int e = 0; e < E; ++e)
         if ((hit_mask >> e) & 1ull) L.set->use_kind[L.expert_slot[e]] = 2;
     } else if (n_hits) {
