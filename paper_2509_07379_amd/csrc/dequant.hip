@@ -1,9 +1,8 @@
-// Expansion of 8-bit expert weights (OCP e4m3 codes, one fp32 scale per output row) and of 4-bit ones
-// (unsigned integers in groups of 128 with scale and zero point; MXFP4) into the bf16 matrices the
-// GPU expert cache holds.  The paper evaluates quantised models (Section VI); in this
-// library only the copy over the host link is 8-bit: a fetched expert lands in a staging area next
-// to the cache and this kernel writes its slot, so every matmul kernel reads bf16 as before.
-//   weight = bf16_rne( fp32( value(code) * scale[row] ) )
+// Expansion of 4-bit expert weights (unsigned integers in groups of 128 with scale and zero point;
+// MXFP4) into the bf16 matrices the GPU expert cache holds for those formats.  The paper evaluates
+// quantised models (Section VI); a fetched 4-bit expert lands in a staging area next to the cache and
+// one of these kernels writes its slot, so the GEMM kernels read bf16.  (8-bit experts are never
+// expanded in memory: every kernel reads their codes.)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -15,45 +14,6 @@ namespace moe {
 namespace {
 
 constexpr int kThreads = 256;
-
-// value(code) as fp32 bits: exponent field e (bias 7) and 3 mantissa bits m; e = 0 is subnormal
-// (m * 2^-9); sign in bit 7.  Code 0x7F / 0xFF is NaN.
-__device__ inline float e4m3_to_f32(int code) {
-  const int e = (code >> 3) & 15, m = code & 7;
-  uint32_t bits;
-  if (e == 15 && m == 7) bits = 0x7FC00000u;
-  else if (e == 0) bits = __float_as_uint((float)m * 0.001953125f);
-  else bits = ((uint32_t)(e + 120) << 23) | ((uint32_t)m << 20);
-  return __uint_as_float(bits | ((uint32_t)(code & 0x80) << 24));
-}
-
-// q [rows, cols] codes, scales [rows], out [rows, cols] bf16; cols % 8 == 0.  One lane expands 8
-// codes (one 8-byte load, one 16-byte store); the 256-entry value table lives in LDS.
-__global__ __launch_bounds__(kThreads) void dequant_e4m3_rows_kernel(const uint8_t *__restrict__ q,
-                                                                     const float *__restrict__ scales,
-                                                                     long long rows, int cols,
-                                                                     uint16_t *__restrict__ out) {
-  __shared__ float table[256];
-  table[threadIdx.x] = e4m3_to_f32(threadIdx.x);
-  __syncthreads();
-  const int per_row = cols >> 3;
-  const long long chunks = rows * per_row;
-  for (long long c = (long long)blockIdx.x * kThreads + threadIdx.x; c < chunks;
-       c += (long long)gridDim.x * kThreads) {
-    const long long row = c / per_row;
-    const float s = scales[row];
-    const uint2 codes = *reinterpret_cast<const uint2 *>(q + c * 8);
-    uint32_t w[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t pair = ((j < 2 ? codes.x : codes.y) >> ((j & 1) * 16)) & 0xFFFFu;
-      const float lo = table[pair & 0xFF] * s;
-      const float hi = table[pair >> 8] * s;
-      w[j] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-    }
-    *reinterpret_cast<uint4 *>(out + c * 8) = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
 
 // 4-bit codes (unsigned, two per byte, even column in the low nibble), groups of 128 along a row with
 // one fp32 scale and one zero point each:  out = bf16_rne(fp32((code - zero) * scale)).
@@ -149,18 +109,6 @@ hipError_t launch_dequant_int4_g128(const uint8_t *codes, const float *scales, c
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(dequant_int4_g128_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, codes, scales,
                      zeros, rows, cols, out);
-  return hipGetLastError();
-}
-
-hipError_t launch_dequant_e4m3_rows(const uint8_t *q, const float *scales, long long rows, int cols,
-                                    uint16_t *out, hipStream_t stream) {
-  if (rows <= 0 || cols <= 0) return hipSuccess;
-  if (cols % 8) return hipErrorInvalidValue;
-  const long long chunks = rows * (cols >> 3);
-  long long blocks = (chunks + kThreads - 1) / kThreads;
-  if (blocks > 4096) blocks = 4096;   // grid-stride beyond: 16 blocks per CU keep HBM busy
-  hipLaunchKernelGGL(dequant_e4m3_rows_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, q, scales, rows,
-                     cols, out);
   return hipGetLastError();
 }
 

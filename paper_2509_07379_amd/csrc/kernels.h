@@ -34,9 +34,6 @@ hipError_t launch_mlp_predictor(const float *state, const int32_t *dims, int n_f
                                 const float *const *bias, const float *const *scale, const float *const *shift,
                                 float *act0, float *act1, int m, float *scores, int32_t *top_out,
                                 hipStream_t stream);
-// 8-bit expert weights -> bf16: out[r, c] = bf16_rne(value_e4m3(q[r, c]) * scales[r]); cols % 8 == 0.
-hipError_t launch_dequant_e4m3_rows(const uint8_t *q, const float *scales, long long rows, int cols,
-                                    uint16_t *out, hipStream_t stream);
 // 4-bit expert weights -> bf16: out[r, c] = bf16_rne((code[r, c] - zeros[r, c/128]) * scales[r, c/128]);
 // two codes per byte, even column in the low nibble; cols % 128 == 0.
 hipError_t launch_dequant_int4_g128(const uint8_t *codes, const float *scales, const uint8_t *zeros,
