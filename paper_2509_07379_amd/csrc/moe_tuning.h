@@ -21,6 +21,12 @@
  *                   0 = default, 1 = wherever the shapes allow it, a large value = never
  *   mode 9          largest group a decode call still gives to the mat-vec launches (0 = default)
  *   mode 10         K slices (waves) per block of the matrix-core mat-vec (0 = by shape, 1..8)
+ *   mode 11         how the persistent down GEMM of a prefill call cuts groups into row tiles and deals
+ *                   them out: 0 = by shape (fewer than 16 experts: 1, else 2), 1 = row tiles of equal
+ *                   height in a fixed order per block, 2 = full tiles plus a remainder, taken from the
+ *                   per-XCD queues of the plan the grouping kernel writes, 3 = equal heights from queues
+ *   mode 12         the same for the gate/up GEMM: 0 = by shape, 1 = equal heights in a fixed order,
+ *                   2 = full tiles plus a remainder from queues
  */
 #ifndef MOE_TUNING_H
 #define MOE_TUNING_H

@@ -265,6 +265,50 @@ def test_per_token_bias_forces_trace(gpu, oracle):
 
 
 # ---------------------------------------------------------------- offloaded: results never depend on the cache
+@pytest.mark.parametrize("up,down", [(0, 0), (2, 2), (1, 3), (2, 1)])
+def test_work_plans_of_the_persistent_gemm(gpu, oracle, up, down):
+    """The grouping kernel writes, per GEMM launch, the prefix of work items per group, eight item ranges
+    and eight queue counters.  Recomputed here from the groups' sizes: items per group for both ways of
+    cutting a group into row tiles, ranges that cover the list in order, and counters that show every range
+    was emptied; the layer's output against the oracle under each schedule (0 = by shape: 32 experts take
+    full tiles plus a remainder from queues)."""
+    H, B = gpu["harness"], gpu["binding"]
+    w = S.Workload("plan", d=512, I=384, E=32, k=4, T=900, seed=77, zipf_s=1.1)
+    x_np, bias = S.activations(w), S.zipf_route_bias(w, 0)
+    ctx = new_ctx(B, w.d, w.I, w.E, w.k, 1, w.E, 0, True)
+    ctx.moe_tune(12, up)
+    ctx.moe_tune(11, down)
+    pool = H.HostPool(w, 0)
+    lay = H.DeviceLayer(ctx, w, 0, pool, list(range(w.E)))
+    buf = H.Buffers(ctx, w.T)
+    ctx.moe_prefill_layer(0, H.np_to_dev(x_np), w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], H.np_to_dev(bias), 0)
+    gpu["compute"].synchronize()
+    routing = buf.routing(ctx, gpu["compute"])
+    plans = ctx.moe_debug_plans(buf.ws, w.T, gpu["compute"])
+    ref = oracle_layer(oracle, w, x_np, lay.router_np, pool, bias=bias)
+    np.testing.assert_array_equal(routing["counts"], ref["counts"])
+    check_out(H.dev_to_np_u16(buf.y), ref["out_f64"], f"schedules {up}/{down}")
+    ctx.close()
+    counts = ref["counts"].astype(np.int64)
+    assert counts.max() > 256 and (counts % 256 != 0).any() and (counts < 64).any()   # the case is ragged
+    # (launch, columns per column tile, schedule): a fixed order (1) uses no plan
+    for plan, ntn, sched in ((plans[0], -(-w.I // 128), up or 2), (plans[1], -(-w.d // 256), down or 2)):
+        if sched == 1:
+            continue
+        equal = sched == 3
+        tiles = -(-counts // 256) if equal else counts // 256 + (counts % 256 > 0)
+        s = plan["s_full"]
+        assert s >= 1 and plan["s_rem"] == s
+        begin = np.concatenate([[0], np.cumsum(tiles * ntn * s)])
+        assert plan["item_begin"][:w.E + 1] == begin.tolist()
+        assert plan["n_items"] == begin[-1] and all(v == begin[-1] for v in plan["item_begin"][w.E + 1:])
+        xb = plan["xcd_begin"]
+        assert xb[0] == 0 and xb[8] == plan["n_items"] and all(a <= b for a, b in zip(xb, xb[1:]))
+        sizes = [b - a for a, b in zip(xb, xb[1:])]
+        assert max(sizes) <= 2 * (plan["n_items"] / 8) + ntn * s * 2      # ranges of comparable cost
+        assert all(q >= n for q, n in zip(plan["queue"], sizes)), (plan["queue"], sizes)
+
+
 @pytest.mark.parametrize("decode", [False, True])
 def test_streaming_through_two_slots_is_bit_identical(gpu, oracle, decode):
     from oracle.cache_sim import CacheSim
