@@ -738,19 +738,20 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 
   bool all_resident = true;
   for (int e = 0; e < E; ++e) all_resident &= L.expert_slot[e] >= 0;
-  // Enqueue everything without looking at the gate's result only when that result cannot change the
-  // launch: all experts resident and, for the mat-vec path, one token (every active expert then has
-  // exactly one row).  A decode batch takes the other path: the per-expert row counts pick a much
-  // leaner mat-vec variant, and the shared experts' launch covers the host's wait.
-  // One token with every expert resident: the mat-vec launches take the k experts from the gate's own
-  // id list on the device, so the host neither waits for the gate nor launches blocks for the others.
+  // A call is enqueued without looking at the gate's result when that result cannot change what is
+  // launched: every expert resident, and
+  //  - a prefill call (one grouped launch over all experts, sized on the device), or
+  //  - one token: the mat-vec launches take the k experts from the gate's own id list on the device, so
+  //    the host neither waits for the gate nor launches blocks for the other experts, or
+  //  - a decode batch on a layer of many experts (at most two thirds as many assignments as experts, so
+  //    nearly every chosen expert gets one or two tokens): the launches are sized for min(E, T k) groups
+  //    of at most two tokens per pass over the weights, find their experts in the list the grouping
+  //    kernel writes, and an expert with more tokens takes further passes.  The shared experts, which
+  //    see every token, keep their own launches on the side stream, beside the gate.
+  // A decode batch on a layer of few experts takes the other path: the per-expert row counts pick a much
+  // leaner mat-vec variant and the host's look at them pays (Mixtral shape, 4 tokens: 381 against
+  // 398 us), while the shared experts' launches cover the host's wait.
   const bool blind_one = decode && T == 1 && !ctx->api_tune.host_looks_always;
-  // A decode batch on a layer of many experts (at most two thirds as many assignments as experts:
-  // nearly every expert that is chosen gets one or two tokens): the launches are sized for min(E, T k)
-  // groups of at most two tokens per pass over the weights, find their experts in the list the grouping
-  // kernel writes, and an expert with more tokens takes a second pass.  The shared experts, which see
-  // every token, keep their own launches on the side stream, beside the gate.  (With few experts the row counts pick a much leaner launch, and the host's
-  // look at them pays: Mixtral shape, 4 tokens, 381 against 398 us.)
   const bool blind_batch = decode && T > 1 && (long long)n * 3 <= (long long)E * 2 && n <= 2048 &&
                            !ctx->api_tune.host_looks_always;
   const bool enqueue_blind = all_resident && (!decode || blind_one || blind_batch);
