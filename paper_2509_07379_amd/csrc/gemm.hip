@@ -103,9 +103,11 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs &args, TileInfo &t) {
 // traffic plus its MFMAs, so two full tiles and a short one are cheaper than three of medium height).
 // A full tile is cut into s_f K slices, a remainder tile into s_r; an item is (row tile, column tile,
 // K slice).  Inside a group the row tiles are numbered in panels of 8 (the remainder tile is the last
-// row tile): inside a panel the row tile runs fastest, then the K slice, then the column tile, so the
-// blocks of an XCD that work side by side share each operand tile through their L2 and walk the
-// same K range at the same time.
+// row tile): inside a panel the row tile runs fastest, then the column tile, then the K slice, so the
+// blocks of an XCD that work side by side are on one K slice: they share each operand tile through
+// their L2 and walk the same K range at the same time (with the K slice ahead of the column tile the
+// 32 blocks of an XCD spread over all slices and re-read the rows of A once per five column tiles:
+// Mixtral shape, down GEMM 483 -> 469 us).
 // (args.equal_heights: the other way to cut a group, ceil(cnt / BM) tiles of equal height rounded up to 32
 // rows, all of them "full" tiles as far as the numbering goes.  Equal tiles keep the blocks of an XCD in
 // step with each other, which the down projection, whose both operands stream from HBM, needs more
@@ -161,16 +163,14 @@ __device__ __forceinline__ void decode_item(const GemmArgs &args, const GemmPlan
   l -= panel * ipp;
   const int pf = min(PANEL, mf - panel * PANEL);  // full tiles of this panel
   const int pr = (panel == mf / PANEL) ? hr : 0;  // ... and the remainder tile, in the group's last panel
-  const int per_n = pf * s_f + pr * s_r;          // > 0 for every valid item
-  const int n_idx = l / per_n;
-  int r = l - n_idx * per_n;
-  int ks = 0;
-  for (;; ++ks) {
-    const int here = (ks < s_f ? pf : 0) + (ks < s_r ? pr : 0);
-    if (r < here || ks >= 7) break;
-    r -= here;
-  }
-  const bool is_rem = ks < s_f ? r >= pf : true;
+  // inside the panel: row tile fastest, then the column tile, then the K slice (s_f == s_r whenever a
+  // remainder tile shares a panel with full tiles: every tile of a launch has the same K slices)
+  const int here = pf + pr;                       // row tiles of this panel, > 0 for every valid item
+  const int ks = l / (here * ntn);
+  const int rr = l - ks * here * ntn;
+  const int n_idx = rr / here;
+  const int r = rr - n_idx * here;
+  const bool is_rem = r >= pf;
   const int m_idx = panel * PANEL + (is_rem ? pf : r);
   // (everything here is the same for all lanes: say so, so that it lives in scalar registers)
   t.grp = __builtin_amdgcn_readfirstlane(grp);
