@@ -616,11 +616,17 @@ def batch_sweep(torch, B, H, S, compute, copy, batches=(1, 2, 4, 8, 12), n_layer
                     torch.cuda.synchronize()
 
                 one_pass()
+                # a pass is 16 layer calls (a millisecond at the small batches): the median of three, so
+                # that one hiccup of the host does not become a table entry; counters from the first
                 ctx.moe_reset_stats()
-                t0 = time.perf_counter()
-                one_pass()
-                us = (time.perf_counter() - t0) * 1e6 / (steps * n_layers)
-                st = ctx.moe_get_stats(-1)
+                times = []
+                for rep in range(3 if slots == w0.E else 1):
+                    t0 = time.perf_counter()
+                    one_pass()
+                    times.append((time.perf_counter() - t0) * 1e6 / (steps * n_layers))
+                    if rep == 0:
+                        st = ctx.moe_get_stats(-1)
+                us = sorted(times)[len(times) // 2]
                 distinct = float(np.mean([len(set(trace[s, l].ravel().tolist()))
                                           for s in range(steps) for l in range(n_layers)]))
                 if slots == w0.E:
