@@ -791,14 +791,16 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   if (decode) {
     a2.splitk = 1;   // a decode call never cuts K into slices
   } else if (n >= 1024) {
-    // Two ways to cut the groups into row tiles and to deal the tiles out.  Few, large groups
-    // (Mixtral-like): tiles of equal height in a fixed order; the blocks of an XCD then stay in step and
-    // share what they fetch, and a group's few left-over rows do not become a tile of their own that
-    // waits for its weights alone (measured in one process: 1508 against 1527 us per layer).  Many groups
-    // of very different size (DeepSeek-like, 48 of 64 groups under 256 rows): full tiles plus a short
-    // remainder tile on its deeper pipeline, taken from per-XCD queues (730 against 803 us per layer);
-    // the plan of those launches is written by the grouping kernel, which has the groups' sizes.
-    const int by_shape = E >= 16 ? 2 : 1;
+    // Two ways to cut the groups into row tiles and to deal the tiles out.  Few groups of a few row tiles
+    // each (Mixtral-like at 2048 tokens): tiles of equal height in a fixed order; the blocks of an XCD then
+    // stay in step and share what they fetch, and a group's few left-over rows do not become a tile of
+    // their own that waits for its weights alone (measured in one process: 1508 against 1527 us per
+    // layer).  Many groups of very different size (DeepSeek-like, 48 of 64 groups under 256 rows), or groups
+    // of many row tiles: full tiles plus a short remainder tile on its deeper pipeline, taken from per-XCD
+    // queues (64 experts: 730 against 803 us per layer; 8 experts: ahead from about 1500 rows per group,
+    // 4.86 against 5.00 ms at 8192 tokens, 18.3 against 19.1 ms at 32768); the plan of those launches is
+    // written by the grouping kernel, which has the groups' sizes.
+    const int by_shape = (E >= 16 || (long long)n >= 1536ll * E) ? 2 : 1;
     const int up = ctx->api_tune.up_sched ? ctx->api_tune.up_sched : by_shape;
     const int down = ctx->api_tune.down_sched ? ctx->api_tune.down_sched : by_shape;
     a1.equal_heights = up == 1;
