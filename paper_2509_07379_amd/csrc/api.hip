@@ -743,16 +743,19 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
   //  - a prefill call (one grouped launch over all experts, sized on the device), or
   //  - one token: the mat-vec launches take the k experts from the gate's own id list on the device, so
   //    the host neither waits for the gate nor launches blocks for the other experts, or
-  //  - a decode batch on a layer of many experts (at most two thirds as many assignments as experts, so
-  //    nearly every chosen expert gets one or two tokens): the launches are sized for min(E, T k) groups
-  //    of at most two tokens per pass over the weights, find their experts in the list the grouping
-  //    kernel writes, and an expert with more tokens takes further passes.  The shared experts, which
-  //    see every token, keep their own launches on the side stream, beside the gate.
+  //  - a decode batch whose experts get few tokens each (on a layer of 16 experts or more at most 2.25
+  //    assignments per expert, on a smaller one at most two thirds of one): the launches are sized for
+  //    min(E, T k) groups of at most two tokens per pass over the weights, find their experts in the list the
+  //    grouping kernel writes, and an expert with more tokens takes further passes.  The shared experts,
+  //    which see every token, keep their own launches on the side stream, beside the gate.  (Qwen shape,
+  //    per layer: 12 tokens 146 against 150 us with the host's look, 24 tokens 214 against 242, 32 tokens 253
+  //    against 283; 48 tokens 334 against 306, so from there on the host looks.)
   // A decode batch on a layer of few experts takes the other path: the per-expert row counts pick a much
   // leaner mat-vec variant and the host's look at them pays (Mixtral shape, 4 tokens: 381 against
   // 398 us), while the shared experts' launches cover the host's wait.
   const bool blind_one = decode && T == 1 && !ctx->api_tune.host_looks_always;
-  const bool blind_batch = decode && T > 1 && (long long)n * 3 <= (long long)E * 2 && n <= 2048 &&
+  const bool few_per_expert = E >= 16 ? (long long)n * 4 <= (long long)E * 9 : (long long)n * 3 <= (long long)E * 2;
+  const bool blind_batch = decode && T > 1 && few_per_expert && n <= 2048 &&
                            !ctx->api_tune.host_looks_always;
   const bool enqueue_blind = all_resident && (!decode || blind_one || blind_batch);
 

@@ -81,7 +81,7 @@ def test_same_program_through_both_tables(gpu, name, E, k, Ish, slots, shared, f
             np.testing.assert_array_equal(top.numpy(), want, err_msg=tag)
             continue
         else:
-            T = int(rng.choice([65, 130, 300, 700]) if op == "prefill" else rng.choice([1, 1, 2, 3, 8, 12]))
+            T = int(rng.choice([65, 130, 300, 700]) if op == "prefill" else rng.choice([1, 1, 2, 3, 8, 12, 24, 32]))
             wl = S.Workload(name, d=w.d, I=w.I, E=E, k=k, T=T, seed=9000 + call, zipf_s=1.1)
             x_np = S.activations(wl, l, call)
             bias_np = S.zipf_route_bias(wl, l) if rng.integers(2) else None   # skewed popularity, or the plain gate
