@@ -133,14 +133,15 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, 
     """Offloaded regime: S = w.S slots, experts fetched from pinned memory on the copy stream; a
     stand-in attention block (4 bf16 GEMMs T x d x d) runs on the compute stream while the first
     experts are prefetched.  Returns T_copy-alone, T_compute-alone and T_pipelined per layer.
-    fmt 1 / 2: the CPU expert cache holds the same experts as e4m3 codes with per-row scales / as 4-bit
-    codes in groups of 128 (half / about a quarter of the bytes on the link, expanded into the bf16
-    slots by a kernel behind each copy)."""
+    fmt 1 / 3: the CPU expert cache holds the same experts as e4m3 codes with per-row scales / as MXFP4
+    (half / about a quarter of the bytes on the link; the slots hold those blobs and every kernel reads
+    the codes); fmt 2: as 4-bit integer codes in groups of 128, expanded into bf16 slots by a kernel
+    behind each copy."""
     q8 = fmt != 0
     if q8:
         t0 = time.time()
         pool = H.HostPool(w, 0, fmt=fmt)
-        log(f"[bench] {8 if fmt == 1 else 4}-bit host pool {w.E * pool.bytes_per_expert / 1e9:.2f} GB quantised in {time.time() - t0:.1f}s")
+        log(f"[bench] {8 if fmt == 1 else 4}-bit host pool (format {fmt}) {w.E * pool.bytes_per_expert / 1e9:.2f} GB quantised in {time.time() - t0:.1f}s")
     ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared, host_format=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, None)
     buf = H.Buffers(ctx, w.T)
@@ -183,14 +184,22 @@ def prefill_offloaded(args, torch, B, H, S, w, pool, x, compute, copy, steps=6, 
     def copies():
         for e in range(w.E):
             s = e % w.S
-            off = (s * stage if fmt == 1 else w.S * w.blob_bytes + s * stage) if q8 else s * w.blob_bytes
+            off = (s * stage if fmt in (1, 3) else w.S * w.blob_bytes + s * stage) if q8 else s * w.blob_bytes
             raw[off:off + hb].copy_(pool.buf[e], non_blocking=True)
 
     with torch.cuda.stream(copy):
         t_c = timed(copies, steps)
     ctx.close()
-    return dict(t_pipelined_ms=t_p, t_copy_ms=t_c, bytes_per_layer=bytes_per_layer, attention=attention,
-                timed=timed)
+    out = dict(t_pipelined_ms=t_p, t_copy_ms=t_c, bytes_per_layer=bytes_per_layer, attention=attention, timed=timed)
+    if fmt in (1, 3):
+        # the same layer with every expert resident in its quantised form: the GEMMs that expand code tiles
+        # on their way into LDS, nothing fetched
+        ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, host_format=fmt)
+        lay = H.DeviceLayer(ctx, w, 0, pool, list(range(w.E)))
+        buf = H.Buffers(ctx, w.T)
+        out["t_resident_ms"] = timed(lambda: ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy), 20)
+        ctx.close()
+    return out
 
 
 def decode_batch_us(torch, H, S, ctx, wl, n_layers, batch, compute, copy, bytes_per_expert, steps=8):
@@ -289,8 +298,8 @@ def decode_regime(args, torch, B, H, S, w, n_layers, steps, compute, copy, pred)
 
 def decode_resident_q8(args, torch, B, H, S, w, n_layers, steps, compute, copy, fmt=1):
     """Kernel regime of decode with a quantised host pool (fmt 1: e4m3 rows, 3: MXFP4): every expert
-    fetched once through the library (so its quantised copy sits in the staging area next to its bf16
-    slot), then steady-state steps in which the mat-vec kernels stream the quantised copies."""
+    fetched once through the library into a slot of its own, then steady-state steps in which the
+    mat-vec kernels stream the quantised blobs."""
     from dataclasses import replace
     wl = replace(w, L=n_layers, steps=steps)
     t0 = time.time()
@@ -819,17 +828,23 @@ def main():
         }
         log(f"[bench] offloaded: {line['offloaded']}")
         formats = {"offloaded_q8": (1, "e4m3 codes + fp32 scale per row"),
+                   "offloaded_mxfp4": (3, "MXFP4: e2m1 codes + one power-of-two scale byte per 32 weights"),
                    "offloaded_q4": (2, "4-bit codes in groups of 128 + fp32 scale and zero point per group")}
         for key, (fmt, what) in ({} if args.no_q8 else formats).items():
             oq = prefill_offloaded(args, torch, B, H, S, w, None, res["x"], compute, copy, fmt=fmt)
             t_c, t_p = oq["t_copy_ms"], oq["t_pipelined_ms"]
             line[key] = {
-                "host_format": what + (": the cache holds the 8-bit blobs, the GEMMs expand tiles on their way into LDS"
-                                       if fmt == 1 else ", expanded into the bf16 slots by a kernel behind each copy"),
+                "host_format": what + (": the cache holds the quantised blobs, the GEMMs expand tiles on their way into LDS"
+                                       if fmt in (1, 3) else ", expanded into the bf16 slots by a kernel behind each copy"),
                 "slots": w.S, "ms_per_layer": t_p, "tokens_per_s": w.T / (t_p * 1e-3), "t_copy_alone_ms": t_c,
                 "bytes_per_layer": oq["bytes_per_layer"], "h2d_GBps": oq["bytes_per_layer"] / (t_c * 1e-3) / 1e9,
                 "overlap": (t_c + t_k - t_p) / min(t_c, t_k), "link_busy_frac": t_c / t_p,
             }
+            if "t_resident_ms" in oq:
+                # overlap above is against the bf16 layer's compute time; this is the quantised layer's own
+                own = oq["t_resident_ms"] + t_attn
+                line[key]["resident_ms_per_layer"] = oq["t_resident_ms"]
+                line[key]["overlap_own_compute"] = (t_c + own - t_p) / min(t_c, own)
             log(f"[bench] {key}: {line[key]}")
 
     if not args.no_c4:

@@ -94,18 +94,20 @@ typedef struct {
  *   stream of the library's own, each behind the copy it reads, so that the next copy does not wait for
  *   them; every call that fetched makes copy_stream wait for the last of them before it returns, so a
  *   synchronised copy_stream still means "the experts are in their slots".  Slots, matmuls and results
- *   are those of MOE_FMT_BF16 run on the expanded weights; the link carries a quarter of the bytes. */
+ *   are those of MOE_FMT_BF16 run on the expanded weights; the link carries a quarter of the bytes, HBM
+ *   holds the bf16 slots.  initial_resident names experts whose expanded bf16 blob is in the slot. */
 #define MOE_FMT_INT4_G128 2
 /* MOE_FMT_MXFP4: the OCP microscaling 4-bit format: e2m1 codes (bit 3 sign, bits 2..1 exponent, bit 0
  *   mantissa: 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte (even column in the low nibble); 32 consecutive
- *   values of a row share the scale 2^(s - 127), s one byte in 1..254; d and I multiples of 32.  Blob:
+ *   values of a row share the scale 2^(s - 127), s one byte in 1..254; d and I multiples of 64.  Blob:
  *   [scale bytes of [W_gate; W_up] (2I x d/32)][scale bytes of W_down (d x I/32)][padding to a multiple
  *   of 16][codes of [W_gate; W_up] (2I x d/2)][codes of W_down (d x I/2)].  weight = value(code) *
- *   2^(s - 127), exact in bf16.  Fetched and expanded like MOE_FMT_INT4_G128; the decode mat-vec kernels
- *   stream a fetched expert's 4-bit form from its staging area (a quarter of the HBM bytes) and expand
- *   it in registers with the hardware's scaled fp4 conversion when the experts are large enough for
- *   that to pay (16 M weights per matrix); otherwise, and for experts the caller placed with
- *   initial_resident, they read the bf16 slot. */
+ *   2^(s - 127), exact in bf16.  Held like MOE_FMT_E4M3_ROWS: the GPU expert cache is the blobs
+ *   themselves, one per slot, rounded up to 256 bytes (about a quarter of the bytes of bf16 on the link
+ *   and in HBM), a fetch is one copy, and every kernel reads the codes as they landed, expanding them
+ *   with the hardware's scaled fp4 conversion: the prefill GEMMs tile by tile on the way into LDS, the
+ *   decode mat-vecs in registers.  The results are those of MOE_FMT_BF16 run on the expanded weights.
+ *   initial_resident names experts whose MXFP4 blob the caller has put into the slot. */
 #define MOE_FMT_MXFP4 3
 
 /* Cache counters (host side).  hits/misses count active experts per layer call.
@@ -141,8 +143,9 @@ int moe_destroy(moe_ctx *ctx);
  * 3*d*I/2 (MXFP4). */
 size_t moe_host_blob_bytes(const moe_config *cfg);
 /* Bytes of one GPU expert cache (dev_slots of moe_bind_layer).  MOE_FMT_BF16: cache_slots slots of 6*d*I
- * bytes.  MOE_FMT_E4M3_ROWS: cache_slots slots of moe_host_blob_bytes rounded up to 256.  The 4-bit
- * formats: cache_slots bf16 slots followed by one staging area (the blob, rounded up to 256) per slot. */
+ * bytes.  MOE_FMT_E4M3_ROWS, MOE_FMT_MXFP4: cache_slots slots of moe_host_blob_bytes rounded up to 256.
+ * MOE_FMT_INT4_G128: cache_slots bf16 slots followed by one staging area (the blob, rounded up to 256)
+ * per slot. */
 size_t moe_cache_bytes(const moe_config *cfg);
 
 /* Bytes of device workspace a layer call on T tokens needs (256-byte aligned base). */

@@ -60,7 +60,6 @@ constexpr int kMaxSplitK = 4;
 struct ApiTune {
   int splitk = 0;            // K slices of the down GEMM, 0 = heuristic, at most kMaxSplitK
   int no_fused_down = 0;     // a one-token call runs the down mat-vec and the weighted sum as two launches
-  int no_q_matvec = 0;       // mat-vecs read the expanded bf16 slots even when a quantised copy exists
   int host_looks_always = 0; // a one-token decode call waits for the gate on the host like any other
   int matvec_max_rows = 0;   // largest group a decode call gives to the mat-vec launches, 0 = default
   int down_sched = 0;        // down GEMM: 0 = by shape, 1 = tiles of equal height in a fixed order, 2 = full +
@@ -183,8 +182,8 @@ constexpr int kMailboxWords = kMaxExperts + 1;
 struct moe_ctx {
   moe_config cfg{};
   int device = 0;
-  size_t blob_bytes = 0;        // one slot: the bf16 blob, 6*d*I; 0 where the cache keeps experts in their 8-bit form only
-  bool direct_q = false;        // MOE_FMT_E4M3_ROWS: every kernel reads the 8-bit blob as fetched; no bf16 slot, no expansion
+  size_t blob_bytes = 0;        // one slot: the bf16 blob, 6*d*I; 0 where the cache keeps experts in their quantised form only
+  bool direct_q = false;        // e4m3 rows, MXFP4: every kernel reads the blob as fetched; no bf16 slot, no expansion
   size_t host_blob_bytes = 0;   // one expert in the CPU expert cache (bf16: the same; e4m3: scales + codes)
   size_t stage_stride = 0;      // e4m3: bytes of one slot's staging area behind the slots (256-aligned)
   std::vector<Layer> layers;
@@ -238,8 +237,8 @@ int check_cfg(const moe_config *c) {
     return fail(MOE_E_ARG, "host_format = %d is not a known format", c->host_format);
   if (c->host_format == MOE_FMT_E4M3_ROWS && (c->d % 64 || c->I % 64))
     return fail(MOE_E_UNSUPPORTED, "MOE_FMT_E4M3_ROWS needs d and I to be multiples of 64");
-  if (c->host_format == MOE_FMT_MXFP4 && (c->d % 32 || c->I % 32))
-    return fail(MOE_E_UNSUPPORTED, "MOE_FMT_MXFP4 needs d and I to be multiples of 32");
+  if (c->host_format == MOE_FMT_MXFP4 && (c->d % 64 || c->I % 64))
+    return fail(MOE_E_UNSUPPORTED, "MOE_FMT_MXFP4 needs d and I to be multiples of 64");
   if (c->host_format == MOE_FMT_INT4_G128 && (c->d % 128 || c->I % 128))
     return fail(MOE_E_UNSUPPORTED, "MOE_FMT_INT4_G128 needs d and I to be multiples of 128");
   return MOE_OK;
@@ -424,9 +423,10 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
   L.set->prefetched[s] = 0;
   L.set->q_valid[s] = 0;
   if (c.host_format != MOE_FMT_BF16) {
-    // The quantised blob ([scales and zero points][gate codes][up codes][down codes]) lands in the
-    // slot's staging area on the copy stream; kernels on the expansion stream, each behind the copy
-    // it reads, write the slot.  copied_up / copied are recorded there, after the expansion.
+    // The quantised blob is [scales and zero points][gate codes][up codes][down codes].  e4m3 rows and
+    // MXFP4 stay as they are: the blob lands in the slot.  The 4-bit integer form lands in the slot's
+    // staging area on the copy stream; kernels on the expansion stream, each behind the copy it reads,
+    // write the bf16 slot, and copied_up / copied are recorded there, after the expansion.
     SlotSet &set = *L.set;
     hipStream_t xs = ctx->expand;
     char *stage = set.slots + (size_t)c.cache_slots * ctx->blob_bytes + (size_t)s * ctx->stage_stride;
@@ -444,27 +444,17 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
       up_codes = Id;
     }
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(stage + meta_bytes);
-    auto expand = [&](bool down) -> int {
-      if (c.host_format == MOE_FMT_E4M3_ROWS) {
-        return MOE_OK;   // (read as fetched; handled below)
-      } else if (c.host_format == MOE_FMT_MXFP4) {
-        const uint8_t *scales = reinterpret_cast<const uint8_t *>(stage);
-        if (!down) HIP_TRY(launch_dequant_mxfp4(codes, scales, 2 * c.I, c.d, w, xs));
-        else HIP_TRY(launch_dequant_mxfp4(codes + up_codes, scales + 2 * Id / 32, c.d, c.I, w + 2 * Id, xs));
-      } else {
-        const size_t n_up = 2 * Id / 128, n_dn = Id / 128;
-        const float *scales = reinterpret_cast<const float *>(stage);
-        const uint8_t *zeros = reinterpret_cast<const uint8_t *>(stage + 4 * (n_up + n_dn));
-        if (!down) HIP_TRY(launch_dequant_int4_g128(codes, scales, zeros, 2 * c.I, c.d, w, xs));
-        else HIP_TRY(launch_dequant_int4_g128(codes + up_codes, scales + n_up, zeros + n_up, c.d, c.I, w + 2 * Id, xs));
-      }
+    auto expand = [&](bool down) -> int {   // MOE_FMT_INT4_G128
+      const size_t n_up = 2 * Id / 128, n_dn = Id / 128;
+      const float *scales = reinterpret_cast<const float *>(stage);
+      const uint8_t *zeros = reinterpret_cast<const uint8_t *>(stage + 4 * (n_up + n_dn));
+      if (!down) HIP_TRY(launch_dequant_int4_g128(codes, scales, zeros, 2 * c.I, c.d, w, xs));
+      else HIP_TRY(launch_dequant_int4_g128(codes + up_codes, scales + n_up, zeros + n_up, c.d, c.I, w + 2 * Id, xs));
       return MOE_OK;
     };
     if (ctx->direct_q) {
-      // The cache holds the 8-bit blob and nothing else: one copy (or two, split behind the gate / up
+      // The cache holds the quantised blob and nothing else: one copy (or two, split behind the gate / up
       // codes), and "landed" is "ready" for every kernel.
-      (void)codes;
-      (void)w;
       if (split) {
         HIP_TRY(hipMemcpyAsync(stage, src, meta_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
         HIP_TRY(hipEventRecord(set.landed_up[s], copy_stream));
@@ -512,8 +502,7 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     HIP_TRY(hipMemcpyAsync(dst, src, ctx->blob_bytes, hipMemcpyHostToDevice, copy_stream));
   }
   if (c.host_format == MOE_FMT_BF16) HIP_TRY(hipEventRecord(L.set->copied[s], copy_stream));
-  // forms the mat-vec kernels read straight from the staging area
-  L.set->q_valid[s] = c.host_format == MOE_FMT_E4M3_ROWS || c.host_format == MOE_FMT_MXFP4;
+  L.set->q_valid[s] = ctx->direct_q;   // forms every kernel reads as fetched
   L.set->slot_expert[s] = e;
   L.set->slot_layer[s] = L.index;
   L.expert_slot[e] = s;
@@ -566,8 +555,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
   a.splitk = 1;
   a.tune = ctx->tune;
   if (c.host_format == MOE_FMT_E4M3_ROWS) {
-    // the mat-vec kernels stream the 8-bit copy that a fetch left in the slot's staging area (half
-    // the bytes; the same weight values as the expanded slot)
+    // every kernel reads the 8-bit blob as the slot holds it: [row scales][gate | up | down codes]
     const long long scale_bytes = (long long)4 * (2 * c.I + c.d), Id = (long long)c.I * c.d;
     a.qfmt = 1;
     a.qbase = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes;
@@ -577,9 +565,8 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
     a.q_s0_off = second ? (long long)4 * 2 * c.I : 0;
     a.q_s1_off = second ? (long long)4 * 2 * c.I : (long long)4 * c.I;
     a.b_quant = 1;        // the GEMM kernels expand the codes on their way into LDS
-    a.tune.q_always = 1;  // and the mat-vecs read them whatever the experts' size: there is no bf16 slot
-  } else if (c.host_format == MOE_FMT_MXFP4 && !ctx->api_tune.no_q_matvec) {
-    // likewise the MXFP4 copy (a quarter of the bytes): codes K/2 bytes per row, scales K/32
+  } else if (c.host_format == MOE_FMT_MXFP4) {
+    // likewise the MXFP4 blob (a quarter of the bytes): [scale bytes, K/32 per row][codes, K/2 bytes per row]
     const long long Id = (long long)c.I * c.d, meta = (3 * Id / 32 + 15) / 16 * 16;
     a.qfmt = 2;
     a.qbase = L.set->slots + (size_t)c.cache_slots * ctx->blob_bytes;
@@ -588,6 +575,7 @@ GemmArgs routed_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
     a.q_b1_off = meta + (second ? Id : Id / 2);
     a.q_s0_off = second ? 2 * Id / 32 : 0;
     a.q_s1_off = second ? 2 * Id / 32 : Id / 32;
+    a.b_quant = 1;
   }
   if (a.qbase)
     for (int e = 0; e < c.E; ++e)
@@ -1090,7 +1078,7 @@ int moe_create(const moe_config *cfg, moe_ctx **out) {
   moe_ctx *ctx = new (std::nothrow) moe_ctx();
   if (!ctx) return fail(MOE_E_ARG, "out of host memory");
   ctx->cfg = *cfg;
-  ctx->direct_q = cfg->host_format == MOE_FMT_E4M3_ROWS;
+  ctx->direct_q = cfg->host_format == MOE_FMT_E4M3_ROWS || cfg->host_format == MOE_FMT_MXFP4;
   ctx->blob_bytes = ctx->direct_q ? 0 : (size_t)6 * cfg->d * cfg->I;
   ctx->host_blob_bytes = moe_host_blob_bytes(cfg);
   ctx->stage_stride = cfg->host_format != MOE_FMT_BF16 ? (ctx->host_blob_bytes + 255) / 256 * 256 : 0;
@@ -1152,7 +1140,7 @@ size_t moe_host_blob_bytes(const moe_config *cfg) {
 
 size_t moe_cache_bytes(const moe_config *cfg) {
   if (check_cfg(cfg)) return 0;
-  const size_t slot = cfg->host_format == MOE_FMT_E4M3_ROWS ? 0 : (size_t)6 * cfg->d * cfg->I;
+  const size_t slot = cfg->host_format == MOE_FMT_E4M3_ROWS || cfg->host_format == MOE_FMT_MXFP4 ? 0 : (size_t)6 * cfg->d * cfg->I;
   const size_t stage = cfg->host_format != MOE_FMT_BF16 ? (moe_host_blob_bytes(cfg) + 255) / 256 * 256 : 0;
   return (size_t)cfg->cache_slots * (slot + stage);
 }
@@ -1601,11 +1589,7 @@ int moe_tune(moe_ctx *ctx, int mode, int variant) {
       ctx->tune.skinny_forced = variant == 1;   // 1: every launch with a token or more, whatever the format
       return MOE_OK;
     case 7: ctx->api_tune.no_fused_down = variant != 0; return MOE_OK;
-    case 6:
-      if (variant > 2) return fail(MOE_E_ARG, "mat-vec source: 0 (by expert size), 1 (never the copy) or 2 (always)");
-      ctx->api_tune.no_q_matvec = variant == 1;
-      ctx->tune.q_always = variant == 2;
-      return MOE_OK;
+    case 6: return fail(MOE_E_ARG, "mode 6 is not in use");
     case 5: ctx->api_tune.host_looks_always = variant == 0; return MOE_OK;
     case 4:
       if (variant != 0 && variant != 1 && variant != 2 && variant != 4)

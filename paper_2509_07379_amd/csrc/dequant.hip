@@ -1,7 +1,7 @@
-// Expansion of 4-bit expert weights (unsigned integers in groups of 128 with scale and zero point;
-// MXFP4) into the bf16 matrices the GPU expert cache holds for those formats.  The paper evaluates
-// quantised models (Section VI); a fetched 4-bit expert lands in a staging area next to the cache and
-// one of these kernels writes its slot, so the GEMM kernels read bf16.  (8-bit experts are never
+// Expansion of 4-bit integer expert weights (unsigned codes in groups of 128 with scale and zero point)
+// into the bf16 matrices the GPU expert cache holds for that format.  The paper evaluates quantised
+// models (Section VI); a fetched expert of this form lands in a staging area next to the cache and the
+// kernel below writes its slot, so the GEMM kernels read bf16.  (e4m3 and MXFP4 experts are never
 // expanded in memory: every kernel reads their codes.)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -48,57 +48,7 @@ __global__ __launch_bounds__(kThreads) void dequant_int4_g128_kernel(const uint8
   }
 }
 
-// MXFP4: e2m1 codes (two per byte, even column in the low nibble), blocks of 32 along a row share the
-// scale 2^(s - 127), s one byte:  out = value(code) * 2^(s - 127), exact in bf16 (1 <= s <= 254).
-// One lane expands 16 codes (one 8-byte load, two 16-byte stores); cols % 32 == 0.
-__global__ __launch_bounds__(kThreads) void dequant_mxfp4_kernel(const uint8_t *__restrict__ codes,
-                                                                 const uint8_t *__restrict__ scales,
-                                                                 long long rows, int cols,
-                                                                 uint16_t *__restrict__ out) {
-  const int per_row = cols >> 4;          // 16-code pieces per row
-  const int blocks = cols >> 5;
-  const long long pieces = rows * per_row;
-  for (long long c = (long long)blockIdx.x * kThreads + threadIdx.x; c < pieces;
-       c += (long long)gridDim.x * kThreads) {
-    const long long row = c / per_row;
-    const int piece = (int)(c - row * per_row);
-    const float s = __uint_as_float((uint32_t)scales[row * blocks + (piece >> 1)] << 23);
-    const uint2 q = *reinterpret_cast<const uint2 *>(codes + c * 8);
-    uint32_t w[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t byte = ((j < 4 ? q.x : q.y) >> ((j & 3) * 8)) & 0xFFu;
-      uint32_t pair = 0;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const uint32_t code = h ? (byte >> 4) : (byte & 15u);
-        const uint32_t e = (code >> 1) & 3u, m = code & 1u;
-        // e = 0: m / 2;  e > 0: 2^(e - 1) * (1 + m / 2), as fp32 bits; the sign is bit 3
-        const float mag = e == 0 ? 0.5f * (float)m : __uint_as_float(((126u + e) << 23) | (m << 22));
-        const float v = __uint_as_float(__float_as_uint(mag * s) | ((code & 8u) << 28));
-        pair |= (uint32_t)f32_to_bf16(v) << (16 * h);
-      }
-      w[j] = pair;
-    }
-    uint4 *dst = reinterpret_cast<uint4 *>(out + c * 16);
-    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-  }
-}
-
 }  // namespace
-
-hipError_t launch_dequant_mxfp4(const uint8_t *codes, const uint8_t *scales, long long rows, int cols,
-                                uint16_t *out, hipStream_t stream) {
-  if (rows <= 0 || cols <= 0) return hipSuccess;
-  if (cols % 32) return hipErrorInvalidValue;
-  const long long pieces = rows * (cols >> 4);
-  long long blocks = (pieces + kThreads - 1) / kThreads;
-  if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(dequant_mxfp4_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, codes, scales, rows,
-                     cols, out);
-  return hipGetLastError();
-}
 
 hipError_t launch_dequant_int4_g128(const uint8_t *codes, const float *scales, const uint8_t *zeros,
                                     long long rows, int cols, uint16_t *out, hipStream_t stream) {

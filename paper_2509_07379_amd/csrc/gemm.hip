@@ -505,14 +505,18 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_dma_kerne
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same tile loop on 8-bit experts (MOE_FMT_E4M3_ROWS): the B operand is e4m3 codes with one fp32
-// scale per B row, read from the expert's blob as it came over the host link.  A tile of codes is
-// 64 bytes per row and K step; every lane fetches 16-byte pieces of it into registers one K step
-// ahead, expands them to the bf16 weights bf16_rne(value(code) * scale[row]) (the hardware's e4m3 ->
-// fp32 conversion, one multiply, the hardware's fp32 -> bf16 rounding: the value the format defines,
-// so the products are those of a GEMM on expanded weights) and writes them into the swizzled LDS tile
-// the MFMAs read.  A keeps its direct global -> LDS loads.  The expansion costs some 70 vector
-// instructions per lane and K step, issued while the other waves' MFMAs run.  Needs K % 64 == 0.
+// The same tile loop on quantised experts: the B operand is read from the expert's blob as it came over
+// the host link.  Every lane fetches 16-byte pieces of the code tile into registers one K step ahead,
+// expands them to bf16 weights and writes them into the swizzled LDS tile the MFMAs read; A keeps its
+// direct global -> LDS loads.  The expansion is issued while the other waves' MFMAs run.
+//   QF = 1 (MOE_FMT_E4M3_ROWS): e4m3 codes, one fp32 scale per B row, 64 bytes per row and K step.  The
+//     weight is bf16_rne(value(code) * scale[row]) (the hardware's e4m3 -> fp32 conversion, one multiply,
+//     the hardware's fp32 -> bf16 rounding), some 70 vector instructions per lane and K step.
+//   QF = 2 (MOE_FMT_MXFP4): e2m1 codes, two per byte, one power-of-two scale byte per 32 codes: 32 bytes
+//     of codes and 2 scale bytes per row and K step.  A lane's piece is one scale block; the hardware
+//     conversion takes a byte of two codes and the scale and returns the exact bf16 pair.
+// Either way the weights are the values the format defines, so the products are those of a GEMM on
+// expanded weights.  Needs K % 64 == 0.
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 typedef float f32x2v __attribute__((ext_vector_type(2)));
 
@@ -526,7 +530,17 @@ __device__ __forceinline__ u32x4 expand8_e4m3(uint32_t c0, uint32_t c1, float sc
                __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2v))};
 }
 
-template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
+__device__ __forceinline__ u32x4 expand8_mxfp4(uint32_t word, float scale) {
+  typedef __bf16 pair_t __attribute__((ext_vector_type(2)));
+  const pair_t p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 0);
+  const pair_t p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 1);
+  const pair_t p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 2);
+  const pair_t p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, 3);
+  return u32x4{__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1), __builtin_bit_cast(uint32_t, p2),
+               __builtin_bit_cast(uint32_t, p3)};
+}
+
+template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE, int QF>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel(const GemmArgs args) {
   constexpr int NW = WARPS_M * WARPS_N;
   constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
@@ -535,8 +549,12 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
   constexpr int STAGE = (BM + BN) * ROW_BYTES;
   constexpr int GPA = BM / 8 / NW;    // wave-wide A loads per wave and stage (8 tile rows each)
-  constexpr int NQ = BN / 16 / NW;    // 16-byte pieces of codes per lane and stage (a wave-wide load = 16 B rows)
-  static_assert(BM % (8 * NW) == 0 && BN % (16 * NW) == 0, "load split mismatch");
+  // 16-byte pieces of codes per lane and stage: a wave-wide load covers 16 B rows of e4m3 codes (4 lanes
+  // per row) or 32 of MXFP4 codes (2 lanes per row); a piece expands to ND 16-byte chunks of the LDS row
+  constexpr int RPL = QF == 2 ? 32 : 16, ND = QF == 2 ? 4 : 2, QSTEP = QF == 2 ? BK / 2 : BK;
+  constexpr int NQ = BN / RPL / NW;
+  static_assert(QF == 1 || QF == 2, "formats: 1 = e4m3 rows, 2 = MXFP4");
+  static_assert(BM % (8 * NW) == 0 && BN % (RPL * NW) == 0, "load split mismatch");
   static_assert(FM <= 4, "fragment-count dispatch covers up to 4 row fragments per wave");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -564,24 +582,33 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel
     const long long srow = args.perm ? (long long)(args.perm[p] / args.k_top) : (long long)p;
     a_src[i] = args.A + srow * args.lda + kc * 8;
   }
-  // B: piece i of this lane is 16 codes of tile row 16 (i NW + wave) + l/4, columns 16 (l%4) .. +15 of the
-  // K step; expanded they are the row's bf16 chunks 2 (l%4) and 2 (l%4) + 1
+  // B, e4m3: piece i of this lane is 16 codes of tile row 16 (i NW + wave) + l/4, columns 16 (l%4) .. +15 of
+  // the K step; expanded they are the row's bf16 chunks 2 (l%4) and 2 (l%4) + 1.  MXFP4: 32 codes of tile row
+  // 32 (i NW + wave) + l/2, columns 32 (l%2) .. +31, with the scale byte of that block; chunks 4 (l%2) .. +3.
   const uint8_t *q_src[NQ];
-  float q_scale[NQ];
-  int q_dst[NQ][2];
+  const uint8_t *sc_src[NQ];   // MXFP4: this piece's scale byte in K step 0
+  float q_scale[NQ];           // e4m3: the row's scale
+  int q_dst[NQ][ND];
 #pragma unroll
   for (int i = 0; i < NQ; ++i) {
-    const int r = (i * NW + wave) * 16 + (lane >> 2);
-    const int c4 = lane & 3;
+    const int r = (i * NW + wave) * RPL + (QF == 2 ? lane >> 1 : lane >> 2);
+    const int piece = QF == 2 ? lane & 1 : lane & 3;
     long long codes_off = args.q_b0_off, scale_off = args.q_s0_off;
     int rr = r;
     if (MODE == GEMM_SWIGLU && r >= BN / 2) { codes_off = args.q_b1_off; scale_off = args.q_s1_off; rr = r - BN / 2; }
     int n = t.n0 + rr;
     if (n >= args.N) n = args.N - 1;
-    q_src[i] = reinterpret_cast<const uint8_t *>(qptr + codes_off) + (long long)n * args.K + c4 * 16;
-    q_scale[i] = reinterpret_cast<const float *>(qptr + scale_off)[n];
-    q_dst[i][0] = BM * ROW_BYTES + swz(r, 2 * c4);
-    q_dst[i][1] = BM * ROW_BYTES + swz(r, 2 * c4 + 1);
+    if constexpr (QF == 2) {
+      q_src[i] = reinterpret_cast<const uint8_t *>(qptr + codes_off) + (long long)n * (args.K / 2) + piece * 16;
+      sc_src[i] = reinterpret_cast<const uint8_t *>(qptr + scale_off) + (long long)n * (args.K / 32) + piece;
+      q_scale[i] = 0.0f;
+    } else {
+      q_src[i] = reinterpret_cast<const uint8_t *>(qptr + codes_off) + (long long)n * args.K + piece * 16;
+      sc_src[i] = nullptr;
+      q_scale[i] = reinterpret_cast<const float *>(qptr + scale_off)[n];
+    }
+#pragma unroll
+    for (int j = 0; j < ND; ++j) q_dst[i][j] = BM * ROW_BYTES + swz(r, ND * piece + j);
   }
 
   int fm_valid = 0;
@@ -608,7 +635,8 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel
       b_off[j] = (j * WARPS_N + wn) * 32 + lrow;
   }
 
-  u32x4 cq[NQ];   // codes of the K step after the one in LDS
+  u32x4 cq[NQ];      // codes of the K step after the one in LDS
+  uint32_t csc[NQ];  // MXFP4: and their scale bytes
 #define MOE_Q_LOADA(kt_, stage_)                                                                     \
   do {                                                                                               \
     _Pragma("unroll") for (int i_ = 0; i_ < GPA; ++i_)                                               \
@@ -618,15 +646,26 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel
   } while (0)
 #define MOE_Q_LOADQ(kt_)                                                                             \
   do {                                                                                               \
-    _Pragma("unroll") for (int i_ = 0; i_ < NQ; ++i_)                                                \
-      cq[i_] = *reinterpret_cast<const u32x4 *>(q_src[i_] + (long long)(kt_) * BK);                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < NQ; ++i_) {                                              \
+      cq[i_] = *reinterpret_cast<const u32x4 *>(q_src[i_] + (long long)(kt_) * QSTEP);               \
+      if constexpr (QF == 2) csc[i_] = sc_src[i_][(long long)(kt_) * (BK / 32)];                     \
+    }                                                                                                \
   } while (0)
 #define MOE_Q_EXPAND(stage_)                                                                         \
   do {                                                                                               \
     _Pragma("unroll") for (int i_ = 0; i_ < NQ; ++i_) {                                              \
       const u32x4 c_ = cq[i_];                                                                       \
-      *reinterpret_cast<u32x4 *>(smem + (stage_) * STAGE + q_dst[i_][0]) = expand8_e4m3(c_.x, c_.y, q_scale[i_]); \
-      *reinterpret_cast<u32x4 *>(smem + (stage_) * STAGE + q_dst[i_][1]) = expand8_e4m3(c_.z, c_.w, q_scale[i_]); \
+      unsigned char *st_ = smem + (stage_) * STAGE;                                                  \
+      if constexpr (QF == 2) {                                                                       \
+        const float f_ = __uint_as_float(csc[i_] << 23);                                             \
+        *reinterpret_cast<u32x4 *>(st_ + q_dst[i_][0]) = expand8_mxfp4(c_.x, f_);                    \
+        *reinterpret_cast<u32x4 *>(st_ + q_dst[i_][1]) = expand8_mxfp4(c_.y, f_);                    \
+        *reinterpret_cast<u32x4 *>(st_ + q_dst[i_][ND - 2]) = expand8_mxfp4(c_.z, f_);               \
+        *reinterpret_cast<u32x4 *>(st_ + q_dst[i_][ND - 1]) = expand8_mxfp4(c_.w, f_);               \
+      } else {                                                                                       \
+        *reinterpret_cast<u32x4 *>(st_ + q_dst[i_][0]) = expand8_e4m3(c_.x, c_.y, q_scale[i_]);      \
+        *reinterpret_cast<u32x4 *>(st_ + q_dst[i_][1]) = expand8_e4m3(c_.z, c_.w, q_scale[i_]);      \
+      }                                                                                              \
     }                                                                                                \
   } while (0)
 #define MOE_Q_MMA(FMV, stage_)                                                                       \
@@ -1340,12 +1379,12 @@ hipError_t launch_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, 
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE>
+template <int BM, int BN, int WARPS_M, int WARPS_N, int MODE, int QF>
 hipError_t launch_q8_cfg(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
   constexpr int NTHR = 64 * WARPS_M * WARPS_N;
   constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES;
-  auto kern = grouped_gemm_q8_kernel<BM, BN, WARPS_M, WARPS_N, MODE>;
+  auto kern = grouped_gemm_q8_kernel<BM, BN, WARPS_M, WARPS_N, MODE, QF>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1457,13 +1496,17 @@ int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.b_quant) {
-    // 8-bit experts: the kernel that expands the codes on their way into LDS, with the tile size by the
+    // quantised experts: the kernel that expands the codes on their way into LDS, with the tile size by the
     // groups' average height
-    if (MODE == GEMM_PLAIN_BF16 || args.qfmt != 1 || !args.qbase || args.K % BK != 0) return hipErrorInvalidValue;
+    if (MODE == GEMM_PLAIN_BF16 || (args.qfmt != 1 && args.qfmt != 2) || !args.qbase || args.K % BK != 0)
+      return hipErrorInvalidValue;
     const long long avg_rows = n_groups_in_mask > 0 ? (long long)max_rows / n_groups_in_mask : max_rows;
-    if (avg_rows > 96 && args.tune.gemm_variant[MODE] != 1)
-      return launch_q8_cfg<256, 256, 2, 4, MODE>(args, max_rows, n_groups_in_mask, stream);
-    return launch_q8_cfg<128, 128, 2, 2, MODE>(args, max_rows, n_groups_in_mask, stream);
+    const bool big = avg_rows > 96 && args.tune.gemm_variant[MODE] != 1;
+    if (args.qfmt == 2)
+      return big ? launch_q8_cfg<256, 256, 2, 4, MODE, 2>(args, max_rows, n_groups_in_mask, stream)
+                 : launch_q8_cfg<128, 128, 2, 2, MODE, 2>(args, max_rows, n_groups_in_mask, stream);
+    return big ? launch_q8_cfg<256, 256, 2, 4, MODE, 1>(args, max_rows, n_groups_in_mask, stream)
+               : launch_q8_cfg<128, 128, 2, 2, MODE, 1>(args, max_rows, n_groups_in_mask, stream);
   }
   switch (gemm_kernel_choice((GemmMode)MODE, args, max_rows, n_groups_in_mask)) {
     case 100: return launch_ktail<MODE>(args, max_rows, n_groups_in_mask, stream);

@@ -738,13 +738,10 @@ void grouped_skinny_kernel(const GemmArgs routed, const GemmArgs extra,
 
 }  // namespace
 
-// 8-bit and 4-bit copies pay where the launch is bound by the bytes it streams: experts of 16 M weights
-// per matrix and more (Mixtral-sized: 1.4 to 2 times faster at 1 to 8 tokens).  Small experts
-// (Qwen-sized, 3 M) are bound by the launch itself at 1 or 2 tokens and by arithmetic above; there
-// the expansion only adds instructions.
+// Quantised experts (e4m3 rows, MXFP4) exist in the cache in that form only: every mat-vec reads the
+// codes and expands them in registers.
 bool gemv_reads_copies(const GemmArgs &args) {
-  return args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0 &&
-         ((long long)args.N * args.K >= (1ll << 24) || args.tune.q_always);
+  return args.qbase != nullptr && args.K % (args.qfmt == 2 ? 32 : 16) == 0;
 }
 
 // One token (its row in the sorted order is offsets[expert]), args = the down projection's arguments

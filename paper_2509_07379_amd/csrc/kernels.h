@@ -38,10 +38,6 @@ hipError_t launch_mlp_predictor(const float *state, const int32_t *dims, int n_f
 // two codes per byte, even column in the low nibble; cols % 128 == 0.
 hipError_t launch_dequant_int4_g128(const uint8_t *codes, const float *scales, const uint8_t *zeros,
                                     long long rows, int cols, uint16_t *out, hipStream_t stream);
-// MXFP4 expert weights -> bf16: out[r, c] = value_e2m1(code[r, c]) * 2^(scales[r, c/32] - 127), exact;
-// two codes per byte, even column in the low nibble; cols % 32 == 0.
-hipError_t launch_dequant_mxfp4(const uint8_t *codes, const uint8_t *scales, long long rows, int cols,
-                                uint16_t *out, hipStream_t stream);
 hipError_t launch_predictor(const uint16_t *x, const uint16_t *wp, int T, int d, int E, int m,
                             float *scores, int32_t *top_out, hipStream_t stream);
 
@@ -66,7 +62,6 @@ struct Tune {
   int skinny_min_tok;    // tokens per expert from which the matrix-core mat-vec is used (0 = by rule)
   int skinny_forced;     // the matrix-core mat-vec wherever the shapes allow it
   int skinny_waves;      // K slices (waves) per block of the matrix-core mat-vec (0 = by shape)
-  int q_always;          // mat-vecs read quantised copies whatever the experts' size
 };
 
 // Work plan of one grouped launch of the persistent GEMM, computed on the device from the groups'
@@ -115,15 +110,14 @@ struct GemmArgs {
                           // with rows, as the plan does); otherwise they are dealt out in a fixed order
   long long out_split_stride;  // elements between planes
   int spare_cus;          // persistent GEMM: compute units to leave to kernels of other streams
-  // Mat-vec kernels only: 8-bit copies of the same weights (e4m3 codes, one fp32 scale per B row).
-  // Expert e with bit e of q8_mask set is streamed from qbase + slot[e] * qstride instead of its bf16
-  // blob: codes of the B rows at q_b0_off / q_b1_off (K bytes per row), their scales at q_s0_off /
-  // q_s1_off.  The weight used is bf16_rne(value(code) * scale), the bf16 blob's value.  K % 16 == 0.
-  // qfmt 2: MXFP4 copies instead (e2m1 codes, two per byte, K / 2 bytes per row at q_b*_off; one scale
+  // Quantised experts.  Expert e with bit e of q8_mask set is read from qbase + slot[e] * qstride, not
+  // from a bf16 blob.  qfmt 1: e4m3 codes of the B rows at q_b0_off / q_b1_off (K bytes per row), one
+  // fp32 scale per B row at q_s0_off / q_s1_off; the weight used is bf16_rne(value(code) * scale).
+  // K % 16 == 0.  qfmt 2: MXFP4 (e2m1 codes, two per byte, K / 2 bytes per row at q_b*_off; one scale
   // byte per 32 columns, K / 32 bytes per row at q_s*_off; weight = value(code) * 2^(scale - 127), exact
-  // in bf16).  K % 32 == 0.
+  // in bf16).  K % 32 == 0.  The mat-vec kernels go by the mask; the GEMM kernels by b_quant.
   int qfmt;               // 0 none, 1 e4m3 with row scales, 2 MXFP4
-  int b_quant;            // GEMM kernels: every expert's B operand is its e4m3 copy at qbase (there is no bf16 blob)
+  int b_quant;            // GEMM kernels: every expert's B operand is its quantised blob at qbase (K % 64 == 0)
   unsigned long long q8_mask;
   const char *qbase;
   long long qstride;
@@ -173,8 +167,8 @@ hipError_t launch_grouped_gemv(GemmMode mode, const GemmArgs &args, int max_rows
 // launch_combine.  Requires K * 2 <= 64 KB for both problems.
 hipError_t launch_fused_down_combine(const GemmArgs &args, const float *gate_w, int k_top, uint16_t *out,
                                      hipStream_t stream, const GemmArgs *extra = nullptr);
-// Whether launch_grouped_gemv streams quantised copies for the experts of args.q8_mask (format,
-// alignment, expert size or the test hook), whatever the mask and the token count.
+// Whether launch_grouped_gemv reads the quantised blobs of the experts of args.q8_mask (a format is set
+// and K fits its pieces), whatever the mask and the token count.
 bool gemv_reads_copies(const GemmArgs &args);
 
 // ---- combine: out[t] = sum_j w[t,j] * Y[inv_perm[t*k+j]] (+ shared), fixed order, bf16 out ----

@@ -12,9 +12,7 @@
  *   mode 5          0: a one-token decode call with every expert resident waits for the gate's
  *                   result on the host like any other call; non-zero (default): it is enqueued at
  *                   once and the mat-vec launches take the k experts from the gate's id list
- *   mode 6          what the decode mat-vec kernels read where a quantised copy of an expert
- *                   exists: 0 = the copy if the experts are large enough for it to pay, 1 = always
- *                   the expanded bf16 slot, 2 = always the copy
+ *   mode 6          (not in use)
  *   mode 7          1: a one-token all-resident decode call runs the down mat-vec and the weighted
  *                   sum as two launches instead of one (the same bits either way)
  *   mode 8          tokens per expert from which a mat-vec launch may use the matrix-core kernel:

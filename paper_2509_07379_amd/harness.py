@@ -76,16 +76,17 @@ class DeviceLayer:
         self.shared_np = S.shared_blob(w, layer)
         self.shared = np_to_dev(self.shared_np, device) if self.shared_np is not None else None
         own = slots is None
-        # the cache: Sslots slots of one bf16 blob each and then (4-bit host formats) one staging area per
-        # slot; for an e4m3 pool the slots hold the 8-bit blobs themselves (each rounded up to 256 bytes)
+        # the cache: Sslots slots of one bf16 blob each and then (4-bit integer host format) one staging area
+        # per slot; for an e4m3 or MXFP4 pool the slots hold the quantised blobs themselves (each rounded up
+        # to 256 bytes)
         self.cache = torch.empty(ctx.moe_cache_bytes() // 2, dtype=torch.int16, device=device) if own else slots
-        direct = pool.fmt == 1
+        direct = pool.fmt in (1, 3)
         self.slot_bytes = (pool.bytes_per_expert + 255) // 256 * 256 if direct else w.blob_bytes
         self.slots = self.cache.view(-1)[:Sslots * self.slot_bytes // 2].view(Sslots, self.slot_bytes // 2)
         if poison and own:
             self.cache.fill_(0x7FC0)  # bf16 NaN pattern (0xC0 0x7F as e4m3 codes: -2 and NaN): an unfilled slot shows up
         if initial is not None:
-            assert pool.fmt in (0, 1), "initial residents are blobs in the form the slots hold"
+            assert pool.fmt in (0, 1, 3), "initial residents are blobs in the form the slots hold"
             for s, e in enumerate(initial):
                 if e >= 0:
                     self.slots[s].view(torch.uint8)[:pool.bytes_per_expert].copy_(pool.buf[e], non_blocking=False)

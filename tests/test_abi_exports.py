@@ -121,11 +121,12 @@ def test_blob_and_cache_sizes_per_host_format():
         cfg = binding.MoeConfig(d, I, 8, 2, 1, slots, 0, 1, 0, fmt)
         assert lib.moe_host_blob_bytes(C.byref(cfg)) == want
         stage = 0 if fmt == 0 else (want + 255) // 256 * 256
-        bf16_slot = 0 if fmt == 1 else 6 * d * I      # an e4m3 cache holds the 8-bit blobs and nothing else
+        bf16_slot = 0 if fmt in (1, 3) else 6 * d * I      # an e4m3 or MXFP4 cache holds the quantised blobs and nothing else
         assert lib.moe_cache_bytes(C.byref(cfg)) == slots * (bf16_slot + stage)
     assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(d, I, 8, 2, 1, slots, 0, 1, 0, 4))) == 0
     assert b"not a known format" in lib.moe_last_error()
     assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(264, I, 8, 2, 1, slots, 0, 1, 0, 2))) == 0
     assert b"multiples of 128" in lib.moe_last_error()
-    assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(d, 136, 8, 2, 1, slots, 0, 1, 0, 1))) == 0
-    assert b"multiples of 64" in lib.moe_last_error()
+    for fmt in (1, 3):
+        assert lib.moe_host_blob_bytes(C.byref(binding.MoeConfig(d, 136, 8, 2, 1, slots, 0, 1, 0, fmt))) == 0
+        assert b"multiples of 64" in lib.moe_last_error()

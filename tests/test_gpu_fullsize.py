@@ -198,9 +198,9 @@ def test_c5_qwen_decode_steps(gpu, oracle):
 @pytest.mark.parametrize("fmt", [1, 3])
 def test_c2_shape_quantised_host_pool(gpu, oracle, fmt):
     """The Mixtral-shaped layer served from an 8-bit (e4m3 rows) or MXFP4 CPU expert cache at full size:
-    prefill through two slots (every expert fetched and used once; the e4m3 GEMMs read the codes as
-    fetched, MXFP4 experts are expanded into bf16 slots), then decode on resident experts, where the
-    mat-vec kernels stream the quantised form.  Outputs on sampled tokens against the oracle run on its
+    prefill through two slots (every expert fetched and used once; the GEMMs read the codes as fetched
+    and expand tiles on their way into LDS), then decode on resident experts, where the mat-vec kernels
+    stream the same blobs.  Outputs on sampled tokens against the oracle run on its
     own expansion of the same blobs."""
     H, B = gpu["harness"], gpu["binding"]
     w = S.WORKLOADS["c2_mixtral_prefill"]
@@ -229,9 +229,6 @@ def test_c2_shape_quantised_host_pool(gpu, oracle, fmt):
     ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, 0, True, host_format=fmt)
     lay = H.DeviceLayer(ctx, w, 0, pool, None, poison=True)
     ctx.expert_cache_prefetch(0, list(range(w.E)), gpu["copy"])
-    torch.cuda.synchronize()
-    if fmt != 1:                     # MXFP4: decode must not need the bf16 slots (an e4m3 pool has none)
-        lay.slots.fill_(0x7FC0)
     torch.cuda.synchronize()
     for T in (1, 4, 8, 24):    # 8 and 24: groups of several tokens, the matrix-core mat-vec on the copies
         buf = H.Buffers(ctx, T)

@@ -40,7 +40,8 @@ def gpu():
 CASES = [("slots_per_layer", 16, 2, 0, 5, False, 0, 48),
          ("one_cache", 16, 2, 0, 6, True, 0, 48),
          ("all_resident_many_experts", 60, 4, 128, 60, False, 0, 36),   # calls are only enqueued
-         ("eight_bit_experts", 16, 4, 64, 7, False, 1, 36)]
+         ("eight_bit_experts", 16, 4, 64, 7, False, 1, 36),
+         ("mxfp4_experts_one_cache", 16, 2, 64, 4, True, 3, 36)]
 
 
 @pytest.mark.parametrize("name,E,k,Ish,slots,shared,fmt,n_calls", CASES)
