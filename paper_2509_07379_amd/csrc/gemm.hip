@@ -858,7 +858,15 @@ __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileIn
 //   M1(H): group 0 the lower A rows, group 1 the upper A rows of stage H+1
 // Loads move whole 128-byte lines (8 tile rows per wave-wide load): half lines would halve the L1
 // fill rate.  Needs K % 64 == 0.
-template <int MODE>
+// QF = 2: the B operand is the experts' MXFP4 blobs (GemmArgs::qbase).  A stage's B tile is then 256 rows of
+// 32 bytes of codes plus 4 scale bytes per row, all brought in by 4-byte direct loads: four wave-wide loads of
+// codes per wave (a load is 8 rows of 8 dwords; the dword that lands at position p of row r is dword
+// p ^ 2 ((r >> 3) & 3) of the row's K step, which spreads the 32 rows of a fragment read over all banks) and
+// one of scales (lanes 0..31: the aligned dword that holds the row's two scale bytes of this K step and of its
+// neighbour).  A lane builds its B fragment of K slice ks from one dword of codes with the hardware's scaled
+// fp4 conversion (exact), so the MFMAs see the weights the format defines.  Short row tiles run through the
+// same loop.  Needs K % 128 == 0 and the blob within 31 bits of byte offset.
+template <int MODE, int QF = 0>
 __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs args) {
   constexpr int BM = 256, BN = 256, WARPS_M = 2, WARPS_N = 4;
   constexpr int BN_OUT = (MODE == GEMM_SWIGLU) ? BN / 2 : BN;
@@ -866,6 +874,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
   constexpr int STAGE = (BM + BN) * ROW_BYTES;   // 64 KB
   constexpr int NL = 4;                          // wave-wide loads per wave and M tick
+  constexpr int NB = QF == 2 ? NL + 1 : NL;      // ... of a B stage (MXFP4: the codes and one load of scales)
+  constexpr int QCODES = BM * ROW_BYTES;         // MXFP4: a stage's codes (8 KB) and scale dwords (1 KB)
+  constexpr int QSCALES = QCODES + BN * 32;
+  static_assert(QF == 0 || QF == 2, "B operand: 0 = bf16, 2 = MXFP4");
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -982,17 +994,35 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
           const_cast<uint16_t *>(args.A + (long long)((tt_).row0 + (tt_).tile_row0) * args.lda), 0,  \
           0x7FFFFFFF, 0x00020000);                                                                   \
     /* B rows are n0 + 8 g + l/8: one per-lane offset, the row group's part is scalar */             \
-    src[NL] = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16_);                                      \
-    _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
-      int r_ = MOE_PGROUP(NL + i_) * 8 - BM;                                                         \
-      long long up_ = 0;                                                                             \
-      if (MODE == GEMM_SWIGLU && r_ >= BN / 2) { up_ = args.b1_off - args.b0_off; r_ -= BN / 2; }    \
-      b_soff[i_] = (int)(up_ + (long long)((tt_).n0 + r_) * args.ldb * 2);                           \
+    if constexpr (QF == 2) {                                                                         \
+      /* codes: K / 2 bytes per row; g & 3 = wave & 3 for all of a wave's B row groups */            \
+      src[NL] = (uint32_t)((lane_s >> 3) * (args.K >> 1) + (((lane_s & 7) ^ ((wave & 3) * 2)) << 2)); \
+      _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                            \
+        int r_ = MOE_PGROUP(NL + i_) * 8 - BM;                                                       \
+        long long base_ = args.q_b0_off;                                                             \
+        if (MODE == GEMM_SWIGLU && r_ >= BN / 2) { base_ = args.q_b1_off; r_ -= BN / 2; }            \
+        b_soff[i_] = (int)(base_ + (long long)((tt_).n0 + r_) * (args.K >> 1));                      \
+      }                                                                                              \
+      /* scales: wave w brings the dwords of tile rows 32 w .. 32 w + 31 (K / 32 bytes per row) */   \
+      int rs_ = wave * 32;                                                                           \
+      long long sbase_ = args.q_s0_off;                                                              \
+      if (MODE == GEMM_SWIGLU && rs_ >= BN / 2) { sbase_ = args.q_s1_off; rs_ -= BN / 2; }           \
+      q_ssrc = lane_s < 32 ? (uint32_t)(lane_s * (args.K >> 5)) : 0x80000000u;                       \
+      q_ssoff = (int)(sbase_ + (long long)((tt_).n0 + rs_) * (args.K >> 5));                         \
+    } else {                                                                                         \
+      src[NL] = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16_);                                    \
+      _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                            \
+        int r_ = MOE_PGROUP(NL + i_) * 8 - BM;                                                       \
+        long long up_ = 0;                                                                           \
+        if (MODE == GEMM_SWIGLU && r_ >= BN / 2) { up_ = args.b1_off - args.b0_off; r_ -= BN / 2; }  \
+        b_soff[i_] = (int)(up_ + (long long)((tt_).n0 + r_) * args.ldb * 2);                         \
+      }                                                                                              \
     }                                                                                                \
   } while (0)
 #define MOE_PTILE_SETUP(tt_)                                                                         \
   do {                                                                                               \
-    const char *wptr_ = args.wbase + (long long)args.slot[(tt_).grp] * args.wstride + args.b0_off;   \
+    const char *wptr_ = QF == 2 ? args.qbase + (long long)args.slot[(tt_).grp] * args.qstride        \
+                                : args.wbase + (long long)args.slot[(tt_).grp] * args.wstride + args.b0_off; \
     b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(wptr_), 0, 0x7FFFFFFF, 0x00020000); \
     const int kt_total_ = args.K / BK;                                                               \
     kt_begin = (int)((long long)kt_total_ * (tt_).ks / (tt_).ns);                                    \
@@ -1006,6 +1036,8 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   int kt_begin, nk, fm_valid;
   uint32_t src[NL + 1];          // per-lane byte offsets: the A row groups, then one for all B rows
   int b_soff[NL];                // scalar byte offsets of the B row groups
+  uint32_t q_ssrc = 0;           // MXFP4: per-lane and scalar byte offset of the scale load
+  int q_ssoff = 0;
   {
     const int lane_s = opaque(lane);
     int prow[NL];
@@ -1017,8 +1049,16 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   // this wave's A (WHICH_ = 0) or B (WHICH_ = 1) loads of stage q_
 #define MOE_PISSUE(q_, WHICH_)                                                                       \
   do {                                                                                               \
+    if ((WHICH_) && QF == 2)                                                                         \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                      \
+          b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QSCALES + wave * 256), 4, (int)q_ssrc,     \
+          q_ssoff + (((kt_begin + (q_)) >> 1) << 2), 0, 0);                                          \
     _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
-      if (WHICH_)                                                                                    \
+      if ((WHICH_) && QF == 2)                                                                       \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
+            b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QCODES + (MOE_PGROUP(NL + i_) - 32) * 256), 4, \
+            (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * (BK / 2), 0, 0);                          \
+      else if (WHICH_)                                                                               \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
             b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + MOE_PGROUP(NL + i_) * 1024), 16,         \
             (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * ROW_BYTES, 0, 0);                         \
@@ -1071,7 +1111,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 // nor multiplied (the loop is instantiated per count, so a tick stays straight-line code).
 // iss1_ / iss2_: the upper-or-lower A rows of stage H+1 / the B rows of stage H+2 are requested
 // here (M1(0) requests nothing: the prologue already has); next_: stage H+1 exists.  A wave's loads
-// complete in order: after M2(H) its youngest are [B(H+1)] [A(H+1)] [B(H+2)].  Group 1 has to
+// complete in order (NL of an A stage, NB of a B stage): after M2(H) its youngest are [B(H+1)] [A(H+1)] [B(H+2)].  Group 1 has to
 // certify its share at the end of its M ticks (group 0 reads in the next tick); group 0 can wait
 // until the end of C2, right before its own M1(H+1).  The flags are wave-uniform: scalar branches.
 #define MOE_PP_STEP(FMV, iss1_, iss2_, next_)                                                        \
@@ -1079,13 +1119,30 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     const unsigned char *st_ = smem + (H & 1) * STAGE;                                               \
     /* M1 */                                                                                         \
     if (FMV > 0) {                                                                                   \
-      _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                              \
-        _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                          \
-          bf_[j_][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (b_addr[j_] ^ (ks_ << 5)));         \
-      MOE_PREAD_A(0, (FMV < 2 ? FMV : 2));                                                           \
+      if constexpr (QF == 2) {                                                                       \
+        uint32_t qc_[FN][4], qs_[FN];                                                                \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_) {                                          \
+          qs_[j_] = *reinterpret_cast<const uint32_t *>(st_ + q_saddr[j_]);                          \
+          _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
+            qc_[j_][ks_] = *reinterpret_cast<const uint32_t *>(st_ + (b_addr[j_] ^ (ks_ << 3)));     \
+        }                                                                                            \
+        MOE_PREAD_A(0, (FMV < 2 ? FMV : 2));                                                         \
+        const int sh_ = ((kt_begin + H) & 1) * 16;   /* this K step's two bytes of the scale dword */ \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_) {                                          \
+          const float f0_ = __uint_as_float(((qs_[j_] >> sh_) & 0xFFu) << 23);                       \
+          const float f1_ = __uint_as_float(((qs_[j_] >> (sh_ + 8)) & 0xFFu) << 23);                 \
+          _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
+            bf_[j_][ks_] = __builtin_bit_cast(bf16x8, expand8_mxfp4(qc_[j_][ks_], ks_ < 2 ? f0_ : f1_)); \
+        }                                                                                            \
+      } else {                                                                                       \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
+          _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
+            bf_[j_][ks_] = *reinterpret_cast<const bf16x8 *>(st_ + (b_addr[j_] ^ (ks_ << 5)));       \
+        MOE_PREAD_A(0, (FMV < 2 ? FMV : 2));                                                         \
+      }                                                                                              \
     }                                                                                                \
     if (iss1_) MOE_PISSUE(H + 1, 0);                                                                 \
-    if (grp) { if (next_) MOE_PVMCNT(2 * NL); else MOE_PVMCNT(0); }  /* upper A rows of stage H */   \
+    if (grp) { if (next_) MOE_PVMCNT(NL + NB); else MOE_PVMCNT(0); }  /* upper A rows of stage H */  \
     __builtin_amdgcn_s_waitcnt(0xC07F);  /* lgkmcnt(0): fragments are in */                          \
     MOE_PBARRIER();                                                                                  \
     /* C1 */                                                                                         \
@@ -1094,12 +1151,12 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     /* M2 */                                                                                         \
     if (FMV > 2) MOE_PREAD_A(2, FMV);                                                                \
     if (iss2_) MOE_PISSUE(H + 2, 1);                                                                 \
-    if (grp) { if (iss2_) MOE_PVMCNT(2 * NL); else if (next_) MOE_PVMCNT(NL); else MOE_PVMCNT(0); }  \
+    if (grp) { if (iss2_) MOE_PVMCNT(NL + NB); else if (next_) MOE_PVMCNT(NL); else MOE_PVMCNT(0); } \
     __builtin_amdgcn_s_waitcnt(0xC07F);                                                              \
     MOE_PBARRIER();                                                                                  \
     /* C2 */                                                                                         \
     if (FMV > 0) MOE_PMMA(FMV, 1);                                                                   \
-    if (!grp) { if (iss2_) MOE_PVMCNT(NL); else MOE_PVMCNT(0); }     /* all of stage H+1 */          \
+    if (!grp) { if (iss2_) MOE_PVMCNT(NB); else MOE_PVMCNT(0); }     /* all of stage H+1 */          \
     MOE_PBARRIER();                                                                                  \
   } while (0)
 #define MOE_PP_LOOP(FMV)                                                                             \
@@ -1119,7 +1176,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     }                                                                                                \
   } while (0)
 
-  if (t.rows_valid > kSmallTileRows) MOE_PPROLOGUE();
+  if (QF != 0 || t.rows_valid > kSmallTileRows) MOE_PPROLOGUE();
   for (;;) {
     const bool has_next = nxt >= 0;
     TileInfo tn = t;
@@ -1139,6 +1196,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     // (the swizzle XORs the chunk index, and slice ks only changes bits 1..2 of it).  Derived from
     // an opaque copy of the lane id so that they live only as long as the K loop.
     int a_addr[FM], b_addr[FN];
+    int q_saddr[FN] = {};   // MXFP4: this lane's scale dwords
     {
       const int lane_k = opaque(lane);
       const int lrow = lane_k & 31, lk = lane_k >> 5;
@@ -1148,7 +1206,13 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       for (int j = 0; j < FN; ++j) {
         const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
                                                : (j * WARPS_N + wn) * 32 + lrow;
-        b_addr[j] = BM * ROW_BYTES + swz(brow, lk);
+        if constexpr (QF == 2) {
+          // dword ks * 2 + lk of the row's codes sits at position (ks * 2 + lk) ^ 2 ((brow >> 3) & 3)
+          b_addr[j] = QCODES + brow * 32 + lk * 4 + (((brow >> 3) & 3) << 3);
+          q_saddr[j] = QSCALES + (brow >> 5) * 256 + (brow & 31) * 4;   // wave brow / 32 brought it, lane brow % 32
+        } else {
+          b_addr[j] = BM * ROW_BYTES + swz(brow, lk);
+        }
       }
     }
 
@@ -1165,7 +1229,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     if (dyn) after_next = qbox[0];
     else after_next = has_next && nxt + nslots < st_end ? nxt + nslots : -1;
     after_next = __builtin_amdgcn_readfirstlane(after_next);
-    if (t.rows_valid <= kSmallTileRows) {
+    if (QF == 0 && t.rows_valid <= kSmallTileRows) {
       // A short tile (pp_small_tile): no loads were requested for it, and its last stage lies over the
       // mailbox word, which everybody has to have read first.
       MOE_PBARRIER();
@@ -1201,7 +1265,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     const int fm_cur = fm_valid;
     const int lane_s = opaque(lane);
     int prow_n[NL];
-    const bool next_full = has_next && tn.rows_valid > kSmallTileRows;   // a short tile sets itself up
+    const bool next_full = has_next && (QF != 0 || tn.rows_valid > kSmallTileRows);   // a short tile sets itself up
     if (next_full) {
       MOE_PPERM(tn, prow_n);
     } else {
@@ -1429,12 +1493,12 @@ static int pp_grid(const GemmArgs &args, GemmMode mode, int max_rows, int n_grou
   return (int)(ub < cap ? ub : cap);
 }
 
-template <int MODE>
+template <int MODE, int QF = 0>
 hipError_t launch_pp(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   constexpr int BM = 256, BN = 256;
   // two stages of A and B tiles + 4 KB per wave for the epilogue's transposition
   constexpr size_t smem = 2 * (size_t)(BM + BN) * ROW_BYTES + 8 * 4096;
-  auto kern = grouped_gemm_pp_kernel<MODE>;
+  auto kern = grouped_gemm_pp_kernel<MODE, QF>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1470,6 +1534,16 @@ hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask
 // args.tune.gemm_variant: 0 picks by shape; a test or tuning run forces 1 = 128 x 128 tiles, 6 = 256 x 256
 // tiles of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
 static bool pp_possible(GemmMode mode, const GemmArgs &args) {
+  if (args.b_quant) {
+    // MXFP4 blobs only: the scale bytes of two K steps are fetched as one aligned dword, and codes and
+    // scales are addressed from the start of the blob with 31-bit byte offsets.
+    const long long codes_end = (args.q_b1_off > args.q_b0_off ? args.q_b1_off : args.q_b0_off) +
+                                (long long)args.N * (args.K / 2);
+    return args.qfmt == 2 && mode != GEMM_PLAIN_BF16 && args.K % 128 == 0 &&
+           (args.q_s0_off % 4) == 0 && (args.q_s1_off % 4) == 0 && codes_end < 0x7FFFFFFFll &&
+           (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
+           args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
+  }
   // The ping-pong kernel addresses a gathered A from its first row (any of its a_rows rows can be
   // named by the permutation), an A used in place from the tile's first row (256 rows), and the
   // blob from its first B row, all with 31-bit byte offsets.
@@ -1496,12 +1570,19 @@ int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.b_quant) {
-    // quantised experts: the kernel that expands the codes on their way into LDS, with the tile size by the
-    // groups' average height
+    // quantised experts: MXFP4 on the persistent kernel where its shape rules allow (always when the layer
+    // call runs from a plan), else the kernel that expands the codes on their way into LDS, with the tile
+    // size by the groups' average height
     if (MODE == GEMM_PLAIN_BF16 || (args.qfmt != 1 && args.qfmt != 2) || !args.qbase || args.K % BK != 0)
       return hipErrorInvalidValue;
     const long long avg_rows = n_groups_in_mask > 0 ? (long long)max_rows / n_groups_in_mask : max_rows;
-    const bool big = avg_rows > 96 && args.tune.gemm_variant[MODE] != 1;
+    const int v = args.tune.gemm_variant[MODE];
+    const bool big = avg_rows > 96 && v != 1;
+    if constexpr (MODE != GEMM_PLAIN_BF16) {
+      if (args.qfmt == 2 && (args.plan || (big && (v == 0 || v == 12) && pp_possible((GemmMode)MODE, args))))
+        return launch_pp<MODE, 2>(args, max_rows, n_groups_in_mask, stream);
+    }
+    if (args.plan) return hipErrorInvalidValue;
     if (args.qfmt == 2)
       return big ? launch_q8_cfg<256, 256, 2, 4, MODE, 2>(args, max_rows, n_groups_in_mask, stream)
                  : launch_q8_cfg<128, 128, 2, 2, MODE, 2>(args, max_rows, n_groups_in_mask, stream);

@@ -449,13 +449,17 @@ def test_q8_cache_holds_the_8bit_blobs_and_prefill_reads_them(gpu, oracle, fmt):
 
 @pytest.mark.parametrize("d,I,E,k,T,Ish,variant", [(256, 128, 8, 2, 1200, 0, 0), (512, 192, 5, 3, 700, 128, 0),
                                                    (256, 320, 16, 4, 2500, 0, 0), (256, 128, 8, 2, 1200, 0, 1),
-                                                   (1024, 64, 64, 6, 900, 64, 0), (128, 4096, 3, 1, 150, 0, 0)])
+                                                   (1024, 64, 64, 6, 900, 64, 0), (128, 4096, 3, 1, 150, 0, 0),
+                                                   (256, 256, 16, 4, 2500, 128, 0), (256, 128, 8, 2, 6200, 0, 0),
+                                                   (384, 640, 6, 2, 1500, 0, 0)])
 @pytest.mark.parametrize("fmt", [1, 3])
 def test_q8_prefill_gemm_on_codes(gpu, oracle, fmt, d, I, E, k, T, Ish, variant):
     """The GEMM kernels that read e4m3 or MXFP4 experts: 256 x 256 and 128 x 128 tiles (by the groups' height, or
-    forced), several K slices of the down projection, ragged groups, resident experts placed by the
-    caller (initial_resident names quantised blobs) and experts streaming through three slots: the same bits
-    either way, and the oracle's output on its own expansion of the codes."""
+    forced), for MXFP4 also the persistent kernel (K a multiple of 128: fixed order, and work plans with
+    queues for 16 experts or 1550 rows per expert), several K slices of the down projection, ragged groups,
+    resident experts placed by the caller (initial_resident names quantised blobs) and experts streaming
+    through three slots: the same bits either way, and the oracle's output on its own expansion of the
+    codes."""
     H, B = gpu["harness"], gpu["binding"]
     w = S.Workload("q8_gemm", d=d, I=I, E=E, k=k, T=T, I_shared=Ish, seed=77, zipf_s=0.9)
     x = S.activations(w)
