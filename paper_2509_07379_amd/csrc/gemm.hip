@@ -866,6 +866,11 @@ __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileIn
 // neighbour).  A lane builds its B fragment of K slice ks from one dword of codes with the hardware's scaled
 // fp4 conversion (exact), so the MFMAs see the weights the format defines.  Short row tiles run through the
 // same loop.  Needs K % 128 == 0 and the blob within 31 bits of byte offset.
+// QF = 1: the e4m3 blobs.  A stage's B tile is 256 rows of 64 bytes of codes, two 16-byte wave-wide loads per wave
+// (a load is 16 rows of four pieces; the piece at position p of row r is piece p ^ ((r >> 2) & 3) of the row's
+// K step).  A lane builds a B fragment from 8 bytes of codes and its row's fp32 scale (fetched once per tile):
+// the hardware's e4m3 -> fp32 conversion, one multiply, nearest-even bf16 - 16 vector instructions per
+// fragment and K slice, issued in the load tick.
 template <int MODE, int QF = 0>
 __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs args) {
   constexpr int BM = 256, BN = 256, WARPS_M = 2, WARPS_N = 4;
@@ -874,10 +879,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
   constexpr int STAGE = (BM + BN) * ROW_BYTES;   // 64 KB
   constexpr int NL = 4;                          // wave-wide loads per wave and M tick
-  constexpr int NB = QF == 2 ? NL + 1 : NL;      // ... of a B stage (MXFP4: the codes and one load of scales)
-  constexpr int QCODES = BM * ROW_BYTES;         // MXFP4: a stage's codes (8 KB) and scale dwords (1 KB)
-  constexpr int QSCALES = QCODES + BN * 32;
-  static_assert(QF == 0 || QF == 2, "B operand: 0 = bf16, 2 = MXFP4");
+  constexpr int NB = QF == 2 ? NL + 1 : QF == 1 ? 2 : NL;   // ... of a B stage (MXFP4: the codes and one load of scales)
+  constexpr int QCODES = BM * ROW_BYTES;         // quantised B: a stage's codes (e4m3 16 KB; MXFP4 8 KB and,
+  constexpr int QSCALES = QCODES + BN * 32;      // behind them, 2 KB for the scale dwords)
+  static_assert(QF >= 0 && QF <= 2, "B operand: 0 = bf16, 1 = e4m3 rows, 2 = MXFP4");
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -1009,6 +1014,15 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       if (MODE == GEMM_SWIGLU && rs_ >= BN / 2) { sbase_ = args.q_s1_off; rs_ -= BN / 2; }           \
       q_ssrc = lane_s < 32 ? (uint32_t)(lane_s * (args.K >> 5)) : 0x80000000u;                       \
       q_ssoff = (int)(sbase_ + (long long)((tt_).n0 + rs_) * (args.K >> 5));                         \
+    } else if constexpr (QF == 1) {                                                                  \
+      /* codes: K bytes per row; load i_ of a wave brings tile rows 16 (8 i_ + wave) .. + 15 */      \
+      src[NL] = (uint32_t)((lane_s >> 2) * args.K + (((lane_s & 3) ^ ((lane_s >> 4) & 3)) << 4));    \
+      _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) {                                             \
+        int r_ = (i_ * 8 + wave) * 16;                                                               \
+        long long base_ = args.q_b0_off;                                                             \
+        if (MODE == GEMM_SWIGLU && r_ >= BN / 2) { base_ = args.q_b1_off; r_ -= BN / 2; }            \
+        b_soff[i_] = (int)(base_ + (long long)((tt_).n0 + r_) * args.K);                             \
+      }                                                                                              \
     } else {                                                                                         \
       src[NL] = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16_);                                    \
       _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                            \
@@ -1021,7 +1035,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   } while (0)
 #define MOE_PTILE_SETUP(tt_)                                                                         \
   do {                                                                                               \
-    const char *wptr_ = QF == 2 ? args.qbase + (long long)args.slot[(tt_).grp] * args.qstride        \
+    const char *wptr_ = QF != 0 ? args.qbase + (long long)args.slot[(tt_).grp] * args.qstride        \
                                 : args.wbase + (long long)args.slot[(tt_).grp] * args.wstride + args.b0_off; \
     b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(wptr_), 0, 0x7FFFFFFF, 0x00020000); \
     const int kt_total_ = args.K / BK;                                                               \
@@ -1030,8 +1044,16 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     fm_valid = 0;                                                                                    \
     _Pragma("unroll") for (int i_ = 0; i_ < FM; ++i_)                                                \
       fm_valid += ((i_ * WARPS_M + wm) * 32 < (tt_).rows_valid) ? 1 : 0;                             \
+    if constexpr (QF == 1) {                                                                         \
+      _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_) {                                            \
+        const long long so_ = (MODE == GEMM_SWIGLU && j_ >= FNH) ? args.q_s1_off : args.q_s0_off;    \
+        const int n_ = (tt_).n0 + (((MODE == GEMM_SWIGLU) ? j_ % FNH : j_) * WARPS_N + wn) * 32 + (lane & 31); \
+        q_rs[j_] = reinterpret_cast<const float *>(wptr_ + so_)[n_];                                 \
+      }                                                                                              \
+    }                                                                                                \
   } while (0)
 
+  float q_rs[FN] = {};           // e4m3: the scales of this lane's B fragment rows
   __amdgpu_buffer_rsrc_t b_rsrc;
   int kt_begin, nk, fm_valid;
   uint32_t src[NL + 1];          // per-lane byte offsets: the A row groups, then one for all B rows
@@ -1053,6 +1075,12 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
       __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                      \
           b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QSCALES + wave * 256), 4, (int)q_ssrc,     \
           q_ssoff + (((kt_begin + (q_)) >> 1) << 2), 0, 0);                                          \
+    if ((WHICH_) && QF == 1) {                                                                       \
+      _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                               \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
+            b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QCODES + (i_ * 8 + wave) * 1024), 16,    \
+            (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * BK, 0, 0);                                \
+    } else                                                                                           \
     _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
       if ((WHICH_) && QF == 2)                                                                       \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
@@ -1088,7 +1116,10 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
 // The two compute ticks of a K step, for FMV valid fragments, with the MFMAs split evenly:
 //   4: {0,1} | {2,3}     3: 0 and the first half of 1 | second half of 1 and 2
 //   2: 0 | 1             1: first half of 0 | second half of 0
-// (fragments 0,1 are read in M1 and 2,3 in M2, whatever tick multiplies them)
+// (fragments 0,1 are read in M1 and 2,3 in M2, whatever tick multiplies them: the A rows of fragments 2, 3 are
+// the ones whose arrival group 1 certifies only at the end of ITS M1, one tick after group 0's, so no wave may
+// read them before M2.  Cutting the ticks along K instead - all fragments' slices 0, 1 in M1 - reads them too
+// early: tried for the e4m3 conversions, wrong sums in rows 128.. of a tile)
 #define MOE_PMMA(FMV, TICK_)                                                                         \
   do {                                                                                               \
     __builtin_amdgcn_s_setprio(1);                                                                   \
@@ -1134,6 +1165,15 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
           _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
             bf_[j_][ks_] = __builtin_bit_cast(bf16x8, expand8_mxfp4(qc_[j_][ks_], ks_ < 2 ? f0_ : f1_)); \
         }                                                                                            \
+      } else if constexpr (QF == 1) {                                                                \
+        u32x2 qc_[FN][4];                                                                            \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
+          _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
+            qc_[j_][ks_] = *reinterpret_cast<const u32x2 *>(st_ + (b_addr[j_] ^ (ks_ << 4)));        \
+        MOE_PREAD_A(0, (FMV < 2 ? FMV : 2));                                                         \
+        _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
+          _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
+            bf_[j_][ks_] = __builtin_bit_cast(bf16x8, expand8_e4m3(qc_[j_][ks_].x, qc_[j_][ks_].y, q_rs[j_])); \
       } else {                                                                                       \
         _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_)                                            \
           _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
@@ -1210,6 +1250,9 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
           // dword ks * 2 + lk of the row's codes sits at position (ks * 2 + lk) ^ 2 ((brow >> 3) & 3)
           b_addr[j] = QCODES + brow * 32 + lk * 4 + (((brow >> 3) & 3) << 3);
           q_saddr[j] = QSCALES + (brow >> 5) * 256 + (brow & 31) * 4;   // wave brow / 32 brought it, lane brow % 32
+        } else if constexpr (QF == 1) {
+          // 8 codes of K slice ks: half lk of piece ks, which sits at position ks ^ ((brow >> 2) & 3)
+          b_addr[j] = QCODES + brow * 64 + lk * 8 + (((brow >> 2) & 3) << 4);
         } else {
           b_addr[j] = BM * ROW_BYTES + swz(brow, lk);
         }
@@ -1535,10 +1578,17 @@ hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask
 // tiles of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
 static bool pp_possible(GemmMode mode, const GemmArgs &args) {
   if (args.b_quant) {
-    // MXFP4 blobs only: the scale bytes of two K steps are fetched as one aligned dword, and codes and
-    // scales are addressed from the start of the blob with 31-bit byte offsets.
+    // Codes and scales are addressed from the start of the blob with 31-bit byte offsets; the MXFP4 scale
+    // bytes of two K steps are fetched as one aligned dword, e4m3 codes in aligned 16-byte pieces.
     const long long codes_end = (args.q_b1_off > args.q_b0_off ? args.q_b1_off : args.q_b0_off) +
                                 (long long)args.N * (args.K / 2);
+    const long long row_bytes = args.qfmt == 2 ? args.K / 2 : args.K;
+    const long long codes_end1 = (args.q_b1_off > args.q_b0_off ? args.q_b1_off : args.q_b0_off) + args.N * row_bytes;
+    if (args.qfmt == 1)
+      return mode != GEMM_PLAIN_BF16 && args.K % BK == 0 && (args.q_s0_off % 4) == 0 && (args.q_s1_off % 4) == 0 &&
+             (args.q_b0_off % 16) == 0 && (args.q_b1_off % 16) == 0 && codes_end1 < 0x7FFFFFFFll &&
+             (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
+             args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
     return args.qfmt == 2 && mode != GEMM_PLAIN_BF16 && args.K % 128 == 0 &&
            (args.q_s0_off % 4) == 0 && (args.q_s1_off % 4) == 0 && codes_end < 0x7FFFFFFFll &&
            (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
@@ -1570,8 +1620,8 @@ int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.b_quant) {
-    // quantised experts: MXFP4 on the persistent kernel where its shape rules allow (always when the layer
-    // call runs from a plan), else the kernel that expands the codes on their way into LDS, with the tile
+    // quantised experts: the persistent kernel where its shape rules allow (always when the layer call runs
+    // from a plan), else the kernel that expands the codes on their way into LDS, with the tile
     // size by the groups' average height
     if (MODE == GEMM_PLAIN_BF16 || (args.qfmt != 1 && args.qfmt != 2) || !args.qbase || args.K % BK != 0)
       return hipErrorInvalidValue;
@@ -1579,8 +1629,9 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
     const int v = args.tune.gemm_variant[MODE];
     const bool big = avg_rows > 96 && v != 1;
     if constexpr (MODE != GEMM_PLAIN_BF16) {
-      if (args.qfmt == 2 && (args.plan || (big && (v == 0 || v == 12) && pp_possible((GemmMode)MODE, args))))
-        return launch_pp<MODE, 2>(args, max_rows, n_groups_in_mask, stream);
+      if (args.plan || (big && (v == 0 || v == 12) && pp_possible((GemmMode)MODE, args)))
+        return args.qfmt == 2 ? launch_pp<MODE, 2>(args, max_rows, n_groups_in_mask, stream)
+                              : launch_pp<MODE, 1>(args, max_rows, n_groups_in_mask, stream);
     }
     if (args.plan) return hipErrorInvalidValue;
     if (args.qfmt == 2)
