@@ -241,25 +241,28 @@ def test_c2_shape_quantised_host_pool(gpu, oracle, fmt):
 
 
 @pytest.mark.parametrize("fmt", [1, 3])
-def test_c2_shape_quantised_gemm_kernels_agree(gpu, fmt):
-    """Quantised experts, every expert resident, at full size (64 and 224 K steps, blocks that walk over
-    several tiles): the persistent kernel, which builds its B fragments from the codes in LDS, against the
+@pytest.mark.parametrize("workload", ["c2_mixtral_prefill", "c4_deepseek_prefill"])
+def test_full_size_quantised_gemm_kernels_agree(gpu, fmt, workload):
+    """Quantised experts, every expert resident, at full size (Mixtral shape: 64 and 224 K steps, blocks that
+    walk over several tiles in a fixed order; DeepSeek shape: 64 experts of very different size, work plans
+    with queues, short row tiles, shared experts beside them): the persistent kernel, which builds its B fragments from the codes in LDS, against the
     single-phase kernel, which expands code tiles into LDS.  Gate/up sums are formed in the same order, so
     with the down GEMM on the same kernel in both runs the outputs are equal bit for bit; with both GEMMs
     on the persistent kernel (other K slices of the down projection) they agree within the bf16 tolerance."""
     H, B = gpu["harness"], gpu["binding"]
-    w = S.WORKLOADS["c2_mixtral_prefill"]
+    w = S.WORKLOADS[workload]
     pool = H.HostPool(w, 0, fmt=fmt)
     x = H.np_to_dev(S.activations(w))
+    bias = H.np_to_dev(S.zipf_route_bias(w, 0)) if w.zipf_s else None
     outs = {}
     for name, tunes in (("single-phase", [(0, 6), (1, 6)]), ("gate/up persistent", [(1, 6)]), ("persistent", [])):
-        ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, 0, True, host_format=fmt)
+        ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, True, host_format=fmt)
         lay = H.DeviceLayer(ctx, w, 0, pool, list(range(w.E)))
         buf = H.Buffers(ctx, w.T)
         for mode, variant in tunes:
             ctx.moe_tune(mode, variant)
         for _ in range(3):       # the launches' timing differs from call to call; the bits must not
-            ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"])
+            ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, gpu["compute"], gpu["copy"], bias, 0)
             gpu["compute"].synchronize()
             out = H.dev_to_np_u16(buf.y)
             assert name not in outs or np.array_equal(outs[name], out), f"format {fmt}, {name}: not repeatable"
