@@ -41,12 +41,13 @@ def ids_against_fp64_logits(oracle, x_np, router_np, bias_np, k, gpu_ids, tag):
     return under
 
 
-def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=False, layer=0):
+def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=False, layer=0, fmt=0):
     """One prefill layer of workload w; `layer` picks the seeded weights, activations and (config 4) the
-    rank permutation of the popularity bias."""
+    rank permutation of the popularity bias; fmt: the experts' format in the CPU expert cache (the oracle
+    then runs on its own expansion of the same blobs)."""
     H, B = gpu["harness"], gpu["binding"]
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, layer + 1, slots, w.I_shared)   # only `layer` is bound
-    pool = H.HostPool(w, layer)
+    ctx = B.MoeContext(w.d, w.I, w.E, w.k, layer + 1, slots, w.I_shared, host_format=fmt)   # only `layer` is bound
+    pool = H.HostPool(w, layer, fmt=fmt)
     initial = list(range(w.E)) if slots == w.E else None
     lay = H.DeviceLayer(ctx, w, layer, pool, initial, poison=initial is None)
     buf = H.Buffers(ctx, w.T)
@@ -68,7 +69,9 @@ def prefill_case(gpu, oracle, w, slots, n_sample, prefetch=None, with_attention=
     stats, state = ctx.moe_get_stats(layer), ctx.moe_cache_state(layer)
     ctx.close()
     sel = sample_tokens(w.T, n_sample, seed=layer)
-    ref = oracle.moe_layer(x_np, lay.router_np, [pool.ptr(e) for e in range(w.E)], w.k, bias=bias_np, sel=sel,
+    expand = {1: oracle.dequant_blob, 2: oracle.dequant4_blob, 3: oracle.dequant_mx4_blob}.get(fmt)
+    blobs = [expand(pool.blob_np(e), w.d, w.I) if fmt else pool.ptr(e) for e in range(w.E)]
+    ref = oracle.moe_layer(x_np, lay.router_np, blobs, w.k, bias=bias_np, sel=sel,
                            shared_blob=lay.shared_np, I=w.I, I_shared=w.I_shared)
     for key in ("ids", "counts", "offsets", "perm", "inv_perm"):
         np.testing.assert_array_equal(routing[key], ref[key], err_msg=key)
@@ -127,6 +130,24 @@ def test_c4_deepseek_prefill_layer(gpu, oracle, layer):
     sim.serve(np.nonzero(counts)[0])
     assert r["stats"] == {**sim.counters(), "layer_calls": 1}
     assert r["state"] == sim.slot_expert
+
+
+@pytest.mark.parametrize("fmt", [1, 3])
+def test_c4_shape_quantised_experts_through_16_slots(gpu, oracle, fmt):
+    """The same layer on e4m3 / MXFP4 experts, 64 of them streaming through 16 slots of quantised blobs
+    (single-expert launches of the persistent kernel behind each copy, the last fetch split), and with
+    every expert resident (one launch over all groups from the work plans)."""
+    from oracle.cache_sim import CacheSim
+    w = S.WORKLOADS["c4_deepseek_prefill"]
+    r = prefill_case(gpu, oracle, w, w.S, 32, prefetch=list(range(w.S)), fmt=fmt)
+    nbytes = S.q8_blob_bytes(w.d, w.I) if fmt == 1 else S.mx4_blob_bytes(w.d, w.I)
+    sim = CacheSim(w.E, w.S, nbytes)
+    sim.prefetch(range(w.S))
+    sim.serve(np.nonzero(r["routing"]["counts"])[0])
+    assert r["stats"] == {**sim.counters(), "layer_calls": 1}
+    assert r["state"] == sim.slot_expert
+    res = prefill_case(gpu, oracle, w, w.E, 32, fmt=fmt)
+    assert res["stats"]["misses"] == 0 and res["stats"]["bytes_h2d"] == 0
 
 
 def decode_case(gpu, oracle, w, n_layers, steps, check_every=1):
