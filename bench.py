@@ -468,28 +468,46 @@ def prefill_c4(args, torch, B, H, S, compute, copy, steps=20, n_check=32):
 
     if args.no_offloaded:
         return out
-    # the configured cache of 16 slots: every expert streams through it once per layer
-    ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared)
-    lay2 = H.DeviceLayer(ctx, w, 0, pool, None)
+    # the configured cache of 16 slots: every expert streams through it once per layer; in bf16, and
+    # (unless --no-q8) with the experts held and fetched as MXFP4 blobs, for which the layer with every
+    # expert resident is timed as well
+    for fmt, key in ((0, "offloaded"),) + (() if args.no_q8 else ((3, "offloaded_mxfp4"),)):
+        qpool = pool if fmt == 0 else H.HostPool(w, 0, fmt=fmt)
+        ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.S, w.I_shared, host_format=fmt)
+        lay2 = H.DeviceLayer(ctx, w, 0, qpool, None)
 
-    def pipelined():
-        ctx.moe_cache_invalidate(0)
-        ctx.expert_cache_prefetch(0, list(range(w.S)), copy)
-        ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy, bias, 0)
+        def pipelined():
+            ctx.moe_cache_invalidate(0)
+            ctx.expert_cache_prefetch(0, list(range(w.S)), copy)
+            ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy, bias, 0)
 
-    pipelined()
-    torch.cuda.synchronize()
-    ctx.moe_reset_stats()
-    t0 = time.perf_counter()
-    for _ in range(3):
         pipelined()
-    torch.cuda.synchronize()
-    t_p = (time.perf_counter() - t0) * 1e3 / 3
-    st = ctx.moe_get_stats(0)
-    ctx.close()
-    del lay2
-    out["offloaded"] = {"slots": w.S, "ms_per_layer": t_p, "bytes_per_layer": st["bytes_h2d"] / st["layer_calls"],
-                        "link_GBps_over_the_layer": st["bytes_h2d"] / st["layer_calls"] / (t_p * 1e-3) / 1e9}
+        torch.cuda.synchronize()
+        ctx.moe_reset_stats()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            pipelined()
+        torch.cuda.synchronize()
+        t_p = (time.perf_counter() - t0) * 1e3 / 3
+        st = ctx.moe_get_stats(0)
+        ctx.close()
+        del lay2
+        out[key] = {"slots": w.S, "ms_per_layer": t_p, "bytes_per_layer": st["bytes_h2d"] / st["layer_calls"],
+                    "link_GBps_over_the_layer": st["bytes_h2d"] / st["layer_calls"] / (t_p * 1e-3) / 1e9}
+        if fmt:
+            ctx = B.MoeContext(w.d, w.I, w.E, w.k, 1, w.E, w.I_shared, host_format=fmt)
+            lay3 = H.DeviceLayer(ctx, w, 0, qpool, list(range(w.E)))
+            layer = lambda: ctx.moe_prefill_layer(0, x, w.T, buf.y, buf.ws, compute, copy, bias, 0)
+            for _ in range(100):
+                layer()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                layer()
+            torch.cuda.synchronize()
+            out[key]["resident_ms_per_layer"] = (time.perf_counter() - t0) * 1e3 / steps
+            ctx.close()
+            del lay3
     return out
 
 

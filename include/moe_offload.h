@@ -239,8 +239,12 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out);
  * through the slots in ascending id, each fetched once on copy_stream while the previous
  * one computes.  Groups of any size run on the MFMA kernels: for a handful of tokens
  * moe_decode_layer gives the same result faster (and itself moves to the GEMM kernels when some
- * expert receives more than 16 tokens, 32 where the mat-vecs read quantised copies).  When some routed expert is not resident the call
- * blocks the host once, until the gate's counts are known.
+ * expert receives more than 16 tokens, 32 where the mat-vecs read quantised experts).  When some routed
+ * expert is not resident the call blocks the host until the gate's counts are known, and again
+ * before each fetch into a slot whose last reader (an expert of this call, S fetches earlier) is
+ * still computing: the copy is then enqueued with no wait in front of it, which starts it sooner
+ * than a wait on the stream would.  Such a call returns when all its work is enqueued, i.e. after
+ * all but the last S experts have been computed.
  *  dev_route_bias  NULL, or fp32 added to the gate logits: element [t*bias_stride + e]
  *                  (bias_stride 0 = one row for all tokens, E = one row per token).
  *  dev_workspace   >= moe_workspace_bytes(cfg, T), 256-byte aligned; holds the routing

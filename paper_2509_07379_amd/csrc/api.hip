@@ -391,26 +391,41 @@ int pick_victim(const Layer &L, unsigned long long protected_mask) {
 }
 
 // The copy stream waits for the last reader of slot s (nothing to wait for if it was never read).
-int wait_slot_free(Layer &L, int s, hipStream_t copy_stream) {
-  if (L.set->use_kind[s] == 1) HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->used[s], 0));
+// The copy into slot s may start when the slot's last reader has finished.  If it has (the usual case in
+// decode: the reader ran a step ago), nothing is enqueued.  Otherwise either the copy stream waits for the
+// reader's event, or (host_waits) the calling thread does and the copy is enqueued without a dependency.
+// A copy behind a wait for an event that is still pending starts some 30 to 45 us after the event fires
+// (the wait and the DMA are handed over by the runtime's queues); a copy that is simply next in the copy
+// stream's queue starts 7 to 25 us after its predecessor.  A layer call that streams misses through the
+// slots has nothing else to do on the host, and every copy it issues waits for the compute of an earlier
+// expert of the same call, so it paces the copies itself (64 experts of 17 MB through 16 slots: 25.5 ->
+// 21.3 ms per layer; as MXFP4 blobs of 4.6 MB: 12.4 -> 8.1 ms; copies alone 20.3 and 7.2 ms).  A prefetch
+// call stays asynchronous: its copy waits on the stream.
+int wait_slot_free(Layer &L, int s, hipStream_t copy_stream, bool host_waits) {
+  hipEvent_t ev = nullptr;
+  if (L.set->use_kind[s] == 1) ev = L.set->used[s];
   if (L.set->use_kind[s] == 2) {
     if (L.set->done_pending) {   // the last grouped launch over resident experts left the recording to us
       HIP_TRY(hipEventRecord(L.set->group_done, L.set->done_stream));
       L.set->done_pending = false;
     }
-    HIP_TRY(hipStreamWaitEvent(copy_stream, L.set->group_done, 0));
+    ev = L.set->group_done;
   }
+  if (!ev || hipEventQuery(ev) == hipSuccess) return MOE_OK;
+  if (host_waits) HIP_TRY(hipEventSynchronize(ev));
+  else HIP_TRY(hipStreamWaitEvent(copy_stream, ev, 0));
   return MOE_OK;
 }
 
 // Enqueue the copy of expert e into slot s on the copy stream, behind the slot's last reader
-// (waited: that wait is already on the stream).  split: the gate / up matrices and the down
+// (waited: that wait is already on the stream; host_waits: see wait_slot_free).
+// split: the gate / up matrices and the down
 // matrix travel as two copies, with copied_up[s] recorded in between, so that the first matmul
 // can start while the down matrix is still on the link.
 int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t copy_stream,
-          bool waited = false, bool split = false) {
+          bool waited = false, bool split = false, bool host_waits = false) {
   if (!waited) {
-    int rc = wait_slot_free(L, s, copy_stream);
+    int rc = wait_slot_free(L, s, copy_stream, host_waits);
     if (rc) return rc;
   }
   char *dst = L.set->slots + (size_t)s * ctx->blob_bytes;
@@ -986,7 +1001,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       const int e = misses[i];
       const int s = pick_victim(L, 0ull);
       const bool last = i + 1 == n_miss;
-      rc = place(ctx, L, e, s, false, ks, false, last);
+      rc = place(ctx, L, e, s, false, ks, false, last, true);
       if (rc) return rc;
       a1.slot[e] = a2.slot[e] = (int16_t)s;
       if (a1.qbase && L.set->q_valid[s]) {   // fetched just now: its quantised copy is in the staging area
