@@ -129,12 +129,12 @@ struct SlotSet {
   std::vector<char> copy_pending;    // a copy into the slot was enqueued; compute has not waited yet
   std::vector<char> pf_landed;       // prefetched slot, when compute first waited for it: 1 = had landed, 2 = had not
   std::vector<char> use_kind;        // 0: never read, 1: read behind used[slot], 2: read behind group_done
-  std::vector<hipEvent_t> copied, used;
-  std::vector<hipEvent_t> copied_up;  // a split fetch has landed its gate / up matrices
-  // 8-bit host format: the bytes of a fetch (its first piece, all of it) are in the staging area
+  std::vector<hipEvent_t> copied, used;   // the slot can be read (fetched and, int4 pool, expanded) / has been read
+  std::vector<hipEvent_t> copied_up;  // a split fetch has brought (and expanded) its gate / up matrices
+  // integer 4-bit host format: the bytes of a fetch (its first piece, all of it) are in the staging area
   std::vector<hipEvent_t> landed_up, landed;
   std::vector<char> staged;          // the slot's staging area has been written before
-  std::vector<char> q_valid;         // the staging area holds the quantised form of what the slot holds
+  std::vector<char> q_valid;         // the slot holds a quantised blob that every kernel reads as it is
   std::vector<char> expand_pending;  // the expansion into the slot was enqueued; compute has not waited for it yet
   hipEvent_t group_done = nullptr;
   bool done_pending = false;         // group_done still has to be recorded, on done_stream, before it is waited for
@@ -304,8 +304,8 @@ void touch(Layer &L, int s) { L.set->stamp[s] = ++L.set->clock; }
 // Section V-C, second synchronisation point: had a prefetched expert landed when compute asked for it
 // (1) or does the computation stream have to wait for the copy (2)?  Taken on the host when the wait
 // is enqueued, which is never later than the stream's own wait.
-int prefetch_arrival(SlotSet &set, int s, bool from_copy) {
-  return hipEventQuery(from_copy ? set.landed[s] : set.copied[s]) == hipSuccess ? 1 : 2;
+int prefetch_arrival(SlotSet &set, int s) {
+  return hipEventQuery(set.copied[s]) == hipSuccess ? 1 : 2;
 }
 
 // A served expert that was resident: recency, hit counter and, the first time after a prefetch
@@ -317,7 +317,7 @@ void account_hit(Layer &L, int s) {
   if (!set.prefetched[s]) return;
   L.stats.prefetch_useful++;
   set.prefetched[s] = 0;
-  const int arrival = set.pf_landed[s] ? set.pf_landed[s] : (set.copy_pending[s] ? prefetch_arrival(set, s, false) : 1);
+  const int arrival = set.pf_landed[s] ? set.pf_landed[s] : (set.copy_pending[s] ? prefetch_arrival(set, s) : 1);
   if (arrival == 1) L.stats.prefetch_ready++;
   else L.stats.prefetch_stalled++;
   set.pf_landed[s] = 0;
@@ -469,17 +469,15 @@ int place(moe_ctx *ctx, Layer &L, int e, int s, bool by_prefetch, hipStream_t co
     };
     if (ctx->direct_q) {
       // The cache holds the quantised blob and nothing else: one copy (or two, split behind the gate / up
-      // codes), and "landed" is "ready" for every kernel.
+      // codes), readable by every kernel the moment it has landed.
       if (split) {
         HIP_TRY(hipMemcpyAsync(stage, src, meta_bytes + up_codes, hipMemcpyHostToDevice, copy_stream));
-        HIP_TRY(hipEventRecord(set.landed_up[s], copy_stream));
         HIP_TRY(hipEventRecord(set.copied_up[s], copy_stream));
         HIP_TRY(hipMemcpyAsync(stage + meta_bytes + up_codes, src + meta_bytes + up_codes,
                                ctx->host_blob_bytes - meta_bytes - up_codes, hipMemcpyHostToDevice, copy_stream));
       } else {
         HIP_TRY(hipMemcpyAsync(stage, src, ctx->host_blob_bytes, hipMemcpyHostToDevice, copy_stream));
       }
-      HIP_TRY(hipEventRecord(set.landed[s], copy_stream));
       HIP_TRY(hipEventRecord(set.copied[s], copy_stream));
     } else {
     // the staging area's last expansion must be over before new bytes land in it
@@ -539,18 +537,12 @@ int join_expand(moe_ctx *ctx, hipStream_t copy_stream) {
   return MOE_OK;
 }
 
-// The compute stream waits until slot s can be read: its quantised copy in the staging area
-// (from_copy: the bytes have landed) or the bf16 slot itself (landed and, for a quantised pool,
-// expanded).
-int wait_ready(Layer &L, int s, bool from_copy, hipStream_t cs) {
+// The compute stream waits until slot s can be read: its bytes have landed and, for an integer 4-bit
+// pool, been expanded.
+int wait_ready(Layer &L, int s, hipStream_t cs) {
   SlotSet &set = *L.set;
-  if (set.copy_pending[s] && set.prefetched[s] && !set.pf_landed[s]) set.pf_landed[s] = prefetch_arrival(set, s, from_copy);
-  if (from_copy) {
-    if (set.copy_pending[s]) {
-      HIP_TRY(hipStreamWaitEvent(cs, set.landed[s], 0));
-      set.copy_pending[s] = 0;
-    }
-  } else if (set.copy_pending[s] || set.expand_pending[s]) {
+  if (set.copy_pending[s] && set.prefetched[s] && !set.pf_landed[s]) set.pf_landed[s] = prefetch_arrival(set, s);
+  if (set.copy_pending[s] || set.expand_pending[s]) {
     HIP_TRY(hipStreamWaitEvent(cs, set.copied[s], 0));
     set.copy_pending[s] = set.expand_pending[s] = 0;
   }
@@ -664,9 +656,11 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
 }
 
 // Decode groups up to this many tokens use the mat-vec launches (one pass over the weights per 16
-// tokens through the matrix cores), larger ones the GEMM kernels; quantised copies are only read by
-// the mat-vec launches, which stay ahead of the bf16 GEMM for longer.
-constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsCopies = 32;
+// tokens through the matrix cores), larger ones the GEMM kernels; on quantised experts the mat-vec
+// launches stream a half or a quarter of the bytes per pass and stay ahead for a little longer (Mixtral
+// shape, largest group 19 rows: e4m3 487 against 551 us per layer on the GEMM kernels, MXFP4 379 against
+// 494; largest group 29 rows: 679 against 554 and 524 against 498).
+constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsCopies = 24;
 
 // Both expert matmuls of the groups in `mask`, on `stream`.
 // A launch that covers every group with rows (use_queues) takes its items from the plan's queues, if
@@ -884,18 +878,11 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
 
   bool combined = false;   // the weighted sum has been done by the down projection's launch
   L.stats.layer_calls++;
-  // Will the launch that runs expert e (its largest group having `rows` rows) read the quantised
-  // copy in the staging area?  Then it only needs the bytes to have landed, not the expansion.
-  const bool copies_possible = decode && gemv_reads_copies(a1) && gemv_reads_copies(a2);
-  auto reads_copy = [&](int e, int rows) {
-    return copies_possible && rows <= 8 && e >= 0 && ((a1.q8_mask >> e) & 1ull);
-  };
-
   if (enqueue_blind) {
     // Every expert is in a slot: nothing to decide on the host, one grouped launch.
     for (int s = 0; s < S; ++s)
       if (L.set->slot_layer[s] == L.index) {
-        rc = wait_ready(L, s, reads_copy(L.set->slot_expert[s], T), cs);
+        rc = wait_ready(L, s, cs);
         if (rc) return rc;
       }
     const unsigned long long mask = E == 64 ? ~0ull : ((1ull << E) - 1ull);
@@ -968,7 +955,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     if (n_hits && n_miss == 0) {
       for (int e = 0; e < E; ++e)
         if ((hit_mask >> e) & 1ull) {
-          rc = wait_ready(L, L.expert_slot[e], reads_copy(e, hit_max), cs);
+          rc = wait_ready(L, L.expert_slot[e], cs);
           if (rc) return rc;
         }
       rc = run_experts(ctx, decode, a1, a2, hit_mask, n_hits, hit_rows, hit_max, cs, nullptr, nullptr, nullptr,
@@ -984,7 +971,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       for (int e = 0; e < E; ++e) {
         if (!((hit_mask >> e) & 1ull)) continue;
         const int s = L.expert_slot[e];
-        rc = wait_ready(L, s, reads_copy(e, counts[e]), cs);  // only this expert's fetch: the next one may still be in flight
+        rc = wait_ready(L, s, cs);  // only this expert's fetch: the next one may still be in flight
         if (rc) return rc;
         rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs);
         if (rc) return rc;
@@ -1004,18 +991,15 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
       rc = place(ctx, L, e, s, false, ks, false, last, true);
       if (rc) return rc;
       a1.slot[e] = a2.slot[e] = (int16_t)s;
-      if (a1.qbase && L.set->q_valid[s]) {   // fetched just now: its quantised copy is in the staging area
+      if (a1.qbase && L.set->q_valid[s]) {   // fetched just now, as a quantised blob
         a1.q8_mask |= 1ull << e;
         a2.q8_mask |= 1ull << e;
       }
-      const bool from_copy = reads_copy(e, counts[e]);   // then the expansion need not be waited for
       SlotSet &set = *L.set;
-      HIP_TRY(hipStreamWaitEvent(cs, from_copy ? (last ? set.landed_up[s] : set.landed[s])
-                                               : (last ? set.copied_up[s] : set.copied[s]), 0));
-      set.copy_pending[s] = 0;
-      if (!from_copy) set.expand_pending[s] = 0;
+      HIP_TRY(hipStreamWaitEvent(cs, last ? set.copied_up[s] : set.copied[s], 0));
+      set.copy_pending[s] = set.expand_pending[s] = 0;
       rc = run_experts(ctx, decode, a1, a2, 1ull << e, 1, counts[e], counts[e], cs, nullptr, nullptr,
-                       last ? (from_copy ? set.landed[s] : set.copied[s]) : nullptr);
+                       last ? set.copied[s] : nullptr);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(L.set->used[s], cs));
       L.set->use_kind[s] = 1;
@@ -1077,7 +1061,7 @@ static int create_parts(moe_ctx *ctx, const moe_config *cfg) {
     HIP_TRY(hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming));
     HIP_TRY(hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming));
   }
-  if (cfg->host_format != MOE_FMT_BF16) HIP_TRY(hipStreamCreateWithFlags(&ctx->expand, hipStreamNonBlocking));
+  if (cfg->host_format == MOE_FMT_INT4_G128) HIP_TRY(hipStreamCreateWithFlags(&ctx->expand, hipStreamNonBlocking));
   HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ctx->dev_scores), kMaxExperts * sizeof(float)));
   return MOE_OK;
 }
@@ -1212,7 +1196,7 @@ int moe_bind_layer(moe_ctx *ctx, int layer, const void *const *host_expert_blob,
     set.staged.assign(S, 0);
     set.q_valid.assign(S, 0);
     set.expand_pending.assign(S, 0);
-    if (c.host_format != MOE_FMT_BF16) {
+    if (c.host_format == MOE_FMT_INT4_G128) {   // the only format with an expansion behind the copy
       set.landed_up.assign(S, nullptr);
       set.landed.assign(S, nullptr);
       for (int s = 0; s < S; ++s) {
