@@ -239,7 +239,7 @@ int moe_state_vector(const moe_state *st, int layer, float *host_out);
  * through the slots in ascending id, each fetched once on copy_stream while the previous
  * one computes.  Groups of any size run on the MFMA kernels: for a handful of tokens
  * moe_decode_layer gives the same result faster (and itself moves to the GEMM kernels when some
- * expert receives more than 16 tokens, 24 where the mat-vecs read quantised experts).  When some routed
+ * expert receives more than 16 tokens, 24 on MXFP4 experts).  When some routed
  * expert is not resident the call blocks the host until the gate's counts are known, and again
  * before each fetch into a slot whose last reader (an expert of this call, S fetches earlier) is
  * still computing: the copy is then enqueued with no wait in front of it, which starts it sooner

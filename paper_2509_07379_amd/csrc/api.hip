@@ -657,10 +657,10 @@ GemmArgs shared_args(const moe_ctx *ctx, const Layer &L, const char *ws, const W
 
 // Decode groups up to this many tokens use the mat-vec launches (one pass over the weights per 16
 // tokens through the matrix cores), larger ones the GEMM kernels; on quantised experts the mat-vec
-// launches stream a half or a quarter of the bytes per pass and stay ahead for a little longer (Mixtral
-// shape, largest group 19 rows: e4m3 487 against 551 us per layer on the GEMM kernels, MXFP4 379 against
-// 494; largest group 29 rows: 679 against 554 and 524 against 498).
-constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsCopies = 24;
+// launches of MXFP4 blobs stream a quarter of the bytes per pass and stay ahead for a little longer
+// (Mixtral shape, largest group 19 rows: 375 against 426 us per layer on the GEMM kernels; 29 rows: 518
+// against 438; e4m3, 19 rows: 483 against 396).
+constexpr int kMatvecMaxRows = 16, kMatvecMaxRowsMx4 = 24;
 
 // Both expert matmuls of the groups in `mask`, on `stream`.
 // A launch that covers every group with rows (use_queues) takes its items from the plan's queues, if
@@ -675,7 +675,7 @@ int run_experts(moe_ctx *ctx, bool decode, GemmArgs a1, GemmArgs a2, unsigned lo
   // The mat-vec kernels pass over an expert's weights once per 16 of its tokens: a decode batch that
   // gives some expert many more goes to the GEMM kernels, which stream the weights once.
   const bool from_copies = a1.q8_mask != 0 && gemv_reads_copies(a1);
-  const int matvec_limit = ctx->api_tune.matvec_max_rows > 0 ? ctx->api_tune.matvec_max_rows : (from_copies ? kMatvecMaxRowsCopies : kMatvecMaxRows);
+  const int matvec_limit = ctx->api_tune.matvec_max_rows > 0 ? ctx->api_tune.matvec_max_rows : (from_copies && a1.qfmt == 2 ? kMatvecMaxRowsMx4 : kMatvecMaxRows);
   if (decode && max_rows_per_group <= matvec_limit) {
     {
       Timer t(ctx, stream, MOE_K_GEMV1);

@@ -737,21 +737,34 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void grouped_gemm_q8_kernel
 // nobody may still use LDS; on exit the same holds.
 constexpr int kSmallTileRows = 64;
 
-template <int MODE>
+// On quantised experts (QF = 1 e4m3 blobs, 2 MXFP4 blobs; layouts and conversions as in the persistent
+// kernel) a stage is [A 64 rows][codes of 256 B rows (+ MXFP4 scale dwords)], 24 KB or 18 KB, so six or
+// eight stages fit and the loads run five or seven K steps ahead: these tiles are bound by the bytes a
+// compute unit has in flight (a loaded memory latency of 4 to 5 us), and smaller stages need more of them.
+template <int MODE, int QF>
 __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileInfo &t, unsigned char *smem,
                                               int lane, int wave) {
   constexpr int BN = 256, SA = kSmallTileRows, WARPS_M = 2, WARPS_N = 4, FN = 2;
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
-  constexpr int SST = (SA + BN) * ROW_BYTES;   // 40 KB per stage
-  constexpr int NST = 4, NLB = BN / 8 / 8;     // stages; B row groups (wave-wide loads) per wave and stage
+  constexpr int SAB = SA * ROW_BYTES;          // the A part of a stage
+  constexpr int SQS = SAB + BN * 32;           // MXFP4: the scale dwords, behind the codes
+  constexpr int SST = SAB + (QF == 2 ? BN * 32 + 2048 : QF == 1 ? BN * 64 : BN * ROW_BYTES);   // 18 / 24 / 40 KB
+  constexpr int NST = QF == 2 ? 8 : QF == 1 ? 6 : 4;   // stages (144 / 144 / 160 KB)
+  // B loads (wave-wide) per wave and stage: 4 of 8 rows x 128 bytes; e4m3 2 of 16 rows x 64 bytes of codes;
+  // MXFP4 one of 32 rows x 32 bytes of codes and one of scale dwords
+  constexpr int NLB = QF == 2 ? 2 : QF == 1 ? 2 : BN / 8 / 8;
+  constexpr int NLC = QF == 2 ? 1 : QF == 1 ? 2 : 4;   // ... of which rows of weights or codes
+  constexpr int LPS = NLB + 1;                 // loads per wave and stage, with the one of A
+  static_assert(NST * SST <= 160 * 1024 && NST <= 8 && (NST - 2) * LPS < 64, "stages must fit LDS and the load counter");
   const int wm = wave >> 2, wn = wave & 3;
   const int kt_total = args.K / BK;
   const int kt_begin = (int)((long long)kt_total * t.ks / t.ns);
   const int nk = (int)((long long)kt_total * (t.ks + 1) / t.ns) - kt_begin;
 
-  // This lane's sources.  A: row group `wave` (rows 8 wave .. 8 wave + 7); B: row groups wave + 8 i.  Lane l
-  // lands at row 8 g + l / 8, chunk position l % 8 and fetches the chunk the swizzle maps there; g & 1 is
-  // wave & 1 for all of them.
+  // This lane's sources.  A: row group `wave` (rows 8 wave .. 8 wave + 7); B (bf16): row groups wave + 8 i.
+  // Lane l lands at row 8 g + l / 8, chunk position l % 8 and fetches the chunk the swizzle maps there;
+  // g & 1 is wave & 1 for all of them.  B (e4m3): 16-row groups wave + 8 i.  B (MXFP4): the 32 rows 32 wave ..,
+  // lane l the half (l / 16) % 2 of row 16 (l / 32) + l % 16 (see the persistent kernel).
   const int lane_s = opaque(lane);
   const int kc16 = ((lane_s & 7) ^ ((wave & 1) * 4 + (lane_s >> 4))) * 16;
   const int a_row = wave * 8 + (lane_s >> 3);
@@ -764,38 +777,80 @@ __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileIn
   const uint16_t *a_base = args.perm ? args.A : args.A + (long long)(t.row0 + t.tile_row0) * args.lda;
   __amdgpu_buffer_rsrc_t a_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(a_base), 0, 0x7FFFFFFF, 0x00020000);
-  const char *wptr = args.wbase + (long long)args.slot[t.grp] * args.wstride + args.b0_off;
+  const char *wptr = QF != 0 ? args.qbase + (long long)args.slot[t.grp] * args.qstride
+                             : args.wbase + (long long)args.slot[t.grp] * args.wstride + args.b0_off;
   __amdgpu_buffer_rsrc_t b_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(wptr), 0, 0x7FFFFFFF, 0x00020000);
-  const uint32_t b_voff = (uint32_t)((lane_s >> 3) * args.ldb * 2 + kc16);
-  int b_soff[NLB];
+  const long long row_bytes = QF == 2 ? args.K >> 1 : QF == 1 ? args.K : (long long)args.ldb * 2;
+  const uint32_t b_voff =
+      QF == 2 ? (uint32_t)(((lane_s >> 5) * 16 + (lane_s & 15)) * row_bytes + ((lane_s >> 4) & 1) * 16)
+      : QF == 1 ? (uint32_t)((lane_s >> 2) * row_bytes + (((lane_s & 3) ^ ((lane_s >> 4) & 3)) << 4))
+                : (uint32_t)((lane_s >> 3) * row_bytes + kc16);
+  int b_soff[NLC];
 #pragma unroll
-  for (int i = 0; i < NLB; ++i) {
-    int r = (wave + 8 * i) * 8;
-    long long up = 0;
-    if (MODE == GEMM_SWIGLU && r >= BN / 2) { up = args.b1_off - args.b0_off; r -= BN / 2; }
-    b_soff[i] = (int)(up + (long long)(t.n0 + r) * args.ldb * 2);
+  for (int i = 0; i < NLC; ++i) {
+    int r = QF == 2 ? wave * 32 : QF == 1 ? (wave + 8 * i) * 16 : (wave + 8 * i) * 8;
+    long long base = QF != 0 ? args.q_b0_off : 0;
+    if (MODE == GEMM_SWIGLU && r >= BN / 2) {
+      base = QF != 0 ? args.q_b1_off : args.b1_off - args.b0_off;
+      r -= BN / 2;
+    }
+    b_soff[i] = (int)(base + (long long)(t.n0 + r) * row_bytes);
+  }
+  // MXFP4: wave w brings the scale dwords of tile rows 32 w .. 32 w + 31 (lanes 0..31)
+  uint32_t q_ssrc = 0x80000000u;
+  int q_ssoff = 0;
+  if constexpr (QF == 2) {
+    int rs = wave * 32;
+    long long sbase = args.q_s0_off;
+    if (MODE == GEMM_SWIGLU && rs >= BN / 2) { sbase = args.q_s1_off; rs -= BN / 2; }
+    if (lane_s < 32) q_ssrc = (uint32_t)(lane_s * (args.K >> 5));
+    q_ssoff = (int)(sbase + (long long)(t.n0 + rs) * (args.K >> 5));
   }
   const int lrow = lane_s & 31, lk = lane_s >> 5;
   const int a_addr = swz(wm * 32 + lrow, lk);
-  int b_addr[FN];
+  int b_addr[FN], q_saddr[FN] = {};
+  float q_rs[FN] = {};   // e4m3: the scales of this lane's B fragment rows
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
     const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
                                            : (j * WARPS_N + wn) * 32 + lrow;
-    b_addr[j] = SA * ROW_BYTES + swz(brow, lk);
+    if constexpr (QF == 2) {
+      b_addr[j] = SAB + (brow >> 4) * 512 + (brow & 15) * 16 + lk * 4;
+      q_saddr[j] = SQS + (brow >> 5) * 256 + (brow & 31) * 4;
+    } else if constexpr (QF == 1) {
+      b_addr[j] = SAB + brow * 64 + lk * 8 + (((brow >> 2) & 3) << 4);
+      const long long so = (MODE == GEMM_SWIGLU && j >= FNH) ? args.q_s1_off : args.q_s0_off;
+      const int n = t.n0 + (((MODE == GEMM_SWIGLU) ? j % FNH : j) * WARPS_N + wn) * 32 + lrow;
+      q_rs[j] = reinterpret_cast<const float *>(wptr + so)[n];
+    } else {
+      b_addr[j] = SAB + swz(brow, lk);
+    }
   }
   const int fm_valid = wm * 32 < t.rows_valid ? 1 : 0;
 
 #define MOE_SISSUE(q_)                                                                               \
   do {                                                                                               \
     unsigned char *st_ = smem + ((q_) % NST) * SST;                                                  \
-    _Pragma("unroll") for (int i_ = 0; i_ < NLB; ++i_)                                               \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(st_ + SA * ROW_BYTES + (wave + 8 * i_) * 1024), \
-                                               16, (int)b_voff, b_soff[i_] + (kt_begin + (q_)) * ROW_BYTES, 0, 0); \
+    const int kt_ = kt_begin + (q_);                                                                 \
+    _Pragma("unroll") for (int i_ = 0; i_ < NLC; ++i_) {                                             \
+      if constexpr (QF == 2)                                                                         \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(st_ + SAB + wave * 1024), 16,  \
+                                                 (int)b_voff, b_soff[i_] + kt_ * (BK / 2), 0, 0);    \
+      else if constexpr (QF == 1)                                                                    \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(st_ + SAB + (wave + 8 * i_) * 1024), 16, \
+                                                 (int)b_voff, b_soff[i_] + kt_ * BK, 0, 0);          \
+      else                                                                                           \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(st_ + SAB + (wave + 8 * i_) * 1024), 16, \
+                                                 (int)b_voff, b_soff[i_] + kt_ * ROW_BYTES, 0, 0);   \
+    }                                                                                                \
+    if constexpr (QF == 2)                                                                           \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(st_ + SQS + wave * 256), 4, (int)q_ssrc, \
+                                               q_ssoff + ((kt_ >> 1) << 2), 0, 0);                   \
     __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)(st_ + wave * 1024), 16, (int)a_voff, \
-                                             (kt_begin + (q_)) * ROW_BYTES, 0, 0);                   \
+                                             kt_ * ROW_BYTES, 0, 0);                                 \
   } while (0)
+#define MOE_SVMCNT(n_) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n_) & 15) | (((n_) >> 4) << 14))
 
   floatx16 acc[1][FN];
 #pragma unroll
@@ -806,23 +861,64 @@ __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileIn
   for (int q = 0; q < NST - 1; ++q)
     if (q < nk) MOE_SISSUE(q);
   for (int H = 0; H < nk; ++H) {
-    // this wave's loads of stage H have landed: the stages requested after it may still be in flight
+    // this wave's loads of stage H have landed: the stages requested after it (at most NST - 2 of them:
+    // the next one is requested behind the barrier) may still be in flight
     const int later = nk - 1 - H;
     __builtin_amdgcn_sched_barrier(0);
-    if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (NLB + 1)));
-    else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (NLB + 1));
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    switch (later < NST - 2 ? later : NST - 2) {
+      case 0: MOE_SVMCNT(0); break;
+      case 1: MOE_SVMCNT(LPS); break;
+      case 2: MOE_SVMCNT(2 * LPS); break;
+      case 3: MOE_SVMCNT(NST > 4 ? 3 * LPS : 0); break;
+      case 4: MOE_SVMCNT(NST > 5 ? 4 * LPS : 0); break;
+      case 5: MOE_SVMCNT(NST > 6 ? 5 * LPS : 0); break;
+      default: MOE_SVMCNT(NST > 7 ? 6 * LPS : 0); break;
+    }
     __builtin_amdgcn_s_barrier();   // ... and everybody's; the stage read in the last step is free
     __builtin_amdgcn_sched_barrier(0);
     if (H + NST - 1 < nk) MOE_SISSUE(H + NST - 1);
     if (fm_valid) {
       const unsigned char *st = smem + (H % NST) * SST;
       bf16x8 af[4], bf[FN][4];
+      if constexpr (QF == 2) {
+        uint32_t qc[FN][4], qs[FN];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        af[ks] = *reinterpret_cast<const bf16x8 *>(st + (a_addr ^ (ks << 5)));
+        for (int j = 0; j < FN; ++j) {
+          qs[j] = *reinterpret_cast<const uint32_t *>(st + q_saddr[j]);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) bf[j][ks] = *reinterpret_cast<const bf16x8 *>(st + (b_addr[j] ^ (ks << 5)));
+          for (int ks = 0; ks < 4; ++ks)
+            qc[j][ks] = *reinterpret_cast<const uint32_t *>(st + (b_addr[j] ^ (((ks >> 1) << 8) | ((ks & 1) << 3))));
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) af[ks] = *reinterpret_cast<const bf16x8 *>(st + (a_addr ^ (ks << 5)));
+        const int sh = ((kt_begin + H) & 1) * 16;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const float f0 = __uint_as_float(((qs[j] >> sh) & 0xFFu) << 23);
+          const float f1 = __uint_as_float(((qs[j] >> (sh + 8)) & 0xFFu) << 23);
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) bf[j][ks] = __builtin_bit_cast(bf16x8, expand8_mxfp4(qc[j][ks], ks < 2 ? f0 : f1));
+        }
+      } else if constexpr (QF == 1) {
+        u32x2 qc[FN][4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) qc[j][ks] = *reinterpret_cast<const u32x2 *>(st + (b_addr[j] ^ (ks << 4)));
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) af[ks] = *reinterpret_cast<const bf16x8 *>(st + (a_addr ^ (ks << 5)));
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks)
+            bf[j][ks] = __builtin_bit_cast(bf16x8, expand8_e4m3(qc[j][ks].x, qc[j][ks].y, q_rs[j]));
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          af[ks] = *reinterpret_cast<const bf16x8 *>(st + (a_addr ^ (ks << 5)));
+#pragma unroll
+          for (int j = 0; j < FN; ++j) bf[j][ks] = *reinterpret_cast<const bf16x8 *>(st + (b_addr[j] ^ (ks << 5)));
+        }
       }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
@@ -831,6 +927,7 @@ __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileIn
           acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j][ks], af[ks], acc[0][j], 0, 0, 0);
     }
   }
+#undef MOE_SVMCNT
 #undef MOE_SISSUE
   __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's fragment reads are done
@@ -859,13 +956,12 @@ __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileIn
 // Loads move whole 128-byte lines (8 tile rows per wave-wide load): half lines would halve the L1
 // fill rate.  Needs K % 64 == 0.
 // QF = 2: the B operand is the experts' MXFP4 blobs (GemmArgs::qbase).  A stage's B tile is then 256 rows of
-// 32 bytes of codes plus 4 scale bytes per row, all brought in by 4-byte direct loads: four wave-wide loads of
-// codes per wave (a load is 8 rows of 8 dwords; the dword that lands at position p of row r is dword
-// p ^ 2 ((r >> 3) & 3) of the row's K step, which spreads the 32 rows of a fragment read over all banks) and
-// one of scales (lanes 0..31: the aligned dword that holds the row's two scale bytes of this K step and of its
-// neighbour).  A lane builds its B fragment of K slice ks from one dword of codes with the hardware's scaled
-// fp4 conversion (exact), so the MFMAs see the weights the format defines.  Short row tiles run through the
-// same loop.  Needs K % 128 == 0 and the blob within 31 bits of byte offset.
+// 32 bytes of codes plus 4 scale bytes per row.  Each wave brings 32 rows of codes with one 16-byte direct
+// load (lane l the half (l / 16) % 2 of row 16 (l / 32) + l % 16; in LDS the 16 first halves of a 16-row
+// block are followed by its 16 second halves, which leaves the fragment reads two-way bank conflicts, the
+// least that 16-byte pieces allow) and 32 rows of scales with one 4-byte load (lanes 0..31: the aligned dword
+// that holds the row's two scale bytes of this K step and of its neighbour).  A lane builds its B fragment of K slice ks from one dword of codes with the hardware's scaled
+// fp4 conversion (exact), so the MFMAs see the weights the format defines.  Needs K % 128 == 0 and the blob within 31 bits of byte offset.
 // QF = 1: the e4m3 blobs.  A stage's B tile is 256 rows of 64 bytes of codes, two 16-byte wave-wide loads per wave
 // (a load is 16 rows of four pieces; the piece at position p of row r is piece p ^ ((r >> 2) & 3) of the row's
 // K step).  A lane builds a B fragment from 8 bytes of codes and its row's fp32 scale (fetched once per tile):
@@ -879,7 +975,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   constexpr int FNH = (MODE == GEMM_SWIGLU) ? FN / 2 : FN;
   constexpr int STAGE = (BM + BN) * ROW_BYTES;   // 64 KB
   constexpr int NL = 4;                          // wave-wide loads per wave and M tick
-  constexpr int NB = QF == 2 ? NL + 1 : QF == 1 ? 2 : NL;   // ... of a B stage (MXFP4: the codes and one load of scales)
+  constexpr int NB = QF != 0 ? 2 : NL;           // ... of a B stage (e4m3: two of codes; MXFP4: codes and scales)
   constexpr int QCODES = BM * ROW_BYTES;         // quantised B: a stage's codes (e4m3 16 KB; MXFP4 8 KB and,
   constexpr int QSCALES = QCODES + BN * 32;      // behind them, 2 KB for the scale dwords)
   static_assert(QF >= 0 && QF <= 2, "B operand: 0 = bf16, 1 = e4m3 rows, 2 = MXFP4");
@@ -1000,15 +1096,15 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
           0x7FFFFFFF, 0x00020000);                                                                   \
     /* B rows are n0 + 8 g + l/8: one per-lane offset, the row group's part is scalar */             \
     if constexpr (QF == 2) {                                                                         \
-      /* codes: K / 2 bytes per row; g & 3 = wave & 3 for all of a wave's B row groups */            \
-      src[NL] = (uint32_t)((lane_s >> 3) * (args.K >> 1) + (((lane_s & 7) ^ ((wave & 3) * 2)) << 2)); \
-      _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                            \
-        int r_ = MOE_PGROUP(NL + i_) * 8 - BM;                                                       \
+      /* codes: K / 2 bytes per row; wave w brings tile rows 32 w .. 32 w + 31 */                    \
+      src[NL] = (uint32_t)(((lane_s >> 5) * 16 + (lane_s & 15)) * (args.K >> 1) + ((lane_s >> 4) & 1) * 16); \
+      {                                                                                              \
+        int r_ = wave * 32;                                                                          \
         long long base_ = args.q_b0_off;                                                             \
         if (MODE == GEMM_SWIGLU && r_ >= BN / 2) { base_ = args.q_b1_off; r_ -= BN / 2; }            \
-        b_soff[i_] = (int)(base_ + (long long)((tt_).n0 + r_) * (args.K >> 1));                      \
+        b_soff[0] = (int)(base_ + (long long)((tt_).n0 + r_) * (args.K >> 1));                       \
       }                                                                                              \
-      /* scales: wave w brings the dwords of tile rows 32 w .. 32 w + 31 (K / 32 bytes per row) */   \
+      /* scales: the dwords of the same rows (K / 32 bytes per row) */                               \
       int rs_ = wave * 32;                                                                           \
       long long sbase_ = args.q_s0_off;                                                              \
       if (MODE == GEMM_SWIGLU && rs_ >= BN / 2) { sbase_ = args.q_s1_off; rs_ -= BN / 2; }           \
@@ -1071,10 +1167,14 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
   // this wave's A (WHICH_ = 0) or B (WHICH_ = 1) loads of stage q_
 #define MOE_PISSUE(q_, WHICH_)                                                                       \
   do {                                                                                               \
-    if ((WHICH_) && QF == 2)                                                                         \
+    if ((WHICH_) && QF == 2) {                                                                       \
       __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                      \
           b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QSCALES + wave * 256), 4, (int)q_ssrc,     \
           q_ssoff + (((kt_begin + (q_)) >> 1) << 2), 0, 0);                                          \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                      \
+          b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QCODES + wave * 1024), 16, (int)src[NL],   \
+          b_soff[0] + (kt_begin + (q_)) * (BK / 2), 0, 0);                                           \
+    } else                                                                                           \
     if ((WHICH_) && QF == 1) {                                                                       \
       _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                               \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
@@ -1082,11 +1182,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
             (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * BK, 0, 0);                                \
     } else                                                                                           \
     _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                              \
-      if ((WHICH_) && QF == 2)                                                                       \
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
-            b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + QCODES + (MOE_PGROUP(NL + i_) - 32) * 256), 4, \
-            (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * (BK / 2), 0, 0);                          \
-      else if (WHICH_)                                                                               \
+      if (WHICH_)                                                                                    \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                    \
             b_rsrc, (lds_ptr_t)(smem + ((q_) & 1) * STAGE + MOE_PGROUP(NL + i_) * 1024), 16,         \
             (int)src[NL], b_soff[i_] + (kt_begin + (q_)) * ROW_BYTES, 0, 0);                         \
@@ -1155,7 +1251,8 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
         _Pragma("unroll") for (int j_ = 0; j_ < FN; ++j_) {                                          \
           qs_[j_] = *reinterpret_cast<const uint32_t *>(st_ + q_saddr[j_]);                          \
           _Pragma("unroll") for (int ks_ = 0; ks_ < 4; ++ks_)                                        \
-            qc_[j_][ks_] = *reinterpret_cast<const uint32_t *>(st_ + (b_addr[j_] ^ (ks_ << 3)));     \
+            qc_[j_][ks_] = *reinterpret_cast<const uint32_t *>(                                      \
+                st_ + (b_addr[j_] ^ (((ks_ >> 1) << 8) | ((ks_ & 1) << 3))));                        \
         }                                                                                            \
         MOE_PREAD_A(0, (FMV < 2 ? FMV : 2));                                                         \
         const int sh_ = ((kt_begin + H) & 1) * 16;   /* this K step's two bytes of the scale dword */ \
@@ -1216,7 +1313,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     }                                                                                                \
   } while (0)
 
-  if (QF != 0 || t.rows_valid > kSmallTileRows) MOE_PPROLOGUE();
+  if (t.rows_valid > kSmallTileRows) MOE_PPROLOGUE();
   for (;;) {
     const bool has_next = nxt >= 0;
     TileInfo tn = t;
@@ -1247,8 +1344,8 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
         const int brow = (MODE == GEMM_SWIGLU) ? (j / FNH) * (BN / 2) + ((j % FNH) * WARPS_N + wn) * 32 + lrow
                                                : (j * WARPS_N + wn) * 32 + lrow;
         if constexpr (QF == 2) {
-          // dword ks * 2 + lk of the row's codes sits at position (ks * 2 + lk) ^ 2 ((brow >> 3) & 3)
-          b_addr[j] = QCODES + brow * 32 + lk * 4 + (((brow >> 3) & 3) << 3);
+          // dword ks * 2 + lk of the row's codes: half ks / 2 of the row, dword 2 (ks % 2) + lk of that half
+          b_addr[j] = QCODES + (brow >> 4) * 512 + (brow & 15) * 16 + lk * 4;
           q_saddr[j] = QSCALES + (brow >> 5) * 256 + (brow & 31) * 4;   // wave brow / 32 brought it, lane brow % 32
         } else if constexpr (QF == 1) {
           // 8 codes of K slice ks: half lk of piece ks, which sits at position ks ^ ((brow >> 2) & 3)
@@ -1272,11 +1369,11 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     if (dyn) after_next = qbox[0];
     else after_next = has_next && nxt + nslots < st_end ? nxt + nslots : -1;
     after_next = __builtin_amdgcn_readfirstlane(after_next);
-    if (QF == 0 && t.rows_valid <= kSmallTileRows) {
+    if (t.rows_valid <= kSmallTileRows) {
       // A short tile (pp_small_tile): no loads were requested for it, and its last stage lies over the
       // mailbox word, which everybody has to have read first.
       MOE_PBARRIER();
-      pp_small_tile<MODE>(args, t, smem, lane, wave);
+      pp_small_tile<MODE, QF>(args, t, smem, lane, wave);
       if (!has_next) break;
       pend_issued = dyn && after_next >= 0 && own_len > 0;
       if (pend_issued && tid == 0) pend_v = MOE_PTAKE_OWN();
@@ -1308,7 +1405,7 @@ __global__ __launch_bounds__(512) void grouped_gemm_pp_kernel(const GemmArgs arg
     const int fm_cur = fm_valid;
     const int lane_s = opaque(lane);
     int prow_n[NL];
-    const bool next_full = has_next && (QF != 0 || tn.rows_valid > kSmallTileRows);   // a short tile sets itself up
+    const bool next_full = has_next && tn.rows_valid > kSmallTileRows;   // a short tile sets itself up
     if (next_full) {
       MOE_PPERM(tn, prow_n);
     } else {
@@ -1620,8 +1717,10 @@ int gemm_kernel_choice(GemmMode mode, const GemmArgs &args, int max_rows, int n_
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_in_mask, hipStream_t stream) {
   if (args.b_quant) {
-    // quantised experts: the persistent kernel where its shape rules allow (always when the layer call runs
-    // from a plan), else the kernel that expands the codes on their way into LDS, with the tile
+    // quantised experts: the persistent kernel where its shape rules allow, whatever the groups' height (its
+    // short-tile pipeline also serves groups of a few rows: Mixtral shape, 16 to 50 rows per expert, e4m3
+    // 389-494 against 534-563 us per layer on the 128 x 128 tiles below, MXFP4 419-510 against 476-501; 60 and 64
+    // experts of 4 to 19 rows each: 5 to 10 % ahead), else the kernel that expands the codes on their way into LDS, with the tile
     // size by the groups' average height
     if (MODE == GEMM_PLAIN_BF16 || (args.qfmt != 1 && args.qfmt != 2) || !args.qbase || args.K % BK != 0)
       return hipErrorInvalidValue;
@@ -1629,7 +1728,7 @@ static hipError_t launch_mode(const GemmArgs &args, int max_rows, int n_groups_i
     const int v = args.tune.gemm_variant[MODE];
     const bool big = avg_rows > 96 && v != 1;
     if constexpr (MODE != GEMM_PLAIN_BF16) {
-      if (args.plan || (big && (v == 0 || v == 12) && pp_possible((GemmMode)MODE, args)))
+      if (args.plan || ((v == 0 || v == 12) && pp_possible((GemmMode)MODE, args)))
         return args.qfmt == 2 ? launch_pp<MODE, 2>(args, max_rows, n_groups_in_mask, stream)
                               : launch_pp<MODE, 1>(args, max_rows, n_groups_in_mask, stream);
     }
