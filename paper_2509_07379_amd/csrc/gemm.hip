@@ -739,8 +739,8 @@ constexpr int kSmallTileRows = 64;
 
 // On quantised experts (QF = 1 e4m3 blobs, 2 MXFP4 blobs; layouts and conversions as in the persistent
 // kernel) a stage is [A 64 rows][codes of 256 B rows (+ MXFP4 scale dwords)], 24 KB or 18 KB, so six or
-// eight stages fit and the loads run five or seven K steps ahead: these tiles are bound by the bytes a
-// compute unit has in flight (a loaded memory latency of 4 to 5 us), and smaller stages need more of them.
+// eight stages fit and the loads run five or seven K steps ahead (one stage fewer measured the same: at
+// about 1 us per K step these tiles are bound by the step itself, not by the loads in flight).
 template <int MODE, int QF>
 __device__ __forceinline__ void pp_small_tile(const GemmArgs &args, const TileInfo &t, unsigned char *smem,
                                               int lane, int wave) {
