@@ -168,14 +168,14 @@ struct TimedLaunch {
 };
 
 // A layer call whose cache counters wait for the gate's per-expert counts: the grouping kernel
-// writes them, followed by the call's number, into mailbox `box` (pinned host memory).
+// writes them, each with the call's number above it, into mailbox `box` (pinned host memory).
 struct PendingCall {
   int layer, box, seq;
   hipStream_t stream;   // with no_event: the stream to wait for instead
   bool no_event;        // the call recorded no event behind its counts
 };
 constexpr int kMailboxes = 32;
-constexpr int kMailboxWords = kMaxExperts + 1;
+constexpr int kMailboxWords = kMaxExperts;   // 8-byte words (mailbox_word): a box is 512 bytes
 
 }  // namespace
 
@@ -188,11 +188,11 @@ struct moe_ctx {
   size_t stage_stride = 0;      // e4m3: bytes of one slot's staging area behind the slots (256-aligned)
   std::vector<Layer> layers;
   std::unique_ptr<SlotSet> shared_set;   // cfg.shared_slots: the one cache all layers use
-  // Mailboxes the grouping kernel fills, one per layer call in flight: [kMaxExperts] counts, then the
-  // call's number.  A call that needs the counts at once waits for its own; a call that could enqueue
+  // Mailboxes the grouping kernel fills, one per layer call in flight: the E counts, each in a word of
+  // its own with the call's number.  A call that needs the counts at once waits for its own; a call that could enqueue
   // everything without them leaves an entry in `pending`, and its counters are filled in by the next
   // API call that looks at the cache (or when the mailbox is needed again).
-  int32_t *mailboxes = nullptr;       // [kMailboxes][kMailboxWords], pinned
+  long long *mailboxes = nullptr;     // [kMailboxes][kMailboxWords], pinned
   hipEvent_t routed[kMailboxes] = {};
   int32_t call_no = 0;
   PendingCall pending[kMailboxes];    // ring, oldest at pend_head (a mailbox has at most one pending call)
@@ -325,15 +325,20 @@ void account_hit(Layer &L, int s) {
 
 
 // The host needs the gate's per-expert counts of the call that owns mailbox `box`.  Waking up on the
-// event costs 10-20 us; the grouping kernel writes the call's number behind the counts in pinned,
-// host-coherent memory, so the host first polls that word for a while (the kernel is a few
-// microseconds away) and only then blocks.
+// event costs 10-20 us; the grouping kernel writes every count together with the call's number, as one
+// 8-byte word, into pinned, host-coherent memory, so the host first polls those words for a while (the
+// kernel is a few microseconds away) and only then blocks.  Each word vouches for itself: with a
+// separate "all written" word behind the counts the host has to rely on the order in which a wave's
+// stores cross the host link, and one run in some thousand calls read two counts of a call as the zeros
+// the mailbox held before.
 bool counts_arrived(const moe_ctx *ctx, int box, int seq) {
-  volatile const int32_t *flag = ctx->mailboxes + (size_t)box * kMailboxWords + kMaxExperts;
-  if (*flag != seq) return false;
+  volatile const long long *w = ctx->mailboxes + (size_t)box * kMailboxWords;
+  for (int e = 0; e < ctx->cfg.E; ++e)
+    if ((int)((unsigned long long)w[e] >> 32) != seq) return false;
   std::atomic_thread_fence(std::memory_order_acquire);
   return true;
 }
+inline int mailbox_count(const long long *box_words, int e) { return (int)(unsigned)(box_words[e] & 0xFFFFFFFFll); }
 
 hipError_t wait_for_counts(moe_ctx *ctx, int box, int seq, hipStream_t stream_instead = nullptr, bool no_event = false) {
   const auto t0 = std::chrono::steady_clock::now();
@@ -352,9 +357,9 @@ hipError_t wait_for_counts(moe_ctx *ctx, int box, int seq, hipStream_t stream_in
 // resident): hits, recency stamps and useful prefetches, exactly as if they had been taken at the call.
 void account_resident_call(moe_ctx *ctx, const PendingCall &p) {
   Layer &L = ctx->layers[p.layer];
-  const int32_t *counts = ctx->mailboxes + (size_t)p.box * kMailboxWords;
+  const long long *words = ctx->mailboxes + (size_t)p.box * kMailboxWords;
   for (int e = 0; e < ctx->cfg.E; ++e)
-    if (counts[e] > 0) {
+    if (mailbox_count(words, e) > 0) {
       const int s = L.expert_slot[e];
       if (s >= 0) account_hit(L, s);   // (always: whatever changes the slots settles the pending calls first)
     }
@@ -768,7 +773,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     rc = settle_pending(ctx, true);
     if (rc) return rc;
   }
-  int32_t *mailbox = ctx->mailboxes + (size_t)box * kMailboxWords;
+  long long *mailbox = ctx->mailboxes + (size_t)box * kMailboxWords;
 
   // A prefill batch of some size: the shared experts get the library's side stream.  Their two
   // launches need nothing but x, so they fill the compute units that the gate and the grouping leave
@@ -938,7 +943,7 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
     int n_hits = 0, hit_rows = 0, hit_max = 0;
     int misses[kMaxExperts], n_miss = 0;
     for (int e = 0; e < E; ++e) {
-      counts[e] = mailbox[e];
+      counts[e] = mailbox_count(mailbox, e);
       if (counts[e] <= 0) continue;
       if (L.expert_slot[e] >= 0) {
         hit_mask |= 1ull << e;
@@ -1053,8 +1058,8 @@ static int create_parts(moe_ctx *ctx, const moe_config *cfg) {
   }
   ctx->layers.resize(cfg->n_layers);
   HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&ctx->mailboxes),
-                        (size_t)kMailboxes * kMailboxWords * sizeof(int32_t), 0));
-  memset(ctx->mailboxes, 0, (size_t)kMailboxes * kMailboxWords * sizeof(int32_t));
+                        (size_t)kMailboxes * kMailboxWords * sizeof(long long), 0));
+  memset(ctx->mailboxes, 0, (size_t)kMailboxes * kMailboxWords * sizeof(long long));
   for (int i = 0; i < kMailboxes; ++i) HIP_TRY(hipEventCreateWithFlags(&ctx->routed[i], hipEventDisableTiming));
   if (cfg->I_shared) {
     HIP_TRY(hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(64 * kScanWaves) void dispatch_scan_kernel(const in
                                                                         int32_t *__restrict__ blk_base,
                                                                         int32_t *__restrict__ counts,
                                                                         int32_t *__restrict__ offsets,
-                                                                        int32_t *__restrict__ host_counts, int seq,
+                                                                        long long *__restrict__ host_counts, int seq,
                                                                         const PlanParams p0, const PlanParams p1) {
   __shared__ int part[kScanWaves][64];
   const int e = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -86,14 +86,9 @@ __global__ __launch_bounds__(64 * kScanWaves) void dispatch_scan_kernel(const in
   if (e < E) {
     counts[e] = total;
     offsets[e] = incl - total;
-    if (host_counts) host_counts[e] = total;
+    if (host_counts) host_counts[e] = mailbox_word(total, seq);   // the host polls these words
   }
   if (e == E - 1) offsets[E] = incl;
-  // the host polls this word: it may trust the counts once it reads the call's sequence number
-  if (host_counts) {
-    __threadfence_system();
-    if (e == 0) host_counts[kMaxExperts] = seq;
-  }
   if (p0.out) make_plan(p0, e, total);
   if (p1.out) make_plan(p1, e, total);
 }
@@ -136,7 +131,7 @@ constexpr int kSmallDispatch = 2048;
 __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
     const int32_t *__restrict__ ids, int n, int E, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm,
-    int32_t *__restrict__ host_counts, int seq, int32_t *__restrict__ active, const PlanParams p0,
+    long long *__restrict__ host_counts, int seq, int32_t *__restrict__ active, const PlanParams p0,
     const PlanParams p1) {
   constexpr int kWaves = kDispatchChunk / 64;
   __shared__ int hist[kMaxExperts];
@@ -159,7 +154,7 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
       counts[lane] = run;
       offsets[lane] = incl - run;
       base[lane] = incl - run;
-      if (host_counts) host_counts[lane] = run;
+      if (host_counts) host_counts[lane] = mailbox_word(run, seq);   // the host polls these words
     }
     if (lane == E - 1) offsets[E] = incl;
     if (active) {
@@ -168,10 +163,6 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
       const unsigned long long has = __ballot(run > 0);
       if (run > 0) active[__popcll(has & ((1ull << lane) - 1ull))] = lane;
       if (lane >= __popcll(has)) active[lane] = -1;
-    }
-    if (host_counts) {   // the host polls this word (see dispatch_scan_kernel)
-      __threadfence_system();
-      if (lane == 0) host_counts[kMaxExperts] = seq;
     }
     if (p0.out) make_plan(p0, lane, run);
     if (p1.out) make_plan(p1, lane, run);
@@ -211,7 +202,7 @@ __global__ __launch_bounds__(kDispatchChunk) void dispatch_small_kernel(
 
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active,
+                           long long *host_counts, int seq, hipStream_t stream, int32_t *active,
                            const PlanParams *plans) {
   const PlanParams none{};
   const PlanParams &p0 = plans ? plans[0] : none, &p1 = plans ? plans[1] : none;

@@ -17,9 +17,16 @@ constexpr int kMaxHidden = 16384;      // the gate's kernel stages 4 token vecto
 // one (T == 1 only, else NULL): the grouping tables of launch_dispatch, written by the gate's kernel
 // itself; host_counts (may be NULL) as there.
 struct SingleTokenDispatch {
-  int32_t *counts, *offsets, *perm, *inv_perm, *host_counts;
+  int32_t *counts, *offsets, *perm, *inv_perm;
+  long long *host_counts;
   int seq;
 };
+// A word of the host's mailbox: an expert's count with the call's number above it, written with ONE 8-byte
+// store.  The host may then trust each word by itself, in whatever order the words cross the host link
+// (stores of one wave to pinned host memory need not arrive in program order, fence or not).
+__host__ __device__ inline long long mailbox_word(int count, int seq) {
+  return (long long)(((unsigned long long)(unsigned)seq << 32) | (unsigned)count);
+}
 hipError_t launch_router_topk(const uint16_t *x, const uint16_t *wr, const float *bias,
                               int bias_stride, int T, int d, int E, int k, int renormalize,
                               float *logits, int32_t *ids, float *w, hipStream_t stream,
@@ -45,13 +52,13 @@ struct PlanParams;
 
 // ---- dispatch: stable counting sort of the T*k assignments by expert ------------------
 // blk_hist / blk_base: [ceil(n/kDispatchChunk) * E] scratch.  counts [E], offsets [E+1],
-// perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned,
-// kMaxExperts + 1 words): after the counts the kernel writes seq into word kMaxExperts.
+// perm [n], inv_perm [n].  host_counts: optional device-visible mirror of counts (pinned, kMaxExperts
+// 8-byte words, of which the first E are written: mailbox_word(count, seq)).
 // active (optional, decode-sized inputs only: n <= 2048): [kMaxExperts] receives the ids of the experts
 // that have rows, ascending, padded with -1.
 hipError_t launch_dispatch(const int32_t *ids, int n, int E, int32_t *blk_hist, int32_t *blk_base,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
-                           int32_t *host_counts, int seq, hipStream_t stream, int32_t *active = nullptr,
+                           long long *host_counts, int seq, hipStream_t stream, int32_t *active = nullptr,
                            const PlanParams *plans = nullptr);   // plans: NULL or two PlanParams (see below)
 
 // Tuning and test hooks of one context (moe_tune); all zero = every choice by shape.  Host side only:

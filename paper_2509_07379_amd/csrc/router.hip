@@ -138,17 +138,13 @@ __global__ __launch_bounds__(64 * NWAVES) void router_topk_kernel(
       if (lane < E) {
         one.counts[lane] = c;
         one.offsets[lane] = excl;
-        if (one.host_counts) one.host_counts[lane] = c;
+        if (one.host_counts) one.host_counts[lane] = mailbox_word(c, one.seq);   // the host polls these words
       }
       if (lane == E - 1) one.offsets[E] = incl;
       const int pos = __shfl(excl, lane < k ? si : 0);   // sorted position of assignment `lane`
       if (lane < k) {
         one.perm[pos] = lane;
         one.inv_perm[lane] = pos;
-      }
-      if (one.host_counts) {
-        __threadfence_system();
-        if (lane == 0) one.host_counts[kMaxExperts] = one.seq;
       }
     }
   }
