@@ -395,7 +395,6 @@ int pick_victim(const Layer &L, unsigned long long protected_mask) {
   return best;
 }
 
-// The copy stream waits for the last reader of slot s (nothing to wait for if it was never read).
 // The copy into slot s may start when the slot's last reader has finished.  If it has (the usual case in
 // decode: the reader ran a step ago), nothing is enqueued.  Otherwise either the copy stream waits for the
 // reader's event, or (host_waits) the calling thread does and the copy is enqueued without a dependency.
@@ -984,11 +983,10 @@ int run_layer(moe_ctx *ctx, int layer, const void *dev_x, int T, const float *bi
         L.set->use_kind[s] = 1;
       }
     }
-    // Misses stream through the slots in ascending id: fetch on the copy stream (behind the
-    // victim's last reader), compute as soon as the copy has landed.  The last fetch is split so
-    // that only the down projection and the weighted sum run after it.  (The copy stream's wait
-    // for a victim's reader cannot be moved ahead of the previous copy: that reader runs right
-    // after the previous copy, so the wait would hold the copy back as well.)
+    // Misses stream through the slots in ascending id: fetch on the copy stream (once the victim's
+    // last reader, an expert of this call S fetches earlier, has been computed: the calling thread
+    // waits for that, see wait_slot_free), compute as soon as the copy has landed.  The last fetch is
+    // split so that only the down projection and the weighted sum run after it.
     for (int i = 0; i < n_miss; ++i) {
       const int e = misses[i];
       const int s = pick_victim(L, 0ull);

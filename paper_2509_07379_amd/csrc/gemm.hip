@@ -1675,19 +1675,14 @@ hipError_t launch_ktail(const GemmArgs &args, int max_rows, int n_groups_in_mask
 // tiles of the single-phase kernel, 12 = the persistent ping-pong kernel (where the shape allows it).
 static bool pp_possible(GemmMode mode, const GemmArgs &args) {
   if (args.b_quant) {
-    // Codes and scales are addressed from the start of the blob with 31-bit byte offsets; the MXFP4 scale
-    // bytes of two K steps are fetched as one aligned dword, e4m3 codes in aligned 16-byte pieces.
-    const long long codes_end = (args.q_b1_off > args.q_b0_off ? args.q_b1_off : args.q_b0_off) +
-                                (long long)args.N * (args.K / 2);
+    // Codes and scales are addressed from the start of the blob with 31-bit byte offsets (the scales lie in
+    // front of the codes); codes travel in aligned 16-byte pieces, the MXFP4 scale bytes of two K steps as one
+    // aligned dword (hence K % 128).
+    if (mode == GEMM_PLAIN_BF16 || (args.qfmt != 1 && args.qfmt != 2)) return false;
     const long long row_bytes = args.qfmt == 2 ? args.K / 2 : args.K;
-    const long long codes_end1 = (args.q_b1_off > args.q_b0_off ? args.q_b1_off : args.q_b0_off) + args.N * row_bytes;
-    if (args.qfmt == 1)
-      return mode != GEMM_PLAIN_BF16 && args.K % BK == 0 && (args.q_s0_off % 4) == 0 && (args.q_s1_off % 4) == 0 &&
-             (args.q_b0_off % 16) == 0 && (args.q_b1_off % 16) == 0 && codes_end1 < 0x7FFFFFFFll &&
-             (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
-             args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
-    return args.qfmt == 2 && mode != GEMM_PLAIN_BF16 && args.K % 128 == 0 &&
-           (args.q_s0_off % 4) == 0 && (args.q_s1_off % 4) == 0 && codes_end < 0x7FFFFFFFll &&
+    const long long codes_end = (args.q_b1_off > args.q_b0_off ? args.q_b1_off : args.q_b0_off) + args.N * row_bytes;
+    return args.K % (args.qfmt == 2 ? 128 : BK) == 0 && (args.q_s0_off % 4) == 0 && (args.q_s1_off % 4) == 0 &&
+           (args.q_b0_off % 16) == 0 && (args.q_b1_off % 16) == 0 && codes_end < 0x7FFFFFFFll &&
            (long long)(args.perm ? args.a_rows : 256) * args.lda * 2 < 0x7FFFFFFFll &&
            args.N >= (mode == GEMM_SWIGLU ? 128 : 256);
   }
